@@ -1,0 +1,374 @@
+"""Pins for the reference CPU codec (oracle/zcref.cpp): CPU only.
+
+The reference is checked against things other than itself: a stream worked by hand from the
+paper's description of fZ-light (Section 3.3), closed forms, the error bound stated in
+Section 3.2, library routines (numpy.rint, int.bit_length, numpy.cumsum, numpy.packbits),
+brute force on tiny inputs, and for the reduce step a float pipeline built only from
+already-pinned calls plus the Sum error model of Section 3.2.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import libmodel as lm
+from paper_2502_18554_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "worked_example.txt")
+
+
+def _read_golden():
+    eb, x, stream, recon = None, None, b"", None
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, rest = line.split(None, 1)
+        if key == "abs_eb":
+            eb = float(rest)
+        elif key == "x":
+            x = np.array(rest.split(), np.float32)
+        elif key == "stream":
+            stream += bytes.fromhex(rest.replace(" ", ""))
+        elif key == "recon":
+            recon = np.array(rest.split(), np.float32)
+    return eb, x, np.frombuffer(stream, np.uint8), recon
+
+
+# ---------------- P1: the hand-worked stream ----------------
+def test_worked_example_bytes(zcref):
+    eb, x, want, recon = _read_golden()
+    st, got, total = zcref.compress(x, eb)
+    assert st == zcref.OK and total == 76
+    assert got.tobytes() == want.tobytes()
+    st, y, n = zcref.decompress(want)
+    assert st == zcref.OK and n == 32
+    assert np.array_equal(y, recon)
+    assert np.max(np.abs(y.astype(np.float64) - x)) == 0.203125
+    st, q, w, off = zcref.inspect(want)
+    assert list(q[:8]) == [10, 11, 13, 12, 12, 12, 9, 10] and list(w) == [2] and list(off) == [0]
+
+
+# ---------------- P3: constant input, closed form ----------------
+@pytest.mark.parametrize("n", [1, 31, 32, 33, 1000, 4096])
+@pytest.mark.parametrize("c", [0.0, -0.0, 3.25, -17.5])
+def test_constant_input_closed_form(zcref, n, c):
+    eb = 1e-2
+    x = np.full(n, c, np.float32)
+    st, s, total = zcref.compress(x, eb)
+    nb = (n + 31) // 32
+    assert st == zcref.OK
+    assert total == 32 + lm.pad16(nb) + lm.pad16(4 * nb) == s.size
+    st, q, w, off = zcref.inspect(s)
+    assert not w.any() and not off.any()
+    assert np.all(q == int(np.rint(np.float64(np.float32(c)) / lm.step(eb))))
+    outl = s[32 + lm.pad16(nb): 32 + lm.pad16(nb) + 4 * nb].view("<i4")
+    assert np.all(outl == q[0])
+
+
+def test_empty_input_is_header_only(zcref):
+    st, s, total = zcref.compress(np.zeros(0, np.float32), 1e-3)
+    assert st == zcref.OK and total == 32 and s.size == 32
+    st, y, n = zcref.decompress(s)
+    assert st == zcref.OK and n == 0 and y.size == 0
+
+
+# ---------------- P5: every piece against a library routine ----------------
+def _fields():
+    yield "sin", synth.sinusoids(1 << 14, seed=0).numpy(), 1e-4
+    yield "grf", synth.power_law_field((16, 32, 32), seed=1).numpy(), 1e-3
+    yield "grf_coarse", synth.power_law_field((16, 32, 32), seed=2).numpy(), 1e-2
+    yield "hard", synth.hard_mix(1 << 14, seed=3).numpy(), 1e-5
+
+
+@pytest.mark.parametrize("name,x,rel", list(_fields()), ids=[f[0] for f in _fields()])
+def test_pieces_match_library_routines(zcref, name, x, rel):
+    eb = synth.abs_bound(torch.from_numpy(x), rel)
+    st, s, total = zcref.compress(x, eb)
+    assert st == zcref.OK
+    q_lib = lm.codes(x, eb)
+    st, q = zcref.quantize(x, eb)
+    assert st == zcref.OK and np.array_equal(q, q_lib)
+    want, widths, offsets = lm.stream_from_codes(q_lib, eb)
+    st, q2, w, off = zcref.inspect(s)
+    assert np.array_equal(q2, q_lib)
+    assert np.array_equal(w, widths)                    # int.bit_length
+    assert np.array_equal(off.astype(np.int64), offsets)  # numpy.cumsum
+    assert s.tobytes() == want.tobytes()                # numpy.packbits planes, struct header
+    st, y, n = zcref.decompress(s)
+    assert st == zcref.OK
+    assert np.array_equal(y, lm.recon(q_lib, eb))       # mid-tread uniform quantiser
+
+
+# ---------------- P2: the error bound (Section 3.2) ----------------
+@pytest.mark.parametrize("seed", range(4))
+def test_error_bound_holds_inside_domain(zcref, seed):
+    rng = np.random.default_rng(seed)
+    eb = np.float32(2e-4 * (1 + seed))
+    # uniform values right up to the edge of the guaranteed domain max|x| <= 2^18 eb
+    x = (rng.uniform(-1, 1, 400_000) * (2.0 ** 18) * eb).astype(np.float32)
+    x = np.clip(x, -np.float32(2.0 ** 18) * eb, np.float32(2.0 ** 18) * eb)
+    st, s, _ = zcref.compress(x, eb)
+    assert st == zcref.OK
+    _, y, _ = zcref.decompress(s)
+    err = np.abs(y.astype(np.float64) - x.astype(np.float64))
+    assert err.max() <= float(eb)
+    ulp = np.spacing(np.abs(y)).astype(np.float64)
+    assert np.all(err <= float(eb) * 63 / 64 + 0.5 * ulp + 1e-300)
+
+
+def test_plain_step_would_break_the_bound():
+    """Why the step carries a 2^-6 guard: with a step of exactly 2*eb the binary32 rounding
+    of the reconstruction pushes some points past eb."""
+    rng = np.random.default_rng(0)
+    eb = np.float32(2e-4)
+    x = rng.uniform(-1, 1, 2_000_000).astype(np.float32)
+    q = np.rint(x.astype(np.float64) / (2.0 * float(eb)))
+    y = (q * 2.0 * float(eb)).astype(np.float32)
+    assert (np.abs(y.astype(np.float64) - x) > float(eb)).sum() > 0
+
+
+def test_bound_status_outside_domain(zcref):
+    # eb = 8.8 ulp of x in [1, 2): |x|/eb ~ 2^20, outside the guaranteed domain.  Errors are
+    # whole ulps here and the worst grid distance, 8.66 ulp, rounds up to 9 ulp > eb.
+    eb = np.float32(8.8 * 2.0 ** -23)
+    x = np.linspace(1.0, 2.0, 50000).astype(np.float32)
+    st, s, total = zcref.compress(x, eb)
+    assert st == zcref.ERR_BOUND and s.size == total
+    st2, y, n = zcref.decompress(s)                          # stream still decodes
+    assert st2 == zcref.OK and n == x.size
+    assert np.array_equal(y, lm.recon(lm.codes(x, eb), eb))
+
+
+# ---------------- P4: idempotence on the grid ----------------
+@pytest.mark.parametrize("name,x,rel", list(_fields()), ids=[f[0] for f in _fields()])
+def test_recompressing_a_reconstruction_gives_the_same_stream(zcref, name, x, rel):
+    eb = synth.abs_bound(torch.from_numpy(x), rel)
+    _, s, _ = zcref.compress(x, eb)
+    _, y, _ = zcref.decompress(s)
+    st, s2, _ = zcref.compress(y, eb)
+    assert st == zcref.OK and s2.tobytes() == s.tobytes()
+    _, y2, _ = zcref.decompress(s2)
+    assert np.array_equal(y, y2)
+
+
+# ---------------- P6: brute force and edge sizes ----------------
+@pytest.mark.parametrize("n", [0, 1, 2, 31, 32, 33, 63, 64, 65, 4095, 4096, 4097])
+def test_edge_sizes(zcref, n):
+    rng = np.random.default_rng(n)
+    x = np.cumsum(rng.normal(0, 0.01, n)).astype(np.float32)
+    eb = 1e-3
+    st, s, total = zcref.compress(x, eb)
+    assert st == zcref.OK
+    want, _, _ = lm.stream_from_codes(lm.codes(x, eb), eb)
+    assert s.tobytes() == want.tobytes()
+    st, y, m = zcref.decompress(s)
+    assert st == zcref.OK and m == n
+    if n:
+        assert np.max(np.abs(y.astype(np.float64) - x)) <= eb
+
+
+def test_all_short_sequences_over_small_alphabet(zcref):
+    eb = 0.5
+    s_ = lm.step(eb)
+    alphabet = [-3.0, -1.0, 0.0, 2.0, 7.0]
+    for n in range(1, 5):
+        for seq in itertools.product(alphabet, repeat=n):
+            x = (np.array(seq) * s_).astype(np.float32)
+            st, s, _ = zcref.compress(x, eb)
+            assert st == zcref.OK
+            st, q, w, off = zcref.inspect(s)
+            assert list(q) == [int(v) for v in seq]
+            d = np.diff(np.array(seq, np.int64))
+            want_w = int(np.abs(d).max()).bit_length() if n > 1 else 0
+            assert int(w[0]) == want_w
+            assert s.size == 32 + 16 + 16 + (4 * (1 + want_w) if want_w else 0)
+
+
+@pytest.mark.parametrize("w", range(0, 32))
+def test_every_code_length_round_trips(zcref, w):
+    """A single delta of +-2^(w-1) or +-(2^w - 1) makes a block of width w (P10 included:
+    widths above 19 are reached only through the encode-from-codes helper)."""
+    for mag in ({0} if w == 0 else {1 << (w - 1), (1 << w) - 1}):
+        for sgn in (1, -1):
+            q = np.zeros(96, np.int64)
+            q[40:] = sgn * mag               # one jump inside block 1
+            q = q - sgn * (mag // 2)         # keep |q| below 2^30
+            st, s, total = zcref.encode_codes(q.astype(np.int32), 1e-3)
+            assert st == zcref.OK
+            st, q2, wid, off = zcref.inspect(s)
+            assert np.array_equal(q2, q)
+            assert list(wid) == [0, w, 0]
+            want, _, _ = lm.stream_from_codes(q, 1e-3)
+            assert s.tobytes() == want.tobytes()
+            assert total == 32 + 16 + 16 + (4 * (1 + w) if w else 0)
+
+
+def test_incompressible_block_costs_133_bytes(zcref):
+    rng = np.random.default_rng(5)
+    q = rng.integers(-(2 ** 30) + 1, 2 ** 30, 32 * 50).astype(np.int32)
+    q[1::2] = np.abs(q[1::2]); q[0::2] = -np.abs(q[0::2])     # every delta near 2^30..2^31
+    st, s, total = zcref.encode_codes(q, 1e-3)
+    st, _, w, _ = zcref.inspect(s)
+    assert np.all(w >= 30)
+    nb = 50
+    assert total <= zcref.compress_bound(q.size) == 32 + lm.pad16(nb) + lm.pad16(4 * nb) + 128 * nb
+    q = np.tile(np.array([-(2 ** 30) + 1, 2 ** 30 - 1], np.int32), 16)
+    st, s, total = zcref.encode_codes(q, 1e-3)
+    assert total == 32 + 16 + 16 + 128 and zcref.compress_bound(32) == total
+
+
+def test_ties_round_to_even_and_signed_zero(zcref):
+    eb = 0.5                                  # step 0.984375; (m + 1/2) * step is exact in binary32
+    s_ = lm.step(eb)
+    m = np.arange(-40, 41)
+    x = ((m + 0.5) * s_).astype(np.float32)
+    assert np.array_equal(x.astype(np.float64), (m + 0.5) * s_)
+    r = x.astype(np.float64) * (1.0 / s_)
+    assert np.array_equal(r, m + 0.5)         # every one is an exact tie on the code axis
+    even = np.where(m % 2 == 0, m, m + 1)     # m + 1/2 goes to the even neighbour
+    st, q = zcref.quantize(x, eb)
+    assert st == zcref.OK and np.array_equal(q, even)
+    x2 = np.array([-0.0, 0.0], np.float32)
+    st, q = zcref.quantize(x2, 16.0)
+    assert list(q) == [0, 0]
+    st, s, _ = zcref.compress(x2, 16.0)
+    _, y, _ = zcref.decompress(s)
+    assert np.array_equal(y.view(np.uint32), np.zeros(2, np.uint32))   # -0.0 decodes as +0.0
+
+
+def test_alternating_signs(zcref):
+    eb = 1e-2
+    x = (np.arange(257) % 2 * 2 - 1).astype(np.float32) * np.linspace(0.1, 5, 257).astype(np.float32)
+    st, s, _ = zcref.compress(x, eb)
+    want, _, _ = lm.stream_from_codes(lm.codes(x, eb), eb)
+    assert st == zcref.OK and s.tobytes() == want.tobytes()
+
+
+# ---------------- error paths ----------------
+def test_argument_and_input_errors(zcref):
+    x = np.ones(40, np.float32)
+    for bad in (0.0, -1.0, np.inf, np.nan, 2.0 ** -97):
+        assert zcref.compress(x, bad)[0] == zcref.ERR_ARG
+    assert zcref.compress(x, 2.0 ** -96)[0] in (zcref.OK, zcref.ERR_BOUND, zcref.ERR_RANGE)
+    y = x.copy(); y[7] = np.nan
+    assert zcref.compress(y, 1e-3)[0] == zcref.ERR_NONFINITE
+    y[7] = -np.inf
+    assert zcref.compress(y, 1e-3)[0] == zcref.ERR_NONFINITE
+    y[7] = 3e9 * 1e-3                         # code ~1.5e9 > 2^30 - 1
+    assert zcref.compress(y, 1e-3)[0] == zcref.ERR_RANGE
+    y[9] = np.nan
+    assert zcref.compress(y, 1e-3)[0] == zcref.ERR_NONFINITE       # precedence
+    x = np.linspace(0, 1, 100).astype(np.float32)
+    st, s, total = zcref.compress(x, 1e-4)
+    st2, _, need = zcref.compress(x, 1e-4, out_cap=total - 1)
+    assert st2 == zcref.ERR_CAPACITY and need == total
+
+
+def test_format_errors(zcref):
+    x = np.linspace(0, 1, 100).astype(np.float32)
+    _, s, total = zcref.compress(x, 1e-4)
+    assert zcref.decompress(s[:31])[0] == zcref.ERR_FORMAT
+    assert zcref.decompress(s[:-1])[0] == zcref.ERR_FORMAT          # truncated
+    for pos in (0, 4, 6, 7):
+        t = s.copy(); t[pos] ^= 1
+        assert zcref.decompress(t)[0] == zcref.ERR_FORMAT
+    t = s.copy(); t[32] = 32                                        # width byte > 31
+    assert zcref.decompress(t)[0] == zcref.ERR_FORMAT
+    t = s.copy(); t[32] ^= 1                                        # sizes no longer add up
+    assert zcref.decompress(t)[0] == zcref.ERR_FORMAT
+    t = s.copy(); t[20:24] = 0                                      # nsum = 0
+    assert zcref.decompress(t)[0] == zcref.ERR_FORMAT
+    t = s.copy(); t[16:20] = 0                                      # eb = 0
+    assert zcref.decompress(t)[0] == zcref.ERR_FORMAT
+    assert zcref.decompress(s, out_cap_elems=99)[0] == zcref.ERR_CAPACITY
+    longer = np.concatenate([s, np.zeros(7, np.uint8)])             # trailing bytes are allowed
+    st, y, n = zcref.decompress(longer)
+    assert st == zcref.OK and n == 100
+
+
+# ---------------- P7/P8: the reduce step ----------------
+def _rank_streams(zcref, k, shape, rel, seed0=0):
+    xs = [synth.power_law_field(shape, seed=seed0 + i).numpy() for i in range(k)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), rel)
+    streams = []
+    for x in xs:
+        st, s, _ = zcref.compress(x, eb)
+        assert st == zcref.OK
+        streams.append(s)
+    return xs, eb, streams
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 8])
+def test_reduce_equals_float_pipeline_of_pinned_calls(zcref, k):
+    """decompress each operand, add in float64, round to binary32, compress again: with a
+    common grid this naive pipeline lands on the same codes, so the streams must match
+    (apart from the operand count in the header)."""
+    xs, eb, streams = _rank_streams(zcref, k, (8, 32, 32), 1e-4)
+    st, r, total = zcref.reduce(streams)
+    assert st == zcref.OK and r.size == total
+    ys = [zcref.decompress(s)[1].astype(np.float64) for s in streams]
+    naive = np.sum(ys, axis=0).astype(np.float32)
+    st, s2, _ = zcref.compress(naive, eb)
+    assert st == zcref.OK
+    s2 = s2.copy(); s2[20:24] = np.frombuffer(np.uint32(k).tobytes(), np.uint8)
+    assert r.tobytes() == s2.tobytes()
+    # and it is the encoding of the summed codes
+    qs = [zcref.inspect(s)[1].astype(np.int64) for s in streams]
+    want, _, _ = lm.stream_from_codes(np.sum(qs, axis=0), eb, nsum=k)
+    assert r.tobytes() == want.tobytes()
+
+
+def test_reduce_error_against_exact_sum(zcref):
+    """Sum over k operands (Section 3.2, Sum aggregation): errors add, so the worst case is
+    k*eb; a uniform quantiser has sigma = step/sqrt(12), so RMS ~ sqrt(k)*sigma and about 95 %
+    of points fall inside +-2 sqrt(k) sigma (the theorem's interval with this sigma)."""
+    k = 8
+    xs, eb, streams = _rank_streams(zcref, k, (32, 64, 64), 1e-4, seed0=10)
+    st, r, _ = zcref.reduce(streams)
+    _, y, _ = zcref.decompress(r)
+    exact = np.sum([x.astype(np.float64) for x in xs], axis=0)
+    err = y.astype(np.float64) - exact
+    assert np.abs(err).max() <= k * eb
+    sigma = lm.step(eb) / np.sqrt(12.0)
+    rms = np.sqrt(np.mean(err ** 2))
+    assert abs(rms / (np.sqrt(k) * sigma) - 1) < 0.10
+    inside = np.mean(np.abs(err) <= 2 * np.sqrt(k) * sigma)
+    assert 0.93 < inside < 0.98
+    # nested reduction gives the same stream as the flat one (sums of codes are exact)
+    _, a, _ = zcref.reduce(streams[:3])
+    _, b, _ = zcref.reduce(streams[3:])
+    _, ab, _ = zcref.reduce([a, b])
+    assert ab.tobytes() == r.tobytes()
+    assert int(r[20:24].view("<u4")[0]) == k
+
+
+def test_reduce_errors(zcref):
+    xs, eb, streams = _rank_streams(zcref, 2, (4, 16, 32), 1e-3)
+    _, other, _ = zcref.compress(xs[0], eb * 2)
+    assert zcref.reduce([streams[0], other])[0] == zcref.ERR_MISMATCH
+    _, short, _ = zcref.compress(xs[0][:-32], eb)
+    assert zcref.reduce([streams[0], short])[0] == zcref.ERR_MISMATCH
+    bad = streams[1].copy(); bad[0] ^= 1
+    assert zcref.reduce([streams[0], bad])[0] == zcref.ERR_FORMAT
+    big = np.full(64, 2 ** 30 - 1, np.int32)
+    _, sb, _ = zcref.encode_codes(big, eb)
+    assert zcref.reduce([sb, sb])[0] == zcref.ERR_RANGE
+    assert zcref.reduce([sb])[0] == zcref.OK
+
+
+# ---------------- P9: size grows as the bound shrinks ----------------
+def test_stream_size_monotone_in_error_bound(zcref):
+    x = synth.power_law_field((16, 64, 64), seed=4).numpy()
+    sizes = []
+    const_share = []
+    for rel in (1e-1, 1e-2, 1e-3, 1e-4, 1e-5):
+        eb = synth.abs_bound(torch.from_numpy(x), rel)
+        st, s, total = zcref.compress(x, eb)
+        assert st == zcref.OK
+        sizes.append(total)
+        const_share.append(np.mean(zcref.inspect(s)[2] == 0))
+    assert sizes == sorted(sizes)
+    assert const_share == sorted(const_share, reverse=True)
