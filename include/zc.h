@@ -1,0 +1,117 @@
+/* zc — fZ-light error-bounded lossy compression and the compressed-Allreduce local step,
+ * hand-written for AMD MI355X (gfx950).  C ABI; every pointer named d_* is DEVICE memory,
+ * everything else is host memory.  The library allocates no device memory and keeps no
+ * global state: the caller owns inputs, outputs and the workspace.
+ *
+ * Method: ZCCL, arXiv 2502.18554.  fZ-light is described in Section 3.3 (block partition,
+ * fused quantisation + 1D Lorenzo prediction, first value kept as a 4-byte outlier, sign
+ * bits, one-byte code length "log max", fixed-length bit-shifting encoding, constant
+ * blocks).  The reduce step is the per-round "decompress, reduce, recompress" of the
+ * collective computation framework (Section 3.1.2) with the Sum aggregation of Section 3.2.
+ *
+ * Stream layout (little endian), n values, nb = ceil(n / 32) blocks of 32 values:
+ *    0  u32 magic 0x314C435A   4  u16 version 1   6  u8 block_log2 5   7  u8 guard_log2 6
+ *    8  u64 n                 16  u32 eb_bits (binary32 pattern of abs_eb)
+ *   20  u32 nsum (1 after zc_compress, sum of the operands' nsum after a reduce)
+ *   24  u64 total_bytes
+ *   32  width table   nb bytes, zero padded to a multiple of 16
+ *   ..  outlier table nb int32 (first code of each block), zero padded to a multiple of 16
+ *   ..  payload: for each block of width w > 0, in block order, (1 + w) u32 words:
+ *       sign word (bit j set iff delta j < 0), then planes p = 0..w-1, least significant
+ *       first, bit j of plane p = bit p of |delta j|.  A block of width 0 has no payload.
+ *  Codes: q = rint(x / s) with s = abs_eb * 63/32 (binary64, round half to even);
+ *  deltas: d0 = 0, dj = qj - q(j-1) inside a block; the last block is padded with its last
+ *  code; width = bit count of max |dj|; reconstruction x' = (float)((double)q * s).
+ *
+ * Calls are asynchronous on the given HIP stream unless the last size pointer is non-NULL,
+ * in which case the call synchronises the stream and returns the final status and size.
+ * In the asynchronous form the status and size are collected later with zc_finish on the
+ * same workspace.  One workspace serves one call at a time.
+ */
+#ifndef ZC_H
+#define ZC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ZC_OK = 0,
+  ZC_ERR_ARG = 1,       /* null pointer, misaligned buffer, abs_eb not finite / < 2^-96, n > 2^31, k out of range, workspace too small */
+  ZC_ERR_CAPACITY = 2,  /* output buffer too small; nothing is written past its end */
+  ZC_ERR_FORMAT = 3,    /* not a valid stream: header fields, truncated, width > 31, sizes do not add up */
+  ZC_ERR_NONFINITE = 4, /* NaN or Inf in the input */
+  ZC_ERR_RANGE = 5,     /* a code (or a sum of codes) exceeds 2^30 - 1 in magnitude */
+  ZC_ERR_BOUND = 6,     /* some |x - x'| > abs_eb: input outside max|x| <= 2^18 abs_eb; the stream is still complete and decodable */
+  ZC_ERR_MISMATCH = 7,  /* reduce operands differ in n or abs_eb */
+  ZC_ERR_HIP = 8        /* a HIP runtime call failed, or an internal wait ran out */
+} zc_status;
+
+#define ZC_MAX_N (1ull << 31)
+#define ZC_MAX_K 64
+
+/* Worst-case stream size in bytes for n values (every block at width 31: 133 B per 128 B). */
+size_t zc_compress_bound(size_t n);
+
+/* Workspace bytes needed by any call on at most n_max values with at most k_max reduce
+ * operands (k_max < 1 is taken as 1).  The workspace is device memory, 16-byte aligned;
+ * its content between calls is irrelevant. */
+size_t zc_workspace_bytes(size_t n_max, int k_max);
+
+/* fZ-light compression (Section 3.3).  d_in: n binary32 values, 16-byte aligned.
+ * d_out: out_cap bytes, 16-byte aligned, receives the stream.  out_bytes (host, may be NULL):
+ * receives total_bytes, also when the status is ZC_ERR_CAPACITY or ZC_ERR_BOUND.
+ * Errors: ARG, NONFINITE, RANGE, CAPACITY, BOUND (in this order of precedence), HIP.
+ * On any error except BOUND the content of d_out is unspecified. */
+int zc_compress(const float* d_in, size_t n, float abs_eb,
+                void* d_out, size_t out_cap, size_t* out_bytes,
+                void* d_ws, size_t ws_bytes, void* hip_stream);
+
+/* fZ-light decompression (inverse of the stages of Section 3.3).  d_in: stream of in_bytes
+ * bytes (trailing bytes beyond total_bytes are ignored), 16-byte aligned.  d_out: room for
+ * out_cap_elems binary32 values, 16-byte aligned.  n_out (host, may be NULL): receives n.
+ * Errors: ARG, FORMAT, CAPACITY (nothing is written), HIP. */
+int zc_decompress(const void* d_in, size_t in_bytes,
+                  float* d_out, size_t out_cap_elems, size_t* n_out,
+                  void* d_ws, size_t ws_bytes, void* hip_stream);
+
+/* Local step of the compressed Allreduce (Section 3.1.2, Sum of Section 3.2): k compressed
+ * operands of the same n and abs_eb -> the compressed sum, computed on the integer codes, so
+ * no new quantisation error appears and decompress(out) is within nsum * abs_eb of the exact
+ * sum of the original buffers.  d_chunks: HOST array of k device pointers (16-byte aligned
+ * streams); chunk_bytes: HOST array of their sizes; 1 <= k <= ZC_MAX_K.
+ * Errors: ARG, FORMAT, MISMATCH, RANGE, CAPACITY, HIP. */
+int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes, int k,
+                         void* d_out, size_t out_cap, size_t* out_bytes,
+                         void* d_ws, size_t ws_bytes, void* hip_stream);
+
+/* Completes an asynchronous call: synchronises hip_stream, returns the status of the last
+ * call that used d_ws and stores its size result (total_bytes, or n for zc_decompress) in
+ * *result (host, may be NULL). */
+int zc_finish(const void* d_ws, size_t* result, void* hip_stream);
+
+/* Reads and validates a stream header (synchronises hip_stream).  Any output may be NULL. */
+int zc_peek_header(const void* d_in, size_t in_bytes, size_t* n, float* abs_eb,
+                   unsigned* nsum, size_t* total_bytes, void* hip_stream);
+
+const char* zc_strerror(int status);
+
+/* Staged checks of the stream's parts (Section 3.3, one stage each). */
+
+/* Quantisation stage only: d_q[i] = rint(d_in[i] / s).  Synchronous.
+ * Errors: ARG, NONFINITE, RANGE, BOUND, HIP. */
+int zc_debug_quantize(const float* d_in, size_t n, float abs_eb, int32_t* d_q,
+                      void* d_ws, size_t ws_bytes, void* hip_stream);
+
+/* Payload offset of every block, in 4-byte words, recomputed from a stream's width table
+ * into d_off_words[nb].  Synchronous.  Errors: ARG, FORMAT, HIP. */
+int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_words, size_t off_cap,
+                           void* d_ws, size_t ws_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZC_H */

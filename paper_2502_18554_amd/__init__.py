@@ -1,0 +1,10 @@
+"""zc: fZ-light error-bounded compression and the compressed-Allreduce local step on MI355X.
+
+`binding` holds thin ctypes wrappers with the names of the C ABI (include/zc.h); every step
+of the path runs in the HIP kernels of libzc.so.  `synth` makes seeded synthetic inputs.
+"""
+from . import binding, synth  # noqa: F401
+from .binding import (  # noqa: F401
+    ZcError, zc_compress, zc_compress_bound, zc_debug_block_offsets, zc_debug_quantize, zc_decompress,
+    zc_finish, zc_peek_header, zc_reduce_compressed, zc_strerror, zc_workspace_bytes,
+)

@@ -1,0 +1,134 @@
+"""ctypes binding of libzc.so: argument marshalling only.
+
+Buffers are torch tensors on the GPU (PyTorch is used for device memory and streams only);
+the functions have the names and argument order of include/zc.h.  There is no CPU fallback:
+if the HIP library has not been built, loading it raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libzc.so")
+
+ZC_OK, ZC_ERR_ARG, ZC_ERR_CAPACITY, ZC_ERR_FORMAT, ZC_ERR_NONFINITE, ZC_ERR_RANGE, ZC_ERR_BOUND, \
+    ZC_ERR_MISMATCH, ZC_ERR_HIP = range(9)
+ZC_MAX_K = 64
+
+EXPORTS = [
+    "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_reduce_compressed",
+    "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
+]
+
+_lib = None
+
+
+class ZcError(RuntimeError):
+    def __init__(self, status, what):
+        super().__init__(f"{what}: {zc_strerror(status)} (status {status})")
+        self.status = status
+
+
+def lib():
+    """Loads libzc.so (built by paper_2502_18554_amd/build.py); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} not found: build it with `python -m paper_2502_18554_amd.build` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(_LIB_PATH)
+        vp, sz, szp = C.c_void_p, C.c_size_t, C.POINTER(C.c_size_t)
+        L.zc_compress_bound.restype = sz
+        L.zc_compress_bound.argtypes = [sz]
+        L.zc_workspace_bytes.restype = sz
+        L.zc_workspace_bytes.argtypes = [sz, C.c_int]
+        L.zc_compress.argtypes = [vp, sz, C.c_float, vp, sz, szp, vp, sz, vp]
+        L.zc_decompress.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
+        L.zc_reduce_compressed.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp]
+        L.zc_finish.argtypes = [vp, szp, vp]
+        L.zc_peek_header.argtypes = [vp, sz, szp, C.POINTER(C.c_float), C.POINTER(C.c_uint), szp, vp]
+        L.zc_strerror.restype = C.c_char_p
+        L.zc_strerror.argtypes = [C.c_int]
+        L.zc_debug_quantize.argtypes = [vp, sz, C.c_float, vp, vp, sz, vp]
+        L.zc_debug_block_offsets.argtypes = [vp, sz, vp, sz, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _p(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def zc_strerror(status):
+    return lib().zc_strerror(int(status)).decode()
+
+
+def zc_compress_bound(n):
+    return int(lib().zc_compress_bound(int(n)))
+
+
+def zc_workspace_bytes(n_max, k_max=1):
+    return int(lib().zc_workspace_bytes(int(n_max), int(k_max)))
+
+
+def zc_compress(d_in, n, abs_eb, d_out, d_ws, sync=True, stream=None, out_cap=None):
+    """Returns (status, total_bytes); total_bytes is None in the asynchronous form."""
+    nbytes = C.c_size_t(0)
+    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
+    st = lib().zc_compress(_p(d_in), n, abs_eb, _p(d_out), cap,
+                           C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
+                           _stream(stream))
+    return st, (nbytes.value if sync else None)
+
+
+def zc_decompress(d_in, in_bytes, d_out, d_ws, sync=True, stream=None, out_cap_elems=None):
+    """Returns (status, n); n is None in the asynchronous form."""
+    n = C.c_size_t(0)
+    cap = (d_out.numel() if d_out is not None else 0) if out_cap_elems is None else out_cap_elems
+    st = lib().zc_decompress(_p(d_in), in_bytes, _p(d_out), cap, C.byref(n) if sync else None,
+                             _p(d_ws), d_ws.numel() * d_ws.element_size(), _stream(stream))
+    return st, (n.value if sync else None)
+
+
+def zc_reduce_compressed(d_chunks, chunk_bytes, d_out, d_ws, sync=True, stream=None, out_cap=None):
+    """d_chunks: list of device tensors holding the k operand streams.  Returns (status, total_bytes)."""
+    k = len(d_chunks)
+    ptrs = (C.c_void_p * max(k, 1))(*[t.data_ptr() for t in d_chunks])
+    sizes = (C.c_size_t * max(k, 1))(*[int(b) for b in chunk_bytes])
+    nbytes = C.c_size_t(0)
+    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
+    st = lib().zc_reduce_compressed(ptrs, sizes, k, _p(d_out), cap,
+                                    C.byref(nbytes) if sync else None, _p(d_ws),
+                                    d_ws.numel() * d_ws.element_size(), _stream(stream))
+    return st, (nbytes.value if sync else None)
+
+
+def zc_finish(d_ws, stream=None):
+    """Returns (status, size result) of the last asynchronous call that used d_ws."""
+    r = C.c_size_t(0)
+    st = lib().zc_finish(_p(d_ws), C.byref(r), _stream(stream))
+    return st, r.value
+
+
+def zc_peek_header(d_in, in_bytes, stream=None):
+    """Returns (status, n, abs_eb, nsum, total_bytes)."""
+    n, eb, nsum, total = C.c_size_t(0), C.c_float(0), C.c_uint(0), C.c_size_t(0)
+    st = lib().zc_peek_header(_p(d_in), in_bytes, C.byref(n), C.byref(eb), C.byref(nsum), C.byref(total),
+                              _stream(stream))
+    return st, n.value, eb.value, nsum.value, total.value
+
+
+def zc_debug_quantize(d_in, n, abs_eb, d_q, d_ws, stream=None):
+    return lib().zc_debug_quantize(_p(d_in), n, abs_eb, _p(d_q), _p(d_ws), d_ws.numel() * d_ws.element_size(),
+                                   _stream(stream))
+
+
+def zc_debug_block_offsets(d_in, in_bytes, d_off_words, d_ws, stream=None):
+    return lib().zc_debug_block_offsets(_p(d_in), in_bytes, _p(d_off_words), d_off_words.numel(), _p(d_ws),
+                                        d_ws.numel() * d_ws.element_size(), _stream(stream))

@@ -1,0 +1,312 @@
+// C ABI of the zc library: argument checks and kernel launches.  All arithmetic of the
+// method runs in the kernels; the host only divides once (1 / step) and launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+
+#include "zc_common.h"
+#include "zc_compress.h"
+#include "zc_decompress.h"
+#include "zc_reduce.h"
+#include "zc_scan.h"
+
+using namespace zc;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool eb_valid(float eb) { return std::isfinite(eb) && eb >= std::ldexp(1.0f, -96); }
+
+// Highest-precedence error in a device status word.
+int status_from_bits(u32 bits) {
+  static const int order[] = {ZC_ERR_HIP, ZC_ERR_ARG, ZC_ERR_FORMAT, ZC_ERR_MISMATCH, ZC_ERR_NONFINITE,
+                              ZC_ERR_RANGE, ZC_ERR_CAPACITY, ZC_ERR_BOUND};
+  for (int code : order)
+    if (bits & status_bit(code)) return code;
+  return ZC_OK;
+}
+
+bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+// Most blocks a stream of `bytes` bytes can describe: each costs at least 5 table bytes.
+u64 blocks_bound(u64 bytes) { return bytes > kHeaderBytes ? (bytes - kHeaderBytes) / 5 : 0; }
+
+int finish(const void* d_ws, size_t* result, hipStream_t stream) {
+  struct { u32 ticket, status; u64 result; } host;
+  if (hipMemcpyAsync(&host, d_ws, sizeof(host), hipMemcpyDeviceToHost, stream) != hipSuccess) return ZC_ERR_HIP;
+  if (hipStreamSynchronize(stream) != hipSuccess) return ZC_ERR_HIP;
+  if (result) *result = size_t(host.result);
+  return status_from_bits(host.status);
+}
+
+void launch_init(const WorkspaceLayout& l, u32 ntiles, u8* out, u64 out_cap, u64 n, u32 eb_bits, hipStream_t stream) {
+  InitArgs ia;
+  ia.ctl = l.ctl;
+  ia.desc = l.desc;
+  ia.ntiles = ntiles;
+  ia.out = out;
+  ia.out_cap = out_cap;
+  ia.n = n;
+  ia.nb = num_blocks(n);
+  ia.eb_bits = eb_bits;
+  ia.nsum = 1;
+  u32 grid = (ntiles + 255) / 256;
+  if (grid < 1) grid = 1;
+  if (grid > 1024) grid = 1024;
+  hipLaunchKernelGGL(init_kernel, dim3(grid), dim3(256), 0, stream, ia);
+}
+
+__global__ void quantize_kernel(CompressArgs a, i32* q) {
+  const u64 i = u64(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i >= a.n) return;
+  u32 err = 0;
+  q[i] = quantize_value(a.in[i], a, err);
+  if (err) atomicOr(&a.ctl->status, err);
+}
+
+struct OffsetsArgs {
+  StreamRef in;
+  u64 tiles_cap;
+  const u32* seg_off;
+  u32* off_words;
+  u64 off_cap;
+  Control* ctl;
+};
+
+__global__ __launch_bounds__(256) void block_offsets_kernel(OffsetsArgs a) {
+  if (validation_failed(a.ctl)) return;
+  const ParsedHeader h = parse_header(a.in);
+  if (!h.ok) return;
+  if (h.nb > a.off_cap) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
+    return;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) a.ctl->result = h.nb;
+  const u64 seg = u64(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (seg >= num_segments(h.nb) || seg >= 4 * a.tiles_cap) return;
+  const u64 b = seg * kWaveBlocks + u64(lane_id());
+  const u32 w = b < h.nb ? u32(a.in.base[kHeaderBytes + b]) : 0u;
+  const u32 words = psize_words(w);
+  const u32 incl = wave_inclusive_sum(words);
+  if (b < h.nb) a.off_words[b] = a.seg_off[seg] + incl - words;
+}
+
+void fill_compress_args(CompressArgs& ca, const float* d_in, u64 n, float abs_eb, void* d_out, u64 out_cap,
+                        const WorkspaceLayout& l) {
+  ca.in = d_in;
+  ca.n = n;
+  ca.nb = num_blocks(n);
+  ca.step = double(abs_eb) * 63.0 / 32.0;
+  ca.inv = 1.0 / ca.step;
+  ca.eb = double(abs_eb);
+  ca.screen = abs_eb * 131072.0f;   // 2^17 * eb; +inf when it overflows, which is still a valid screen
+  std::memcpy(&ca.eb_bits, &abs_eb, 4);
+  ca.out = static_cast<u8*>(d_out);
+  ca.out_cap = out_cap;
+  ca.ctl = l.ctl;
+  ca.desc = l.desc;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t zc_compress_bound(size_t n) {
+  const u64 nb = num_blocks(n);
+  return size_t(tables_end(nb) + 128 * nb);
+}
+
+size_t zc_workspace_bytes(size_t n_max, int k_max) { return size_t(workspace_bytes(n_max, k_max)); }
+
+const char* zc_strerror(int status) {
+  switch (status) {
+    case ZC_OK: return "ok";
+    case ZC_ERR_ARG: return "invalid argument";
+    case ZC_ERR_CAPACITY: return "output buffer too small";
+    case ZC_ERR_FORMAT: return "not a valid zc stream";
+    case ZC_ERR_NONFINITE: return "NaN or Inf in the input";
+    case ZC_ERR_RANGE: return "quantisation code out of range";
+    case ZC_ERR_BOUND: return "error bound not met (input outside the guaranteed domain)";
+    case ZC_ERR_MISMATCH: return "reduce operands differ in size or error bound";
+    case ZC_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int zc_finish(const void* d_ws, size_t* result, void* hip_stream) {
+  if (!d_ws) return ZC_ERR_ARG;
+  return finish(d_ws, result, static_cast<hipStream_t>(hip_stream));
+}
+
+int zc_compress(const float* d_in, size_t n, float abs_eb, void* d_out, size_t out_cap, size_t* out_bytes,
+                void* d_ws, size_t ws_bytes, void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (!eb_valid(abs_eb) || n > ZC_MAX_N || (n && !d_in) || !d_out || !d_ws) return ZC_ERR_ARG;
+  if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
+  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
+  const u64 nb = num_blocks(n);
+  const u64 ntiles = num_tiles(nb);
+  if (l.tiles_cap < 1 || ntiles > l.tiles_cap) return ZC_ERR_ARG;
+  CompressArgs ca;
+  fill_compress_args(ca, d_in, n, abs_eb, d_out, out_cap, l);
+  launch_init(l, u32(ntiles), ca.out, out_cap, n, ca.eb_bits, stream);
+  if (ntiles) hipLaunchKernelGGL(compress_kernel, dim3(u32(ntiles)), dim3(kTileThreads), 0, stream, ca);
+  if (!launch_ok()) return ZC_ERR_HIP;
+  if (!out_bytes) return ZC_OK;
+  return finish(d_ws, out_bytes, stream);
+}
+
+int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
+                  void* d_ws, size_t ws_bytes, void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (!d_in || !d_ws || (out_cap_elems && !d_out)) return ZC_ERR_ARG;
+  if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
+  if (in_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
+  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
+  if (l.tiles_cap < 1) return ZC_ERR_ARG;
+  u64 tiles = num_tiles(blocks_bound(in_bytes));
+  const u64 tiles_out = num_tiles(num_blocks(out_cap_elems));
+  if (tiles > tiles_out) tiles = tiles_out;
+  if (tiles > l.tiles_cap) tiles = l.tiles_cap;
+  if (tiles < 1) tiles = 1;
+  launch_init(l, 0, nullptr, 0, 0, 0, stream);
+  ScanArgs sa;
+  sa.streams[0].base = static_cast<const u8*>(d_in);
+  sa.streams[0].bytes = in_bytes;
+  sa.k = 1;
+  sa.check_match = 0;
+  sa.tiles_cap = l.tiles_cap;
+  sa.seg_off = l.seg_off;
+  sa.ctl = l.ctl;
+  hipLaunchKernelGGL(segment_sizes_kernel, dim3(u32(tiles), 1), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(segment_scan_kernel, dim3(1), dim3(1024), 0, stream, sa);
+  DecompressArgs da;
+  da.in = sa.streams[0];
+  da.out = d_out;
+  da.out_cap_elems = out_cap_elems;
+  da.tiles_cap = l.tiles_cap;
+  da.seg_off = l.seg_off;
+  da.ctl = l.ctl;
+  hipLaunchKernelGGL(decompress_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, da);
+  if (!launch_ok()) return ZC_ERR_HIP;
+  if (!n_out) return ZC_OK;
+  return finish(d_ws, n_out, stream);
+}
+
+int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes, int k, void* d_out, size_t out_cap,
+                         size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (k < 1 || k > ZC_MAX_K || !d_chunks || !chunk_bytes || !d_out || !d_ws) return ZC_ERR_ARG;
+  if (!aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
+  for (int i = 0; i < k; ++i)
+    if (!d_chunks[i] || !aligned16(d_chunks[i])) return ZC_ERR_ARG;
+  for (int i = 0; i < k; ++i)
+    if (chunk_bytes[i] < kHeaderBytes) return ZC_ERR_FORMAT;
+  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, k);
+  if (l.tiles_cap < 1) return ZC_ERR_ARG;
+  u64 tiles = l.tiles_cap;
+  for (int i = 0; i < k; ++i) {
+    const u64 t = num_tiles(blocks_bound(chunk_bytes[i]));
+    if (t < tiles) tiles = t;
+  }
+  if (tiles < 1) tiles = 1;
+  launch_init(l, u32(tiles), nullptr, 0, 0, 0, stream);
+  ScanArgs sa;
+  ReduceArgs ra;
+  for (int i = 0; i < k; ++i) {
+    sa.streams[i].base = static_cast<const u8*>(d_chunks[i]);
+    sa.streams[i].bytes = chunk_bytes[i];
+    ra.in[i] = sa.streams[i];
+  }
+  sa.k = k;
+  sa.check_match = 1;
+  sa.tiles_cap = l.tiles_cap;
+  sa.seg_off = l.seg_off;
+  sa.ctl = l.ctl;
+  hipLaunchKernelGGL(segment_sizes_kernel, dim3(u32(tiles), u32(k)), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(segment_scan_kernel, dim3(u32(k)), dim3(1024), 0, stream, sa);
+  ra.k = k;
+  ra.tiles_cap = l.tiles_cap;
+  ra.seg_off = l.seg_off;
+  ra.out = static_cast<u8*>(d_out);
+  ra.out_cap = out_cap;
+  ra.ctl = l.ctl;
+  ra.desc = l.desc;
+  hipLaunchKernelGGL(reduce_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
+  if (!launch_ok()) return ZC_ERR_HIP;
+  if (!out_bytes) return ZC_OK;
+  return finish(d_ws, out_bytes, stream);
+}
+
+int zc_peek_header(const void* d_in, size_t in_bytes, size_t* n, float* abs_eb, unsigned* nsum,
+                   size_t* total_bytes, void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (!d_in) return ZC_ERR_ARG;
+  if (in_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
+  u32 w[8];
+  if (hipMemcpyAsync(w, d_in, sizeof(w), hipMemcpyDeviceToHost, stream) != hipSuccess) return ZC_ERR_HIP;
+  if (hipStreamSynchronize(stream) != hipSuccess) return ZC_ERR_HIP;
+  const u64 nn = u64(w[2]) | (u64(w[3]) << 32);
+  const u64 total = u64(w[6]) | (u64(w[7]) << 32);
+  float eb;
+  std::memcpy(&eb, &w[4], 4);
+  if (w[0] != kMagic || w[1] != (1u | (5u << 16) | (6u << 24)) || nn > ZC_MAX_N || !eb_valid(eb) || w[5] < 1 ||
+      total > in_bytes || total < tables_end(num_blocks(nn)))
+    return ZC_ERR_FORMAT;
+  if (n) *n = size_t(nn);
+  if (abs_eb) *abs_eb = eb;
+  if (nsum) *nsum = w[5];
+  if (total_bytes) *total_bytes = size_t(total);
+  return ZC_OK;
+}
+
+int zc_debug_quantize(const float* d_in, size_t n, float abs_eb, int32_t* d_q, void* d_ws, size_t ws_bytes,
+                      void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (!eb_valid(abs_eb) || n > ZC_MAX_N || (n && (!d_in || !d_q)) || !d_ws || ws_bytes < sizeof(Control))
+    return ZC_ERR_ARG;
+  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
+  CompressArgs ca;
+  fill_compress_args(ca, d_in, n, abs_eb, nullptr, 0, l);
+  launch_init(l, 0, nullptr, 0, 0, 0, stream);
+  if (n) hipLaunchKernelGGL(quantize_kernel, dim3(u32((n + 255) / 256)), dim3(256), 0, stream, ca, d_q);
+  if (!launch_ok()) return ZC_ERR_HIP;
+  return finish(d_ws, nullptr, stream);
+}
+
+int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_words, size_t off_cap, void* d_ws,
+                           size_t ws_bytes, void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (!d_in || !d_ws || (off_cap && !d_off_words) || !aligned16(d_in) || !aligned16(d_ws)) return ZC_ERR_ARG;
+  if (in_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
+  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
+  if (l.tiles_cap < 1) return ZC_ERR_ARG;
+  u64 tiles = num_tiles(blocks_bound(in_bytes));
+  if (tiles > l.tiles_cap) tiles = l.tiles_cap;
+  if (tiles < 1) tiles = 1;
+  launch_init(l, 0, nullptr, 0, 0, 0, stream);
+  ScanArgs sa;
+  sa.streams[0].base = static_cast<const u8*>(d_in);
+  sa.streams[0].bytes = in_bytes;
+  sa.k = 1;
+  sa.check_match = 0;
+  sa.tiles_cap = l.tiles_cap;
+  sa.seg_off = l.seg_off;
+  sa.ctl = l.ctl;
+  hipLaunchKernelGGL(segment_sizes_kernel, dim3(u32(tiles), 1), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(segment_scan_kernel, dim3(1), dim3(1024), 0, stream, sa);
+  OffsetsArgs oa;
+  oa.in = sa.streams[0];
+  oa.tiles_cap = l.tiles_cap;
+  oa.seg_off = l.seg_off;
+  oa.off_words = d_off_words;
+  oa.off_cap = off_cap;
+  oa.ctl = l.ctl;
+  hipLaunchKernelGGL(block_offsets_kernel, dim3(u32(tiles)), dim3(256), 0, stream, oa);
+  if (!launch_ok()) return ZC_ERR_HIP;
+  return finish(d_ws, nullptr, stream);
+}
+
+}  // extern "C"

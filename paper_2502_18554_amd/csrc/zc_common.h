@@ -1,0 +1,189 @@
+// Shared definitions of the HIP codec: stream geometry, workspace layout, status bits and
+// the wave-level building blocks (scan, look-back) used by the kernels.  gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/zc.h"
+
+namespace zc {
+
+using u8 = uint8_t;
+using u16 = uint16_t;
+using u32 = uint32_t;
+using u64 = uint64_t;
+using i32 = int32_t;
+using i64 = int64_t;
+
+constexpr u32 kMagic = 0x314C435Au;
+constexpr u32 kHeaderBytes = 32;
+constexpr int kBlockValues = 32;           // values per block (Section 3.3 "small blocks")
+constexpr int kWaveBlocks = 64;            // one lane owns one block
+constexpr int kTileWaves = 4;
+constexpr int kTileThreads = kTileWaves * 64;
+constexpr int kTileBlocks = kTileWaves * kWaveBlocks;        // 256 blocks
+constexpr int kTileValues = kTileBlocks * kBlockValues;      // 8192 values = 32 KiB of input
+constexpr int kRow = 36;                   // LDS row stride in words (32 + 4: conflict-free 128-bit access)
+constexpr int kWaveLds = kWaveBlocks * kRow;                 // words of LDS per wave
+constexpr i64 kMaxCode = (i64(1) << 30) - 1;
+constexpr u32 kSpinLimit = 1u << 20;       // bound on every look-back wait
+
+__host__ __device__ inline u64 pad16(u64 v) { return (v + 15) / 16 * 16; }
+__host__ __device__ inline u64 num_blocks(u64 n) { return (n + kBlockValues - 1) / kBlockValues; }
+__host__ __device__ inline u64 num_tiles(u64 nb) { return (nb + kTileBlocks - 1) / kTileBlocks; }
+__host__ __device__ inline u64 tables_end(u64 nb) { return kHeaderBytes + pad16(nb) + pad16(4 * nb); }
+__host__ __device__ inline u32 psize_words(u32 w) { return w ? 1 + w : 0; }
+
+// Device status word: bit i set <=> error code i was raised.
+__host__ __device__ constexpr u32 status_bit(int code) { return 1u << code; }
+
+// Errors that only the validation kernels (zc_scan.h) raise.  They are final before a main
+// kernel starts, so every workgroup of a main kernel takes the same decision on them.
+constexpr u32 kGateBits = status_bit(ZC_ERR_ARG) | status_bit(ZC_ERR_FORMAT) | status_bit(ZC_ERR_MISMATCH);
+
+// Control part of the caller's workspace.  Tile descriptors and segment-offset tables follow.
+struct Control {
+  u32 ticket;     // next tile to hand out (compress, reduce)
+  u32 status;     // OR of status_bit()s
+  u64 result;     // total_bytes, or n for decompress
+  u32 pad[12];
+};
+static_assert(sizeof(Control) == 64, "control block is 64 bytes");
+
+// A segment is the 64 blocks owned by one wave; a tile is 4 segments.
+__host__ __device__ inline u64 num_segments(u64 nb) { return (nb + kWaveBlocks - 1) / kWaveBlocks; }
+
+// How a workspace of ws_bytes is carved up for calls with k input streams:
+//   Control | desc[tiles_cap] (u64) | seg_off[k][4 * tiles_cap] (u32)
+// tiles_cap follows from ws_bytes alone, so kernels can refuse streams that do not fit.
+struct WorkspaceLayout {
+  u64 tiles_cap;
+  Control* ctl;
+  u64* desc;
+  u32* seg_off;     // row stride = 4 * tiles_cap
+};
+
+constexpr u64 kWsFixed = sizeof(Control) + 32;
+
+__host__ inline u64 workspace_bytes(u64 n_max, int k_max) {
+  if (k_max < 1) k_max = 1;
+  const u64 t = num_tiles(num_blocks(n_max)) + 1;
+  return kWsFixed + t * (8 + 16 * u64(k_max));
+}
+
+__host__ inline WorkspaceLayout workspace_layout(void* d_ws, u64 ws_bytes, int k) {
+  if (k < 1) k = 1;
+  WorkspaceLayout l;
+  l.tiles_cap = ws_bytes > kWsFixed ? (ws_bytes - kWsFixed) / (8 + 16 * u64(k)) : 0;
+  u8* p = static_cast<u8*>(d_ws);
+  l.ctl = reinterpret_cast<Control*>(p);
+  l.desc = reinterpret_cast<u64*>(p + sizeof(Control));
+  l.seg_off = reinterpret_cast<u32*>(p + sizeof(Control) + pad16(8 * l.tiles_cap));
+  return l;
+}
+
+// ---------------------------------------------------------------------------------------
+// Wave-level primitives (64 lanes).
+// ---------------------------------------------------------------------------------------
+__device__ inline int lane_id() { return int(threadIdx.x) & 63; }
+
+// True when validation failed and the main kernel must not touch the stream.
+__device__ inline bool validation_failed(const Control* ctl) {
+  return (__hip_atomic_load(&ctl->status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kGateBits) != 0;
+}
+
+// Row shift right by S lanes inside each row of 16 lanes; lanes without a source get 0.
+template <int S>
+__device__ inline u32 dpp_row_shr_or_zero(u32 v) {
+  return u32(__builtin_amdgcn_update_dpp(0, int(v), 0x110 + S, 0xf, 0xf, false));
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ inline u32 wave_inclusive_sum(u32 v) {
+  v += dpp_row_shr_or_zero<1>(v);
+  v += dpp_row_shr_or_zero<2>(v);
+  v += dpp_row_shr_or_zero<4>(v);
+  v += dpp_row_shr_or_zero<8>(v);
+  // v is now the scan inside each row of 16; add the totals of the earlier rows
+  u32 t0 = u32(__shfl(int(v), 15)), t1 = u32(__shfl(int(v), 31)), t2 = u32(__shfl(int(v), 47));
+  int row = lane_id() >> 4;
+  u32 carry = (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
+  return v + carry;
+}
+
+__device__ inline u32 wave_sum_u32(u32 v) {
+  for (int s = 32; s >= 1; s >>= 1) v += u32(__shfl_xor(int(v), s));
+  return v;
+}
+
+// A value known to be the same in every lane, moved to a scalar register so that branches on
+// it are scalar branches.
+__device__ inline u32 uniform(u32 v) { return u32(__builtin_amdgcn_readfirstlane(int(v))); }
+
+__device__ inline u32 wave_max_u32(u32 v) {
+  for (int s = 32; s >= 1; s >>= 1) {
+    u32 o = u32(__shfl_xor(int(v), s));
+    v = o > v ? o : v;
+  }
+  return uniform(v);
+}
+
+__device__ inline u64 wave_sum_u64(u64 v) {
+  for (int s = 32; s >= 1; s >>= 1) {
+    u32 lo = u32(__shfl_xor(int(u32(v)), s));
+    u32 hi = u32(__shfl_xor(int(u32(v >> 32)), s));
+    v += (u64(hi) << 32) | lo;
+  }
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// Decoupled look-back over tile descriptors.  A descriptor is one 64-bit word:
+// bits 63..62 = state (0 empty, 1 tile aggregate, 2 inclusive prefix), bits 61..0 = value.
+// Only the descriptor word itself is communicated, so relaxed device-scope atomics suffice.
+// ---------------------------------------------------------------------------------------
+constexpr u64 kDescAggregate = u64(1) << 62;
+constexpr u64 kDescPrefix = u64(2) << 62;
+constexpr u64 kDescValueMask = (u64(1) << 62) - 1;
+
+__device__ inline void desc_store(u64* d, u64 v) {
+  __hip_atomic_store(d, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline u64 desc_load(const u64* d) {
+  return __hip_atomic_load(d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Called by all 64 lanes of one wave.  Returns the sum of the values of tiles [0, tile).
+// Every predecessor tile has taken its ticket before this tile did and publishes its
+// aggregate without waiting for anything, so the wait below ends; it is bounded anyway and
+// raises ZC_ERR_HIP in *status if the bound is hit.
+__device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status) {
+  const int lane = lane_id();
+  u64 excl = 0;
+  i64 look = i64(tile) - 1;                  // lane 0 inspects the nearest predecessor
+  u32 spins = 0;
+  while (true) {
+    i64 idx = look - lane;
+    u64 d = idx >= 0 ? desc_load(desc + idx) : kDescPrefix;   // "tile -1" has prefix 0
+    u32 state = u32(d >> 62);
+    u64 has_prefix = __ballot(state == 2);
+    u64 is_empty = __ballot(state == 0);
+    int first = has_prefix ? __builtin_ctzll(has_prefix) : 63;
+    u64 needed = first == 63 ? ~u64(0) : ((u64(2) << first) - 1);   // lanes 0..first
+    if (is_empty & needed) {
+      if (++spins > kSpinLimit) {
+        if (lane == 0) atomicOr(status, status_bit(ZC_ERR_HIP));
+        return excl;
+      }
+      __builtin_amdgcn_s_sleep(1);
+      continue;
+    }
+    u64 contrib = lane <= first ? (d & kDescValueMask) : 0;
+    excl += wave_sum_u64(contrib);
+    if (has_prefix) return excl;
+    look -= 64;
+  }
+}
+
+}  // namespace zc

@@ -1,0 +1,63 @@
+"""Helpers for the GPU parity tests: run the HIP library through its C ABI on torch buffers
+and hand back numpy arrays that can be compared with the reference CPU codec."""
+import numpy as np
+import torch
+
+import paper_2502_18554_amd as zc
+
+DEV = "cuda:0"
+
+
+def to_dev(x):
+    if isinstance(x, np.ndarray):
+        x = torch.from_numpy(np.ascontiguousarray(x))
+    return x.to(DEV).contiguous()
+
+
+def workspace(n, k=1):
+    return torch.empty(zc.zc_workspace_bytes(n, k) + 16, dtype=torch.uint8, device=DEV)
+
+
+def gpu_compress(x, eb, out_cap=None, ws=None):
+    """-> (status, stream bytes (numpy uint8), total_bytes)"""
+    d_in = to_dev(x)
+    n = d_in.numel()
+    cap = zc.zc_compress_bound(n) if out_cap is None else out_cap
+    d_out = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device=DEV)
+    ws = workspace(n) if ws is None else ws
+    st, total = zc.zc_compress(d_in, n, float(eb), d_out, ws, out_cap=cap)
+    assert bool((d_out[cap:] == 0xA5).all()), "wrote past out_cap"
+    torch.cuda.synchronize()
+    out = d_out[: min(total, cap)].cpu().numpy() if st in (zc.binding.ZC_OK, zc.binding.ZC_ERR_BOUND) else None
+    return st, out, total
+
+
+def gpu_decompress(stream, n_cap, in_bytes=None, ws=None):
+    """-> (status, float32 numpy array of n values, n)"""
+    d_in = to_dev(stream)
+    in_bytes = d_in.numel() if in_bytes is None else in_bytes
+    d_out = torch.full((max(n_cap, 4),), float("nan"), dtype=torch.float32, device=DEV)
+    ws = workspace(max(n_cap, 1)) if ws is None else ws
+    st, n = zc.zc_decompress(d_in, in_bytes, d_out, ws, out_cap_elems=n_cap)
+    torch.cuda.synchronize()
+    return st, (d_out[:n].cpu().numpy() if st == zc.binding.ZC_OK else None), n
+
+
+def gpu_reduce(streams, n, out_cap=None, ws=None):
+    """-> (status, stream bytes, total_bytes)"""
+    d_chunks = [to_dev(s) for s in streams]
+    cap = zc.zc_compress_bound(n) if out_cap is None else out_cap
+    d_out = torch.full((cap + 64,), 0x5A, dtype=torch.uint8, device=DEV)
+    ws = workspace(max(n, 1), len(streams)) if ws is None else ws
+    st, total = zc.zc_reduce_compressed(d_chunks, [c.numel() for c in d_chunks], d_out, ws, out_cap=cap)
+    assert bool((d_out[cap:] == 0x5A).all()), "wrote past out_cap"
+    torch.cuda.synchronize()
+    return st, (d_out[: min(total, cap)].cpu().numpy() if st == zc.binding.ZC_OK else None), total
+
+
+def first_diff(a, b):
+    a = np.asarray(a); b = np.asarray(b)
+    if a.shape != b.shape:
+        return f"shape {a.shape} vs {b.shape}"
+    d = np.nonzero(a != b)[0]
+    return "equal" if d.size == 0 else f"{d.size} differ, first at {d[0]}: {a[d[0]]} vs {b[d[0]]}"

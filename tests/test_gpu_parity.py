@@ -1,0 +1,321 @@
+"""GPU parity: the HIP library, called through its C ABI, against the reference CPU codec on the
+same seeded inputs.  Bit-exact on codes, widths, offsets and stream bytes; reconstructed
+floats bit-exact (the tolerance allowed is 1 ulp) and within eb of the input."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_18554_amd as zc
+from paper_2502_18554_amd import synth
+from paper_2502_18554_amd.binding import (ZC_ERR_ARG, ZC_ERR_BOUND, ZC_ERR_CAPACITY, ZC_ERR_FORMAT,
+                                           ZC_ERR_MISMATCH, ZC_ERR_NONFINITE, ZC_ERR_RANGE, ZC_OK)
+
+pytestmark = pytest.mark.gpu
+
+TILE = 8192
+
+
+def _u():
+    import gpuutil
+    return gpuutil
+
+
+def _inputs():
+    yield "sin_1M", lambda: synth.sinusoids(1 << 20, seed=0).numpy(), 1e-4          # config 1
+    yield "grf_ragged", lambda: synth.power_law_field((24, 64, 64), seed=1).numpy()[: 3 * TILE + 777], 1e-3
+    yield "grf_1e-2", lambda: synth.power_law_field((32, 64, 64), seed=2).numpy(), 1e-2
+    yield "grf_1e-4", lambda: synth.power_law_field((32, 64, 64), seed=3).numpy(), 1e-4
+    yield "hard", lambda: synth.hard_mix(5 * TILE + 4097, seed=4).numpy(), 1e-5
+
+
+_IDS = [i[0] for i in _inputs()]
+
+
+@pytest.mark.parametrize("name,make,rel", list(_inputs()), ids=_IDS)
+def test_compress_stream_matches_reference(zcref, name, make, rel):
+    u = _u()
+    x = make()
+    eb = synth.abs_bound(torch.from_numpy(x), rel)
+    st_ref, s_ref, total_ref = zcref.compress(x, eb)
+    # stage 1: quantisation codes
+    d_q = torch.empty(x.size, dtype=torch.int32, device=u.DEV)
+    st = zc.zc_debug_quantize(u.to_dev(x), x.size, eb, d_q, u.workspace(x.size))
+    _, q_ref = zcref.quantize(x, eb)
+    assert st == st_ref == ZC_OK
+    assert np.array_equal(d_q.cpu().numpy(), q_ref), u.first_diff(d_q.cpu().numpy(), q_ref)
+    # stage 2: the stream
+    st, s, total = u.gpu_compress(x, eb)
+    assert st == ZC_OK and total == total_ref
+    nb = (x.size + 31) // 32
+    _, _, w_ref, off_ref = zcref.inspect(s_ref)
+    assert np.array_equal(s[32:32 + nb], w_ref), "widths: " + u.first_diff(s[32:32 + nb], w_ref)
+    assert s.tobytes() == s_ref.tobytes(), u.first_diff(s, s_ref)
+    # stage 3: block offsets recomputed from the stream
+    d_off = torch.empty(nb, dtype=torch.int32, device=u.DEV)
+    st = zc.zc_debug_block_offsets(u.to_dev(s), s.size, d_off, u.workspace(x.size))
+    assert st == ZC_OK
+    assert np.array_equal(d_off.cpu().numpy().astype(np.uint64) * 4, off_ref)
+
+
+@pytest.mark.parametrize("name,make,rel", list(_inputs()), ids=_IDS)
+def test_decompress_matches_reference(zcref, name, make, rel):
+    u = _u()
+    x = make()
+    eb = synth.abs_bound(torch.from_numpy(x), rel)
+    _, s_ref, _ = zcref.compress(x, eb)
+    _, y_ref, _ = zcref.decompress(s_ref)
+    st, y, n = u.gpu_decompress(s_ref, x.size)
+    assert st == ZC_OK and n == x.size
+    assert np.array_equal(y.view(np.uint32), y_ref.view(np.uint32)), u.first_diff(y, y_ref)
+    assert np.max(np.abs(y.astype(np.float64) - x.astype(np.float64))) <= eb
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 31, 32, 33, 63, 64, 65, 2047, 2048, 2049, 4095, 4096, 4097,
+                               TILE - 1, TILE, TILE + 1, 2 * TILE + 31])
+def test_edge_sizes_round_trip(zcref, n):
+    u = _u()
+    rng = np.random.default_rng(n)
+    x = np.cumsum(rng.normal(0, 0.01, n)).astype(np.float32)
+    eb = 1e-3
+    st_ref, s_ref, total_ref = zcref.compress(x, eb)
+    st, s, total = u.gpu_compress(x, eb)
+    assert st == st_ref == ZC_OK and total == total_ref
+    assert s.tobytes() == s_ref.tobytes(), u.first_diff(s, s_ref)
+    st, y, m = u.gpu_decompress(s, max(n, 1))
+    _, y_ref, _ = zcref.decompress(s_ref)
+    assert st == ZC_OK and m == n
+    assert np.array_equal(y.view(np.uint32), y_ref.view(np.uint32))
+
+
+def test_constant_blocks_and_worked_example(zcref):
+    u = _u()
+    x = np.full(3 * TILE + 5, 3.25, np.float32)
+    st, s, total = u.gpu_compress(x, 1e-2)
+    nb = (x.size + 31) // 32
+    assert st == ZC_OK and total == 32 + (nb + 15) // 16 * 16 + (4 * nb + 15) // 16 * 16
+    assert not s[32:32 + nb].any()
+    assert s.tobytes() == zcref.compress(x, 1e-2)[1].tobytes()
+    xw = np.array([10, 11, 13, 12, 12, 12, 9, 10] + [10] * 24, np.float32)
+    st, s, total = u.gpu_compress(xw, 0.5)
+    assert total == 76 and s[64:76].tobytes() == bytes.fromhex("48000000CA00000044000000")
+
+
+def test_wide_widths_and_bound_status(zcref):
+    """Widths up to 31 come from inputs outside the guaranteed domain; status and stream must
+    still agree with the reference."""
+    u = _u()
+    rng = np.random.default_rng(7)
+    eb = np.float32(2.0 ** -20)
+    step = float(eb) * 63 / 32
+    scale = np.repeat(2.0 ** rng.integers(0, 30, 4 * TILE // 32), 32)
+    q = (rng.uniform(-1, 1, scale.size) * scale).astype(np.int64)
+    x = (q * step).astype(np.float32)
+    st_ref, s_ref, total_ref = zcref.compress(x, eb)
+    st, s, total = u.gpu_compress(x, eb)
+    assert st == st_ref and st in (ZC_OK, ZC_ERR_BOUND) and total == total_ref
+    assert s.tobytes() == s_ref.tobytes(), u.first_diff(s, s_ref)
+    assert zcref.inspect(s_ref)[2].max() >= 28
+    st, y, n = u.gpu_decompress(s_ref, x.size)
+    assert np.array_equal(y.view(np.uint32), zcref.decompress(s_ref)[1].view(np.uint32))
+    # streams that only the encode-from-codes helper can make: every block at width 31
+    q = np.tile(np.array([-(2 ** 30) + 1, 2 ** 30 - 1], np.int32), 16 * 300)
+    q[::7] //= 3
+    _, s31, _ = zcref.encode_codes(q, 1e-3)
+    st, y, n = u.gpu_decompress(s31, q.size)
+    assert st == ZC_OK and np.array_equal(y.view(np.uint32), zcref.decompress(s31)[1].view(np.uint32))
+    # the status screen: values around 2^17 eb and 2^18 eb, inside and outside the domain
+    eb2 = np.float32(8.8 * 2.0 ** -23)
+    x2 = np.linspace(1.0, 2.0, 50000).astype(np.float32)
+    st_ref, s_ref, _ = zcref.compress(x2, eb2)
+    st, s, _ = u.gpu_compress(x2, eb2)
+    assert st == st_ref == ZC_ERR_BOUND and s.tobytes() == s_ref.tobytes()
+    for top in (2.0 ** 17, 2.0 ** 17 * 1.001, 2.0 ** 18, 2.0 ** 19):
+        x3 = (np.linspace(-1, 1, 3 * TILE + 3) * top * 1e-3).astype(np.float32)
+        st_ref, s_ref, _ = zcref.compress(x3, 1e-3)
+        st, s, _ = u.gpu_compress(x3, 1e-3)
+        assert st == st_ref and s.tobytes() == s_ref.tobytes()
+
+
+def test_ties_and_signed_zero(zcref):
+    u = _u()
+    step = 0.5 * 63 / 32
+    m = np.arange(-4000, 4001)
+    x = ((m + 0.5) * step).astype(np.float32)
+    x = np.concatenate([x, np.array([-0.0, 0.0, 1e-40, -1e-40], np.float32)])
+    st_ref, s_ref, _ = zcref.compress(x, 0.5)
+    st, s, _ = u.gpu_compress(x, 0.5)
+    assert st == st_ref == ZC_OK and s.tobytes() == s_ref.tobytes()
+    st, y, _ = u.gpu_decompress(s, x.size)
+    assert np.array_equal(y.view(np.uint32), zcref.decompress(s_ref)[1].view(np.uint32))
+
+
+def test_compress_error_paths(zcref):
+    u = _u()
+    x = np.linspace(0, 1, 3 * TILE).astype(np.float32)
+    for bad in (0.0, -1.0, float("inf"), float("nan"), 2.0 ** -97):
+        assert u.gpu_compress(x, bad)[0] == ZC_ERR_ARG
+    y = x.copy(); y[TILE + 7] = np.nan
+    assert u.gpu_compress(y, 1e-3)[0] == ZC_ERR_NONFINITE == zcref.compress(y, 1e-3)[0]
+    y[TILE + 7] = -np.inf
+    assert u.gpu_compress(y, 1e-3)[0] == ZC_ERR_NONFINITE
+    y[TILE + 7] = 3e6
+    assert u.gpu_compress(y, 1e-3)[0] == ZC_ERR_RANGE == zcref.compress(y, 1e-3)[0]
+    y[9] = np.nan
+    assert u.gpu_compress(y, 1e-3)[0] == ZC_ERR_NONFINITE
+    st_ref, s_ref, total = zcref.compress(x, 1e-5)
+    for cap in (total - 1, total - 4, 40, 0, 16):
+        st, _, need = u.gpu_compress(x, 1e-5, out_cap=cap)
+        assert st == ZC_ERR_CAPACITY and need == total
+    # nothing is written past out_cap
+    d_in = u.to_dev(x)
+    d_out = torch.full((total + 64,), 0xA5, dtype=torch.uint8, device=u.DEV)
+    cap = total - 4096
+    st, need = zc.zc_compress(d_in, x.size, 1e-5, d_out[:cap], u.workspace(x.size))
+    assert st == ZC_ERR_CAPACITY and need == total
+    assert bool((d_out[cap:] == 0xA5).all())
+    st, _, _ = u.gpu_compress(x, 1e-5, ws=torch.empty(64, dtype=torch.uint8, device=u.DEV))
+    assert st == ZC_ERR_ARG                      # workspace too small
+
+
+def test_decompress_error_paths(zcref):
+    u = _u()
+    x = np.linspace(0, 1, 2 * TILE + 100).astype(np.float32)
+    _, s, total = zcref.compress(x, 1e-4)
+    assert u.gpu_decompress(s[:16], x.size)[0] == ZC_ERR_FORMAT
+    assert u.gpu_decompress(s[:-1], x.size)[0] == ZC_ERR_FORMAT == zcref.decompress(s[:-1])[0]
+    for pos in (0, 4, 6, 7):
+        t = s.copy(); t[pos] ^= 1
+        assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT
+    t = s.copy(); t[32 + 300] = 32
+    assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT
+    t = s.copy(); t[32 + 300] ^= 1
+    assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT
+    t = s.copy(); t[20:24] = 0
+    assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT
+    t = s.copy(); t[16:20] = 0
+    assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT
+    st, _, n = u.gpu_decompress(s, x.size - 1)
+    assert st == ZC_ERR_CAPACITY and n == x.size
+    longer = np.concatenate([s, np.zeros(7, np.uint8)])
+    st, y, n = u.gpu_decompress(longer, x.size + 1000)
+    assert st == ZC_OK and n == x.size and np.array_equal(y, zcref.decompress(s)[1])
+    st, h_n, h_eb, h_nsum, h_total = zc.zc_peek_header(u.to_dev(s), s.size)
+    assert (st, h_n, h_nsum, h_total) == (ZC_OK, x.size, 1, total) and h_eb == np.float32(1e-4)
+
+
+def _rank_streams(zcref, k, n, rel, seed0):
+    xs = [synth.power_law_field((n // 4096, 64, 64), seed=seed0 + i).numpy()[:n] for i in range(k)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), rel)
+    streams = [zcref.compress(x, eb)[1] for x in xs]
+    return xs, eb, streams
+
+
+@pytest.mark.parametrize("k,n", [(1, 4096 * 4), (2, 4096 * 4 - 37), (3, 4096 * 9 + 1), (8, 4096 * 16), (17, 4096 * 3 + 5)])
+def test_reduce_stream_matches_reference(zcref, k, n):
+    u = _u()
+    xs, eb, streams = _rank_streams(zcref, k, (n + 4095) // 4096 * 4096, 1e-4, seed0=20)
+    xs = [x[:n] for x in xs]
+    streams = [zcref.compress(x, eb)[1] for x in xs]
+    st_ref, r_ref, total_ref = zcref.reduce(streams)
+    st, r, total = u.gpu_reduce(streams, n)
+    assert st == st_ref == ZC_OK and total == total_ref
+    assert r.tobytes() == r_ref.tobytes(), u.first_diff(r, r_ref)
+    st, y, _ = u.gpu_decompress(r, n)
+    exact = np.sum([x.astype(np.float64) for x in xs], axis=0)
+    assert np.max(np.abs(y.astype(np.float64) - exact)) <= k * eb
+    assert int(r[20:24].view("<u4")[0]) == k
+    # nested reduce on the GPU gives the flat result
+    if k >= 3:
+        _, a, _ = u.gpu_reduce(streams[:2], n)
+        _, b, _ = u.gpu_reduce(streams[2:], n)
+        _, ab, _ = u.gpu_reduce([a, b], n)
+        assert ab.tobytes() == r_ref.tobytes()
+
+
+def test_reduce_wide_and_cancelling_operands(zcref):
+    u = _u()
+    rng = np.random.default_rng(11)
+    n = 3 * TILE + 77
+    scale = np.repeat(2.0 ** rng.integers(0, 27, (n + 31) // 32), 32)[:n]
+    qs = [(rng.uniform(-1, 1, n) * scale).astype(np.int32) for _ in range(5)]
+    qs.append(-qs[0])                                 # exact cancellation with operand 0
+    qs.append(np.zeros(n, np.int32))                  # all-constant operand
+    streams = [zcref.encode_codes(q, 1e-3)[1] for q in qs]
+    st_ref, r_ref, total_ref = zcref.reduce(streams)
+    st, r, total = u.gpu_reduce(streams, n)
+    assert st == st_ref == ZC_OK and total == total_ref
+    assert r.tobytes() == r_ref.tobytes(), u.first_diff(r, r_ref)
+    # everything cancels: all widths zero
+    st, r, total = u.gpu_reduce([streams[0], streams[5]], n)
+    assert st == ZC_OK and r.tobytes() == zcref.reduce([streams[0], streams[5]])[1].tobytes()
+    assert not r[32:32 + (n + 31) // 32].any()
+
+
+def test_reduce_error_paths(zcref):
+    u = _u()
+    xs, eb, streams = _rank_streams(zcref, 2, 4096 * 3, 1e-3, seed0=30)
+    n = xs[0].size
+    _, other, _ = zcref.compress(xs[0], eb * 2)
+    assert u.gpu_reduce([streams[0], other], n)[0] == ZC_ERR_MISMATCH == zcref.reduce([streams[0], other])[0]
+    _, short, _ = zcref.compress(xs[0][:-32], eb)
+    assert u.gpu_reduce([streams[0], short], n)[0] == ZC_ERR_MISMATCH
+    bad = streams[1].copy(); bad[0] ^= 1
+    assert u.gpu_reduce([streams[0], bad], n)[0] == ZC_ERR_FORMAT
+    assert u.gpu_reduce([streams[0], bad, other], n)[0] == ZC_ERR_FORMAT      # precedence
+    big = np.full(TILE + 64, 2 ** 30 - 1, np.int32)
+    big[TILE:] = 5
+    _, sb, _ = zcref.encode_codes(big, eb)
+    assert u.gpu_reduce([sb, sb], big.size)[0] == ZC_ERR_RANGE == zcref.reduce([sb, sb])[0]
+    assert u.gpu_reduce([sb], big.size)[0] == ZC_OK
+    # a block whose outlier is fine but whose chain runs out of range
+    ramp = np.zeros(TILE, np.int32); ramp[40:] = 2 ** 29 + 5
+    _, sr, _ = zcref.encode_codes(ramp, eb)
+    assert u.gpu_reduce([sr, sr], ramp.size)[0] == ZC_ERR_RANGE == zcref.reduce([sr, sr])[0]
+    # near the limit but inside: exact check must accept
+    ok = np.zeros(TILE, np.int32); ok[40:] = 2 ** 29 - 1
+    _, so, _ = zcref.encode_codes(ok, eb)
+    st, r, _ = u.gpu_reduce([so, so], ok.size)
+    assert st == ZC_OK and r.tobytes() == zcref.reduce([so, so])[1].tobytes()
+    st_ref, r_ref, total = zcref.reduce(streams)
+    st, _, need = u.gpu_reduce(streams, n, out_cap=total - 4)
+    assert st == ZC_ERR_CAPACITY and need == total
+    assert u.gpu_reduce([], n)[0] == ZC_ERR_ARG
+
+
+def test_async_form_and_workspace_reuse(zcref):
+    u = _u()
+    x = synth.power_law_field((8, 64, 64), seed=5).numpy()
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    _, s_ref, total_ref = zcref.compress(x, eb)
+    d_in = u.to_dev(x)
+    d_out = torch.empty(zc.zc_compress_bound(x.size), dtype=torch.uint8, device=u.DEV)
+    ws = u.workspace(x.size)
+    ws.fill_(0xFF)                                     # stale workspace content must not matter
+    for _ in range(3):
+        st, none = zc.zc_compress(d_in, x.size, eb, d_out, ws, sync=False)
+        assert st == ZC_OK and none is None
+        st, total = zc.zc_finish(ws)
+        assert st == ZC_OK and total == total_ref
+        assert d_out[:total].cpu().numpy().tobytes() == s_ref.tobytes()
+    d_y = torch.empty(x.size, dtype=torch.float32, device=u.DEV)
+    st, _ = zc.zc_decompress(d_out, total_ref, d_y, ws, sync=False)
+    st, n = zc.zc_finish(ws)
+    assert st == ZC_OK and n == x.size
+    assert np.array_equal(d_y.cpu().numpy(), zcref.decompress(s_ref)[1])
+
+
+def test_repeated_runs_are_identical():
+    """The look-back scan is the only cross-workgroup protocol: many tiles, many runs, one answer."""
+    u = _u()
+    x = synth.hard_mix(1 << 22, seed=6, device=u.DEV)
+    eb = synth.abs_bound(x, 1e-5)
+    d_out = torch.empty(zc.zc_compress_bound(x.numel()), dtype=torch.uint8, device=u.DEV)
+    ws = u.workspace(x.numel())
+    first = None
+    for _ in range(20):
+        st, total = zc.zc_compress(x, x.numel(), eb, d_out, ws)
+        assert st == ZC_OK
+        got = d_out[:total].clone()
+        if first is None:
+            first = got
+        assert torch.equal(first, got)
