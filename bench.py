@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the zc hot path on one MI355X.
+
+One step = one pass of the whole hot path on synthetic data already resident in HBM:
+  1. zc_compress    of a 512^3 fp32 Gaussian random field (P(k) ~ k^-3), rel. bound 1e-4
+  2. zc_decompress  of that stream
+  3. zc_reduce_compressed of 8 compressed rank buffers of 64M values (same generator, other
+     seeds, common absolute bound), the local step of a compressed Allreduce.
+`value` is fp32 gigabytes moved through the step per second: 4n (compress input) + 4n
+(decompress output) + 4*8*m (the fp32 data the 8 reduce operands stand for), over the step
+time.  Per-stage throughput and roofline figures are in `stages`; `roofline` repeats the stage
+whose kernel runs longest.  The reference CPU codec is timed on a bounded sample of the same
+buffers as `cpu_baseline` (reported baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--rel", type=float, default=1e-4, help="value-range-relative error bound of the timed step")
+    ap.add_argument("--side", type=int, default=512, help="field side; 512 is the benchmark configuration")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the untimed sweep over the other error bounds")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import paper_2502_18554_amd as zc
+    from paper_2502_18554_amd import synth
+    from paper_2502_18554_amd.binding import ZC_OK
+
+    zc.binding.lib()                      # fails loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    side = args.side
+    K = 8
+    shape_c = (side, side, side)
+    shape_r = (side // 2, side, side)
+
+    def u8(nbytes):
+        return torch.empty(nbytes + 64, dtype=torch.uint8, device=dev)
+
+    def check(st, what):
+        if st != ZC_OK:
+            raise zc.ZcError(st, what)
+
+    # ---------------- inputs, resident in HBM ----------------
+    x = synth.power_law_field(shape_c, seed=0, device=dev)
+    n = x.numel()
+    eb = synth.abs_bound(x, args.rel)
+    d_stream = u8(zc.zc_compress_bound(n))
+    d_y = torch.empty(n, dtype=torch.float32, device=dev)
+    ws_c, ws_d = u8(zc.zc_workspace_bytes(n, 1)), u8(zc.zc_workspace_bytes(n, 1))
+
+    ranks, chunks, chunk_bytes = [], [], []
+    m = shape_r[0] * shape_r[1] * shape_r[2]
+    eb_r = float(torch.tensor(args.rel * 2.0, dtype=torch.float32))     # common bound: fields span [-1, 1]
+    scratch = u8(zc.zc_compress_bound(m))
+    ws_r = u8(zc.zc_workspace_bytes(m, K))
+    for r in range(K):
+        xr = synth.power_law_field(shape_r, seed=100 + r, device=dev)
+        st, total = zc.zc_compress(xr, m, eb_r, scratch, ws_r)
+        check(st, f"compress rank {r}")
+        chunks.append(scratch[:total].clone())
+        chunk_bytes.append(total)
+        ranks.append(xr)
+    d_red = u8(zc.zc_compress_bound(m))
+
+    st, c_bytes = zc.zc_compress(x, n, eb, d_stream, ws_c)
+    check(st, "compress")
+    st, n_out = zc.zc_decompress(d_stream, c_bytes, d_y, ws_d)
+    check(st, "decompress")
+    st, r_bytes = zc.zc_reduce_compressed(chunks, chunk_bytes, d_red, ws_r)
+    check(st, "reduce")
+    assert n_out == n
+    max_err = float((d_y.double() - x.double()).abs().max())
+    assert max_err <= eb, (max_err, eb)
+
+    stage_names = ("compress", "decompress", "reduce")
+    alg_bytes = {
+        "compress": 4 * n + c_bytes,
+        "decompress": c_bytes + 4 * n,
+        "reduce": sum(chunk_bytes) + r_bytes,
+    }
+    fp32_bytes = {"compress": 4 * n, "decompress": 4 * n, "reduce": 4 * m * K}
+
+    def step(events=None):
+        if events:
+            events[0].record()
+        zc.zc_compress(x, n, eb, d_stream, ws_c, sync=False)
+        if events:
+            events[1].record()
+        zc.zc_decompress(d_stream, c_bytes, d_y, ws_d, sync=False)
+        if events:
+            events[2].record()
+        zc.zc_reduce_compressed(chunks, chunk_bytes, d_red, ws_r, sync=False)
+        if events:
+            events[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for ws, what in ((ws_c, "compress"), (ws_d, "decompress"), (ws_r, "reduce")):
+        st, _ = zc.zc_finish(ws)
+        check(st, what + " (timed loop)")
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    stage_ms = {s: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, s in enumerate(stage_names)}
+    stages = {}
+    for s in stage_names:
+        gbs = alg_bytes[s] / stage_ms[s] / 1e6
+        stages[s] = {
+            "ms": round(stage_ms[s], 4),
+            "fp32_GBps": round(fp32_bytes[s] / stage_ms[s] / 1e6, 1),
+            "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None},
+            "algorithmic_bytes": alg_bytes[s],
+        }
+    dominant = max(stage_names, key=lambda s: stage_ms[s])
+    total_fp32 = sum(fp32_bytes.values())
+    value = total_fp32 / ms_per_step / 1e6
+
+    # ---------------- untimed extras: the other error bounds of the 512^3 configuration ----------------
+    extras = {}
+    if not args.no_extras:
+        for rel in (1e-2, 1e-3, 1e-4):
+            e = synth.abs_bound(x, rel)
+            st, cb = zc.zc_compress(x, n, e, d_stream, ws_c)
+            check(st, "compress extra")
+            res = {"ratio": round(4 * n / cb, 3)}
+            for name, fn in (("compress", lambda: zc.zc_compress(x, n, e, d_stream, ws_c, sync=False)),
+                             ("decompress", lambda: zc.zc_decompress(d_stream, cb, d_y, ws_d, sync=False))):
+                for _ in range(10):
+                    fn()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(10):
+                    fn()
+                b.record()
+                torch.cuda.synchronize()
+                ms = a.elapsed_time(b) / 10
+                res[name] = {"ms": round(ms, 4), "fp32_GBps": round(4 * n / ms / 1e6, 1),
+                             "hbm_frac": round((4 * n + cb) / ms / 1e6 / HBM_PEAK_GBS, 4)}
+            extras[f"rel_{rel:g}"] = res
+
+    # ---------------- reference CPU codec on a bounded sample (same mix as the step) ----------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import zcref
+        ns = min(n, 1 << 27)
+        mr = min(m, 1 << 26)
+        xs = x[:ns].cpu().numpy()
+        rs = [r[:mr].cpu().numpy() for r in ranks]
+        t = time.perf_counter()
+        st, s_ref, _ = zcref.compress(xs, eb)
+        t_c = time.perf_counter() - t
+        t = time.perf_counter()
+        _, y_ref, _ = zcref.decompress(s_ref)
+        t_d = time.perf_counter() - t
+        ss = [zcref.compress(r, eb_r)[1] for r in rs]      # untimed setup, as on the GPU
+        t = time.perf_counter()
+        st_r, red_ref, _ = zcref.reduce(ss)
+        t_r = time.perf_counter() - t
+        assert st == 0 and st_r == 0
+        # the sample is a prefix, blocks are independent: reconstruction and widths must agree bit for bit
+        assert np.array_equal(d_y[:ns].cpu().numpy().view(np.uint32), y_ref.view(np.uint32)), "GPU != reference"
+        nbs = ns // 32
+        assert np.array_equal(d_stream[32:32 + nbs].cpu().numpy(), s_ref[32:32 + nbs]), "widths differ"
+        assert np.array_equal(d_red[32:32 + mr // 32].cpu().numpy(), red_ref[32:32 + mr // 32]), "reduce widths differ"
+        sample_bytes = 4 * ns + 4 * ns + 4 * mr * K
+        cpu = {
+            "value": round(sample_bytes / (t_c + t_d + t_r) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {ns} values of the field (compress+decompress) and first {mr} values of each of the "
+                      f"{K} rank buffers (reduce); {t_c + t_d + t_r:.1f} s of CPU time",
+            "compress_GBps": round(4 * ns / t_c / 1e9, 4), "decompress_GBps": round(4 * ns / t_d / 1e9, 4),
+            "reduce_GBps": round(4 * mr * K / t_r / 1e9, 4),
+        }
+
+    out = {
+        "metric": "compress / decompress / fused-reduce GB/s (fp32 input) and % HBM peak",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64+u32", "data": "synthetic",
+        "config": {"workload": f"{side}^3 fp32 power-law Gaussian field, rel eb {args.rel:g}: compress + decompress; "
+                               f"fused reduce of {K} compressed rank buffers of {m} values",
+                   "block": 32, "abs_eb": eb, "compressed_bytes": c_bytes, "ratio": round(4 * n / c_bytes, 3),
+                   "reduce_in_bytes": sum(chunk_bytes), "reduce_out_bytes": r_bytes},
+        "roofline": dict(stages[dominant]["roofline"], kernel=dominant + "_kernel"),
+        "stages": stages,
+        "extras": extras,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
