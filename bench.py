@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--side", type=int, default=512, help="field side; 512 is the benchmark configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed sweep over the other error bounds")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run plain device copies of the field (4n B read + 4n B written each): the known "
+                         "traffic that calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     return ap.parse_args()
 
 
@@ -93,6 +96,11 @@ def main():
     assert n_out == n
     max_err = float((d_y.double() - x.double()).abs().max())
     assert max_err <= eb, (max_err, eb)
+
+    if args.copy_probe:
+        for _ in range(3):
+            d_y.copy_(x)
+        torch.cuda.synchronize()
 
     stage_names = ("compress", "decompress", "reduce")
     alg_bytes = {

@@ -30,11 +30,24 @@ int status_from_bits(u32 bits) {
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
+// Number of workgroups of a persistent kernel that fit the current device at once
+// (compute units x workgroups per unit).  Purely a launch-shape hint: correctness does not
+// depend on all of them being resident, because tiles are handed out by an atomic ticket.
+template <typename K>
+u32 resident_workgroups(K kernel) {
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 1024;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kTileThreads, 0) != hipSuccess || per_cu < 1)
+    per_cu = 4;
+  return u32(cus) * u32(per_cu);
+}
+
 // Most blocks a stream of `bytes` bytes can describe: each costs at least 5 table bytes.
 u64 blocks_bound(u64 bytes) { return bytes > kHeaderBytes ? (bytes - kHeaderBytes) / 5 : 0; }
 
 int finish(const void* d_ws, size_t* result, hipStream_t stream) {
-  struct { u32 ticket, status; u64 result; } host;
+  struct { u32 status, reserved; u64 result; } host;
   if (hipMemcpyAsync(&host, d_ws, sizeof(host), hipMemcpyDeviceToHost, stream) != hipSuccess) return ZC_ERR_HIP;
   if (hipStreamSynchronize(stream) != hipSuccess) return ZC_ERR_HIP;
   if (result) *result = size_t(host.result);

@@ -2,8 +2,8 @@
 // sign + plane packing, single-pass placement of the variable-size blocks.
 //
 // Work split.  A tile is 256 blocks (8192 values, 32 KiB of input) handled by a workgroup of
-// 4 waves; tiles are handed out by an atomic ticket so that look-back only ever waits on
-// tiles that are already running.  Each wave loads 2048 consecutive values with 16-byte
+// 4 waves; tiles are handed out by atomic tickets, so that look-back
+// only ever waits on tiles that are already running.  Each wave loads 2048 consecutive values with 16-byte
 // loads, quantises them where they land, and transposes the integer codes through LDS so
 // that one lane owns one block.  Delta, width and plane packing are then in-lane; the
 // packed words go back to LDS at the wave's running offset and leave as coalesced stores
@@ -54,9 +54,15 @@ __device__ inline i32 quantize_checked(float x, const CompressArgs& a, u32& err)
 
 // Inside |x| <= 2^17 eb the code is below 2^17 and the bound cannot fail (the guard of 1/64
 // of eb exceeds the binary32 rounding of the reconstruction there), so the checks are skipped.
-__device__ inline i32 quantize_value(float x, const CompressArgs& a, u32& err) {
-  if (__builtin_expect(!(__builtin_fabsf(x) <= a.screen), 0)) return quantize_checked(x, a, err);
+__device__ inline bool needs_checks(float x, const CompressArgs& a) { return !(__builtin_fabsf(x) <= a.screen); }
+
+__device__ inline i32 quantize_fast(float x, const CompressArgs& a) {
   return rint_small(__dmul_rn(double(x), a.inv));
+}
+
+__device__ inline i32 quantize_value(float x, const CompressArgs& a, u32& err) {
+  if (__builtin_expect(needs_checks(x, a), 0)) return quantize_checked(x, a, err);
+  return quantize_fast(x, a);
 }
 
 __global__ __launch_bounds__(kTileThreads) void compress_kernel(CompressArgs a) {
@@ -67,10 +73,11 @@ __global__ __launch_bounds__(kTileThreads) void compress_kernel(CompressArgs a) 
 
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
-  if (threadIdx.x == 0) sh_tile = atomicAdd(&a.ctl->ticket, 1u);
+  const u32 ntiles = u32(num_tiles(a.nb));
+  if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
   __syncthreads();
   const u32 tile = uniform(sh_tile);
-  const u32 ntiles = u32(num_tiles(a.nb));
+  if (tile == kNoTile) return;
 
   u32* wl = lds + wave * kWaveLds;
   const u64 wblock0 = u64(tile) * kTileBlocks + u64(wave) * kWaveBlocks;
@@ -78,25 +85,47 @@ __global__ __launch_bounds__(kTileThreads) void compress_kernel(CompressArgs a) 
   const bool full = v0 + u64(kWaveBlocks) * kBlockValues <= a.n;
   u32 err = 0;
 
-  // ---- load 16 B per lane, quantise in place, park the codes in LDS row = block ----
+  // ---- load 16 B per lane (all eight loads in flight before the first use) ----
+  float4 x[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const u64 idx = v0 + u64(256 * i + 4 * lane);
-    float4 x;
     if (full) {
-      x = *reinterpret_cast<const float4*>(a.in + idx);
+      x[i] = *reinterpret_cast<const float4*>(a.in + idx);
     } else {
-      x.x = idx + 0 < a.n ? a.in[idx + 0] : 0.0f;
-      x.y = idx + 1 < a.n ? a.in[idx + 1] : 0.0f;
-      x.z = idx + 2 < a.n ? a.in[idx + 2] : 0.0f;
-      x.w = idx + 3 < a.n ? a.in[idx + 3] : 0.0f;
+      x[i].x = idx + 0 < a.n ? a.in[idx + 0] : 0.0f;
+      x[i].y = idx + 1 < a.n ? a.in[idx + 1] : 0.0f;
+      x[i].z = idx + 2 < a.n ? a.in[idx + 2] : 0.0f;
+      x[i].w = idx + 3 < a.n ? a.in[idx + 3] : 0.0f;
     }
-    int4 q;
-    q.x = quantize_value(x.x, a, err);
-    q.y = quantize_value(x.y, a, err);
-    q.z = quantize_value(x.z, a, err);
-    q.w = quantize_value(x.w, a, err);
-    *reinterpret_cast<int4*>(wl + (8 * i + (lane >> 3)) * kRow + 4 * (lane & 7)) = q;
+  }
+
+  // ---- quantise where the values landed, park the codes in LDS row = block ----
+  bool flagged = false;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    flagged |= needs_checks(x[i].x, a) | needs_checks(x[i].y, a) | needs_checks(x[i].z, a) | needs_checks(x[i].w, a);
+  if (__builtin_expect(__any(flagged), 0)) {
+    // some value of this wave lies outside the screened domain: the checked arithmetic for all
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int4 q;
+      q.x = quantize_value(x[i].x, a, err);
+      q.y = quantize_value(x[i].y, a, err);
+      q.z = quantize_value(x[i].z, a, err);
+      q.w = quantize_value(x[i].w, a, err);
+      *reinterpret_cast<int4*>(wl + (8 * i + (lane >> 3)) * kRow + 4 * (lane & 7)) = q;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int4 q;
+      q.x = quantize_fast(x[i].x, a);
+      q.y = quantize_fast(x[i].y, a);
+      q.z = quantize_fast(x[i].z, a);
+      q.w = quantize_fast(x[i].w, a);
+      *reinterpret_cast<int4*>(wl + (8 * i + (lane >> 3)) * kRow + 4 * (lane & 7)) = q;
+    }
   }
   __syncthreads();
 
@@ -151,7 +180,7 @@ __global__ __launch_bounds__(kTileThreads) void compress_kernel(CompressArgs a) 
     if (i < wave) wave_off += t;
     tile_total += t;
   }
-  // publish this tile's size before the long packing phase so successors never wait for it
+  // publish this tile's size before the packing phase so successors never wait for it
   if (threadIdx.x == 0) desc_store(a.desc + tile, (tile == 0 ? kDescPrefix : kDescAggregate) | u64(tile_total));
 
   // ---- pack sign + planes into LDS at the wave's running offset ----
@@ -159,12 +188,11 @@ __global__ __launch_bounds__(kTileThreads) void compress_kernel(CompressArgs a) 
 
   // ---- look back for the tile's base offset ----
   if (wave == 0) {
-    u64 base = 0;
-    if (tile != 0) {
-      base = lookback_exclusive(a.desc, tile, &a.ctl->status);
-      if (lane == 0) desc_store(a.desc + tile, kDescPrefix | (base + tile_total));
+    const u64 base = tile ? lookback_exclusive(a.desc, tile, &a.ctl->status) : 0;
+    if (lane == 0) {
+      if (tile) desc_store(a.desc + tile, kDescPrefix | (base + tile_total));
+      sh_base = base;
     }
-    if (lane == 0) sh_base = base;
   }
   if (err) atomicOr(&a.ctl->status, err);
   __syncthreads();
@@ -206,7 +234,7 @@ __global__ void init_kernel(InitArgs a) {
   const u64 stride = u64(gridDim.x) * blockDim.x;
   for (u64 i = gid; i < a.ntiles; i += stride) a.desc[i] = 0;
   if (gid == 0) {
-    a.ctl->ticket = 0;
+    for (int i = 0; i < kTicketShards; ++i) a.ctl->ticket[i] = 0;
     a.ctl->status = 0;
     a.ctl->result = 0;
     if (a.out) {

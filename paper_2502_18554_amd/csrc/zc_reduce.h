@@ -137,10 +137,10 @@ __global__ __launch_bounds__(kTileThreads) void reduce_kernel(ReduceArgs a) {
 
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
-  if (threadIdx.x == 0) sh_tile = atomicAdd(&a.ctl->ticket, 1u);
+  if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
   __syncthreads();
   const u32 tile = uniform(sh_tile);
-  if (tile >= ntiles) return;
+  if (tile == kNoTile) return;
 
   u32* wl = lds + wave * kWaveLds;
   const u64 seg = u64(tile) * kTileWaves + u64(wave);
@@ -224,12 +224,11 @@ __global__ __launch_bounds__(kTileThreads) void reduce_kernel(ReduceArgs a) {
   store_sum_planes<0>(acc, w, wmax, wl + off_in_wave);
 
   if (wave == 0) {
-    u64 base = 0;
-    if (tile != 0) {
-      base = lookback_exclusive(a.desc, tile, &a.ctl->status);
-      if (lane == 0) desc_store(a.desc + tile, kDescPrefix | (base + tile_total));
+    const u64 base = tile ? lookback_exclusive(a.desc, tile, &a.ctl->status) : 0;
+    if (lane == 0) {
+      if (tile) desc_store(a.desc + tile, kDescPrefix | (base + tile_total));
+      sh_base = base;
     }
-    if (lane == 0) sh_base = base;
   }
   if (err) atomicOr(&a.ctl->status, err);
   __syncthreads();
