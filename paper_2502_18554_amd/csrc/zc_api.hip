@@ -57,6 +57,7 @@ int finish(const void* d_ws, size_t* result, hipStream_t stream) {
 void launch_init(const WorkspaceLayout& l, u32 ntiles, u8* out, u64 out_cap, u64 n, u32 eb_bits, hipStream_t stream) {
   InitArgs ia;
   ia.ctl = l.ctl;
+  ia.done = l.index.done;
   ia.desc = l.desc;
   ia.ntiles = ntiles;
   ia.out = out;
@@ -81,8 +82,7 @@ __global__ void quantize_kernel(CompressArgs a, i32* q) {
 
 struct OffsetsArgs {
   StreamRef in;
-  u64 tiles_cap;
-  const u32* seg_off;
+  StreamIndex index;
   u32* off_words;
   u64 off_cap;
   Control* ctl;
@@ -98,12 +98,13 @@ __global__ __launch_bounds__(256) void block_offsets_kernel(OffsetsArgs a) {
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) a.ctl->result = h.nb;
   const u64 seg = u64(blockIdx.x) * 4 + (threadIdx.x >> 6);
-  if (seg >= num_segments(h.nb) || seg >= 4 * a.tiles_cap) return;
+  if (seg >= num_segments(h.nb) || seg >= 4 * a.index.tiles_cap) return;
   const u64 b = seg * kWaveBlocks + u64(lane_id());
   const u32 w = b < h.nb ? u32(a.in.base[kHeaderBytes + b]) : 0u;
   const u32 words = psize_words(w);
   const u32 incl = wave_inclusive_sum(words);
-  if (b < h.nb) a.off_words[b] = a.seg_off[seg] + incl - words;
+  const u32 seg_off = u32(segment_offset(a.index, 0, seg));
+  if (b < h.nb) a.off_words[b] = seg_off + incl - words;
 }
 
 void fill_compress_args(CompressArgs& ca, const float* d_in, u64 n, float abs_eb, void* d_out, u64 out_cap,
@@ -190,17 +191,14 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
   sa.streams[0].bytes = in_bytes;
   sa.k = 1;
   sa.check_match = 0;
-  sa.tiles_cap = l.tiles_cap;
-  sa.seg_off = l.seg_off;
+  sa.index = l.index;
   sa.ctl = l.ctl;
-  hipLaunchKernelGGL(segment_sizes_kernel, dim3(u32(tiles), 1), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(segment_scan_kernel, dim3(1), dim3(1024), 0, stream, sa);
+  hipLaunchKernelGGL(stream_index_kernel, dim3(u32((tiles + 15) / 16), 1), dim3(256), 0, stream, sa);
   DecompressArgs da;
   da.in = sa.streams[0];
   da.out = d_out;
   da.out_cap_elems = out_cap_elems;
-  da.tiles_cap = l.tiles_cap;
-  da.seg_off = l.seg_off;
+  da.index = l.index;
   da.ctl = l.ctl;
   hipLaunchKernelGGL(decompress_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, da);
   if (!launch_ok()) return ZC_ERR_HIP;
@@ -235,14 +233,11 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   }
   sa.k = k;
   sa.check_match = 1;
-  sa.tiles_cap = l.tiles_cap;
-  sa.seg_off = l.seg_off;
+  sa.index = l.index;
   sa.ctl = l.ctl;
-  hipLaunchKernelGGL(segment_sizes_kernel, dim3(u32(tiles), u32(k)), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(segment_scan_kernel, dim3(u32(k)), dim3(1024), 0, stream, sa);
+  hipLaunchKernelGGL(stream_index_kernel, dim3(u32((tiles + 15) / 16), u32(k)), dim3(256), 0, stream, sa);
   ra.k = k;
-  ra.tiles_cap = l.tiles_cap;
-  ra.seg_off = l.seg_off;
+  ra.index = l.index;
   ra.out = static_cast<u8*>(d_out);
   ra.out_cap = out_cap;
   ra.ctl = l.ctl;
@@ -305,15 +300,12 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
   sa.streams[0].bytes = in_bytes;
   sa.k = 1;
   sa.check_match = 0;
-  sa.tiles_cap = l.tiles_cap;
-  sa.seg_off = l.seg_off;
+  sa.index = l.index;
   sa.ctl = l.ctl;
-  hipLaunchKernelGGL(segment_sizes_kernel, dim3(u32(tiles), 1), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(segment_scan_kernel, dim3(1), dim3(1024), 0, stream, sa);
+  hipLaunchKernelGGL(stream_index_kernel, dim3(u32((tiles + 15) / 16), 1), dim3(256), 0, stream, sa);
   OffsetsArgs oa;
   oa.in = sa.streams[0];
-  oa.tiles_cap = l.tiles_cap;
-  oa.seg_off = l.seg_off;
+  oa.index = l.index;
   oa.off_words = d_off_words;
   oa.off_cap = off_cap;
   oa.ctl = l.ctl;

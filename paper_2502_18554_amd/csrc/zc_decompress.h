@@ -1,7 +1,7 @@
 // fZ-light decompression kernel: the inverse of the stages of Section 3.3.
 //
 // Same geometry as compression: a tile is 256 blocks, one lane owns one block.  A wave's
-// payload offset comes from the segment-offset table (zc_scan.h); inside the wave a scan of
+// payload offset comes from the stream index (zc_scan.h); inside the wave a scan of
 // the block sizes places each lane.  The lane reads its sign and plane words, rebuilds the
 // deltas, runs the Lorenzo chain from the block's outlier, dequantises, and the floats are
 // transposed through LDS so that they leave as 16-byte coalesced stores.
@@ -17,8 +17,7 @@ struct DecompressArgs {
   StreamRef in;
   float* out;
   u64 out_cap_elems;
-  u64 tiles_cap;
-  const u32* seg_off;
+  StreamIndex index;
   Control* ctl;
 };
 
@@ -34,7 +33,7 @@ __global__ __launch_bounds__(kTileThreads) void decompress_kernel(DecompressArgs
     return;
   }
   const u32 tile = blockIdx.x;
-  if (u64(tile) >= num_tiles(h.nb) || u64(tile) >= a.tiles_cap) return;
+  if (u64(tile) >= num_tiles(h.nb) || u64(tile) >= a.index.tiles_cap) return;
 
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
@@ -53,7 +52,7 @@ __global__ __launch_bounds__(kTileThreads) void decompress_kernel(DecompressArgs
   const u32 incl = wave_inclusive_sum(words);
   const u64 seg = u64(tile) * kTileWaves + u64(wave);
   u64 off = 0;
-  if (seg < num_segments(h.nb)) off = u64(a.seg_off[seg]) + (incl - words);
+  if (seg < num_segments(h.nb)) off = segment_offset(a.index, 0, seg) + (incl - words);
   if (off + words > payload_words) w = 0;        // cannot happen once the scan has validated the stream
   const u32 wmax = wave_max_u32(w);
 

@@ -22,8 +22,7 @@ constexpr int kAccPlanes = 39;   // |sum of 64 deltas| < 2^37: 38 magnitude bits
 struct ReduceArgs {
   StreamRef in[ZC_MAX_K];
   int k;
-  u64 tiles_cap;
-  const u32* seg_off;   // [k][4 * tiles_cap]
+  StreamIndex index;
   u8* out;
   u64 out_cap;
   Control* ctl;
@@ -163,7 +162,7 @@ __global__ __launch_bounds__(kTileThreads) void reduce_kernel(ReduceArgs a) {
     const u32 words = psize_words(w);
     const u32 incl = wave_inclusive_sum(words);
     u64 off = 0;
-    if (seg_live) off = u64(a.seg_off[u64(s) * 4 * a.tiles_cap + seg]) + (incl - words);
+    if (seg_live) off = segment_offset(a.index, s, seg) + (incl - words);
     if (off + words > pw) w = 0;                  // cannot happen on a validated stream
     const u32 wmax = wave_max_u32(w);
     if (active) outlier += i64(reinterpret_cast<const i32*>(base + kHeaderBytes + pad16(h.nb))[b]);

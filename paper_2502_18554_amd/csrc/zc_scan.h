@@ -3,12 +3,8 @@
 // a block's position is the sum of the sizes before it), kept per segment of 64 blocks, the
 // share of one wave.
 //
-// segment_sizes_kernel : one wave per segment sums the payload words of its 64 blocks and
-//                        checks every width byte; the first thread of each stream's first
-//                        workgroup validates the header (and, for a reduce, that the stream
-//                        matches stream 0).
-// segment_scan_kernel  : one workgroup per stream turns the segment sums into exclusive
-//                        offsets and checks that header total_bytes = tables + payload.
+// stream_index_kernel records the payload size of every segment and the exclusive offset of
+// every scan group of 64 segments, and validates header and width bytes on the way.
 #pragma once
 
 #include "zc_common.h"
@@ -55,12 +51,28 @@ struct ScanArgs {
   StreamRef streams[ZC_MAX_K];
   int k;
   int check_match;   // reduce: every stream must have the n and eb_bits of stream 0
-  u64 tiles_cap;     // tiles the workspace has room for; row stride of seg_off is 4 * tiles_cap
-  u32* seg_off;      // [k][4 * tiles_cap]
+  StreamIndex index;
   Control* ctl;
 };
 
-__global__ __launch_bounds__(256) void segment_sizes_kernel(ScanArgs a) {
+// Payload word offset of segment `seg` of stream `s`: the offset of its scan group plus the
+// sizes of the segments before it inside the group.  Called by all 64 lanes of a wave.
+__device__ inline u64 segment_offset(const StreamIndex& ix, int s, u64 seg) {
+  const u64 g = seg / kScanGroupSegs;
+  const u32 r = u32(seg % kScanGroupSegs);
+  const u32* sums = ix.seg_sum + u64(s) * 4 * ix.tiles_cap + g * kScanGroupSegs;
+  const u32 mine = u32(lane_id()) < r ? sums[lane_id()] : 0u;
+  return u64(ix.grp_off[u64(s) * ix.groups_cap + g]) + wave_sum_u32(mine);
+}
+
+// One workgroup per scan group of 4096 blocks (64 segments) and stream.  Each thread sums
+// the payload sizes of 16 blocks (one 16-byte load of the width table) and checks the width
+// bytes; four threads make a segment.  The workgroup that finishes last for a stream turns
+// the group sums into exclusive offsets and checks header total_bytes = tables + payload.
+__global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
+  __shared__ u32 sh_wave[4];
+  __shared__ u32 sh_last;
+  __shared__ u64 sh_carry;
   const int s = blockIdx.y;
   const StreamRef st = a.streams[s];
   const ParsedHeader h = parse_header(st);
@@ -68,69 +80,78 @@ __global__ __launch_bounds__(256) void segment_sizes_kernel(ScanArgs a) {
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
     return;
   }
+  const u64 ngroups = num_scan_groups(h.nb);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
-    if (num_tiles(h.nb) > a.tiles_cap) atomicOr(&a.ctl->status, status_bit(ZC_ERR_ARG));
+    if (num_tiles(h.nb) > a.index.tiles_cap || ngroups > a.index.groups_cap)
+      atomicOr(&a.ctl->status, status_bit(ZC_ERR_ARG));
     if (a.check_match && s > 0) {
       const ParsedHeader h0 = parse_header(a.streams[0]);
       if (h0.ok && (h0.n != h.n || h0.eb_bits != h.eb_bits)) atomicOr(&a.ctl->status, status_bit(ZC_ERR_MISMATCH));
     }
   }
-  const u64 nseg = num_segments(h.nb);
-  const u64 seg = u64(blockIdx.x) * 4 + (threadIdx.x >> 6);
-  if (seg >= nseg || seg >= 4 * a.tiles_cap) return;
-  const int lane = lane_id();
-  const u64 b = seg * kWaveBlocks + u64(lane);
-  u32 w = b < h.nb ? u32(st.base[kHeaderBytes + b]) : 0u;
-  if (w > 31) {
-    atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
-    w = 0;
-  }
-  const u32 sum = wave_sum_u32(psize_words(w));
-  if (lane == 0) a.seg_off[u64(s) * 4 * a.tiles_cap + seg] = sum;
-}
+  if (num_tiles(h.nb) > a.index.tiles_cap || ngroups > a.index.groups_cap) return;
+  const u64 group = blockIdx.x;
+  if (group >= ngroups) return;
 
-constexpr int kScanPerThread = 16;
-
-__global__ __launch_bounds__(1024) void segment_scan_kernel(ScanArgs a) {
-  __shared__ u32 sh_wave[16];
-  __shared__ u64 sh_carry;
-  const int s = blockIdx.x;
-  const StreamRef st = a.streams[s];
-  const ParsedHeader h = parse_header(st);
-  if (!h.ok) return;                      // already flagged by segment_sizes_kernel
-  u64 nseg = num_segments(h.nb);
-  if (nseg > 4 * a.tiles_cap) return;     // already flagged: workspace too small
-  u32* row = a.seg_off + u64(s) * 4 * a.tiles_cap;
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
+  const u8* widths = st.base + kHeaderBytes;
+  const u64 b0 = group * kScanGroupBlocks + u64(threadIdx.x) * 16;
+  u32 bytes[4] = {0, 0, 0, 0};
+  if (b0 + 16 <= h.nb) {
+    const uint4 v = *reinterpret_cast<const uint4*>(widths + b0);
+    bytes[0] = v.x; bytes[1] = v.y; bytes[2] = v.z; bytes[3] = v.w;
+  } else {
+    for (int i = 0; i < 16; ++i)
+      if (b0 + i < h.nb) bytes[i >> 2] |= u32(widths[b0 + i]) << (8 * (i & 3));
+  }
+  u32 sum = 0;
+  bool bad = false;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const u32 w = (bytes[i >> 2] >> (8 * (i & 3))) & 0xffu;
+    bad |= w > 31;
+    sum += psize_words(w > 31 ? 0 : w);
+  }
+  if (bad) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
+  // four threads = one segment of 64 blocks
+  u32 seg_total = sum + u32(__shfl_xor(int(sum), 1));
+  seg_total += u32(__shfl_xor(int(seg_total), 2));
+  const u64 seg = group * kScanGroupSegs + (threadIdx.x >> 2);
+  if ((threadIdx.x & 3) == 0 && seg < num_segments(h.nb))
+    a.index.seg_sum[u64(s) * 4 * a.index.tiles_cap + seg] = seg_total;
+  const u32 wave_total = wave_sum_u32(sum);
+  if (lane == 0) sh_wave[wave] = wave_total;
+  __syncthreads();
+  u32* grp = a.index.grp_off + u64(s) * a.index.groups_cap;
+  if (threadIdx.x == 0) {
+    desc32_store(grp + group, sh_wave[0] + sh_wave[1] + sh_wave[2] + sh_wave[3]);
+    __threadfence();
+    const u32 finished = atomicAdd(&a.index.done[s], 1u);
+    sh_last = (finished + 1 == u32(ngroups));
+  }
+  __syncthreads();
+  if (!sh_last) return;
+
+  // ---- last workgroup of this stream: exclusive scan of the group sums, in place ----
+  __threadfence();
   if (threadIdx.x == 0) sh_carry = 0;
   __syncthreads();
-  for (u64 start = 0; start < nseg; start += 1024 * kScanPerThread) {
-    const u64 i0 = start + u64(threadIdx.x) * kScanPerThread;
-    u32 v[kScanPerThread];
-    u32 mine = 0;
-#pragma unroll
-    for (int j = 0; j < kScanPerThread; ++j) {
-      v[j] = i0 + j < nseg ? row[i0 + j] : 0u;
-      mine += v[j];
-    }
-    const u32 incl = wave_inclusive_sum(mine);
+  for (u64 start = 0; start < ngroups; start += 256) {
+    const u64 i = start + threadIdx.x;
+    const u32 v = i < ngroups ? desc32_load(grp + i) : 0u;
+    const u32 incl = wave_inclusive_sum(v);
     if (lane == 63) sh_wave[wave] = incl;
     __syncthreads();
     u32 before = 0, all = 0;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
+    for (int j = 0; j < 4; ++j) {
       const u32 t = sh_wave[j];
       if (j < wave) before += t;
       all += t;
     }
     const u64 carry = sh_carry;
-    u32 run = u32(carry) + before + incl - mine;
-#pragma unroll
-    for (int j = 0; j < kScanPerThread; ++j) {
-      if (i0 + j < nseg) row[i0 + j] = run;
-      run += v[j];
-    }
+    if (i < ngroups) grp[i] = u32(carry) + before + incl - v;
     __syncthreads();
     if (threadIdx.x == 0) sh_carry = carry + all;
     __syncthreads();
