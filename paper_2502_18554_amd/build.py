@@ -8,7 +8,7 @@ LIB = os.path.join(HERE, "libzc.so")
 SOURCES = ["zc_api.hip"]
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared",
     "-ffp-contract=off",                                     # quantisation is defined by separate roundings
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",

@@ -2,16 +2,19 @@
 // sign + plane packing, single-pass placement of the variable-size blocks.
 //
 // Work split.  A tile is 256 blocks (8192 values, 32 KiB of input) handled by a workgroup of
-// 4 waves; tiles are handed out by atomic tickets, so that look-back
-// only ever waits on tiles that are already running.  Each wave loads 2048 consecutive values with 16-byte
-// loads, quantises them where they land, and transposes the integer codes through LDS so
-// that one lane owns one block.  Delta, width and plane packing are then in-lane; the
-// packed words go back to LDS at the wave's running offset and leave as coalesced stores
-// once the tile's base offset is known from the look-back scan.
+// 4 waves; tiles are handed out by atomic tickets, so that look-back only ever waits on tiles
+// that are already running.  Each wave loads 2048 consecutive values with 16-byte loads,
+// quantises them where they land, and transposes the integer codes through LDS so that one
+// lane owns one block.  Delta, width and the bit-matrix transpose that yields the plane
+// words are then in-lane; the packed words wait in registers for the tile's base offset
+// from the look-back scan and leave through LDS as coalesced stores.
 #pragma once
 
+#include <type_traits>
+#include <utility>
+
+#include "zc_bitmatrix.h"
 #include "zc_common.h"
-#include "zc_planes.h"
 
 namespace zc {
 
@@ -65,25 +68,61 @@ __device__ inline i32 quantize_value(float x, const CompressArgs& a, u32& err) {
   return quantize_fast(x, a);
 }
 
-__global__ __launch_bounds__(kTileThreads) void compress_kernel(CompressArgs a) {
-  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveLds];
-  __shared__ u32 sh_tile;
-  __shared__ u32 sh_wave_total[kTileWaves];
-  __shared__ u64 sh_base;
+// LDS of one wave: 32 rows (blocks) of 32 codes + 4 words of padding, which keeps the 128-bit
+// row reads of 16 consecutive lanes on distinct banks.  A wave's 64 blocks pass through it in
+// two halves (blocks of lanes 0..31, then 32..63), codes on the way in and packed payload
+// on the way out, so that five or more workgroups fit a compute unit.
+constexpr int kStageRow = 36;
+constexpr int kWaveStage = 32 * kStageRow;              // 1152 words = 4.5 KiB per wave
+static_assert(kWaveStage >= 32 * 33, "one half-wave of worst-case blocks must fit the staging area");
 
-  const int lane = lane_id();
-  const int wave = int(threadIdx.x) >> 6;
-  const u32 ntiles = u32(num_tiles(a.nb));
-  if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
-  __syncthreads();
-  const u32 tile = uniform(sh_tile);
-  if (tile == kNoTile) return;
+__device__ inline void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
-  u32* wl = lds + wave * kWaveLds;
-  const u64 wblock0 = u64(tile) * kTileBlocks + u64(wave) * kWaveBlocks;
+__device__ inline int4 quantize4(const float4& x, const CompressArgs& a, bool checked, u32& err) {
+  int4 q;
+  if (__builtin_expect(checked, 0)) {
+    q.x = quantize_value(x.x, a, err);
+    q.y = quantize_value(x.y, a, err);
+    q.z = quantize_value(x.z, a, err);
+    q.w = quantize_value(x.w, a, err);
+  } else {
+    q.x = quantize_fast(x.x, a);
+    q.y = quantize_fast(x.y, a);
+    q.z = quantize_fast(x.z, a);
+    q.w = quantize_fast(x.w, a);
+  }
+  return q;
+}
+
+// Writes the payload words of the lanes of one half-wave to the wave's staging area and copies
+// them out with coalesced stores.  Word 0 is the sign word, word 1 + p is plane p; `word(i)`
+// yields word i from registers and is only ever called with compile-time constants.
+template <int NW, typename WordFn>
+__device__ inline void stage_and_copy_half(WordFn word, u32 w, u32 wmax, bool in_half, u32 off_in_half,
+                                           u32 half_total, u32* wl, u32* dst, u64 dst_room, int lane) {
+  if (in_half && w) {
+    wl[off_in_half] = word(std::integral_constant<int, 0>{});
+    [&]<int... P>(std::integer_sequence<int, P...>) {
+      ((u32(P) < w ? void(wl[off_in_half + 1 + P] = word(std::integral_constant<int, 1 + P>{})) : void()), ...);
+    }(std::make_integer_sequence<int, NW - 1>{});
+  }
+  (void)wmax;
+  wave_lds_sync();
+  for (u32 i = u32(lane); i < half_total; i += 64)
+    if (i < dst_room) dst[i] = wl[i];
+  wave_lds_sync();
+}
+
+// Front half of the work of one wave on its 64 blocks: load, quantise, transpose through LDS,
+// Lorenzo delta.  Leaves in d[j] delta j of the lane's block (d[0] = 0) and returns the
+// block's first code (the outlier).  `err` collects status bits of the checked path.
+__device__ inline i32 block_deltas(const CompressArgs& a, u64 wblock0, int lane, u32* wl, i32 (&d)[32], u32& err) {
   const u64 v0 = wblock0 * kBlockValues;
   const bool full = v0 + u64(kWaveBlocks) * kBlockValues <= a.n;
-  u32 err = 0;
 
   // ---- load 16 B per lane (all eight loads in flight before the first use) ----
   float4 x[8];
@@ -100,91 +139,157 @@ __global__ __launch_bounds__(kTileThreads) void compress_kernel(CompressArgs a) 
     }
   }
 
-  // ---- quantise where the values landed, park the codes in LDS row = block ----
+  // Some value of this wave outside the screened domain: the checked arithmetic for all of it.
   bool flagged = false;
 #pragma unroll
   for (int i = 0; i < 8; ++i)
     flagged |= needs_checks(x[i].x, a) | needs_checks(x[i].y, a) | needs_checks(x[i].z, a) | needs_checks(x[i].w, a);
-  if (__builtin_expect(__any(flagged), 0)) {
-    // some value of this wave lies outside the screened domain: the checked arithmetic for all
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int4 q;
-      q.x = quantize_value(x[i].x, a, err);
-      q.y = quantize_value(x[i].y, a, err);
-      q.z = quantize_value(x[i].z, a, err);
-      q.w = quantize_value(x[i].w, a, err);
-      *reinterpret_cast<int4*>(wl + (8 * i + (lane >> 3)) * kRow + 4 * (lane & 7)) = q;
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int4 q;
-      q.x = quantize_fast(x[i].x, a);
-      q.y = quantize_fast(x[i].y, a);
-      q.z = quantize_fast(x[i].z, a);
-      q.w = quantize_fast(x[i].w, a);
-      *reinterpret_cast<int4*>(wl + (8 * i + (lane >> 3)) * kRow + 4 * (lane & 7)) = q;
-    }
-  }
-  __syncthreads();
+  const bool checked = __any(flagged);
 
-  // ---- one lane = one block: fetch its 32 codes ----
+  // ---- quantise where the values landed; through LDS to one lane = one block ----
+  // Loads 0..3 hold blocks 0..31 (lanes 0..31), loads 4..7 blocks 32..63.
   i32 q[32];
 #pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    int4 r = *reinterpret_cast<const int4*>(wl + lane * kRow + 4 * t);
-    q[4 * t + 0] = r.x; q[4 * t + 1] = r.y; q[4 * t + 2] = r.z; q[4 * t + 3] = r.w;
+  for (int half = 0; half < 2; ++half) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *reinterpret_cast<int4*>(wl + (8 * i + (lane >> 3)) * kStageRow + 4 * (lane & 7)) =
+          quantize4(x[4 * half + i], a, checked, err);
+      __builtin_amdgcn_sched_barrier(0);   // one group of four values at a time keeps the 64-bit temporaries few
+    }
+    wave_lds_sync();
+    if ((lane >> 5) == half) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int4 r = *reinterpret_cast<const int4*>(wl + (lane & 31) * kStageRow + 4 * t);
+        q[4 * t + 0] = r.x; q[4 * t + 1] = r.y; q[4 * t + 2] = r.z; q[4 * t + 3] = r.w;
+      }
+    }
+    wave_lds_sync();
   }
-  const u64 b = wblock0 + u64(lane);
-  const bool active = b < a.nb;
   if (!full) {
     // the last block repeats its last code up to 32 values
-    u64 cnt = active ? a.n - b * kBlockValues : 0;
+    const u64 b = wblock0 + u64(lane);
+    const u64 cnt = b < a.nb ? a.n - b * kBlockValues : 0;
 #pragma unroll
     for (int j = 1; j < 32; ++j) q[j] = u64(j) < cnt ? q[j] : q[j - 1];
   }
 
-  // ---- Lorenzo delta, sign-magnitude, rotate by j, width ----
-  u32 c[32];
-  u32 any = 0;
-  c[0] = 0;
+  // ---- Lorenzo delta ----
+  d[0] = 0;
 #pragma unroll
-  for (int j = 1; j < 32; ++j) {
-    i32 d = q[j] - q[j - 1];
-    u32 neg = u32(d) & 0x80000000u;
-    u32 mag = u32(d < 0 ? -d : d);
-    any |= mag;
-    c[j] = rotl32(mag | neg, j);
+  for (int j = 1; j < 32; ++j) d[j] = q[j] - q[j - 1];
+  return q[0];
+}
+
+// Payload of a wave that holds a block wider than 15 bits (inputs outside the guaranteed
+// domain).  Such waves are rare, so rather than keep 32 more registers alive across the
+// look-back for them, the front half is redone here; and the function is kept out of line so
+// that its register needs do not shape the allocation of the common path.
+__device__ __attribute__((noinline)) void wide_payload(const CompressArgs& a, u64 wblock0, int lane, u32* wl, u32 w,
+                                                       u32 wmax, u32 off_in_wave, u32 half0_total, u32 wave_total,
+                                                       u32* payload, u64 dst0, u64 cap_words) {
+  u32 lo[16], hi[16];
+  {
+    i32 d[32];
+    u32 ignored = 0;
+    block_deltas(a, wblock0, lane, wl, d, ignored);
+    planes_from_deltas32(d, lo, hi);
   }
-  const u32 w = (active && any) ? 32u - u32(__builtin_clz(any)) : 0u;
+  auto word = [&](auto i) {
+    constexpr int I = decltype(i)::value;      // 0: sign, 1..16: low planes, 17..31: high planes
+    if constexpr (I == 0) return hi[15];
+    else if constexpr (I <= 16) return lo[I - 1];
+    else return hi[I - 17];
+  };
+  const u32 half_base[2] = {0u, half0_total};
+  const u32 half_total[2] = {half0_total, wave_total - half0_total};
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const u64 d0 = dst0 + half_base[h];
+    stage_and_copy_half<32>(word, w, wmax, (lane >> 5) == h, off_in_wave - half_base[h], half_total[h], wl,
+                            payload + d0, cap_words > d0 ? cap_words - d0 : 0, lane);
+  }
+}
+
+__global__ __launch_bounds__(kTileThreads, 6) void compress_kernel(CompressArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
+  __shared__ u32 sh_tile;
+  __shared__ u32 sh_wave_total[kTileWaves];
+  __shared__ u64 sh_base;
+
+  const int lane = lane_id();
+  const int wave = int(threadIdx.x) >> 6;
+  const u32 ntiles = u32(num_tiles(a.nb));
+  if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
+  __syncthreads();
+  const u32 tile = uniform(sh_tile);
+  if (tile == kNoTile) return;
+
+  u32* const wl = lds + wave * kWaveStage;
+  const u64 wblock0 = u64(tile) * kTileBlocks + u64(wave) * kWaveBlocks;
+  const u64 b = wblock0 + u64(lane);
+  const bool active = b < a.nb;
+  u32 err = 0;
+
+  u32 pw[16];          // pw[0] = sign, pw[1 + p] = plane p   (widths up to 15)
+  u32 w, wmax;
+  {
+    i32 d[32];
+    const i32 outlier = block_deltas(a, wblock0, lane, wl, d, err);
+    u32 any = 0;
+#pragma unroll
+    for (int j = 1; j < 32; ++j) any |= u32(d[j] < 0 ? -d[j] : d[j]);
+    w = (active && any) ? 32u - u32(__builtin_clz(any)) : 0u;
+    wmax = wave_max_u32(w);
+    if (active && a.out_cap >= tables_end(a.nb)) {
+      a.out[kHeaderBytes + b] = u8(w);
+      reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(a.nb))[b] = outlier;
+    }
+    // ---- values -> sign + plane words, in registers (wide blocks are packed after the look-back) ----
+    // (the empty asm keeps the compiler from hoisting the sign-magnitude split of all 32
+    //  deltas above the branch, where it would hold twice as many registers)
+    if (wmax <= 7) {
+      u32 r[8];
+#pragma unroll
+      for (int j = 0; j < 32; ++j) asm volatile("" : "+v"(d[j]));
+      planes_from_deltas8(d, r);
+      pw[0] = r[7];
+#pragma unroll
+      for (int p = 0; p < 7; ++p) pw[1 + p] = r[p];
+#pragma unroll
+      for (int p = 8; p < 16; ++p) pw[p] = 0;
+    } else if (wmax <= 15) {
+      u32 r[16];
+#pragma unroll
+      for (int j = 0; j < 32; ++j) asm volatile("" : "+v"(d[j]));
+      planes_from_deltas16(d, r);
+      pw[0] = r[15];
+#pragma unroll
+      for (int p = 0; p < 15; ++p) pw[1 + p] = r[p];
+    } else {
+#pragma unroll
+      for (int p = 0; p < 16; ++p) pw[p] = 0;
+    }
+  }
   const u32 words = psize_words(w);
 
   // ---- place the block inside the wave and the wave inside the tile ----
   const u32 incl = wave_inclusive_sum(words);
   const u32 wave_total = uniform(u32(__shfl(int(incl), 63)));
+  const u32 half0_total = uniform(u32(__shfl(int(incl), 31)));
   const u32 off_in_wave = incl - words;
-  const u32 wmax = wave_max_u32(w);
   if (lane == 0) sh_wave_total[wave] = wave_total;
-
-  if (active && a.out_cap >= tables_end(a.nb)) {
-    a.out[kHeaderBytes + b] = u8(w);
-    reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(a.nb))[b] = q[0];
-  }
-  __syncthreads();   // all q reads of this wave's LDS rows are done; wave totals visible
+  __syncthreads();   // wave totals visible
 
   u32 wave_off = 0, tile_total = 0;
 #pragma unroll
   for (int i = 0; i < kTileWaves; ++i) {
-    u32 t = sh_wave_total[i];
+    const u32 t = sh_wave_total[i];
     if (i < wave) wave_off += t;
     tile_total += t;
   }
-  // publish this tile's size before the packing phase so successors never wait for it
   if (threadIdx.x == 0) desc_store(a.desc + tile, (tile == 0 ? kDescPrefix : kDescAggregate) | u64(tile_total));
-
-  // ---- pack sign + planes into LDS at the wave's running offset ----
-  store_block_planes(c, w, wmax, wl + off_in_wave);
 
   // ---- look back for the tile's base offset ----
   if (wave == 0) {
@@ -197,22 +302,30 @@ __global__ __launch_bounds__(kTileThreads) void compress_kernel(CompressArgs a) 
   if (err) atomicOr(&a.ctl->status, err);
   __syncthreads();
 
-  // ---- copy the wave's packed words out, coalesced ----
+  // ---- payload out: each half-wave through the staging area, coalesced stores ----
   const u64 base = sh_base;
   const u64 tend = tables_end(a.nb);
   const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
-  u32* payload = reinterpret_cast<u32*>(a.out + tend);
+  u32* const payload = reinterpret_cast<u32*>(a.out + tend);
   const u64 dst0 = base + wave_off;
-  for (u32 i = u32(lane); i < wave_total; i += 64) {
-    if (dst0 + i < cap_words) payload[dst0 + i] = wl[i];
+  const u32 half_base[2] = {0u, half0_total};
+  const u32 half_total[2] = {half0_total, wave_total - half0_total};
+  if (wmax <= 15) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const u64 d0 = dst0 + half_base[h];
+      stage_and_copy_half<16>([&](auto i) { return pw[decltype(i)::value]; }, w, wmax, (lane >> 5) == h,
+                              off_in_wave - half_base[h], half_total[h], wl, payload + d0,
+                              cap_words > d0 ? cap_words - d0 : 0, lane);
+    }
+  } else {
+    wide_payload(a, wblock0, lane, wl, w, wmax, off_in_wave, half0_total, wave_total, payload, dst0, cap_words);
   }
 
   if (tile == ntiles - 1 && threadIdx.x == 0) {
     const u64 total = tend + 4 * (base + tile_total);
     a.ctl->result = total;
-    if (total > a.out_cap) {
-      atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
-    }
+    if (total > a.out_cap) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
     if (a.out_cap >= kHeaderBytes) reinterpret_cast<u64*>(a.out)[3] = total;
   }
 }
