@@ -30,19 +30,6 @@ int status_from_bits(u32 bits) {
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
-// Number of workgroups of a persistent kernel that fit the current device at once
-// (compute units x workgroups per unit).  Purely a launch-shape hint: correctness does not
-// depend on all of them being resident, because tiles are handed out by an atomic ticket.
-template <typename K>
-u32 resident_workgroups(K kernel) {
-  int dev = 0, cus = 0, per_cu = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 1024;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kTileThreads, 0) != hipSuccess || per_cu < 1)
-    per_cu = 4;
-  return u32(cus) * u32(per_cu);
-}
-
 // Most blocks a stream of `bytes` bytes can describe: each costs at least 5 table bytes.
 u64 blocks_bound(u64 bytes) { return bytes > kHeaderBytes ? (bytes - kHeaderBytes) / 5 : 0; }
 
@@ -166,7 +153,11 @@ int zc_compress(const float* d_in, size_t n, float abs_eb, void* d_out, size_t o
   CompressArgs ca;
   fill_compress_args(ca, d_in, n, abs_eb, d_out, out_cap, l);
   launch_init(l, u32(ntiles), ca.out, out_cap, n, ca.eb_bits, stream);
-  if (ntiles) hipLaunchKernelGGL(compress_kernel, dim3(u32(ntiles)), dim3(kTileThreads), 0, stream, ca);
+  const u32 full_tiles = u32(n / kTileValues);      // tiles whose 8192 values all exist
+  if (full_tiles)
+    hipLaunchKernelGGL(compress_kernel<true>, dim3(full_tiles), dim3(kTileThreads), 0, stream, ca, 0u, full_tiles);
+  if (ntiles > full_tiles)                          // the ragged last tile
+    hipLaunchKernelGGL(compress_kernel<false>, dim3(1), dim3(kTileThreads), 0, stream, ca, full_tiles, u32(ntiles));
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);

@@ -148,6 +148,44 @@ __device__ inline u32 take_tile(Control* ctl, u32 ntiles, u32 first_shard) {
   return kNoTile;
 }
 
+// Lane-crossing primitives are built from DPP moves and v_readlane, which need no address
+// registers and do not go through the LDS pipe (unlike ds_bpermute shuffles).
+template <int CTRL>
+__device__ inline u32 dpp_mov(u32 v) {
+  return u32(__builtin_amdgcn_update_dpp(int(v), int(v), CTRL, 0xf, 0xf, false));
+}
+constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+
+__device__ inline u32 lane_value(u32 v, int lane) { return u32(__builtin_amdgcn_readlane(int(v), lane)); }
+
+// A value known to be the same in every lane, moved to a scalar register so that branches on
+// it are scalar branches.
+__device__ inline u32 uniform(u32 v) { return u32(__builtin_amdgcn_readfirstlane(int(v))); }
+
+// Sum over the 64 lanes (result uniform).
+__device__ inline u32 wave_sum_u32(u32 v) {
+  v += dpp_mov<kDppQuadSwap1>(v);
+  v += dpp_mov<kDppQuadSwap2>(v);
+  v += dpp_mov<kDppRowHalfMirror>(v);
+  v += dpp_mov<kDppRowMirror>(v);          // every lane of a row of 16 now holds the row's sum
+  return lane_value(v, 0) + lane_value(v, 16) + lane_value(v, 32) + lane_value(v, 48);
+}
+
+// Maximum over the 64 lanes (result uniform).
+__device__ inline u32 wave_max_u32(u32 v) {
+  u32 o;
+  o = dpp_mov<kDppQuadSwap1>(v); v = o > v ? o : v;
+  o = dpp_mov<kDppQuadSwap2>(v); v = o > v ? o : v;
+  o = dpp_mov<kDppRowHalfMirror>(v); v = o > v ? o : v;
+  o = dpp_mov<kDppRowMirror>(v); v = o > v ? o : v;
+  const u32 a = lane_value(v, 0), b = lane_value(v, 16), c = lane_value(v, 32), d = lane_value(v, 48);
+  const u32 ab = a > b ? a : b, cd = c > d ? c : d;
+  return ab > cd ? ab : cd;
+}
+
 // Row shift right by S lanes inside each row of 16 lanes; lanes without a source get 0.
 template <int S>
 __device__ inline u32 dpp_row_shr_or_zero(u32 v) {
@@ -161,44 +199,16 @@ __device__ inline u32 wave_inclusive_sum(u32 v) {
   v += dpp_row_shr_or_zero<4>(v);
   v += dpp_row_shr_or_zero<8>(v);
   // v is now the scan inside each row of 16; add the totals of the earlier rows
-  u32 t0 = u32(__shfl(int(v), 15)), t1 = u32(__shfl(int(v), 31)), t2 = u32(__shfl(int(v), 47));
+  const u32 t0 = lane_value(v, 15), t1 = lane_value(v, 31), t2 = lane_value(v, 47);
   int row = lane_id() >> 4;
   u32 carry = (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
   return v + carry;
-}
-
-__device__ inline u32 wave_sum_u32(u32 v) {
-  for (int s = 32; s >= 1; s >>= 1) v += u32(__shfl_xor(int(v), s));
-  return v;
-}
-
-// A value known to be the same in every lane, moved to a scalar register so that branches on
-// it are scalar branches.
-__device__ inline u32 uniform(u32 v) { return u32(__builtin_amdgcn_readfirstlane(int(v))); }
-
-__device__ inline u32 wave_max_u32(u32 v) {
-  for (int s = 32; s >= 1; s >>= 1) {
-    u32 o = u32(__shfl_xor(int(v), s));
-    v = o > v ? o : v;
-  }
-  return uniform(v);
-}
-
-__device__ inline u64 wave_sum_u64(u64 v) {
-  for (int s = 32; s >= 1; s >>= 1) {
-    u32 lo = u32(__shfl_xor(int(u32(v)), s));
-    u32 hi = u32(__shfl_xor(int(u32(v >> 32)), s));
-    v += (u64(hi) << 32) | lo;
-  }
-  return v;
 }
 
 // ---------------------------------------------------------------------------------------
 // Decoupled look-back over tile descriptors.  A descriptor is one 64-bit word:
 // bits 63..62 = state (0 empty, 1 tile aggregate, 2 inclusive prefix), bits 61..0 = value.
 // Only the descriptor word itself is communicated, so relaxed device-scope atomics suffice.
-// Measured on the 512^3 field: a tile waits about 2.5 us here, most of it the two memory
-// round trips (a predecessor's store becoming visible, then this tile's load).
 // ---------------------------------------------------------------------------------------
 constexpr u64 kDescAggregate = u64(1) << 62;
 constexpr u64 kDescPrefix = u64(2) << 62;
@@ -220,33 +230,61 @@ __device__ inline u32 desc32_load(const u32* d) {
 }
 
 // Called by all 64 lanes of one wave.  Returns the sum of the values of tiles [0, tile).
-// Every tile below `tile` was claimed earlier by a running workgroup that publishes its
-// aggregate without waiting for anything, so the wait below ends; it is bounded anyway and
-// raises ZC_ERR_HIP in *status if the bound is hit.
+// Every tile below `tile` is in work on a resident workgroup (or done), and a workgroup
+// publishes its aggregate without waiting for anything, so the wait below ends; it is
+// bounded anyway and raises ZC_ERR_HIP in *status if the bound is hit.
+// One poll inspects kLookWindows x 64 descriptors (all loads in flight together).  The
+// prefix frontier advances by at most one poll's reach per memory round trip, and at this
+// kernel's rate (about 100 tiles per microsecond) a reach of 64 tiles cannot keep up.
+constexpr int kLookWindows = 1;
+
 __device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status) {
   const int lane = lane_id();
   u64 excl = 0;
-  i64 look = i64(tile) - 1;                  // lane 0 inspects the nearest predecessor
+  i64 look = i64(tile) - 1;                  // lane 0 of window 0 inspects the nearest predecessor
   u32 spins = 0;
   while (true) {
-    const i64 idx = look - lane;
-    const u64 d = idx >= 0 ? desc_load(desc + idx) : kDescPrefix;   // "tile -1" has prefix 0
-    const u32 state = u32(d >> 62);
-    const u64 has_prefix = __ballot(state == 2);
-    const u64 is_empty = __ballot(state == 0);
-    const int first = has_prefix ? __builtin_ctzll(has_prefix) : 63;
-    const u64 needed = first == 63 ? ~u64(0) : ((u64(2) << first) - 1);   // lanes 0..first
-    if (is_empty & needed) {
+    u64 d[kLookWindows];
+#pragma unroll
+    for (int e = 0; e < kLookWindows; ++e) {
+      const i64 idx = look - lane - 64 * e;
+      d[e] = idx >= 0 ? desc_load(desc + idx) : kDescPrefix;        // "tile -1" has prefix 0
+    }
+    bool retry = false, done = false;
+    u64 got = 0;
+    int used = 0;
+#pragma unroll
+    for (int e = 0; e < kLookWindows; ++e) {
+      if (!retry && !done) {
+        const u32 state = u32(d[e] >> 62);
+        const u64 has_prefix = __ballot(state == 2);
+        const u64 is_empty = __ballot(state == 0);
+        const int first = has_prefix ? __builtin_ctzll(has_prefix) : 63;
+        const u64 needed = first == 63 ? ~u64(0) : ((u64(2) << first) - 1);   // lanes 0..first
+        if (is_empty & needed) {
+          retry = true;      // keep what the complete windows before this one gave
+        } else {
+          // lanes before `first` hold tile aggregates (small); lane `first` may hold a prefix (64-bit)
+          got += wave_sum_u32(lane < first || (lane == first && !has_prefix) ? u32(d[e]) : 0u);
+          used = e + 1;
+          if (has_prefix) {
+            const u64 p = u64(lane_value(u32(d[e]), first)) | (u64(lane_value(u32(d[e] >> 32), first)) << 32);
+            got += p & kDescValueMask;
+            done = true;
+          }
+        }
+      }
+    }
+    excl += got;
+    if (done) return excl;
+    look -= 64 * used;       // complete windows are final: aggregates never change
+    if (retry) {
       if (++spins > kSpinLimit) {
         if (lane == 0) atomicOr(status, status_bit(ZC_ERR_HIP));
         return excl;
       }
       __builtin_amdgcn_s_sleep(1);
-      continue;
     }
-    excl += wave_sum_u64(lane <= first ? (d & kDescValueMask) : 0);
-    if (has_prefix) return excl;
-    look -= 64;
   }
 }
 

@@ -2,8 +2,7 @@
 // sign + plane packing, single-pass placement of the variable-size blocks.
 //
 // Work split.  A tile is 256 blocks (8192 values, 32 KiB of input) handled by a workgroup of
-// 4 waves; tiles are handed out by atomic tickets, so that look-back only ever waits on tiles
-// that are already running.  Each wave loads 2048 consecutive values with 16-byte loads,
+// 4 waves.  Each wave loads 2048 consecutive values with 16-byte loads,
 // quantises them where they land, and transposes the integer codes through LDS so that one
 // lane owns one block.  Delta, width and the bit-matrix transpose that yields the plane
 // words are then in-lane; the packed words wait in registers for the tile's base offset
@@ -117,28 +116,31 @@ __device__ inline void stage_and_copy_half(WordFn word, u32 w, u32 wmax, bool in
   wave_lds_sync();
 }
 
-// Front half of the work of one wave on its 64 blocks: load, quantise, transpose through LDS,
-// Lorenzo delta.  Leaves in d[j] delta j of the lane's block (d[0] = 0) and returns the
-// block's first code (the outlier).  `err` collects status bits of the checked path.
-__device__ inline i32 block_deltas(const CompressArgs& a, u64 wblock0, int lane, u32* wl, i32 (&d)[32], u32& err) {
+// Raw input of one wave's share of a tile: 8 x 16 bytes per lane, every load in flight at once.
+template <bool FULL>
+__device__ inline void load_raw(const CompressArgs& a, u64 wblock0, int lane, float4 (&x)[8]) {
   const u64 v0 = wblock0 * kBlockValues;
-  const bool full = v0 + u64(kWaveBlocks) * kBlockValues <= a.n;
-
-  // ---- load 16 B per lane (all eight loads in flight before the first use) ----
-  float4 x[8];
+  if (FULL) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const u64 idx = v0 + u64(256 * i + 4 * lane);
-    if (full) {
-      x[i] = *reinterpret_cast<const float4*>(a.in + idx);
-    } else {
+    for (int i = 0; i < 8; ++i) x[i] = *reinterpret_cast<const float4*>(a.in + v0 + u64(256 * i + 4 * lane));
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const u64 idx = v0 + u64(256 * i + 4 * lane);
       x[i].x = idx + 0 < a.n ? a.in[idx + 0] : 0.0f;
       x[i].y = idx + 1 < a.n ? a.in[idx + 1] : 0.0f;
       x[i].z = idx + 2 < a.n ? a.in[idx + 2] : 0.0f;
       x[i].w = idx + 3 < a.n ? a.in[idx + 3] : 0.0f;
     }
   }
+}
 
+// Quantise the wave's values where they landed, transpose the codes through LDS so that one
+// lane owns one block, and take the Lorenzo delta.  Leaves in d[j] delta j of the lane's
+// block (d[0] = 0) and returns the block's first code (the outlier).
+template <bool FULL>
+__device__ inline i32 block_deltas(const CompressArgs& a, const float4 (&x)[8], u64 wblock0, int lane, u32* wl,
+                                   i32 (&d)[32], u32& err) {
   // Some value of this wave outside the screened domain: the checked arithmetic for all of it.
   bool flagged = false;
 #pragma unroll
@@ -146,17 +148,14 @@ __device__ inline i32 block_deltas(const CompressArgs& a, u64 wblock0, int lane,
     flagged |= needs_checks(x[i].x, a) | needs_checks(x[i].y, a) | needs_checks(x[i].z, a) | needs_checks(x[i].w, a);
   const bool checked = __any(flagged);
 
-  // ---- quantise where the values landed; through LDS to one lane = one block ----
   // Loads 0..3 hold blocks 0..31 (lanes 0..31), loads 4..7 blocks 32..63.
   i32 q[32];
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i)
       *reinterpret_cast<int4*>(wl + (8 * i + (lane >> 3)) * kStageRow + 4 * (lane & 7)) =
           quantize4(x[4 * half + i], a, checked, err);
-      __builtin_amdgcn_sched_barrier(0);   // one group of four values at a time keeps the 64-bit temporaries few
-    }
     wave_lds_sync();
     if ((lane >> 5) == half) {
 #pragma unroll
@@ -167,167 +166,174 @@ __device__ inline i32 block_deltas(const CompressArgs& a, u64 wblock0, int lane,
     }
     wave_lds_sync();
   }
-  if (!full) {
+  const u64 b = wblock0 + u64(lane);
+  if (!FULL) {
     // the last block repeats its last code up to 32 values
-    const u64 b = wblock0 + u64(lane);
     const u64 cnt = b < a.nb ? a.n - b * kBlockValues : 0;
 #pragma unroll
     for (int j = 1; j < 32; ++j) q[j] = u64(j) < cnt ? q[j] : q[j - 1];
   }
-
-  // ---- Lorenzo delta ----
   d[0] = 0;
 #pragma unroll
   for (int j = 1; j < 32; ++j) d[j] = q[j] - q[j - 1];
   return q[0];
 }
 
-// Payload of a wave that holds a block wider than 15 bits (inputs outside the guaranteed
-// domain).  Such waves are rare, so rather than keep 32 more registers alive across the
-// look-back for them, the front half is redone here; and the function is kept out of line so
-// that its register needs do not shape the allocation of the common path.
-__device__ __attribute__((noinline)) void wide_payload(const CompressArgs& a, u64 wblock0, int lane, u32* wl, u32 w,
-                                                       u32 wmax, u32 off_in_wave, u32 half0_total, u32 wave_total,
-                                                       u32* payload, u64 dst0, u64 cap_words) {
-  u32 lo[16], hi[16];
-  {
-    i32 d[32];
-    u32 ignored = 0;
-    block_deltas(a, wblock0, lane, wl, d, ignored);
-    planes_from_deltas32(d, lo, hi);
+// Per-wave view of where its payload goes.
+struct Placement {
+  u32 w, wmax;              // this block's width; the widest of the wave
+  u32 off_in_wave;          // payload word offset of this block inside the wave
+  u32 half0_total, wave_total;
+  u32 wave_off, tile_total; // the wave inside the tile; payload words of the tile
+};
+
+// Back half of a tile once the plane words sit in registers (`word(i)`: 0 = sign, 1 + p =
+// plane p): publish the tile's size, look back for the base offset, then move the payload out
+// through LDS.  Called by all four waves; one barrier.
+template <bool FULL, int NW, typename WordFn>
+__device__ inline void finish_tile(const CompressArgs& a, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
+                                   u32* wl, u64* sh_base, int wave, int lane) {
+  if (threadIdx.x == 0)
+    desc_store(a.desc + tile, (tile == 0 ? kDescPrefix : kDescAggregate) | u64(pl.tile_total));
+  if (wave == 0) {
+    const u64 base = tile ? lookback_exclusive(a.desc, tile, &a.ctl->status) : 0;
+    if (lane == 0) {
+      if (tile) desc_store(a.desc + tile, kDescPrefix | (base + pl.tile_total));
+      *sh_base = base;
+    }
   }
-  auto word = [&](auto i) {
-    constexpr int I = decltype(i)::value;      // 0: sign, 1..16: low planes, 17..31: high planes
-    if constexpr (I == 0) return hi[15];
-    else if constexpr (I <= 16) return lo[I - 1];
-    else return hi[I - 17];
-  };
-  const u32 half_base[2] = {0u, half0_total};
-  const u32 half_total[2] = {half0_total, wave_total - half0_total};
+  __syncthreads();
+
+  const u64 base = *sh_base;
+  const u64 tend = tables_end(a.nb);
+  const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
+  u32* const payload = reinterpret_cast<u32*>(a.out + tend);
+  const u64 dst0 = base + pl.wave_off;
+  const u32 half_base[2] = {0u, pl.half0_total};
+  const u32 half_total[2] = {pl.half0_total, pl.wave_total - pl.half0_total};
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const u64 d0 = dst0 + half_base[h];
-    stage_and_copy_half<32>(word, w, wmax, (lane >> 5) == h, off_in_wave - half_base[h], half_total[h], wl,
+    stage_and_copy_half<NW>(word, pl.w, pl.wmax, (lane >> 5) == h, pl.off_in_wave - half_base[h], half_total[h], wl,
                             payload + d0, cap_words > d0 ? cap_words - d0 : 0, lane);
+  }
+  if (tile == ntiles - 1 && threadIdx.x == 0) {
+    const u64 total = tend + 4 * (base + pl.tile_total);
+    a.ctl->result = total;
+    if (total > a.out_cap) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
+    if (a.out_cap >= kHeaderBytes) reinterpret_cast<u64*>(a.out)[3] = total;
   }
 }
 
-__global__ __launch_bounds__(kTileThreads, 6) void compress_kernel(CompressArgs a) {
+// One workgroup per tile.  FULL = the launch covers tiles whose 8192 values all exist (pure
+// 16-byte loads, no tail), handed out by the per-XCD tickets over [first_tile, end_tile); the
+// ragged last tile of an input runs as a second launch of one workgroup with FULL = false.
+template <bool FULL>
+__global__ __launch_bounds__(kTileThreads, 4) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
   __shared__ u32 sh_tile;
   __shared__ u32 sh_wave_total[kTileWaves];
+  __shared__ u32 sh_wave_wmax[kTileWaves];
   __shared__ u64 sh_base;
 
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
   const u32 ntiles = u32(num_tiles(a.nb));
-  if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
-  __syncthreads();
-  const u32 tile = uniform(sh_tile);
-  if (tile == kNoTile) return;
-
   u32* const wl = lds + wave * kWaveStage;
-  const u64 wblock0 = u64(tile) * kTileBlocks + u64(wave) * kWaveBlocks;
-  const u64 b = wblock0 + u64(lane);
-  const bool active = b < a.nb;
+  const bool tables_fit = a.out_cap >= tables_end(a.nb);
   u32 err = 0;
 
-  u32 pw[16];          // pw[0] = sign, pw[1 + p] = plane p   (widths up to 15)
-  u32 w, wmax;
+  u32 tile = first_tile;
+  if (FULL) {
+    if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, end_tile, xcc_id());
+    __syncthreads();
+    tile = uniform(sh_tile);
+    if (tile == kNoTile) return;
+  }
   {
+    const u64 wblock0 = u64(tile) * kTileBlocks + u64(wave) * kWaveBlocks;
+    const u64 b = wblock0 + u64(lane);
+    const bool active = b < a.nb;
+    float4 x[8];
+    load_raw<FULL>(a, wblock0, lane, x);
+
     i32 d[32];
-    const i32 outlier = block_deltas(a, wblock0, lane, wl, d, err);
+    const i32 outlier = block_deltas<FULL>(a, x, wblock0, lane, wl, d, err);
     u32 any = 0;
 #pragma unroll
     for (int j = 1; j < 32; ++j) any |= u32(d[j] < 0 ? -d[j] : d[j]);
-    w = (active && any) ? 32u - u32(__builtin_clz(any)) : 0u;
-    wmax = wave_max_u32(w);
-    if (active && a.out_cap >= tables_end(a.nb)) {
-      a.out[kHeaderBytes + b] = u8(w);
+    Placement pl;
+    pl.w = (active && any) ? 32u - u32(__builtin_clz(any)) : 0u;
+    pl.wmax = wave_max_u32(pl.w);
+    if (active && tables_fit) {
+      a.out[kHeaderBytes + b] = u8(pl.w);
       reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(a.nb))[b] = outlier;
     }
-    // ---- values -> sign + plane words, in registers (wide blocks are packed after the look-back) ----
-    // (the empty asm keeps the compiler from hoisting the sign-magnitude split of all 32
-    //  deltas above the branch, where it would hold twice as many registers)
-    if (wmax <= 7) {
-      u32 r[8];
-#pragma unroll
-      for (int j = 0; j < 32; ++j) asm volatile("" : "+v"(d[j]));
-      planes_from_deltas8(d, r);
-      pw[0] = r[7];
-#pragma unroll
-      for (int p = 0; p < 7; ++p) pw[1 + p] = r[p];
-#pragma unroll
-      for (int p = 8; p < 16; ++p) pw[p] = 0;
-    } else if (wmax <= 15) {
-      u32 r[16];
-#pragma unroll
-      for (int j = 0; j < 32; ++j) asm volatile("" : "+v"(d[j]));
-      planes_from_deltas16(d, r);
-      pw[0] = r[15];
-#pragma unroll
-      for (int p = 0; p < 15; ++p) pw[1 + p] = r[p];
-    } else {
-#pragma unroll
-      for (int p = 0; p < 16; ++p) pw[p] = 0;
-    }
-  }
-  const u32 words = psize_words(w);
 
-  // ---- place the block inside the wave and the wave inside the tile ----
-  const u32 incl = wave_inclusive_sum(words);
-  const u32 wave_total = uniform(u32(__shfl(int(incl), 63)));
-  const u32 half0_total = uniform(u32(__shfl(int(incl), 31)));
-  const u32 off_in_wave = incl - words;
-  if (lane == 0) sh_wave_total[wave] = wave_total;
-  __syncthreads();   // wave totals visible
-
-  u32 wave_off = 0, tile_total = 0;
-#pragma unroll
-  for (int i = 0; i < kTileWaves; ++i) {
-    const u32 t = sh_wave_total[i];
-    if (i < wave) wave_off += t;
-    tile_total += t;
-  }
-  if (threadIdx.x == 0) desc_store(a.desc + tile, (tile == 0 ? kDescPrefix : kDescAggregate) | u64(tile_total));
-
-  // ---- look back for the tile's base offset ----
-  if (wave == 0) {
-    const u64 base = tile ? lookback_exclusive(a.desc, tile, &a.ctl->status) : 0;
+    // ---- place the block inside the wave and the wave inside the tile ----
+    const u32 words = psize_words(pl.w);
+    const u32 incl = wave_inclusive_sum(words);
+    pl.wave_total = lane_value(incl, 63);
+    pl.half0_total = lane_value(incl, 31);
+    pl.off_in_wave = incl - words;
     if (lane == 0) {
-      if (tile) desc_store(a.desc + tile, kDescPrefix | (base + tile_total));
-      sh_base = base;
+      sh_wave_total[wave] = pl.wave_total;
+      sh_wave_wmax[wave] = pl.wmax;
+    }
+    __syncthreads();   // wave totals visible; also fences the previous tile's use of sh_base
+    pl.wave_off = 0;
+    pl.tile_total = 0;
+    u32 tile_wmax = 0;
+#pragma unroll
+    for (int i = 0; i < kTileWaves; ++i) {
+      const u32 t = sh_wave_total[i];
+      if (i < wave) pl.wave_off += t;
+      pl.tile_total += t;
+      tile_wmax = tile_wmax > sh_wave_wmax[i] ? tile_wmax : sh_wave_wmax[i];
+    }
+    tile_wmax = uniform(tile_wmax);
+
+    // ---- deltas -> sign + plane words in registers, then the back half ----
+    // (the empty asm keeps the compiler from hoisting the sign-magnitude split of all 32
+    //  deltas above the branches, where it would hold twice as many registers)
+    if (tile_wmax <= 15) {
+      u32 pw[16];          // pw[0] = sign, pw[1 + p] = plane p
+      if (pl.wmax <= 7) {
+        u32 r[8];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) asm volatile("" : "+v"(d[j]));
+        planes_from_deltas8(d, r);
+        pw[0] = r[7];
+#pragma unroll
+        for (int p = 0; p < 7; ++p) pw[1 + p] = r[p];
+#pragma unroll
+        for (int p = 8; p < 16; ++p) pw[p] = 0;
+      } else {
+        u32 r[16];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) asm volatile("" : "+v"(d[j]));
+        planes_from_deltas16(d, r);
+        pw[0] = r[15];
+#pragma unroll
+        for (int p = 0; p < 15; ++p) pw[1 + p] = r[p];
+      }
+      finish_tile<FULL, 16>(a, [&](auto i) { return pw[decltype(i)::value]; }, pl, tile, ntiles, wl, &sh_base, wave, lane);
+    } else {
+      // a tile with a block wider than 15 bits (input outside the guaranteed domain): all planes
+      u32 lo[16], hi[16];
+#pragma unroll
+      for (int j = 0; j < 32; ++j) asm volatile("" : "+v"(d[j]));
+      planes_from_deltas32(d, lo, hi);
+      auto word = [&](auto i) {
+        constexpr int I = decltype(i)::value;      // 0: sign, 1..16: low planes, 17..31: high planes
+        if constexpr (I == 0) return hi[15];
+        else if constexpr (I <= 16) return lo[I - 1];
+        else return hi[I - 17];
+      };
+      finish_tile<FULL, 32>(a, word, pl, tile, ntiles, wl, &sh_base, wave, lane);
     }
   }
   if (err) atomicOr(&a.ctl->status, err);
-  __syncthreads();
-
-  // ---- payload out: each half-wave through the staging area, coalesced stores ----
-  const u64 base = sh_base;
-  const u64 tend = tables_end(a.nb);
-  const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
-  u32* const payload = reinterpret_cast<u32*>(a.out + tend);
-  const u64 dst0 = base + wave_off;
-  const u32 half_base[2] = {0u, half0_total};
-  const u32 half_total[2] = {half0_total, wave_total - half0_total};
-  if (wmax <= 15) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const u64 d0 = dst0 + half_base[h];
-      stage_and_copy_half<16>([&](auto i) { return pw[decltype(i)::value]; }, w, wmax, (lane >> 5) == h,
-                              off_in_wave - half_base[h], half_total[h], wl, payload + d0,
-                              cap_words > d0 ? cap_words - d0 : 0, lane);
-    }
-  } else {
-    wide_payload(a, wblock0, lane, wl, w, wmax, off_in_wave, half0_total, wave_total, payload, dst0, cap_words);
-  }
-
-  if (tile == ntiles - 1 && threadIdx.x == 0) {
-    const u64 total = tend + 4 * (base + tile_total);
-    a.ctl->result = total;
-    if (total > a.out_cap) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
-    if (a.out_cap >= kHeaderBytes) reinterpret_cast<u64*>(a.out)[3] = total;
-  }
 }
 
 // Clears the control block and the tile descriptors, and writes the fixed header fields and

@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kTileThreads) void reduce_kernel(ReduceArgs a) {
 
   // ---- place, publish, pack, look back, copy out (as in compression) ----
   const u32 incl = wave_inclusive_sum(words);
-  const u32 wave_total = uniform(u32(__shfl(int(incl), 63)));
+  const u32 wave_total = lane_value(incl, 63);
   const u32 off_in_wave = incl - words;
   const u32 wmax = wave_max_u32(w);
   if (lane == 0) sh_wave_total[wave] = wave_total;

@@ -115,8 +115,8 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
   }
   if (bad) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
   // four threads = one segment of 64 blocks
-  u32 seg_total = sum + u32(__shfl_xor(int(sum), 1));
-  seg_total += u32(__shfl_xor(int(seg_total), 2));
+  u32 seg_total = sum + dpp_mov<kDppQuadSwap1>(sum);
+  seg_total += dpp_mov<kDppQuadSwap2>(seg_total);
   const u64 seg = group * kScanGroupSegs + (threadIdx.x >> 2);
   if ((threadIdx.x & 3) == 0 && seg < num_segments(h.nb))
     a.index.seg_sum[u64(s) * 4 * a.index.tiles_cap + seg] = seg_total;
