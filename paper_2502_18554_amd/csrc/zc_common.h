@@ -221,6 +221,20 @@ __device__ inline u64 desc_load(const u64* d) {
   return __hip_atomic_load(d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// LDS of one wave: 32 rows (blocks) of 32 codes + 4 words of padding, which keeps the 128-bit
+// row reads of 16 consecutive lanes on distinct banks.  A wave's 64 blocks pass through it in
+// two halves (blocks of lanes 0..31, then 32..63): codes or reconstructed values on one side,
+// packed payload on the other, so that five or more workgroups fit a compute unit.
+constexpr int kStageRow = 36;
+constexpr int kWaveStage = 32 * kStageRow;              // 1152 words = 4.5 KiB per wave
+static_assert(kWaveStage >= 32 * 33, "one half-wave of worst-case blocks must fit the staging area");
+
+__device__ inline void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // 32-bit values passed between workgroups of one kernel (group sums of the stream index).
 __device__ inline void desc32_store(u32* d, u32 v) {
   __hip_atomic_store(d, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -67,20 +67,6 @@ __device__ inline i32 quantize_value(float x, const CompressArgs& a, u32& err) {
   return quantize_fast(x, a);
 }
 
-// LDS of one wave: 32 rows (blocks) of 32 codes + 4 words of padding, which keeps the 128-bit
-// row reads of 16 consecutive lanes on distinct banks.  A wave's 64 blocks pass through it in
-// two halves (blocks of lanes 0..31, then 32..63), codes on the way in and packed payload
-// on the way out, so that five or more workgroups fit a compute unit.
-constexpr int kStageRow = 36;
-constexpr int kWaveStage = 32 * kStageRow;              // 1152 words = 4.5 KiB per wave
-static_assert(kWaveStage >= 32 * 33, "one half-wave of worst-case blocks must fit the staging area");
-
-__device__ inline void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 __device__ inline int4 quantize4(const float4& x, const CompressArgs& a, bool checked, u32& err) {
   int4 q;
   if (__builtin_expect(checked, 0)) {

@@ -1,14 +1,17 @@
 // fZ-light decompression kernel: the inverse of the stages of Section 3.3.
 //
-// Same geometry as compression: a tile is 256 blocks, one lane owns one block.  A wave's
-// payload offset comes from the stream index (zc_scan.h); inside the wave a scan of
-// the block sizes places each lane.  The lane reads its sign and plane words, rebuilds the
-// deltas, runs the Lorenzo chain from the block's outlier, dequantises, and the floats are
-// transposed through LDS so that they leave as 16-byte coalesced stores.
+// Same geometry as compression: a tile is 256 blocks, one lane owns one block, and there is no
+// dependency between workgroups: a wave's payload offset comes from the stream index
+// (zc_scan.h), and a scan of the block sizes places each lane inside the wave.  The wave's
+// payload is contiguous, so it is copied into LDS with coalesced loads (each byte leaves the
+// L2 once) and every lane then picks its sign and plane words there.  A bit-matrix transpose
+// turns them back into deltas; the Lorenzo chain from the block's outlier and the
+// dequantisation follow in registers; the floats go back through LDS so that they leave as
+// 16-byte coalesced stores.  Both LDS passes handle the wave in two halves of 32 blocks.
 #pragma once
 
+#include "zc_bitmatrix.h"
 #include "zc_common.h"
-#include "zc_planes.h"
 #include "zc_scan.h"
 
 namespace zc {
@@ -21,8 +24,8 @@ struct DecompressArgs {
   Control* ctl;
 };
 
-__global__ __launch_bounds__(kTileThreads) void decompress_kernel(DecompressArgs a) {
-  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveLds];
+__global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
 
   if (validation_failed(a.ctl)) return;
   const ParsedHeader h = parse_header(a.in);
@@ -37,8 +40,10 @@ __global__ __launch_bounds__(kTileThreads) void decompress_kernel(DecompressArgs
 
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
-  u32* wl = lds + wave * kWaveLds;
-  const u64 wblock0 = u64(tile) * kTileBlocks + u64(wave) * kWaveBlocks;
+  u32* const wl = lds + wave * kWaveStage;
+  const u64 seg = u64(tile) * kTileWaves + u64(wave);
+  if (seg >= num_segments(h.nb)) return;           // no barrier below: waves are independent
+  const u64 wblock0 = seg * kWaveBlocks;
   const u64 b = wblock0 + u64(lane);
   const bool active = b < h.nb;
 
@@ -48,49 +53,108 @@ __global__ __launch_bounds__(kTileThreads) void decompress_kernel(DecompressArgs
   const u64 payload_words = (h.total - tables_end(h.nb)) / 4;
 
   u32 w = active ? u32(widths[b]) : 0u;
+  u32 cur = active ? u32(outliers[b]) : 0u;
   const u32 words = psize_words(w);
   const u32 incl = wave_inclusive_sum(words);
-  const u64 seg = u64(tile) * kTileWaves + u64(wave);
-  u64 off = 0;
-  if (seg < num_segments(h.nb)) off = segment_offset(a.index, 0, seg) + (incl - words);
-  if (off + words > payload_words) w = 0;        // cannot happen once the scan has validated the stream
+  const u32 off_in_wave = incl - words;
+  const u32 wave_total = lane_value(incl, 63);
+  const u32 half0_total = lane_value(incl, 31);
+  const u64 seg_off = segment_offset(a.index, 0, seg);
   const u32 wmax = wave_max_u32(w);
+  // a validated stream keeps every segment inside the payload; refuse to read outside anyway
+  const bool inside = seg_off + wave_total <= payload_words;
 
-  // ---- planes -> sign-magnitude deltas -> codes ----
-  u32 c[32];
-  load_block_planes(c, w, wmax, payload + off);
+  // ---- the wave's payload through LDS; each lane picks its sign and plane words ----
+  i32 d[32];
+  if (wmax <= 15) {
+    u32 pw[16];              // pw[0] = sign, pw[1 + p] = plane p
+#pragma unroll
+    for (int p = 0; p < 16; ++p) pw[p] = 0;
+    const u32 half_base[2] = {0u, half0_total};
+    const u32 half_total[2] = {half0_total, wave_total - half0_total};
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const u32* src = payload + seg_off + half_base[hh];
+      for (u32 i = u32(lane); i < half_total[hh]; i += 64) wl[i] = inside ? src[i] : 0u;
+      wave_lds_sync();
+      if ((lane >> 5) == hh && w) {
+        const u32* mine = wl + (off_in_wave - half_base[hh]);
+        pw[0] = mine[0];
+#pragma unroll
+        for (int p = 0; p < 15; ++p) {
+          if (u32(p) >= wmax) break;
+          if (u32(p) < w) pw[1 + p] = mine[1 + p];
+        }
+      }
+      wave_lds_sync();
+    }
+    if (wmax <= 7) {
+      u32 r[8];
+#pragma unroll
+      for (int p = 0; p < 7; ++p) r[p] = pw[1 + p];
+      r[7] = pw[0];
+      deltas_from_planes8(r, d);
+    } else {
+      u32 r[16];
+#pragma unroll
+      for (int p = 0; p < 15; ++p) r[p] = pw[1 + p];
+      r[15] = pw[0];
+      deltas_from_planes16(r, d);
+    }
+  } else {
+    // a block wider than 15 bits (stream of an input outside the guaranteed domain): each lane
+    // fetches its words straight from global memory
+    u32 lo[16], hi[16];
+#pragma unroll
+    for (int p = 0; p < 16; ++p) lo[p] = hi[p] = 0;
+    if (w && inside) {
+      const u32* mine = payload + seg_off + off_in_wave;
+      hi[15] = mine[0];
+#pragma unroll
+      for (int p = 0; p < 16; ++p)
+        if (u32(p) < w) lo[p] = mine[1 + p];
+#pragma unroll
+      for (int p = 0; p < 15; ++p)
+        if (u32(16 + p) < w) hi[p] = mine[17 + p];
+    }
+    deltas_from_planes32(lo, hi, d);
+  }
+
+  // ---- Lorenzo chain from the outlier, dequantise ----
   const double step = double(__uint_as_float(h.eb_bits)) * 63.0 / 32.0;
-  u32 cur = active ? u32(outliers[b]) : 0u;
   float x[32];
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
-    const u32 sm = rotr32(c[j], j);
-    const u32 m = u32(i32(sm) >> 31);             // all ones when the delta is negative
-    cur += ((sm & 0x7fffffffu) ^ m) - m;
+    cur += u32(d[j]);
     x[j] = float(__dmul_rn(double(i32(cur)), step));
   }
 
-  // ---- transpose through LDS, 16-byte coalesced stores ----
-#pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    float4 v = make_float4(x[4 * t], x[4 * t + 1], x[4 * t + 2], x[4 * t + 3]);
-    *reinterpret_cast<float4*>(wl + lane * kRow + 4 * t) = v;
-  }
-  __syncthreads();
+  // ---- transpose through LDS (two halves of 32 blocks), 16-byte coalesced stores ----
   const u64 v0 = wblock0 * kBlockValues;
   const bool full = v0 + u64(kWaveBlocks) * kBlockValues <= h.n;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const u64 idx = v0 + u64(256 * i + 4 * lane);
-    const float4 v = *reinterpret_cast<const float4*>(wl + (8 * i + (lane >> 3)) * kRow + 4 * (lane & 7));
-    if (full) {
-      *reinterpret_cast<float4*>(a.out + idx) = v;
-    } else {
-      if (idx + 0 < h.n) a.out[idx + 0] = v.x;
-      if (idx + 1 < h.n) a.out[idx + 1] = v.y;
-      if (idx + 2 < h.n) a.out[idx + 2] = v.z;
-      if (idx + 3 < h.n) a.out[idx + 3] = v.w;
+  for (int hh = 0; hh < 2; ++hh) {
+    if ((lane >> 5) == hh) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        *reinterpret_cast<float4*>(wl + (lane & 31) * kStageRow + 4 * t) =
+            make_float4(x[4 * t], x[4 * t + 1], x[4 * t + 2], x[4 * t + 3]);
     }
+    wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const u64 idx = v0 + u64(1024 * hh + 256 * i + 4 * lane);
+      const float4 v = *reinterpret_cast<const float4*>(wl + (8 * i + (lane >> 3)) * kStageRow + 4 * (lane & 7));
+      if (full) {
+        *reinterpret_cast<float4*>(a.out + idx) = v;
+      } else {
+        if (idx + 0 < h.n) a.out[idx + 0] = v.x;
+        if (idx + 1 < h.n) a.out[idx + 1] = v.y;
+        if (idx + 2 < h.n) a.out[idx + 2] = v.z;
+        if (idx + 3 < h.n) a.out[idx + 3] = v.w;
+      }
+    }
+    wave_lds_sync();
   }
 }
 
