@@ -1,7 +1,8 @@
 /* zc — fZ-light error-bounded lossy compression and the compressed-Allreduce local step,
  * hand-written for AMD MI355X (gfx950).  C ABI; every pointer named d_* is DEVICE memory,
  * everything else is host memory.  The library allocates no device memory and keeps no
- * global state: the caller owns inputs, outputs and the workspace.
+ * state between calls (but see zc_profile_enable): the caller owns inputs, outputs and the
+ * workspace.
  *
  * Method: ZCCL, arXiv 2502.18554.  fZ-light is described in Section 3.3 (block partition,
  * fused quantisation + 1D Lorenzo prediction, first value kept as a 4-byte outlier, sign
@@ -110,6 +111,21 @@ int zc_debug_quantize(const float* d_in, size_t n, float abs_eb, int32_t* d_q,
  * into d_off_words[nb].  Synchronous.  Errors: ARG, FORMAT, HIP. */
 int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_words, size_t off_cap,
                            void* d_ws, size_t ws_bytes, void* hip_stream);
+
+/* Measurement aid (not part of the method).  While enabled, zc_compress, zc_decompress and
+ * zc_reduce_compressed record a pair of HIP events on the call's stream around their main
+ * kernel (the compress kernel over the full tiles, the decompress kernel, the reduce kernel;
+ * not the small set-up kernels before it).  zc_profile_collect waits for the recorded pairs,
+ * stores up to cap elapsed times in milliseconds in ms[] and the matching ZC_KERNEL_* ids in
+ * kernel[] (host arrays, either may be NULL) in call order, forgets them, and returns how
+ * many it stored (a negative status on a HIP error).  The events are host objects created on
+ * first use and reused; this is the only state the library keeps.  Enabling or disabling
+ * forgets the pairs recorded so far. */
+#define ZC_KERNEL_COMPRESS 1
+#define ZC_KERNEL_DECOMPRESS 2
+#define ZC_KERNEL_REDUCE 3
+int zc_profile_enable(int on);
+int zc_profile_collect(float* ms, int* kernel, int cap);
 
 #ifdef __cplusplus
 }

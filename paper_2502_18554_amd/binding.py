@@ -19,6 +19,7 @@ ZC_MAX_K = 64
 EXPORTS = [
     "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_reduce_compressed",
     "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
+    "zc_profile_enable", "zc_profile_collect",
 ]
 
 _lib = None
@@ -52,6 +53,8 @@ def lib():
         L.zc_strerror.argtypes = [C.c_int]
         L.zc_debug_quantize.argtypes = [vp, sz, C.c_float, vp, vp, sz, vp]
         L.zc_debug_block_offsets.argtypes = [vp, sz, vp, sz, vp, sz, vp]
+        L.zc_profile_enable.argtypes = [C.c_int]
+        L.zc_profile_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int), C.c_int]
         _lib = L
     return _lib
 
@@ -132,3 +135,20 @@ def zc_debug_quantize(d_in, n, abs_eb, d_q, d_ws, stream=None):
 def zc_debug_block_offsets(d_in, in_bytes, d_off_words, d_ws, stream=None):
     return lib().zc_debug_block_offsets(_p(d_in), in_bytes, _p(d_off_words), d_off_words.numel(), _p(d_ws),
                                         d_ws.numel() * d_ws.element_size(), _stream(stream))
+
+
+KERNEL_NAMES = {1: "compress", 2: "decompress", 3: "reduce"}
+
+
+def zc_profile_enable(on):
+    return lib().zc_profile_enable(1 if on else 0)
+
+
+def zc_profile_collect(cap=65536):
+    """Returns [(kernel name, milliseconds)] for the main kernels launched since zc_profile_enable(True)."""
+    ms = (C.c_float * cap)()
+    kind = (C.c_int * cap)()
+    count = lib().zc_profile_collect(ms, kind, cap)
+    if count < 0:
+        raise ZcError(-count, "zc_profile_collect")
+    return [(KERNEL_NAMES.get(kind[i], str(kind[i])), float(ms[i])) for i in range(count)]

@@ -4,6 +4,8 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "zc_common.h"
 #include "zc_compress.h"
@@ -30,8 +32,39 @@ int status_from_bits(u32 bits) {
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
+// Optional timing of the main kernel of each entry point (zc_profile_*): host-side state only.
+struct KernelTimer {
+  std::mutex mu;
+  bool on = false;
+  struct Slot { hipEvent_t a, b; int kind; };
+  std::vector<Slot> pool;   // events are created once and reused
+  size_t used = 0;
+  Slot* begin(int kind, hipStream_t stream) {
+    std::lock_guard<std::mutex> g(mu);
+    if (!on) return nullptr;
+    if (used == pool.size()) {
+      Slot s;
+      s.kind = 0;
+      if (hipEventCreate(&s.a) != hipSuccess) return nullptr;
+      if (hipEventCreate(&s.b) != hipSuccess) { (void)hipEventDestroy(s.a); return nullptr; }
+      pool.push_back(s);
+    }
+    Slot* s = &pool[used++];
+    s->kind = kind;
+    (void)hipEventRecord(s->a, stream);
+    return s;
+  }
+  void end(Slot* s, hipStream_t stream) {
+    if (s) (void)hipEventRecord(s->b, stream);
+  }
+};
+KernelTimer g_timer;
+
 // Most blocks a stream of `bytes` bytes can describe: each costs at least 5 table bytes.
 u64 blocks_bound(u64 bytes) { return bytes > kHeaderBytes ? (bytes - kHeaderBytes) / 5 : 0; }
+
+// Workgroups of stream_index_kernel per stream: 16 tiles make a scan group.
+u32 index_grid(u64 tiles) { return u32(((tiles + 15) / 16 + kIndexGroups - 1) / kIndexGroups); }
 
 int finish(const void* d_ws, size_t* result, hipStream_t stream) {
   struct { u32 status, reserved; u64 result; } host;
@@ -154,8 +187,10 @@ int zc_compress(const float* d_in, size_t n, float abs_eb, void* d_out, size_t o
   fill_compress_args(ca, d_in, n, abs_eb, d_out, out_cap, l);
   launch_init(l, u32(ntiles), ca.out, out_cap, n, ca.eb_bits, stream);
   const u32 full_tiles = u32(n / kTileValues);      // tiles whose 8192 values all exist
+  KernelTimer::Slot* slot = full_tiles ? g_timer.begin(ZC_KERNEL_COMPRESS, stream) : nullptr;
   if (full_tiles)
     hipLaunchKernelGGL(compress_kernel<true>, dim3(full_tiles), dim3(kTileThreads), 0, stream, ca, 0u, full_tiles);
+  g_timer.end(slot, stream);
   if (ntiles > full_tiles)                          // the ragged last tile
     hipLaunchKernelGGL(compress_kernel<false>, dim3(1), dim3(kTileThreads), 0, stream, ca, full_tiles, u32(ntiles));
   if (!launch_ok()) return ZC_ERR_HIP;
@@ -184,14 +219,16 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
   sa.check_match = 0;
   sa.index = l.index;
   sa.ctl = l.ctl;
-  hipLaunchKernelGGL(stream_index_kernel, dim3(u32((tiles + 15) / 16), 1), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), 1), dim3(256), 0, stream, sa);
   DecompressArgs da;
   da.in = sa.streams[0];
   da.out = d_out;
   da.out_cap_elems = out_cap_elems;
   da.index = l.index;
   da.ctl = l.ctl;
+  KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_DECOMPRESS, stream);
   hipLaunchKernelGGL(decompress_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, da);
+  g_timer.end(slot, stream);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!n_out) return ZC_OK;
   return finish(d_ws, n_out, stream);
@@ -226,17 +263,44 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   sa.check_match = 1;
   sa.index = l.index;
   sa.ctl = l.ctl;
-  hipLaunchKernelGGL(stream_index_kernel, dim3(u32((tiles + 15) / 16), u32(k)), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), u32(k)), dim3(256), 0, stream, sa);
   ra.k = k;
   ra.index = l.index;
   ra.out = static_cast<u8*>(d_out);
   ra.out_cap = out_cap;
   ra.ctl = l.ctl;
   ra.desc = l.desc;
+  KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_REDUCE, stream);
   hipLaunchKernelGGL(reduce_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
+  g_timer.end(slot, stream);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
+}
+
+int zc_profile_enable(int on) {
+  std::lock_guard<std::mutex> g(g_timer.mu);
+  g_timer.on = on != 0;
+  g_timer.used = 0;
+  return ZC_OK;
+}
+
+int zc_profile_collect(float* ms, int* kernel, int cap) {
+  std::lock_guard<std::mutex> g(g_timer.mu);
+  int count = 0;
+  for (size_t i = 0; i < g_timer.used && count < cap; ++i) {
+    KernelTimer::Slot& s = g_timer.pool[i];
+    float t = 0.f;
+    if (hipEventSynchronize(s.b) != hipSuccess || hipEventElapsedTime(&t, s.a, s.b) != hipSuccess) {
+      g_timer.used = 0;
+      return -ZC_ERR_HIP;
+    }
+    if (ms) ms[count] = t;
+    if (kernel) kernel[count] = s.kind;
+    ++count;
+  }
+  g_timer.used = 0;
+  return count;
 }
 
 int zc_peek_header(const void* d_in, size_t in_bytes, size_t* n, float* abs_eb, unsigned* nsum,
@@ -293,7 +357,7 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
   sa.check_match = 0;
   sa.index = l.index;
   sa.ctl = l.ctl;
-  hipLaunchKernelGGL(stream_index_kernel, dim3(u32((tiles + 15) / 16), 1), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), 1), dim3(256), 0, stream, sa);
   OffsetsArgs oa;
   oa.in = sa.streams[0];
   oa.index = l.index;

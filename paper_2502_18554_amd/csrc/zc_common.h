@@ -56,22 +56,22 @@ static_assert(sizeof(Control) == 64, "control block is 64 bytes");
 // A segment is the 64 blocks owned by one wave; a tile is 4 segments.
 __host__ __device__ inline u64 num_segments(u64 nb) { return (nb + kWaveBlocks - 1) / kWaveBlocks; }
 
-// Positions inside an existing stream are kept at two levels (see zc_scan.h): the payload
-// size of every segment, and the exclusive offset of every scan group of 64 segments.
+// Positions inside an existing stream are kept at two levels (see zc_scan.h): the offset of
+// every segment inside its scan group of 64 segments, and the exclusive offset of every group.
 constexpr int kScanGroupSegs = 64;
 constexpr int kScanGroupBlocks = kScanGroupSegs * kWaveBlocks;     // 4096 blocks
 __host__ __device__ inline u64 num_scan_groups(u64 nb) { return (nb + kScanGroupBlocks - 1) / kScanGroupBlocks; }
 
 struct StreamIndex {
-  u32* seg_sum;     // [k][4 * tiles_cap]   payload words of each segment
+  u32* seg_off;     // [k][4 * tiles_cap]   payload word offset of each segment inside its scan group
   u32* grp_off;     // [k][groups_cap]      payload word offset of each scan group
-  u32* done;        // [ZC_MAX_K]           scan groups finished, per stream
+  u32* done;        // [ZC_MAX_K]           index workgroups finished, per stream
   u64 tiles_cap;
   u64 groups_cap;
 };
 
 // How a workspace of ws_bytes is carved up for calls with k input streams:
-//   Control | done[ZC_MAX_K] | desc[tiles_cap] (u64) | seg_sum[k][4 * tiles_cap] | grp_off[k][groups_cap]
+//   Control | done[ZC_MAX_K] | desc[tiles_cap] (u64) | seg_off[k][4 * tiles_cap] | grp_off[k][groups_cap]
 // tiles_cap follows from ws_bytes alone, so kernels can refuse streams that do not fit.
 struct WorkspaceLayout {
   u64 tiles_cap;
@@ -85,7 +85,7 @@ constexpr u64 kWsFixed = sizeof(Control) + 4 * ZC_MAX_K + 4 * ZC_MAX_K + 64;   /
 __host__ inline u64 workspace_bytes(u64 n_max, int k_max) {
   if (k_max < 1) k_max = 1;
   const u64 t = num_tiles(num_blocks(n_max)) + 16;
-  return kWsFixed + t * (8 + 17 * u64(k_max));      // 17 = segment sums (16) + the tile's share of the group offsets
+  return kWsFixed + t * (8 + 17 * u64(k_max));      // 17 = segment offsets (16) + the tile's share of the group offsets
 }
 
 __host__ inline WorkspaceLayout workspace_layout(void* d_ws, u64 ws_bytes, int k) {
@@ -99,7 +99,7 @@ __host__ inline WorkspaceLayout workspace_layout(void* d_ws, u64 ws_bytes, int k
   p += 4 * ZC_MAX_K;
   l.desc = reinterpret_cast<u64*>(p);
   p += pad16(8 * l.tiles_cap);
-  l.index.seg_sum = reinterpret_cast<u32*>(p);
+  l.index.seg_off = reinterpret_cast<u32*>(p);
   p += pad16(16 * l.tiles_cap * u64(k));
   l.index.grp_off = reinterpret_cast<u32*>(p);
   l.index.tiles_cap = l.tiles_cap;

@@ -6,8 +6,8 @@
 // payload is contiguous, so it is copied into LDS with coalesced loads (each byte leaves the
 // L2 once) and every lane then picks its sign and plane words there.  A bit-matrix transpose
 // turns them back into deltas; the Lorenzo chain from the block's outlier and the
-// dequantisation follow in registers; the floats go back through LDS so that they leave as
-// 16-byte coalesced stores.  Both LDS passes handle the wave in two halves of 32 blocks.
+// dequantisation follow in registers; the floats go back through LDS, in two halves of 32
+// blocks, so that they leave as 16-byte coalesced stores.
 #pragma once
 
 #include "zc_bitmatrix.h"
@@ -58,7 +58,6 @@ __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressA
   const u32 incl = wave_inclusive_sum(words);
   const u32 off_in_wave = incl - words;
   const u32 wave_total = lane_value(incl, 63);
-  const u32 half0_total = lane_value(incl, 31);
   const u64 seg_off = segment_offset(a.index, 0, seg);
   const u32 wmax = wave_max_u32(w);
   // a validated stream keeps every segment inside the payload; refuse to read outside anyway
@@ -67,27 +66,47 @@ __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressA
   // ---- the wave's payload through LDS; each lane picks its sign and plane words ----
   i32 d[32];
   if (wmax <= 15) {
+    // At most 64 * 16 words.  The copy starts at the 16-byte boundary at or below the segment
+    // (the payload area itself is 16-byte aligned) and keeps that misalignment in LDS, so it
+    // moves 16 bytes per lane and instruction, all loads in flight together.
+    const u32 mis = u32(seg_off) & 3u;
+    const u64 src0 = seg_off - mis;                    // in words, multiple of 4
+    const u32 span = inside ? mis + wave_total : 0u;   // words to bring in, <= 1027
+    uint4 stage[5];
+#pragma unroll
+    for (int i = 0; i < 5; ++i) {
+      const u32 idx = 4u * u32(lane) + 256u * u32(i);
+      stage[i] = make_uint4(0, 0, 0, 0);
+      if (idx < span) {
+        if (src0 + idx + 4 <= payload_words) {
+          stage[i] = *reinterpret_cast<const uint4*>(payload + src0 + idx);
+        } else {                                       // the last words of the stream
+          const u64 left = payload_words - (src0 + idx);
+          stage[i].x = payload[src0 + idx];
+          if (left > 1) stage[i].y = payload[src0 + idx + 1];
+          if (left > 2) stage[i].z = payload[src0 + idx + 2];
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 5; ++i) {
+      const u32 idx = 4u * u32(lane) + 256u * u32(i);
+      if (idx < span) *reinterpret_cast<uint4*>(wl + idx) = stage[i];
+    }
+    wave_lds_sync();
     u32 pw[16];              // pw[0] = sign, pw[1 + p] = plane p
 #pragma unroll
     for (int p = 0; p < 16; ++p) pw[p] = 0;
-    const u32 half_base[2] = {0u, half0_total};
-    const u32 half_total[2] = {half0_total, wave_total - half0_total};
+    if (w && inside) {
+      const u32* mine = wl + mis + off_in_wave;
+      pw[0] = mine[0];
 #pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
-      const u32* src = payload + seg_off + half_base[hh];
-      for (u32 i = u32(lane); i < half_total[hh]; i += 64) wl[i] = inside ? src[i] : 0u;
-      wave_lds_sync();
-      if ((lane >> 5) == hh && w) {
-        const u32* mine = wl + (off_in_wave - half_base[hh]);
-        pw[0] = mine[0];
-#pragma unroll
-        for (int p = 0; p < 15; ++p) {
-          if (u32(p) >= wmax) break;
-          if (u32(p) < w) pw[1 + p] = mine[1 + p];
-        }
+      for (int p = 0; p < 15; ++p) {
+        if (u32(p) >= wmax) break;
+        if (u32(p) < w) pw[1 + p] = mine[1 + p];
       }
-      wave_lds_sync();
     }
+    wave_lds_sync();
     if (wmax <= 7) {
       u32 r[8];
 #pragma unroll

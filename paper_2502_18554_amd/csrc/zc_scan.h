@@ -3,8 +3,9 @@
 // a block's position is the sum of the sizes before it), kept per segment of 64 blocks, the
 // share of one wave.
 //
-// stream_index_kernel records the payload size of every segment and the exclusive offset of
-// every scan group of 64 segments, and validates header and width bytes on the way.
+// stream_index_kernel records the offset of every segment inside its scan group of 64
+// segments and the exclusive offset of every scan group, and validates header and width
+// bytes on the way.
 #pragma once
 
 #include "zc_common.h"
@@ -55,22 +56,32 @@ struct ScanArgs {
   Control* ctl;
 };
 
-// Payload word offset of segment `seg` of stream `s`: the offset of its scan group plus the
-// sizes of the segments before it inside the group.  Called by all 64 lanes of a wave.
+// Payload word offset of segment `seg` of stream `s` (the same value in every lane).
 __device__ inline u64 segment_offset(const StreamIndex& ix, int s, u64 seg) {
-  const u64 g = seg / kScanGroupSegs;
-  const u32 r = u32(seg % kScanGroupSegs);
-  const u32* sums = ix.seg_sum + u64(s) * 4 * ix.tiles_cap + g * kScanGroupSegs;
-  const u32 mine = u32(lane_id()) < r ? sums[lane_id()] : 0u;
-  return u64(ix.grp_off[u64(s) * ix.groups_cap + g]) + wave_sum_u32(mine);
+  return u64(ix.grp_off[u64(s) * ix.groups_cap + seg / kScanGroupSegs]) +
+         u64(ix.seg_off[u64(s) * 4 * ix.tiles_cap + seg]);
 }
 
-// One workgroup per scan group of 4096 blocks (64 segments) and stream.  Each thread sums
-// the payload sizes of 16 blocks (one 16-byte load of the width table) and checks the width
-// bytes; four threads make a segment.  The workgroup that finishes last for a stream turns
-// the group sums into exclusive offsets and checks header total_bytes = tables + payload.
+// Payload words of the four blocks whose width bytes are packed in x, and whether any byte
+// exceeds 31.  Sum of (1 + w) over the non-zero bytes = byte sum + number of non-zero bytes.
+__device__ inline u32 psize_words4(u32 x, bool& bad) {
+  bad |= (x & 0xE0E0E0E0u) != 0;
+  const u32 nonzero = (((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x) & 0x80808080u;   // top bit of every non-zero byte
+  return __builtin_amdgcn_sad_u8(x, 0u, u32(__builtin_popcount(nonzero)));
+}
+
+// A workgroup covers kIndexGroups scan groups of 4096 blocks (64 segments) of one stream.
+// Each thread takes 16 blocks of a group (one 16-byte load of the width table), four threads
+// make a segment; a scan over the workgroup gives every segment its offset inside the group.
+// Few, fat workgroups keep the number of updates of the per-stream `done` counter small:
+// atomics on one address retire one after the other.  The workgroup that finishes last for a
+// stream turns the group sums into exclusive offsets and checks that the header's
+// total_bytes equals tables + payload.
+constexpr int kIndexGroups = 8;
+
 __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
-  __shared__ u32 sh_wave[4];
+  __shared__ u32 sh_wave[kIndexGroups][4];
+  __shared__ u32 sh_scan[4];
   __shared__ u32 sh_last;
   __shared__ u64 sh_carry;
   const int s = blockIdx.y;
@@ -90,45 +101,61 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
     }
   }
   if (num_tiles(h.nb) > a.index.tiles_cap || ngroups > a.index.groups_cap) return;
-  const u64 group = blockIdx.x;
-  if (group >= ngroups) return;
+  const u64 group0 = u64(blockIdx.x) * kIndexGroups;
+  if (group0 >= ngroups) return;
 
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
   const u8* widths = st.base + kHeaderBytes;
-  const u64 b0 = group * kScanGroupBlocks + u64(threadIdx.x) * 16;
-  u32 bytes[4] = {0, 0, 0, 0};
-  if (b0 + 16 <= h.nb) {
-    const uint4 v = *reinterpret_cast<const uint4*>(widths + b0);
-    bytes[0] = v.x; bytes[1] = v.y; bytes[2] = v.z; bytes[3] = v.w;
-  } else {
-    for (int i = 0; i < 16; ++i)
-      if (b0 + i < h.nb) bytes[i >> 2] |= u32(widths[b0 + i]) << (8 * (i & 3));
+  // all loads first: the table is padded to a multiple of 16 bytes, so a 16-byte load that
+  // starts below nb stays inside it; bytes of blocks that do not exist are masked off
+  uint4 v[kIndexGroups];
+#pragma unroll
+  for (int i = 0; i < kIndexGroups; ++i) {
+    const u64 b0 = (group0 + u64(i)) * kScanGroupBlocks + u64(threadIdx.x) * 16;
+    v[i] = make_uint4(0, 0, 0, 0);
+    if (b0 < h.nb) v[i] = *reinterpret_cast<const uint4*>(widths + b0);
   }
-  u32 sum = 0;
+  u32 sum[kIndexGroups], incl[kIndexGroups];
   bool bad = false;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const u32 w = (bytes[i >> 2] >> (8 * (i & 3))) & 0xffu;
-    bad |= w > 31;
-    sum += psize_words(w > 31 ? 0 : w);
+  for (int i = 0; i < kIndexGroups; ++i) {
+    const u64 b0 = (group0 + u64(i)) * kScanGroupBlocks + u64(threadIdx.x) * 16;
+    u32 x[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+    if (b0 < h.nb && b0 + 16 > h.nb) {
+      const u32 live = u32(h.nb - b0);                 // 1..15 bytes exist
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const u32 keep = live >= 4u * j + 4 ? 0xFFFFFFFFu : (live > 4u * j ? (1u << (8 * (live - 4u * j))) - 1u : 0u);
+        x[j] &= keep;
+      }
+    }
+    sum[i] = psize_words4(x[0], bad) + psize_words4(x[1], bad) + psize_words4(x[2], bad) + psize_words4(x[3], bad);
+    incl[i] = wave_inclusive_sum(sum[i]);
+    if (lane == 63) sh_wave[i][wave] = incl[i];
   }
   if (bad) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
-  // four threads = one segment of 64 blocks
-  u32 seg_total = sum + dpp_mov<kDppQuadSwap1>(sum);
-  seg_total += dpp_mov<kDppQuadSwap2>(seg_total);
-  const u64 seg = group * kScanGroupSegs + (threadIdx.x >> 2);
-  if ((threadIdx.x & 3) == 0 && seg < num_segments(h.nb))
-    a.index.seg_sum[u64(s) * 4 * a.index.tiles_cap + seg] = seg_total;
-  const u32 wave_total = wave_sum_u32(sum);
-  if (lane == 0) sh_wave[wave] = wave_total;
   __syncthreads();
   u32* grp = a.index.grp_off + u64(s) * a.index.groups_cap;
+  u32* seg_off = a.index.seg_off + u64(s) * 4 * a.index.tiles_cap;
+  const u64 nsegs = num_segments(h.nb);
+#pragma unroll
+  for (int i = 0; i < kIndexGroups; ++i) {
+    u32 before = 0, all = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const u32 t = sh_wave[i][j];
+      if (j < wave) before += t;
+      all += t;
+    }
+    const u64 seg = (group0 + u64(i)) * kScanGroupSegs + (threadIdx.x >> 2);
+    if ((threadIdx.x & 3) == 0 && seg < nsegs) seg_off[seg] = before + incl[i] - sum[i];
+    if (threadIdx.x == 0 && group0 + u64(i) < ngroups) desc32_store(grp + group0 + u64(i), all);
+  }
   if (threadIdx.x == 0) {
-    desc32_store(grp + group, sh_wave[0] + sh_wave[1] + sh_wave[2] + sh_wave[3]);
     __threadfence();
     const u32 finished = atomicAdd(&a.index.done[s], 1u);
-    sh_last = (finished + 1 == u32(ngroups));
+    sh_last = (u64(finished) + 1 == (ngroups + kIndexGroups - 1) / kIndexGroups);
   }
   __syncthreads();
   if (!sh_last) return;
@@ -139,19 +166,19 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
   __syncthreads();
   for (u64 start = 0; start < ngroups; start += 256) {
     const u64 i = start + threadIdx.x;
-    const u32 v = i < ngroups ? desc32_load(grp + i) : 0u;
-    const u32 incl = wave_inclusive_sum(v);
-    if (lane == 63) sh_wave[wave] = incl;
+    const u32 val = i < ngroups ? desc32_load(grp + i) : 0u;
+    const u32 inc = wave_inclusive_sum(val);
+    if (lane == 63) sh_scan[wave] = inc;
     __syncthreads();
     u32 before = 0, all = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const u32 t = sh_wave[j];
+      const u32 t = sh_scan[j];
       if (j < wave) before += t;
       all += t;
     }
     const u64 carry = sh_carry;
-    if (i < ngroups) grp[i] = u32(carry) + before + incl - v;
+    if (i < ngroups) grp[i] = u32(carry) + before + inc - val;
     __syncthreads();
     if (threadIdx.x == 0) sh_carry = carry + all;
     __syncthreads();
