@@ -181,18 +181,18 @@ int zc_compress(const float* d_in, size_t n, float abs_eb, void* d_out, size_t o
   if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
   const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
   const u64 nb = num_blocks(n);
-  const u64 ntiles = num_tiles(nb);
-  if (l.tiles_cap < 1 || ntiles > l.tiles_cap) return ZC_ERR_ARG;
+  const u64 ntiles = num_pack_tiles(nb);
+  if (l.tiles_cap < 1 || num_tiles(nb) > l.tiles_cap) return ZC_ERR_ARG;
   CompressArgs ca;
   fill_compress_args(ca, d_in, n, abs_eb, d_out, out_cap, l);
   launch_init(l, u32(ntiles), ca.out, out_cap, n, ca.eb_bits, stream);
-  const u32 full_tiles = u32(n / kTileValues);      // tiles whose 8192 values all exist
+  const u32 full_tiles = u32(n / kPackValues);      // tiles whose values all exist
   KernelTimer::Slot* slot = full_tiles ? g_timer.begin(ZC_KERNEL_COMPRESS, stream) : nullptr;
   if (full_tiles)
-    hipLaunchKernelGGL(compress_kernel<true>, dim3(full_tiles), dim3(kTileThreads), 0, stream, ca, 0u, full_tiles);
+    hipLaunchKernelGGL(compress_kernel<true>, dim3(full_tiles), dim3(kPackThreads), 0, stream, ca, 0u, full_tiles);
   g_timer.end(slot, stream);
   if (ntiles > full_tiles)                          // the ragged last tile
-    hipLaunchKernelGGL(compress_kernel<false>, dim3(1), dim3(kTileThreads), 0, stream, ca, full_tiles, u32(ntiles));
+    hipLaunchKernelGGL(compress_kernel<false>, dim3(1), dim3(kPackThreads), 0, stream, ca, full_tiles, u32(ntiles));
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);

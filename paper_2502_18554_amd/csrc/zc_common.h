@@ -48,10 +48,18 @@ struct Control {
   u32 status;                  // OR of status_bit()s
   u32 reserved;
   u64 result;                  // total_bytes, or n for decompress
-  u32 ticket[kTicketShards];   // tile hand-out counters, one per XCD (see take_tile)
-  u32 pad[4];
+  u32 pad[12];
 };
 static_assert(sizeof(Control) == 64, "control block is 64 bytes");
+
+// Tile hand-out counters, one per XCD (see take_tile), follow the control block.  Each sits
+// in a 128-byte line of its own: atomics on one line retire one after the other even when
+// they address different words of it.
+constexpr int kTicketStride = 32;            // in u32
+constexpr u64 kTicketBytes = u64(kTicketShards) * kTicketStride * 4;
+__host__ __device__ inline u32* ticket_counter(Control* ctl, u32 shard) {
+  return reinterpret_cast<u32*>(ctl + 1) + shard * kTicketStride;
+}
 
 // A segment is the 64 blocks owned by one wave; a tile is 4 segments.
 __host__ __device__ inline u64 num_segments(u64 nb) { return (nb + kWaveBlocks - 1) / kWaveBlocks; }
@@ -71,34 +79,35 @@ struct StreamIndex {
 };
 
 // How a workspace of ws_bytes is carved up for calls with k input streams:
-//   Control | done[ZC_MAX_K] | desc[tiles_cap] (u64) | seg_off[k][4 * tiles_cap] | grp_off[k][groups_cap]
+//   Control | tickets | done[ZC_MAX_K] | desc[tiles_cap] (128 B each) | seg_off[k][4 * tiles_cap] | grp_off[k][groups_cap]
 // tiles_cap follows from ws_bytes alone, so kernels can refuse streams that do not fit.
 struct WorkspaceLayout {
   u64 tiles_cap;
   Control* ctl;
-  u64* desc;        // look-back descriptors, one per tile
+  u64* desc;        // look-back descriptors, kDescStride words per tile
   StreamIndex index;
 };
 
-constexpr u64 kWsFixed = sizeof(Control) + 4 * ZC_MAX_K + 4 * ZC_MAX_K + 64;   // control, done[], the +1 of every grp_off row, padding
+constexpr u64 kDescBytes = 128;           // per tile, see kDescStride
+constexpr u64 kWsFixed = sizeof(Control) + kTicketBytes + 4 * ZC_MAX_K + 4 * ZC_MAX_K + 64;   // control, done[], the +1 of every grp_off row, padding
 
 __host__ inline u64 workspace_bytes(u64 n_max, int k_max) {
   if (k_max < 1) k_max = 1;
   const u64 t = num_tiles(num_blocks(n_max)) + 16;
-  return kWsFixed + t * (8 + 17 * u64(k_max));      // 17 = segment offsets (16) + the tile's share of the group offsets
+  return kWsFixed + t * (kDescBytes + 17 * u64(k_max));      // 17 = segment offsets (16) + the tile's share of the group offsets
 }
 
 __host__ inline WorkspaceLayout workspace_layout(void* d_ws, u64 ws_bytes, int k) {
   if (k < 1) k = 1;
   WorkspaceLayout l;
-  l.tiles_cap = ws_bytes > kWsFixed ? (ws_bytes - kWsFixed) / (8 + 17 * u64(k)) : 0;
+  l.tiles_cap = ws_bytes > kWsFixed ? (ws_bytes - kWsFixed) / (kDescBytes + 17 * u64(k)) : 0;
   u8* p = static_cast<u8*>(d_ws);
   l.ctl = reinterpret_cast<Control*>(p);
-  p += sizeof(Control);
+  p += sizeof(Control) + kTicketBytes;
   l.index.done = reinterpret_cast<u32*>(p);
   p += 4 * ZC_MAX_K;
   l.desc = reinterpret_cast<u64*>(p);
-  p += pad16(8 * l.tiles_cap);
+  p += kDescBytes * l.tiles_cap;
   l.index.seg_off = reinterpret_cast<u32*>(p);
   p += pad16(16 * l.tiles_cap * u64(k));
   l.index.grp_off = reinterpret_cast<u32*>(p);
@@ -142,7 +151,7 @@ __device__ inline u32 take_tile(Control* ctl, u32 ntiles, u32 first_shard) {
   for (u32 i = 0; i < u32(kTicketShards); ++i) {
     const u32 y = (first_shard + i) & (kTicketShards - 1);
     if (y >= ntiles) continue;
-    const u32 t = tile_of_ticket(y, atomicAdd(&ctl->ticket[y], 1u), ntiles);
+    const u32 t = tile_of_ticket(y, atomicAdd(ticket_counter(ctl, y), 1u), ntiles);
     if (t != kNoTile) return t;
   }
   return kNoTile;
@@ -214,6 +223,11 @@ constexpr u64 kDescAggregate = u64(1) << 62;
 constexpr u64 kDescPrefix = u64(2) << 62;
 constexpr u64 kDescValueMask = (u64(1) << 62) - 1;
 
+// Descriptors are polled by every tile in flight, so neighbours must not share a memory
+// line (polls of one line queue up behind each other): one descriptor per 128 bytes.
+constexpr int kDescStride = 16;            // in u64
+__host__ __device__ inline u64 desc_slot(u64 tile) { return tile * kDescStride; }
+
 __device__ inline void desc_store(u64* d, u64 v) {
   __hip_atomic_store(d, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -247,58 +261,40 @@ __device__ inline u32 desc32_load(const u32* d) {
 // Every tile below `tile` is in work on a resident workgroup (or done), and a workgroup
 // publishes its aggregate without waiting for anything, so the wait below ends; it is
 // bounded anyway and raises ZC_ERR_HIP in *status if the bound is hit.
-// One poll inspects kLookWindows x 64 descriptors (all loads in flight together).  The
-// prefix frontier advances by at most one poll's reach per memory round trip, and at this
-// kernel's rate (about 100 tiles per microsecond) a reach of 64 tiles cannot keep up.
-constexpr int kLookWindows = 1;
+// A poll inspects the 32 nearest predecessors: measured on the 512^3 benchmark, wider polls
+// only add memory requests without finishing earlier.
+constexpr int kLookLanes = 32;
 
 __device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status) {
   const int lane = lane_id();
+  const u64 lanes_mask = kLookLanes == 64 ? ~u64(0) : ((u64(1) << kLookLanes) - 1);
   u64 excl = 0;
-  i64 look = i64(tile) - 1;                  // lane 0 of window 0 inspects the nearest predecessor
+  i64 look = i64(tile) - 1;                  // lane 0 inspects the nearest predecessor
   u32 spins = 0;
   while (true) {
-    u64 d[kLookWindows];
-#pragma unroll
-    for (int e = 0; e < kLookWindows; ++e) {
-      const i64 idx = look - lane - 64 * e;
-      d[e] = idx >= 0 ? desc_load(desc + idx) : kDescPrefix;        // "tile -1" has prefix 0
-    }
-    bool retry = false, done = false;
-    u64 got = 0;
-    int used = 0;
-#pragma unroll
-    for (int e = 0; e < kLookWindows; ++e) {
-      if (!retry && !done) {
-        const u32 state = u32(d[e] >> 62);
-        const u64 has_prefix = __ballot(state == 2);
-        const u64 is_empty = __ballot(state == 0);
-        const int first = has_prefix ? __builtin_ctzll(has_prefix) : 63;
-        const u64 needed = first == 63 ? ~u64(0) : ((u64(2) << first) - 1);   // lanes 0..first
-        if (is_empty & needed) {
-          retry = true;      // keep what the complete windows before this one gave
-        } else {
-          // lanes before `first` hold tile aggregates (small); lane `first` may hold a prefix (64-bit)
-          got += wave_sum_u32(lane < first || (lane == first && !has_prefix) ? u32(d[e]) : 0u);
-          used = e + 1;
-          if (has_prefix) {
-            const u64 p = u64(lane_value(u32(d[e]), first)) | (u64(lane_value(u32(d[e] >> 32), first)) << 32);
-            got += p & kDescValueMask;
-            done = true;
-          }
-        }
-      }
-    }
-    excl += got;
-    if (done) return excl;
-    look -= 64 * used;       // complete windows are final: aggregates never change
-    if (retry) {
+    const i64 idx = look - lane;
+    u64 d = kDescPrefix;                     // "tile -1" has prefix 0
+    if (lane < kLookLanes && idx >= 0) d = desc_load(desc + desc_slot(u64(idx)));
+    const u32 state = u32(d >> 62);
+    const u64 has_prefix = __ballot(state == 2) & lanes_mask;
+    const u64 is_empty = __ballot(state == 0) & lanes_mask;
+    const int first = has_prefix ? __builtin_ctzll(has_prefix) : kLookLanes - 1;
+    const u64 needed = first == 63 ? ~u64(0) : ((u64(2) << first) - 1);   // lanes 0..first
+    if (is_empty & needed) {
       if (++spins > kSpinLimit) {
         if (lane == 0) atomicOr(status, status_bit(ZC_ERR_HIP));
         return excl;
       }
       __builtin_amdgcn_s_sleep(1);
+      continue;
     }
+    // lanes before `first` hold tile aggregates (small); lane `first` may hold a prefix (64-bit)
+    excl += wave_sum_u32(lane < first || (lane == first && !has_prefix) ? u32(d) : 0u);
+    if (has_prefix) {
+      const u64 p = u64(lane_value(u32(d), first)) | (u64(lane_value(u32(d >> 32), first)) << 32);
+      return excl + (p & kDescValueMask);
+    }
+    look -= kLookLanes;                      // a complete window is final: aggregates never change
   }
 }
 

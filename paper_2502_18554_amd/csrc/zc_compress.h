@@ -1,8 +1,8 @@
 // fZ-light compression kernel (Section 3.3): quantise, per-block Lorenzo delta, code length,
 // sign + plane packing, single-pass placement of the variable-size blocks.
 //
-// Work split.  A tile is 256 blocks (8192 values, 32 KiB of input) handled by a workgroup of
-// 4 waves.  Each wave loads 2048 consecutive values with 16-byte loads,
+// Work split.  A tile is 512 blocks (16384 values, 64 KiB of input) handled by a workgroup of
+// 8 waves.  Each wave loads 2048 consecutive values with 16-byte loads,
 // quantises them where they land, and transposes the integer codes through LDS so that one
 // lane owns one block.  Delta, width and the bit-matrix transpose that yields the plane
 // words are then in-lane; the packed words wait in registers for the tile's base offset
@@ -16,6 +16,16 @@
 #include "zc_common.h"
 
 namespace zc {
+
+// A scan tile of the compression kernel: the blocks of one workgroup, one descriptor of the
+// look-back scan.  Every tile pays the latency of that scan once, so compression uses tiles
+// twice the size of the other kernels' tiles (512 blocks, 64 KiB of input); 1024 blocks
+// measured slower, because a compute unit then holds a single workgroup.
+constexpr int kPackWaves = 8;
+constexpr int kPackThreads = kPackWaves * 64;
+constexpr int kPackBlocks = kPackWaves * kWaveBlocks;
+constexpr int kPackValues = kPackBlocks * kBlockValues;
+__host__ __device__ inline u64 num_pack_tiles(u64 nb) { return (nb + kPackBlocks - 1) / kPackBlocks; }
 
 struct CompressArgs {
   const float* in;
@@ -179,12 +189,10 @@ struct Placement {
 template <bool FULL, int NW, typename WordFn>
 __device__ inline void finish_tile(const CompressArgs& a, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
                                    u32* wl, u64* sh_base, int wave, int lane) {
-  if (threadIdx.x == 0)
-    desc_store(a.desc + tile, (tile == 0 ? kDescPrefix : kDescAggregate) | u64(pl.tile_total));
   if (wave == 0) {
     const u64 base = tile ? lookback_exclusive(a.desc, tile, &a.ctl->status) : 0;
     if (lane == 0) {
-      if (tile) desc_store(a.desc + tile, kDescPrefix | (base + pl.tile_total));
+      if (tile) desc_store(a.desc + desc_slot(tile), kDescPrefix | (base + pl.tile_total));
       *sh_base = base;
     }
   }
@@ -215,16 +223,16 @@ __device__ inline void finish_tile(const CompressArgs& a, WordFn word, const Pla
 // 16-byte loads, no tail), handed out by the per-XCD tickets over [first_tile, end_tile); the
 // ragged last tile of an input runs as a second launch of one workgroup with FULL = false.
 template <bool FULL>
-__global__ __launch_bounds__(kTileThreads, 4) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
-  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
+__global__ __launch_bounds__(kPackThreads, 16 / kPackWaves) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kPackWaves * kWaveStage];
   __shared__ u32 sh_tile;
-  __shared__ u32 sh_wave_total[kTileWaves];
-  __shared__ u32 sh_wave_wmax[kTileWaves];
+  __shared__ u32 sh_wave_total[kPackWaves];
+  __shared__ u32 sh_wave_wmax[kPackWaves];
   __shared__ u64 sh_base;
 
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
-  const u32 ntiles = u32(num_tiles(a.nb));
+  const u32 ntiles = u32(num_pack_tiles(a.nb));
   u32* const wl = lds + wave * kWaveStage;
   const bool tables_fit = a.out_cap >= tables_end(a.nb);
   u32 err = 0;
@@ -237,7 +245,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void compress_kernel(CompressArgs 
     if (tile == kNoTile) return;
   }
   {
-    const u64 wblock0 = u64(tile) * kTileBlocks + u64(wave) * kWaveBlocks;
+    const u64 wblock0 = u64(tile) * kPackBlocks + u64(wave) * kWaveBlocks;
     const u64 b = wblock0 + u64(lane);
     const bool active = b < a.nb;
     float4 x[8];
@@ -271,13 +279,16 @@ __global__ __launch_bounds__(kTileThreads, 4) void compress_kernel(CompressArgs 
     pl.tile_total = 0;
     u32 tile_wmax = 0;
 #pragma unroll
-    for (int i = 0; i < kTileWaves; ++i) {
+    for (int i = 0; i < kPackWaves; ++i) {
       const u32 t = sh_wave_total[i];
       if (i < wave) pl.wave_off += t;
       pl.tile_total += t;
       tile_wmax = tile_wmax > sh_wave_wmax[i] ? tile_wmax : sh_wave_wmax[i];
     }
     tile_wmax = uniform(tile_wmax);
+    // publish the tile's size as early as possible: the tiles after this one wait for it
+    if (threadIdx.x == 0)
+      desc_store(a.desc + desc_slot(tile), (tile == 0 ? kDescPrefix : kDescAggregate) | u64(pl.tile_total));
 
     // ---- deltas -> sign + plane words in registers, then the back half ----
     // (the empty asm keeps the compiler from hoisting the sign-magnitude split of all 32
@@ -338,10 +349,10 @@ struct InitArgs {
 __global__ void init_kernel(InitArgs a) {
   const u64 gid = u64(blockIdx.x) * blockDim.x + threadIdx.x;
   const u64 stride = u64(gridDim.x) * blockDim.x;
-  for (u64 i = gid; i < a.ntiles; i += stride) a.desc[i] = 0;
+  for (u64 i = gid; i < a.ntiles; i += stride) a.desc[desc_slot(i)] = 0;
   if (gid < ZC_MAX_K) a.done[gid] = 0;
   if (gid == 0) {
-    for (int i = 0; i < kTicketShards; ++i) a.ctl->ticket[i] = 0;
+    for (int i = 0; i < kTicketShards; ++i) *ticket_counter(a.ctl, u32(i)) = 0;
     a.ctl->status = 0;
     a.ctl->result = 0;
     if (a.out) {

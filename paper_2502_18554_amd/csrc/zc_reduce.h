@@ -217,7 +217,7 @@ __global__ __launch_bounds__(kTileThreads) void reduce_kernel(ReduceArgs a) {
     if (i < wave) wave_off += t;
     tile_total += t;
   }
-  if (threadIdx.x == 0) desc_store(a.desc + tile, (tile == 0 ? kDescPrefix : kDescAggregate) | u64(tile_total));
+  if (threadIdx.x == 0) desc_store(a.desc + desc_slot(tile), (tile == 0 ? kDescPrefix : kDescAggregate) | u64(tile_total));
 
   if (w) wl[off_in_wave] = ext;
   store_sum_planes<0>(acc, w, wmax, wl + off_in_wave);
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(kTileThreads) void reduce_kernel(ReduceArgs a) {
   if (wave == 0) {
     const u64 base = tile ? lookback_exclusive(a.desc, tile, &a.ctl->status) : 0;
     if (lane == 0) {
-      if (tile) desc_store(a.desc + tile, kDescPrefix | (base + tile_total));
+      if (tile) desc_store(a.desc + desc_slot(tile), kDescPrefix | (base + tile_total));
       sh_base = base;
     }
   }
