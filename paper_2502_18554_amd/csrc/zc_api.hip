@@ -273,10 +273,16 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_REDUCE, stream);
   hipLaunchKernelGGL(reduce_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
   g_timer.end(slot, stream);
+  // for operands with blocks wider than 15 bits; returns at once otherwise
+  hipLaunchKernelGGL(reduce_wide_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
 }
+
+#ifdef ZC_REC
+int zc_set_rec(void* p) { return hipMemcpyToSymbol(HIP_SYMBOL(g_rec), &p, sizeof(p)) == hipSuccess ? 0 : 8; }
+#endif
 
 int zc_profile_enable(int on) {
   std::lock_guard<std::mutex> g(g_timer.mu);

@@ -16,6 +16,13 @@ using u64 = uint64_t;
 using i32 = int32_t;
 using i64 = int64_t;
 
+#ifdef ZC_REC
+__device__ u64* g_rec;
+#define REC(tile, i) do { if (threadIdx.x == 0 && g_rec) g_rec[u64(tile) * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define REC(tile, i) do {} while (0)
+#endif
+
 constexpr u32 kMagic = 0x314C435Au;
 constexpr u32 kHeaderBytes = 32;
 constexpr int kBlockValues = 32;           // values per block (Section 3.3 "small blocks")
@@ -24,8 +31,6 @@ constexpr int kTileWaves = 4;
 constexpr int kTileThreads = kTileWaves * 64;
 constexpr int kTileBlocks = kTileWaves * kWaveBlocks;        // 256 blocks
 constexpr int kTileValues = kTileBlocks * kBlockValues;      // 8192 values = 32 KiB of input
-constexpr int kRow = 36;                   // LDS row stride in words (32 + 4: conflict-free 128-bit access)
-constexpr int kWaveLds = kWaveBlocks * kRow;                 // words of LDS per wave
 constexpr i64 kMaxCode = (i64(1) << 30) - 1;
 constexpr u32 kSpinLimit = 1u << 20;       // bound on every look-back wait
 
@@ -46,19 +51,20 @@ constexpr u32 kGateBits = status_bit(ZC_ERR_ARG) | status_bit(ZC_ERR_FORMAT) | s
 constexpr int kTicketShards = 8;
 struct Control {
   u32 status;                  // OR of status_bit()s
-  u32 reserved;
+  u32 flags;                   // kFlagWide: some input stream has a block wider than 15 bits
   u64 result;                  // total_bytes, or n for decompress
   u32 pad[12];
 };
 static_assert(sizeof(Control) == 64, "control block is 64 bytes");
 
 // Tile hand-out counters, one per XCD (see take_tile), follow the control block.  Each sits
-// in a 128-byte line of its own: atomics on one line retire one after the other even when
-// they address different words of it.
+// in a 128-byte line of its own, and none shares the line of the control block: accesses to
+// one line retire one after the other even when they address different words of it, and every
+// workgroup reads the control block when it starts.
 constexpr int kTicketStride = 32;            // in u32
-constexpr u64 kTicketBytes = u64(kTicketShards) * kTicketStride * 4;
+constexpr u64 kTicketBytes = u64(kTicketShards + 1) * kTicketStride * 4;
 __host__ __device__ inline u32* ticket_counter(Control* ctl, u32 shard) {
-  return reinterpret_cast<u32*>(ctl + 1) + shard * kTicketStride;
+  return reinterpret_cast<u32*>(ctl + 1) + (shard + 1) * kTicketStride;
 }
 
 // A segment is the 64 blocks owned by one wave; a tile is 4 segments.
@@ -121,9 +127,13 @@ __host__ inline WorkspaceLayout workspace_layout(void* d_ws, u64 ws_bytes, int k
 // ---------------------------------------------------------------------------------------
 __device__ inline int lane_id() { return int(threadIdx.x) & 63; }
 
+constexpr u32 kFlagWide = 1u;
+// (flags and the gate bits of status are final before a main kernel starts: plain loads)
+__device__ inline bool streams_are_wide(const Control* ctl) { return (ctl->flags & kFlagWide) != 0; }
+
 // True when validation failed and the main kernel must not touch the stream.
 __device__ inline bool validation_failed(const Control* ctl) {
-  return (__hip_atomic_load(&ctl->status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kGateBits) != 0;
+  return (ctl->status & kGateBits) != 0;
 }
 
 // Tile hand-out.  One atomic counter would serialise the whole kernel: atomics on one

@@ -9,11 +9,9 @@
 // from the look-back scan and leave through LDS as coalesced stores.
 #pragma once
 
-#include <type_traits>
-#include <utility>
-
 #include "zc_bitmatrix.h"
 #include "zc_common.h"
+#include "zc_place.h"
 
 namespace zc {
 
@@ -93,25 +91,6 @@ __device__ inline int4 quantize4(const float4& x, const CompressArgs& a, bool ch
   return q;
 }
 
-// Writes the payload words of the lanes of one half-wave to the wave's staging area and copies
-// them out with coalesced stores.  Word 0 is the sign word, word 1 + p is plane p; `word(i)`
-// yields word i from registers and is only ever called with compile-time constants.
-template <int NW, typename WordFn>
-__device__ inline void stage_and_copy_half(WordFn word, u32 w, u32 wmax, bool in_half, u32 off_in_half,
-                                           u32 half_total, u32* wl, u32* dst, u64 dst_room, int lane) {
-  if (in_half && w) {
-    wl[off_in_half] = word(std::integral_constant<int, 0>{});
-    [&]<int... P>(std::integer_sequence<int, P...>) {
-      ((u32(P) < w ? void(wl[off_in_half + 1 + P] = word(std::integral_constant<int, 1 + P>{})) : void()), ...);
-    }(std::make_integer_sequence<int, NW - 1>{});
-  }
-  (void)wmax;
-  wave_lds_sync();
-  for (u32 i = u32(lane); i < half_total; i += 64)
-    if (i < dst_room) dst[i] = wl[i];
-  wave_lds_sync();
-}
-
 // Raw input of one wave's share of a tile: 8 x 16 bytes per lane, every load in flight at once.
 template <bool FULL>
 __device__ inline void load_raw(const CompressArgs& a, u64 wblock0, int lane, float4 (&x)[8]) {
@@ -173,50 +152,6 @@ __device__ inline i32 block_deltas(const CompressArgs& a, const float4 (&x)[8], 
 #pragma unroll
   for (int j = 1; j < 32; ++j) d[j] = q[j] - q[j - 1];
   return q[0];
-}
-
-// Per-wave view of where its payload goes.
-struct Placement {
-  u32 w, wmax;              // this block's width; the widest of the wave
-  u32 off_in_wave;          // payload word offset of this block inside the wave
-  u32 half0_total, wave_total;
-  u32 wave_off, tile_total; // the wave inside the tile; payload words of the tile
-};
-
-// Back half of a tile once the plane words sit in registers (`word(i)`: 0 = sign, 1 + p =
-// plane p): publish the tile's size, look back for the base offset, then move the payload out
-// through LDS.  Called by all four waves; one barrier.
-template <bool FULL, int NW, typename WordFn>
-__device__ inline void finish_tile(const CompressArgs& a, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
-                                   u32* wl, u64* sh_base, int wave, int lane) {
-  if (wave == 0) {
-    const u64 base = tile ? lookback_exclusive(a.desc, tile, &a.ctl->status) : 0;
-    if (lane == 0) {
-      if (tile) desc_store(a.desc + desc_slot(tile), kDescPrefix | (base + pl.tile_total));
-      *sh_base = base;
-    }
-  }
-  __syncthreads();
-
-  const u64 base = *sh_base;
-  const u64 tend = tables_end(a.nb);
-  const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
-  u32* const payload = reinterpret_cast<u32*>(a.out + tend);
-  const u64 dst0 = base + pl.wave_off;
-  const u32 half_base[2] = {0u, pl.half0_total};
-  const u32 half_total[2] = {pl.half0_total, pl.wave_total - pl.half0_total};
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const u64 d0 = dst0 + half_base[h];
-    stage_and_copy_half<NW>(word, pl.w, pl.wmax, (lane >> 5) == h, pl.off_in_wave - half_base[h], half_total[h], wl,
-                            payload + d0, cap_words > d0 ? cap_words - d0 : 0, lane);
-  }
-  if (tile == ntiles - 1 && threadIdx.x == 0) {
-    const u64 total = tend + 4 * (base + pl.tile_total);
-    a.ctl->result = total;
-    if (total > a.out_cap) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
-    if (a.out_cap >= kHeaderBytes) reinterpret_cast<u64*>(a.out)[3] = total;
-  }
 }
 
 // One workgroup per tile.  FULL = the launch covers tiles whose 8192 values all exist (pure
@@ -287,8 +222,8 @@ __global__ __launch_bounds__(kPackThreads, 16 / kPackWaves) void compress_kernel
     }
     tile_wmax = uniform(tile_wmax);
     // publish the tile's size as early as possible: the tiles after this one wait for it
-    if (threadIdx.x == 0)
-      desc_store(a.desc + desc_slot(tile), (tile == 0 ? kDescPrefix : kDescAggregate) | u64(pl.tile_total));
+    const PayloadSink sink{a.out, a.out_cap, a.nb, a.ctl, a.desc};
+    if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total);
 
     // ---- deltas -> sign + plane words in registers, then the back half ----
     // (the empty asm keeps the compiler from hoisting the sign-magnitude split of all 32
@@ -314,7 +249,7 @@ __global__ __launch_bounds__(kPackThreads, 16 / kPackWaves) void compress_kernel
 #pragma unroll
         for (int p = 0; p < 15; ++p) pw[1 + p] = r[p];
       }
-      finish_tile<FULL, 16>(a, [&](auto i) { return pw[decltype(i)::value]; }, pl, tile, ntiles, wl, &sh_base, wave, lane);
+      finish_tile<16>(sink, [&](auto i) { return pw[decltype(i)::value]; }, pl, tile, ntiles, wl, &sh_base, wave, lane);
     } else {
       // a tile with a block wider than 15 bits (input outside the guaranteed domain): all planes
       u32 lo[16], hi[16];
@@ -327,7 +262,7 @@ __global__ __launch_bounds__(kPackThreads, 16 / kPackWaves) void compress_kernel
         else if constexpr (I <= 16) return lo[I - 1];
         else return hi[I - 17];
       };
-      finish_tile<FULL, 32>(a, word, pl, tile, ntiles, wl, &sh_base, wave, lane);
+      finish_tile<32>(sink, word, pl, tile, ntiles, wl, &sh_base, wave, lane);
     }
   }
   if (err) atomicOr(&a.ctl->status, err);
@@ -354,6 +289,7 @@ __global__ void init_kernel(InitArgs a) {
   if (gid == 0) {
     for (int i = 0; i < kTicketShards; ++i) *ticket_counter(a.ctl, u32(i)) = 0;
     a.ctl->status = 0;
+    a.ctl->flags = 0;
     a.ctl->result = 0;
     if (a.out) {
       const u64 tend = tables_end(a.nb);

@@ -1,0 +1,104 @@
+// Placement of a tile's variable-size payload in the output stream, shared by the kernels
+// that write streams (compression and the fused reduce): the tile publishes its size, looks
+// back for its base offset (the exclusive sum of the sizes of all tiles before it, in block
+// order), and copies its packed words out through LDS as coalesced stores.
+#pragma once
+
+#include <type_traits>
+#include <utility>
+
+#include "zc_common.h"
+
+namespace zc {
+
+// The stream being written.
+struct PayloadSink {
+  u8* out;          // stream base
+  u64 out_cap;      // bytes
+  u64 nb;           // blocks of the stream
+  Control* ctl;
+  u64* desc;        // look-back descriptors
+};
+
+// Per-wave view of where its payload goes.
+struct Placement {
+  u32 w, wmax;              // this block's width; the widest of the wave
+  u32 off_in_wave;          // payload word offset of this block inside the wave
+  u32 half0_total, wave_total;
+  u32 wave_off, tile_total; // the wave inside the tile; payload words of the tile
+};
+
+// Writes the payload words of the lanes of one half-wave to the wave's staging area and copies
+// them out with coalesced stores.  Word 0 is the sign word, word 1 + p is plane p; `word(i)`
+// yields word i from registers and is only ever called with compile-time constants.
+// half_total <= 32 * NW.
+template <int NW, typename WordFn>
+__device__ inline void stage_and_copy_half(WordFn word, u32 w, bool in_half, u32 off_in_half, u32 half_total,
+                                           u32* wl, u32* dst, u64 dst_room, int lane) {
+  if (in_half && w) {
+    wl[off_in_half] = word(std::integral_constant<int, 0>{});
+    [&]<int... P>(std::integer_sequence<int, P...>) {
+      ((u32(P) < w ? void(wl[off_in_half + 1 + P] = word(std::integral_constant<int, 1 + P>{})) : void()), ...);
+    }(std::make_integer_sequence<int, NW - 1>{});
+  }
+  wave_lds_sync();
+  const u32 limit = u64(half_total) < dst_room ? half_total : u32(dst_room);
+#pragma unroll
+  for (int r = 0; r < NW / 2; ++r) {
+    const u32 i = u32(lane) + 64u * u32(r);
+    if (64u * u32(r) >= limit) break;          // uniform
+    if (i < limit) dst[i] = wl[i];
+  }
+  wave_lds_sync();
+}
+
+// Publishes the tile's payload size; called by one thread as soon as the size is known,
+// because the tiles after this one wait for it.
+__device__ inline void publish_tile_size(const PayloadSink& s, u32 tile, u32 tile_total) {
+  desc_store(s.desc + desc_slot(tile), (tile == 0 ? kDescPrefix : kDescAggregate) | u64(tile_total));
+}
+
+// Back half of a tile once the plane words sit in registers (`word(i)`: 0 = sign, 1 + p =
+// plane p) and its size is published: look back for the base offset, then move the payload
+// out through LDS, one half-wave of blocks at a time (the staging area `wl` of a wave holds
+// kWaveStage words).  Called by every wave of the workgroup; one barrier.
+template <int NW, typename WordFn>
+__device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
+                                   u32* wl, u64* sh_base, int wave, int lane) {
+  static_assert(32 * NW <= kWaveStage, "a half-wave of widest blocks must fit the staging area");
+  if (wave == 0) {
+#ifdef ZC_ABL_NOLOOK
+    const u64 base = u64(tile) * 3000;
+#else
+    const u64 base = tile ? lookback_exclusive(s.desc, tile, &s.ctl->status) : 0;
+#endif
+    if (lane == 0) {
+      if (tile) desc_store(s.desc + desc_slot(tile), kDescPrefix | (base + pl.tile_total));
+      *sh_base = base;
+    }
+  }
+  __syncthreads();
+  REC(tile, 5);
+
+  const u64 base = *sh_base;
+  const u64 tend = tables_end(s.nb);
+  const u64 cap_words = s.out_cap > tend ? (s.out_cap - tend) / 4 : 0;
+  u32* const payload = reinterpret_cast<u32*>(s.out + tend);
+  const u64 dst0 = base + pl.wave_off;
+  const u32 half_base[2] = {0u, pl.half0_total};
+  const u32 half_total[2] = {pl.half0_total, pl.wave_total - pl.half0_total};
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const u64 d0 = dst0 + half_base[h];
+    stage_and_copy_half<NW>(word, pl.w, (lane >> 5) == h, pl.off_in_wave - half_base[h], half_total[h], wl,
+                            payload + d0, cap_words > d0 ? cap_words - d0 : 0, lane);
+  }
+  if (tile == ntiles - 1 && threadIdx.x == 0) {
+    const u64 total = tend + 4 * (base + pl.tile_total);
+    s.ctl->result = total;
+    if (total > s.out_cap) atomicOr(&s.ctl->status, status_bit(ZC_ERR_CAPACITY));
+    if (s.out_cap >= kHeaderBytes) reinterpret_cast<u64*>(s.out)[3] = total;
+  }
+}
+
+}  // namespace zc

@@ -6,18 +6,24 @@
 // be dequantised, and no prefix sum is needed.  More than that, the deltas never have to leave
 // their bit-plane form.  One lane owns one block; a plane word holds one bit of each of the
 // block's 32 deltas, so a ripple-carry adder written with bitwise operations on plane words
-// adds 32 deltas at once: about four operations per plane per operand for the whole block.
+// adds 32 deltas at once: a handful of operations per plane per operand for the whole block.
 // The sum is kept in two's complement planes, converted back to sign + magnitude planes at
 // the end, and its highest non-zero plane gives the new code length.  Output placement is
 // the same ticketed look-back scan as in compression.
+//
+// Two kernels share this scheme.  reduce_kernel serves streams whose blocks are all at most
+// 15 bits wide (every stream of an input inside the guaranteed domain of a sensible bound):
+// a wave's payload of one operand is then at most 1024 words, is brought into LDS with
+// 16-byte loads, and the loads of the next operand fly while the current one is added.
+// reduce_wide_kernel takes any widths with per-lane loads.  The stream index records whether
+// any operand has a wider block; each kernel returns at once when the streams are not its.
 #pragma once
 
 #include "zc_common.h"
+#include "zc_place.h"
 #include "zc_scan.h"
 
 namespace zc {
-
-constexpr int kAccPlanes = 39;   // |sum of 64 deltas| < 2^37: 38 magnitude bits + sign
 
 struct ReduceArgs {
   StreamRef in[ZC_MAX_K];
@@ -28,6 +34,376 @@ struct ReduceArgs {
   Control* ctl;
   u64* desc;
 };
+
+// Header fields and table padding of the output stream; one thread.
+__device__ inline void write_reduce_header(const ReduceArgs& a, const ParsedHeader& h, u32 ntiles) {
+  const u64 tend = tables_end(h.nb);
+  u64 nsum = 0;
+  for (int s = 0; s < a.k; ++s) nsum += parse_header(a.in[s]).nsum;
+  if (nsum > 0xffffffffull) atomicOr(&a.ctl->status, status_bit(ZC_ERR_RANGE));
+  if (a.out_cap >= tend) {
+    u32* hw = reinterpret_cast<u32*>(a.out);
+    hw[0] = kMagic;
+    hw[1] = 1u | (5u << 16) | (6u << 24);
+    hw[2] = u32(h.n);
+    hw[3] = u32(h.n >> 32);
+    hw[4] = h.eb_bits;
+    hw[5] = u32(nsum);
+    if (ntiles == 0) {
+      hw[6] = u32(tend);
+      hw[7] = u32(tend >> 32);
+    }
+    for (u64 i = h.nb; i < pad16(h.nb); ++i) a.out[kHeaderBytes + i] = 0;
+    u8* ot = a.out + kHeaderBytes + pad16(h.nb);
+    for (u64 i = 4 * h.nb; i < pad16(4 * h.nb); ++i) ot[i] = 0;
+  } else {
+    atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
+  }
+  if (ntiles == 0) a.ctl->result = tend;
+}
+
+// Exact range check of one block's summed codes, for lanes whose cheap bound did not settle
+// it: rebuild every delta from the magnitude planes and walk the Lorenzo chain in 64 bits.
+template <int NP>
+__device__ inline bool block_out_of_range(const u32 (&mag)[NP], u32 sign, i64 outlier) {
+  i64 q = outlier;
+  bool bad = q > kMaxCode || q < -kMaxCode;
+  for (int j = 1; j < 32; ++j) {
+    i64 m = 0;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) m |= i64((mag[p] >> j) & 1u) << p;
+    q += ((sign >> j) & 1u) ? -m : m;
+    bad |= q > kMaxCode || q < -kMaxCode;
+  }
+  return bad;
+}
+
+// Range screen and placement of a summed block inside its wave and tile, then the shared
+// back half.  mag[0..NP) = magnitude planes, sign = sign word, w = highest non-zero plane + 1;
+// `word(i)` hands out the sign word (i = 0) and plane i - 1, for at most NW words.
+template <int NW, int NP, typename WordFn>
+__device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, const u32 (&mag)[NP], u32 sign, u32 w,
+                                 i64 outlier, bool active, u64 b, u32 tile, u32 ntiles, WordFn word, u32* wl,
+                                 u32* sh_wave_total, u64* sh_base, int wave, int lane) {
+  const u64 tend = tables_end(h.nb);
+  if (!active) w = 0;
+  u32 err = 0;
+  if (active) {
+    const i64 ao = outlier < 0 ? -outlier : outlier;
+    const i64 reach = ao + 31 * ((i64(1) << w) - 1);
+    if (reach > kMaxCode || w > 31) {
+      if (w > 31 || block_out_of_range(mag, sign, outlier)) {
+        err |= status_bit(ZC_ERR_RANGE);
+        w = 0;
+      }
+    }
+  }
+  Placement pl;
+  pl.w = w;
+  pl.wmax = wave_max_u32(w);
+  const u32 words = psize_words(w);
+  const u32 incl = wave_inclusive_sum(words);
+  pl.wave_total = lane_value(incl, 63);
+  pl.half0_total = lane_value(incl, 31);
+  pl.off_in_wave = incl - words;
+  if (lane == 0) sh_wave_total[wave] = pl.wave_total;
+  if (active && a.out_cap >= tend) {
+    a.out[kHeaderBytes + b] = u8(w);
+    reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(h.nb))[b] = i32(outlier);
+  }
+  __syncthreads();
+  pl.wave_off = 0;
+  pl.tile_total = 0;
+#pragma unroll
+  for (int i = 0; i < kTileWaves; ++i) {
+    const u32 t = sh_wave_total[i];
+    if (i < wave) pl.wave_off += t;
+    pl.tile_total += t;
+  }
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc};
+  if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total);
+  REC(tile, 4);
+  if (err) atomicOr(&a.ctl->status, err);
+  finish_tile<NW>(sink, word, pl, tile, ntiles, wl, sh_base, wave, lane);
+  REC(tile, 6);
+}
+
+// ---------------------------------------------------------------------------------------
+// Streams without blocks wider than 15 bits.
+// ---------------------------------------------------------------------------------------
+
+// The accumulator: 24 two's complement planes hold the sum of up to 64 deltas below 2^16 in
+// magnitude.  Planes [0, top) are valid, top a multiple of 4 and wave-uniform; plane top - 1
+// is a copy of the sign plane.
+constexpr int kSumPlanes = 24;
+constexpr int kSumChunk = 4;
+#ifndef ZC_RED_OCC
+#define ZC_RED_OCC 5
+#endif
+
+// What a wave needs to know about one operand's share: loaded two operands ahead.
+struct OperandMeta {
+  u32 w;            // this lane's block width
+  i32 outlier;
+  u64 seg_off;      // payload word offset of the wave's segment (uniform)
+  u64 payload_words;
+};
+
+// ... and after the scan of the widths: one operand ahead.
+struct OperandPlace {
+  u32 w;            // this lane's block width (0 if the block must be skipped)
+  u32 pick;         // LDS word index of this lane's sign word
+  u32 wcap;         // uniform: 0 (nothing to add), 4, 8, 12 or 16: at least the widest block of the wave
+  u32 span;         // uniform: words the wave stages, from the aligned start
+  u64 src0;         // uniform: payload word index of the aligned start
+  u64 payload_words;
+};
+
+__device__ inline OperandMeta load_operand_meta(const ReduceArgs& a, int s, const ParsedHeader& h, u64 seg, u64 b,
+                                                bool active, bool seg_live) {
+  OperandMeta m;
+  const u8* base = a.in[s].base;
+  const u64 total_s = reinterpret_cast<const u64*>(base)[3];
+  m.payload_words = (total_s - tables_end(h.nb)) / 4;
+  m.w = active ? u32(base[kHeaderBytes + b]) : 0u;
+  m.outlier = active ? reinterpret_cast<const i32*>(base + kHeaderBytes + pad16(h.nb))[b] : 0;
+  m.seg_off = seg_live ? segment_offset(a.index, s, seg) : 0;
+  return m;
+}
+
+__device__ inline OperandPlace place_operand(const OperandMeta& m) {
+  OperandPlace p;
+  const u32 w = m.w > 15 ? 0u : m.w;           // cannot happen here; keeps every LDS access in range
+  const u32 words = psize_words(w);
+  const u32 incl = wave_inclusive_sum(words);
+  const u32 wave_total = lane_value(incl, 63);
+  const bool inside = m.seg_off + wave_total <= m.payload_words;   // true on a validated stream
+  const u32 mis = u32(m.seg_off) & 3u;
+  p.src0 = m.seg_off - mis;
+  p.span = inside ? mis + wave_total : 0u;     // <= 3 + 64 * 16
+  p.pick = mis + (incl - words);
+  p.w = inside ? w : 0u;
+  p.payload_words = m.payload_words;
+  p.wcap = __any(p.w > 12) ? 16u : __any(p.w > 8) ? 12u : __any(p.w > 4) ? 8u : __any(p.w != 0) ? 4u : 0u;
+  return p;
+}
+
+// The operand's payload for this wave: 16 bytes per lane and load, all in flight together.
+// The copy starts at the 16-byte boundary at or below the segment (the payload area itself is
+// 16-byte aligned) and keeps that misalignment in LDS.
+struct OperandStage {
+  uint4 v[5];
+};
+
+__device__ inline OperandStage load_operand_payload(const u32* payload, const OperandPlace& p, int lane) {
+  OperandStage st;
+#pragma unroll
+  for (int i = 0; i < 5; ++i) {
+    const u32 idx = 4u * u32(lane) + 256u * u32(i);
+    st.v[i] = make_uint4(0, 0, 0, 0);
+    if (idx < p.span) {
+      if (p.src0 + idx + 4 <= p.payload_words) {
+        st.v[i] = *reinterpret_cast<const uint4*>(payload + p.src0 + idx);
+      } else {                                     // the last words of the stream
+        const u64 left = p.payload_words - (p.src0 + idx);
+        st.v[i].x = payload[p.src0 + idx];
+        if (left > 1) st.v[i].y = payload[p.src0 + idx + 1];
+        if (left > 2) st.v[i].z = payload[p.src0 + idx + 2];
+      }
+    }
+  }
+  return st;
+}
+
+__device__ inline void stage_to_lds(const OperandStage& st, const OperandPlace& p, u32* wl, int lane) {
+#pragma unroll
+  for (int i = 0; i < 5; ++i) {
+    const u32 idx = 4u * u32(lane) + 256u * u32(i);
+    if (idx < p.span) *reinterpret_cast<uint4*>(wl + idx) = st.v[i];
+  }
+}
+
+// acc += operand, planes [4C, 4C + 4).  DATA: the operand has magnitude planes here, read
+// from LDS (`mine` points at the lane's sign word) and masked by the block's own width;
+// otherwise the operand only contributes its sign extension.
+template <int C, bool DATA>
+__device__ inline void add_chunk(u32 (&acc)[kSumPlanes], const u32* mine, u32 w, u32 sgn, u32& carry) {
+#pragma unroll
+  for (int i = 0; i < kSumChunk; ++i) {
+    constexpr int kFirst = C * kSumChunk;
+    const int P = kFirst + i;
+    u32 x = sgn;                                  // two's complement of the operand: (mag ^ s) + s
+    if (DATA) {
+      const u32 plane = mine[1 + P];
+      x ^= u32(P) < w ? plane : 0u;
+    }
+    const u32 cur = acc[P];
+    const u32 t = cur ^ x;
+    acc[P] = t ^ carry;
+    carry = (t & carry) | (~t & cur);             // majority(cur, x, carry)
+  }
+}
+
+template <int C>
+__device__ inline void add_operand_chunks(u32 (&acc)[kSumPlanes], const u32* mine, u32 w, u32 sgn, u32& carry,
+                                          u32 wcap, u32 top) {
+  if constexpr (C * kSumChunk < kSumPlanes) {
+    if (u32(C * kSumChunk) >= top) return;        // uniform
+    if (C * kSumChunk < 16 && u32(C * kSumChunk) < wcap) add_chunk<C, true>(acc, mine, w, sgn, carry);
+    else add_chunk<C, false>(acc, mine, w, sgn, carry);
+    add_operand_chunks<C + 1>(acc, mine, w, sgn, carry, wcap, top);
+  }
+}
+
+// Extends the valid planes from `top` to `new_top` with copies of the sign plane.
+template <int C>
+__device__ inline void grow_sum(u32 (&acc)[kSumPlanes], u32 top, u32 new_top) {
+  if constexpr (C * kSumChunk < kSumPlanes) {
+    if (u32(C * kSumChunk) >= new_top) return;    // uniform
+    if (u32(C * kSumChunk) >= top) {
+      u32 e = 0;
+      if constexpr (C > 0) e = acc[C * kSumChunk - 1];
+#pragma unroll
+      for (int i = 0; i < kSumChunk; ++i) acc[C * kSumChunk + i] = e;
+    }
+    grow_sum<C + 1>(acc, top, new_top);
+  }
+}
+
+// Two's complement planes -> magnitude planes (in place), given the sign plane; tracks the width.
+template <int C>
+__device__ inline void sum_to_magnitude(u32 (&acc)[kSumPlanes], u32 sgn, u32& carry, u32& width, u32 top) {
+  if constexpr (C * kSumChunk < kSumPlanes) {
+    if (u32(C * kSumChunk) >= top) {
+#pragma unroll
+      for (int i = 0; i < kSumChunk; ++i) acc[C * kSumChunk + i] = 0;
+    } else {
+#pragma unroll
+      for (int i = 0; i < kSumChunk; ++i) {
+        constexpr int kFirst = C * kSumChunk;
+        const int P = kFirst + i;
+        const u32 t = acc[P] ^ sgn;
+        const u32 m = t ^ carry;
+        carry = t & carry;
+        acc[P] = m;
+        width = m ? u32(P + 1) : width;
+      }
+    }
+    sum_to_magnitude<C + 1>(acc, sgn, carry, width, top);
+  }
+}
+
+template <int C>
+__device__ inline u32 sign_plane(const u32 (&acc)[kSumPlanes], u32 top) {
+  if constexpr ((C + 1) * kSumChunk > kSumPlanes) {
+    return 0u;
+  } else {
+    if (top == u32((C + 1) * kSumChunk)) return acc[(C + 1) * kSumChunk - 1];
+    return sign_plane<C + 1>(acc, top);
+  }
+}
+
+__global__ __launch_bounds__(kTileThreads, ZC_RED_OCC) void reduce_kernel(ReduceArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
+  __shared__ u32 sh_tile;
+  __shared__ u32 sh_wave_total[kTileWaves];
+  __shared__ u64 sh_base;
+
+  if (validation_failed(a.ctl) || streams_are_wide(a.ctl)) return;
+  const ParsedHeader h = parse_header(a.in[0]);
+  if (!h.ok) return;
+  const u64 tend = tables_end(h.nb);
+  const u32 ntiles = u32(num_tiles(h.nb));
+  if (blockIdx.x == 0 && threadIdx.x == 0) write_reduce_header(a, h, ntiles);
+  if (ntiles == 0) return;
+
+  const int lane = lane_id();
+  const int wave = int(threadIdx.x) >> 6;
+#ifdef ZC_REC
+  const u64 t_start = wall_clock64();
+#endif
+#ifdef ZC_ABL_BLOCKORDER
+  const u32 tile = blockIdx.x;
+#else
+  if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
+  __syncthreads();
+  const u32 tile = uniform(sh_tile);
+  if (tile == kNoTile) return;
+#endif
+
+#ifdef ZC_REC
+  if (threadIdx.x == 0 && g_rec) {
+    g_rec[u64(tile) * 8] = t_start;
+    g_rec[u64(tile) * 8 + 7] = (u64(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (4 << 11))) << 32) | blockIdx.x;
+  }
+#endif
+  REC(tile, 1);
+  u32* const wl = lds + wave * kWaveStage;
+  const u64 seg = u64(tile) * kTileWaves + u64(wave);
+  const bool seg_live = seg < num_segments(h.nb);
+  const u64 b = seg * kWaveBlocks + u64(lane);
+  const bool active = b < h.nb;
+
+  // ---- add the k operands' blocks in plane form; loads run ahead of the adds ----
+  u32 acc[kSumPlanes];
+#pragma unroll
+  for (int p = 0; p < kSumPlanes; ++p) acc[p] = 0;
+  u32 top = 0;
+  u32 bound = 0;          // wave-uniform bound on |sum of deltas| so far (< 64 * 2^16)
+  i64 outlier = 0;
+
+  OperandMeta meta = load_operand_meta(a, 0, h, seg, b, active, seg_live);
+  OperandPlace next = place_operand(meta);
+  outlier += i64(meta.outlier);
+  if (a.k > 1) meta = load_operand_meta(a, 1, h, seg, b, active, seg_live);
+  OperandStage stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[0].base + tend), next, lane);
+  for (int s = 0; s < a.k; ++s) {
+    const OperandPlace cur = next;
+    stage_to_lds(stage, cur, wl, lane);
+    wave_lds_sync();
+    if (s == 0) REC(tile, 2);
+    if (s + 1 < a.k) {
+      next = place_operand(meta);
+      outlier += i64(meta.outlier);
+      if (s + 2 < a.k) meta = load_operand_meta(a, s + 2, h, seg, b, active, seg_live);
+      stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[s + 1].base + tend), next, lane);
+    }
+#ifdef ZC_ABL_NOADD
+    if (cur.wcap && s == 0) {
+#else
+    if (cur.wcap) {
+#endif
+      bound += (1u << cur.wcap) - 1u;
+      u32 new_top = (32u - u32(__builtin_clz(bound)) + 1u + 3u) & ~3u;
+      if (new_top > u32(kSumPlanes)) new_top = kSumPlanes;      // cannot happen for k <= 64
+      grow_sum<0>(acc, top, new_top);
+      top = new_top;
+      const u32* mine = wl + cur.pick;
+      const u32 sgn = cur.w ? mine[0] : 0u;
+      u32 carry = sgn;
+      add_operand_chunks<0>(acc, mine, cur.w, sgn, carry, cur.wcap, top);
+    }
+    wave_lds_sync();
+  }
+
+  REC(tile, 3);
+  // ---- back to sign + magnitude planes; new code length; placement and copy-out ----
+  const u32 sgn = sign_plane<0>(acc, top);
+  u32 carry = sgn, w = 0;
+  sum_to_magnitude<0>(acc, sgn, carry, w, top);
+  auto word = [&](auto i) {
+    constexpr int I = decltype(i)::value;        // 0: sign, 1 + p: plane p
+    if constexpr (I == 0) return sgn;
+    else return acc[I - 1];
+  };
+  place_sum<kSumPlanes>(a, h, acc, sgn, w, outlier, active, b, tile, ntiles, word, wl, sh_wave_total, &sh_base, wave,
+                        lane);
+}
+
+// ---------------------------------------------------------------------------------------
+// Any widths.
+// ---------------------------------------------------------------------------------------
+constexpr int kAccPlanes = 39;   // |sum of 64 deltas| < 2^37: 38 magnitude bits + sign
 
 // acc (two's complement, `top` planes valid, `ext` = its sign plane) += operand given as
 // sign word s and magnitude planes a[0..31) (zero above the operand's width).
@@ -71,67 +447,18 @@ __device__ inline void magnitude_planes(u32 (&acc)[kAccPlanes], u32 s, u32 carry
   }
 }
 
-template <int P>
-__device__ inline void store_sum_planes(const u32 (&acc)[kAccPlanes], u32 w, u32 wmax, u32* dst) {
-  if constexpr (P < 31) {
-    if (u32(P) >= wmax) return;
-    if (u32(P) < w) dst[1 + P] = acc[P];
-    store_sum_planes<P + 1>(acc, w, wmax, dst);
-  }
-}
-
-// Exact range check of one block's summed codes, for lanes whose cheap bound did not settle
-// it: rebuild every delta from the magnitude planes and walk the Lorenzo chain in 64 bits.
-__device__ inline bool block_out_of_range(const u32 (&mag)[kAccPlanes], u32 sign, i64 outlier) {
-  i64 q = outlier;
-  bool bad = q > kMaxCode || q < -kMaxCode;
-  for (int j = 1; j < 32; ++j) {
-    i64 m = 0;
-#pragma unroll
-    for (int p = 0; p < kAccPlanes; ++p) m |= i64((mag[p] >> j) & 1u) << p;
-    q += ((sign >> j) & 1u) ? -m : m;
-    bad |= q > kMaxCode || q < -kMaxCode;
-  }
-  return bad;
-}
-
-__global__ __launch_bounds__(kTileThreads) void reduce_kernel(ReduceArgs a) {
-  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveLds];
+__global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
   __shared__ u32 sh_tile;
   __shared__ u32 sh_wave_total[kTileWaves];
   __shared__ u64 sh_base;
 
-  if (validation_failed(a.ctl)) return;
+  if (validation_failed(a.ctl) || !streams_are_wide(a.ctl)) return;
   const ParsedHeader h = parse_header(a.in[0]);
   if (!h.ok) return;
   const u64 tend = tables_end(h.nb);
   const u32 ntiles = u32(num_tiles(h.nb));
-
-  // The first workgroup writes the header fields and the table padding.
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    u64 nsum = 0;
-    for (int s = 0; s < a.k; ++s) nsum += parse_header(a.in[s]).nsum;
-    if (nsum > 0xffffffffull) atomicOr(&a.ctl->status, status_bit(ZC_ERR_RANGE));
-    if (a.out_cap >= tend) {
-      u32* hw = reinterpret_cast<u32*>(a.out);
-      hw[0] = kMagic;
-      hw[1] = 1u | (5u << 16) | (6u << 24);
-      hw[2] = u32(h.n);
-      hw[3] = u32(h.n >> 32);
-      hw[4] = h.eb_bits;
-      hw[5] = u32(nsum);
-      if (ntiles == 0) {
-        hw[6] = u32(tend);
-        hw[7] = u32(tend >> 32);
-      }
-      for (u64 i = h.nb; i < pad16(h.nb); ++i) a.out[kHeaderBytes + i] = 0;
-      u8* ot = a.out + kHeaderBytes + pad16(h.nb);
-      for (u64 i = 4 * h.nb; i < pad16(4 * h.nb); ++i) ot[i] = 0;
-    } else {
-      atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
-    }
-    if (ntiles == 0) a.ctl->result = tend;
-  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) write_reduce_header(a, h, ntiles);
   if (ntiles == 0) return;
 
   const int lane = lane_id();
@@ -141,13 +468,12 @@ __global__ __launch_bounds__(kTileThreads) void reduce_kernel(ReduceArgs a) {
   const u32 tile = uniform(sh_tile);
   if (tile == kNoTile) return;
 
-  u32* wl = lds + wave * kWaveLds;
+  u32* const wl = lds + wave * kWaveStage;
   const u64 seg = u64(tile) * kTileWaves + u64(wave);
   const bool seg_live = seg < num_segments(h.nb);
   const u64 b = seg * kWaveBlocks + u64(lane);
   const bool active = b < h.nb;
 
-  // ---- add the k operands' blocks in plane form ----
   u32 acc[kAccPlanes];
 #pragma unroll
   for (int p = 0; p < kAccPlanes; ++p) acc[p] = 0;
@@ -182,69 +508,14 @@ __global__ __launch_bounds__(kTileThreads) void reduce_kernel(ReduceArgs a) {
     top = new_top;
   }
 
-  // ---- back to sign + magnitude planes; new code length ----
   u32 w = 0;
   magnitude_planes<0>(acc, ext, ext, top, w);
-  if (!active) w = 0;
-  u32 err = 0;
-  if (active) {
-    const i64 ao = outlier < 0 ? -outlier : outlier;
-    const i64 reach = ao + 31 * ((i64(1) << w) - 1);
-    if (reach > kMaxCode || w > 31) {
-      if (w > 31 || block_out_of_range(acc, ext, outlier)) {
-        err |= status_bit(ZC_ERR_RANGE);
-        w = 0;
-      }
-    }
-  }
-  const u32 words = psize_words(w);
-
-  // ---- place, publish, pack, look back, copy out (as in compression) ----
-  const u32 incl = wave_inclusive_sum(words);
-  const u32 wave_total = lane_value(incl, 63);
-  const u32 off_in_wave = incl - words;
-  const u32 wmax = wave_max_u32(w);
-  if (lane == 0) sh_wave_total[wave] = wave_total;
-  if (active && a.out_cap >= tend) {
-    a.out[kHeaderBytes + b] = u8(w);
-    reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(h.nb))[b] = i32(outlier);
-  }
-  __syncthreads();
-  u32 wave_off = 0, tile_total = 0;
-#pragma unroll
-  for (int i = 0; i < kTileWaves; ++i) {
-    u32 t = sh_wave_total[i];
-    if (i < wave) wave_off += t;
-    tile_total += t;
-  }
-  if (threadIdx.x == 0) desc_store(a.desc + desc_slot(tile), (tile == 0 ? kDescPrefix : kDescAggregate) | u64(tile_total));
-
-  if (w) wl[off_in_wave] = ext;
-  store_sum_planes<0>(acc, w, wmax, wl + off_in_wave);
-
-  if (wave == 0) {
-    const u64 base = tile ? lookback_exclusive(a.desc, tile, &a.ctl->status) : 0;
-    if (lane == 0) {
-      if (tile) desc_store(a.desc + desc_slot(tile), kDescPrefix | (base + tile_total));
-      sh_base = base;
-    }
-  }
-  if (err) atomicOr(&a.ctl->status, err);
-  __syncthreads();
-
-  const u64 base = sh_base;
-  const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
-  u32* payload = reinterpret_cast<u32*>(a.out + tend);
-  const u64 dst0 = base + wave_off;
-  for (u32 i = u32(lane); i < wave_total; i += 64) {
-    if (dst0 + i < cap_words) payload[dst0 + i] = wl[i];
-  }
-  if (tile == ntiles - 1 && threadIdx.x == 0) {
-    const u64 total = tend + 4 * (base + tile_total);
-    a.ctl->result = total;
-    if (total > a.out_cap) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
-    if (a.out_cap >= kHeaderBytes) reinterpret_cast<u64*>(a.out)[3] = total;
-  }
+  auto word = [&](auto i) {
+    constexpr int I = decltype(i)::value;        // 0: sign, 1 + p: plane p
+    if constexpr (I == 0) return ext;
+    else return acc[I - 1];
+  };
+  place_sum<32>(a, h, acc, ext, w, outlier, active, b, tile, ntiles, word, wl, sh_wave_total, &sh_base, wave, lane);
 }
 
 }  // namespace zc

@@ -63,9 +63,10 @@ __device__ inline u64 segment_offset(const StreamIndex& ix, int s, u64 seg) {
 }
 
 // Payload words of the four blocks whose width bytes are packed in x, and whether any byte
-// exceeds 31.  Sum of (1 + w) over the non-zero bytes = byte sum + number of non-zero bytes.
-__device__ inline u32 psize_words4(u32 x, bool& bad) {
+// exceeds 31 (bad) or 15 (wide).  Sum of (1 + w) over the non-zero bytes = byte sum + number of non-zero bytes.
+__device__ inline u32 psize_words4(u32 x, bool& bad, bool& wide) {
   bad |= (x & 0xE0E0E0E0u) != 0;
+  wide |= (x & 0xF0F0F0F0u) != 0;
   const u32 nonzero = (((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x) & 0x80808080u;   // top bit of every non-zero byte
   return __builtin_amdgcn_sad_u8(x, 0u, u32(__builtin_popcount(nonzero)));
 }
@@ -117,7 +118,7 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
     if (b0 < h.nb) v[i] = *reinterpret_cast<const uint4*>(widths + b0);
   }
   u32 sum[kIndexGroups], incl[kIndexGroups];
-  bool bad = false;
+  bool bad = false, wide = false;
 #pragma unroll
   for (int i = 0; i < kIndexGroups; ++i) {
     const u64 b0 = (group0 + u64(i)) * kScanGroupBlocks + u64(threadIdx.x) * 16;
@@ -130,11 +131,13 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
         x[j] &= keep;
       }
     }
-    sum[i] = psize_words4(x[0], bad) + psize_words4(x[1], bad) + psize_words4(x[2], bad) + psize_words4(x[3], bad);
+    sum[i] = psize_words4(x[0], bad, wide) + psize_words4(x[1], bad, wide) + psize_words4(x[2], bad, wide) +
+             psize_words4(x[3], bad, wide);
     incl[i] = wave_inclusive_sum(sum[i]);
     if (lane == 63) sh_wave[i][wave] = incl[i];
   }
   if (bad) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
+  if (wide) atomicOr(&a.ctl->flags, kFlagWide);
   __syncthreads();
   u32* grp = a.index.grp_off + u64(s) * a.index.groups_cap;
   u32* seg_off = a.index.seg_off + u64(s) * 4 * a.index.tiles_cap;

@@ -251,6 +251,33 @@ def test_reduce_wide_and_cancelling_operands(zcref):
     assert not r[32:32 + (n + 31) // 32].any()
 
 
+@pytest.mark.parametrize("k", [2, 9, 64])
+def test_reduce_narrow_widths_all_classes(zcref, k):
+    """Every block at most 15 bits wide (the staged kernel), widths 0..15 mixed inside each wave, up to 64 operands."""
+    u = _u()
+    rng = np.random.default_rng(100 + k)
+    n = 5 * TILE + 45
+    nb = (n + 31) // 32
+    qs = []
+    for i in range(k):
+        scale = np.repeat(2.0 ** rng.integers(-2, 14, nb), 32)[:n]       # |code| < 2^13: |delta| < 2^14
+        q = (rng.uniform(-1, 1, n) * scale).astype(np.int32)
+        if i % 5 == 4:
+            q[: n // 2] = 7                                              # long runs of constant blocks
+        qs.append(q)
+    qs[1] = -qs[0]                                                       # exact cancellation
+    # extreme deltas of the class: +-(2^15 - 1) next to each other, all operands in phase
+    for q in qs[2:]:
+        q[64:96:2] = 2 ** 14 - 1
+        q[65:96:2] = -(2 ** 14)
+    streams = [zcref.encode_codes(q, 1e-3)[1] for q in qs]
+    assert max(int(s[32:32 + nb].max()) for s in streams) <= 15
+    st_ref, r_ref, total_ref = zcref.reduce(streams)
+    st, r, total = u.gpu_reduce(streams, n)
+    assert st == st_ref == ZC_OK and total == total_ref
+    assert r.tobytes() == r_ref.tobytes(), u.first_diff(r, r_ref)
+
+
 def test_reduce_error_paths(zcref):
     u = _u()
     xs, eb, streams = _rank_streams(zcref, 2, 4096 * 3, 1e-3, seed0=30)
