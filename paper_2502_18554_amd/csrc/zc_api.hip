@@ -64,7 +64,7 @@ KernelTimer g_timer;
 u64 blocks_bound(u64 bytes) { return bytes > kHeaderBytes ? (bytes - kHeaderBytes) / 5 : 0; }
 
 // Workgroups of stream_index_kernel per stream: 16 tiles make a scan group.
-u32 index_grid(u64 tiles) { return u32(((tiles + 15) / 16 + kIndexGroups - 1) / kIndexGroups); }
+u32 index_grid(u64 tiles) { return u32(((tiles + 15) / 16 + kIndexGroups - 1) / kIndexGroups); }   // spans
 
 int finish(const void* d_ws, size_t* result, hipStream_t stream) {
   struct { u32 status, reserved; u64 result; } host;
@@ -77,7 +77,6 @@ int finish(const void* d_ws, size_t* result, hipStream_t stream) {
 void launch_init(const WorkspaceLayout& l, u32 ntiles, u8* out, u64 out_cap, u64 n, u32 eb_bits, hipStream_t stream) {
   InitArgs ia;
   ia.ctl = l.ctl;
-  ia.done = l.index.done;
   ia.desc = l.desc;
   ia.ntiles = ntiles;
   ia.out = out;
@@ -220,6 +219,7 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
   sa.index = l.index;
   sa.ctl = l.ctl;
   hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), 1), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(span_scan_kernel, dim3(1), dim3(256), 0, stream, sa);
   DecompressArgs da;
   da.in = sa.streams[0];
   da.out = d_out;
@@ -264,6 +264,7 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   sa.index = l.index;
   sa.ctl = l.ctl;
   hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), u32(k)), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(span_scan_kernel, dim3(u32(k)), dim3(256), 0, stream, sa);
   ra.k = k;
   ra.index = l.index;
   ra.out = static_cast<u8*>(d_out);
@@ -364,6 +365,7 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
   sa.index = l.index;
   sa.ctl = l.ctl;
   hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), 1), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(span_scan_kernel, dim3(1), dim3(256), 0, stream, sa);
   OffsetsArgs oa;
   oa.in = sa.streams[0];
   oa.index = l.index;

@@ -70,22 +70,29 @@ __host__ __device__ inline u32* ticket_counter(Control* ctl, u32 shard) {
 // A segment is the 64 blocks owned by one wave; a tile is 4 segments.
 __host__ __device__ inline u64 num_segments(u64 nb) { return (nb + kWaveBlocks - 1) / kWaveBlocks; }
 
-// Positions inside an existing stream are kept at two levels (see zc_scan.h): the offset of
-// every segment inside its scan group of 64 segments, and the exclusive offset of every group.
+// Positions inside an existing stream are kept at three levels (see zc_scan.h): the offset of
+// every segment inside its scan group of 64 segments, the offset of every group inside its
+// index span of 8 groups (the share of one workgroup of the index kernel), and the offset of
+// every span.  A reader adds the three.
 constexpr int kScanGroupSegs = 64;
 constexpr int kScanGroupBlocks = kScanGroupSegs * kWaveBlocks;     // 4096 blocks
+constexpr int kIndexGroups = 8;                                    // scan groups per index span
+constexpr int kSpanSegs = kIndexGroups * kScanGroupSegs;           // 512 segments = 32768 blocks
 __host__ __device__ inline u64 num_scan_groups(u64 nb) { return (nb + kScanGroupBlocks - 1) / kScanGroupBlocks; }
+__host__ __device__ inline u64 num_spans(u64 nb) { return (num_scan_groups(nb) + kIndexGroups - 1) / kIndexGroups; }
 
 struct StreamIndex {
   u32* seg_off;     // [k][4 * tiles_cap]   payload word offset of each segment inside its scan group
-  u32* grp_off;     // [k][groups_cap]      payload word offset of each scan group
-  u32* done;        // [ZC_MAX_K]           index workgroups finished, per stream
+  u32* grp_off;     // [k][groups_cap]      payload word offset of each scan group inside its span
+  u32* span_off;    // [k][spans_cap]       payload word offset of each span (its size between the two index kernels)
   u64 tiles_cap;
   u64 groups_cap;
+  u64 spans_cap;
 };
 
 // How a workspace of ws_bytes is carved up for calls with k input streams:
-//   Control | tickets | done[ZC_MAX_K] | desc[tiles_cap] (128 B each) | seg_off[k][4 * tiles_cap] | grp_off[k][groups_cap]
+//   Control | tickets | desc[tiles_cap] (128 B each) | seg_off[k][4 * tiles_cap] | grp_off[k][groups_cap] |
+//   span_off[k][spans_cap]
 // tiles_cap follows from ws_bytes alone, so kernels can refuse streams that do not fit.
 struct WorkspaceLayout {
   u64 tiles_cap;
@@ -95,12 +102,12 @@ struct WorkspaceLayout {
 };
 
 constexpr u64 kDescBytes = 128;           // per tile, see kDescStride
-constexpr u64 kWsFixed = sizeof(Control) + kTicketBytes + 4 * ZC_MAX_K + 4 * ZC_MAX_K + 64;   // control, done[], the +1 of every grp_off row, padding
+constexpr u64 kWsFixed = sizeof(Control) + kTicketBytes + 8 * ZC_MAX_K + 64;   // control, tickets, the +1 of every grp_off and span_sum row, padding
 
 __host__ inline u64 workspace_bytes(u64 n_max, int k_max) {
   if (k_max < 1) k_max = 1;
   const u64 t = num_tiles(num_blocks(n_max)) + 16;
-  return kWsFixed + t * (kDescBytes + 17 * u64(k_max));      // 17 = segment offsets (16) + the tile's share of the group offsets
+  return kWsFixed + t * (kDescBytes + 17 * u64(k_max));      // 17 >= segment offsets (16) + the tile's share of the two coarser levels
 }
 
 __host__ inline WorkspaceLayout workspace_layout(void* d_ws, u64 ws_bytes, int k) {
@@ -110,15 +117,16 @@ __host__ inline WorkspaceLayout workspace_layout(void* d_ws, u64 ws_bytes, int k
   u8* p = static_cast<u8*>(d_ws);
   l.ctl = reinterpret_cast<Control*>(p);
   p += sizeof(Control) + kTicketBytes;
-  l.index.done = reinterpret_cast<u32*>(p);
-  p += 4 * ZC_MAX_K;
   l.desc = reinterpret_cast<u64*>(p);
   p += kDescBytes * l.tiles_cap;
+  l.index.tiles_cap = l.tiles_cap;
+  l.index.groups_cap = l.tiles_cap / 16 + 1;        // 16 tiles = 64 segments = one scan group
+  l.index.spans_cap = l.tiles_cap / (16 * kIndexGroups) + 1;
   l.index.seg_off = reinterpret_cast<u32*>(p);
   p += pad16(16 * l.tiles_cap * u64(k));
   l.index.grp_off = reinterpret_cast<u32*>(p);
-  l.index.tiles_cap = l.tiles_cap;
-  l.index.groups_cap = l.tiles_cap / 16 + 1;        // 16 tiles = 64 segments = one scan group
+  p += 4 * l.index.groups_cap * u64(k);
+  l.index.span_off = reinterpret_cast<u32*>(p);
   return l;
 }
 

@@ -272,7 +272,6 @@ __global__ __launch_bounds__(kPackThreads, 16 / kPackWaves) void compress_kernel
 // the zero padding of the two tables.  Runs before compress_kernel / reduce_kernel.
 struct InitArgs {
   Control* ctl;
-  u32* done;        // per-stream counters of the stream index
   u64* desc;
   u32 ntiles;
   u8* out;          // may be null (decompress has no output stream)
@@ -285,7 +284,6 @@ __global__ void init_kernel(InitArgs a) {
   const u64 gid = u64(blockIdx.x) * blockDim.x + threadIdx.x;
   const u64 stride = u64(gridDim.x) * blockDim.x;
   for (u64 i = gid; i < a.ntiles; i += stride) a.desc[desc_slot(i)] = 0;
-  if (gid < ZC_MAX_K) a.done[gid] = 0;
   if (gid == 0) {
     for (int i = 0; i < kTicketShards; ++i) *ticket_counter(a.ctl, u32(i)) = 0;
     a.ctl->status = 0;

@@ -3,9 +3,10 @@
 // a block's position is the sum of the sizes before it), kept per segment of 64 blocks, the
 // share of one wave.
 //
-// stream_index_kernel records the offset of every segment inside its scan group of 64
-// segments and the exclusive offset of every scan group, and validates header and width
-// bytes on the way.
+// stream_index_kernel records the offset of every segment inside its scan group, of every
+// group inside its index span and the size of every span, and validates header and width
+// bytes on the way; span_scan_kernel then turns the span sizes into offsets and compares the
+// header's total_bytes with the indexed payload.  No workgroup waits for, or counts, another.
 #pragma once
 
 #include "zc_common.h"
@@ -56,9 +57,11 @@ struct ScanArgs {
   Control* ctl;
 };
 
-// Payload word offset of segment `seg` of stream `s` (the same value in every lane).
+// Payload word offset of segment `seg` of stream `s`: the offset of its index span, plus its
+// group's offset in the span, plus its own offset in the group.  Three independent loads.
 __device__ inline u64 segment_offset(const StreamIndex& ix, int s, u64 seg) {
-  return u64(ix.grp_off[u64(s) * ix.groups_cap + seg / kScanGroupSegs]) +
+  return u64(ix.span_off[u64(s) * ix.spans_cap + seg / kSpanSegs]) +
+         u64(ix.grp_off[u64(s) * ix.groups_cap + seg / kScanGroupSegs]) +
          u64(ix.seg_off[u64(s) * 4 * ix.tiles_cap + seg]);
 }
 
@@ -71,20 +74,12 @@ __device__ inline u32 psize_words4(u32 x, bool& bad, bool& wide) {
   return __builtin_amdgcn_sad_u8(x, 0u, u32(__builtin_popcount(nonzero)));
 }
 
-// A workgroup covers kIndexGroups scan groups of 4096 blocks (64 segments) of one stream.
-// Each thread takes 16 blocks of a group (one 16-byte load of the width table), four threads
-// make a segment; a scan over the workgroup gives every segment its offset inside the group.
-// Few, fat workgroups keep the number of updates of the per-stream `done` counter small:
-// atomics on one address retire one after the other.  The workgroup that finishes last for a
-// stream turns the group sums into exclusive offsets and checks that the header's
-// total_bytes equals tables + payload.
-constexpr int kIndexGroups = 8;
-
+// A workgroup covers one index span: kIndexGroups scan groups of 4096 blocks (64 segments)
+// of one stream.  Each thread takes 16 blocks of a group (one 16-byte load of the width
+// table), four threads make a segment; a scan over the workgroup gives every segment its
+// offset inside the group, every group its offset inside the span, and the span its size.
 __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
   __shared__ u32 sh_wave[kIndexGroups][4];
-  __shared__ u32 sh_scan[4];
-  __shared__ u32 sh_last;
-  __shared__ u64 sh_carry;
   const int s = blockIdx.y;
   const StreamRef st = a.streams[s];
   const ParsedHeader h = parse_header(st);
@@ -93,15 +88,16 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
     return;
   }
   const u64 ngroups = num_scan_groups(h.nb);
+  const bool fits = num_tiles(h.nb) <= a.index.tiles_cap && ngroups <= a.index.groups_cap &&
+                    num_spans(h.nb) <= a.index.spans_cap;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
-    if (num_tiles(h.nb) > a.index.tiles_cap || ngroups > a.index.groups_cap)
-      atomicOr(&a.ctl->status, status_bit(ZC_ERR_ARG));
+    if (!fits) atomicOr(&a.ctl->status, status_bit(ZC_ERR_ARG));
     if (a.check_match && s > 0) {
       const ParsedHeader h0 = parse_header(a.streams[0]);
       if (h0.ok && (h0.n != h.n || h0.eb_bits != h.eb_bits)) atomicOr(&a.ctl->status, status_bit(ZC_ERR_MISMATCH));
     }
   }
-  if (num_tiles(h.nb) > a.index.tiles_cap || ngroups > a.index.groups_cap) return;
+  if (!fits) return;
   const u64 group0 = u64(blockIdx.x) * kIndexGroups;
   if (group0 >= ngroups) return;
 
@@ -142,6 +138,7 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
   u32* grp = a.index.grp_off + u64(s) * a.index.groups_cap;
   u32* seg_off = a.index.seg_off + u64(s) * 4 * a.index.tiles_cap;
   const u64 nsegs = num_segments(h.nb);
+  u32 span_before = 0;                                   // payload words of the span's groups so far
 #pragma unroll
   for (int i = 0; i < kIndexGroups; ++i) {
     u32 before = 0, all = 0;
@@ -153,23 +150,30 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
     }
     const u64 seg = (group0 + u64(i)) * kScanGroupSegs + (threadIdx.x >> 2);
     if ((threadIdx.x & 3) == 0 && seg < nsegs) seg_off[seg] = before + incl[i] - sum[i];
-    if (threadIdx.x == 0 && group0 + u64(i) < ngroups) desc32_store(grp + group0 + u64(i), all);
+    if (threadIdx.x == 0 && group0 + u64(i) < ngroups) grp[group0 + u64(i)] = span_before;
+    span_before += all;
   }
-  if (threadIdx.x == 0) {
-    __threadfence();
-    const u32 finished = atomicAdd(&a.index.done[s], 1u);
-    sh_last = (u64(finished) + 1 == (ngroups + kIndexGroups - 1) / kIndexGroups);
-  }
-  __syncthreads();
-  if (!sh_last) return;
+  if (threadIdx.x == 0) a.index.span_off[u64(s) * a.index.spans_cap + blockIdx.x] = span_before;   // its size; span_scan_kernel makes it an offset
+}
 
-  // ---- last workgroup of this stream: exclusive scan of the group sums, in place ----
-  __threadfence();
+// Second step of the index: one workgroup per stream turns the span sizes into exclusive
+// offsets, in place, and checks that the header's total_bytes equals tables + payload.
+__global__ __launch_bounds__(256) void span_scan_kernel(ScanArgs a) {
+  __shared__ u32 sh_scan[4];
+  __shared__ u64 sh_carry;
+  const int s = blockIdx.x;
+  const ParsedHeader h = parse_header(a.streams[s]);
+  if (!h.ok) return;
+  const u64 nspans = num_spans(h.nb);
+  if (nspans > a.index.spans_cap) return;               // already flagged by stream_index_kernel
+  const int lane = lane_id();
+  const int wave = int(threadIdx.x) >> 6;
+  u32* spans = a.index.span_off + u64(s) * a.index.spans_cap;
   if (threadIdx.x == 0) sh_carry = 0;
   __syncthreads();
-  for (u64 start = 0; start < ngroups; start += 256) {
+  for (u64 start = 0; start < nspans; start += 256) {
     const u64 i = start + threadIdx.x;
-    const u32 val = i < ngroups ? desc32_load(grp + i) : 0u;
+    const u32 val = i < nspans ? spans[i] : 0u;
     const u32 inc = wave_inclusive_sum(val);
     if (lane == 63) sh_scan[wave] = inc;
     __syncthreads();
@@ -181,15 +185,12 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
       all += t;
     }
     const u64 carry = sh_carry;
-    if (i < ngroups) grp[i] = u32(carry) + before + inc - val;
+    if (i < nspans) spans[i] = u32(carry) + before + inc - val;
     __syncthreads();
     if (threadIdx.x == 0) sh_carry = carry + all;
     __syncthreads();
   }
-  if (threadIdx.x == 0) {
-    const u64 payload_bytes = 4 * sh_carry;
-    if (tables_end(h.nb) + payload_bytes != h.total) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
-  }
+  if (threadIdx.x == 0 && tables_end(h.nb) + 4 * sh_carry != h.total) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
 }
 
 }  // namespace zc
