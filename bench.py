@@ -25,6 +25,12 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of each main kernel on the default workload, from the rocprofv3 counter runs
+# summarised under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads on a plain
+# copy of the field in the same run).  Counters cannot be read from inside this script, so the figures are
+# carried here and reported only when the run is that workload.
+PROFILED_TRAFFIC = {"compress": 755.2e6, "decompress": 746.1e6, "reduce": 956.1e6}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -156,7 +162,8 @@ def main():
             "fp32_GBps": round(fp32_bytes[s] / stage_ms[s] / 1e6, 1),
             "kernel_ms": round(kernel_ms[s], 4),
             "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None},
+                         "frac": round(gbs / HBM_PEAK_GBS, 4),
+                         "traffic": PROFILED_TRAFFIC[s] if (side == 512 and args.rel == 1e-4) else None},
             "algorithmic_bytes": alg_bytes[s],
         }
     dominant = max(stage_names, key=lambda s: kernel_ms[s])
