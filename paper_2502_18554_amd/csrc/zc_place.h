@@ -67,11 +67,7 @@ __device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Plac
                                    u32* wl, u64* sh_base, int wave, int lane) {
   static_assert(32 * NW <= kWaveStage, "a half-wave of widest blocks must fit the staging area");
   if (wave == 0) {
-#ifdef ZC_ABL_NOLOOK
-    const u64 base = u64(tile) * 3000;
-#else
     const u64 base = tile ? lookback_exclusive(s.desc, tile, &s.ctl->status) : 0;
-#endif
     if (lane == 0) {
       if (tile) desc_store(s.desc + desc_slot(tile), kDescPrefix | (base + pl.tile_total));
       *sh_base = base;

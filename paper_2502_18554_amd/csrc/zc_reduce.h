@@ -137,9 +137,6 @@ __device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, con
 // is a copy of the sign plane.
 constexpr int kSumPlanes = 24;
 constexpr int kSumChunk = 4;
-#ifndef ZC_RED_OCC
-#define ZC_RED_OCC 5
-#endif
 
 // What a wave needs to know about one operand's share: loaded two operands ahead.
 struct OperandMeta {
@@ -303,7 +300,7 @@ __device__ inline u32 sign_plane(const u32 (&acc)[kSumPlanes], u32 top) {
   }
 }
 
-__global__ __launch_bounds__(kTileThreads, ZC_RED_OCC) void reduce_kernel(ReduceArgs a) {
+__global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
   __shared__ u32 sh_tile;
   __shared__ u32 sh_wave_total[kTileWaves];
@@ -322,14 +319,10 @@ __global__ __launch_bounds__(kTileThreads, ZC_RED_OCC) void reduce_kernel(Reduce
 #ifdef ZC_REC
   const u64 t_start = wall_clock64();
 #endif
-#ifdef ZC_ABL_BLOCKORDER
-  const u32 tile = blockIdx.x;
-#else
   if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
   __syncthreads();
   const u32 tile = uniform(sh_tile);
   if (tile == kNoTile) return;
-#endif
 
 #ifdef ZC_REC
   if (threadIdx.x == 0 && g_rec) {
@@ -368,11 +361,7 @@ __global__ __launch_bounds__(kTileThreads, ZC_RED_OCC) void reduce_kernel(Reduce
       if (s + 2 < a.k) meta = load_operand_meta(a, s + 2, h, seg, b, active, seg_live);
       stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[s + 1].base + tend), next, lane);
     }
-#ifdef ZC_ABL_NOADD
-    if (cur.wcap && s == 0) {
-#else
     if (cur.wcap) {
-#endif
       bound += (1u << cur.wcap) - 1u;
       u32 new_top = (32u - u32(__builtin_clz(bound)) + 1u + 3u) & ~3u;
       if (new_top > u32(kSumPlanes)) new_top = kSumPlanes;      // cannot happen for k <= 64
