@@ -1,0 +1,260 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times (asynchronous calls on device-resident buffers).
+
+The reference CPU codec cannot run whole buffers of this size inside a test, but blocks are
+independent: a block-aligned slice of the input, compressed alone by the reference codec, must
+reproduce the GPU stream's width bytes, outliers and payload bytes of those blocks (found
+through the exclusive sum of the GPU stream's own width table, computed with torch), and its
+reconstruction must equal the GPU's bit for bit.  Slices are drawn with a fixed seed and always
+include the first blocks and the ragged end.  On top of that come the properties that hold at
+any size: error bound on every value, idempotence on the grid, header fields, sizes that add up.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_18554_amd as zc
+from paper_2502_18554_amd import synth
+from paper_2502_18554_amd.binding import ZC_OK
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+SLICE = 1 << 17          # values per sampled slice (4096 blocks: 16 tiles, crosses index groups)
+
+
+def pad16(v):
+    return (v + 15) // 16 * 16
+
+
+def tables_end(nb):
+    return 32 + pad16(nb) + pad16(4 * nb)
+
+
+def u8(nbytes):
+    return torch.empty(nbytes + 64, dtype=torch.uint8, device=DEV)
+
+
+class Stream:
+    """A GPU stream plus the block positions derived from its own width table."""
+
+    def __init__(self, buf, total, n):
+        self.buf, self.total, self.n = buf, total, n
+        self.nb = (n + 31) // 32
+        self.widths = buf[32:32 + self.nb]
+        words = torch.where(self.widths > 0, self.widths.to(torch.int64) + 1, torch.zeros((), dtype=torch.int64, device=DEV))
+        self.off = torch.cumsum(words, 0) - words            # exclusive, in words
+        self.payload_words = int(words.sum())
+        o0 = 32 + pad16(self.nb)
+        self.outliers = buf[o0:o0 + 4 * self.nb].view(torch.int32)
+        self.tend = tables_end(self.nb)
+
+    def header(self):
+        h = self.buf[:32].cpu().numpy()
+        return dict(magic=int(h[0:4].view("<u4")[0]), n=int(h[8:16].view("<u8")[0]), eb_bits=int(h[16:20].view("<u4")[0]),
+                    nsum=int(h[20:24].view("<u4")[0]), total=int(h[24:32].view("<u8")[0]))
+
+    def payload_of(self, b0, b1):
+        lo = int(self.off[b0])
+        hi = int(self.off[b1]) if b1 < self.nb else self.payload_words
+        return self.buf[self.tend + 4 * lo: self.tend + 4 * hi].cpu().numpy()
+
+
+def sample_starts(n, rng, count):
+    nb = (n + 31) // 32
+    span = SLICE // 32
+    last = max(nb - span, 0)
+    starts = {0, last}
+    while len(starts) < min(count, last + 1):
+        starts.add(int(rng.integers(0, last + 1)))
+    return sorted(starts)
+
+
+def compress_async(x, eb, ws):
+    n = x.numel()
+    out = u8(zc.zc_compress_bound(n))
+    st, _ = zc.zc_compress(x, n, eb, out, ws, sync=False)
+    assert st == ZC_OK
+    st, total = zc.zc_finish(ws)
+    return st, out, total
+
+
+def decompress_async(stream, total, out, ws):
+    st, _ = zc.zc_decompress(stream, total, out, ws, sync=False)
+    assert st == ZC_OK
+    return zc.zc_finish(ws)
+
+
+def check_header_and_sizes(s, eb, nsum=1):
+    h = s.header()
+    assert h["magic"] == 0x314C435A and h["n"] == s.n and h["nsum"] == nsum and h["total"] == s.total
+    assert h["eb_bits"] == int(np.float32(eb).view(np.uint32))
+    assert s.total == s.tend + 4 * s.payload_words
+    assert int(s.widths.max()) <= 31
+
+
+def check_slices_against_reference(zcref, x, eb, s, y, rng, count=6):
+    for b0 in sample_starts(s.n, rng, count):
+        v0, v1 = 32 * b0, min(s.n, 32 * b0 + SLICE)
+        st, ref, total = zcref.compress(x[v0:v1].cpu().numpy(), eb)
+        assert st == 0
+        nbs = (v1 - v0 + 31) // 32
+        assert np.array_equal(s.widths[b0:b0 + nbs].cpu().numpy(), ref[32:32 + nbs]), f"widths differ in slice at block {b0}"
+        o0 = 32 + pad16(nbs)
+        assert np.array_equal(s.outliers[b0:b0 + nbs].cpu().numpy(), ref[o0:o0 + 4 * nbs].view("<i4")), f"outliers differ at block {b0}"
+        assert np.array_equal(s.payload_of(b0, b0 + nbs), ref[tables_end(nbs):total]), f"payload differs at block {b0}"
+        if y is not None:
+            st, y_ref, _ = zcref.decompress(ref)
+            assert np.array_equal(y[v0:v1].cpu().numpy().view(np.uint32), y_ref.view(np.uint32)), f"floats differ at block {b0}"
+
+
+def max_abs_err(x, y, chunk=1 << 27):
+    worst = 0.0
+    for i in range(0, x.numel(), chunk):
+        worst = max(worst, float((x[i:i + chunk].double() - y[i:i + chunk].double()).abs().max()))
+    return worst
+
+
+@pytest.mark.parametrize("rel", [1e-2, 1e-3, 1e-4])
+def test_field_512cube(zcref, rel):
+    """Benchmark configuration 2: the 512^3 power-law field at the three bounds."""
+    rng = np.random.default_rng(int(round(-np.log10(rel))))
+    x = synth.power_law_field((512, 512, 512), seed=0, device=DEV)
+    n = x.numel()
+    eb = synth.abs_bound(x, rel)
+    ws = u8(zc.zc_workspace_bytes(n, 1))
+    st, buf, total = compress_async(x, eb, ws)
+    assert st == ZC_OK
+    s = Stream(buf, total, n)
+    check_header_and_sizes(s, eb)
+    y = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    st, n_out = decompress_async(buf, total, y, ws)
+    assert st == ZC_OK and n_out == n
+    assert max_abs_err(x, y) <= eb
+    check_slices_against_reference(zcref, x, eb, s, y, rng)
+    # idempotence on the grid: the reconstruction compresses to the same bytes
+    st, buf2, total2 = compress_async(y, eb, ws)
+    assert st == ZC_OK and total2 == total and torch.equal(buf2[:total], buf[:total])
+
+
+def _rank_buffers(k=8):
+    return [synth.power_law_field((256, 512, 512), seed=100 + r, device=DEV) for r in range(k)]
+
+
+def test_allgather_8x64M(zcref):
+    """Configuration 3: 8 rank buffers compressed at rel 1e-3, all decompressed into one 2^29-value output."""
+    rng = np.random.default_rng(3)
+    xs = _rank_buffers()
+    m = xs[0].numel()
+    ws = u8(zc.zc_workspace_bytes(m, 1))
+    out = torch.full((8 * m,), float("nan"), dtype=torch.float32, device=DEV)
+    streams = []
+    for x in xs:
+        eb = synth.abs_bound(x, 1e-3)
+        st, buf, total = compress_async(x, eb, ws)
+        assert st == ZC_OK
+        streams.append((Stream(buf, total, m), eb))
+    for r in reversed(range(8)):                 # a call that overran its slice would damage one already checked
+        s, eb = streams[r]
+        st, n_out = decompress_async(s.buf, s.total, out[r * m:(r + 1) * m], ws)
+        assert st == ZC_OK and n_out == m
+    for r, (s, eb) in enumerate(streams):
+        check_header_and_sizes(s, eb)
+        assert max_abs_err(xs[r], out[r * m:(r + 1) * m]) <= eb
+        if r in (0, 7):
+            check_slices_against_reference(zcref, xs[r], eb, s, out[r * m:(r + 1) * m], rng, count=3)
+
+
+def test_allreduce_8x64M(zcref):
+    """Configuration 4: fused reduce of 8 compressed rank buffers at a common bound; error <= 8 eb."""
+    rng = np.random.default_rng(4)
+    xs = _rank_buffers()
+    m = xs[0].numel()
+    eb = float(torch.tensor(2e-4, dtype=torch.float32))
+    ws = u8(zc.zc_workspace_bytes(m, 8))
+    streams = []
+    for x in xs:
+        st, buf, total = compress_async(x, eb, ws)
+        assert st == ZC_OK
+        streams.append(Stream(buf[:total].clone(), total, m))
+    red = u8(zc.zc_compress_bound(m))
+    st, _ = zc.zc_reduce_compressed([s.buf for s in streams], [s.total for s in streams], red, ws, sync=False)
+    assert st == ZC_OK
+    st, total = zc.zc_finish(ws)
+    assert st == ZC_OK
+    r = Stream(red, total, m)
+    check_header_and_sizes(r, eb, nsum=8)
+    y = torch.empty(m, dtype=torch.float32, device=DEV)
+    st, n_out = decompress_async(red, total, y, ws)
+    assert st == ZC_OK and n_out == m
+    exact = torch.zeros(m, dtype=torch.float64, device=DEV)
+    for x in xs:
+        exact += x.double()
+    assert float((y.double() - exact).abs().max()) <= 8 * eb
+    del exact
+    # sampled slices: the reference reduce of the operands' slices reproduces the GPU stream there
+    for b0 in sample_starts(m, rng, 4):
+        v0, v1 = 32 * b0, min(m, 32 * b0 + SLICE)
+        refs = [zcref.compress(x[v0:v1].cpu().numpy(), eb)[1] for x in xs]
+        st, ref, tot = zcref.reduce(refs)
+        assert st == 0
+        nbs = (v1 - v0 + 31) // 32
+        assert np.array_equal(r.widths[b0:b0 + nbs].cpu().numpy(), ref[32:32 + nbs]), f"widths differ at block {b0}"
+        o0 = 32 + pad16(nbs)
+        assert np.array_equal(r.outliers[b0:b0 + nbs].cpu().numpy(), ref[o0:o0 + 4 * nbs].view("<i4"))
+        assert np.array_equal(r.payload_of(b0, b0 + nbs), ref[tables_end(nbs):tot]), f"payload differs at block {b0}"
+
+
+def test_hard_mix_256M(zcref):
+    """Configuration 5: steps, spikes and exactly constant blocks at rel 1e-5."""
+    rng = np.random.default_rng(5)
+    n = 1 << 28
+    x = synth.hard_mix(n, seed=0, device=DEV)
+    eb = synth.abs_bound(x, 1e-5)
+    ws = u8(zc.zc_workspace_bytes(n, 1))
+    st, buf, total = compress_async(x, eb, ws)
+    assert st == ZC_OK
+    s = Stream(buf, total, n)
+    check_header_and_sizes(s, eb)
+    # exactly constant blocks cost no payload
+    xb = x.reshape(-1, 32)
+    const_blocks = (xb == xb[:, :1]).all(dim=1)
+    assert float(const_blocks.float().mean()) > 0.09
+    assert not bool(s.widths[const_blocks].any())
+    assert int(s.widths.max()) >= 16          # the spikes make wide blocks
+    y = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    st, n_out = decompress_async(buf, total, y, ws)
+    assert st == ZC_OK and n_out == n
+    assert max_abs_err(x, y) <= eb
+    check_slices_against_reference(zcref, x, eb, s, y, rng)
+
+
+def test_largest_input(zcref):
+    """n = 2^31 - 77 (close to the largest size the interface takes, ragged): 64-bit offsets everywhere."""
+    rng = np.random.default_rng(6)
+    n = (1 << 31) - 77
+    x = torch.empty(n, dtype=torch.float32, device=DEV)
+    chunk = 1 << 27
+    for i in range(0, n, chunk):                   # smooth waves plus small noise, made in chunks
+        j = torch.arange(i, min(n, i + chunk), dtype=torch.float64, device=DEV)
+        v = torch.sin(j * (2 * np.pi / 1e3)) + torch.sin(j * (2 * np.pi / 1e5)) + 0.5 * torch.sin(j * (2 * np.pi / 7e7))
+        x[i:i + j.numel()] = (0.4 * v).to(torch.float32)
+        del j, v
+    g = torch.Generator(device=DEV)
+    g.manual_seed(6)
+    for i in range(0, n, chunk):
+        m = min(n, i + chunk) - i
+        x[i:i + m] += torch.randn(m, device=DEV, generator=g) * 0.08
+    eb = float(np.float32(1e-5))                   # widths around 15, a few beyond: the stream exceeds 2^32 bytes
+    assert float(x.abs().max()) <= eb * 2 ** 18    # inside the guaranteed domain
+    ws = u8(zc.zc_workspace_bytes(n, 1))
+    st, buf, total = compress_async(x, eb, ws)
+    assert st == ZC_OK
+    s = Stream(buf, total, n)
+    check_header_and_sizes(s, eb)
+    assert total > (1 << 32)
+    y = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    st, n_out = decompress_async(buf, total, y, ws)
+    assert st == ZC_OK and n_out == n
+    assert max_abs_err(x, y) <= eb
+    check_slices_against_reference(zcref, x, eb, s, y, rng, count=5)
