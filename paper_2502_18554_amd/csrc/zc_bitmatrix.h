@@ -91,11 +91,33 @@ ZC_HD inline void planes_from_deltas8(const int32_t (&d)[32], uint32_t (&out)[8]
   transpose8x8_quads(out);
 }
 
+// 16-bit fields, two per word: word j holds value j in its low half and value j + 16 in its
+// high half.  This is the form the compression kernel keeps a block in once its deltas are
+// known: half the registers of the deltas themselves.
+ZC_HD inline uint32_t field16_pair(int32_t lo, int32_t hi) {
+  return sign_magnitude_field<16>(lo) | (sign_magnitude_field<16>(hi) << 16);
+}
+
+// Widths up to 15, from the paired fields, in place: f[0..15) = planes 0..14, f[15] = sign word.
+ZC_HD inline void planes16_from_fields(uint32_t (&f)[16]) { transpose16x16_pairs(f); }
+
+// Widths up to 7, from the paired 16-bit fields: out[0..7) = planes 0..6, out[7] = sign word.
+// The fields are narrowed to 8 bits (sign moved from bit 15 to bit 7), four per word.
+ZC_HD inline void planes8_from_fields16(const uint32_t (&f)[16], uint32_t (&out)[8]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t a = (f[j] & 0x007F007Fu) | ((f[j] >> 8) & 0x00800080u);          // values j, j + 16
+    const uint32_t b = (f[j + 8] & 0x007F007Fu) | ((f[j + 8] >> 8) & 0x00800080u);  // values j + 8, j + 24
+    out[j] = a | (b << 8);
+  }
+  transpose8x8_quads(out);
+}
+
 // Widths up to 15: out[0..15) = planes 0..14, out[15] = sign word.
 ZC_HD inline void planes_from_deltas16(const int32_t (&d)[32], uint32_t (&out)[16]) {
 #pragma unroll
-  for (int j = 0; j < 16; ++j) out[j] = sign_magnitude_field<16>(d[j]) | (sign_magnitude_field<16>(d[j + 16]) << 16);
-  transpose16x16_pairs(out);
+  for (int j = 0; j < 16; ++j) out[j] = field16_pair(d[j], d[j + 16]);
+  planes16_from_fields(out);
 }
 
 // Any width: lo[0..16) = planes 0..15; hi[0..15) = planes 16..30, hi[15] = sign word.

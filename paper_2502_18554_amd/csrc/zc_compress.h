@@ -20,6 +20,9 @@ namespace zc {
 // twice the size of the other kernels' tiles (512 blocks, 64 KiB of input); 1024 blocks
 // measured slower, because a compute unit then holds a single workgroup.
 constexpr int kPackWaves = 8;
+#ifndef ZC_C_OCC
+#define ZC_C_OCC 4
+#endif
 constexpr int kPackThreads = kPackWaves * 64;
 constexpr int kPackBlocks = kPackWaves * kWaveBlocks;
 constexpr int kPackValues = kPackBlocks * kBlockValues;
@@ -110,12 +113,11 @@ __device__ inline void load_raw(const CompressArgs& a, u64 wblock0, int lane, fl
   }
 }
 
-// Quantise the wave's values where they landed, transpose the codes through LDS so that one
-// lane owns one block, and take the Lorenzo delta.  Leaves in d[j] delta j of the lane's
-// block (d[0] = 0) and returns the block's first code (the outlier).
+// Quantise the wave's values where they landed and transpose the codes through LDS so that one
+// lane owns one block: q[j] = code j of the lane's block.
 template <bool FULL>
-__device__ inline i32 block_deltas(const CompressArgs& a, const float4 (&x)[8], u64 wblock0, int lane, u32* wl,
-                                   i32 (&d)[32], u32& err) {
+__device__ inline void block_codes(const CompressArgs& a, const float4 (&x)[8], u64 wblock0, int lane, u32* wl,
+                                   i32 (&q)[32], u32& err) {
   // Some value of this wave outside the screened domain: the checked arithmetic for all of it.
   bool flagged = false;
 #pragma unroll
@@ -124,7 +126,6 @@ __device__ inline i32 block_deltas(const CompressArgs& a, const float4 (&x)[8], 
   const bool checked = __any(flagged);
 
   // Loads 0..3 hold blocks 0..31 (lanes 0..31), loads 4..7 blocks 32..63.
-  i32 q[32];
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
 #pragma unroll
@@ -141,24 +142,116 @@ __device__ inline i32 block_deltas(const CompressArgs& a, const float4 (&x)[8], 
     }
     wave_lds_sync();
   }
-  const u64 b = wblock0 + u64(lane);
   if (!FULL) {
     // the last block repeats its last code up to 32 values
+    const u64 b = wblock0 + u64(lane);
     const u64 cnt = b < a.nb ? a.n - b * kBlockValues : 0;
 #pragma unroll
     for (int j = 1; j < 32; ++j) q[j] = u64(j) < cnt ? q[j] : q[j - 1];
   }
-  d[0] = 0;
+}
+
+// The block as the kernel keeps it: the Lorenzo deltas (d0 = 0) as sign-magnitude fields of
+// 16 bits, two per word (exact for widths up to 15), the OR of their magnitudes, which gives
+// the width, and the first code (the outlier).
+struct BlockFields {
+  u32 f[16];
+  u32 any;
+  i32 outlier;
+};
+
+template <bool FULL>
+__device__ inline void block_fields(const CompressArgs& a, const float4 (&x)[8], u64 wblock0, int lane, u32* wl,
+                                    BlockFields& bf, u32& err) {
+  i32 q[32];
+  block_codes<FULL>(a, x, wblock0, lane, wl, q, err);
+  bf.outlier = q[0];
+  u32 any = 0;
 #pragma unroll
-  for (int j = 1; j < 32; ++j) d[j] = q[j] - q[j - 1];
-  return q[0];
+  for (int j = 0; j < 16; ++j) {
+    const i32 lo = j ? q[j] - q[j - 1] : 0;
+    const i32 hi = q[j + 16] - q[j + 15];
+    any |= u32(lo < 0 ? -lo : lo) | u32(hi < 0 ? -hi : hi);
+    bf.f[j] = field16_pair(lo, hi);
+  }
+  bf.any = any;
+}
+
+// A tile that holds a block wider than 15 bits (an input outside the guaranteed domain).
+// The 16-bit fields are of no use then.  Once the tile's base offset is known, every wave
+// fetches and quantises its values again, half a wave of blocks at a time, and leaves the
+// codes in LDS; then 32 lanes take the 32 values of one block (two blocks per step), and a
+// plane word is simply the ballot of one bit of the magnitudes.  Slow, rare, and it needs
+// next to no registers, so it does not limit how many waves of the kernel fit a SIMD.
+template <bool FULL>
+__device__ inline void wide_tile(const CompressArgs& a, const PayloadSink& sink, const Placement& pl, u32 tile,
+                                 u32 ntiles, u64 wblock0, u32* wl, u64* sh_base, int wave, int lane) {
+  const u64 base = resolve_tile_base(sink, pl, tile, sh_base, wave, lane);
+  const u64 tend = tables_end(a.nb);
+  const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
+  u32* const payload = reinterpret_cast<u32*>(a.out + tend);
+  const u64 wave_first = base + pl.wave_off;                      // first payload word of this wave
+  const int j = lane & 31;                                        // value inside the block
+  u32 ignored = 0;                                                // errors were raised on the first pass
+
+#pragma nounroll
+  for (int half = 0; half < 2; ++half) {
+    // codes of blocks [32 half, 32 half + 32) of the wave -> LDS rows of 32 codes
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const u64 idx = wblock0 * kBlockValues + u64(1024 * half + 256 * i + 4 * lane);
+      float4 x;
+      if (FULL) {
+        x = *reinterpret_cast<const float4*>(a.in + idx);
+      } else {
+        x.x = idx + 0 < a.n ? a.in[idx + 0] : 0.0f;
+        x.y = idx + 1 < a.n ? a.in[idx + 1] : 0.0f;
+        x.z = idx + 2 < a.n ? a.in[idx + 2] : 0.0f;
+        x.w = idx + 3 < a.n ? a.in[idx + 3] : 0.0f;
+      }
+      *reinterpret_cast<int4*>(wl + (8 * i + (lane >> 3)) * kStageRow + 4 * (lane & 7)) = quantize4(x, a, true, ignored);
+    }
+    wave_lds_sync();
+#pragma nounroll
+    for (int bp = 0; bp < 16; ++bp) {
+      const int blk_a = 32 * half + 2 * bp;                       // blocks of this step, inside the wave
+      const u32 w_a = lane_value(pl.w, blk_a), w_b = lane_value(pl.w, blk_a + 1);
+      if ((w_a | w_b) == 0) continue;
+      const u32 off_a = lane_value(pl.off_in_wave, blk_a), off_b = lane_value(pl.off_in_wave, blk_a + 1);
+      const int row = 2 * bp + (lane >> 5);                       // LDS row of this lane's block
+      int jj = j;
+      if (!FULL) {                                                // the last block repeats its last code
+        const u64 b = wblock0 + u64(32 * half + row);
+        const u64 cnt = b < a.nb ? a.n - b * kBlockValues : 1;
+        if (u64(jj) >= cnt) jj = int(cnt) - 1;
+      }
+      const i32 q = i32(wl[row * kStageRow + jj]);
+      const i32 qp = i32(wl[row * kStageRow + (jj ? jj - 1 : 0)]);
+      const i32 d = j ? q - qp : 0;
+      const u32 mag = u32(d < 0 ? -d : d);
+      const bool first_lane = j == 0;
+      const u32 w_mine = lane < 32 ? w_a : w_b;
+      const u64 dst = wave_first + (lane < 32 ? off_a : off_b);   // this block's sign word
+      const u64 sign = __ballot(d < 0);
+      if (first_lane && w_mine && dst < cap_words) payload[dst] = lane < 32 ? u32(sign) : u32(sign >> 32);
+      const u32 w_top = w_a > w_b ? w_a : w_b;
+#pragma nounroll
+      for (u32 p = 0; p < w_top; ++p) {
+        const u64 plane = __ballot(((mag >> p) & 1u) != 0);
+        if (first_lane && p < w_mine && dst + 1 + p < cap_words)
+          payload[dst + 1 + p] = lane < 32 ? u32(plane) : u32(plane >> 32);
+      }
+    }
+    wave_lds_sync();
+  }
+  finish_stream(sink, pl, tile, ntiles, base);
 }
 
 // One workgroup per tile.  FULL = the launch covers tiles whose 8192 values all exist (pure
 // 16-byte loads, no tail), handed out by the per-XCD tickets over [first_tile, end_tile); the
 // ragged last tile of an input runs as a second launch of one workgroup with FULL = false.
 template <bool FULL>
-__global__ __launch_bounds__(kPackThreads, 16 / kPackWaves) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
+__global__ __launch_bounds__(kPackThreads, ZC_C_OCC) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
   __shared__ __attribute__((aligned(16))) u32 lds[kPackWaves * kWaveStage];
   __shared__ u32 sh_tile;
   __shared__ u32 sh_wave_total[kPackWaves];
@@ -186,17 +279,14 @@ __global__ __launch_bounds__(kPackThreads, 16 / kPackWaves) void compress_kernel
     float4 x[8];
     load_raw<FULL>(a, wblock0, lane, x);
 
-    i32 d[32];
-    const i32 outlier = block_deltas<FULL>(a, x, wblock0, lane, wl, d, err);
-    u32 any = 0;
-#pragma unroll
-    for (int j = 1; j < 32; ++j) any |= u32(d[j] < 0 ? -d[j] : d[j]);
+    BlockFields bf;
+    block_fields<FULL>(a, x, wblock0, lane, wl, bf, err);
     Placement pl;
-    pl.w = (active && any) ? 32u - u32(__builtin_clz(any)) : 0u;
+    pl.w = (active && bf.any) ? 32u - u32(__builtin_clz(bf.any)) : 0u;
     pl.wmax = wave_max_u32(pl.w);
     if (active && tables_fit) {
       a.out[kHeaderBytes + b] = u8(pl.w);
-      reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(a.nb))[b] = outlier;
+      reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(a.nb))[b] = bf.outlier;
     }
 
     // ---- place the block inside the wave and the wave inside the tile ----
@@ -225,44 +315,28 @@ __global__ __launch_bounds__(kPackThreads, 16 / kPackWaves) void compress_kernel
     const PayloadSink sink{a.out, a.out_cap, a.nb, a.ctl, a.desc};
     if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total);
 
-    // ---- deltas -> sign + plane words in registers, then the back half ----
-    // (the empty asm keeps the compiler from hoisting the sign-magnitude split of all 32
-    //  deltas above the branches, where it would hold twice as many registers)
+    // ---- fields -> sign + plane words in registers, then the back half ----
     if (tile_wmax <= 15) {
       u32 pw[16];          // pw[0] = sign, pw[1 + p] = plane p
       if (pl.wmax <= 7) {
         u32 r[8];
-#pragma unroll
-        for (int j = 0; j < 32; ++j) asm volatile("" : "+v"(d[j]));
-        planes_from_deltas8(d, r);
+        planes8_from_fields16(bf.f, r);
         pw[0] = r[7];
 #pragma unroll
         for (int p = 0; p < 7; ++p) pw[1 + p] = r[p];
 #pragma unroll
         for (int p = 8; p < 16; ++p) pw[p] = 0;
       } else {
-        u32 r[16];
+        planes16_from_fields(bf.f);
+        pw[0] = bf.f[15];
 #pragma unroll
-        for (int j = 0; j < 32; ++j) asm volatile("" : "+v"(d[j]));
-        planes_from_deltas16(d, r);
-        pw[0] = r[15];
-#pragma unroll
-        for (int p = 0; p < 15; ++p) pw[1 + p] = r[p];
+        for (int p = 0; p < 15; ++p) pw[1 + p] = bf.f[p];
       }
       finish_tile<16>(sink, [&](auto i) { return pw[decltype(i)::value]; }, pl, tile, ntiles, wl, &sh_base, wave, lane);
     } else {
-      // a tile with a block wider than 15 bits (input outside the guaranteed domain): all planes
-      u32 lo[16], hi[16];
-#pragma unroll
-      for (int j = 0; j < 32; ++j) asm volatile("" : "+v"(d[j]));
-      planes_from_deltas32(d, lo, hi);
-      auto word = [&](auto i) {
-        constexpr int I = decltype(i)::value;      // 0: sign, 1..16: low planes, 17..31: high planes
-        if constexpr (I == 0) return hi[15];
-        else if constexpr (I <= 16) return lo[I - 1];
-        else return hi[I - 17];
-      };
-      finish_tile<32>(sink, word, pl, tile, ntiles, wl, &sh_base, wave, lane);
+#ifndef ZC_NO_WIDE
+      wide_tile<FULL>(a, sink, pl, tile, ntiles, wblock0, wl, &sh_base, wave, lane);
+#endif
     }
   }
   if (err) atomicOr(&a.ctl->status, err);

@@ -58,14 +58,10 @@ __device__ inline void publish_tile_size(const PayloadSink& s, u32 tile, u32 til
   desc_store(s.desc + desc_slot(tile), (tile == 0 ? kDescPrefix : kDescAggregate) | u64(tile_total));
 }
 
-// Back half of a tile once the plane words sit in registers (`word(i)`: 0 = sign, 1 + p =
-// plane p) and its size is published: look back for the base offset, then move the payload
-// out through LDS, one half-wave of blocks at a time (the staging area `wl` of a wave holds
-// kWaveStage words).  Called by every wave of the workgroup; one barrier.
-template <int NW, typename WordFn>
-__device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
-                                   u32* wl, u64* sh_base, int wave, int lane) {
-  static_assert(32 * NW <= kWaveStage, "a half-wave of widest blocks must fit the staging area");
+// Base offset of the tile, in payload words: wave 0 looks back, everyone meets at one barrier.
+// The tile's size must have been published.  Called by every wave of the workgroup.
+__device__ inline u64 resolve_tile_base(const PayloadSink& s, const Placement& pl, u32 tile, u64* sh_base, int wave,
+                                        int lane) {
   if (wave == 0) {
     const u64 base = tile ? lookback_exclusive(s.desc, tile, &s.ctl->status) : 0;
     if (lane == 0) {
@@ -75,8 +71,28 @@ __device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Plac
   }
   __syncthreads();
   REC(tile, 5);
+  return *sh_base;
+}
 
-  const u64 base = *sh_base;
+// The last tile knows the size of the stream.
+__device__ inline void finish_stream(const PayloadSink& s, const Placement& pl, u32 tile, u32 ntiles, u64 base) {
+  if (tile == ntiles - 1 && threadIdx.x == 0) {
+    const u64 total = tables_end(s.nb) + 4 * (base + pl.tile_total);
+    s.ctl->result = total;
+    if (total > s.out_cap) atomicOr(&s.ctl->status, status_bit(ZC_ERR_CAPACITY));
+    if (s.out_cap >= kHeaderBytes) reinterpret_cast<u64*>(s.out)[3] = total;
+  }
+}
+
+// Back half of a tile once the plane words sit in registers (`word(i)`: 0 = sign, 1 + p =
+// plane p) and its size is published: look back for the base offset, then move the payload
+// out through LDS, one half-wave of blocks at a time (the staging area `wl` of a wave holds
+// kWaveStage words).  Called by every wave of the workgroup; one barrier.
+template <int NW, typename WordFn>
+__device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
+                                   u32* wl, u64* sh_base, int wave, int lane) {
+  static_assert(32 * NW <= kWaveStage, "a half-wave of widest blocks must fit the staging area");
+  const u64 base = resolve_tile_base(s, pl, tile, sh_base, wave, lane);
   const u64 tend = tables_end(s.nb);
   const u64 cap_words = s.out_cap > tend ? (s.out_cap - tend) / 4 : 0;
   u32* const payload = reinterpret_cast<u32*>(s.out + tend);
@@ -89,12 +105,7 @@ __device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Plac
     stage_and_copy_half<NW>(word, pl.w, (lane >> 5) == h, pl.off_in_wave - half_base[h], half_total[h], wl,
                             payload + d0, cap_words > d0 ? cap_words - d0 : 0, lane);
   }
-  if (tile == ntiles - 1 && threadIdx.x == 0) {
-    const u64 total = tend + 4 * (base + pl.tile_total);
-    s.ctl->result = total;
-    if (total > s.out_cap) atomicOr(&s.ctl->status, status_bit(ZC_ERR_CAPACITY));
-    if (s.out_cap >= kHeaderBytes) reinterpret_cast<u64*>(s.out)[3] = total;
-  }
+  finish_stream(s, pl, tile, ntiles, base);
 }
 
 }  // namespace zc

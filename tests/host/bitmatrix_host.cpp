@@ -14,6 +14,12 @@ void bm_planes_from_deltas(const int32_t* din, int cls, uint32_t* out) {
     zc::planes_from_deltas8(d, r);
     out[0] = r[7];
     for (int p = 0; p < 7; ++p) out[1 + p] = r[p];
+  } else if (cls == 816) {            // widths up to 7 by way of the paired 16-bit fields
+    uint32_t f[16], r[8];
+    for (int j = 0; j < 16; ++j) f[j] = zc::field16_pair(d[j], d[j + 16]);
+    zc::planes8_from_fields16(f, r);
+    out[0] = r[7];
+    for (int p = 0; p < 7; ++p) out[1 + p] = r[p];
   } else if (cls == 16) {
     uint32_t r[16];
     zc::planes_from_deltas16(d, r);
