@@ -9,7 +9,8 @@
 //   width <= 7  : four values per word (bytes), three stages on 8 words
 //   width <= 15 : two values per word (halves), four stages on 16 words
 //   wider       : the 16-bit form twice, for the low and the high half of the magnitudes
-// The sign rides as the top bit of each value's field and comes out as the last row.
+// Narrow values enter as two's complement fields, so the sign comes out as the last row and
+// the conversion between two's complement and sign + magnitude happens on the planes.
 // The same swaps undo themselves, so decompression runs the identical transposes.
 //
 // Everything here is plain integer C++ so that the host tests can exercise it too.
@@ -62,8 +63,47 @@ ZC_HD inline void transpose8x8_quads(uint32_t (&r)[8]) {
     if ((j & 1) == 0) swap_bits(r[j], r[j + 1], 1, 0x55555555u);
 }
 
+// ---- two's complement <-> sign + magnitude, on planes -------------------------------------
+// r[0..N-1) = planes of N-bit two's complement values (one bit of 32 values per word), r[N-1]
+// their sign plane.  Negating where the sign is set, with a ripple of carries over the planes,
+// turns them into magnitude planes and back: three operations per plane for 32 values, where
+// the same conversion value by value costs five operations per value.
+template <int N>
+ZC_HD inline void twos_planes_to_magnitude(uint32_t (&r)[N]) {
+  const uint32_t s = r[N - 1];
+  uint32_t carry = s;                       // (bits ^ s) + s
+#pragma unroll
+  for (int p = 0; p < N - 1; ++p) {
+    const uint32_t t = r[p] ^ s;
+    r[p] = t ^ carry;
+    carry &= t;
+  }
+}
+// The inverse is the same operation: negate the magnitudes where the sign is set.
+template <int N>
+ZC_HD inline void magnitude_planes_to_twos(uint32_t (&r)[N]) { twos_planes_to_magnitude<N>(r); }
+
+// Low 16 bits of two values in one word / low 8 bits of four values in one word.
+ZC_HD inline uint32_t pack16(uint32_t lo, uint32_t hi) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+#else
+  return (lo & 0xFFFFu) | (hi << 16);
+#endif
+}
+// From two words of paired 16-bit fields (values a, c and b, d): bytes a, b, c, d.
+ZC_HD inline uint32_t narrow_pairs_to_bytes(uint32_t ac, uint32_t bd) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_amdgcn_perm(bd, ac, 0x06020400u);
+#else
+  return (ac & 0xFFu) | ((bd & 0xFFu) << 8) | (((ac >> 16) & 0xFFu) << 16) | (((bd >> 16) & 0xFFu) << 24);
+#endif
+}
+
 // ---- values -> planes -------------------------------------------------------------------
 // d[j] = delta j in two's complement.  The planes hold its magnitude; the sign word its sign.
+// Narrow blocks go through two's complement fields (a plain truncation of the delta), the
+// bit-matrix transpose, and the conversion to magnitudes on the planes.
 
 // Field of `bits` bits: magnitude in the low bits - 1, sign in the top bit.
 template <int BITS>
@@ -79,38 +119,32 @@ ZC_HD inline int32_t delta_from_field(uint32_t f) {
   return int32_t((mag ^ m) - m);
 }
 
-// Widths up to 7: out[0..7) = planes 0..6, out[7] = sign word.
-ZC_HD inline void planes_from_deltas8(const int32_t (&d)[32], uint32_t (&out)[8]) {
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    uint32_t w = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) w |= sign_magnitude_field<8>(d[j + 8 * k]) << (8 * k);
-    out[j] = w;
-  }
-  transpose8x8_quads(out);
-}
-
-// 16-bit fields, two per word: word j holds value j in its low half and value j + 16 in its
-// high half.  This is the form the compression kernel keeps a block in once its deltas are
-// known: half the registers of the deltas themselves.
-ZC_HD inline uint32_t field16_pair(int32_t lo, int32_t hi) {
-  return sign_magnitude_field<16>(lo) | (sign_magnitude_field<16>(hi) << 16);
-}
+// Paired 16-bit two's complement fields: word j holds delta j in its low half and delta
+// j + 16 in its high half (exact for |delta| < 2^15).  This is the form the compression
+// kernel keeps a block in once its deltas are known: half the registers of the deltas.
+ZC_HD inline uint32_t field16_pair(int32_t lo, int32_t hi) { return pack16(uint32_t(lo), uint32_t(hi)); }
 
 // Widths up to 15, from the paired fields, in place: f[0..15) = planes 0..14, f[15] = sign word.
-ZC_HD inline void planes16_from_fields(uint32_t (&f)[16]) { transpose16x16_pairs(f); }
+ZC_HD inline void planes16_from_fields(uint32_t (&f)[16]) {
+  transpose16x16_pairs(f);
+  twos_planes_to_magnitude<16>(f);
+}
 
 // Widths up to 7, from the paired 16-bit fields: out[0..7) = planes 0..6, out[7] = sign word.
-// The fields are narrowed to 8 bits (sign moved from bit 15 to bit 7), four per word.
+// The fields are narrowed to 8 bits, four per word (byte k of word j = delta j + 8k).
 ZC_HD inline void planes8_from_fields16(const uint32_t (&f)[16], uint32_t (&out)[8]) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint32_t a = (f[j] & 0x007F007Fu) | ((f[j] >> 8) & 0x00800080u);          // values j, j + 16
-    const uint32_t b = (f[j + 8] & 0x007F007Fu) | ((f[j + 8] >> 8) & 0x00800080u);  // values j + 8, j + 24
-    out[j] = a | (b << 8);
-  }
+  for (int j = 0; j < 8; ++j) out[j] = narrow_pairs_to_bytes(f[j], f[j + 8]);
   transpose8x8_quads(out);
+  twos_planes_to_magnitude<8>(out);
+}
+
+// Widths up to 7: out[0..7) = planes 0..6, out[7] = sign word.
+ZC_HD inline void planes_from_deltas8(const int32_t (&d)[32], uint32_t (&out)[8]) {
+  uint32_t f[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) f[j] = field16_pair(d[j], d[j + 16]);
+  planes8_from_fields16(f, out);
 }
 
 // Widths up to 15: out[0..15) = planes 0..14, out[15] = sign word.
@@ -134,21 +168,25 @@ ZC_HD inline void planes_from_deltas32(const int32_t (&d)[32], uint32_t (&lo)[16
 
 // ---- planes -> values -------------------------------------------------------------------
 
+// in[0..7) = planes 0..6, in[7] = sign word.
 ZC_HD inline void deltas_from_planes8(uint32_t (&in)[8], int32_t (&d)[32]) {
+  magnitude_planes_to_twos<8>(in);
   transpose8x8_quads(in);
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) d[j + 8 * k] = delta_from_field<8>((in[j] >> (8 * k)) & 0xFFu);
+    for (int k = 0; k < 4; ++k) d[j + 8 * k] = int32_t(in[j] << (24 - 8 * k)) >> 24;   // sign-extend byte k
   }
 }
 
+// in[0..15) = planes 0..14, in[15] = sign word.
 ZC_HD inline void deltas_from_planes16(uint32_t (&in)[16], int32_t (&d)[32]) {
+  magnitude_planes_to_twos<16>(in);
   transpose16x16_pairs(in);
 #pragma unroll
   for (int j = 0; j < 16; ++j) {
-    d[j] = delta_from_field<16>(in[j] & 0xFFFFu);
-    d[j + 16] = delta_from_field<16>(in[j] >> 16);
+    d[j] = int32_t(in[j] << 16) >> 16;
+    d[j + 16] = int32_t(in[j]) >> 16;
   }
 }
 

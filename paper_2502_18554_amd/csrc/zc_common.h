@@ -175,6 +175,22 @@ __device__ inline u32 take_tile(Control* ctl, u32 ntiles, u32 first_shard) {
   return kNoTile;
 }
 
+// Hand-out for persistent workgroups, which pick their shard themselves (shard < nshards <=
+// kTicketShards): counter y hands out tiles y, y + nshards, ...
+__device__ inline u32 claim_from_shard(Control* ctl, u32 shard, u32 nshards, u32 ntiles) {
+  if (shard >= ntiles) return kNoTile;
+  const u64 t = u64(atomicAdd(ticket_counter(ctl, shard), 1u)) * nshards + shard;
+  return t < ntiles ? u32(t) : kNoTile;
+}
+__device__ inline u32 claim_any_shard(Control* ctl, u32 first_shard, u32 nshards, u32 ntiles) {
+  for (u32 i = 0; i < nshards; ++i) {
+    const u32 y = first_shard + i < nshards ? first_shard + i : first_shard + i - nshards;
+    const u32 t = claim_from_shard(ctl, y, nshards, ntiles);
+    if (t != kNoTile) return t;
+  }
+  return kNoTile;
+}
+
 // Lane-crossing primitives are built from DPP moves and v_readlane, which need no address
 // registers and do not go through the LDS pipe (unlike ds_bpermute shuffles).
 template <int CTRL>
@@ -261,6 +277,14 @@ constexpr int kStageRow = 36;
 constexpr int kWaveStage = 32 * kStageRow;              // 1152 words = 4.5 KiB per wave
 static_assert(kWaveStage >= 32 * 33, "one half-wave of worst-case blocks must fit the staging area");
 
+// Workgroup barrier that orders LDS accesses only: global loads and stores that are in flight
+// stay in flight (a full __syncthreads waits for every outstanding vector memory operation).
+__device__ inline void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __device__ inline void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -281,39 +305,56 @@ __device__ inline u32 desc32_load(const u32* d) {
 // bounded anyway and raises ZC_ERR_HIP in *status if the bound is hit.
 // A poll inspects the 32 nearest predecessors: measured on the 512^3 benchmark, wider polls
 // only add memory requests without finishing earlier.
-constexpr int kLookLanes = 32;
+#ifndef ZC_LOOK_LANES
+#define ZC_LOOK_LANES 32
+#endif
+constexpr int kLookLanes = ZC_LOOK_LANES;
 
-__device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status) {
+// One poll: lane l < kLookLanes fetches the descriptor of tile `look` - l.
+__device__ inline u64 lookback_poll(const u64* desc, i64 look) {
+  const i64 idx = look - lane_id();
+  u64 d = kDescPrefix;                       // "tile -1" has prefix 0
+  if (lane_id() < kLookLanes && idx >= 0) d = desc_load(desc + desc_slot(u64(idx)));
+  return d;
+}
+
+// `first` = lookback_poll(desc, tile - 1), issued by the caller, who may put other memory
+// operations between that poll and this call so that they overlap with its round trip.
+__device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status, u64 first) {
   const int lane = lane_id();
   const u64 lanes_mask = kLookLanes == 64 ? ~u64(0) : ((u64(1) << kLookLanes) - 1);
   u64 excl = 0;
   i64 look = i64(tile) - 1;                  // lane 0 inspects the nearest predecessor
   u32 spins = 0;
+  u64 d = first;
   while (true) {
-    const i64 idx = look - lane;
-    u64 d = kDescPrefix;                     // "tile -1" has prefix 0
-    if (lane < kLookLanes && idx >= 0) d = desc_load(desc + desc_slot(u64(idx)));
     const u32 state = u32(d >> 62);
     const u64 has_prefix = __ballot(state == 2) & lanes_mask;
     const u64 is_empty = __ballot(state == 0) & lanes_mask;
-    const int first = has_prefix ? __builtin_ctzll(has_prefix) : kLookLanes - 1;
-    const u64 needed = first == 63 ? ~u64(0) : ((u64(2) << first) - 1);   // lanes 0..first
+    const int first_prefix = has_prefix ? __builtin_ctzll(has_prefix) : kLookLanes - 1;
+    const u64 needed = first_prefix == 63 ? ~u64(0) : ((u64(2) << first_prefix) - 1);   // lanes 0..first_prefix
     if (is_empty & needed) {
       if (++spins > kSpinLimit) {
         if (lane == 0) atomicOr(status, status_bit(ZC_ERR_HIP));
         return excl;
       }
       __builtin_amdgcn_s_sleep(1);
+      d = lookback_poll(desc, look);
       continue;
     }
-    // lanes before `first` hold tile aggregates (small); lane `first` may hold a prefix (64-bit)
-    excl += wave_sum_u32(lane < first || (lane == first && !has_prefix) ? u32(d) : 0u);
+    // lanes before `first_prefix` hold tile aggregates (small); lane `first_prefix` may hold a prefix (64-bit)
+    excl += wave_sum_u32(lane < first_prefix || (lane == first_prefix && !has_prefix) ? u32(d) : 0u);
     if (has_prefix) {
-      const u64 p = u64(lane_value(u32(d), first)) | (u64(lane_value(u32(d >> 32), first)) << 32);
+      const u64 p = u64(lane_value(u32(d), first_prefix)) | (u64(lane_value(u32(d >> 32), first_prefix)) << 32);
       return excl + (p & kDescValueMask);
     }
     look -= kLookLanes;                      // a complete window is final: aggregates never change
+    d = lookback_poll(desc, look);
   }
+}
+
+__device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status) {
+  return lookback_exclusive(desc, tile, status, lookback_poll(desc, i64(tile) - 1));
 }
 
 }  // namespace zc

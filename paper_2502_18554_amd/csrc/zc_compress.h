@@ -19,7 +19,10 @@ namespace zc {
 // look-back scan.  Every tile pays the latency of that scan once, so compression uses tiles
 // twice the size of the other kernels' tiles (512 blocks, 64 KiB of input); 1024 blocks
 // measured slower, because a compute unit then holds a single workgroup.
-constexpr int kPackWaves = 8;
+#ifndef ZC_PACK_WAVES
+#define ZC_PACK_WAVES 8
+#endif
+constexpr int kPackWaves = ZC_PACK_WAVES;
 #ifndef ZC_C_OCC
 #define ZC_C_OCC 4
 #endif
@@ -151,9 +154,9 @@ __device__ inline void block_codes(const CompressArgs& a, const float4 (&x)[8], 
   }
 }
 
-// The block as the kernel keeps it: the Lorenzo deltas (d0 = 0) as sign-magnitude fields of
-// 16 bits, two per word (exact for widths up to 15), the OR of their magnitudes, which gives
-// the width, and the first code (the outlier).
+// The block as the kernel keeps it: the Lorenzo deltas (d0 = 0) as two's complement fields of
+// 16 bits, two per word (exact for widths up to 15), their largest magnitude, which gives the
+// width, and the first code (the outlier).
 struct BlockFields {
   u32 f[16];
   u32 any;
@@ -166,14 +169,19 @@ __device__ inline void block_fields(const CompressArgs& a, const float4 (&x)[8],
   i32 q[32];
   block_codes<FULL>(a, x, wblock0, lane, wl, q, err);
   bf.outlier = q[0];
-  u32 any = 0;
+  i32 top = 0, bottom = 0;              // largest and smallest delta (d0 = 0 is one of them)
 #pragma unroll
   for (int j = 0; j < 16; ++j) {
     const i32 lo = j ? q[j] - q[j - 1] : 0;
     const i32 hi = q[j + 16] - q[j + 15];
-    any |= u32(lo < 0 ? -lo : lo) | u32(hi < 0 ? -hi : hi);
+    top = max(top, max(lo, hi));
+    bottom = min(bottom, min(lo, hi));
     bf.f[j] = field16_pair(lo, hi);
+    // (pins the field here: left to itself the compiler keeps all 32 deltas alive instead and
+    //  builds the fields where they are used, after the barrier)
+    asm volatile("" : "+v"(bf.f[j]));
   }
+  const u32 any = max(u32(top), u32(-bottom));   // largest magnitude: its bit length is the width
   bf.any = any;
 }
 

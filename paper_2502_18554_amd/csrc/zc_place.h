@@ -60,18 +60,29 @@ __device__ inline void publish_tile_size(const PayloadSink& s, u32 tile, u32 til
 
 // Base offset of the tile, in payload words: wave 0 looks back, everyone meets at one barrier.
 // The tile's size must have been published.  Called by every wave of the workgroup.
+// `meanwhile()` runs in every wave once wave 0 has sent its first poll: memory operations
+// issued there overlap with the poll's round trip instead of queueing in front of it.
+template <typename MeanwhileFn>
 __device__ inline u64 resolve_tile_base(const PayloadSink& s, const Placement& pl, u32 tile, u64* sh_base, int wave,
-                                        int lane) {
+                                        int lane, MeanwhileFn meanwhile) {
+  u64 first = 0;
+  if (wave == 0 && tile) first = lookback_poll(s.desc, i64(tile) - 1);
+  meanwhile();
   if (wave == 0) {
-    const u64 base = tile ? lookback_exclusive(s.desc, tile, &s.ctl->status) : 0;
+    const u64 base = tile ? lookback_exclusive(s.desc, tile, &s.ctl->status, first) : 0;
     if (lane == 0) {
       if (tile) desc_store(s.desc + desc_slot(tile), kDescPrefix | (base + pl.tile_total));
       *sh_base = base;
     }
   }
-  __syncthreads();
+  lds_barrier();                // only sh_base passes through it
   REC(tile, 5);
   return *sh_base;
+}
+
+__device__ inline u64 resolve_tile_base(const PayloadSink& s, const Placement& pl, u32 tile, u64* sh_base, int wave,
+                                        int lane) {
+  return resolve_tile_base(s, pl, tile, sh_base, wave, lane, [] {});
 }
 
 // The last tile knows the size of the stream.
@@ -88,11 +99,11 @@ __device__ inline void finish_stream(const PayloadSink& s, const Placement& pl, 
 // plane p) and its size is published: look back for the base offset, then move the payload
 // out through LDS, one half-wave of blocks at a time (the staging area `wl` of a wave holds
 // kWaveStage words).  Called by every wave of the workgroup; one barrier.
-template <int NW, typename WordFn>
+template <int NW, typename WordFn, typename MeanwhileFn>
 __device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
-                                   u32* wl, u64* sh_base, int wave, int lane) {
+                                   u32* wl, u64* sh_base, int wave, int lane, MeanwhileFn meanwhile) {
   static_assert(32 * NW <= kWaveStage, "a half-wave of widest blocks must fit the staging area");
-  const u64 base = resolve_tile_base(s, pl, tile, sh_base, wave, lane);
+  const u64 base = resolve_tile_base(s, pl, tile, sh_base, wave, lane, meanwhile);
   const u64 tend = tables_end(s.nb);
   const u64 cap_words = s.out_cap > tend ? (s.out_cap - tend) / 4 : 0;
   u32* const payload = reinterpret_cast<u32*>(s.out + tend);
@@ -106,6 +117,12 @@ __device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Plac
                             payload + d0, cap_words > d0 ? cap_words - d0 : 0, lane);
   }
   finish_stream(s, pl, tile, ntiles, base);
+}
+
+template <int NW, typename WordFn>
+__device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
+                                   u32* wl, u64* sh_base, int wave, int lane) {
+  finish_tile<NW>(s, word, pl, tile, ntiles, wl, sh_base, wave, lane, [] {});
 }
 
 }  // namespace zc
