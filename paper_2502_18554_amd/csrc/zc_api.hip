@@ -210,7 +210,6 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
   if (tiles > tiles_out) tiles = tiles_out;
   if (tiles > l.tiles_cap) tiles = l.tiles_cap;
   if (tiles < 1) tiles = 1;
-  launch_init(l, 0, nullptr, 0, 0, 0, stream);
   ScanArgs sa;
   sa.streams[0].base = static_cast<const u8*>(d_in);
   sa.streams[0].bytes = in_bytes;
@@ -218,8 +217,10 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
   sa.check_match = 0;
   sa.index = l.index;
   sa.ctl = l.ctl;
+  sa.desc = nullptr;
+  sa.ndesc = 0;
   hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), 1), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(span_scan_kernel, dim3(1), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(index_prep_kernel, dim3(1), dim3(256), 0, stream, sa);
   DecompressArgs da;
   da.in = sa.streams[0];
   da.out = d_out;
@@ -251,7 +252,6 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
     if (t < tiles) tiles = t;
   }
   if (tiles < 1) tiles = 1;
-  launch_init(l, u32(tiles), nullptr, 0, 0, 0, stream);
   ScanArgs sa;
   ReduceArgs ra;
   for (int i = 0; i < k; ++i) {
@@ -263,8 +263,10 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   sa.check_match = 1;
   sa.index = l.index;
   sa.ctl = l.ctl;
+  sa.desc = l.desc;
+  sa.ndesc = u32(tiles);
   hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), u32(k)), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(span_scan_kernel, dim3(u32(k)), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(index_prep_kernel, dim3(u32((tiles + 255) / 256 > 64 ? 64 : (tiles + 255) / 256)), dim3(256), 0, stream, sa);
   ra.k = k;
   ra.index = l.index;
   ra.out = static_cast<u8*>(d_out);
@@ -356,7 +358,6 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
   u64 tiles = num_tiles(blocks_bound(in_bytes));
   if (tiles > l.tiles_cap) tiles = l.tiles_cap;
   if (tiles < 1) tiles = 1;
-  launch_init(l, 0, nullptr, 0, 0, 0, stream);
   ScanArgs sa;
   sa.streams[0].base = static_cast<const u8*>(d_in);
   sa.streams[0].bytes = in_bytes;
@@ -364,8 +365,10 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
   sa.check_match = 0;
   sa.index = l.index;
   sa.ctl = l.ctl;
+  sa.desc = nullptr;
+  sa.ndesc = 0;
   hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), 1), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(span_scan_kernel, dim3(1), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(index_prep_kernel, dim3(1), dim3(256), 0, stream, sa);
   OffsetsArgs oa;
   oa.in = sa.streams[0];
   oa.index = l.index;

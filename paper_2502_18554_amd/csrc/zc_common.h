@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "../../include/zc.h"
 
 namespace zc {
@@ -85,6 +87,7 @@ struct StreamIndex {
   u32* seg_off;     // [k][4 * tiles_cap]   payload word offset of each segment inside its scan group
   u32* grp_off;     // [k][groups_cap]      payload word offset of each scan group inside its span
   u32* span_off;    // [k][spans_cap]       payload word offset of each span (its size between the two index kernels)
+  u32* span_flags;  // [k][spans_cap]       what stream_index_kernel saw in each span
   u64 tiles_cap;
   u64 groups_cap;
   u64 spans_cap;
@@ -92,7 +95,7 @@ struct StreamIndex {
 
 // How a workspace of ws_bytes is carved up for calls with k input streams:
 //   Control | tickets | desc[tiles_cap] (128 B each) | seg_off[k][4 * tiles_cap] | grp_off[k][groups_cap] |
-//   span_off[k][spans_cap]
+//   span_off[k][spans_cap] | span_flags[k][spans_cap]
 // tiles_cap follows from ws_bytes alone, so kernels can refuse streams that do not fit.
 struct WorkspaceLayout {
   u64 tiles_cap;
@@ -102,7 +105,7 @@ struct WorkspaceLayout {
 };
 
 constexpr u64 kDescBytes = 128;           // per tile, see kDescStride
-constexpr u64 kWsFixed = sizeof(Control) + kTicketBytes + 8 * ZC_MAX_K + 64;   // control, tickets, the +1 of every grp_off and span_sum row, padding
+constexpr u64 kWsFixed = sizeof(Control) + kTicketBytes + 12 * ZC_MAX_K + 64;   // control, tickets, the +1 of every grp_off, span_off and span_flags row, padding
 
 __host__ inline u64 workspace_bytes(u64 n_max, int k_max) {
   if (k_max < 1) k_max = 1;
@@ -127,6 +130,8 @@ __host__ inline WorkspaceLayout workspace_layout(void* d_ws, u64 ws_bytes, int k
   l.index.grp_off = reinterpret_cast<u32*>(p);
   p += 4 * l.index.groups_cap * u64(k);
   l.index.span_off = reinterpret_cast<u32*>(p);
+  p += 4 * l.index.spans_cap * u64(k);
+  l.index.span_flags = reinterpret_cast<u32*>(p);
   return l;
 }
 
@@ -175,22 +180,6 @@ __device__ inline u32 take_tile(Control* ctl, u32 ntiles, u32 first_shard) {
   return kNoTile;
 }
 
-// Hand-out for persistent workgroups, which pick their shard themselves (shard < nshards <=
-// kTicketShards): counter y hands out tiles y, y + nshards, ...
-__device__ inline u32 claim_from_shard(Control* ctl, u32 shard, u32 nshards, u32 ntiles) {
-  if (shard >= ntiles) return kNoTile;
-  const u64 t = u64(atomicAdd(ticket_counter(ctl, shard), 1u)) * nshards + shard;
-  return t < ntiles ? u32(t) : kNoTile;
-}
-__device__ inline u32 claim_any_shard(Control* ctl, u32 first_shard, u32 nshards, u32 ntiles) {
-  for (u32 i = 0; i < nshards; ++i) {
-    const u32 y = first_shard + i < nshards ? first_shard + i : first_shard + i - nshards;
-    const u32 t = claim_from_shard(ctl, y, nshards, ntiles);
-    if (t != kNoTile) return t;
-  }
-  return kNoTile;
-}
-
 // Lane-crossing primitives are built from DPP moves and v_readlane, which need no address
 // registers and do not go through the LDS pipe (unlike ds_bpermute shuffles).
 template <int CTRL>
@@ -207,6 +196,16 @@ __device__ inline u32 lane_value(u32 v, int lane) { return u32(__builtin_amdgcn_
 // A value known to be the same in every lane, moved to a scalar register so that branches on
 // it are scalar branches.
 __device__ inline u32 uniform(u32 v) { return u32(__builtin_amdgcn_readfirstlane(int(v))); }
+__device__ inline u64 uniform64(u64 v) { return u64(uniform(u32(v))) | (u64(uniform(u32(v >> 32))) << 32); }
+// Index of the calling wave in its workgroup, as a scalar.
+__device__ inline int wave_id() { return int(uniform(threadIdx.x >> 6)); }
+// base + byte offset, for a base that is the same in every lane: it stays in scalar registers
+// and the access needs one 32-bit vector register for the offset instead of a 64-bit address.
+template <typename T>
+__device__ inline T* at_bytes(T* uniform_base, u32 byte_offset) {
+  using Byte = std::conditional_t<std::is_const_v<T>, const char, char>;
+  return reinterpret_cast<T*>(reinterpret_cast<Byte*>(uniform_base) + byte_offset);
+}
 
 // Sum over the 64 lanes (result uniform).
 __device__ inline u32 wave_sum_u32(u32 v) {
@@ -305,10 +304,7 @@ __device__ inline u32 desc32_load(const u32* d) {
 // bounded anyway and raises ZC_ERR_HIP in *status if the bound is hit.
 // A poll inspects the 32 nearest predecessors: measured on the 512^3 benchmark, wider polls
 // only add memory requests without finishing earlier.
-#ifndef ZC_LOOK_LANES
-#define ZC_LOOK_LANES 32
-#endif
-constexpr int kLookLanes = ZC_LOOK_LANES;
+constexpr int kLookLanes = 32;
 
 // One poll: lane l < kLookLanes fetches the descriptor of tile `look` - l.
 __device__ inline u64 lookback_poll(const u64* desc, i64 look) {

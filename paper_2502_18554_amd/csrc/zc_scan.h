@@ -5,8 +5,9 @@
 //
 // stream_index_kernel records the offset of every segment inside its scan group, of every
 // group inside its index span and the size of every span, and validates header and width
-// bytes on the way; span_scan_kernel then turns the span sizes into offsets and compares the
-// header's total_bytes with the indexed payload.  No workgroup waits for, or counts, another.
+// bytes on the way; index_prep_kernel then turns the span sizes into offsets, compares the
+// header's total_bytes with the indexed payload and writes the control block.  No workgroup
+// waits for, or counts, another, and neither kernel needs anything cleared beforehand.
 #pragma once
 
 #include "zc_common.h"
@@ -55,7 +56,17 @@ struct ScanArgs {
   int check_match;   // reduce: every stream must have the n and eb_bits of stream 0
   StreamIndex index;
   Control* ctl;
+  u64* desc;         // look-back descriptors to clear for the kernel that follows (may be null)
+  u32 ndesc;
 };
+
+constexpr u32 kSpanBadWidth = 1u;   // per-span flags left by stream_index_kernel: a width byte above 31
+constexpr u32 kSpanWide = 2u;       //                                               a width byte above 15
+
+// Whether the caller's workspace has room for the index of this stream.
+__device__ inline bool stream_fits(const ParsedHeader& h, const StreamIndex& ix) {
+  return num_tiles(h.nb) <= ix.tiles_cap && num_scan_groups(h.nb) <= ix.groups_cap && num_spans(h.nb) <= ix.spans_cap;
+}
 
 // Payload word offset of segment `seg` of stream `s`: the offset of its index span, plus its
 // group's offset in the span, plus its own offset in the group.  Three independent loads.
@@ -80,29 +91,18 @@ __device__ inline u32 psize_words4(u32 x, bool& bad, bool& wide) {
 // offset inside the group, every group its offset inside the span, and the span its size.
 __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
   __shared__ u32 sh_wave[kIndexGroups][4];
+  __shared__ u32 sh_flags;
   const int s = blockIdx.y;
   const StreamRef st = a.streams[s];
   const ParsedHeader h = parse_header(st);
-  if (!h.ok) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
-    return;
-  }
+  if (!h.ok || !stream_fits(h, a.index)) return;        // index_prep_kernel reports both
   const u64 ngroups = num_scan_groups(h.nb);
-  const bool fits = num_tiles(h.nb) <= a.index.tiles_cap && ngroups <= a.index.groups_cap &&
-                    num_spans(h.nb) <= a.index.spans_cap;
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    if (!fits) atomicOr(&a.ctl->status, status_bit(ZC_ERR_ARG));
-    if (a.check_match && s > 0) {
-      const ParsedHeader h0 = parse_header(a.streams[0]);
-      if (h0.ok && (h0.n != h.n || h0.eb_bits != h.eb_bits)) atomicOr(&a.ctl->status, status_bit(ZC_ERR_MISMATCH));
-    }
-  }
-  if (!fits) return;
   const u64 group0 = u64(blockIdx.x) * kIndexGroups;
   if (group0 >= ngroups) return;
 
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
+  if (threadIdx.x == 0) sh_flags = 0;
   const u8* widths = st.base + kHeaderBytes;
   // all loads first: the table is padded to a multiple of 16 bytes, so a 16-byte load that
   // starts below nb stays inside it; bytes of blocks that do not exist are masked off
@@ -132,9 +132,8 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
     incl[i] = wave_inclusive_sum(sum[i]);
     if (lane == 63) sh_wave[i][wave] = incl[i];
   }
-  if (bad) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
-  if (wide) atomicOr(&a.ctl->flags, kFlagWide);
-  __syncthreads();
+  __syncthreads();                                       // sh_flags cleared, wave sums visible
+  if (bad || wide) atomicOr(&sh_flags, (bad ? kSpanBadWidth : 0u) | (wide ? kSpanWide : 0u));
   u32* grp = a.index.grp_off + u64(s) * a.index.groups_cap;
   u32* seg_off = a.index.seg_off + u64(s) * 4 * a.index.tiles_cap;
   const u64 nsegs = num_segments(h.nb);
@@ -153,44 +152,70 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
     if (threadIdx.x == 0 && group0 + u64(i) < ngroups) grp[group0 + u64(i)] = span_before;
     span_before += all;
   }
-  if (threadIdx.x == 0) a.index.span_off[u64(s) * a.index.spans_cap + blockIdx.x] = span_before;   // its size; span_scan_kernel makes it an offset
+  __syncthreads();                                       // every thread's flags are in
+  if (threadIdx.x == 0) {
+    const u64 slot = u64(s) * a.index.spans_cap + blockIdx.x;
+    a.index.span_off[slot] = span_before;                // its size; index_prep_kernel makes it an offset
+    a.index.span_flags[slot] = sh_flags;
+  }
 }
 
-// Second step of the index: one workgroup per stream turns the span sizes into exclusive
-// offsets, in place, and checks that the header's total_bytes equals tables + payload.
-__global__ __launch_bounds__(256) void span_scan_kernel(ScanArgs a) {
-  __shared__ u32 sh_scan[4];
-  __shared__ u64 sh_carry;
-  const int s = blockIdx.x;
-  const ParsedHeader h = parse_header(a.streams[s]);
-  if (!h.ok) return;
-  const u64 nspans = num_spans(h.nb);
-  if (nspans > a.index.spans_cap) return;               // already flagged by stream_index_kernel
+// Second step of the index, and set-up of the kernel that follows; one launch for all streams.
+// Workgroup 0: each wave takes streams (wave, wave + 4, ...): validates the header, turns the
+// span sizes into exclusive offsets in place, collects the spans' flags and checks that the
+// header's total_bytes equals tables + payload; thread 0 then writes the control block, so
+// nothing has to clear it beforehand.  All workgroups clear the look-back descriptors and the
+// tile tickets for the kernel that writes a stream (reduce).
+__global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
+  __shared__ u32 sh_status[4], sh_wide[4];
+  for (u64 i = u64(blockIdx.x) * blockDim.x + threadIdx.x; i < a.ndesc; i += u64(gridDim.x) * blockDim.x)
+    a.desc[desc_slot(i)] = 0;
+  if (blockIdx.x != 0) return;
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
-  u32* spans = a.index.span_off + u64(s) * a.index.spans_cap;
-  if (threadIdx.x == 0) sh_carry = 0;
-  __syncthreads();
-  for (u64 start = 0; start < nspans; start += 256) {
-    const u64 i = start + threadIdx.x;
-    const u32 val = i < nspans ? spans[i] : 0u;
-    const u32 inc = wave_inclusive_sum(val);
-    if (lane == 63) sh_scan[wave] = inc;
-    __syncthreads();
-    u32 before = 0, all = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const u32 t = sh_scan[j];
-      if (j < wave) before += t;
-      all += t;
+  u32 status = 0, wide = 0;
+  ParsedHeader h0;
+  h0.ok = false;
+  if (a.check_match) h0 = parse_header(a.streams[0]);
+  for (int s = wave; s < a.k; s += 4) {
+    const ParsedHeader h = parse_header(a.streams[s]);
+    if (!h.ok) {
+      status |= status_bit(ZC_ERR_FORMAT);
+      continue;
     }
-    const u64 carry = sh_carry;
-    if (i < nspans) spans[i] = u32(carry) + before + inc - val;
-    __syncthreads();
-    if (threadIdx.x == 0) sh_carry = carry + all;
-    __syncthreads();
+    if (!stream_fits(h, a.index)) {
+      status |= status_bit(ZC_ERR_ARG);
+      continue;
+    }
+    if (a.check_match && h0.ok && (h0.n != h.n || h0.eb_bits != h.eb_bits)) status |= status_bit(ZC_ERR_MISMATCH);
+    const u64 nspans = num_spans(h.nb);
+    u32* spans = a.index.span_off + u64(s) * a.index.spans_cap;
+    const u32* flags = a.index.span_flags + u64(s) * a.index.spans_cap;
+    u64 carry = 0;
+    u32 seen = 0;
+    for (u64 start = 0; start < nspans; start += 64) {
+      const u64 i = start + u64(lane);
+      const u32 val = i < nspans ? spans[i] : 0u;
+      seen |= i < nspans ? flags[i] : 0u;
+      const u32 inc = wave_inclusive_sum(val);
+      if (i < nspans) spans[i] = u32(carry) + inc - val;
+      carry += lane_value(inc, 63);
+    }
+    if (__any((seen & kSpanBadWidth) != 0)) status |= status_bit(ZC_ERR_FORMAT);
+    if (__any((seen & kSpanWide) != 0)) wide = kFlagWide;
+    if (tables_end(h.nb) + 4 * carry != h.total) status |= status_bit(ZC_ERR_FORMAT);
   }
-  if (threadIdx.x == 0 && tables_end(h.nb) + 4 * sh_carry != h.total) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
+  if (lane == 0) {
+    sh_status[wave] = status;
+    sh_wide[wave] = wide;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a.ctl->status = sh_status[0] | sh_status[1] | sh_status[2] | sh_status[3];
+    a.ctl->flags = sh_wide[0] | sh_wide[1] | sh_wide[2] | sh_wide[3];
+    a.ctl->result = 0;
+    for (int i = 0; i < kTicketShards; ++i) *ticket_counter(a.ctl, u32(i)) = 0;
+  }
 }
 
 }  // namespace zc
