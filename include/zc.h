@@ -112,6 +112,19 @@ int zc_debug_quantize(const float* d_in, size_t n, float abs_eb, int32_t* d_q,
 int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_words, size_t off_cap,
                            void* d_ws, size_t ws_bytes, void* hip_stream);
 
+/* How zc_compress and zc_reduce_compressed hand out their tiles (256 or 512 blocks each) to
+ * workgroups.  Their single-pass placement (a device-wide exclusive sum of block sizes by
+ * look-back) needs every tile before a tile in work to be in work or finished.
+ * ZC_HAND_OUT_DISPATCH_ORDER (default): tile = workgroup id; relies on the GPU starting the
+ * workgroups of a launch in increasing id order, which is how its dispatcher works but not an
+ * architectural promise.  ZC_HAND_OUT_TICKETS: tiles are claimed with atomic tickets, which
+ * needs no assumption and costs a few percent.  In both modes a wait that does not end within
+ * 2^20 polls ends the call with ZC_ERR_HIP.  Process-wide; applies to calls made afterwards.
+ * Returns ZC_OK or ZC_ERR_ARG. */
+#define ZC_HAND_OUT_DISPATCH_ORDER 0
+#define ZC_HAND_OUT_TICKETS 1
+int zc_set_tile_hand_out(int mode);
+
 /* Measurement aid (not part of the method).  While enabled, zc_compress, zc_decompress and
  * zc_reduce_compressed record a pair of HIP events on the call's stream around their main
  * kernel (the compress kernel over the full tiles, the decompress kernel, the reduce kernel;
@@ -119,7 +132,7 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
  * stores up to cap elapsed times in milliseconds in ms[] and the matching ZC_KERNEL_* ids in
  * kernel[] (host arrays, either may be NULL) in call order, forgets them, and returns how
  * many it stored (a negative status on a HIP error).  The events are host objects created on
- * first use and reused; this is the only state the library keeps.  Enabling or disabling
+ * first use and reused; with the hand-out mode above this is the only state the library keeps.  Enabling or disabling
  * forgets the pairs recorded so far. */
 #define ZC_KERNEL_COMPRESS 1
 #define ZC_KERNEL_DECOMPRESS 2

@@ -19,7 +19,7 @@ ZC_MAX_K = 64
 EXPORTS = [
     "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_reduce_compressed",
     "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
-    "zc_profile_enable", "zc_profile_collect",
+    "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out",
 ]
 
 _lib = None
@@ -53,6 +53,7 @@ def lib():
         L.zc_strerror.argtypes = [C.c_int]
         L.zc_debug_quantize.argtypes = [vp, sz, C.c_float, vp, vp, sz, vp]
         L.zc_debug_block_offsets.argtypes = [vp, sz, vp, sz, vp, sz, vp]
+        L.zc_set_tile_hand_out.argtypes = [C.c_int]
         L.zc_profile_enable.argtypes = [C.c_int]
         L.zc_profile_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int), C.c_int]
         _lib = L
@@ -152,3 +153,10 @@ def zc_profile_collect(cap=65536):
     if count < 0:
         raise ZcError(-count, "zc_profile_collect")
     return [(KERNEL_NAMES.get(kind[i], str(kind[i])), float(ms[i])) for i in range(count)]
+
+
+ZC_HAND_OUT_DISPATCH_ORDER, ZC_HAND_OUT_TICKETS = 0, 1
+
+
+def zc_set_tile_hand_out(mode):
+    return lib().zc_set_tile_hand_out(int(mode))

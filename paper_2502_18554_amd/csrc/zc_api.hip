@@ -60,6 +60,9 @@ struct KernelTimer {
 };
 KernelTimer g_timer;
 
+// How the kernels that write a stream hand out their tiles (zc_set_tile_hand_out).
+int g_hand_out = ZC_HAND_OUT_DISPATCH_ORDER;
+
 // Most blocks a stream of `bytes` bytes can describe: each costs at least 5 table bytes.
 u64 blocks_bound(u64 bytes) { return bytes > kHeaderBytes ? (bytes - kHeaderBytes) / 5 : 0; }
 
@@ -140,6 +143,7 @@ void fill_compress_args(CompressArgs& ca, const float* d_in, u64 n, float abs_eb
   ca.out_cap = out_cap;
   ca.ctl = l.ctl;
   ca.desc = l.desc;
+  ca.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
 }
 
 }  // namespace
@@ -273,6 +277,7 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   ra.out_cap = out_cap;
   ra.ctl = l.ctl;
   ra.desc = l.desc;
+  ra.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
   KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_REDUCE, stream);
   hipLaunchKernelGGL(reduce_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
   g_timer.end(slot, stream);
@@ -286,6 +291,12 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
 #ifdef ZC_REC
 int zc_set_rec(void* p) { return hipMemcpyToSymbol(HIP_SYMBOL(g_rec), &p, sizeof(p)) == hipSuccess ? 0 : 8; }
 #endif
+
+int zc_set_tile_hand_out(int mode) {
+  if (mode != ZC_HAND_OUT_DISPATCH_ORDER && mode != ZC_HAND_OUT_TICKETS) return ZC_ERR_ARG;
+  g_hand_out = mode;
+  return ZC_OK;
+}
 
 int zc_profile_enable(int on) {
   std::lock_guard<std::mutex> g(g_timer.mu);

@@ -149,7 +149,16 @@ __device__ inline bool validation_failed(const Control* ctl) {
   return (ctl->status & kGateBits) != 0;
 }
 
-// Tile hand-out.  One atomic counter would serialise the whole kernel: atomics on one
+// Tile hand-out.  A kernel that places its output by look-back needs every tile below a tile
+// in work to be in work too, or finished.  Two ways to get that:
+//  - by workgroup id (the default): tile = blockIdx.x.  The dispatcher of this GPU starts the
+//    workgroups of a launch in increasing id order (measured: workgroup i always lands on XCD
+//    (i + 7) mod 8, and start times follow the ids), so a running workgroup's predecessors have
+//    all started.  That order is how the hardware works, not an architectural promise, which
+//    is why every look-back wait is bounded and turns into ZC_ERR_HIP instead of a hang.
+//  - by tickets: the order of the claims is the order of the tiles, whatever the dispatcher
+//    does.  It costs each workgroup one atomic round trip before it can issue its first load.
+// Tickets: one atomic counter would serialise the whole kernel: atomics on one
 // address retire at about 11 ns each on this machine, which for 16384 tiles is longer than
 // the kernel should run.  So there is one counter per XCD, picked by the hardware XCC_ID of
 // the wave that asks, and counter y hands out tiles y, y + 8, y + 16, ...  A workgroup whose
@@ -330,7 +339,10 @@ __device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status,
     const int first_prefix = has_prefix ? __builtin_ctzll(has_prefix) : kLookLanes - 1;
     const u64 needed = first_prefix == 63 ? ~u64(0) : ((u64(2) << first_prefix) - 1);   // lanes 0..first_prefix
     if (is_empty & needed) {
-      if (++spins > kSpinLimit) {
+      // give up after kSpinLimit polls, or as soon as another tile has given up
+      const bool lost = (++spins & 1023u) == 0 &&
+                        (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & status_bit(ZC_ERR_HIP)) != 0;
+      if (spins > kSpinLimit || lost) {
         if (lane == 0) atomicOr(status, status_bit(ZC_ERR_HIP));
         return excl;
       }

@@ -43,6 +43,7 @@ struct CompressArgs {
   u64 out_cap;       // bytes
   Control* ctl;
   u64* desc;
+  u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
 };
 
 // Round-to-nearest-even of r for |r| < 2^31 as the low word of r + 1.5 * 2^52.
@@ -275,10 +276,13 @@ __global__ __launch_bounds__(kPackThreads, ZC_C_OCC) void compress_kernel(Compre
 
   u32 tile = first_tile;
   if (FULL) {
-    if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, end_tile, xcc_id());
-    __syncthreads();
-    tile = uniform(sh_tile);
-    if (tile == kNoTile) return;
+    tile = blockIdx.x;                       // tiles in the order in which workgroups start
+    if (a.ticketed) {                        // ... or handed out by tickets, see take_tile
+      if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, end_tile, xcc_id());
+      __syncthreads();
+      tile = uniform(sh_tile);
+    }
+    if (tile >= end_tile) return;
   }
   {
     const u64 wblock0 = u64(tile) * kPackBlocks + u64(wave) * kWaveBlocks;

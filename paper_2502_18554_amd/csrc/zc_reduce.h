@@ -33,6 +33,7 @@ struct ReduceArgs {
   u64 out_cap;
   Control* ctl;
   u64* desc;
+  u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
 };
 
 // Header fields and table padding of the output stream; one thread.
@@ -319,10 +320,13 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
 #ifdef ZC_REC
   const u64 t_start = wall_clock64();
 #endif
-  if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
-  __syncthreads();
-  const u32 tile = uniform(sh_tile);
-  if (tile == kNoTile) return;
+  u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
+  if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
+    if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
+    __syncthreads();
+    tile = uniform(sh_tile);
+  }
+  if (tile >= ntiles) return;
 
 #ifdef ZC_REC
   if (threadIdx.x == 0 && g_rec) {
@@ -452,10 +456,13 @@ __global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a)
 
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
-  if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
-  __syncthreads();
-  const u32 tile = uniform(sh_tile);
-  if (tile == kNoTile) return;
+  u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
+  if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
+    if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
+    __syncthreads();
+    tile = uniform(sh_tile);
+  }
+  if (tile >= ntiles) return;
 
   u32* const wl = lds + wave * kWaveStage;
   const u64 seg = u64(tile) * kTileWaves + u64(wave);

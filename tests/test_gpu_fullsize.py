@@ -165,8 +165,19 @@ def test_allgather_8x64M(zcref):
             check_slices_against_reference(zcref, xs[r], eb, s, out[r * m:(r + 1) * m], rng, count=3)
 
 
-def test_allreduce_8x64M(zcref):
-    """Configuration 4: fused reduce of 8 compressed rank buffers at a common bound; error <= 8 eb."""
+@pytest.mark.parametrize("hand_out", ["dispatch_order", "tickets"])
+def test_allreduce_8x64M(zcref, hand_out):
+    """Configuration 4: fused reduce of 8 compressed rank buffers at a common bound; error <= 8 eb.
+    Run with both ways of handing out tiles (the other tests of this file use the default)."""
+    mode = zc.binding.ZC_HAND_OUT_TICKETS if hand_out == "tickets" else zc.binding.ZC_HAND_OUT_DISPATCH_ORDER
+    assert zc.zc_set_tile_hand_out(mode) == ZC_OK
+    try:
+        _allreduce_8x64M(zcref)
+    finally:
+        zc.zc_set_tile_hand_out(zc.binding.ZC_HAND_OUT_DISPATCH_ORDER)
+
+
+def _allreduce_8x64M(zcref):
     rng = np.random.default_rng(4)
     xs = _rank_buffers()
     m = xs[0].numel()

@@ -15,6 +15,15 @@ pytestmark = pytest.mark.gpu
 TILE = 8192
 
 
+@pytest.fixture(params=["dispatch_order", "tickets"], autouse=True)
+def tile_hand_out(request):
+    """Every test of this module runs with both ways of handing out tiles to workgroups."""
+    mode = zc.binding.ZC_HAND_OUT_TICKETS if request.param == "tickets" else zc.binding.ZC_HAND_OUT_DISPATCH_ORDER
+    assert zc.zc_set_tile_hand_out(mode) == ZC_OK
+    yield request.param
+    zc.zc_set_tile_hand_out(zc.binding.ZC_HAND_OUT_DISPATCH_ORDER)
+
+
 def _u():
     import gpuutil
     return gpuutil

@@ -55,6 +55,7 @@ def test_argument_checks_without_gpu(libzc):
     assert libzc.zc_compress(0x1000, 10, 0.0, 0x2000, 100, None, 0x3000, 4096, None) == 1      # eb
     assert libzc.zc_compress(0x1004, 10, 1e-3, 0x2000, 100, None, 0x3000, 4096, None) == 1     # alignment
     assert libzc.zc_compress(0x1000, 1 << 20, 1e-3, 0x2000, 100, None, 0x3000, 64, None) == 1  # workspace
+    assert libzc.zc_set_tile_hand_out(7) == 1 and libzc.zc_set_tile_hand_out(1) == 0 and libzc.zc_set_tile_hand_out(0) == 0
     assert libzc.zc_decompress(None, 100, None, 0, None, None, 0, None) == 1
     assert libzc.zc_decompress(0x1000, 16, 0x2000, 8, None, 0x3000, 4096, None) == 3           # shorter than a header
     assert libzc.zc_reduce_compressed(None, None, 0, None, 0, None, None, 0, None) == 1
