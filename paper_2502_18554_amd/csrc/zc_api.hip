@@ -288,9 +288,6 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   return finish(d_ws, out_bytes, stream);
 }
 
-#ifdef ZC_REC
-int zc_set_rec(void* p) { return hipMemcpyToSymbol(HIP_SYMBOL(g_rec), &p, sizeof(p)) == hipSuccess ? 0 : 8; }
-#endif
 
 int zc_set_tile_hand_out(int mode) {
   if (mode != ZC_HAND_OUT_DISPATCH_ORDER && mode != ZC_HAND_OUT_TICKETS) return ZC_ERR_ARG;

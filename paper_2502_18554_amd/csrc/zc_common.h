@@ -18,13 +18,6 @@ using u64 = uint64_t;
 using i32 = int32_t;
 using i64 = int64_t;
 
-#ifdef ZC_REC
-__device__ u64* g_rec;
-#define REC(tile, i) do { if (threadIdx.x == 0 && g_rec) g_rec[u64(tile) * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define REC(tile, i) do {} while (0)
-#endif
-
 constexpr u32 kMagic = 0x314C435Au;
 constexpr u32 kHeaderBytes = 32;
 constexpr int kBlockValues = 32;           // values per block (Section 3.3 "small blocks")

@@ -19,13 +19,7 @@ namespace zc {
 // look-back scan.  Every tile pays the latency of that scan once, so compression uses tiles
 // twice the size of the other kernels' tiles (512 blocks, 64 KiB of input); 1024 blocks
 // measured slower, because a compute unit then holds a single workgroup.
-#ifndef ZC_PACK_WAVES
-#define ZC_PACK_WAVES 8
-#endif
-constexpr int kPackWaves = ZC_PACK_WAVES;
-#ifndef ZC_C_OCC
-#define ZC_C_OCC 4
-#endif
+constexpr int kPackWaves = 8;
 constexpr int kPackThreads = kPackWaves * 64;
 constexpr int kPackBlocks = kPackWaves * kWaveBlocks;
 constexpr int kPackValues = kPackBlocks * kBlockValues;
@@ -260,7 +254,7 @@ __device__ inline void wide_tile(const CompressArgs& a, const PayloadSink& sink,
 // 16-byte loads, no tail), handed out by the per-XCD tickets over [first_tile, end_tile); the
 // ragged last tile of an input runs as a second launch of one workgroup with FULL = false.
 template <bool FULL>
-__global__ __launch_bounds__(kPackThreads, ZC_C_OCC) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
+__global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
   __shared__ __attribute__((aligned(16))) u32 lds[kPackWaves * kWaveStage];
   __shared__ u32 sh_tile;
   __shared__ u32 sh_wave_total[kPackWaves];
@@ -346,9 +340,7 @@ __global__ __launch_bounds__(kPackThreads, ZC_C_OCC) void compress_kernel(Compre
       }
       finish_tile<16>(sink, [&](auto i) { return pw[decltype(i)::value]; }, pl, tile, ntiles, wl, &sh_base, wave, lane);
     } else {
-#ifndef ZC_NO_WIDE
       wide_tile<FULL>(a, sink, pl, tile, ntiles, wblock0, wl, &sh_base, wave, lane);
-#endif
     }
   }
   if (err) atomicOr(&a.ctl->status, err);

@@ -76,7 +76,6 @@ __device__ inline u64 resolve_tile_base(const PayloadSink& s, const Placement& p
     }
   }
   lds_barrier();                // only sh_base passes through it
-  REC(tile, 5);
   return *sh_base;
 }
 

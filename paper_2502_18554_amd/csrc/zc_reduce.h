@@ -123,10 +123,8 @@ __device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, con
   }
   const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total);
-  REC(tile, 4);
   if (err) atomicOr(&a.ctl->status, err);
   finish_tile<NW>(sink, word, pl, tile, ntiles, wl, sh_base, wave, lane);
-  REC(tile, 6);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -317,9 +315,6 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
 
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
-#ifdef ZC_REC
-  const u64 t_start = wall_clock64();
-#endif
   u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
   if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
     if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
@@ -328,13 +323,6 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
   }
   if (tile >= ntiles) return;
 
-#ifdef ZC_REC
-  if (threadIdx.x == 0 && g_rec) {
-    g_rec[u64(tile) * 8] = t_start;
-    g_rec[u64(tile) * 8 + 7] = (u64(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (4 << 11))) << 32) | blockIdx.x;
-  }
-#endif
-  REC(tile, 1);
   u32* const wl = lds + wave * kWaveStage;
   const u64 seg = u64(tile) * kTileWaves + u64(wave);
   const bool seg_live = seg < num_segments(h.nb);
@@ -358,7 +346,6 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
     const OperandPlace cur = next;
     stage_to_lds(stage, cur, wl, lane);
     wave_lds_sync();
-    if (s == 0) REC(tile, 2);
     if (s + 1 < a.k) {
       next = place_operand(meta);
       outlier += i64(meta.outlier);
@@ -379,7 +366,6 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
     wave_lds_sync();
   }
 
-  REC(tile, 3);
   // ---- back to sign + magnitude planes; new code length; placement and copy-out ----
   const u32 sgn = sign_plane<0>(acc, top);
   u32 carry = sgn, w = 0;
