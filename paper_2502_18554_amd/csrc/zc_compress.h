@@ -4,9 +4,10 @@
 // Work split.  A tile is 512 blocks (16384 values, 64 KiB of input) handled by a workgroup of
 // 8 waves.  Each wave loads 2048 consecutive values with 16-byte loads,
 // quantises them where they land, and transposes the integer codes through LDS so that one
-// lane owns one block.  Delta, width and the bit-matrix transpose that yields the plane
-// words are then in-lane; the packed words wait in registers for the tile's base offset
-// from the look-back scan and leave through LDS as coalesced stores.
+// lane owns one block.  Deltas (kept as 16 words of paired 16-bit fields), width and the
+// bit-matrix transpose that yields the plane words are then in-lane; the packed words wait
+// in registers for the tile's base offset from the look-back scan and leave through LDS as
+// coalesced stores.
 #pragma once
 
 #include "zc_bitmatrix.h"
@@ -250,9 +251,10 @@ __device__ inline void wide_tile(const CompressArgs& a, const PayloadSink& sink,
   finish_stream(sink, pl, tile, ntiles, base);
 }
 
-// One workgroup per tile.  FULL = the launch covers tiles whose 8192 values all exist (pure
-// 16-byte loads, no tail), handed out by the per-XCD tickets over [first_tile, end_tile); the
-// ragged last tile of an input runs as a second launch of one workgroup with FULL = false.
+// One workgroup per tile.  FULL = the launch covers the tiles whose 16384 values all exist
+// (pure 16-byte loads, no tail), tile = workgroup id or a ticket (see take_tile) over
+// [0, end_tile); the ragged last tile of an input runs as a second launch of one workgroup
+// with FULL = false on tile first_tile.
 template <bool FULL>
 __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
   __shared__ __attribute__((aligned(16))) u32 lds[kPackWaves * kWaveStage];
