@@ -355,3 +355,20 @@ def test_repeated_runs_are_identical():
         if first is None:
             first = got
         assert torch.equal(first, got)
+
+
+def test_kernel_timing_hook(zcref):
+    """zc_profile_enable / zc_profile_collect: one positive time per main kernel, in call order."""
+    u = _u()
+    x = synth.power_law_field((16, 64, 64), seed=9).numpy()
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    zc.zc_profile_enable(True)
+    st, s, total = u.gpu_compress(x, eb)
+    st2, y, n = u.gpu_decompress(s, x.size)
+    st3, r, _ = u.gpu_reduce([s, s], x.size)
+    got = zc.zc_profile_collect()
+    zc.zc_profile_enable(False)
+    assert st == st2 == st3 == ZC_OK
+    assert [name for name, _ in got] == ["compress", "decompress", "reduce"]
+    assert all(0.0 < ms < 100.0 for _, ms in got)
+    assert zc.zc_profile_collect() == []
