@@ -219,35 +219,41 @@ __device__ inline void stage_to_lds(const OperandStage& st, const OperandPlace& 
   }
 }
 
+// Three-input bitwise functions, one v_bitop3_b32 each.  The table is the function evaluated
+// on a = 0xF0, b = 0xCC, c = 0xAA.
+__device__ inline u32 xor3(u32 a, u32 b, u32 c) { return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96); }
+__device__ inline u32 majority(u32 a, u32 b, u32 c) { return __builtin_amdgcn_bitop3_b32(a, b, c, 0xE8); }
+__device__ inline u32 and_xor(u32 a, u32 b, u32 c) { return __builtin_amdgcn_bitop3_b32(a, b, c, 0x6A); }   // (a & b) ^ c
+
 // acc += operand, planes [4C, 4C + 4).  DATA: the operand has magnitude planes here, read
-// from LDS (`mine` points at the lane's sign word) and masked by the block's own width;
-// otherwise the operand only contributes its sign extension.
+// from LDS (`mine` points at the lane's sign word) and masked by the block's own width (bit P
+// of `keep` is set iff the block has plane P); otherwise the operand only contributes its
+// sign extension.  Four instructions per plane: mask, operand bit, sum, carry.
 template <int C, bool DATA>
-__device__ inline void add_chunk(u32 (&acc)[kSumPlanes], const u32* mine, u32 w, u32 sgn, u32& carry) {
+__device__ inline void add_chunk(u32 (&acc)[kSumPlanes], const u32* mine, u32 keep, u32 sgn, u32& carry) {
 #pragma unroll
   for (int i = 0; i < kSumChunk; ++i) {
     constexpr int kFirst = C * kSumChunk;
     const int P = kFirst + i;
     u32 x = sgn;                                  // two's complement of the operand: (mag ^ s) + s
     if (DATA) {
-      const u32 plane = mine[1 + P];
-      x ^= u32(P) < w ? plane : 0u;
+      const u32 m = u32(__builtin_amdgcn_sbfe(i32(keep), u32(P), 1u));   // all ones iff the block has plane P
+      x = and_xor(mine[1 + P], m, sgn);
     }
-    const u32 cur = acc[P];
-    const u32 t = cur ^ x;
-    acc[P] = t ^ carry;
-    carry = (t & carry) | (~t & cur);             // majority(cur, x, carry)
+    const u32 cur = acc[P];                       // full adder
+    acc[P] = xor3(cur, x, carry);
+    carry = majority(cur, x, carry);
   }
 }
 
 template <int C>
-__device__ inline void add_operand_chunks(u32 (&acc)[kSumPlanes], const u32* mine, u32 w, u32 sgn, u32& carry,
+__device__ inline void add_operand_chunks(u32 (&acc)[kSumPlanes], const u32* mine, u32 keep, u32 sgn, u32& carry,
                                           u32 wcap, u32 top) {
   if constexpr (C * kSumChunk < kSumPlanes) {
     if (u32(C * kSumChunk) >= top) return;        // uniform
-    if (C * kSumChunk < 16 && u32(C * kSumChunk) < wcap) add_chunk<C, true>(acc, mine, w, sgn, carry);
-    else add_chunk<C, false>(acc, mine, w, sgn, carry);
-    add_operand_chunks<C + 1>(acc, mine, w, sgn, carry, wcap, top);
+    if (C * kSumChunk < 16 && u32(C * kSumChunk) < wcap) add_chunk<C, true>(acc, mine, keep, sgn, carry);
+    else add_chunk<C, false>(acc, mine, keep, sgn, carry);
+    add_operand_chunks<C + 1>(acc, mine, keep, sgn, carry, wcap, top);
   }
 }
 
@@ -361,7 +367,8 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
       const u32* mine = wl + cur.pick;
       const u32 sgn = cur.w ? mine[0] : 0u;
       u32 carry = sgn;
-      add_operand_chunks<0>(acc, mine, cur.w, sgn, carry, cur.wcap, top);
+      const u32 keep = (1u << cur.w) - 1u;      // bit P set iff the block has plane P
+      add_operand_chunks<0>(acc, mine, keep, sgn, carry, cur.wcap, top);
     }
     wave_lds_sync();
   }
