@@ -213,6 +213,7 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
   const u64 tiles_out = num_tiles(num_blocks(out_cap_elems));
   if (tiles > tiles_out) tiles = tiles_out;
   if (tiles > l.tiles_cap) tiles = l.tiles_cap;
+  if (tiles > kMaxTiles) tiles = kMaxTiles;
   if (tiles < 1) tiles = 1;
   ScanArgs sa;
   sa.streams[0].base = static_cast<const u8*>(d_in);
@@ -255,6 +256,7 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
     const u64 t = num_tiles(blocks_bound(chunk_bytes[i]));
     if (t < tiles) tiles = t;
   }
+  if (tiles > kMaxTiles) tiles = kMaxTiles;
   if (tiles < 1) tiles = 1;
   ScanArgs sa;
   ReduceArgs ra;
@@ -365,6 +367,7 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
   if (l.tiles_cap < 1) return ZC_ERR_ARG;
   u64 tiles = num_tiles(blocks_bound(in_bytes));
   if (tiles > l.tiles_cap) tiles = l.tiles_cap;
+  if (tiles > kMaxTiles) tiles = kMaxTiles;
   if (tiles < 1) tiles = 1;
   ScanArgs sa;
   sa.streams[0].base = static_cast<const u8*>(d_in);

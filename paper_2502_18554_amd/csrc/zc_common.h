@@ -32,6 +32,8 @@ constexpr u32 kSpinLimit = 1u << 20;       // bound on every look-back wait
 __host__ __device__ inline u64 pad16(u64 v) { return (v + 15) / 16 * 16; }
 __host__ __device__ inline u64 num_blocks(u64 n) { return (n + kBlockValues - 1) / kBlockValues; }
 __host__ __device__ inline u64 num_tiles(u64 nb) { return (nb + kTileBlocks - 1) / kTileBlocks; }
+// No stream has more tiles than this (n <= ZC_MAX_N), so block and segment numbers fit 32 bits.
+constexpr u64 kMaxTiles = (ZC_MAX_N / kBlockValues + kTileBlocks - 1) / kTileBlocks;
 __host__ __device__ inline u64 tables_end(u64 nb) { return kHeaderBytes + pad16(nb) + pad16(4 * nb); }
 __host__ __device__ inline u32 psize_words(u32 w) { return w ? 1 + w : 0; }
 
@@ -199,6 +201,18 @@ __device__ inline u32 lane_value(u32 v, int lane) { return u32(__builtin_amdgcn_
 // it are scalar branches.
 __device__ inline u32 uniform(u32 v) { return u32(__builtin_amdgcn_readfirstlane(int(v))); }
 __device__ inline u64 uniform64(u64 v) { return u64(uniform(u32(v))) | (u64(uniform(u32(v >> 32))) << 32); }
+// A zero in a vector register that the compiler cannot see through.  An address that has it
+// added is not provably the same in every lane, so the access becomes a vector memory load.
+// Vector loads return in order and have a counter of their own: several independent loads
+// are all in flight behind a single wait.  Loads from a provably uniform address of memory
+// not yet written by the kernel are turned into scalar loads instead, which share one
+// counter with the fetches of kernel arguments and return in any order, so the compiler has
+// to drain all of them at every use: three round trips where one will do.
+__device__ inline u32 opaque_zero() {
+  u32 z;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+  return z;
+}
 // Index of the calling wave in its workgroup, as a scalar.
 __device__ inline int wave_id() { return int(uniform(threadIdx.x >> 6)); }
 // base + byte offset, for a base that is the same in every lane: it stays in scalar registers

@@ -27,38 +27,46 @@ struct DecompressArgs {
 __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
 
-  if (validation_failed(a.ctl)) return;
-  const ParsedHeader h = parse_header(a.in);
-  if (!h.ok) return;
+  // Everything that can be asked for before the header is known goes out at once: the control
+  // block, the header, the segment's position and the width bytes.  The loads are fenced in
+  // by sizes the host passed; what the header then rules out is dropped.
+  const int lane = lane_id();
+  const int wave = wave_id();
+  const u32 tile = blockIdx.x;
+  const u32 seg = tile * kTileWaves + u32(wave);       // < 2^22: the host launches at most 2^20 tiles
+  const u32 wblock0 = seg * kWaveBlocks;
+  const u32 b = wblock0 + u32(lane);                   // a stream has at most 2^26 blocks
+  const u32 zero = opaque_zero();
+  const uint2 gate = load_gate(a.ctl, zero);
+  const HeaderWords hw = load_header_words(a.in.base, zero);
+  SegmentOffsetParts seg_parts{0, 0, 0};
+  if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, 0, seg, zero);
+  u32 w = u64(kHeaderBytes) + b < a.in.bytes ? u32(*at_bytes(a.in.base, kHeaderBytes + b)) : 0u;
+
+  const ParsedHeader h = parse_header(hw, a.in.bytes);
+  if (gate_failed(gate) || !h.ok) return;
   if (blockIdx.x == 0 && threadIdx.x == 0) a.ctl->result = h.n;
   if (h.n > a.out_cap_elems) {
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
     return;
   }
-  const u32 tile = blockIdx.x;
   if (u64(tile) >= num_tiles(h.nb) || u64(tile) >= a.index.tiles_cap) return;
 
-  const int lane = lane_id();
-  const int wave = int(threadIdx.x) >> 6;
   u32* const wl = lds + wave * kWaveStage;
-  const u64 seg = u64(tile) * kTileWaves + u64(wave);
   if (seg >= num_segments(h.nb)) return;           // no barrier below: waves are independent
-  const u64 wblock0 = seg * kWaveBlocks;
-  const u64 b = wblock0 + u64(lane);
   const bool active = b < h.nb;
+  if (!active) w = 0;
 
-  const u8* widths = a.in.base + kHeaderBytes;
   const i32* outliers = reinterpret_cast<const i32*>(a.in.base + kHeaderBytes + pad16(h.nb));
   const u32* payload = reinterpret_cast<const u32*>(a.in.base + tables_end(h.nb));
   const u64 payload_words = (h.total - tables_end(h.nb)) / 4;
 
-  u32 w = active ? u32(widths[b]) : 0u;
   u32 cur = active ? u32(outliers[b]) : 0u;
   const u32 words = psize_words(w);
   const u32 incl = wave_inclusive_sum(words);
   const u32 off_in_wave = incl - words;
   const u32 wave_total = lane_value(incl, 63);
-  const u64 seg_off = segment_offset(a.index, 0, seg);
+  const u64 seg_off = segment_offset(seg_parts);
   const u32 wmax = wave_max_u32(w);
   // a validated stream keeps every segment inside the payload; refuse to read outside anyway
   const bool inside = seg_off + wave_total <= payload_words;
@@ -149,7 +157,7 @@ __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressA
   }
 
   // ---- transpose through LDS (two halves of 32 blocks), 16-byte coalesced stores ----
-  const u64 v0 = wblock0 * kBlockValues;
+  const u64 v0 = u64(wblock0) * kBlockValues;
   const bool full = v0 + u64(kWaveBlocks) * kBlockValues <= h.n;
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh) {

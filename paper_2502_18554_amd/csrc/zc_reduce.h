@@ -112,7 +112,7 @@ __device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, con
     a.out[kHeaderBytes + b] = u8(w);
     reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(h.nb))[b] = i32(outlier);
   }
-  __syncthreads();
+  lds_barrier();                // the wave totals; the stores above stay in flight
   pl.wave_off = 0;
   pl.tile_total = 0;
 #pragma unroll
@@ -137,12 +137,14 @@ __device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, con
 constexpr int kSumPlanes = 24;
 constexpr int kSumChunk = 4;
 
-// What a wave needs to know about one operand's share: loaded two operands ahead.
+// What a wave needs to know about one operand's share, loaded two operands ahead: the values
+// as they come from memory.  Nothing is computed from them where they are loaded, so that
+// no load has to be waited for there.
 struct OperandMeta {
   u32 w;            // this lane's block width
   i32 outlier;
-  u64 seg_off;      // payload word offset of the wave's segment (uniform)
-  u64 payload_words;
+  SegmentOffsetParts seg_off;   // payload word offset of the wave's segment (uniform)
+  u64 total_bytes;              // of the stream
 };
 
 // ... and after the scan of the widths: one operand ahead.
@@ -155,31 +157,50 @@ struct OperandPlace {
   u64 payload_words;
 };
 
-__device__ inline OperandMeta load_operand_meta(const ReduceArgs& a, int s, const ParsedHeader& h, u64 seg, u64 b,
-                                                bool active, bool seg_live) {
+// The tables of operand s for the wave's segment (seg: the same in every lane; b: the lane's
+// block; both fit 32 bits because a stream has at most 2^26 blocks, and so do all byte offsets
+// into the tables).  w_ok and seg_ok say which loads stay inside the stream and the index;
+// they need not be the exact "block exists" conditions (the caller drops what it must not
+// use), which lets a workgroup ask before it knows the header.
+__device__ inline OperandMeta load_operand_tables(const ReduceArgs& a, int s, u32 seg, u32 b, bool w_ok, bool seg_ok,
+                                                  u32 zero = 0) {
   OperandMeta m;
   const u8* base = a.in[s].base;
-  const u64 total_s = reinterpret_cast<const u64*>(base)[3];
-  m.payload_words = (total_s - tables_end(h.nb)) / 4;
-  m.w = active ? u32(base[kHeaderBytes + b]) : 0u;
-  m.outlier = active ? reinterpret_cast<const i32*>(base + kHeaderBytes + pad16(h.nb))[b] : 0;
-  m.seg_off = seg_live ? segment_offset(a.index, s, seg) : 0;
+  m.seg_off = SegmentOffsetParts{0, 0, 0};
+  if (seg_ok) m.seg_off = load_segment_offset(a.index, s, seg, zero);
+  m.total_bytes = *reinterpret_cast<const u64*>(at_bytes(base, zero + 24u));
+  m.w = w_ok ? u32(*at_bytes(base, kHeaderBytes + b)) : 0u;
+  m.outlier = 0;
   return m;
 }
 
-__device__ inline OperandPlace place_operand(const OperandMeta& m) {
+__device__ inline i32 load_operand_outlier(const ReduceArgs& a, int s, const ParsedHeader& h, u32 b, bool active) {
+  const u8* base = a.in[s].base;
+  return active ? *reinterpret_cast<const i32*>(at_bytes(base, kHeaderBytes + u32(pad16(h.nb)) + 4u * b)) : 0;
+}
+
+__device__ inline OperandMeta load_operand_meta(const ReduceArgs& a, int s, const ParsedHeader& h, u32 seg, u32 b,
+                                                bool active, bool seg_live) {
+  OperandMeta m = load_operand_tables(a, s, seg, b, active, seg_live);
+  m.outlier = load_operand_outlier(a, s, h, b, active);
+  return m;
+}
+
+__device__ inline OperandPlace place_operand(const OperandMeta& m, const ParsedHeader& h) {
   OperandPlace p;
+  // the same in every lane, and long since loaded: into scalar registers
+  const u64 seg_off = segment_offset(m.seg_off);
+  p.payload_words = (m.total_bytes - tables_end(h.nb)) / 4;
   const u32 w = m.w > 15 ? 0u : m.w;           // cannot happen here; keeps every LDS access in range
   const u32 words = psize_words(w);
   const u32 incl = wave_inclusive_sum(words);
   const u32 wave_total = lane_value(incl, 63);
-  const bool inside = m.seg_off + wave_total <= m.payload_words;   // true on a validated stream
-  const u32 mis = u32(m.seg_off) & 3u;
-  p.src0 = m.seg_off - mis;
+  const bool inside = seg_off + wave_total <= p.payload_words;   // true on a validated stream
+  const u32 mis = u32(seg_off) & 3u;
+  p.src0 = seg_off - mis;
   p.span = inside ? mis + wave_total : 0u;     // <= 3 + 64 * 16
   p.pick = mis + (incl - words);
   p.w = inside ? w : 0u;
-  p.payload_words = m.payload_words;
   p.wcap = __any(p.w > 12) ? 16u : __any(p.w > 8) ? 12u : __any(p.w > 4) ? 8u : __any(p.w != 0) ? 4u : 0u;
   return p;
 }
@@ -311,16 +332,29 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
   __shared__ u32 sh_wave_total[kTileWaves];
   __shared__ u64 sh_base;
 
-  if (validation_failed(a.ctl) || streams_are_wide(a.ctl)) return;
-  const ParsedHeader h = parse_header(a.in[0]);
-  if (!h.ok) return;
+  const int lane = lane_id();
+  const int wave = wave_id();
+
+  // A workgroup that takes the tile of its own number asks for the first operand's tables
+  // together with the control block and the header, before it knows the header: one memory
+  // round trip instead of two.  The loads are fenced in by sizes the host passed.
+  const bool early = !a.ticketed;
+  const u32 zero = opaque_zero();
+  OperandMeta meta;
+  if (early) {
+    const u32 seg = blockIdx.x * kTileWaves + u32(wave);     // < 2^22: the host launches at most 2^20 tiles
+    const u32 b = seg * kWaveBlocks + u32(lane);
+    meta = load_operand_tables(a, 0, seg, b, u64(kHeaderBytes) + b < a.in[0].bytes, seg < 4 * a.index.tiles_cap, zero);
+  }
+  const uint2 gate = load_gate(a.ctl, zero);
+  const HeaderWords hw = load_header_words(a.in[0].base, zero);
+  const ParsedHeader h = parse_header(hw, a.in[0].bytes);
+  if (gate_failed(gate) || gate_wide(gate) || !h.ok) return;
   const u64 tend = tables_end(h.nb);
   const u32 ntiles = u32(num_tiles(h.nb));
   if (blockIdx.x == 0 && threadIdx.x == 0) write_reduce_header(a, h, ntiles);
   if (ntiles == 0) return;
 
-  const int lane = lane_id();
-  const int wave = int(threadIdx.x) >> 6;
   u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
   if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
     if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
@@ -330,10 +364,17 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
   if (tile >= ntiles) return;
 
   u32* const wl = lds + wave * kWaveStage;
-  const u64 seg = u64(tile) * kTileWaves + u64(wave);
+  const u32 seg = tile * kTileWaves + u32(wave);
   const bool seg_live = seg < num_segments(h.nb);
-  const u64 b = seg * kWaveBlocks + u64(lane);
+  const u32 b = seg * kWaveBlocks + u32(lane);
   const bool active = b < h.nb;
+  if (early) {
+    if (!active) meta.w = 0;
+    if (!seg_live) meta.seg_off = SegmentOffsetParts{0, 0, 0};
+    meta.outlier = load_operand_outlier(a, 0, h, b, active);
+  } else {
+    meta = load_operand_meta(a, 0, h, seg, b, active, seg_live);
+  }
 
   // ---- add the k operands' blocks in plane form; loads run ahead of the adds ----
   u32 acc[kSumPlanes];
@@ -343,9 +384,8 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
   u32 bound = 0;          // wave-uniform bound on |sum of deltas| so far (< 64 * 2^16)
   i64 outlier = 0;
 
-  OperandMeta meta = load_operand_meta(a, 0, h, seg, b, active, seg_live);
-  OperandPlace next = place_operand(meta);
-  outlier += i64(meta.outlier);
+  OperandPlace next = place_operand(meta, h);
+  const i32 outlier0 = meta.outlier;      // may still be on its way: added after the loop
   if (a.k > 1) meta = load_operand_meta(a, 1, h, seg, b, active, seg_live);
   OperandStage stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[0].base + tend), next, lane);
   for (int s = 0; s < a.k; ++s) {
@@ -353,7 +393,7 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
     stage_to_lds(stage, cur, wl, lane);
     wave_lds_sync();
     if (s + 1 < a.k) {
-      next = place_operand(meta);
+      next = place_operand(meta, h);
       outlier += i64(meta.outlier);
       if (s + 2 < a.k) meta = load_operand_meta(a, s + 2, h, seg, b, active, seg_live);
       stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[s + 1].base + tend), next, lane);
@@ -373,6 +413,7 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
     wave_lds_sync();
   }
 
+  outlier += i64(outlier0);
   // ---- back to sign + magnitude planes; new code length; placement and copy-out ----
   const u32 sgn = sign_plane<0>(acc, top);
   u32 carry = sgn, w = 0;

@@ -26,29 +26,65 @@ struct ParsedHeader {
 };
 
 // Field checks that need nothing but the 32 header bytes and the buffer size.
-__device__ inline ParsedHeader parse_header(const StreamRef& s) {
+__device__ inline ParsedHeader parse_header_words(const u32 (&w)[8], u64 bytes) {
   ParsedHeader h;
   h.ok = false;
-  h.n = h.nb = h.total = 0;
-  h.eb_bits = h.nsum = 0;
-  if (s.bytes < kHeaderBytes) return h;
-  const u32* w = reinterpret_cast<const u32*>(s.base);
-  const u32 w0 = w[0], w1 = w[1];
+  h.nb = 0;
   h.n = u64(w[2]) | (u64(w[3]) << 32);
   h.eb_bits = w[4];
   h.nsum = w[5];
   h.total = u64(w[6]) | (u64(w[7]) << 32);
-  if (w0 != kMagic || w1 != (1u | (5u << 16) | (6u << 24))) return h;
+  if (bytes < kHeaderBytes) return h;
+  if (w[0] != kMagic || w[1] != (1u | (5u << 16) | (6u << 24))) return h;
   if (h.n > ZC_MAX_N) return h;
   // abs_eb must be a finite binary32 >= 2^-96: sign 0, biased exponent in [31, 254]
   const u32 e = h.eb_bits >> 23;
   if (e < 31 || e > 254) return h;
   if (h.nsum < 1) return h;
   h.nb = num_blocks(h.n);
-  if (h.total > s.bytes || h.total < tables_end(h.nb)) return h;
+  if (h.total > bytes || h.total < tables_end(h.nb)) return h;
   h.ok = true;
   return h;
 }
+
+__device__ inline ParsedHeader parse_header(const StreamRef& s) {
+  u32 w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (s.bytes >= kHeaderBytes) {
+    const u32* src = reinterpret_cast<const u32*>(s.base);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[i] = src[i];
+  }
+  return parse_header_words(w, s.bytes);
+}
+
+// The same for a main kernel's first instructions: the header (and with load_gate the control
+// block) is asked for with vector loads (see opaque_zero), so that it travels together with
+// whatever else the kernel can ask for before it knows the header.  The stream must have
+// at least kHeaderBytes bytes (the host checks that before it launches anything).
+struct HeaderWords {
+  uint4 lo, hi;
+};
+
+__device__ inline HeaderWords load_header_words(const u8* base, u32 zero) {
+  HeaderWords hw;
+  hw.lo = *reinterpret_cast<const uint4*>(at_bytes(base, zero));
+  hw.hi = *reinterpret_cast<const uint4*>(at_bytes(base, zero + 16u));
+  return hw;
+}
+
+__device__ inline ParsedHeader parse_header(const HeaderWords& hw, u64 bytes) {
+  const u32 w[8] = {uniform(hw.lo.x), uniform(hw.lo.y), uniform(hw.lo.z), uniform(hw.lo.w),
+                    uniform(hw.hi.x), uniform(hw.hi.y), uniform(hw.hi.z), uniform(hw.hi.w)};
+  return parse_header_words(w, bytes);
+}
+
+// status and flags of the control block (final before a main kernel starts).
+__device__ inline uint2 load_gate(const Control* ctl, u32 zero) {
+  return *reinterpret_cast<const uint2*>(at_bytes(reinterpret_cast<const u8*>(ctl), zero));
+}
+
+__device__ inline bool gate_failed(uint2 gate) { return (uniform(gate.x) & kGateBits) != 0; }
+__device__ inline bool gate_wide(uint2 gate) { return (uniform(gate.y) & kFlagWide) != 0; }
 
 struct ScanArgs {
   StreamRef streams[ZC_MAX_K];
@@ -69,11 +105,32 @@ __device__ inline bool stream_fits(const ParsedHeader& h, const StreamIndex& ix)
 }
 
 // Payload word offset of segment `seg` of stream `s`: the offset of its index span, plus its
-// group's offset in the span, plus its own offset in the group.  Three independent loads.
+// group's offset in the span, plus its own offset in the group: three independent loads.
+// The parts are kept apart until the sum is needed.  Summing them where they are loaded makes
+// the compiler wait for two of the loads before it issues the third, which puts two memory
+// round trips where one will do.
+struct SegmentOffsetParts {
+  u32 span, grp, seg;
+};
+
+// `zero`: 0, or opaque_zero() to have vector loads whatever the compiler knows about seg.
+__device__ inline SegmentOffsetParts load_segment_offset(const StreamIndex& ix, int s, u64 seg, u32 zero = 0) {
+  SegmentOffsetParts p;
+  p.span = ix.span_off[u64(s) * ix.spans_cap + seg / kSpanSegs + zero];
+  p.grp = ix.grp_off[u64(s) * ix.groups_cap + seg / kScanGroupSegs + zero];
+  p.seg = ix.seg_off[u64(s) * 4 * ix.tiles_cap + seg + zero];
+  return p;
+}
+
+// The three loads above are in flight together when this is reached: nothing may use one of
+// the parts before all of them have been asked for.
+__device__ inline u64 segment_offset(SegmentOffsetParts p) {
+  asm volatile("" : "+v"(p.span), "+v"(p.grp), "+v"(p.seg));
+  return u64(p.span) + u64(p.grp) + u64(p.seg);
+}
+
 __device__ inline u64 segment_offset(const StreamIndex& ix, int s, u64 seg) {
-  return u64(ix.span_off[u64(s) * ix.spans_cap + seg / kSpanSegs]) +
-         u64(ix.grp_off[u64(s) * ix.groups_cap + seg / kScanGroupSegs]) +
-         u64(ix.seg_off[u64(s) * 4 * ix.tiles_cap + seg]);
+  return segment_offset(load_segment_offset(ix, s, seg));
 }
 
 // Payload words of the four blocks whose width bytes are packed in x, and whether any byte
