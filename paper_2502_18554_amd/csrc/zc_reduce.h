@@ -127,6 +127,77 @@ __device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, con
   finish_tile<NW>(sink, word, pl, tile, ntiles, wl, sh_base, wave, lane);
 }
 
+// The same for a wave whose whole payload fits its staging area (kWholeStage words per wave):
+// the plane words go to LDS in one pass before the wait for the tile's base offset, so the
+// registers that hold them are free from then on, and the copy-out is a plain LDS-to-memory
+// copy of the wave's words.
+constexpr int kWholeStage = 64 * 24;
+
+template <int NW, int NP, typename WordFn>
+__device__ inline void place_sum_staged(const ReduceArgs& a, const ParsedHeader& h, const u32 (&mag)[NP], u32 sign, u32 w,
+                                        i64 outlier, bool active, u64 b, u32 tile, u32 ntiles, WordFn word, u32* wl,
+                                        u32* sh_wave_total, u64* sh_base, int wave, int lane) {
+  static_assert(64 * NW <= kWholeStage, "a wave of widest blocks must fit the staging area");
+  const u64 tend = tables_end(h.nb);
+  if (!active) w = 0;
+  u32 err = 0;
+  if (active) {
+    const i64 ao = outlier < 0 ? -outlier : outlier;
+    const i64 reach = ao + 31 * ((i64(1) << w) - 1);
+    if (reach > kMaxCode || w > 31) {
+      if (w > 31 || block_out_of_range(mag, sign, outlier)) {
+        err |= status_bit(ZC_ERR_RANGE);
+        w = 0;
+      }
+    }
+  }
+  Placement pl;
+  pl.w = w;
+  pl.wmax = wave_max_u32(w);
+  const u32 words = psize_words(w);
+  const u32 incl = wave_inclusive_sum(words);
+  pl.wave_total = lane_value(incl, 63);
+  pl.half0_total = lane_value(incl, 31);
+  pl.off_in_wave = incl - words;
+  if (lane == 0) sh_wave_total[wave] = pl.wave_total;
+  if (active && a.out_cap >= tend) {
+    a.out[kHeaderBytes + b] = u8(w);
+    reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(h.nb))[b] = i32(outlier);
+  }
+  if (w) {
+    wl[pl.off_in_wave] = word(std::integral_constant<int, 0>{});
+    [&]<int... P>(std::integer_sequence<int, P...>) {
+      ((u32(P) < w ? void(wl[pl.off_in_wave + 1 + P] = word(std::integral_constant<int, 1 + P>{})) : void()), ...);
+    }(std::make_integer_sequence<int, NW - 1>{});
+  }
+  lds_barrier();                // the wave totals (and the words above); the stores stay in flight
+  pl.wave_off = 0;
+  pl.tile_total = 0;
+#pragma unroll
+  for (int i = 0; i < kTileWaves; ++i) {
+    const u32 t = sh_wave_total[i];
+    if (i < wave) pl.wave_off += t;
+    pl.tile_total += t;
+  }
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc};
+  if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total);
+  if (err) atomicOr(&a.ctl->status, err);
+  const u64 base = resolve_tile_base(sink, pl, tile, sh_base, wave, lane);
+  const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
+  const u64 d0 = base + pl.wave_off;
+  u32* const dst = reinterpret_cast<u32*>(a.out + tend) + d0;
+  const u64 room = cap_words > d0 ? cap_words - d0 : 0;
+  const u32 limit = u64(pl.wave_total) < room ? pl.wave_total : u32(room);
+#pragma unroll 4
+  for (u32 r = 0; r < u32(NW); ++r) {
+    const u32 i = u32(lane) + 64u * r;
+    if (64u * r >= limit) break;             // uniform
+    if (i < limit) dst[i] = wl[i];
+  }
+  wave_lds_sync();
+  finish_stream(sink, pl, tile, ntiles, base);
+}
+
 // ---------------------------------------------------------------------------------------
 // Streams without blocks wider than 15 bits.
 // ---------------------------------------------------------------------------------------
@@ -135,6 +206,7 @@ __device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, con
 // magnitude.  Planes [0, top) are valid, top a multiple of 4 and wave-uniform; plane top - 1
 // is a copy of the sign plane.
 constexpr int kSumPlanes = 24;
+static_assert(64 * kSumPlanes <= kWholeStage && kWholeStage >= kWaveStage, "staging area of reduce_kernel");
 constexpr int kSumChunk = 4;
 
 // What a wave needs to know about one operand's share, loaded two operands ahead: the values
@@ -142,9 +214,8 @@ constexpr int kSumChunk = 4;
 // no load has to be waited for there.
 struct OperandMeta {
   u32 w;            // this lane's block width
-  i32 outlier;
   SegmentOffsetParts seg_off;   // payload word offset of the wave's segment (uniform)
-  u64 total_bytes;              // of the stream
+  u32 payload_room;             // words between the start of the payload and the end of the caller's buffer (saturated)
 };
 
 // ... and after the scan of the widths: one operand ahead.
@@ -153,8 +224,8 @@ struct OperandPlace {
   u32 pick;         // LDS word index of this lane's sign word
   u32 wcap;         // uniform: 0 (nothing to add), 4, 8, 12 or 16: at least the widest block of the wave
   u32 span;         // uniform: words the wave stages, from the aligned start
-  u64 src0;         // uniform: payload word index of the aligned start
-  u64 payload_words;
+  u32 src0;         // uniform: payload word index of the aligned start
+  u32 room;         // uniform: words from src0 to the end of the caller's buffer
 };
 
 // The tables of operand s for the wave's segment (seg: the same in every lane; b: the lane's
@@ -168,9 +239,8 @@ __device__ inline OperandMeta load_operand_tables(const ReduceArgs& a, int s, u3
   const u8* base = a.in[s].base;
   m.seg_off = SegmentOffsetParts{0, 0, 0};
   if (seg_ok) m.seg_off = load_segment_offset(a.index, s, seg, zero);
-  m.total_bytes = *reinterpret_cast<const u64*>(at_bytes(base, zero + 24u));
+  m.payload_room = 0;
   m.w = w_ok ? u32(*at_bytes(base, kHeaderBytes + b)) : 0u;
-  m.outlier = 0;
   return m;
 }
 
@@ -179,25 +249,36 @@ __device__ inline i32 load_operand_outlier(const ReduceArgs& a, int s, const Par
   return active ? *reinterpret_cast<const i32*>(at_bytes(base, kHeaderBytes + u32(pad16(h.nb)) + 4u * b)) : 0;
 }
 
+__device__ inline u32 payload_room(const ReduceArgs& a, int s, const ParsedHeader& h) {
+  const u64 tend = tables_end(h.nb);
+  const u64 room = a.in[s].bytes > tend ? (a.in[s].bytes - tend) / 4 : 0;
+  return room > 0xffffffffull ? 0xffffffffu : u32(room);   // a stream's payload has at most 2^31 words
+}
+
+// The payload is fenced in by the size of the caller's buffer, which a validated stream does
+// not exceed (a 16-byte load may run up to 12 bytes past the stream's own end, inside the
+// buffer; nothing reads those words).
 __device__ inline OperandMeta load_operand_meta(const ReduceArgs& a, int s, const ParsedHeader& h, u32 seg, u32 b,
                                                 bool active, bool seg_live) {
   OperandMeta m = load_operand_tables(a, s, seg, b, active, seg_live);
-  m.outlier = load_operand_outlier(a, s, h, b, active);
+  m.payload_room = payload_room(a, s, h);
   return m;
 }
 
 __device__ inline OperandPlace place_operand(const OperandMeta& m, const ParsedHeader& h) {
   OperandPlace p;
-  // the same in every lane, and long since loaded: into scalar registers
-  const u64 seg_off = segment_offset(m.seg_off);
-  p.payload_words = (m.total_bytes - tables_end(h.nb)) / 4;
+  // the same in every lane, and long since loaded: into scalar registers, 32-bit arithmetic
+  const u64 seg_off64 = uniform64(segment_offset(m.seg_off));
+  const u32 seg_off = u32(seg_off64);
   const u32 w = m.w > 15 ? 0u : m.w;           // cannot happen here; keeps every LDS access in range
   const u32 words = psize_words(w);
   const u32 incl = wave_inclusive_sum(words);
   const u32 wave_total = lane_value(incl, 63);
-  const bool inside = seg_off + wave_total <= p.payload_words;   // true on a validated stream
-  const u32 mis = u32(seg_off) & 3u;
+  // true on a validated stream
+  const bool inside = (seg_off64 >> 32) == 0 && seg_off <= m.payload_room && wave_total <= m.payload_room - seg_off;
+  const u32 mis = seg_off & 3u;
   p.src0 = seg_off - mis;
+  p.room = m.payload_room - p.src0;
   p.span = inside ? mis + wave_total : 0u;     // <= 3 + 64 * 16
   p.pick = mis + (incl - words);
   p.w = inside ? w : 0u;
@@ -207,36 +288,44 @@ __device__ inline OperandPlace place_operand(const OperandMeta& m, const ParsedH
 
 // The operand's payload for this wave: 16 bytes per lane and load, all in flight together.
 // The copy starts at the 16-byte boundary at or below the segment (the payload area itself is
-// 16-byte aligned) and keeps that misalignment in LDS.
+// 16-byte aligned) and keeps that misalignment in LDS.  Four loads cover 1024 words; a wave
+// whose 64 blocks are all 15 bits wide can need up to three more words, which stage_to_lds
+// fetches on the spot.
+constexpr int kStageLoads = 4;
 struct OperandStage {
-  uint4 v[5];
+  uint4 v[kStageLoads];
 };
 
 __device__ inline OperandStage load_operand_payload(const u32* payload, const OperandPlace& p, int lane) {
   OperandStage st;
+  const u32* src = payload + p.src0;             // uniform
 #pragma unroll
-  for (int i = 0; i < 5; ++i) {
+  for (int i = 0; i < kStageLoads; ++i) {
     const u32 idx = 4u * u32(lane) + 256u * u32(i);
     st.v[i] = make_uint4(0, 0, 0, 0);
     if (idx < p.span) {
-      if (p.src0 + idx + 4 <= p.payload_words) {
-        st.v[i] = *reinterpret_cast<const uint4*>(payload + p.src0 + idx);
-      } else {                                     // the last words of the stream
-        const u64 left = p.payload_words - (p.src0 + idx);
-        st.v[i].x = payload[p.src0 + idx];
-        if (left > 1) st.v[i].y = payload[p.src0 + idx + 1];
-        if (left > 2) st.v[i].z = payload[p.src0 + idx + 2];
+      if (idx + 4 <= p.room) {
+        st.v[i] = load_once(reinterpret_cast<const uint4*>(src + idx));
+      } else {                                     // the last words of the caller's buffer
+        const u32 left = p.room - idx;
+        st.v[i].x = src[idx];
+        if (left > 1) st.v[i].y = src[idx + 1];
+        if (left > 2) st.v[i].z = src[idx + 2];
       }
     }
   }
   return st;
 }
 
-__device__ inline void stage_to_lds(const OperandStage& st, const OperandPlace& p, u32* wl, int lane) {
+__device__ inline void stage_to_lds(const OperandStage& st, const OperandPlace& p, const u32* payload, u32* wl, int lane) {
 #pragma unroll
-  for (int i = 0; i < 5; ++i) {
+  for (int i = 0; i < kStageLoads; ++i) {
     const u32 idx = 4u * u32(lane) + 256u * u32(i);
     if (idx < p.span) *reinterpret_cast<uint4*>(wl + idx) = st.v[i];
+  }
+  if (p.span > 256u * kStageLoads) {               // uniform, and rare: words 1024 .. 1026
+    const u32 idx = 256u * kStageLoads + u32(lane);
+    if (idx < p.span) wl[idx] = payload[p.src0 + idx];
   }
 }
 
@@ -326,13 +415,22 @@ __device__ inline u32 sign_plane(const u32 (&acc)[kSumPlanes], u32 top) {
   }
 }
 
-__global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
-  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
+// The lane number, in a way that keeps the compiler from recognising two calls as the same value.
+// What an operand step derives from the lane number is cheap to compute and is computed on
+// the spot: hoisted out of the loop over the operands it would sit in registers that the
+// adder needs.
+__device__ inline int fresh_lane() {
+  int lane = lane_id();
+  asm volatile("" : "+v"(lane));
+  return lane;
+}
+
+__global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWholeStage];   // also holds an operand's payload
   __shared__ u32 sh_tile;
   __shared__ u32 sh_wave_total[kTileWaves];
   __shared__ u64 sh_base;
 
-  const int lane = lane_id();
   const int wave = wave_id();
 
   // A workgroup that takes the tile of its own number asks for the first operand's tables
@@ -342,8 +440,8 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
   const u32 zero = opaque_zero();
   OperandMeta meta;
   if (early) {
-    const u32 seg = blockIdx.x * kTileWaves + u32(wave);     // < 2^22: the host launches at most 2^20 tiles
-    const u32 b = seg * kWaveBlocks + u32(lane);
+    const u32 seg = blockIdx.x * kTileWaves + u32(wave);     // < 2^22: the host launches at most 2^18 tiles
+    const u32 b = seg * kWaveBlocks + u32(fresh_lane());
     meta = load_operand_tables(a, 0, seg, b, u64(kHeaderBytes) + b < a.in[0].bytes, seg < 4 * a.index.tiles_cap, zero);
   }
   const uint2 gate = load_gate(a.ctl, zero);
@@ -363,17 +461,27 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
   }
   if (tile >= ntiles) return;
 
-  u32* const wl = lds + wave * kWaveStage;
+  u32* const wl = lds + wave * kWholeStage;
   const u32 seg = tile * kTileWaves + u32(wave);
   const bool seg_live = seg < num_segments(h.nb);
-  const u32 b = seg * kWaveBlocks + u32(lane);
-  const bool active = b < h.nb;
-  if (early) {
-    if (!active) meta.w = 0;
-    if (!seg_live) meta.seg_off = SegmentOffsetParts{0, 0, 0};
-    meta.outlier = load_operand_outlier(a, 0, h, b, active);
-  } else {
-    meta = load_operand_meta(a, 0, h, seg, b, active, seg_live);
+  OperandPlace next;
+  OperandStage stage;
+  i32 outlier_next;        // the outlier of the operand in `stage`: travels with the payload
+  {
+    const int lane = fresh_lane();
+    const u32 b = seg * kWaveBlocks + u32(lane);
+    const bool active = b < h.nb;
+    if (early) {
+      if (!active) meta.w = 0;
+      if (!seg_live) meta.seg_off = SegmentOffsetParts{0, 0, 0};
+      meta.payload_room = payload_room(a, 0, h);
+    } else {
+      meta = load_operand_meta(a, 0, h, seg, b, active, seg_live);
+    }
+    next = place_operand(meta, h);
+    if (a.k > 1) meta = load_operand_meta(a, 1, h, seg, b, active, seg_live);
+    stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[0].base + tend), next, lane);
+    outlier_next = load_operand_outlier(a, 0, h, b, active);
   }
 
   // ---- add the k operands' blocks in plane form; loads run ahead of the adds ----
@@ -383,20 +491,19 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
   u32 top = 0;
   u32 bound = 0;          // wave-uniform bound on |sum of deltas| so far (< 64 * 2^16)
   i64 outlier = 0;
-
-  OperandPlace next = place_operand(meta, h);
-  const i32 outlier0 = meta.outlier;      // may still be on its way: added after the loop
-  if (a.k > 1) meta = load_operand_meta(a, 1, h, seg, b, active, seg_live);
-  OperandStage stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[0].base + tend), next, lane);
   for (int s = 0; s < a.k; ++s) {
+    const int lane = fresh_lane();
+    const u32 b = seg * kWaveBlocks + u32(lane);
+    const bool active = b < h.nb;
     const OperandPlace cur = next;
-    stage_to_lds(stage, cur, wl, lane);
+    stage_to_lds(stage, cur, reinterpret_cast<const u32*>(a.in[s].base + tend), wl, lane);
     wave_lds_sync();
+    outlier += i64(outlier_next);
     if (s + 1 < a.k) {
       next = place_operand(meta, h);
-      outlier += i64(meta.outlier);
       if (s + 2 < a.k) meta = load_operand_meta(a, s + 2, h, seg, b, active, seg_live);
       stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[s + 1].base + tend), next, lane);
+      outlier_next = load_operand_outlier(a, s + 1, h, b, active);
     }
     if (cur.wcap) {
       bound += (1u << cur.wcap) - 1u;
@@ -413,7 +520,6 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
     wave_lds_sync();
   }
 
-  outlier += i64(outlier0);
   // ---- back to sign + magnitude planes; new code length; placement and copy-out ----
   const u32 sgn = sign_plane<0>(acc, top);
   u32 carry = sgn, w = 0;
@@ -423,8 +529,10 @@ __global__ __launch_bounds__(kTileThreads, 5) void reduce_kernel(ReduceArgs a) {
     if constexpr (I == 0) return sgn;
     else return acc[I - 1];
   };
-  place_sum<kSumPlanes>(a, h, acc, sgn, w, outlier, active, b, tile, ntiles, word, wl, sh_wave_total, &sh_base, wave,
-                        lane);
+  const int lane = fresh_lane();
+  const u32 b = seg * kWaveBlocks + u32(lane);
+  place_sum_staged<kSumPlanes>(a, h, acc, sgn, w, outlier, b < h.nb, b, tile, ntiles, word, wl, sh_wave_total, &sh_base,
+                               wave, lane);
 }
 
 // ---------------------------------------------------------------------------------------
