@@ -6,8 +6,9 @@
 // (Section 3.3, the paragraph that introduces fZ-light: multi-layer blocks, fused
 // quantisation + Lorenzo prediction, a 4-byte first-value outlier, sign bits, a one-byte
 // code length "log max", fixed-length bit-shifting encoding, constant blocks; Section 3.1.2
-// and the Sum aggregation equation of Section 3.2 for the reduce step; the statement in
-// Section 3.2 that a once-compressed point stays within the error bound).
+// and the Sum aggregation equation of Section 3.2 for the reduce step and for one round of
+// the ring reduce-scatter; the statement in Section 3.2 that a once-compressed point stays
+// within the error bound).
 // Only tests, the smoke check and the benchmark's CPU-baseline leg may call it.  It shares
 // no code, header, table or constant with the HIP library.
 //
@@ -332,6 +333,40 @@ int zcref_reduce(const void* const* chunks, const size_t* chunk_bytes, int k,
     q[j] = int32_t(total[j]);
   }
   return encode_codes(q.data(), n, ps[0].eb_bits, uint32_t(nsum), static_cast<uint8_t*>(out), out_cap, out_bytes);
+}
+
+// One round of the ring reduce-scatter (Section 3.1.2: per round a received compressed chunk
+// is decompressed, reduced with the local chunk and compressed again; the Sum chain of
+// Section 3.2 adds one bounded error per such round).  The received stream is decoded to
+// binary32 values, the local uncompressed values are added in binary32, and the sums are
+// compressed under the stream's own bound.  nsum grows by one.
+// Status precedence: ARG, FORMAT, MISMATCH (n_local differs from the stream's n), NONFINITE,
+// RANGE, CAPACITY, BOUND (measured against the binary32 sums).
+int zcref_reduce_step(const void* in, size_t in_bytes, const float* local, size_t n_local,
+                      void* out, size_t out_cap, size_t* out_bytes) {
+  if (!in || !out) return ERR_ARG;
+  Parsed ps;
+  int st = parse_stream(static_cast<const uint8_t*>(in), in_bytes, &ps);
+  if (st != OK) return st;
+  if (ps.n != n_local) return ERR_MISMATCH;
+  if (ps.n && !local) return ERR_ARG;
+  if (uint64_t(ps.nsum) + 1 > 0xFFFFFFFFull) return ERR_RANGE;
+  const size_t n = size_t(ps.n);
+  const float eb = bits_to_float(ps.eb_bits);
+  const double s = quant_step(eb);
+  std::vector<int32_t> q(n);
+  decode_codes(ps, q.data());
+  std::vector<float> y(n);
+  for (size_t i = 0; i < n; ++i) y[i] = dequantize_one(q[i], s) + local[i];
+  st = zcref_quantize(y.data(), n, eb, q.data());
+  if (st != OK) return st;
+  st = encode_codes(q.data(), n, ps.eb_bits, ps.nsum + 1, static_cast<uint8_t*>(out), out_cap, out_bytes);
+  if (st != OK) return st;
+  for (size_t i = 0; i < n; ++i) {
+    double err = std::fabs(double(y[i]) - double(dequantize_one(q[i], s)));
+    if (!(err <= double(eb))) return ERR_BOUND;
+  }
+  return OK;
 }
 
 }  // extern "C"

@@ -30,6 +30,8 @@ def lib():
         L.zcref_decompress.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                                        C.POINTER(C.c_size_t)]
         L.zcref_inspect.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.zcref_reduce_step.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
+                                        C.POINTER(C.c_size_t)]
         L.zcref_reduce.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_size_t), C.c_int, C.c_void_p,
                                    C.c_size_t, C.POINTER(C.c_size_t)]
         _lib = L
@@ -115,4 +117,17 @@ def reduce(streams, out_cap=None):
     out = np.zeros(max(out_cap, 1), dtype=np.uint8)
     nbytes = C.c_size_t(0)
     st = lib().zcref_reduce(ptrs, sizes, k, _ptr(out), out_cap, C.byref(nbytes))
+    return st, (out[: nbytes.value].copy() if st == OK else out[:0]), nbytes.value
+
+
+def reduce_step(stream, local, out_cap=None):
+    """One ring round: decompress `stream`, add `local` (binary32), compress again.
+    Returns (status, stream bytes, total_bytes reported)."""
+    stream = np.ascontiguousarray(stream, dtype=np.uint8)
+    local = np.ascontiguousarray(local, dtype=np.float32)
+    if out_cap is None:
+        out_cap = compress_bound(local.size)
+    out = np.zeros(max(out_cap, 1), dtype=np.uint8)
+    nbytes = C.c_size_t(0)
+    st = lib().zcref_reduce_step(_ptr(stream), stream.size, _ptr(local), local.size, _ptr(out), out_cap, C.byref(nbytes))
     return st, (out[: nbytes.value].copy() if st == OK else out[:0]), nbytes.value

@@ -372,3 +372,83 @@ def test_stream_size_monotone_in_error_bound(zcref):
         const_share.append(np.mean(zcref.inspect(s)[2] == 0))
     assert sizes == sorted(sizes)
     assert const_share == sorted(const_share, reverse=True)
+
+
+# ---------------- P9: one ring round (decompress, add the local chunk, compress again) ----------------
+def test_reduce_step_codes_chosen_by_hand(zcref):
+    """The received stream holds codes q; the local values sit a quarter of a step above m
+    whole steps, so every sum lies a quarter step above grid point q + m and must round to it:
+    the output is the encoding of q + m (numpy model of the stream), with nsum = 2.  A wrong
+    sign, a shifted index or a dropped operand changes the codes."""
+    eb = 1e-2
+    s = lm.step(eb)
+    rng = np.random.default_rng(5)
+    for n in (1, 31, 32, 33, 100, 4096 + 7):
+        q = rng.integers(-500, 500, n)
+        m = rng.integers(-300, 300, n)
+        received, _, _ = lm.stream_from_codes(q, eb)
+        local = ((m + 0.25) * s).astype(np.float32)
+        st, out, total = zcref.reduce_step(received, local)
+        assert st == zcref.OK and total == out.size
+        want, _, _ = lm.stream_from_codes(q + m, eb, nsum=2)
+        assert out.tobytes() == want.tobytes()
+
+
+def test_reduce_step_special_cases(zcref):
+    """Adding zeros changes nothing but the operand count (grid points quantise to
+    themselves); adding to a stream of zeros is compressing the local chunk."""
+    x = synth.power_law_field((4, 32, 33), seed=3).numpy().ravel()
+    y = synth.power_law_field((4, 32, 33), seed=4).numpy().ravel()
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    _, sx, _ = zcref.compress(x, eb)
+    st, out, _ = zcref.reduce_step(sx, np.zeros_like(x))
+    assert st == zcref.OK
+    want = sx.copy(); want[20:24] = np.frombuffer(np.uint32(2).tobytes(), np.uint8)
+    assert out.tobytes() == want.tobytes()
+    _, s0, _ = zcref.compress(np.zeros_like(x), eb)
+    st, out, _ = zcref.reduce_step(s0, y)
+    _, sy, _ = zcref.compress(y, eb)
+    want = sy.copy(); want[20:24] = np.frombuffer(np.uint32(2).tobytes(), np.uint8)
+    assert st == zcref.OK and out.tobytes() == want.tobytes()
+
+
+def test_reduce_step_error_chain(zcref):
+    """Section 3.2, Sum aggregation along the ring: every round adds one error of at most eb,
+    so after compressing the first chunk and N - 1 rounds the result is within N * eb of the
+    exact sum (float64 here), and each single round is within eb of what it was given."""
+    N = 6
+    xs = [synth.power_law_field((8, 32, 32), seed=20 + i).numpy().ravel() for i in range(N)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), 1e-3)
+    st, s, _ = zcref.compress(xs[0], eb)
+    assert st == zcref.OK
+    for i in range(1, N):
+        _, before, _ = zcref.decompress(s)
+        st, s, _ = zcref.reduce_step(s, xs[i])
+        assert st == zcref.OK
+        _, after, _ = zcref.decompress(s)
+        given = before.astype(np.float64) + xs[i].astype(np.float64)
+        assert np.abs(after.astype(np.float64) - given).max() <= eb * (1 + 1e-6)
+        assert int(s[20:24].view("<u4")[0]) == i + 1
+    exact = np.sum([x.astype(np.float64) for x in xs], axis=0)
+    _, y, _ = zcref.decompress(s)
+    err = y.astype(np.float64) - exact
+    assert np.abs(err).max() <= N * eb
+    sigma = lm.step(eb) / np.sqrt(12.0)
+    assert abs(np.sqrt(np.mean(err ** 2)) / (np.sqrt(N) * sigma) - 1) < 0.10
+
+
+def test_reduce_step_errors(zcref):
+    x = synth.power_law_field((2, 16, 32), seed=1).numpy().ravel()
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    _, s, _ = zcref.compress(x, eb)
+    assert zcref.reduce_step(s, x[:-1])[0] == zcref.ERR_MISMATCH
+    bad = s.copy(); bad[0] ^= 1
+    assert zcref.reduce_step(bad, x)[0] == zcref.ERR_FORMAT
+    y = x.copy(); y[5] = np.inf
+    assert zcref.reduce_step(s, y)[0] == zcref.ERR_NONFINITE
+    y = x.copy(); y[5] = np.float32(eb * 2.0 ** 32)
+    assert zcref.reduce_step(s, y)[0] == zcref.ERR_RANGE
+    assert zcref.reduce_step(s, x, out_cap=40)[0] == zcref.ERR_CAPACITY
+    y = x.copy(); y[7] = np.float32(eb * 2.0 ** 27)            # outside the guaranteed domain
+    st, out, _ = zcref.reduce_step(s, y)
+    assert st in (zcref.OK, zcref.ERR_BOUND)
