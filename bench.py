@@ -192,6 +192,28 @@ def main():
                 res[name] = {"ms": round(ms, 4), "fp32_GBps": round(4 * n / ms / 1e6, 1),
                              "hbm_frac": round((4 * n + cb) / ms / 1e6 / HBM_PEAK_GBS, 4)}
             extras[f"rel_{rel:g}"] = res
+        # one round of the ring reduce-scatter at the shape of the reduce above: the received
+        # stream of rank 0 plus the uncompressed buffer of rank 1 -> stream of the sums
+        st, s_bytes = zc.zc_reduce_step(chunks[0], chunk_bytes[0], ranks[1], m, d_red, ws_r)
+        check(st, "reduce_step extra")
+        for _ in range(5):
+            zc.zc_reduce_step(chunks[0], chunk_bytes[0], ranks[1], m, d_red, ws_r, sync=False)
+        torch.cuda.synchronize()
+        zc.zc_profile_enable(True)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            zc.zc_reduce_step(chunks[0], chunk_bytes[0], ranks[1], m, d_red, ws_r, sync=False)
+        b.record()
+        torch.cuda.synchronize()
+        kt = [ms for name, ms in zc.zc_profile_collect() if name == "reduce_step"]
+        zc.zc_profile_enable(False)
+        ms = a.elapsed_time(b) / 10
+        alg = chunk_bytes[0] + 4 * m + s_bytes
+        extras["reduce_step"] = {"workload": f"received stream of {m} values + {m} local fp32 values -> stream",
+                                 "ms": round(ms, 4), "kernel_ms": round(sum(kt) / len(kt), 4),
+                                 "algorithmic_bytes": alg, "fp32_GBps": round(8 * m / ms / 1e6, 1),
+                                 "hbm_frac": round(alg / (sum(kt) / len(kt)) / 1e6 / HBM_PEAK_GBS, 4)}
 
     # ---------------- reference CPU codec on a bounded sample (same mix as the step) ----------------
     cpu = None

@@ -89,6 +89,20 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
                          void* d_out, size_t out_cap, size_t* out_bytes,
                          void* d_ws, size_t ws_bytes, void* hip_stream);
 
+/* One round of the ring reduce-scatter (Section 3.1.2: a received compressed chunk is
+ * decompressed, reduced with the local chunk and compressed again; Section 3.2, Sum: each such
+ * round adds at most abs_eb to the error).  d_chunk: the received stream (chunk_bytes bytes,
+ * 16-byte aligned).  d_local: n_local binary32 values, 16-byte aligned; n_local must equal
+ * the stream's n.  d_out receives the stream of dequantised(received) + local, the addition in
+ * binary32, under the received stream's own bound; its nsum is the received one + 1.
+ * out_bytes (host, may be NULL): receives total_bytes.  Nothing but the two streams and the
+ * local values moves through memory.
+ * Errors: ARG, FORMAT, MISMATCH, NONFINITE, RANGE, CAPACITY, BOUND (against the binary32
+ * sums; the stream is complete then), HIP. */
+int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local,
+                   void* d_out, size_t out_cap, size_t* out_bytes,
+                   void* d_ws, size_t ws_bytes, void* hip_stream);
+
 /* Completes an asynchronous call: synchronises hip_stream, returns the status of the last
  * call that used d_ws and stores its size result (total_bytes, or n for zc_decompress) in
  * *result (host, may be NULL). */
@@ -112,7 +126,7 @@ int zc_debug_quantize(const float* d_in, size_t n, float abs_eb, int32_t* d_q,
 int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_words, size_t off_cap,
                            void* d_ws, size_t ws_bytes, void* hip_stream);
 
-/* How zc_compress and zc_reduce_compressed hand out their tiles (256 or 512 blocks each) to
+/* How zc_compress, zc_reduce_compressed and zc_reduce_step hand out their tiles (256 or 512 blocks each) to
  * workgroups.  Their single-pass placement (a device-wide exclusive sum of block sizes by
  * look-back) needs every tile before a tile in work to be in work or finished.
  * ZC_HAND_OUT_DISPATCH_ORDER (default): tile = workgroup id; relies on the GPU starting the
@@ -125,9 +139,9 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
 #define ZC_HAND_OUT_TICKETS 1
 int zc_set_tile_hand_out(int mode);
 
-/* Measurement aid (not part of the method).  While enabled, zc_compress, zc_decompress and
- * zc_reduce_compressed record a pair of HIP events on the call's stream around their main
- * kernel (the compress kernel over the full tiles, the decompress kernel, the reduce kernel;
+/* Measurement aid (not part of the method).  While enabled, zc_compress, zc_decompress,
+ * zc_reduce_compressed and zc_reduce_step record a pair of HIP events on the call's stream around
+ * their main kernel (the compress kernel over the full tiles, the decompress, reduce or step kernel;
  * not the small set-up kernels before it).  zc_profile_collect waits for the recorded pairs,
  * stores up to cap elapsed times in milliseconds in ms[] and the matching ZC_KERNEL_* ids in
  * kernel[] (host arrays, either may be NULL) in call order, forgets them, and returns how
@@ -137,6 +151,7 @@ int zc_set_tile_hand_out(int mode);
 #define ZC_KERNEL_COMPRESS 1
 #define ZC_KERNEL_DECOMPRESS 2
 #define ZC_KERNEL_REDUCE 3
+#define ZC_KERNEL_REDUCE_STEP 4
 int zc_profile_enable(int on);
 int zc_profile_collect(float* ms, int* kernel, int cap);
 

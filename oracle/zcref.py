@@ -130,4 +130,4 @@ def reduce_step(stream, local, out_cap=None):
     out = np.zeros(max(out_cap, 1), dtype=np.uint8)
     nbytes = C.c_size_t(0)
     st = lib().zcref_reduce_step(_ptr(stream), stream.size, _ptr(local), local.size, _ptr(out), out_cap, C.byref(nbytes))
-    return st, (out[: nbytes.value].copy() if st == OK else out[:0]), nbytes.value
+    return st, (out[: nbytes.value].copy() if st in (OK, ERR_BOUND) else out[:0]), nbytes.value

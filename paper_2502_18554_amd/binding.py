@@ -17,7 +17,7 @@ ZC_OK, ZC_ERR_ARG, ZC_ERR_CAPACITY, ZC_ERR_FORMAT, ZC_ERR_NONFINITE, ZC_ERR_RANG
 ZC_MAX_K = 64
 
 EXPORTS = [
-    "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_reduce_compressed",
+    "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_step",
     "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
     "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out",
 ]
@@ -47,6 +47,7 @@ def lib():
         L.zc_compress.argtypes = [vp, sz, C.c_float, vp, sz, szp, vp, sz, vp]
         L.zc_decompress.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_compressed.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp]
+        L.zc_reduce_step.argtypes = [vp, sz, vp, sz, vp, sz, szp, vp, sz, vp]
         L.zc_finish.argtypes = [vp, szp, vp]
         L.zc_peek_header.argtypes = [vp, sz, szp, C.POINTER(C.c_float), C.POINTER(C.c_uint), szp, vp]
         L.zc_strerror.restype = C.c_char_p
@@ -113,6 +114,16 @@ def zc_reduce_compressed(d_chunks, chunk_bytes, d_out, d_ws, sync=True, stream=N
     return st, (nbytes.value if sync else None)
 
 
+def zc_reduce_step(d_chunk, chunk_bytes, d_local, n_local, d_out, d_ws, sync=True, stream=None, out_cap=None):
+    """One ring round: received stream + local fp32 values -> stream of the sums.  Returns (status, total_bytes)."""
+    nbytes = C.c_size_t(0)
+    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
+    st = lib().zc_reduce_step(_p(d_chunk), int(chunk_bytes), _p(d_local), int(n_local), _p(d_out), cap,
+                              C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
+                              _stream(stream))
+    return st, (nbytes.value if sync else None)
+
+
 def zc_finish(d_ws, stream=None):
     """Returns (status, size result) of the last asynchronous call that used d_ws."""
     r = C.c_size_t(0)
@@ -138,7 +149,7 @@ def zc_debug_block_offsets(d_in, in_bytes, d_off_words, d_ws, stream=None):
                                         d_ws.numel() * d_ws.element_size(), _stream(stream))
 
 
-KERNEL_NAMES = {1: "compress", 2: "decompress", 3: "reduce"}
+KERNEL_NAMES = {1: "compress", 2: "decompress", 3: "reduce", 4: "reduce_step"}
 
 
 def zc_profile_enable(on):

@@ -12,6 +12,7 @@
 #include "zc_decompress.h"
 #include "zc_reduce.h"
 #include "zc_scan.h"
+#include "zc_step.h"
 
 using namespace zc;
 
@@ -285,6 +286,45 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   g_timer.end(slot, stream);
   // for operands with blocks wider than 15 bits; returns at once otherwise
   hipLaunchKernelGGL(reduce_wide_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
+  if (!launch_ok()) return ZC_ERR_HIP;
+  if (!out_bytes) return ZC_OK;
+  return finish(d_ws, out_bytes, stream);
+}
+
+int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, void* d_out,
+                   size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (!d_chunk || !d_out || !d_ws || (n_local && !d_local) || n_local > ZC_MAX_N) return ZC_ERR_ARG;
+  if (!aligned16(d_chunk) || !aligned16(d_local) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
+  if (chunk_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
+  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
+  u64 tiles = num_tiles(num_blocks(n_local));
+  if (l.tiles_cap < 1 || tiles > l.tiles_cap) return ZC_ERR_ARG;
+  if (tiles < 1) tiles = 1;
+  ScanArgs sa;
+  sa.streams[0].base = static_cast<const u8*>(d_chunk);
+  sa.streams[0].bytes = chunk_bytes;
+  sa.k = 1;
+  sa.check_match = 0;
+  sa.index = l.index;
+  sa.ctl = l.ctl;
+  sa.desc = l.desc;
+  sa.ndesc = u32(tiles);
+  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), 1), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(index_prep_kernel, dim3(u32((tiles + 255) / 256 > 64 ? 64 : (tiles + 255) / 256)), dim3(256), 0, stream, sa);
+  StepArgs ta;
+  ta.in = sa.streams[0];
+  ta.local = d_local;
+  ta.n_local = n_local;
+  ta.index = l.index;
+  ta.out = static_cast<u8*>(d_out);
+  ta.out_cap = out_cap;
+  ta.ctl = l.ctl;
+  ta.desc = l.desc;
+  ta.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
+  KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_REDUCE_STEP, stream);
+  hipLaunchKernelGGL(step_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ta);
+  g_timer.end(slot, stream);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);

@@ -24,6 +24,97 @@ struct DecompressArgs {
   Control* ctl;
 };
 
+// The sign and plane words of the lane's block (width w, 0 for a block that does not exist) out
+// of a stream's payload.  seg_off = payload word offset of the wave's segment.  The wave's
+// payload goes through its LDS staging area `wl` (kWaveStage words); a wave with a block wider
+// than 15 bits fetches per lane instead.  Returns the widest block of the wave.  Widths up to
+// 15: lo[0..15) = planes 0..14, lo[15] = sign word.  Wider: lo[0..16) = planes 0..15,
+// hi[0..15) = planes 16..30, hi[15] = sign word.  `wl` is free again on return.
+__device__ inline u32 wave_block_words(const u32* payload, u64 payload_words, u32 w, u64 seg_off, u32* wl, int lane,
+                                       u32 (&lo)[16], u32 (&hi)[16]) {
+  const u32 words = psize_words(w);
+  const u32 incl = wave_inclusive_sum(words);
+  const u32 off_in_wave = incl - words;
+  const u32 wave_total = lane_value(incl, 63);
+  const u32 wmax = wave_max_u32(w);
+  // a validated stream keeps every segment inside the payload; refuse to read outside anyway
+  const bool inside = seg_off + wave_total <= payload_words;
+#pragma unroll
+  for (int p = 0; p < 16; ++p) lo[p] = 0;
+
+  if (wmax <= 15) {
+    // At most 64 * 16 words.  The copy starts at the 16-byte boundary at or below the segment
+    // (the payload area itself is 16-byte aligned) and keeps that misalignment in LDS, so it
+    // moves 16 bytes per lane and instruction, all loads in flight together.
+    const u32 mis = u32(seg_off) & 3u;
+    const u64 src0 = seg_off - mis;                    // in words, multiple of 4
+    const u32 span = inside ? mis + wave_total : 0u;   // words to bring in, <= 1027
+    uint4 stage[5];
+#pragma unroll
+    for (int i = 0; i < 5; ++i) {
+      const u32 idx = 4u * u32(lane) + 256u * u32(i);
+      stage[i] = make_uint4(0, 0, 0, 0);
+      if (idx < span) {
+        if (src0 + idx + 4 <= payload_words) {
+          stage[i] = *reinterpret_cast<const uint4*>(payload + src0 + idx);
+        } else {                                       // the last words of the stream
+          const u64 left = payload_words - (src0 + idx);
+          stage[i].x = payload[src0 + idx];
+          if (left > 1) stage[i].y = payload[src0 + idx + 1];
+          if (left > 2) stage[i].z = payload[src0 + idx + 2];
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 5; ++i) {
+      const u32 idx = 4u * u32(lane) + 256u * u32(i);
+      if (idx < span) *reinterpret_cast<uint4*>(wl + idx) = stage[i];
+    }
+    wave_lds_sync();
+    if (w && inside) {
+      const u32* mine = wl + mis + off_in_wave;
+      lo[15] = mine[0];
+#pragma unroll
+      for (int p = 0; p < 15; ++p) {
+        if (u32(p) >= wmax) break;
+        if (u32(p) < w) lo[p] = mine[1 + p];
+      }
+    }
+    wave_lds_sync();
+  } else {
+    // a block wider than 15 bits (stream of an input outside the guaranteed domain): each lane
+    // fetches its words straight from global memory
+#pragma unroll
+    for (int p = 0; p < 16; ++p) hi[p] = 0;
+    if (w && inside) {
+      const u32* mine = payload + seg_off + off_in_wave;
+      hi[15] = mine[0];
+#pragma unroll
+      for (int p = 0; p < 16; ++p)
+        if (u32(p) < w) lo[p] = mine[1 + p];
+#pragma unroll
+      for (int p = 0; p < 15; ++p)
+        if (u32(16 + p) < w) hi[p] = mine[17 + p];
+    }
+  }
+  return wmax;
+}
+
+// ... and from those words the block's Lorenzo deltas (bit-matrix transposes back).
+__device__ inline void deltas_from_block_words(u32 wmax, u32 (&lo)[16], u32 (&hi)[16], i32 (&d)[32]) {
+  if (wmax <= 7) {
+    u32 r[8];
+#pragma unroll
+    for (int p = 0; p < 7; ++p) r[p] = lo[p];
+    r[7] = lo[15];
+    deltas_from_planes8(r, d);
+  } else if (wmax <= 15) {
+    deltas_from_planes16(lo, d);
+  } else {
+    deltas_from_planes32(lo, hi, d);
+  }
+}
+
 __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
 
@@ -62,89 +153,12 @@ __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressA
   const u64 payload_words = (h.total - tables_end(h.nb)) / 4;
 
   u32 cur = active ? u32(outliers[b]) : 0u;
-  const u32 words = psize_words(w);
-  const u32 incl = wave_inclusive_sum(words);
-  const u32 off_in_wave = incl - words;
-  const u32 wave_total = lane_value(incl, 63);
   const u64 seg_off = segment_offset(seg_parts);
-  const u32 wmax = wave_max_u32(w);
-  // a validated stream keeps every segment inside the payload; refuse to read outside anyway
-  const bool inside = seg_off + wave_total <= payload_words;
-
-  // ---- the wave's payload through LDS; each lane picks its sign and plane words ----
   i32 d[32];
-  if (wmax <= 15) {
-    // At most 64 * 16 words.  The copy starts at the 16-byte boundary at or below the segment
-    // (the payload area itself is 16-byte aligned) and keeps that misalignment in LDS, so it
-    // moves 16 bytes per lane and instruction, all loads in flight together.
-    const u32 mis = u32(seg_off) & 3u;
-    const u64 src0 = seg_off - mis;                    // in words, multiple of 4
-    const u32 span = inside ? mis + wave_total : 0u;   // words to bring in, <= 1027
-    uint4 stage[5];
-#pragma unroll
-    for (int i = 0; i < 5; ++i) {
-      const u32 idx = 4u * u32(lane) + 256u * u32(i);
-      stage[i] = make_uint4(0, 0, 0, 0);
-      if (idx < span) {
-        if (src0 + idx + 4 <= payload_words) {
-          stage[i] = *reinterpret_cast<const uint4*>(payload + src0 + idx);
-        } else {                                       // the last words of the stream
-          const u64 left = payload_words - (src0 + idx);
-          stage[i].x = payload[src0 + idx];
-          if (left > 1) stage[i].y = payload[src0 + idx + 1];
-          if (left > 2) stage[i].z = payload[src0 + idx + 2];
-        }
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 5; ++i) {
-      const u32 idx = 4u * u32(lane) + 256u * u32(i);
-      if (idx < span) *reinterpret_cast<uint4*>(wl + idx) = stage[i];
-    }
-    wave_lds_sync();
-    u32 pw[16];              // pw[0] = sign, pw[1 + p] = plane p
-#pragma unroll
-    for (int p = 0; p < 16; ++p) pw[p] = 0;
-    if (w && inside) {
-      const u32* mine = wl + mis + off_in_wave;
-      pw[0] = mine[0];
-#pragma unroll
-      for (int p = 0; p < 15; ++p) {
-        if (u32(p) >= wmax) break;
-        if (u32(p) < w) pw[1 + p] = mine[1 + p];
-      }
-    }
-    wave_lds_sync();
-    if (wmax <= 7) {
-      u32 r[8];
-#pragma unroll
-      for (int p = 0; p < 7; ++p) r[p] = pw[1 + p];
-      r[7] = pw[0];
-      deltas_from_planes8(r, d);
-    } else {
-      u32 r[16];
-#pragma unroll
-      for (int p = 0; p < 15; ++p) r[p] = pw[1 + p];
-      r[15] = pw[0];
-      deltas_from_planes16(r, d);
-    }
-  } else {
-    // a block wider than 15 bits (stream of an input outside the guaranteed domain): each lane
-    // fetches its words straight from global memory
+  {
     u32 lo[16], hi[16];
-#pragma unroll
-    for (int p = 0; p < 16; ++p) lo[p] = hi[p] = 0;
-    if (w && inside) {
-      const u32* mine = payload + seg_off + off_in_wave;
-      hi[15] = mine[0];
-#pragma unroll
-      for (int p = 0; p < 16; ++p)
-        if (u32(p) < w) lo[p] = mine[1 + p];
-#pragma unroll
-      for (int p = 0; p < 15; ++p)
-        if (u32(16 + p) < w) hi[p] = mine[17 + p];
-    }
-    deltas_from_planes32(lo, hi, d);
+    const u32 wmax = wave_block_words(payload, payload_words, w, seg_off, wl, lane, lo, hi);
+    deltas_from_block_words(wmax, lo, hi, d);
   }
 
   // ---- Lorenzo chain from the outlier, dequantise ----

@@ -94,15 +94,11 @@ __device__ inline void finish_stream(const PayloadSink& s, const Placement& pl, 
   }
 }
 
-// Back half of a tile once the plane words sit in registers (`word(i)`: 0 = sign, 1 + p =
-// plane p) and its size is published: look back for the base offset, then move the payload
-// out through LDS, one half-wave of blocks at a time (the staging area `wl` of a wave holds
-// kWaveStage words).  Called by every wave of the workgroup; one barrier.
-template <int NW, typename WordFn, typename MeanwhileFn>
-__device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
-                                   u32* wl, u64* sh_base, int wave, int lane, MeanwhileFn meanwhile) {
+// Moves a wave's payload out once the tile's base offset is known: through LDS, one half-wave
+// of blocks at a time (the staging area `wl` of a wave holds kWaveStage words).
+template <int NW, typename WordFn>
+__device__ inline void copy_wave_out(const PayloadSink& s, WordFn word, const Placement& pl, u64 base, u32* wl, int lane) {
   static_assert(32 * NW <= kWaveStage, "a half-wave of widest blocks must fit the staging area");
-  const u64 base = resolve_tile_base(s, pl, tile, sh_base, wave, lane, meanwhile);
   const u64 tend = tables_end(s.nb);
   const u64 cap_words = s.out_cap > tend ? (s.out_cap - tend) / 4 : 0;
   u32* const payload = reinterpret_cast<u32*>(s.out + tend);
@@ -115,6 +111,16 @@ __device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Plac
     stage_and_copy_half<NW>(word, pl.w, (lane >> 5) == h, pl.off_in_wave - half_base[h], half_total[h], wl,
                             payload + d0, cap_words > d0 ? cap_words - d0 : 0, lane);
   }
+}
+
+// Back half of a tile once the plane words sit in registers (`word(i)`: 0 = sign, 1 + p =
+// plane p) and its size is published: look back for the base offset, then move the payload
+// out.  Called by every wave of the workgroup; one barrier.
+template <int NW, typename WordFn, typename MeanwhileFn>
+__device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
+                                   u32* wl, u64* sh_base, int wave, int lane, MeanwhileFn meanwhile) {
+  const u64 base = resolve_tile_base(s, pl, tile, sh_base, wave, lane, meanwhile);
+  copy_wave_out<NW>(s, word, pl, base, wl, lane);
   finish_stream(s, pl, tile, ntiles, base);
 }
 

@@ -1,0 +1,250 @@
+// One round of the ring reduce-scatter in a single kernel (Section 3.1.2: per round the
+// received compressed chunk is decompressed, reduced with the local chunk and compressed again;
+// Section 3.2: the Sum chain adds one bounded error per round).
+//
+// The local chunk is uncompressed binary32, so unlike the k-way reduce of zc_reduce.h this
+// step has to leave the integer domain: decode the received codes, dequantise, add the local
+// values in binary32, quantise the sums on the stream's own grid, and encode again.  It is
+// the decompression kernel's front half (stream index -> payload through LDS -> deltas) and
+// the compression kernel's back half (deltas -> width -> planes -> look-back placement) around
+// one addition, with nothing written to memory in between: 4 bytes per value of local input
+// plus the two streams, instead of the 12 more that separate decompress, add and compress
+// calls would move.
+//
+// Geometry: tiles of 256 blocks, one wave per 64 blocks, one lane per block.  The local
+// values arrive as coalesced 16-byte loads (lane = 4 consecutive values), asked for before
+// anything else, and are transposed through the wave's LDS area (64 rows of one block) so
+// that a lane finds its block's 32 values in its own row.
+#pragma once
+
+#include "zc_bitmatrix.h"
+#include "zc_common.h"
+#include "zc_compress.h"
+#include "zc_decompress.h"
+#include "zc_place.h"
+#include "zc_scan.h"
+
+namespace zc {
+
+struct StepArgs {
+  StreamRef in;
+  const float* local;
+  u64 n_local;
+  StreamIndex index;
+  u8* out;
+  u64 out_cap;
+  Control* ctl;
+  u64* desc;
+  u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
+};
+
+constexpr int kStepStage = kWaveBlocks * kStageRow;     // 64 rows of 36 words = 9 KiB per wave
+static_assert(kStepStage >= kWaveStage, "the payload staging of the decoder must fit too");
+
+// Header fields and table padding of the output stream; one thread.
+__device__ inline void write_step_header(const StepArgs& a, const ParsedHeader& h, u32 ntiles) {
+  const u64 tend = tables_end(h.nb);
+  const u64 nsum = u64(h.nsum) + 1;
+  if (nsum > 0xffffffffull) atomicOr(&a.ctl->status, status_bit(ZC_ERR_RANGE));
+  if (a.out_cap >= tend) {
+    u32* hw = reinterpret_cast<u32*>(a.out);
+    hw[0] = kMagic;
+    hw[1] = 1u | (5u << 16) | (6u << 24);
+    hw[2] = u32(h.n);
+    hw[3] = u32(h.n >> 32);
+    hw[4] = h.eb_bits;
+    hw[5] = u32(nsum);
+    if (ntiles == 0) {
+      hw[6] = u32(tend);
+      hw[7] = u32(tend >> 32);
+    }
+    for (u64 i = h.nb; i < pad16(h.nb); ++i) a.out[kHeaderBytes + i] = 0;
+    u8* ot = a.out + kHeaderBytes + pad16(h.nb);
+    for (u64 i = 4 * h.nb; i < pad16(4 * h.nb); ++i) ot[i] = 0;
+  } else {
+    atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
+  }
+  if (ntiles == 0) a.ctl->result = tend;
+}
+
+__global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kStepStage];
+  __shared__ u32 sh_tile;
+  __shared__ u32 sh_wave_total[kTileWaves];
+  __shared__ u64 sh_base;
+
+  const int lane = lane_id();
+  const int wave = wave_id();
+  u32* const wl = lds + wave * kStepStage;
+
+  // Everything that can be asked for before the header is known goes out at once.  A workgroup
+  // that takes the tile of its own number also asks for its local values, its segment's
+  // position and its width bytes (fenced in by sizes the host passed).
+  const bool early = !a.ticketed;
+  const u32 zero = opaque_zero();
+  const uint2 gate = load_gate(a.ctl, zero);
+  const HeaderWords hw = load_header_words(a.in.base, zero);
+  float4 x[8];
+  SegmentOffsetParts seg_parts{0, 0, 0};
+  u32 w = 0;
+  if (early) {
+    const u32 seg = blockIdx.x * kTileWaves + u32(wave);
+    const u32 b = seg * kWaveBlocks + u32(lane);
+    const u64 v0 = u64(seg) * kWaveBlocks * kBlockValues;
+    const bool whole = v0 + u64(kWaveBlocks) * kBlockValues <= a.n_local;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const u64 idx = v0 + u64(256 * i + 4 * lane);
+      if (whole) {
+        x[i] = *reinterpret_cast<const float4*>(a.local + idx);
+      } else {
+        x[i].x = idx + 0 < a.n_local ? a.local[idx + 0] : 0.0f;
+        x[i].y = idx + 1 < a.n_local ? a.local[idx + 1] : 0.0f;
+        x[i].z = idx + 2 < a.n_local ? a.local[idx + 2] : 0.0f;
+        x[i].w = idx + 3 < a.n_local ? a.local[idx + 3] : 0.0f;
+      }
+    }
+    if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, 0, seg, zero);
+    if (u64(kHeaderBytes) + b < a.in.bytes) w = u32(*at_bytes(a.in.base, kHeaderBytes + b));
+  }
+
+  const ParsedHeader h = parse_header(hw, a.in.bytes);
+  if (gate_failed(gate) || !h.ok) return;
+  if (a.n_local != h.n) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_MISMATCH));
+    return;
+  }
+  const u64 tend = tables_end(h.nb);
+  const u32 ntiles = u32(num_tiles(h.nb));
+  if (blockIdx.x == 0 && threadIdx.x == 0) write_step_header(a, h, ntiles);
+  if (ntiles == 0) return;
+
+  u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
+  if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
+    if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
+    __syncthreads();
+    tile = uniform(sh_tile);
+  }
+  if (tile >= ntiles) return;
+
+  const u32 seg = tile * kTileWaves + u32(wave);
+  const bool seg_live = seg < num_segments(h.nb);
+  const u32 b = seg * kWaveBlocks + u32(lane);
+  const bool active = b < h.nb;
+  const u64 v0 = u64(seg) * kWaveBlocks * kBlockValues;
+  if (!early) {
+    const bool whole = v0 + u64(kWaveBlocks) * kBlockValues <= h.n;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const u64 idx = v0 + u64(256 * i + 4 * lane);
+      if (whole) {
+        x[i] = *reinterpret_cast<const float4*>(a.local + idx);
+      } else {
+        x[i].x = idx + 0 < h.n ? a.local[idx + 0] : 0.0f;
+        x[i].y = idx + 1 < h.n ? a.local[idx + 1] : 0.0f;
+        x[i].z = idx + 2 < h.n ? a.local[idx + 2] : 0.0f;
+        x[i].w = idx + 3 < h.n ? a.local[idx + 3] : 0.0f;
+      }
+    }
+    if (seg_live) seg_parts = load_segment_offset(a.index, 0, seg);
+    w = active ? u32(*at_bytes(a.in.base, kHeaderBytes + b)) : 0u;
+  }
+  if (!active) w = 0;
+  if (!seg_live) seg_parts = SegmentOffsetParts{0, 0, 0};
+  u32 cur = active ? u32(reinterpret_cast<const i32*>(a.in.base + kHeaderBytes + pad16(h.nb))[b]) : 0u;
+
+  // ---- the received block's sign and plane words; then the local values, one block per row
+  //      of the same LDS area; then the received block's deltas ----
+  u32 lo[16], hi[16];
+  const u32 wmax_in = wave_block_words(reinterpret_cast<const u32*>(a.in.base + tend), (h.total - tend) / 4, w,
+                                       segment_offset(seg_parts), wl, lane, lo, hi);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *reinterpret_cast<float4*>(wl + (8 * i + (lane >> 3)) * kStageRow + 4 * (lane & 7)) = x[i];
+  wave_lds_sync();
+  i32 d[32];
+  deltas_from_block_words(wmax_in, lo, hi, d);
+
+  // ---- codes in, sums, codes out, new deltas (in place) ----
+  CompressArgs qa;               // the quantiser's constants, from the stream's own bound
+  const float eb = __uint_as_float(h.eb_bits);
+  qa.step = double(eb) * 63.0 / 32.0;
+  qa.inv = 1.0 / qa.step;
+  qa.eb = double(eb);
+  qa.screen = eb * 131072.0f;
+  u32 err = 0;
+  const u64 cnt64 = active ? h.n - u64(b) * kBlockValues : 0;      // values of this block that exist
+  const u32 cnt = cnt64 < 32 ? u32(cnt64) : 32u;
+  i32 outlier = 0, prev = 0, top = 0, bottom = 0;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const float4 l4 = *reinterpret_cast<const float4*>(wl + lane * kStageRow + 4 * t);
+    const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = 4 * t + u;
+      cur += u32(d[j]);
+      const float y = float(__dmul_rn(double(i32(cur)), qa.step)) + lv[u];
+      i32 q = prev;                                   // the last block repeats its last code
+      if (u32(j) < cnt) q = quantize_value(y, qa, err);
+      if (j == 0) outlier = q;
+      const i32 nd = j ? q - prev : 0;
+      top = max(top, nd);
+      bottom = min(bottom, nd);
+      d[j] = nd;
+      prev = q;
+    }
+  }
+  wave_lds_sync();
+
+  // ---- width, tables, placement ----
+  const u32 any = max(u32(top), u32(-bottom));
+  Placement pl;
+  pl.w = (active && any) ? 32u - u32(__builtin_clz(any)) : 0u;
+  pl.wmax = wave_max_u32(pl.w);
+  if (active && a.out_cap >= tend) {
+    a.out[kHeaderBytes + b] = u8(pl.w);
+    reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(h.nb))[b] = outlier;
+  }
+  const u32 words = psize_words(pl.w);
+  const u32 incl = wave_inclusive_sum(words);
+  pl.wave_total = lane_value(incl, 63);
+  pl.half0_total = lane_value(incl, 31);
+  pl.off_in_wave = incl - words;
+  if (lane == 0) sh_wave_total[wave] = pl.wave_total;
+  lds_barrier();                // the wave totals; the stores above stay in flight
+  pl.wave_off = 0;
+  pl.tile_total = 0;
+#pragma unroll
+  for (int i = 0; i < kTileWaves; ++i) {
+    const u32 t = sh_wave_total[i];
+    if (i < wave) pl.wave_off += t;
+    pl.tile_total += t;
+  }
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc};
+  if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total);
+  if (err) atomicOr(&a.ctl->status, err);
+  const u64 base = resolve_tile_base(sink, pl, tile, &sh_base, wave, lane);
+
+  // ---- deltas -> sign + plane words, out through LDS ----
+  if (pl.wmax <= 15) {           // per wave: each wave copies its own words
+    u32 pw[16];
+    planes_from_deltas16(d, pw);
+    copy_wave_out<16>(sink, [&](auto i) {
+      constexpr int I = decltype(i)::value;          // 0: sign, 1 + p: plane p
+      if constexpr (I == 0) return pw[15];
+      else return pw[I - 1];
+    }, pl, base, wl, lane);
+  } else {
+    u32 lo[16], hi[16];
+    planes_from_deltas32(d, lo, hi);
+    copy_wave_out<32>(sink, [&](auto i) {
+      constexpr int I = decltype(i)::value;
+      if constexpr (I == 0) return hi[15];
+      else if constexpr (I <= 16) return lo[I - 1];
+      else return hi[I - 17];
+    }, pl, base, wl, lane);
+  }
+  finish_stream(sink, pl, tile, ntiles, base);
+}
+
+}  // namespace zc

@@ -55,6 +55,21 @@ def gpu_reduce(streams, n, out_cap=None, ws=None):
     return st, (d_out[: min(total, cap)].cpu().numpy() if st == zc.binding.ZC_OK else None), total
 
 
+def gpu_reduce_step(stream, local, out_cap=None, ws=None, n_local=None):
+    """-> (status, stream bytes, total_bytes)"""
+    d_in = to_dev(stream)
+    d_loc = to_dev(np.ascontiguousarray(local, dtype=np.float32)) if len(local) else torch.zeros(4, device=DEV)
+    n = len(local) if n_local is None else n_local
+    cap = zc.zc_compress_bound(n) if out_cap is None else out_cap
+    d_out = torch.full((cap + 64,), 0x3C, dtype=torch.uint8, device=DEV)
+    ws = workspace(max(n, 1)) if ws is None else ws
+    st, total = zc.zc_reduce_step(d_in, d_in.numel(), d_loc, n, d_out, ws, out_cap=cap)
+    assert bool((d_out[cap:] == 0x3C).all()), "wrote past out_cap"
+    torch.cuda.synchronize()
+    ok = st in (zc.binding.ZC_OK, zc.binding.ZC_ERR_BOUND)
+    return st, (d_out[: min(total, cap)].cpu().numpy() if ok else None), total
+
+
 def first_diff(a, b):
     a = np.asarray(a); b = np.asarray(b)
     if a.shape != b.shape:

@@ -216,6 +216,56 @@ def _allreduce_8x64M(zcref):
         assert np.array_equal(r.payload_of(b0, b0 + nbs), ref[tables_end(nbs):tot]), f"payload differs at block {b0}"
 
 
+def test_ring_rounds_64M(zcref):
+    """Three rounds of the ring reduce-scatter at the per-GPU shape of configuration 4 (a chunk
+    of 2^26 values): compress rank 0, then add ranks 1..3 uncompressed, one round each.  Every
+    round is checked on sampled slices against the reference round applied to the GPU's own
+    received stream there, and by its bound; the end result by the N * eb bound of the chain."""
+    rng = np.random.default_rng(9)
+    xs = _rank_buffers(4)
+    m = xs[0].numel()
+    eb = float(torch.tensor(2e-4, dtype=torch.float32))
+    ws = u8(zc.zc_workspace_bytes(m, 1))
+    st, buf, total = compress_async(xs[0], eb, ws)
+    assert st == ZC_OK
+    cur = Stream(buf, total, m)
+    y_prev = torch.empty(m, dtype=torch.float32, device=DEV)
+    y_next = torch.empty(m, dtype=torch.float32, device=DEV)
+    st, _ = decompress_async(cur.buf, cur.total, y_prev, ws)
+    assert st == ZC_OK
+    for i in range(1, 4):
+        out = u8(zc.zc_compress_bound(m))
+        st, _ = zc.zc_reduce_step(cur.buf, cur.total, xs[i], m, out, ws, sync=False)
+        assert st == ZC_OK
+        st, total = zc.zc_finish(ws)
+        assert st == ZC_OK
+        nxt = Stream(out, total, m)
+        check_header_and_sizes(nxt, eb, nsum=i + 1)
+        st, n_out = decompress_async(nxt.buf, nxt.total, y_next, ws)
+        assert st == ZC_OK and n_out == m
+        given = y_prev + xs[i]                                   # the binary32 sums the round quantises
+        assert max_abs_err(given, y_next) <= eb
+        del given
+        for b0 in sample_starts(m, rng, 3):
+            v0, v1 = 32 * b0, min(m, 32 * b0 + SLICE)
+            nbs = (v1 - v0 + 31) // 32
+            # the received stream of the slice, rebuilt from the GPU stream's own codes
+            st, rec, _ = zcref.compress(y_prev[v0:v1].cpu().numpy(), eb)
+            assert st == 0
+            st, ref, tot = zcref.reduce_step(rec, xs[i][v0:v1].cpu().numpy())
+            assert st == 0
+            assert np.array_equal(nxt.widths[b0:b0 + nbs].cpu().numpy(), ref[32:32 + nbs]), f"round {i}: widths differ at block {b0}"
+            o0 = 32 + pad16(nbs)
+            assert np.array_equal(nxt.outliers[b0:b0 + nbs].cpu().numpy(), ref[o0:o0 + 4 * nbs].view("<i4"))
+            assert np.array_equal(nxt.payload_of(b0, b0 + nbs), ref[tables_end(nbs):tot]), f"round {i}: payload differs at block {b0}"
+        cur = nxt
+        y_prev, y_next = y_next, y_prev
+    exact = torch.zeros(m, dtype=torch.float64, device=DEV)
+    for x in xs:
+        exact += x.double()
+    assert float((y_prev.double() - exact).abs().max()) <= 4 * eb
+
+
 def test_hard_mix_256M(zcref):
     """Configuration 5: steps, spikes and exactly constant blocks at rel 1e-5."""
     rng = np.random.default_rng(5)

@@ -318,6 +318,104 @@ def test_reduce_error_paths(zcref):
     assert u.gpu_reduce([], n)[0] == ZC_ERR_ARG
 
 
+# ---------------- one ring round: received stream + local values -> stream of the sums ----------------
+@pytest.mark.parametrize("n,rel", [(1, 1e-3), (31, 1e-3), (32, 1e-3), (33, 1e-3), (2048, 1e-2), (TILE, 1e-4), (TILE + 1, 1e-3),
+                                   (3 * TILE + 777, 1e-3), (16 * TILE, 1e-4), (9 * TILE - 5, 1e-5)])
+def test_reduce_step_stream_matches_reference(zcref, n, rel):
+    u = _u()
+    x = synth.power_law_field((max(1, (n + 4095) // 4096), 64, 64), seed=40).numpy().ravel()[:n]
+    y = synth.power_law_field((max(1, (n + 4095) // 4096), 64, 64), seed=41).numpy().ravel()[:n]
+    eb = synth.abs_bound(torch.from_numpy(np.concatenate([x, [1.0]]).astype(np.float32)), rel)
+    _, received, _ = zcref.compress(x, eb)
+    st_ref, s_ref, total_ref = zcref.reduce_step(received, y)
+    st, s, total = u.gpu_reduce_step(received, y)
+    assert st == st_ref == ZC_OK and total == total_ref
+    assert s.tobytes() == s_ref.tobytes(), u.first_diff(s, s_ref)
+
+
+def test_reduce_step_chain_and_special_cases(zcref):
+    """N rounds in a row on the GPU against N rounds of the reference; adding zeros keeps the
+    stream, adding to zeros compresses the local chunk."""
+    u = _u()
+    n = 5 * TILE + 321
+    xs = [synth.power_law_field((8, 64, 128), seed=50 + i).numpy().ravel()[:n] for i in range(5)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), 1e-3)
+    _, s_ref, _ = zcref.compress(xs[0], eb)
+    s = s_ref
+    for i in range(1, 5):
+        _, s_ref, _ = zcref.reduce_step(s_ref, xs[i])
+        st, s, _ = u.gpu_reduce_step(s, xs[i])
+        assert st == ZC_OK and s.tobytes() == s_ref.tobytes(), (i, u.first_diff(s, s_ref))
+    exact = np.sum([x.astype(np.float64) for x in xs], axis=0)
+    _, yv, _ = u.gpu_decompress(s, n)
+    assert np.abs(yv.astype(np.float64) - exact).max() <= 5 * eb
+    st, same, _ = u.gpu_reduce_step(s, np.zeros(n, np.float32))
+    want = s.copy(); want[20:24] = np.frombuffer(np.uint32(6).tobytes(), np.uint8)
+    assert st == ZC_OK and same.tobytes() == want.tobytes()
+    _, zeros, _ = zcref.compress(np.zeros(n, np.float32), eb)
+    st, fresh, _ = u.gpu_reduce_step(zeros, xs[1])
+    _, want, _ = zcref.compress(xs[1], eb)
+    want = want.copy(); want[20:24] = np.frombuffer(np.uint32(2).tobytes(), np.uint8)
+    assert st == ZC_OK and fresh.tobytes() == want.tobytes()
+
+
+def test_reduce_step_wide_and_out_of_domain(zcref):
+    """Received streams and sums with blocks wider than 15 bits, constant blocks, values that
+    need the checked quantiser, and sums that leave the guaranteed domain (BOUND)."""
+    u = _u()
+    rng = np.random.default_rng(11)
+    eb = np.float32(2.0 ** -20)
+    step = float(eb) * 63 / 32
+    n = 4 * TILE + 100
+    scale = np.repeat(2.0 ** rng.integers(0, 28, (n + 31) // 32), 32)[:n]
+    q = (rng.uniform(-1, 1, n) * scale).astype(np.int64)
+    q[:TILE] = 7                                                   # constant blocks
+    _, received, _ = zcref.encode_codes(q.astype(np.int32), eb)
+    local = (rng.uniform(-1, 1, n) * np.roll(scale, 4096) * step).astype(np.float32)
+    local[TILE // 2: TILE] = 0.0
+    st_ref, s_ref, total_ref = zcref.reduce_step(received, local)
+    st, s, total = u.gpu_reduce_step(received, local)
+    assert st == st_ref and st in (ZC_OK, ZC_ERR_BOUND) and total == total_ref
+    assert s.tobytes() == s_ref.tobytes(), u.first_diff(s, s_ref)
+    assert zcref.inspect(s_ref)[2].max() >= 24
+    # narrow received stream, wide sums
+    x = synth.power_law_field((4, 64, 64), seed=60).numpy().ravel()
+    eb2 = synth.abs_bound(torch.from_numpy(x), 1e-4)
+    _, rec2, _ = zcref.compress(x, eb2)
+    loc2 = (rng.standard_normal(x.size) * 3000).astype(np.float32)
+    st_ref, s_ref, _ = zcref.reduce_step(rec2, loc2)
+    st, s, _ = u.gpu_reduce_step(rec2, loc2)
+    assert st == st_ref and s.tobytes() == s_ref.tobytes(), u.first_diff(s, s_ref)
+    assert zcref.inspect(s_ref)[2].max() > 15
+
+
+def test_reduce_step_error_paths(zcref):
+    u = _u()
+    x = synth.power_law_field((3, 64, 64), seed=70).numpy().ravel()
+    n = x.size
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    _, s, _ = zcref.compress(x, eb)
+    assert u.gpu_reduce_step(s, x[:-1])[0] == ZC_ERR_MISMATCH == zcref.reduce_step(s, x[:-1])[0]
+    bad = s.copy(); bad[0] ^= 1
+    assert u.gpu_reduce_step(bad, x)[0] == ZC_ERR_FORMAT
+    y = x.copy(); y[5000] = np.inf
+    assert u.gpu_reduce_step(s, y)[0] == ZC_ERR_NONFINITE == zcref.reduce_step(s, y)[0]
+    y = x.copy(); y[5000] = np.float32(eb * 2.0 ** 32)
+    assert u.gpu_reduce_step(s, y)[0] == ZC_ERR_RANGE == zcref.reduce_step(s, y)[0]
+    y[77] = np.nan                                                  # precedence: NONFINITE before RANGE
+    assert u.gpu_reduce_step(s, y)[0] == ZC_ERR_NONFINITE == zcref.reduce_step(s, y)[0]
+    _, _, total = zcref.reduce_step(s, x)
+    st, _, need = u.gpu_reduce_step(s, x, out_cap=total - 4)
+    assert st == ZC_ERR_CAPACITY and need == total
+    st, _, _ = u.gpu_reduce_step(s, x, out_cap=16)
+    assert st == ZC_ERR_CAPACITY
+    # empty input
+    _, s0, _ = zcref.compress(np.zeros(0, np.float32), eb)
+    st, r0, total0 = u.gpu_reduce_step(s0, np.zeros(0, np.float32))
+    st_ref, r_ref, _ = zcref.reduce_step(s0, np.zeros(0, np.float32))
+    assert st == st_ref == ZC_OK and r0.tobytes() == r_ref.tobytes()
+
+
 def test_async_form_and_workspace_reuse(zcref):
     u = _u()
     x = synth.power_law_field((8, 64, 64), seed=5).numpy()
