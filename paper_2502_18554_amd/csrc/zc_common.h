@@ -210,6 +210,11 @@ __device__ inline uint4 load_once(const uint4* p) {
   const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(t.x, t.y, t.z, t.w);
 }
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ inline float4 load_once(const float4* p) {
+  const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  return make_float4(t.x, t.y, t.z, t.w);
+}
 
 // A zero in a vector register that the compiler cannot see through.  An address that has it
 // added is not provably the same in every lane, so the access becomes a vector memory load.

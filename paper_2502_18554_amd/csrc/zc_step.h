@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
     for (int i = 0; i < 8; ++i) {
       const u64 idx = v0 + u64(256 * i + 4 * lane);
       if (whole) {
-        x[i] = *reinterpret_cast<const float4*>(a.local + idx);
+        x[i] = load_once(reinterpret_cast<const float4*>(a.local + idx));
       } else {
         x[i].x = idx + 0 < a.n_local ? a.local[idx + 0] : 0.0f;
         x[i].y = idx + 1 < a.n_local ? a.local[idx + 1] : 0.0f;
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
     for (int i = 0; i < 8; ++i) {
       const u64 idx = v0 + u64(256 * i + 4 * lane);
       if (whole) {
-        x[i] = *reinterpret_cast<const float4*>(a.local + idx);
+        x[i] = load_once(reinterpret_cast<const float4*>(a.local + idx));
       } else {
         x[i].x = idx + 0 < h.n ? a.local[idx + 0] : 0.0f;
         x[i].y = idx + 1 < h.n ? a.local[idx + 1] : 0.0f;
@@ -174,7 +174,9 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
   u32 err = 0;
   const u64 cnt64 = active ? h.n - u64(b) * kBlockValues : 0;      // values of this block that exist
   const u32 cnt = cnt64 < 32 ? u32(cnt64) : 32u;
-  i32 outlier = 0, prev = 0, top = 0, bottom = 0;
+  // first the sums (in place of the deltas) and their largest magnitude: a NaN or an infinity
+  // has the largest bit pattern of all, so one unsigned maximum screens the whole block
+  u32 amax = 0;
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
     const float4 l4 = *reinterpret_cast<const float4*>(wl + lane * kStageRow + 4 * t);
@@ -184,8 +186,30 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
       const int j = 4 * t + u;
       cur += u32(d[j]);
       const float y = float(__dmul_rn(double(i32(cur)), qa.step)) + lv[u];
+      amax = max(amax, __float_as_uint(y) & 0x7fffffffu);
+      d[j] = i32(__float_as_uint(y));
+    }
+  }
+  // (values past the end of the last block are sums of a repeated code and zero: harmless here)
+  const bool checked = __any(active && needs_checks(__uint_as_float(amax), qa));
+  const bool ragged = __any(active && cnt < 32);      // only the wave that holds the stream's last block
+  i32 outlier = 0, prev = 0, top = 0, bottom = 0;
+  if (__builtin_expect(!checked && !ragged, 1)) {
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      const i32 q = quantize_fast(__uint_as_float(u32(d[j])), qa);
+      if (j == 0) outlier = q;
+      const i32 nd = j ? q - prev : 0;
+      top = max(top, nd);
+      bottom = min(bottom, nd);
+      d[j] = nd;
+      prev = q;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
       i32 q = prev;                                   // the last block repeats its last code
-      if (u32(j) < cnt) q = quantize_value(y, qa, err);
+      if (u32(j) < cnt) q = quantize_value(__uint_as_float(u32(d[j])), qa, err);
       if (j == 0) outlier = q;
       const i32 nd = j ? q - prev : 0;
       top = max(top, nd);
