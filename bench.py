@@ -192,6 +192,35 @@ def main():
                 res[name] = {"ms": round(ms, 4), "fp32_GBps": round(4 * n / ms / 1e6, 1),
                              "hbm_frac": round((4 * n + cb) / ms / 1e6 / HBM_PEAK_GBS, 4)}
             extras[f"rel_{rel:g}"] = res
+        # the tail of the compressed Allgather at the shape of the reduce above: the 8 rank streams
+        # decompressed by 8 calls and by one call
+        outs = [torch.empty(m, dtype=torch.float32, device=dev) for _ in range(K)]
+        ws_k = [u8(zc.zc_workspace_bytes(m, 1)) for _ in range(K)]
+
+        def eight_calls():
+            for i in range(K):
+                zc.zc_decompress(chunks[i], chunk_bytes[i], outs[i], ws_k[i], sync=False)
+
+        def one_call():
+            zc.zc_decompress_many(chunks, chunk_bytes, outs, ws_r, sync=False)
+
+        res = {"workload": f"{K} streams of {m} values (abs eb {eb_r:g}) -> {K} fp32 buffers"}
+        for name, fn in (("eight_calls", eight_calls), ("one_call", one_call)):
+            for _ in range(3):
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(5):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / 5
+            res[name] = {"ms": round(ms, 4), "fp32_GBps": round(4 * m * K / ms / 1e6, 1),
+                         "hbm_frac": round((sum(chunk_bytes) + 4 * m * K) / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        st, _ = zc.zc_finish(ws_r)
+        check(st, "decompress_many extra")
+        extras["decompress_many"] = res
+        del outs, ws_k
         # one round of the ring reduce-scatter at the shape of the reduce above: the received
         # stream of rank 0 plus the uncompressed buffer of rank 1 -> stream of the sums
         st, s_bytes = zc.zc_reduce_step(chunks[0], chunk_bytes[0], ranks[1], m, d_red, ws_r)

@@ -79,6 +79,18 @@ int zc_decompress(const void* d_in, size_t in_bytes,
                   float* d_out, size_t out_cap_elems, size_t* n_out,
                   void* d_ws, size_t ws_bytes, void* hip_stream);
 
+/* Decompression of k streams in one call: the tail of the compressed Allgather (Section 3.5.1:
+ * a rank decompresses all the chunks it has received at the end), one launch instead of k.
+ * d_chunks, chunk_bytes, d_outs, out_cap_elems: HOST arrays of k entries (device pointers 16-byte
+ * aligned); stream i is decoded into d_outs[i] exactly as zc_decompress would.  The streams need
+ * not agree in n or bound.  n_out (host array of k entries, may be NULL): receives every
+ * stream's n.  In the asynchronous form zc_finish reports the sum of the k values of n.
+ * Errors: ARG, FORMAT (any stream; nothing is written then), CAPACITY (that stream is not
+ * written, the others are), HIP. */
+int zc_decompress_many(const void* const* d_chunks, const size_t* chunk_bytes, int k,
+                       float* const* d_outs, const size_t* out_cap_elems, size_t* n_out,
+                       void* d_ws, size_t ws_bytes, void* hip_stream);
+
 /* Local step of the compressed Allreduce (Section 3.1.2, Sum of Section 3.2): k compressed
  * operands of the same n and abs_eb -> the compressed sum, computed on the integer codes, so
  * no new quantisation error appears and decompress(out) is within nsum * abs_eb of the exact
@@ -140,7 +152,7 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
 int zc_set_tile_hand_out(int mode);
 
 /* Measurement aid (not part of the method).  While enabled, zc_compress, zc_decompress,
- * zc_reduce_compressed and zc_reduce_step record a pair of HIP events on the call's stream around
+ * zc_decompress_many, zc_reduce_compressed and zc_reduce_step record a pair of HIP events on the call's stream around
  * their main kernel (the compress kernel over the full tiles, the decompress, reduce or step kernel;
  * not the small set-up kernels before it).  zc_profile_collect waits for the recorded pairs,
  * stores up to cap elapsed times in milliseconds in ms[] and the matching ZC_KERNEL_* ids in

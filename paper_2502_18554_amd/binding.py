@@ -17,7 +17,8 @@ ZC_OK, ZC_ERR_ARG, ZC_ERR_CAPACITY, ZC_ERR_FORMAT, ZC_ERR_NONFINITE, ZC_ERR_RANG
 ZC_MAX_K = 64
 
 EXPORTS = [
-    "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_step",
+    "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_decompress_many",
+    "zc_reduce_compressed", "zc_reduce_step",
     "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
     "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out",
 ]
@@ -48,6 +49,7 @@ def lib():
         L.zc_decompress.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_compressed.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_step.argtypes = [vp, sz, vp, sz, vp, sz, szp, vp, sz, vp]
+        L.zc_decompress_many.argtypes = [C.POINTER(vp), szp, C.c_int, C.POINTER(vp), szp, szp, vp, sz, vp]
         L.zc_finish.argtypes = [vp, szp, vp]
         L.zc_peek_header.argtypes = [vp, sz, szp, C.POINTER(C.c_float), C.POINTER(C.c_uint), szp, vp]
         L.zc_strerror.restype = C.c_char_p
@@ -112,6 +114,19 @@ def zc_reduce_compressed(d_chunks, chunk_bytes, d_out, d_ws, sync=True, stream=N
                                     C.byref(nbytes) if sync else None, _p(d_ws),
                                     d_ws.numel() * d_ws.element_size(), _stream(stream))
     return st, (nbytes.value if sync else None)
+
+
+def zc_decompress_many(d_chunks, chunk_bytes, d_outs, d_ws, sync=True, stream=None, out_cap_elems=None):
+    """d_chunks / d_outs: lists of k device tensors.  Returns (status, [n of every stream]) (None when not sync)."""
+    k = len(d_chunks)
+    ptrs = (C.c_void_p * max(k, 1))(*[t.data_ptr() for t in d_chunks])
+    sizes = (C.c_size_t * max(k, 1))(*[int(b) for b in chunk_bytes])
+    outs = (C.c_void_p * max(k, 1))(*[t.data_ptr() for t in d_outs])
+    caps = (C.c_size_t * max(k, 1))(*([t.numel() for t in d_outs] if out_cap_elems is None else [int(c) for c in out_cap_elems]))
+    ns = (C.c_size_t * max(k, 1))()
+    st = lib().zc_decompress_many(ptrs, sizes, k, outs, caps, ns if sync else None, _p(d_ws),
+                                  d_ws.numel() * d_ws.element_size(), _stream(stream))
+    return st, ([int(ns[i]) for i in range(k)] if sync else None)
 
 
 def zc_reduce_step(d_chunk, chunk_bytes, d_local, n_local, d_out, d_ws, sync=True, stream=None, out_cap=None):

@@ -241,6 +241,59 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
   return finish(d_ws, n_out, stream);
 }
 
+int zc_decompress_many(const void* const* d_chunks, const size_t* chunk_bytes, int k, float* const* d_outs,
+                       const size_t* out_cap_elems, size_t* n_out, void* d_ws, size_t ws_bytes, void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (k < 1 || k > ZC_MAX_K || !d_chunks || !chunk_bytes || !d_outs || !out_cap_elems || !d_ws) return ZC_ERR_ARG;
+  if (!aligned16(d_ws)) return ZC_ERR_ARG;
+  for (int i = 0; i < k; ++i)
+    if (!d_chunks[i] || !aligned16(d_chunks[i]) || !aligned16(d_outs[i]) || (out_cap_elems[i] && !d_outs[i])) return ZC_ERR_ARG;
+  for (int i = 0; i < k; ++i)
+    if (chunk_bytes[i] < kHeaderBytes) return ZC_ERR_FORMAT;
+  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, k);
+  if (l.tiles_cap < 1) return ZC_ERR_ARG;
+  ScanArgs sa;
+  DecompressManyArgs da;
+  u64 tiles = 1;
+  for (int i = 0; i < k; ++i) {
+    sa.streams[i].base = static_cast<const u8*>(d_chunks[i]);
+    sa.streams[i].bytes = chunk_bytes[i];
+    da.in[i] = sa.streams[i];
+    da.out[i] = d_outs[i];
+    da.out_cap_elems[i] = out_cap_elems[i];
+    u64 t = num_tiles(blocks_bound(chunk_bytes[i]));
+    const u64 t_out = num_tiles(num_blocks(out_cap_elems[i]));
+    if (t > t_out) t = t_out;
+    if (t > tiles) tiles = t;
+  }
+  if (tiles > l.tiles_cap) tiles = l.tiles_cap;
+  if (tiles > kMaxTiles) tiles = kMaxTiles;
+  sa.k = k;
+  sa.check_match = 0;
+  sa.index = l.index;
+  sa.ctl = l.ctl;
+  sa.desc = nullptr;
+  sa.ndesc = 0;
+  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), u32(k)), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(index_prep_kernel, dim3(1), dim3(256), 0, stream, sa);
+  da.index = l.index;
+  da.ctl = l.ctl;
+  KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_DECOMPRESS, stream);
+  hipLaunchKernelGGL(decompress_many_kernel, dim3(u32(tiles), u32(k)), dim3(kTileThreads), 0, stream, da);
+  g_timer.end(slot, stream);
+  if (!launch_ok()) return ZC_ERR_HIP;
+  if (!n_out) return ZC_OK;
+  size_t total = 0;
+  const int st = finish(d_ws, &total, stream);
+  if (st == ZC_ERR_HIP || st == ZC_ERR_ARG || st == ZC_ERR_FORMAT) return st;
+  for (int i = 0; i < k; ++i) {          // every header passed validation: its n is the stream's
+    u64 n = 0;
+    if (hipMemcpy(&n, static_cast<const u8*>(d_chunks[i]) + 8, 8, hipMemcpyDeviceToHost) != hipSuccess) return ZC_ERR_HIP;
+    n_out[i] = size_t(n);
+  }
+  return st;
+}
+
 int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes, int k, void* d_out, size_t out_cap,
                          size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);

@@ -115,8 +115,11 @@ __device__ inline void deltas_from_block_words(u32 wmax, u32 (&lo)[16], u32 (&hi
   }
 }
 
-__global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressArgs a) {
-  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
+// One tile (blockIdx.x) of stream `s` of the index, into `out`.  `counted`: the stream's n is
+// added to the control block's result instead of stored there (several streams per call).
+__device__ inline void decompress_tile(const StreamRef& in, float* out_values, u64 out_cap_elems, const StreamIndex& index,
+                                       int s, Control* ctl, bool counted, u32* lds) {
+  const DecompressArgs a{in, out_values, out_cap_elems, index, ctl};
 
   // Everything that can be asked for before the header is known goes out at once: the control
   // block, the header, the segment's position and the width bytes.  The loads are fenced in
@@ -131,12 +134,15 @@ __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressA
   const uint2 gate = load_gate(a.ctl, zero);
   const HeaderWords hw = load_header_words(a.in.base, zero);
   SegmentOffsetParts seg_parts{0, 0, 0};
-  if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, 0, seg, zero);
+  if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, s, seg, zero);
   u32 w = u64(kHeaderBytes) + b < a.in.bytes ? u32(*at_bytes(a.in.base, kHeaderBytes + b)) : 0u;
 
   const ParsedHeader h = parse_header(hw, a.in.bytes);
   if (gate_failed(gate) || !h.ok) return;
-  if (blockIdx.x == 0 && threadIdx.x == 0) a.ctl->result = h.n;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (counted) atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->result), static_cast<unsigned long long>(h.n));
+    else a.ctl->result = h.n;
+  }
   if (h.n > a.out_cap_elems) {
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
     return;
@@ -197,6 +203,27 @@ __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressA
     }
     wave_lds_sync();
   }
+}
+
+__global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
+  decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, false, lds);
+}
+
+// k streams in one launch (the tail of the compressed Allgather, Section 3.5.1: every rank
+// decompresses all the chunks it has received): blockIdx.y = stream, blockIdx.x = tile.
+struct DecompressManyArgs {
+  StreamRef in[ZC_MAX_K];
+  float* out[ZC_MAX_K];
+  u64 out_cap_elems[ZC_MAX_K];
+  StreamIndex index;
+  Control* ctl;
+};
+
+__global__ __launch_bounds__(kTileThreads, 5) void decompress_many_kernel(DecompressManyArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
+  const int s = blockIdx.y;
+  decompress_tile(a.in[s], a.out[s], a.out_cap_elems[s], a.index, s, a.ctl, true, lds);
 }
 
 }  // namespace zc

@@ -55,6 +55,18 @@ def gpu_reduce(streams, n, out_cap=None, ws=None):
     return st, (d_out[: min(total, cap)].cpu().numpy() if st == zc.binding.ZC_OK else None), total
 
 
+def gpu_decompress_many(streams, n_caps, ws=None):
+    """-> (status, [float32 arrays], [n])"""
+    d_chunks = [to_dev(s) for s in streams]
+    d_outs = [torch.full((max(c, 4) + 4,), float("nan"), dtype=torch.float32, device=DEV) for c in n_caps]
+    ws = workspace(max(max(n_caps), 1), len(streams)) if ws is None else ws
+    st, ns = zc.zc_decompress_many(d_chunks, [c.numel() for c in d_chunks], d_outs, ws, out_cap_elems=n_caps)
+    torch.cuda.synchronize()
+    for o, c in zip(d_outs, n_caps):
+        assert bool(torch.isnan(o[max(c, 4):]).all()), "wrote past out_cap_elems"
+    return st, [o.cpu().numpy() for o in d_outs], ns
+
+
 def gpu_reduce_step(stream, local, out_cap=None, ws=None, n_local=None):
     """-> (status, stream bytes, total_bytes)"""
     d_in = to_dev(stream)

@@ -163,6 +163,16 @@ def test_allgather_8x64M(zcref):
         assert max_abs_err(xs[r], out[r * m:(r + 1) * m]) <= eb
         if r in (0, 7):
             check_slices_against_reference(zcref, xs[r], eb, s, out[r * m:(r + 1) * m], rng, count=3)
+    # the same eight streams in one call: bit for bit what the eight calls wrote
+    del xs
+    out2 = torch.full((8 * m,), float("nan"), dtype=torch.float32, device=DEV)
+    ws8 = u8(zc.zc_workspace_bytes(m, 8))
+    st, _ = zc.zc_decompress_many([s.buf for s, _ in streams], [s.total for s, _ in streams],
+                                  [out2[r * m:(r + 1) * m] for r in range(8)], ws8, sync=False)
+    assert st == ZC_OK
+    st, total_n = zc.zc_finish(ws8)
+    assert st == ZC_OK and total_n == 8 * m
+    assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
 
 
 @pytest.mark.parametrize("hand_out", ["dispatch_order", "tickets"])

@@ -318,6 +318,57 @@ def test_reduce_error_paths(zcref):
     assert u.gpu_reduce([], n)[0] == ZC_ERR_ARG
 
 
+# ---------------- k streams decompressed in one call ----------------
+def test_decompress_many_matches_reference(zcref):
+    """Streams of different lengths and bounds (one of them empty, one with wide blocks) in one
+    call: every output equals the reference decompression of its stream, bit for bit."""
+    u = _u()
+    rng = np.random.default_rng(21)
+    sizes = [4 * TILE + 5, 1, 0, 7 * TILE, 33, 2 * TILE - 1, 3 * TILE + 2048]
+    rels = [1e-3, 1e-2, 1e-3, 1e-4, 1e-3, 1e-5, 1e-2]
+    streams, wants = [], []
+    for i, (n, rel) in enumerate(zip(sizes, rels)):
+        x = synth.power_law_field((8, 64, 128), seed=80 + i).numpy().ravel()[:n]
+        st, s, _ = zcref.compress(x, 2 * rel)               # the fields span about [-1, 1]
+        assert st == ZC_OK
+        streams.append(s); wants.append(zcref.decompress(s)[1])
+    q = (rng.uniform(-1, 1, 2 * TILE) * 2.0 ** rng.integers(0, 29, 2 * TILE)).astype(np.int32)
+    _, wide, _ = zcref.encode_codes(q, 1e-3)
+    streams.append(wide); wants.append(zcref.decompress(wide)[1]); sizes.append(q.size)
+    st, outs, ns = u.gpu_decompress_many(streams, sizes)
+    assert st == ZC_OK and ns == sizes
+    for i, (o, w) in enumerate(zip(outs, wants)):
+        assert np.array_equal(o[: sizes[i]].view(np.uint32), w.view(np.uint32)), (i, u.first_diff(o[: sizes[i]], w))
+    # one call with a single stream is zc_decompress
+    st, outs, ns = u.gpu_decompress_many(streams[:1], sizes[:1])
+    assert st == ZC_OK and np.array_equal(outs[0][: sizes[0]].view(np.uint32), wants[0].view(np.uint32))
+
+
+def test_decompress_many_error_paths(zcref):
+    u = _u()
+    xs = [synth.power_law_field((2, 64, 64), seed=90 + i).numpy().ravel() for i in range(3)]
+    streams = [zcref.compress(x, 1e-3)[1] for x in xs]
+    n = xs[0].size
+    # too little room for stream 1: CAPACITY, the others are decoded
+    st, outs, ns = u.gpu_decompress_many(streams, [n, n - 1, n])
+    assert st == ZC_ERR_CAPACITY and ns == [n, n, n]
+    for i in (0, 2):
+        assert np.array_equal(outs[i][:n].view(np.uint32), zcref.decompress(streams[i])[1].view(np.uint32))
+    assert np.isnan(outs[1]).all()
+    bad = streams[2].copy(); bad[4] ^= 1
+    st, outs, _ = u.gpu_decompress_many([streams[0], bad], [n, n])
+    assert st == ZC_ERR_FORMAT and np.isnan(outs[0]).all()
+    ws = u.workspace(n, 3)
+    d_chunks = [u.to_dev(s) for s in streams]
+    d_outs = [torch.empty(n, dtype=torch.float32, device=u.DEV) for _ in streams]
+    st, _ = zc.zc_decompress_many(d_chunks, [c.numel() for c in d_chunks], d_outs, ws, sync=False)
+    assert st == ZC_OK
+    st, total = zc.zc_finish(ws)
+    assert st == ZC_OK and total == 3 * n
+    for o, s in zip(d_outs, streams):
+        assert np.array_equal(o.cpu().numpy().view(np.uint32), zcref.decompress(s)[1].view(np.uint32))
+
+
 # ---------------- one ring round: received stream + local values -> stream of the sums ----------------
 @pytest.mark.parametrize("n,rel", [(1, 1e-3), (31, 1e-3), (32, 1e-3), (33, 1e-3), (2048, 1e-2), (TILE, 1e-4), (TILE + 1, 1e-3),
                                    (3 * TILE + 777, 1e-3), (16 * TILE, 1e-4), (9 * TILE - 5, 1e-5)])
