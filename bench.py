@@ -192,6 +192,24 @@ def main():
                 res[name] = {"ms": round(ms, 4), "fp32_GBps": round(4 * n / ms / 1e6, 1),
                              "hbm_frac": round((4 * n + cb) / ms / 1e6 / HBM_PEAK_GBS, 4)}
             extras[f"rel_{rel:g}"] = res
+        # the step as a HIP graph: the asynchronous calls only launch kernels, so the three calls
+        # are captured once and replayed
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0g = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_g = (time.perf_counter() - t0g) * 1e3 / args.steps
+        for ws, what in ((ws_c, "compress"), (ws_d, "decompress"), (ws_r, "reduce")):
+            st, _ = zc.zc_finish(ws)
+            check(st, what + " (graph replay)")
+        extras["hip_graph"] = {"ms_per_step": round(ms_g, 4), "value_GBps": round(total_fp32 / ms_g / 1e6, 1)}
+        del graph
         # the tail of the compressed Allgather at the shape of the reduce above: the 8 rank streams
         # decompressed by 8 calls and by one call
         outs = [torch.empty(m, dtype=torch.float32, device=dev) for _ in range(K)]

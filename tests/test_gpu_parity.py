@@ -489,6 +489,67 @@ def test_async_form_and_workspace_reuse(zcref):
     assert np.array_equal(d_y.cpu().numpy(), zcref.decompress(s_ref)[1])
 
 
+def test_hip_graph_replay(zcref):
+    """The asynchronous forms only launch kernels (nothing is cleared with a memset, nothing
+    synchronises), so a sequence of calls can be captured into a HIP graph.  Every replay, with
+    eager calls and synchronisations in between, must reproduce the eager results bit for bit."""
+    u = _u()
+    k, n = 3, 6 * TILE + 123
+    xs = [u.to_dev(synth.power_law_field((8, 64, 128), seed=110 + i).numpy().ravel()[:n]) for i in range(k)]
+    eb = 2e-3
+    cap = zc.zc_compress_bound(n)
+    fixed, sizes = [], []
+    ws0 = u.workspace(n, k)
+    for x in xs:                                             # operand streams, made once
+        buf = torch.empty(cap, dtype=torch.uint8, device=u.DEV)
+        st, total = zc.zc_compress(x, n, eb, buf, ws0)
+        assert st == ZC_OK
+        fixed.append(buf); sizes.append(total)
+    out_c = torch.empty(cap, dtype=torch.uint8, device=u.DEV)
+    out_y = torch.empty(n, dtype=torch.float32, device=u.DEV)
+    out_r = torch.empty(cap, dtype=torch.uint8, device=u.DEV)
+    out_s = torch.empty(cap, dtype=torch.uint8, device=u.DEV)
+    out_m = [torch.empty(n, dtype=torch.float32, device=u.DEV) for _ in range(k)]
+    wss = [u.workspace(n, k) for _ in range(5)]
+
+    def calls():
+        zc.zc_compress(xs[0], n, eb, out_c, wss[0], sync=False)
+        zc.zc_decompress(fixed[1], sizes[1], out_y, wss[1], sync=False)
+        zc.zc_reduce_compressed(fixed, sizes, out_r, wss[2], sync=False)
+        zc.zc_reduce_step(fixed[2], sizes[2], xs[0], n, out_s, wss[3], sync=False)
+        zc.zc_decompress_many(fixed, sizes, out_m, wss[4], sync=False)
+
+    def results():
+        torch.cuda.synchronize()
+        res = []
+        for w in wss:
+            st, r = zc.zc_finish(w)
+            assert st == ZC_OK
+            res.append(r)
+        outs = [out_c[: res[0]], out_y, out_r[: res[2]], out_s[: res[3]]] + out_m
+        return res, [o.clone() for o in outs]
+
+    calls()
+    want_res, want = results()
+    assert want[0].cpu().numpy().tobytes() == zcref.compress(xs[0].cpu().numpy(), eb)[1].tobytes()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        calls()
+    for rep in range(3):
+        for o in [out_c, out_r, out_s]:
+            o.fill_(0x11)
+        for o in [out_y] + out_m:
+            o.fill_(float("nan"))
+        st, _ = zc.zc_compress(xs[1], n, eb, torch.empty(cap, dtype=torch.uint8, device=u.DEV), ws0)   # eager work in between
+        assert st == ZC_OK
+        torch.cuda.synchronize()
+        g.replay()
+        got_res, got = results()
+        assert got_res == want_res, rep
+        for i, (a, b) in enumerate(zip(got, want)):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (rep, i)
+
+
 def test_repeated_runs_are_identical():
     """The look-back scan is the only cross-workgroup protocol: many tiles, many runs, one answer."""
     u = _u()
