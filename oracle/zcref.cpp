@@ -369,4 +369,24 @@ int zcref_reduce_step(const void* in, size_t in_bytes, const float* local, size_
   return OK;
 }
 
+// Quality of a reconstruction `test` against its original `ref` (the measures of Section 3.3's
+// quality table and of Section 4.6): out[0] = max |ref - test|, out[1] = sum of squared
+// differences, out[2] = min(ref), out[3] = max(ref), all in binary64 and in index order.
+// With range = max - min: RMSE = sqrt(out[1] / n), NRMSE = RMSE / range, PSNR = 20 log10(range / RMSE).
+// n = 0 gives {0, 0, +inf, -inf}.  Status: ARG.
+int zcref_quality(const float* ref, const float* test, size_t n, double* out) {
+  if (!out || (n && (!ref || !test))) return ERR_ARG;
+  double worst = 0.0, sse = 0.0, lo = INFINITY, hi = -INFINITY;
+  for (size_t i = 0; i < n; ++i) {
+    const double d = double(ref[i]) - double(test[i]);
+    const double a = std::fabs(d);
+    if (a > worst || std::isnan(a)) worst = a;
+    sse += d * d;
+    if (double(ref[i]) < lo) lo = ref[i];
+    if (double(ref[i]) > hi) hi = ref[i];
+  }
+  out[0] = worst; out[1] = sse; out[2] = lo; out[3] = hi;
+  return OK;
+}
+
 }  // extern "C"

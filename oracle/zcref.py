@@ -30,6 +30,7 @@ def lib():
         L.zcref_decompress.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                                        C.POINTER(C.c_size_t)]
         L.zcref_inspect.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.zcref_quality.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.zcref_reduce_step.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                                         C.POINTER(C.c_size_t)]
         L.zcref_reduce.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_size_t), C.c_int, C.c_void_p,
@@ -131,3 +132,23 @@ def reduce_step(stream, local, out_cap=None):
     nbytes = C.c_size_t(0)
     st = lib().zcref_reduce_step(_ptr(stream), stream.size, _ptr(local), local.size, _ptr(out), out_cap, C.byref(nbytes))
     return st, (out[: nbytes.value].copy() if st in (OK, ERR_BOUND) else out[:0]), nbytes.value
+
+
+def quality(ref, test):
+    """Returns (status, dict(max_err, sse, min, max, rmse, nrmse, psnr)) of `test` against `ref`."""
+    ref = np.ascontiguousarray(ref, dtype=np.float32)
+    test = np.ascontiguousarray(test, dtype=np.float32)
+    out = np.zeros(4, dtype=np.float64)
+    st = lib().zcref_quality(_ptr(ref), _ptr(test), ref.size, _ptr(out))
+    return st, metrics(out, ref.size)
+
+
+def metrics(out, n):
+    """The derived measures from the four sums."""
+    worst, sse, lo, hi = (float(v) for v in out)
+    rng = hi - lo
+    rmse = (sse / n) ** 0.5 if n else 0.0
+    with np.errstate(divide="ignore", invalid="ignore"):
+        nrmse = float(np.float64(rmse) / np.float64(rng)) if n else 0.0
+        psnr = float(20.0 * np.log10(np.float64(rng) / np.float64(rmse))) if n else 0.0
+    return dict(max_err=worst, sse=sse, min=lo, max=hi, rmse=rmse, nrmse=nrmse, psnr=psnr)

@@ -452,3 +452,33 @@ def test_reduce_step_errors(zcref):
     y = x.copy(); y[7] = np.float32(eb * 2.0 ** 27)            # outside the guaranteed domain
     st, out, _ = zcref.reduce_step(s, y)
     assert st in (zcref.OK, zcref.ERR_BOUND)
+
+
+# ---------------- P10: quality measures ----------------
+def test_quality_closed_forms_and_numpy(zcref):
+    """A constant offset c gives max error c, sum of squares n c^2, and PSNR / NRMSE that follow
+    from the definitions; on random data the four sums agree with numpy's."""
+    rng = np.random.default_rng(1)
+    n = 10007
+    ref = rng.uniform(-3, 5, n).astype(np.float32)
+    ref[0], ref[1] = -3.0, 5.0
+    c = 0.125                                                    # exact in binary32 at this magnitude
+    st, m = zcref.quality(ref, (ref.astype(np.float64) + c).astype(np.float32))
+    assert st == zcref.OK and m["min"] == -3.0 and m["max"] == 5.0
+    assert abs(m["max_err"] - c) < 1e-6 and abs(m["sse"] / (n * c * c) - 1) < 1e-5
+    assert abs(m["nrmse"] - c / 8.0) < 1e-6 and abs(m["psnr"] - 20 * np.log10(8.0 / c)) < 1e-4
+    test = (ref + rng.normal(0, 1e-3, n)).astype(np.float32)
+    st, m = zcref.quality(ref, test)
+    d = ref.astype(np.float64) - test.astype(np.float64)
+    assert m["max_err"] == np.abs(d).max() and m["min"] == ref.min() and m["max"] == ref.max()
+    assert abs(m["sse"] / np.sum(d * d) - 1) < 1e-12
+    st, m = zcref.quality(ref, ref)
+    assert m["max_err"] == 0.0 and m["sse"] == 0.0 and m["psnr"] == np.inf
+    # a compressed field: NRMSE of a uniform quantiser is step / sqrt(12) / range
+    x = synth.power_law_field((16, 64, 64), seed=7).numpy().ravel()
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    _, s, _ = zcref.compress(x, eb)
+    _, y, _ = zcref.decompress(s)
+    st, m = zcref.quality(x, y)
+    assert m["max_err"] <= eb
+    assert abs(m["nrmse"] / (lm.step(eb) / np.sqrt(12.0) / float(x.max() - x.min())) - 1) < 0.05
