@@ -192,6 +192,19 @@ def main():
                 res[name] = {"ms": round(ms, 4), "fp32_GBps": round(4 * n / ms / 1e6, 1),
                              "hbm_frac": round((4 * n + cb) / ms / 1e6 / HBM_PEAK_GBS, 4)}
             extras[f"rel_{rel:g}"] = res
+        # quality sums of the reconstruction (synchronous call: timed on the host)
+        st, q4 = zc.zc_quality(x, d_y, n, ws_c)
+        check(st, "quality extra")
+        torch.cuda.synchronize()
+        tq = time.perf_counter()
+        for _ in range(5):
+            zc.zc_quality(x, d_y, n, ws_c)
+        ms = (time.perf_counter() - tq) * 1e3 / 5
+        rng_x = q4[3] - q4[2]
+        rmse = (q4[1] / n) ** 0.5
+        import math
+        extras["quality"] = {"max_err": q4[0], "nrmse": rmse / rng_x, "psnr_dB": round(20 * math.log10(rng_x / rmse), 2),
+                             "ms": round(ms, 4), "hbm_frac": round(8 * n / ms / 1e6 / HBM_PEAK_GBS, 4)}
         # the step as a HIP graph: the asynchronous calls only launch kernels, so the three calls
         # are captured once and replayed
         graph = torch.cuda.CUDAGraph()

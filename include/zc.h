@@ -115,6 +115,16 @@ int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local
                    void* d_out, size_t out_cap, size_t* out_bytes,
                    void* d_ws, size_t ws_bytes, void* hip_stream);
 
+/* Quality of a reconstruction d_test against its original d_ref (n binary32 values each,
+ * 16-byte aligned): the sums behind the paper's quality figures (NRMSE in Section 3.3, PSNR
+ * and NRMSE in Section 4.6).  out4 (host, 4 doubles): max |ref - test|, sum of squared
+ * differences, min(ref), max(ref), accumulated in binary64 in a fixed order.  With range =
+ * max - min and RMSE = sqrt(sum / n): NRMSE = RMSE / range, PSNR = 20 log10(range / RMSE).
+ * n = 0 gives {0, 0, +inf, -inf}.  Synchronous.  The workspace must hold at least
+ * zc_workspace_bytes(n, 1) bytes.  Errors: ARG, HIP. */
+int zc_quality(const float* d_ref, const float* d_test, size_t n, double* out4,
+               void* d_ws, size_t ws_bytes, void* hip_stream);
+
 /* Completes an asynchronous call: synchronises hip_stream, returns the status of the last
  * call that used d_ws and stores its size result (total_bytes, or n for zc_decompress) in
  * *result (host, may be NULL). */

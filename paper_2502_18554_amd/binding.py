@@ -18,7 +18,7 @@ ZC_MAX_K = 64
 
 EXPORTS = [
     "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_decompress_many",
-    "zc_reduce_compressed", "zc_reduce_step",
+    "zc_reduce_compressed", "zc_reduce_step", "zc_quality",
     "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
     "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out",
 ]
@@ -49,6 +49,7 @@ def lib():
         L.zc_decompress.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_compressed.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_step.argtypes = [vp, sz, vp, sz, vp, sz, szp, vp, sz, vp]
+        L.zc_quality.argtypes = [vp, vp, sz, C.POINTER(C.c_double), vp, sz, vp]
         L.zc_decompress_many.argtypes = [C.POINTER(vp), szp, C.c_int, C.POINTER(vp), szp, szp, vp, sz, vp]
         L.zc_finish.argtypes = [vp, szp, vp]
         L.zc_peek_header.argtypes = [vp, sz, szp, C.POINTER(C.c_float), C.POINTER(C.c_uint), szp, vp]
@@ -137,6 +138,14 @@ def zc_reduce_step(d_chunk, chunk_bytes, d_local, n_local, d_out, d_ws, sync=Tru
                               C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
                               _stream(stream))
     return st, (nbytes.value if sync else None)
+
+
+def zc_quality(d_ref, d_test, n, d_ws, stream=None):
+    """Returns (status, [max |ref - test|, sum of squared differences, min(ref), max(ref)])."""
+    out = (C.c_double * 4)()
+    st = lib().zc_quality(_p(d_ref), _p(d_test), int(n), out, _p(d_ws), d_ws.numel() * d_ws.element_size(),
+                          _stream(stream))
+    return st, [float(v) for v in out]
 
 
 def zc_finish(d_ws, stream=None):

@@ -12,6 +12,7 @@
 #include "zc_decompress.h"
 #include "zc_reduce.h"
 #include "zc_scan.h"
+#include "zc_quality.h"
 #include "zc_step.h"
 
 using namespace zc;
@@ -381,6 +382,37 @@ int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
+}
+
+int zc_quality(const float* d_ref, const float* d_test, size_t n, double* out4, void* d_ws, size_t ws_bytes,
+               void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (!out4 || !d_ws || (n && (!d_ref || !d_test)) || n > ZC_MAX_N) return ZC_ERR_ARG;
+  if (!aligned16(d_ref) || !aligned16(d_test) || !aligned16(d_ws)) return ZC_ERR_ARG;
+  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
+  if (l.tiles_cap < 1 || num_tiles(num_blocks(n)) > l.tiles_cap) return ZC_ERR_ARG;
+  // partial results live where the other calls keep their tile descriptors: 128 bytes per tile
+  u64 groups = l.tiles_cap * kDescBytes / sizeof(QualityPartial) - 1;
+  const u64 wanted = (n / 4 + kQualityThreads - 1) / kQualityThreads;
+  if (groups > wanted) groups = wanted;
+  if (groups > 2048) groups = 2048;
+  if (groups < 1) groups = 1;
+  QualityArgs qa;
+  qa.ref = d_ref;
+  qa.test = d_test;
+  qa.n = n;
+  qa.partials = reinterpret_cast<QualityPartial*>(l.desc);
+  hipLaunchKernelGGL(quality_partial_kernel, dim3(u32(groups)), dim3(kQualityThreads), 0, stream, qa);
+  hipLaunchKernelGGL(quality_final_kernel, dim3(1), dim3(kQualityThreads), 0, stream, qa, u32(groups));
+  if (!launch_ok()) return ZC_ERR_HIP;
+  QualityPartial host;
+  if (hipMemcpyAsync(&host, qa.partials + groups, sizeof(host), hipMemcpyDeviceToHost, stream) != hipSuccess) return ZC_ERR_HIP;
+  if (hipStreamSynchronize(stream) != hipSuccess) return ZC_ERR_HIP;
+  out4[0] = host.worst;
+  out4[1] = host.sse;
+  out4[2] = host.lo;
+  out4[3] = host.hi;
+  return ZC_OK;
 }
 
 

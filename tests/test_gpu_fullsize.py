@@ -108,6 +108,23 @@ def check_slices_against_reference(zcref, x, eb, s, y, rng, count=6):
             assert np.array_equal(y[v0:v1].cpu().numpy().view(np.uint32), y_ref.view(np.uint32)), f"floats differ at block {b0}"
 
 
+def check_quality(zcref, x, y, eb, rng):
+    """zc_quality on the whole buffers: its maximum is the torch maximum, a sampled slice agrees with
+    the reference, and the NRMSE is that of a uniform quantiser of this step."""
+    n = x.numel()
+    st, q = zc.zc_quality(x, y, n, u8(zc.zc_workspace_bytes(n, 1)))
+    assert st == ZC_OK
+    assert q[0] == max_abs_err(x, y) and q[2] == float(x.min()) and q[3] == float(x.max())
+    step = float(np.float32(eb)) * 63.0 / 32.0
+    nrmse = (q[1] / n) ** 0.5 / (q[3] - q[2])
+    assert abs(nrmse / (step / 12 ** 0.5 / (q[3] - q[2])) - 1) < 0.05
+    v0 = 32 * int(rng.integers(0, max(1, (n - SLICE) // 32)))
+    st, part = zc.zc_quality(x[v0:v0 + SLICE], y[v0:v0 + SLICE], min(SLICE, n - v0), u8(zc.zc_workspace_bytes(SLICE, 1)))
+    _, want = zcref.quality(x[v0:v0 + SLICE].cpu().numpy(), y[v0:v0 + SLICE].cpu().numpy())
+    assert part[0] == want["max_err"] and part[2] == want["min"] and part[3] == want["max"]
+    assert abs(part[1] / want["sse"] - 1) < 1e-10
+
+
 def max_abs_err(x, y, chunk=1 << 27):
     worst = 0.0
     for i in range(0, x.numel(), chunk):
@@ -132,6 +149,7 @@ def test_field_512cube(zcref, rel):
     assert st == ZC_OK and n_out == n
     assert max_abs_err(x, y) <= eb
     check_slices_against_reference(zcref, x, eb, s, y, rng)
+    check_quality(zcref, x, y, eb, rng)
     # idempotence on the grid: the reconstruction compresses to the same bytes
     st, buf2, total2 = compress_async(y, eb, ws)
     assert st == ZC_OK and total2 == total and torch.equal(buf2[:total], buf[:total])

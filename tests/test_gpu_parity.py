@@ -489,6 +489,30 @@ def test_async_form_and_workspace_reuse(zcref):
     assert np.array_equal(d_y.cpu().numpy(), zcref.decompress(s_ref)[1])
 
 
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 1023, 1024, 4 * TILE + 3, (1 << 22) + 1])
+def test_quality_sums_match_reference(zcref, n):
+    """Max error, min and max are exact; the sum of squares is accumulated in binary64 in another
+    order than the reference's, so it agrees to rounding (n * 2^-53 relative at worst)."""
+    u = _u()
+    rng = np.random.default_rng(n)
+    ref = rng.uniform(-2, 3, n).astype(np.float32)
+    test = (ref + rng.normal(0, 1e-3, n)).astype(np.float32)
+    st_ref, want = zcref.quality(ref, test)
+    d_ref = u.to_dev(ref) if n else torch.zeros(4, device=u.DEV)
+    d_test = u.to_dev(test) if n else torch.zeros(4, device=u.DEV)
+    st, got = zc.zc_quality(d_ref, d_test, n, u.workspace(max(n, 1)))
+    assert st == st_ref == ZC_OK
+    assert got[0] == want["max_err"] and got[2] == want["min"] and got[3] == want["max"]
+    assert got[1] == want["sse"] or abs(got[1] / want["sse"] - 1) <= max(n, 1) * 2.0 ** -53
+    st, again = zc.zc_quality(d_ref, d_test, n, u.workspace(max(n, 1)))
+    assert again == got                                              # fixed order: same bits every run
+    if n > 4:
+        test[n // 2] = np.nan
+        st, got = zc.zc_quality(d_ref, u.to_dev(test), n, u.workspace(n))
+        assert st == ZC_OK and np.isnan(got[0]) and np.isnan(zcref.quality(ref, test)[1]["max_err"])
+    assert zc.zc_quality(d_ref, None, 8, u.workspace(8))[0] == ZC_ERR_ARG
+
+
 def test_hip_graph_replay(zcref):
     """The asynchronous forms only launch kernels (nothing is cleared with a memset, nothing
     synchronises), so a sequence of calls can be captured into a HIP graph.  Every replay, with
