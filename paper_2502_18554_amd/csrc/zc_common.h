@@ -201,16 +201,27 @@ __device__ inline u32 lane_value(u32 v, int lane) { return u32(__builtin_amdgcn_
 // it are scalar branches.
 __device__ inline u32 uniform(u32 v) { return u32(__builtin_amdgcn_readfirstlane(int(v))); }
 __device__ inline u64 uniform64(u64 v) { return u64(uniform(u32(v))) | (u64(uniform(u32(v >> 32))) << 32); }
-// Load of data that a kernel touches once: the non-temporal hint keeps it from pushing the
-// lines that are used again (the stream index, tables shared by neighbouring waves, tile
-// descriptors) out of the L2.  It pays for the reduce, which reads several streams side by
-// side (measured: 8 % less time); it costs time for the single stream of the decompression.
+// Loads and stores of data that a kernel touches once, with the non-temporal hint.  Such data
+// then neither pushes the lines that are used again (the stream index, tables shared by
+// neighbouring waves, tile descriptors) out of the L2, nor stays behind as dirty lines that
+// the next kernel has to write back while it runs.  Where it pays is a matter of measurement
+// (times of the three kernels inside one loop): the input values of the compression (-21 us
+// for it, +15 us for the kernel after it), the floats the decompression writes (-27 us for
+// it, nothing lost elsewhere), the payload loads of the reduce (-23 us; they read several
+// streams side by side) and the payload it writes (-14 us).  It costs time on the payload the
+// compression writes (the decompression that follows finds it in the memory-side cache
+// otherwise) and on the payload and outlier loads of the decompression.
 typedef u32 u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 __device__ inline uint4 load_once(const uint4* p) {
   const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(t.x, t.y, t.z, t.w);
 }
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ inline void store_once(float4* p, const float4& v) {
+  const f32x4_t t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<f32x4_t*>(p));
+}
+__device__ inline void store_once(u32* p, u32 v) { __builtin_nontemporal_store(v, p); }
 __device__ inline float4 load_once(const float4* p) {
   const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
   return make_float4(t.x, t.y, t.z, t.w);

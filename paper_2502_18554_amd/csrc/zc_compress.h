@@ -99,7 +99,7 @@ __device__ inline void load_raw(const CompressArgs& a, u64 wblock0, int lane, fl
   const u64 v0 = wblock0 * kBlockValues;
   if (FULL) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) x[i] = *reinterpret_cast<const float4*>(a.in + v0 + u64(256 * i + 4 * lane));
+    for (int i = 0; i < 8; ++i) x[i] = load_once(reinterpret_cast<const float4*>(a.in + v0 + u64(256 * i + 4 * lane)));
   } else {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {

@@ -193,7 +193,7 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
       const u64 idx = v0 + u64(1024 * hh + 256 * i + 4 * lane);
       const float4 v = *reinterpret_cast<const float4*>(wl + (8 * i + (lane >> 3)) * kStageRow + 4 * (lane & 7));
       if (full) {
-        *reinterpret_cast<float4*>(a.out + idx) = v;
+        store_once(reinterpret_cast<float4*>(a.out + idx), v);
       } else {
         if (idx + 0 < h.n) a.out[idx + 0] = v.x;
         if (idx + 1 < h.n) a.out[idx + 1] = v.y;

@@ -192,7 +192,7 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ParsedHeader&
   for (u32 r = 0; r < u32(NW); ++r) {
     const u32 i = u32(lane) + 64u * r;
     if (64u * r >= limit) break;             // uniform
-    if (i < limit) dst[i] = wl[i];
+    if (i < limit) store_once(dst + i, wl[i]);
   }
   wave_lds_sync();
   finish_stream(sink, pl, tile, ntiles, base);
