@@ -63,8 +63,8 @@ __global__ __launch_bounds__(kQualityThreads) void quality_partial_kernel(Qualit
   const u64 quads = a.n / 4;
   const u64 stride = u64(gridDim.x) * kQualityThreads;
   for (u64 i = u64(blockIdx.x) * kQualityThreads + threadIdx.x; i < quads; i += stride) {
-    const float4 r = reinterpret_cast<const float4*>(a.ref)[i];
-    const float4 t = reinterpret_cast<const float4*>(a.test)[i];
+    const float4 r = load_once(reinterpret_cast<const float4*>(a.ref) + i);
+    const float4 t = load_once(reinterpret_cast<const float4*>(a.test) + i);
     quality_take(p, r.x, t.x);
     quality_take(p, r.y, t.y);
     quality_take(p, r.z, t.z);
