@@ -161,8 +161,9 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ParsedHeader&
   pl.off_in_wave = incl - words;
   if (lane == 0) sh_wave_total[wave] = pl.wave_total;
   if (active && a.out_cap >= tend) {
-    a.out[kHeaderBytes + b] = u8(w);
-    reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(h.nb))[b] = i32(outlier);
+    // (the whole output stream is written with the non-temporal hint, see store_once)
+    __builtin_nontemporal_store(u8(w), a.out + kHeaderBytes + b);
+    __builtin_nontemporal_store(i32(outlier), reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(h.nb)) + b);
   }
   if (w) {
     wl[pl.off_in_wave] = word(std::integral_constant<int, 0>{});
