@@ -62,6 +62,25 @@ def test_argument_checks_without_gpu(libzc):
     ptrs = (vp * 1)(0x1000)
     sizes = (sz * 1)(100)
     assert libzc.zc_reduce_compressed(ptrs, sizes, 65, 0x2000, 100, None, 0x3000, 4096, None) == 1
+    libzc.zc_reduce_step.argtypes = [vp, sz, vp, sz, vp, sz, C.POINTER(sz), vp, sz, vp]
+    assert libzc.zc_reduce_step(None, 100, 0x1000, 8, 0x2000, 100, None, 0x3000, 4096, None) == 1
+    assert libzc.zc_reduce_step(0x1000, 100, None, 8, 0x2000, 100, None, 0x3000, 4096, None) == 1      # no local values
+    assert libzc.zc_reduce_step(0x1000, 100, 0x1008, 8, 0x2000, 100, None, 0x3000, 4096, None) == 1    # alignment
+    assert libzc.zc_reduce_step(0x1000, 16, 0x4000, 8, 0x2000, 100, None, 0x3000, 4096, None) == 3     # shorter than a header
+    assert libzc.zc_reduce_step(0x1000, 100, 0x4000, 1 << 20, 0x2000, 100, None, 0x3000, 64, None) == 1  # workspace
+    libzc.zc_decompress_many.argtypes = [C.POINTER(vp), C.POINTER(sz), C.c_int, C.POINTER(vp), C.POINTER(sz), C.POINTER(sz),
+                                         vp, sz, vp]
+    outs = (vp * 1)(0x4000)
+    caps = (sz * 1)(8)
+    assert libzc.zc_decompress_many(ptrs, sizes, 0, outs, caps, None, 0x3000, 4096, None) == 1
+    assert libzc.zc_decompress_many(ptrs, sizes, 1, None, caps, None, 0x3000, 4096, None) == 1
+    assert libzc.zc_decompress_many(ptrs, (sz * 1)(16), 1, outs, caps, None, 0x3000, 4096, None) == 3
+    assert libzc.zc_decompress_many(ptrs, sizes, 1, (vp * 1)(0x4004), caps, None, 0x3000, 4096, None) == 1
+    libzc.zc_quality.argtypes = [vp, vp, sz, C.POINTER(C.c_double), vp, sz, vp]
+    out4 = (C.c_double * 4)()
+    assert libzc.zc_quality(0x1000, 0x2000, 8, None, 0x3000, 4096, None) == 1
+    assert libzc.zc_quality(0x1000, None, 8, out4, 0x3000, 4096, None) == 1
+    assert libzc.zc_quality(0x1000, 0x2000, 1 << 24, out4, 0x3000, 64, None) == 1                       # workspace
 
 
 @pytest.fixture(scope="module")
