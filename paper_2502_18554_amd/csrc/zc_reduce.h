@@ -14,7 +14,9 @@
 // Two kernels share this scheme.  reduce_kernel serves streams whose blocks are all at most
 // 15 bits wide (every stream of an input inside the guaranteed domain of a sensible bound):
 // a wave's payload of one operand is then at most 1024 words, is brought into LDS with
-// 16-byte loads, and the loads of the next operand fly while the current one is added.
+// 16-byte loads, and the loads of the next operand fly while the current one is added; the
+// summed planes go to LDS in one pass and leave as coalesced stores.  Operand payloads are
+// read, and the output stream is written, with the non-temporal hint (see load_once).
 // reduce_wide_kernel takes any widths with per-lane loads.  The stream index records whether
 // any operand has a wider block; each kernel returns at once when the streams are not its.
 #pragma once
