@@ -32,6 +32,12 @@
 //                       u32 sign word (bit j set iff delta j < 0), then w plane words,
 //                       least significant plane first, bit j of plane p = bit p of |delta j|
 //   nb = ceil(n / 32); a block of width 0 has no payload.
+//
+// Indexed variant (Section 3.5.2 keeps the compressed size of every chunk in an index at the
+// front of the buffer, so that chunks can be handled one by one): version = 2, or 3 when some
+// block is wider than 15 bits, and between the outlier table and the payload sits one u32 per
+// segment of 64 blocks, the payload word offset of the segment's first block, zero padded to
+// 16 bytes.  zcref_set_indexed() chooses which variant is written and which one is accepted.
 
 #include <cmath>
 #include <cstddef>
@@ -51,10 +57,15 @@ constexpr size_t kBlock = 32;
 constexpr size_t kHeader = 32;
 constexpr uint64_t kMaxN = uint64_t(1) << 31;
 constexpr int64_t kMaxCode = (int64_t(1) << 30) - 1;
+constexpr size_t kSegBlocks = 64;
+
+bool g_indexed = false;       // which stream variant is written and accepted
 
 size_t pad16(size_t v) { return (v + 15) / 16 * 16; }
 size_t num_blocks(size_t n) { return (n + kBlock - 1) / kBlock; }
-size_t tables_end(size_t nb) { return kHeader + pad16(nb) + pad16(4 * nb); }
+size_t num_segments(size_t nb) { return (nb + kSegBlocks - 1) / kSegBlocks; }
+size_t index_bytes(size_t nb) { return g_indexed ? pad16(4 * num_segments(nb)) : 0; }
+size_t tables_end(size_t nb) { return kHeader + pad16(nb) + pad16(4 * nb) + index_bytes(nb); }
 
 // Error bound accepted by the codec: finite, and at least 2^-96 so that no reconstructed
 // value can be a binary32 subnormal.
@@ -108,7 +119,10 @@ int encode_codes(const int32_t* q, size_t n, uint32_t eb_bits, uint32_t nsum,
   std::vector<uint8_t> width(nb);
   std::vector<int32_t> outlier(nb);
   std::vector<uint32_t> words;            // payload, block after block
+  std::vector<uint32_t> seg_start;        // payload word offset of every 64th block
+  bool wide = false;
   for (size_t b = 0; b < nb; ++b) {
+    if (b % kSegBlocks == 0) seg_start.push_back(uint32_t(words.size()));
     int64_t Q[kBlock];
     for (size_t j = 0; j < kBlock; ++j) {
       size_t i = b * kBlock + j;
@@ -123,6 +137,7 @@ int encode_codes(const int32_t* q, size_t n, uint32_t eb_bits, uint32_t nsum,
       if (mag > maxmag) maxmag = mag;
     }
     unsigned w = bit_length(maxmag);
+    if (w > 15) wide = true;
     width[b] = uint8_t(w);
     outlier[b] = int32_t(Q[0]);
     if (w == 0) continue;
@@ -143,7 +158,7 @@ int encode_codes(const int32_t* q, size_t n, uint32_t eb_bits, uint32_t nsum,
   if (total > out_cap) return ERR_CAPACITY;
   std::memset(out, 0, tables_end(nb));
   put_u32(out + 0, kMagic);
-  put_u16(out + 4, 1);
+  put_u16(out + 4, g_indexed ? (wide ? 3 : 2) : 1);
   out[6] = 5;
   out[7] = 6;
   put_u64(out + 8, n);
@@ -152,7 +167,9 @@ int encode_codes(const int32_t* q, size_t n, uint32_t eb_bits, uint32_t nsum,
   put_u64(out + 24, total);
   uint8_t* wt = out + kHeader;
   uint8_t* ot = wt + pad16(nb);
-  uint8_t* pl = ot + pad16(4 * nb);
+  uint8_t* ix = ot + pad16(4 * nb);
+  uint8_t* pl = ix + index_bytes(nb);
+  if (g_indexed) for (size_t i = 0; i < seg_start.size(); ++i) put_u32(ix + 4 * i, seg_start[i]);
   for (size_t b = 0; b < nb; ++b) wt[b] = width[b];
   for (size_t b = 0; b < nb; ++b) put_u32(ot + 4 * b, uint32_t(outlier[b]));
   for (size_t i = 0; i < words.size(); ++i) put_u32(pl + 4 * i, words[i]);
@@ -172,7 +189,9 @@ struct Parsed {
 // Header and table validation shared by decompress, reduce and inspect.
 int parse_stream(const uint8_t* in, size_t in_bytes, Parsed* ps) {
   if (in_bytes < kHeader) return ERR_FORMAT;
-  if (get_u32(in) != kMagic || get_u16(in + 4) != 1 || in[6] != 5 || in[7] != 6) return ERR_FORMAT;
+  const unsigned version = get_u16(in + 4);
+  if (get_u32(in) != kMagic || in[6] != 5 || in[7] != 6) return ERR_FORMAT;
+  if (g_indexed ? (version != 2 && version != 3) : version != 1) return ERR_FORMAT;
   ps->n = get_u64(in + 8);
   ps->eb_bits = get_u32(in + 16);
   ps->nsum = get_u32(in + 20);
@@ -184,14 +203,20 @@ int parse_stream(const uint8_t* in, size_t in_bytes, Parsed* ps) {
   if (ps->total > in_bytes || ps->total < tables_end(ps->nb)) return ERR_FORMAT;
   ps->widths = in + kHeader;
   ps->outliers = ps->widths + pad16(ps->nb);
-  ps->payload = ps->outliers + pad16(4 * ps->nb);
+  const uint8_t* index = ps->outliers + pad16(4 * ps->nb);
+  ps->payload = index + index_bytes(ps->nb);
   ps->off.resize(ps->nb);
   uint64_t acc = 0;
+  bool wide = false;
   for (size_t b = 0; b < ps->nb; ++b) {
     if (ps->widths[b] > 31) return ERR_FORMAT;
+    if (ps->widths[b] > 15) wide = true;
+    // the index must say what the width table implies
+    if (g_indexed && b % kSegBlocks == 0 && get_u32(index + 4 * (b / kSegBlocks)) != acc / 4) return ERR_FORMAT;
     ps->off[b] = acc;                     // exclusive prefix sum of the block sizes
     acc += payload_size(ps->widths[b]);
   }
+  if (g_indexed && (version == 3) != wide) return ERR_FORMAT;
   if (tables_end(ps->nb) + acc != ps->total) return ERR_FORMAT;
   return OK;
 }
@@ -221,7 +246,10 @@ void decode_codes(const Parsed& ps, int32_t* q) {
 
 extern "C" {
 
-// Worst-case stream size: every block at width 31 costs 1 + 4 + 128 bytes.
+// Which stream variant the functions below write and accept: 0 plain, 1 indexed.
+void zcref_set_indexed(int on) { g_indexed = on != 0; }
+
+// Worst-case stream size of the chosen variant: every block at width 31 costs 1 + 4 + 128 bytes.
 size_t zcref_compress_bound(size_t n) {
   size_t nb = num_blocks(n);
   return tables_end(nb) + 128 * nb;

@@ -43,6 +43,11 @@ def _ptr(a):
     return a.ctypes.data_as(C.c_void_p) if a is not None else None
 
 
+def set_indexed(on):
+    """Chooses the stream variant that is written and accepted: False plain, True indexed."""
+    lib().zcref_set_indexed(1 if on else 0)
+
+
 def compress_bound(n):
     return int(lib().zcref_compress_bound(n))
 

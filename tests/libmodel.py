@@ -37,7 +37,7 @@ def blocks_of(q):
     return qp
 
 
-def stream_from_codes(q, abs_eb, nsum=1):
+def stream_from_codes(q, abs_eb, nsum=1, indexed=False):
     q = np.asarray(q, np.int64)
     n = q.size
     qp = blocks_of(q)
@@ -56,9 +56,16 @@ def stream_from_codes(q, abs_eb, nsum=1):
         payload += np.packbits((d[b] < 0).astype(np.uint8), bitorder="little").tobytes()
         for p in range(w):
             payload += np.packbits(((mag[b] >> p) & 1).astype(np.uint8), bitorder="little").tobytes()
-    total = 32 + pad16(nb) + pad16(4 * nb) + len(payload)
+    # indexed variant: the payload word offset of every 64th block, from the same cumsum
+    ix = b""
+    version = 1
+    if indexed:
+        nseg = (nb + 63) // 64
+        ix = (offsets[::64] // 4).astype("<u4").tobytes().ljust(pad16(4 * nseg), b"\0") if nb else b""
+        version = 3 if nb and widths.max() > 15 else 2
+    total = 32 + pad16(nb) + pad16(4 * nb) + len(ix) + len(payload)
     eb_bits = int(np.float32(abs_eb).view(np.uint32))
-    head = struct.pack("<IHBBQIIQ", 0x314C435A, 1, 5, 6, n, eb_bits, nsum, total)
+    head = struct.pack("<IHBBQIIQ", 0x314C435A, version, 5, 6, n, eb_bits, nsum, total)
     wt = widths.astype(np.uint8).tobytes().ljust(pad16(nb), b"\0")
     ot = qp[:, 0].astype("<i4").tobytes().ljust(pad16(4 * nb), b"\0") if nb else b""
-    return np.frombuffer(head + wt + ot + bytes(payload), np.uint8), widths, offsets
+    return np.frombuffer(head + wt + ot + ix + bytes(payload), np.uint8), widths, offsets

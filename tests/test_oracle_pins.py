@@ -482,3 +482,135 @@ def test_quality_closed_forms_and_numpy(zcref):
     st, m = zcref.quality(x, y)
     assert m["max_err"] <= eb
     assert abs(m["nrmse"] / (lm.step(eb) / np.sqrt(12.0) / float(x.max() - x.min())) - 1) < 0.05
+
+
+# ---------------- P11: the indexed stream variant (Section 3.5.2) ----------------
+@pytest.fixture
+def indexed(zcref):
+    zcref.set_indexed(True)
+    yield zcref
+    zcref.set_indexed(False)
+
+
+def _to_indexed(plain):
+    """The indexed stream with the same content as a plain one, built with numpy.cumsum."""
+    plain = np.asarray(plain, np.uint8)
+    n = int(plain[8:16].view("<u8")[0])
+    nb = (n + 31) // 32
+    nseg = (nb + 63) // 64
+    w = plain[32:32 + nb].astype(np.int64)
+    words = np.where(w > 0, 1 + w, 0)
+    start = np.concatenate([[0], np.cumsum(words)])[:-1][::64] if nb else np.zeros(0, np.int64)
+    ix = np.zeros(lm.pad16(4 * nseg), np.uint8)
+    ix[:4 * nseg] = start.astype("<u4").view(np.uint8)
+    cut = 32 + lm.pad16(nb) + lm.pad16(4 * nb)
+    total = int(plain[24:32].view("<u8")[0])
+    out = np.concatenate([plain[:cut], ix, plain[cut:total]])
+    out[4:6] = np.array([3 if nb and w.max() > 15 else 2], "<u2").view(np.uint8)
+    out[24:32] = np.array([total + ix.size], "<u8").view(np.uint8)
+    return out
+
+
+def test_indexed_worked_example(indexed):
+    zcref = indexed
+    eb, x, plain, recon = _read_golden()
+    st, got, total = zcref.compress(x, eb)
+    assert st == zcref.OK and total == 76 + 16                 # one segment: one entry, padded to 16 bytes
+    assert got[4] == 2 and got[5] == 0
+    assert got[40 + 16 + 16 - 8:][:16].tobytes() == bytes(16)  # the entry of segment 0 is 0
+    assert got.tobytes() == _to_indexed(plain).tobytes()
+    st, y, n = zcref.decompress(got)
+    assert st == zcref.OK and np.array_equal(y, recon)
+    assert zcref.compress_bound(32) == 32 + 16 + 16 + 16 + 128
+
+
+@pytest.mark.parametrize("name,x,rel", list(_fields()), ids=[f[0] for f in _fields()])
+def test_indexed_stream_against_library_routines(zcref, name, x, rel):
+    eb = synth.abs_bound(torch.from_numpy(x), rel)
+    st, plain, _ = zcref.compress(x, eb)
+    zcref.set_indexed(True)
+    try:
+        st, s, total = zcref.compress(x, eb)
+        assert st == zcref.OK
+        want, widths, offsets = lm.stream_from_codes(lm.codes(x, eb), eb, indexed=True)
+        assert s.tobytes() == want.tobytes() == _to_indexed(plain).tobytes()
+        nb = widths.size
+        first = 32 + lm.pad16(nb) + lm.pad16(4 * nb)
+        ix = s[first:first + 4 * ((nb + 63) // 64)].view("<u4")
+        assert np.array_equal(ix, offsets[::64] // 4) and np.all(np.diff(ix.astype(np.int64)) >= 0)
+        st, q, w, off = zcref.inspect(s)
+        assert np.array_equal(off.astype(np.int64), offsets)
+        st, y, n = zcref.decompress(s)
+        assert st == zcref.OK and np.array_equal(y, lm.recon(lm.codes(x, eb), eb))
+    finally:
+        zcref.set_indexed(False)
+
+
+@pytest.mark.parametrize("n", [0, 1, 32, 33, 2047, 2048, 2049, 4096, 4097, 2048 * 5 + 7])
+def test_indexed_edge_sizes(zcref, n):
+    x = synth.sinusoids(max(n, 1), seed=n).numpy()[:n]
+    st, plain, _ = zcref.compress(x, 1e-3)
+    zcref.set_indexed(True)
+    try:
+        st, s, total = zcref.compress(x, 1e-3)
+        assert st == zcref.OK and s.tobytes() == _to_indexed(plain).tobytes()
+        nb = (n + 31) // 32
+        assert total == plain.size + lm.pad16(4 * ((nb + 63) // 64))
+        st, y, m = zcref.decompress(s)
+        assert st == zcref.OK and m == n
+    finally:
+        zcref.set_indexed(False)
+    st, y0, _ = zcref.decompress(plain)
+    assert np.array_equal(y, y0)
+
+
+def test_indexed_version_tells_wide_blocks(indexed):
+    zcref = indexed
+    q = np.zeros(64 * 32 * 3, np.int32)
+    st, s, _ = zcref.encode_codes(q, 1e-3)
+    assert s[4] == 2
+    q[5000] = 1 << 15                                           # |delta| = 2^15: 16 bits
+    st, s, _ = zcref.encode_codes(q, 1e-3)
+    assert st == zcref.OK and s[4] == 3
+    q[5000] = (1 << 15) - 1                                     # 15 bits: still narrow
+    st, s, _ = zcref.encode_codes(q, 1e-3)
+    assert s[4] == 2
+    t = s.copy(); t[4] = 3                                      # flag without a wide block
+    assert zcref.decompress(t)[0] == zcref.ERR_FORMAT
+
+
+def test_indexed_format_errors(zcref):
+    x = synth.sinusoids(64 * 32 * 3 + 100, seed=9).numpy()
+    st, plain, _ = zcref.compress(x, 1e-3)
+    zcref.set_indexed(True)
+    try:
+        st, s, _ = zcref.compress(x, 1e-3)
+        assert zcref.decompress(plain)[0] == zcref.ERR_FORMAT     # the other variant is refused
+        nb = (x.size + 31) // 32
+        first = 32 + lm.pad16(nb) + lm.pad16(4 * nb)
+        for seg in range(4):
+            t = s.copy(); t[first + 4 * seg] ^= 1                # an entry that contradicts the widths
+            assert zcref.decompress(t)[0] == zcref.ERR_FORMAT
+        assert zcref.decompress(s[:-1])[0] == zcref.ERR_FORMAT
+        st, y, n = zcref.decompress(s)
+        assert st == zcref.OK
+    finally:
+        zcref.set_indexed(False)
+    assert zcref.decompress(s)[0] == zcref.ERR_FORMAT             # and the other way round
+    st, y0, _ = zcref.decompress(plain)
+    assert np.array_equal(y, y0)
+
+
+def test_indexed_reduce_and_step_carry_the_same_content(zcref):
+    xs, eb, plain = _rank_streams(zcref, 3, (8, 32, 33), 1e-3)
+    st, red_plain, _ = zcref.reduce(plain)
+    st, step_plain, _ = zcref.reduce_step(plain[0], xs[1].ravel())
+    zcref.set_indexed(True)
+    try:
+        streams = [_to_indexed(s) for s in plain]
+        st, red, _ = zcref.reduce(streams)
+        assert st == zcref.OK and red.tobytes() == _to_indexed(red_plain).tobytes()
+        st, stp, _ = zcref.reduce_step(streams[0], xs[1].ravel())
+        assert st == zcref.OK and stp.tobytes() == _to_indexed(step_plain).tobytes()
+    finally:
+        zcref.set_indexed(False)
