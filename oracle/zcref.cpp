@@ -34,10 +34,12 @@
 //   nb = ceil(n / 32); a block of width 0 has no payload.
 //
 // Indexed variant (Section 3.5.2 keeps the compressed size of every chunk in an index at the
-// front of the buffer, so that chunks can be handled one by one): version = 2, or 3 when some
-// block is wider than 15 bits, and between the outlier table and the payload sits one u32 per
-// segment of 64 blocks, the payload word offset of the segment's first block, zero padded to
-// 16 bytes.  zcref_set_indexed() chooses which variant is written and which one is accepted.
+// front of the buffer, so that chunks can be handled one by one; here a chunk is a segment of
+// 64 blocks): version = 2 when no block is wider than 15 bits, else 3, and between the header
+// and the width table sits an index of nseg + 1 u32, nseg = ceil(nb / 64): entry i is the
+// payload word offset of the first block of segment i, entry nseg the number of payload
+// words; zero padded to 16 bytes.  A reader accepts version 3 without a wide block, but not
+// version 2 with one.  zcref_set_indexed() chooses which variant is written and accepted.
 
 #include <cmath>
 #include <cstddef>
@@ -64,7 +66,7 @@ bool g_indexed = false;       // which stream variant is written and accepted
 size_t pad16(size_t v) { return (v + 15) / 16 * 16; }
 size_t num_blocks(size_t n) { return (n + kBlock - 1) / kBlock; }
 size_t num_segments(size_t nb) { return (nb + kSegBlocks - 1) / kSegBlocks; }
-size_t index_bytes(size_t nb) { return g_indexed ? pad16(4 * num_segments(nb)) : 0; }
+size_t index_bytes(size_t nb) { return g_indexed ? pad16(4 * (num_segments(nb) + 1)) : 0; }
 size_t tables_end(size_t nb) { return kHeader + pad16(nb) + pad16(4 * nb) + index_bytes(nb); }
 
 // Error bound accepted by the codec: finite, and at least 2^-96 so that no reconstructed
@@ -165,11 +167,14 @@ int encode_codes(const int32_t* q, size_t n, uint32_t eb_bits, uint32_t nsum,
   put_u32(out + 16, eb_bits);
   put_u32(out + 20, nsum);
   put_u64(out + 24, total);
-  uint8_t* wt = out + kHeader;
+  uint8_t* ix = out + kHeader;
+  uint8_t* wt = ix + index_bytes(nb);
   uint8_t* ot = wt + pad16(nb);
-  uint8_t* ix = ot + pad16(4 * nb);
-  uint8_t* pl = ix + index_bytes(nb);
-  if (g_indexed) for (size_t i = 0; i < seg_start.size(); ++i) put_u32(ix + 4 * i, seg_start[i]);
+  uint8_t* pl = ot + pad16(4 * nb);
+  if (g_indexed) {
+    seg_start.push_back(uint32_t(words.size()));      // the closing entry: all payload words
+    for (size_t i = 0; i < seg_start.size(); ++i) put_u32(ix + 4 * i, seg_start[i]);
+  }
   for (size_t b = 0; b < nb; ++b) wt[b] = width[b];
   for (size_t b = 0; b < nb; ++b) put_u32(ot + 4 * b, uint32_t(outlier[b]));
   for (size_t i = 0; i < words.size(); ++i) put_u32(pl + 4 * i, words[i]);
@@ -201,10 +206,10 @@ int parse_stream(const uint8_t* in, size_t in_bytes, Parsed* ps) {
   if (ps->nsum < 1) return ERR_FORMAT;
   ps->nb = num_blocks(size_t(ps->n));
   if (ps->total > in_bytes || ps->total < tables_end(ps->nb)) return ERR_FORMAT;
-  ps->widths = in + kHeader;
+  const uint8_t* index = in + kHeader;
+  ps->widths = index + index_bytes(ps->nb);
   ps->outliers = ps->widths + pad16(ps->nb);
-  const uint8_t* index = ps->outliers + pad16(4 * ps->nb);
-  ps->payload = index + index_bytes(ps->nb);
+  ps->payload = ps->outliers + pad16(4 * ps->nb);
   ps->off.resize(ps->nb);
   uint64_t acc = 0;
   bool wide = false;
@@ -216,7 +221,8 @@ int parse_stream(const uint8_t* in, size_t in_bytes, Parsed* ps) {
     ps->off[b] = acc;                     // exclusive prefix sum of the block sizes
     acc += payload_size(ps->widths[b]);
   }
-  if (g_indexed && (version == 3) != wide) return ERR_FORMAT;
+  if (g_indexed && get_u32(index + 4 * num_segments(ps->nb)) != acc / 4) return ERR_FORMAT;
+  if (g_indexed && version == 2 && wide) return ERR_FORMAT;
   if (tables_end(ps->nb) + acc != ps->total) return ERR_FORMAT;
   return OK;
 }

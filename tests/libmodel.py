@@ -61,11 +61,12 @@ def stream_from_codes(q, abs_eb, nsum=1, indexed=False):
     version = 1
     if indexed:
         nseg = (nb + 63) // 64
-        ix = (offsets[::64] // 4).astype("<u4").tobytes().ljust(pad16(4 * nseg), b"\0") if nb else b""
+        entries = np.concatenate([offsets[::64], [len(payload)]]) // 4          # nseg starts and the payload size
+        ix = entries.astype("<u4").tobytes().ljust(pad16(4 * (nseg + 1)), b"\0")
         version = 3 if nb and widths.max() > 15 else 2
     total = 32 + pad16(nb) + pad16(4 * nb) + len(ix) + len(payload)
     eb_bits = int(np.float32(abs_eb).view(np.uint32))
     head = struct.pack("<IHBBQIIQ", 0x314C435A, version, 5, 6, n, eb_bits, nsum, total)
     wt = widths.astype(np.uint8).tobytes().ljust(pad16(nb), b"\0")
     ot = qp[:, 0].astype("<i4").tobytes().ljust(pad16(4 * nb), b"\0") if nb else b""
-    return np.frombuffer(head + wt + ot + ix + bytes(payload), np.uint8), widths, offsets
+    return np.frombuffer(head + ix + wt + ot + bytes(payload), np.uint8), widths, offsets

@@ -500,24 +500,31 @@ def _to_indexed(plain):
     nseg = (nb + 63) // 64
     w = plain[32:32 + nb].astype(np.int64)
     words = np.where(w > 0, 1 + w, 0)
-    start = np.concatenate([[0], np.cumsum(words)])[:-1][::64] if nb else np.zeros(0, np.int64)
-    ix = np.zeros(lm.pad16(4 * nseg), np.uint8)
-    ix[:4 * nseg] = start.astype("<u4").view(np.uint8)
-    cut = 32 + lm.pad16(nb) + lm.pad16(4 * nb)
+    csum = np.concatenate([[0], np.cumsum(words)])
+    ix = np.zeros(lm.pad16(4 * (nseg + 1)), np.uint8)
+    ix[:4 * (nseg + 1)] = np.concatenate([csum[:-1][::64], csum[-1:]]).astype("<u4").view(np.uint8)
     total = int(plain[24:32].view("<u8")[0])
-    out = np.concatenate([plain[:cut], ix, plain[cut:total]])
+    out = np.concatenate([plain[:32], ix, plain[32:total]])
     out[4:6] = np.array([3 if nb and w.max() > 15 else 2], "<u2").view(np.uint8)
     out[24:32] = np.array([total + ix.size], "<u8").view(np.uint8)
     return out
+
+
+def _index_of(s):
+    n = int(s[8:16].view("<u8")[0])
+    nseg = ((n + 31) // 32 + 63) // 64
+    return s[32:32 + 4 * (nseg + 1)].view("<u4")
 
 
 def test_indexed_worked_example(indexed):
     zcref = indexed
     eb, x, plain, recon = _read_golden()
     st, got, total = zcref.compress(x, eb)
-    assert st == zcref.OK and total == 76 + 16                 # one segment: one entry, padded to 16 bytes
+    assert st == zcref.OK and total == 76 + 16                 # one segment: two entries, padded to 16 bytes
     assert got[4] == 2 and got[5] == 0
-    assert got[40 + 16 + 16 - 8:][:16].tobytes() == bytes(16)  # the entry of segment 0 is 0
+    assert list(_index_of(got)) == [0, 3]                       # one block of width 2: sign word + 2 planes
+    assert got[40:48].tobytes() == bytes(8)                     # padding
+    assert got[48] == 2                                         # the width table follows the index
     assert got.tobytes() == _to_indexed(plain).tobytes()
     st, y, n = zcref.decompress(got)
     assert st == zcref.OK and np.array_equal(y, recon)
@@ -534,10 +541,10 @@ def test_indexed_stream_against_library_routines(zcref, name, x, rel):
         assert st == zcref.OK
         want, widths, offsets = lm.stream_from_codes(lm.codes(x, eb), eb, indexed=True)
         assert s.tobytes() == want.tobytes() == _to_indexed(plain).tobytes()
+        ix = _index_of(s).astype(np.int64)
+        assert np.array_equal(ix[:-1], offsets[::64] // 4) and np.all(np.diff(ix) >= 0)
         nb = widths.size
-        first = 32 + lm.pad16(nb) + lm.pad16(4 * nb)
-        ix = s[first:first + 4 * ((nb + 63) // 64)].view("<u4")
-        assert np.array_equal(ix, offsets[::64] // 4) and np.all(np.diff(ix.astype(np.int64)) >= 0)
+        assert 32 + lm.pad16(4 * ix.size) + lm.pad16(nb) + lm.pad16(4 * nb) + 4 * ix[-1] == total
         st, q, w, off = zcref.inspect(s)
         assert np.array_equal(off.astype(np.int64), offsets)
         st, y, n = zcref.decompress(s)
@@ -555,7 +562,7 @@ def test_indexed_edge_sizes(zcref, n):
         st, s, total = zcref.compress(x, 1e-3)
         assert st == zcref.OK and s.tobytes() == _to_indexed(plain).tobytes()
         nb = (n + 31) // 32
-        assert total == plain.size + lm.pad16(4 * ((nb + 63) // 64))
+        assert total == plain.size + lm.pad16(4 * ((nb + 63) // 64 + 1))
         st, y, m = zcref.decompress(s)
         assert st == zcref.OK and m == n
     finally:
@@ -575,7 +582,11 @@ def test_indexed_version_tells_wide_blocks(indexed):
     q[5000] = (1 << 15) - 1                                     # 15 bits: still narrow
     st, s, _ = zcref.encode_codes(q, 1e-3)
     assert s[4] == 2
-    t = s.copy(); t[4] = 3                                      # flag without a wide block
+    t = s.copy(); t[4] = 3                                      # "may hold wide blocks" with none: accepted
+    assert zcref.decompress(t)[0] == zcref.OK
+    q[5000] = 1 << 15
+    st, s, _ = zcref.encode_codes(q, 1e-3)
+    t = s.copy(); t[4] = 2                                      # "no wide block" with one: refused
     assert zcref.decompress(t)[0] == zcref.ERR_FORMAT
 
 
@@ -586,10 +597,9 @@ def test_indexed_format_errors(zcref):
     try:
         st, s, _ = zcref.compress(x, 1e-3)
         assert zcref.decompress(plain)[0] == zcref.ERR_FORMAT     # the other variant is refused
-        nb = (x.size + 31) // 32
-        first = 32 + lm.pad16(nb) + lm.pad16(4 * nb)
-        for seg in range(4):
-            t = s.copy(); t[first + 4 * seg] ^= 1                # an entry that contradicts the widths
+        assert _index_of(s).size == 5
+        for seg in range(5):
+            t = s.copy(); t[32 + 4 * seg] ^= 1                   # an entry that contradicts the widths
             assert zcref.decompress(t)[0] == zcref.ERR_FORMAT
         assert zcref.decompress(s[:-1])[0] == zcref.ERR_FORMAT
         st, y, n = zcref.decompress(s)
