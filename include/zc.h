@@ -24,6 +24,11 @@
  *  deltas: d0 = 0, dj = qj - q(j-1) inside a block; the last block is padded with its last
  *  code; width = bit count of max |dj|; reconstruction x' = (float)((double)q * s).
  *
+ * Indexed streams (zc_set_indexed_streams): version is 2, or 3 when some block is wider than
+ * 15 bits, and between the header and the width table sits an index of nseg + 1 u32,
+ * nseg = ceil(nb / 64), zero padded to a multiple of 16 bytes: entry i is the payload word
+ * offset of block 64 i, entry nseg the number of payload words.  Everything else is as above.
+ *
  * Calls are asynchronous on the given HIP stream unless the last size pointer is non-NULL,
  * in which case the call synchronises the stream and returns the final status and size.
  * In the asynchronous form the status and size are collected later with zc_finish on the
@@ -54,7 +59,8 @@ typedef enum {
 #define ZC_MAX_N (1ull << 31)
 #define ZC_MAX_K 64
 
-/* Worst-case stream size in bytes for n values (every block at width 31: 133 B per 128 B). */
+/* Worst-case stream size in bytes for n values (every block at width 31: 133 B per 128 B),
+ * for the stream variant in force when it is called. */
 size_t zc_compress_bound(size_t n);
 
 /* Workspace bytes needed by any call on at most n_max values with at most k_max reduce
@@ -147,6 +153,20 @@ int zc_debug_quantize(const float* d_in, size_t n, float abs_eb, int32_t* d_q,
  * into d_off_words[nb].  Synchronous.  Errors: ARG, FORMAT, HIP. */
 int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_words, size_t off_cap,
                            void* d_ws, size_t ws_bytes, void* hip_stream);
+
+/* Which stream variant every entry point writes and accepts from now on: 0 (default) the plain
+ * stream, non-zero the indexed one.  The index is the chunk size table of Section 3.5.2: the
+ * compressed size of every chunk is kept in front of the data so that a chunk can be taken up
+ * without looking at the rest.  Here a chunk is 64 blocks (2048 values), the share of one
+ * wave: zc_compress, zc_reduce_compressed and zc_reduce_step write the table as a by-product
+ * of placing their payload, and zc_decompress, zc_decompress_many, zc_reduce_compressed and
+ * zc_reduce_step read their segments' positions from it instead of first summing the width
+ * table, which saves one kernel per call.  A stream of the other variant is ZC_ERR_FORMAT; so
+ * is an index that contradicts the width table, a width above 31, or a width above 15 in a
+ * version-2 stream, which the kernels find as they use each segment: the output of such a
+ * call is unspecified.  Costs 4 bytes per 2048 values.  Process-wide; applies to calls made
+ * afterwards (zc_compress_bound included).  Returns ZC_OK. */
+int zc_set_indexed_streams(int on);
 
 /* How zc_compress, zc_reduce_compressed and zc_reduce_step hand out their tiles (256 or 512 blocks each) to
  * workgroups.  Their single-pass placement (a device-wide exclusive sum of block sizes by

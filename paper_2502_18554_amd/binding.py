@@ -20,7 +20,7 @@ EXPORTS = [
     "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_decompress_many",
     "zc_reduce_compressed", "zc_reduce_step", "zc_quality",
     "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
-    "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out",
+    "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out", "zc_set_indexed_streams",
 ]
 
 _lib = None
@@ -58,6 +58,7 @@ def lib():
         L.zc_debug_quantize.argtypes = [vp, sz, C.c_float, vp, vp, sz, vp]
         L.zc_debug_block_offsets.argtypes = [vp, sz, vp, sz, vp, sz, vp]
         L.zc_set_tile_hand_out.argtypes = [C.c_int]
+        L.zc_set_indexed_streams.argtypes = [C.c_int]
         L.zc_profile_enable.argtypes = [C.c_int]
         L.zc_profile_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int), C.c_int]
         _lib = L
@@ -195,3 +196,7 @@ ZC_HAND_OUT_DISPATCH_ORDER, ZC_HAND_OUT_TICKETS = 0, 1
 
 def zc_set_tile_hand_out(mode):
     return lib().zc_set_tile_hand_out(int(mode))
+
+
+def zc_set_indexed_streams(on):
+    return lib().zc_set_indexed_streams(1 if on else 0)

@@ -65,6 +65,9 @@ KernelTimer g_timer;
 // How the kernels that write a stream hand out their tiles (zc_set_tile_hand_out).
 int g_hand_out = ZC_HAND_OUT_DISPATCH_ORDER;
 
+// Which stream variant the entry points write and accept (zc_set_indexed_streams).
+bool g_indexed = false;
+
 // Most blocks a stream of `bytes` bytes can describe: each costs at least 5 table bytes.
 u64 blocks_bound(u64 bytes) { return bytes > kHeaderBytes ? (bytes - kHeaderBytes) / 5 : 0; }
 
@@ -79,6 +82,18 @@ int finish(const void* d_ws, size_t* result, hipStream_t stream) {
   return status_from_bits(host.status);
 }
 
+// Validation and positions of the input streams ahead of a kernel that reads them.  A plain
+// stream has its block positions computed here; an indexed one brings them along.
+void launch_index(ScanArgs& sa, u64 tiles, u32 prep_grid, hipStream_t stream) {
+  sa.ix = g_indexed;
+  if (!g_indexed)
+    hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), u32(sa.k)), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(index_prep_kernel, dim3(prep_grid), dim3(256), 0, stream, sa);
+}
+
+// Workgroups of index_prep_kernel when it also clears `tiles` look-back descriptors.
+u32 prep_grid_for(u64 tiles) { return u32((tiles + 255) / 256 > 64 ? 64 : (tiles + 255) / 256); }
+
 void launch_init(const WorkspaceLayout& l, u32 ntiles, u8* out, u64 out_cap, u64 n, u32 eb_bits, hipStream_t stream) {
   InitArgs ia;
   ia.ctl = l.ctl;
@@ -90,6 +105,7 @@ void launch_init(const WorkspaceLayout& l, u32 ntiles, u8* out, u64 out_cap, u64
   ia.nb = num_blocks(n);
   ia.eb_bits = eb_bits;
   ia.nsum = 1;
+  ia.ix = g_indexed;
   u32 grid = (ntiles + 255) / 256;
   if (grid < 1) grid = 1;
   if (grid > 1024) grid = 1024;
@@ -110,11 +126,12 @@ struct OffsetsArgs {
   u32* off_words;
   u64 off_cap;
   Control* ctl;
+  bool ix;
 };
 
 __global__ __launch_bounds__(256) void block_offsets_kernel(OffsetsArgs a) {
   if (validation_failed(a.ctl)) return;
-  const ParsedHeader h = parse_header(a.in);
+  const ParsedHeader h = parse_header(a.in, a.ix);
   if (!h.ok) return;
   if (h.nb > a.off_cap) {
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
@@ -124,10 +141,10 @@ __global__ __launch_bounds__(256) void block_offsets_kernel(OffsetsArgs a) {
   const u64 seg = u64(blockIdx.x) * 4 + (threadIdx.x >> 6);
   if (seg >= num_segments(h.nb) || seg >= 4 * a.index.tiles_cap) return;
   const u64 b = seg * kWaveBlocks + u64(lane_id());
-  const u32 w = b < h.nb ? u32(a.in.base[kHeaderBytes + b]) : 0u;
+  const u32 w = b < h.nb ? u32(a.in.base[widths_begin(h.nb, a.ix) + b]) : 0u;
   const u32 words = psize_words(w);
   const u32 incl = wave_inclusive_sum(words);
-  const u32 seg_off = u32(segment_offset(a.index, 0, seg));
+  const u32 seg_off = a.ix ? reinterpret_cast<const u32*>(a.in.base + kHeaderBytes)[seg] : u32(segment_offset(a.index, 0, seg));
   if (b < h.nb) a.off_words[b] = seg_off + incl - words;
 }
 
@@ -146,6 +163,7 @@ void fill_compress_args(CompressArgs& ca, const float* d_in, u64 n, float abs_eb
   ca.ctl = l.ctl;
   ca.desc = l.desc;
   ca.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
+  ca.ix = g_indexed;
 }
 
 }  // namespace
@@ -154,7 +172,7 @@ extern "C" {
 
 size_t zc_compress_bound(size_t n) {
   const u64 nb = num_blocks(n);
-  return size_t(tables_end(nb) + 128 * nb);
+  return size_t(tables_end(nb, g_indexed) + 128 * nb);
 }
 
 size_t zc_workspace_bytes(size_t n_max, int k_max) { return size_t(workspace_bytes(n_max, k_max)); }
@@ -226,8 +244,7 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
   sa.ctl = l.ctl;
   sa.desc = nullptr;
   sa.ndesc = 0;
-  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), 1), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(index_prep_kernel, dim3(1), dim3(256), 0, stream, sa);
+  launch_index(sa, tiles, 1, stream);
   DecompressArgs da;
   da.in = sa.streams[0];
   da.out = d_out;
@@ -235,7 +252,8 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
   da.index = l.index;
   da.ctl = l.ctl;
   KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_DECOMPRESS, stream);
-  hipLaunchKernelGGL(decompress_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, da);
+  hipLaunchKernelGGL(g_indexed ? decompress_kernel<true> : decompress_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), 0,
+                     stream, da);
   g_timer.end(slot, stream);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!n_out) return ZC_OK;
@@ -275,12 +293,12 @@ int zc_decompress_many(const void* const* d_chunks, const size_t* chunk_bytes, i
   sa.ctl = l.ctl;
   sa.desc = nullptr;
   sa.ndesc = 0;
-  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), u32(k)), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(index_prep_kernel, dim3(1), dim3(256), 0, stream, sa);
+  launch_index(sa, tiles, 1, stream);
   da.index = l.index;
   da.ctl = l.ctl;
   KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_DECOMPRESS, stream);
-  hipLaunchKernelGGL(decompress_many_kernel, dim3(u32(tiles), u32(k)), dim3(kTileThreads), 0, stream, da);
+  hipLaunchKernelGGL(g_indexed ? decompress_many_kernel<true> : decompress_many_kernel<false>, dim3(u32(tiles), u32(k)),
+                     dim3(kTileThreads), 0, stream, da);
   g_timer.end(slot, stream);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!n_out) return ZC_OK;
@@ -326,8 +344,7 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   sa.ctl = l.ctl;
   sa.desc = l.desc;
   sa.ndesc = u32(tiles);
-  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), u32(k)), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(index_prep_kernel, dim3(u32((tiles + 255) / 256 > 64 ? 64 : (tiles + 255) / 256)), dim3(256), 0, stream, sa);
+  launch_index(sa, tiles, prep_grid_for(tiles), stream);
   ra.k = k;
   ra.index = l.index;
   ra.out = static_cast<u8*>(d_out);
@@ -336,10 +353,11 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   ra.desc = l.desc;
   ra.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
   KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_REDUCE, stream);
-  hipLaunchKernelGGL(reduce_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
+  hipLaunchKernelGGL(g_indexed ? reduce_kernel<true> : reduce_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
   g_timer.end(slot, stream);
   // for operands with blocks wider than 15 bits; returns at once otherwise
-  hipLaunchKernelGGL(reduce_wide_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
+  hipLaunchKernelGGL(g_indexed ? reduce_wide_kernel<true> : reduce_wide_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), 0,
+                     stream, ra);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
@@ -364,8 +382,7 @@ int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local
   sa.ctl = l.ctl;
   sa.desc = l.desc;
   sa.ndesc = u32(tiles);
-  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), 1), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(index_prep_kernel, dim3(u32((tiles + 255) / 256 > 64 ? 64 : (tiles + 255) / 256)), dim3(256), 0, stream, sa);
+  launch_index(sa, tiles, prep_grid_for(tiles), stream);
   StepArgs ta;
   ta.in = sa.streams[0];
   ta.local = d_local;
@@ -377,7 +394,7 @@ int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local
   ta.desc = l.desc;
   ta.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
   KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_REDUCE_STEP, stream);
-  hipLaunchKernelGGL(step_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ta);
+  hipLaunchKernelGGL(g_indexed ? step_kernel<true> : step_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ta);
   g_timer.end(slot, stream);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
@@ -415,6 +432,11 @@ int zc_quality(const float* d_ref, const float* d_test, size_t n, double* out4, 
   return ZC_OK;
 }
 
+
+int zc_set_indexed_streams(int on) {
+  g_indexed = on != 0;
+  return ZC_OK;
+}
 
 int zc_set_tile_hand_out(int mode) {
   if (mode != ZC_HAND_OUT_DISPATCH_ORDER && mode != ZC_HAND_OUT_TICKETS) return ZC_ERR_ARG;
@@ -459,8 +481,9 @@ int zc_peek_header(const void* d_in, size_t in_bytes, size_t* n, float* abs_eb, 
   const u64 total = u64(w[6]) | (u64(w[7]) << 32);
   float eb;
   std::memcpy(&eb, &w[4], 4);
-  if (w[0] != kMagic || w[1] != (1u | (5u << 16) | (6u << 24)) || nn > ZC_MAX_N || !eb_valid(eb) || w[5] < 1 ||
-      total > in_bytes || total < tables_end(num_blocks(nn)))
+  const bool version_ok = g_indexed ? (w[1] | 1u) == (kVersionIndexed | 1u) : w[1] == kVersionPlain;
+  if (w[0] != kMagic || !version_ok || nn > ZC_MAX_N || !eb_valid(eb) || w[5] < 1 || total > in_bytes ||
+      total < tables_end(num_blocks(nn), g_indexed))
     return ZC_ERR_FORMAT;
   if (n) *n = size_t(nn);
   if (abs_eb) *abs_eb = eb;
@@ -503,14 +526,14 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
   sa.ctl = l.ctl;
   sa.desc = nullptr;
   sa.ndesc = 0;
-  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), 1), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(index_prep_kernel, dim3(1), dim3(256), 0, stream, sa);
+  launch_index(sa, tiles, 1, stream);
   OffsetsArgs oa;
   oa.in = sa.streams[0];
   oa.index = l.index;
   oa.off_words = d_off_words;
   oa.off_cap = off_cap;
   oa.ctl = l.ctl;
+  oa.ix = g_indexed;
   hipLaunchKernelGGL(block_offsets_kernel, dim3(u32(tiles)), dim3(256), 0, stream, oa);
   if (!launch_ok()) return ZC_ERR_HIP;
   return finish(d_ws, nullptr, stream);

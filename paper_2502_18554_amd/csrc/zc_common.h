@@ -34,8 +34,23 @@ __host__ __device__ inline u64 num_blocks(u64 n) { return (n + kBlockValues - 1)
 __host__ __device__ inline u64 num_tiles(u64 nb) { return (nb + kTileBlocks - 1) / kTileBlocks; }
 // No stream has more tiles than this (n <= ZC_MAX_N), so block and segment numbers fit 32 bits.
 constexpr u64 kMaxTiles = (ZC_MAX_N / kBlockValues + kTileBlocks - 1) / kTileBlocks;
-__host__ __device__ inline u64 tables_end(u64 nb) { return kHeaderBytes + pad16(nb) + pad16(4 * nb); }
 __host__ __device__ inline u32 psize_words(u32 w) { return w ? 1 + w : 0; }
+
+// Stream layout.  The plain stream (version 1) is header, width table, outlier table,
+// payload.  The indexed stream (Section 3.5.2 keeps the compressed size of every chunk in
+// front of the data, so that a chunk can be handled without looking at the others; here a
+// chunk is a segment, the 64 blocks of one wave) has version 2, or 3 when some block is wider
+// than 15 bits, and between header and width table an index of nseg + 1 u32: entry i is the
+// payload word offset of segment i, entry nseg the number of payload words; zero padded to 16
+// bytes.  `ix` says which of the two a kernel reads and writes; it is the same for every
+// stream of a process at any one time (zc_set_indexed_streams).
+__host__ __device__ inline u64 num_segments(u64 nb) { return (nb + kWaveBlocks - 1) / kWaveBlocks; }
+__host__ __device__ inline u64 index_bytes(u64 nb, bool ix) { return ix ? pad16(4 * (num_segments(nb) + 1)) : 0; }
+__host__ __device__ inline u64 widths_begin(u64 nb, bool ix) { return kHeaderBytes + index_bytes(nb, ix); }
+__host__ __device__ inline u64 outliers_begin(u64 nb, bool ix) { return widths_begin(nb, ix) + pad16(nb); }
+__host__ __device__ inline u64 tables_end(u64 nb, bool ix) { return outliers_begin(nb, ix) + pad16(4 * nb); }
+constexpr u32 kVersionPlain = 1u | (5u << 16) | (6u << 24);     // header word 1: version, block_log2, guard_log2
+constexpr u32 kVersionIndexed = 2u | (5u << 16) | (6u << 24);   // | 1 when some block is wider than 15 bits
 
 // Device status word: bit i set <=> error code i was raised.
 __host__ __device__ constexpr u32 status_bit(int code) { return 1u << code; }
@@ -65,7 +80,6 @@ __host__ __device__ inline u32* ticket_counter(Control* ctl, u32 shard) {
 }
 
 // A segment is the 64 blocks owned by one wave; a tile is 4 segments.
-__host__ __device__ inline u64 num_segments(u64 nb) { return (nb + kWaveBlocks - 1) / kWaveBlocks; }
 
 // Positions inside an existing stream are kept at three levels (see zc_scan.h): the offset of
 // every segment inside its scan group of 64 segments, the offset of every group inside its
@@ -291,12 +305,14 @@ __device__ inline u32 wave_inclusive_sum(u32 v) {
 
 // ---------------------------------------------------------------------------------------
 // Decoupled look-back over tile descriptors.  A descriptor is one 64-bit word:
-// bits 63..62 = state (0 empty, 1 tile aggregate, 2 inclusive prefix), bits 61..0 = value.
+// bits 63..62 = state (0 empty, 1 tile aggregate, 2 inclusive prefix), bit 61 = the tile (or,
+// in a prefix, some tile up to this one) holds a block wider than 15 bits, bits 60..0 = value.
 // Only the descriptor word itself is communicated, so relaxed device-scope atomics suffice.
 // ---------------------------------------------------------------------------------------
 constexpr u64 kDescAggregate = u64(1) << 62;
 constexpr u64 kDescPrefix = u64(2) << 62;
-constexpr u64 kDescValueMask = (u64(1) << 62) - 1;
+constexpr u64 kDescWide = u64(1) << 61;
+constexpr u64 kDescValueMask = (u64(1) << 61) - 1;
 
 // Descriptors are polled by every tile in flight, so neighbours must not share a memory
 // line (polls of one line queue up behind each other): one descriptor per 128 bytes.
@@ -340,7 +356,8 @@ __device__ inline u32 desc32_load(const u32* d) {
   return __hip_atomic_load(d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Called by all 64 lanes of one wave.  Returns the sum of the values of tiles [0, tile).
+// Called by all 64 lanes of one wave.  Returns the sum of the values of tiles [0, tile), with
+// kDescWide set if one of those tiles has it set.
 // Every tile below `tile` is in work on a resident workgroup (or done), and a workgroup
 // publishes its aggregate without waiting for anything, so the wait below ends; it is
 // bounded anyway and raises ZC_ERR_HIP in *status if the bound is hit.
@@ -362,6 +379,7 @@ __device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status,
   const int lane = lane_id();
   const u64 lanes_mask = kLookLanes == 64 ? ~u64(0) : ((u64(1) << kLookLanes) - 1);
   u64 excl = 0;
+  u64 wide = 0;
   i64 look = i64(tile) - 1;                  // lane 0 inspects the nearest predecessor
   u32 spins = 0;
   u64 d = first;
@@ -377,17 +395,18 @@ __device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status,
                         (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & status_bit(ZC_ERR_HIP)) != 0;
       if (spins > kSpinLimit || lost) {
         if (lane == 0) atomicOr(status, status_bit(ZC_ERR_HIP));
-        return excl;
+        return excl | wide;
       }
       __builtin_amdgcn_s_sleep(1);
       d = lookback_poll(desc, look);
       continue;
     }
+    if (__ballot((d & kDescWide) != 0) & lanes_mask & needed) wide = kDescWide;
     // lanes before `first_prefix` hold tile aggregates (small); lane `first_prefix` may hold a prefix (64-bit)
     excl += wave_sum_u32(lane < first_prefix || (lane == first_prefix && !has_prefix) ? u32(d) : 0u);
     if (has_prefix) {
       const u64 p = u64(lane_value(u32(d), first_prefix)) | (u64(lane_value(u32(d >> 32), first_prefix)) << 32);
-      return excl + (p & kDescValueMask);
+      return (excl + (p & kDescValueMask)) | wide;
     }
     look -= kLookLanes;                      // a complete window is final: aggregates never change
     d = lookback_poll(desc, look);

@@ -39,6 +39,7 @@ struct CompressArgs {
   Control* ctl;
   u64* desc;
   u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
+  u32 ix;            // write an indexed stream (see index_bytes)
 };
 
 // Round-to-nearest-even of r for |r| < 2^31 as the low word of r + 1.5 * 2^52.
@@ -190,8 +191,10 @@ __device__ inline void block_fields(const CompressArgs& a, const float4 (&x)[8],
 template <bool FULL>
 __device__ inline void wide_tile(const CompressArgs& a, const PayloadSink& sink, const Placement& pl, u32 tile,
                                  u32 ntiles, u64 wblock0, u32* wl, u64* sh_base, int wave, int lane) {
-  const u64 base = resolve_tile_base(sink, pl, tile, sh_base, wave, lane);
-  const u64 tend = tables_end(a.nb);
+  const TileBase tb = resolve_tile_base(sink, pl, tile, sh_base, wave, lane);
+  const u64 base = tb.words;
+  if (lane == 0) write_index_entry(sink, tile * kPackWaves + u32(wave), base + pl.wave_off);
+  const u64 tend = tables_end(a.nb, a.ix);
   const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
   u32* const payload = reinterpret_cast<u32*>(a.out + tend);
   const u64 wave_first = base + pl.wave_off;                      // first payload word of this wave
@@ -248,7 +251,7 @@ __device__ inline void wide_tile(const CompressArgs& a, const PayloadSink& sink,
     }
     wave_lds_sync();
   }
-  finish_stream(sink, pl, tile, ntiles, base);
+  finish_stream(sink, pl, tile, ntiles, tb);
 }
 
 // One workgroup per tile.  FULL = the launch covers the tiles whose 16384 values all exist
@@ -267,7 +270,7 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
   const int wave = int(threadIdx.x) >> 6;
   const u32 ntiles = u32(num_pack_tiles(a.nb));
   u32* const wl = lds + wave * kWaveStage;
-  const bool tables_fit = a.out_cap >= tables_end(a.nb);
+  const bool tables_fit = a.out_cap >= tables_end(a.nb, a.ix);
   u32 err = 0;
 
   u32 tile = first_tile;
@@ -293,8 +296,8 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
     pl.w = (active && bf.any) ? 32u - u32(__builtin_clz(bf.any)) : 0u;
     pl.wmax = wave_max_u32(pl.w);
     if (active && tables_fit) {
-      a.out[kHeaderBytes + b] = u8(pl.w);
-      reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(a.nb))[b] = bf.outlier;
+      a.out[widths_begin(a.nb, a.ix) + b] = u8(pl.w);
+      reinterpret_cast<i32*>(a.out + outliers_begin(a.nb, a.ix))[b] = bf.outlier;
     }
 
     // ---- place the block inside the wave and the wave inside the tile ----
@@ -320,8 +323,9 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
     }
     tile_wmax = uniform(tile_wmax);
     // publish the tile's size as early as possible: the tiles after this one wait for it
-    const PayloadSink sink{a.out, a.out_cap, a.nb, a.ctl, a.desc};
-    if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total);
+    pl.tile_wide = a.ix && tile_wmax > 15;
+    const PayloadSink sink{a.out, a.out_cap, a.nb, a.ctl, a.desc, a.ix != 0};
+    if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
 
     // ---- fields -> sign + plane words in registers, then the back half ----
     if (tile_wmax <= 15) {
@@ -358,6 +362,7 @@ struct InitArgs {
   u64 out_cap;
   u64 n, nb;
   u32 eb_bits, nsum;
+  bool ix;
 };
 
 __global__ void init_kernel(InitArgs a) {
@@ -370,20 +375,9 @@ __global__ void init_kernel(InitArgs a) {
     a.ctl->flags = 0;
     a.ctl->result = 0;
     if (a.out) {
-      const u64 tend = tables_end(a.nb);
+      const u64 tend = tables_end(a.nb, a.ix);
       if (a.out_cap >= tend) {
-        u32* h = reinterpret_cast<u32*>(a.out);
-        h[0] = kMagic;
-        h[1] = 1u | (5u << 16) | (6u << 24);
-        h[2] = u32(a.n);
-        h[3] = u32(a.n >> 32);
-        h[4] = a.eb_bits;
-        h[5] = a.nsum;
-        h[6] = u32(tend);           // total_bytes of an empty payload; the last tile overwrites it
-        h[7] = u32(tend >> 32);
-        for (u64 i = a.nb; i < pad16(a.nb); ++i) a.out[kHeaderBytes + i] = 0;
-        u8* ot = a.out + kHeaderBytes + pad16(a.nb);
-        for (u64 i = 4 * a.nb; i < pad16(4 * a.nb); ++i) ot[i] = 0;
+        write_stream_header(a.out, a.n, a.nb, a.eb_bits, a.nsum, a.ix, true);
       } else {
         a.ctl->status = status_bit(ZC_ERR_CAPACITY);
       }

@@ -30,41 +30,75 @@ struct DecompressArgs {
 // than 15 bits fetches per lane instead.  Returns the widest block of the wave.  Widths up to
 // 15: lo[0..15) = planes 0..14, lo[15] = sign word.  Wider: lo[0..16) = planes 0..15,
 // hi[0..15) = planes 16..30, hi[15] = sign word.  `wl` is free again on return.
+// Indexed stream (ix): seg_words = the segment's size by the stream's own index.  The staged
+// copy is asked for on that figure, before the widths are looked at, so it travels together
+// with the loads of the tables; a segment whose widths add up to another figure, a width above
+// 31, or one above 15 in a stream that promised none (!may_be_wide) make the stream malformed
+// (`err`), and nothing of the segment's payload is used.
+struct WaveStage {
+  uint4 v[5];
+};
+
+// The copy starts at the 16-byte boundary at or below the segment (the payload area itself is
+// 16-byte aligned) and keeps that misalignment in LDS, so it moves 16 bytes per lane and
+// instruction, all loads in flight together.  span = words to bring in, <= 1027.
+__device__ inline WaveStage load_wave_stage(const u32* payload, u64 payload_words, u64 src0, u32 span, int lane) {
+  WaveStage st;
+#pragma unroll
+  for (int i = 0; i < 5; ++i) {
+    const u32 idx = 4u * u32(lane) + 256u * u32(i);
+    st.v[i] = make_uint4(0, 0, 0, 0);
+    if (idx < span) {
+      if (src0 + idx + 4 <= payload_words) {
+        st.v[i] = *reinterpret_cast<const uint4*>(payload + src0 + idx);
+      } else {                                       // the last words of the stream
+        const u64 left = payload_words - (src0 + idx);
+        st.v[i].x = payload[src0 + idx];
+        if (left > 1) st.v[i].y = payload[src0 + idx + 1];
+        if (left > 2) st.v[i].z = payload[src0 + idx + 2];
+      }
+    }
+  }
+  return st;
+}
+
 __device__ inline u32 wave_block_words(const u32* payload, u64 payload_words, u32 w, u64 seg_off, u32* wl, int lane,
-                                       u32 (&lo)[16], u32 (&hi)[16]) {
+                                       u32 (&lo)[16], u32 (&hi)[16], bool ix, u32 seg_words, bool may_be_wide,
+                                       u32& err) {
+  const u32 mis = u32(seg_off) & 3u;
+  const u64 src0 = seg_off - mis;                      // in words, multiple of 4
+  WaveStage st;
+  u32 span = 0;
+  if (ix) {
+    // at most 64 * 16 words when no block is wider than 15 bits
+    if (seg_words <= 64u * 16u && seg_off + seg_words <= payload_words) span = mis + seg_words;
+    st = load_wave_stage(payload, payload_words, src0, span, lane);
+  }
+  bool unfit = false;
+  if (ix) {
+    unfit = __any(w > (may_be_wide ? 31u : 15u));
+    if (unfit) w = 0;
+  }
   const u32 words = psize_words(w);
   const u32 incl = wave_inclusive_sum(words);
   const u32 off_in_wave = incl - words;
   const u32 wave_total = lane_value(incl, 63);
   const u32 wmax = wave_max_u32(w);
   // a validated stream keeps every segment inside the payload; refuse to read outside anyway
-  const bool inside = seg_off + wave_total <= payload_words;
+  bool inside = seg_off + wave_total <= payload_words;
+  if (ix && (unfit || wave_total != seg_words)) {
+    err |= status_bit(ZC_ERR_FORMAT);
+    inside = false;
+  }
 #pragma unroll
   for (int p = 0; p < 16; ++p) lo[p] = 0;
 
   if (wmax <= 15) {
-    // At most 64 * 16 words.  The copy starts at the 16-byte boundary at or below the segment
-    // (the payload area itself is 16-byte aligned) and keeps that misalignment in LDS, so it
-    // moves 16 bytes per lane and instruction, all loads in flight together.
-    const u32 mis = u32(seg_off) & 3u;
-    const u64 src0 = seg_off - mis;                    // in words, multiple of 4
-    const u32 span = inside ? mis + wave_total : 0u;   // words to bring in, <= 1027
-    uint4 stage[5];
-#pragma unroll
-    for (int i = 0; i < 5; ++i) {
-      const u32 idx = 4u * u32(lane) + 256u * u32(i);
-      stage[i] = make_uint4(0, 0, 0, 0);
-      if (idx < span) {
-        if (src0 + idx + 4 <= payload_words) {
-          stage[i] = *reinterpret_cast<const uint4*>(payload + src0 + idx);
-        } else {                                       // the last words of the stream
-          const u64 left = payload_words - (src0 + idx);
-          stage[i].x = payload[src0 + idx];
-          if (left > 1) stage[i].y = payload[src0 + idx + 1];
-          if (left > 2) stage[i].z = payload[src0 + idx + 2];
-        }
-      }
+    if (!ix) {
+      span = inside ? mis + wave_total : 0u;
+      st = load_wave_stage(payload, payload_words, src0, span, lane);
     }
+    const uint4 (&stage)[5] = st.v;
 #pragma unroll
     for (int i = 0; i < 5; ++i) {
       const u32 idx = 4u * u32(lane) + 256u * u32(i);
@@ -117,8 +151,10 @@ __device__ inline void deltas_from_block_words(u32 wmax, u32 (&lo)[16], u32 (&hi
 
 // One tile (blockIdx.x) of stream `s` of the index, into `out`.  `counted`: the stream's n is
 // added to the control block's result instead of stored there (several streams per call).
+// `ix`: the stream is indexed; its width bytes then sit behind the index, whose size only
+// the header tells, so they are asked for together with the outlier and the payload.
 __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u64 out_cap_elems, const StreamIndex& index,
-                                       int s, Control* ctl, bool counted, u32* lds) {
+                                       int s, Control* ctl, bool counted, u32* lds, bool ix) {
   const DecompressArgs a{in, out_values, out_cap_elems, index, ctl};
 
   // Everything that can be asked for before the header is known goes out at once: the control
@@ -134,10 +170,18 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
   const uint2 gate = load_gate(a.ctl, zero);
   const HeaderWords hw = load_header_words(a.in.base, zero);
   SegmentOffsetParts seg_parts{0, 0, 0};
-  if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, s, seg, zero);
-  u32 w = u64(kHeaderBytes) + b < a.in.bytes ? u32(*at_bytes(a.in.base, kHeaderBytes + b)) : 0u;
+  u32 seg_end = 0, w = 0;
+  if (ix) {
+    if (u64(kHeaderBytes) + 4 * u64(seg) + 8 <= a.in.bytes) {
+      seg_parts = load_segment_offset(a.index, s, seg, zero, a.in.base);
+      seg_end = load_segment_end(a.in.base, seg, zero);
+    }
+  } else {
+    if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, s, seg, zero);
+    if (u64(kHeaderBytes) + b < a.in.bytes) w = u32(*at_bytes(a.in.base, kHeaderBytes + b));
+  }
 
-  const ParsedHeader h = parse_header(hw, a.in.bytes);
+  const ParsedHeader h = parse_header(hw, a.in.bytes, ix);
   if (gate_failed(gate) || !h.ok) return;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     if (counted) atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->result), static_cast<unsigned long long>(h.n));
@@ -152,18 +196,22 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
   u32* const wl = lds + wave * kWaveStage;
   if (seg >= num_segments(h.nb)) return;           // no barrier below: waves are independent
   const bool active = b < h.nb;
+  if (ix && active) w = u32(*at_bytes(a.in.base, u32(widths_begin(h.nb, true)) + b));
   if (!active) w = 0;
 
-  const i32* outliers = reinterpret_cast<const i32*>(a.in.base + kHeaderBytes + pad16(h.nb));
-  const u32* payload = reinterpret_cast<const u32*>(a.in.base + tables_end(h.nb));
-  const u64 payload_words = (h.total - tables_end(h.nb)) / 4;
+  const i32* outliers = reinterpret_cast<const i32*>(a.in.base + outliers_begin(h.nb, ix));
+  const u32* payload = reinterpret_cast<const u32*>(a.in.base + tables_end(h.nb, ix));
+  const u64 payload_words = (h.total - tables_end(h.nb, ix)) / 4;
 
   u32 cur = active ? u32(outliers[b]) : 0u;
-  const u64 seg_off = segment_offset(seg_parts);
+  const u64 seg_off = ix ? u64(uniform(seg_parts.seg)) : segment_offset(seg_parts);
   i32 d[32];
   {
     u32 lo[16], hi[16];
-    const u32 wmax = wave_block_words(payload, payload_words, w, seg_off, wl, lane, lo, hi);
+    u32 err = 0;
+    const u32 wmax = wave_block_words(payload, payload_words, w, seg_off, wl, lane, lo, hi, ix,
+                                      uniform(seg_end) - u32(seg_off), h.wide, err);
+    if (err && lane == 0) atomicOr(&a.ctl->status, err);
     deltas_from_block_words(wmax, lo, hi, d);
   }
 
@@ -205,9 +253,10 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
   }
 }
 
+template <bool IX>
 __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
-  decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, false, lds);
+  decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, false, lds, IX);
 }
 
 // k streams in one launch (the tail of the compressed Allgather, Section 3.5.1: every rank
@@ -220,10 +269,11 @@ struct DecompressManyArgs {
   Control* ctl;
 };
 
+template <bool IX>
 __global__ __launch_bounds__(kTileThreads, 5) void decompress_many_kernel(DecompressManyArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
   const int s = blockIdx.y;
-  decompress_tile(a.in[s], a.out[s], a.out_cap_elems[s], a.index, s, a.ctl, true, lds);
+  decompress_tile(a.in[s], a.out[s], a.out_cap_elems[s], a.index, s, a.ctl, true, lds, IX);
 }
 
 }  // namespace zc

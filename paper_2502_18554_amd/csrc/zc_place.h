@@ -18,6 +18,7 @@ struct PayloadSink {
   u64 nb;           // blocks of the stream
   Control* ctl;
   u64* desc;        // look-back descriptors
+  bool ix;          // the stream carries a segment index (see index_bytes)
 };
 
 // Per-wave view of where its payload goes.
@@ -26,7 +27,65 @@ struct Placement {
   u32 off_in_wave;          // payload word offset of this block inside the wave
   u32 half0_total, wave_total;
   u32 wave_off, tile_total; // the wave inside the tile; payload words of the tile
+  bool tile_wide;           // some block of the tile is wider than 15 bits (only indexed streams record it)
 };
+
+// Where a tile starts, as resolve_tile_base hands it out.
+struct TileBase {
+  u64 words;                // payload words of all tiles before this one
+  bool wide_so_far;         // this tile or one before it holds a block wider than 15 bits
+};
+
+// The waves of a tile tell each other their payload sizes through LDS; a wave that writes an
+// indexed stream marks its size when it holds a block wider than 15 bits.
+constexpr u32 kWaveWideMark = 1u << 31;
+
+__device__ inline void sum_wave_totals(const u32* sh_wave_total, int wave, bool ix, Placement& pl) {
+  pl.wave_off = 0;
+  pl.tile_total = 0;
+  u32 marks = 0;
+#pragma unroll
+  for (int i = 0; i < kTileWaves; ++i) {
+    u32 t = sh_wave_total[i];
+    if (ix) {
+      marks |= t;
+      t &= ~kWaveWideMark;
+    }
+    if (i < wave) pl.wave_off += t;
+    pl.tile_total += t;
+  }
+  pl.tile_wide = ix && (marks & kWaveWideMark) != 0;
+}
+
+// Fixed header fields and the zero padding of the tables of the stream being written; one
+// thread, and out_cap >= tables_end.  The version word of an indexed stream, total_bytes and
+// the closing entry of the index belong to the last tile (finish_stream), whose stores must
+// not meet others to the same bytes from the same kernel: `closing` says that no tile follows
+// in this kernel (an empty stream, or a kernel of its own ahead of the tiles), and has them
+// written here, for an empty payload.
+__device__ inline void write_stream_header(u8* out, u64 n, u64 nb, u32 eb_bits, u32 nsum, bool ix, bool closing) {
+  const u64 tend = tables_end(nb, ix);
+  const u64 nseg = num_segments(nb);
+  u32* hw = reinterpret_cast<u32*>(out);
+  hw[0] = kMagic;
+  if (!ix) hw[1] = kVersionPlain;
+  hw[2] = u32(n);
+  hw[3] = u32(n >> 32);
+  hw[4] = eb_bits;
+  hw[5] = nsum;
+  if (closing) {
+    if (ix) hw[1] = kVersionIndexed;
+    hw[6] = u32(tend);
+    hw[7] = u32(tend >> 32);
+    if (ix) hw[kHeaderBytes / 4 + nseg] = 0;
+  }
+  if (ix)
+    for (u64 i = nseg + 1; i < index_bytes(nb, true) / 4; ++i) hw[kHeaderBytes / 4 + i] = 0;
+  u8* wt = out + widths_begin(nb, ix);
+  for (u64 i = nb; i < pad16(nb); ++i) wt[i] = 0;
+  u8* ot = out + outliers_begin(nb, ix);
+  for (u64 i = 4 * nb; i < pad16(4 * nb); ++i) ot[i] = 0;
+}
 
 // Writes the payload words of the lanes of one half-wave to the wave's staging area and copies
 // them out with coalesced stores.  Word 0 is the sign word, word 1 + p is plane p; `word(i)`
@@ -54,8 +113,9 @@ __device__ inline void stage_and_copy_half(WordFn word, u32 w, bool in_half, u32
 
 // Publishes the tile's payload size; called by one thread as soon as the size is known,
 // because the tiles after this one wait for it.
-__device__ inline void publish_tile_size(const PayloadSink& s, u32 tile, u32 tile_total) {
-  desc_store(s.desc + desc_slot(tile), (tile == 0 ? kDescPrefix : kDescAggregate) | u64(tile_total));
+__device__ inline void publish_tile_size(const PayloadSink& s, u32 tile, u32 tile_total, bool tile_wide) {
+  desc_store(s.desc + desc_slot(tile),
+             (tile == 0 ? kDescPrefix : kDescAggregate) | (tile_wide ? kDescWide : 0) | u64(tile_total));
 }
 
 // Base offset of the tile, in payload words: wave 0 looks back, everyone meets at one barrier.
@@ -63,34 +123,48 @@ __device__ inline void publish_tile_size(const PayloadSink& s, u32 tile, u32 til
 // `meanwhile()` runs in every wave once wave 0 has sent its first poll: memory operations
 // issued there overlap with the poll's round trip instead of queueing in front of it.
 template <typename MeanwhileFn>
-__device__ inline u64 resolve_tile_base(const PayloadSink& s, const Placement& pl, u32 tile, u64* sh_base, int wave,
-                                        int lane, MeanwhileFn meanwhile) {
+__device__ inline TileBase resolve_tile_base(const PayloadSink& s, const Placement& pl, u32 tile, u64* sh_base, int wave,
+                                             int lane, MeanwhileFn meanwhile) {
   u64 first = 0;
   if (wave == 0 && tile) first = lookback_poll(s.desc, i64(tile) - 1);
   meanwhile();
   if (wave == 0) {
-    const u64 base = tile ? lookback_exclusive(s.desc, tile, &s.ctl->status, first) : 0;
+    // words of the tiles before this one, and kDescWide if one of them, or this one, is wide
+    const u64 before = (tile ? lookback_exclusive(s.desc, tile, &s.ctl->status, first) : 0) | (pl.tile_wide ? kDescWide : 0);
     if (lane == 0) {
-      if (tile) desc_store(s.desc + desc_slot(tile), kDescPrefix | (base + pl.tile_total));
-      *sh_base = base;
+      if (tile) desc_store(s.desc + desc_slot(tile), kDescPrefix | (before + pl.tile_total));
+      *sh_base = before;
     }
   }
   lds_barrier();                // only sh_base passes through it
-  return *sh_base;
+  const u64 before = *sh_base;
+  return TileBase{before & kDescValueMask, (before & kDescWide) != 0};
 }
 
-__device__ inline u64 resolve_tile_base(const PayloadSink& s, const Placement& pl, u32 tile, u64* sh_base, int wave,
-                                        int lane) {
+__device__ inline TileBase resolve_tile_base(const PayloadSink& s, const Placement& pl, u32 tile, u64* sh_base, int wave,
+                                             int lane) {
   return resolve_tile_base(s, pl, tile, sh_base, wave, lane, [] {});
 }
 
-// The last tile knows the size of the stream.
-__device__ inline void finish_stream(const PayloadSink& s, const Placement& pl, u32 tile, u32 ntiles, u64 base) {
+// Index entry of a segment of the stream being written: one lane of the wave that owns it.
+__device__ inline void write_index_entry(const PayloadSink& s, u32 seg, u64 seg_words_before) {
+  if (s.ix && u64(seg) < num_segments(s.nb) && s.out_cap >= tables_end(s.nb, true))
+    reinterpret_cast<u32*>(s.out + kHeaderBytes)[seg] = u32(seg_words_before);
+}
+
+// The last tile knows the size of the stream, and of an indexed one whether it holds wide blocks.
+__device__ inline void finish_stream(const PayloadSink& s, const Placement& pl, u32 tile, u32 ntiles, const TileBase& tb) {
   if (tile == ntiles - 1 && threadIdx.x == 0) {
-    const u64 total = tables_end(s.nb) + 4 * (base + pl.tile_total);
+    const u64 words = tb.words + pl.tile_total;
+    const u64 total = tables_end(s.nb, s.ix) + 4 * words;
     s.ctl->result = total;
     if (total > s.out_cap) atomicOr(&s.ctl->status, status_bit(ZC_ERR_CAPACITY));
     if (s.out_cap >= kHeaderBytes) reinterpret_cast<u64*>(s.out)[3] = total;
+    if (s.ix && s.out_cap >= tables_end(s.nb, true)) {
+      u32* hw = reinterpret_cast<u32*>(s.out);
+      hw[1] = kVersionIndexed | (tb.wide_so_far ? 1u : 0u);
+      hw[kHeaderBytes / 4 + num_segments(s.nb)] = u32(words);      // the closing entry of the index
+    }
   }
 }
 
@@ -99,7 +173,7 @@ __device__ inline void finish_stream(const PayloadSink& s, const Placement& pl, 
 template <int NW, typename WordFn>
 __device__ inline void copy_wave_out(const PayloadSink& s, WordFn word, const Placement& pl, u64 base, u32* wl, int lane) {
   static_assert(32 * NW <= kWaveStage, "a half-wave of widest blocks must fit the staging area");
-  const u64 tend = tables_end(s.nb);
+  const u64 tend = tables_end(s.nb, s.ix);
   const u64 cap_words = s.out_cap > tend ? (s.out_cap - tend) / 4 : 0;
   u32* const payload = reinterpret_cast<u32*>(s.out + tend);
   const u64 dst0 = base + pl.wave_off;
@@ -119,9 +193,10 @@ __device__ inline void copy_wave_out(const PayloadSink& s, WordFn word, const Pl
 template <int NW, typename WordFn, typename MeanwhileFn>
 __device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
                                    u32* wl, u64* sh_base, int wave, int lane, MeanwhileFn meanwhile) {
-  const u64 base = resolve_tile_base(s, pl, tile, sh_base, wave, lane, meanwhile);
-  copy_wave_out<NW>(s, word, pl, base, wl, lane);
-  finish_stream(s, pl, tile, ntiles, base);
+  const TileBase tb = resolve_tile_base(s, pl, tile, sh_base, wave, lane, meanwhile);
+  if (lane == 0) write_index_entry(s, tile * (blockDim.x >> 6) + u32(wave), tb.words + pl.wave_off);
+  copy_wave_out<NW>(s, word, pl, tb.words, wl, lane);
+  finish_stream(s, pl, tile, ntiles, tb);
 }
 
 template <int NW, typename WordFn>

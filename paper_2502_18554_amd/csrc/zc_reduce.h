@@ -39,29 +39,13 @@ struct ReduceArgs {
 };
 
 // Header fields and table padding of the output stream; one thread.
-__device__ inline void write_reduce_header(const ReduceArgs& a, const ParsedHeader& h, u32 ntiles) {
-  const u64 tend = tables_end(h.nb);
+__device__ inline void write_reduce_header(const ReduceArgs& a, const ParsedHeader& h, u32 ntiles, bool ix) {
+  const u64 tend = tables_end(h.nb, ix);
   u64 nsum = 0;
-  for (int s = 0; s < a.k; ++s) nsum += parse_header(a.in[s]).nsum;
+  for (int s = 0; s < a.k; ++s) nsum += parse_header(a.in[s], ix).nsum;
   if (nsum > 0xffffffffull) atomicOr(&a.ctl->status, status_bit(ZC_ERR_RANGE));
-  if (a.out_cap >= tend) {
-    u32* hw = reinterpret_cast<u32*>(a.out);
-    hw[0] = kMagic;
-    hw[1] = 1u | (5u << 16) | (6u << 24);
-    hw[2] = u32(h.n);
-    hw[3] = u32(h.n >> 32);
-    hw[4] = h.eb_bits;
-    hw[5] = u32(nsum);
-    if (ntiles == 0) {
-      hw[6] = u32(tend);
-      hw[7] = u32(tend >> 32);
-    }
-    for (u64 i = h.nb; i < pad16(h.nb); ++i) a.out[kHeaderBytes + i] = 0;
-    u8* ot = a.out + kHeaderBytes + pad16(h.nb);
-    for (u64 i = 4 * h.nb; i < pad16(4 * h.nb); ++i) ot[i] = 0;
-  } else {
-    atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
-  }
+  if (a.out_cap >= tend) write_stream_header(a.out, h.n, h.nb, h.eb_bits, u32(nsum), ix, ntiles == 0);
+  else atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
   if (ntiles == 0) a.ctl->result = tend;
 }
 
@@ -87,8 +71,8 @@ __device__ inline bool block_out_of_range(const u32 (&mag)[NP], u32 sign, i64 ou
 template <int NW, int NP, typename WordFn>
 __device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, const u32 (&mag)[NP], u32 sign, u32 w,
                                  i64 outlier, bool active, u64 b, u32 tile, u32 ntiles, WordFn word, u32* wl,
-                                 u32* sh_wave_total, u64* sh_base, int wave, int lane) {
-  const u64 tend = tables_end(h.nb);
+                                 u32* sh_wave_total, u64* sh_base, int wave, int lane, bool ix) {
+  const u64 tend = tables_end(h.nb, ix);
   if (!active) w = 0;
   u32 err = 0;
   if (active) {
@@ -109,22 +93,15 @@ __device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, con
   pl.wave_total = lane_value(incl, 63);
   pl.half0_total = lane_value(incl, 31);
   pl.off_in_wave = incl - words;
-  if (lane == 0) sh_wave_total[wave] = pl.wave_total;
+  if (lane == 0) sh_wave_total[wave] = pl.wave_total | (ix && pl.wmax > 15 ? kWaveWideMark : 0u);
   if (active && a.out_cap >= tend) {
-    a.out[kHeaderBytes + b] = u8(w);
-    reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(h.nb))[b] = i32(outlier);
+    a.out[widths_begin(h.nb, ix) + b] = u8(w);
+    reinterpret_cast<i32*>(a.out + outliers_begin(h.nb, ix))[b] = i32(outlier);
   }
   lds_barrier();                // the wave totals; the stores above stay in flight
-  pl.wave_off = 0;
-  pl.tile_total = 0;
-#pragma unroll
-  for (int i = 0; i < kTileWaves; ++i) {
-    const u32 t = sh_wave_total[i];
-    if (i < wave) pl.wave_off += t;
-    pl.tile_total += t;
-  }
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc};
-  if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total);
+  sum_wave_totals(sh_wave_total, wave, ix, pl);
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix};
+  if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) atomicOr(&a.ctl->status, err);
   finish_tile<NW>(sink, word, pl, tile, ntiles, wl, sh_base, wave, lane);
 }
@@ -138,9 +115,9 @@ constexpr int kWholeStage = 64 * 24;
 template <int NW, int NP, typename WordFn>
 __device__ inline void place_sum_staged(const ReduceArgs& a, const ParsedHeader& h, const u32 (&mag)[NP], u32 sign, u32 w,
                                         i64 outlier, bool active, u64 b, u32 tile, u32 ntiles, WordFn word, u32* wl,
-                                        u32* sh_wave_total, u64* sh_base, int wave, int lane) {
+                                        u32* sh_wave_total, u64* sh_base, int wave, int lane, bool ix) {
   static_assert(64 * NW <= kWholeStage, "a wave of widest blocks must fit the staging area");
-  const u64 tend = tables_end(h.nb);
+  const u64 tend = tables_end(h.nb, ix);
   if (!active) w = 0;
   u32 err = 0;
   if (active) {
@@ -161,11 +138,11 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ParsedHeader&
   pl.wave_total = lane_value(incl, 63);
   pl.half0_total = lane_value(incl, 31);
   pl.off_in_wave = incl - words;
-  if (lane == 0) sh_wave_total[wave] = pl.wave_total;
+  if (lane == 0) sh_wave_total[wave] = pl.wave_total | (ix && pl.wmax > 15 ? kWaveWideMark : 0u);
   if (active && a.out_cap >= tend) {
     // (the whole output stream is written with the non-temporal hint, see store_once)
-    __builtin_nontemporal_store(u8(w), a.out + kHeaderBytes + b);
-    __builtin_nontemporal_store(i32(outlier), reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(h.nb)) + b);
+    __builtin_nontemporal_store(u8(w), a.out + widths_begin(h.nb, ix) + b);
+    __builtin_nontemporal_store(i32(outlier), reinterpret_cast<i32*>(a.out + outliers_begin(h.nb, ix)) + b);
   }
   if (w) {
     wl[pl.off_in_wave] = word(std::integral_constant<int, 0>{});
@@ -174,20 +151,14 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ParsedHeader&
     }(std::make_integer_sequence<int, NW - 1>{});
   }
   lds_barrier();                // the wave totals (and the words above); the stores stay in flight
-  pl.wave_off = 0;
-  pl.tile_total = 0;
-#pragma unroll
-  for (int i = 0; i < kTileWaves; ++i) {
-    const u32 t = sh_wave_total[i];
-    if (i < wave) pl.wave_off += t;
-    pl.tile_total += t;
-  }
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc};
-  if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total);
+  sum_wave_totals(sh_wave_total, wave, ix, pl);
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix};
+  if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) atomicOr(&a.ctl->status, err);
-  const u64 base = resolve_tile_base(sink, pl, tile, sh_base, wave, lane);
+  const TileBase tb = resolve_tile_base(sink, pl, tile, sh_base, wave, lane);
   const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
-  const u64 d0 = base + pl.wave_off;
+  const u64 d0 = tb.words + pl.wave_off;
+  if (lane == 0) write_index_entry(sink, tile * kTileWaves + u32(wave), d0);
   u32* const dst = reinterpret_cast<u32*>(a.out + tend) + d0;
   const u64 room = cap_words > d0 ? cap_words - d0 : 0;
   const u32 limit = u64(pl.wave_total) < room ? pl.wave_total : u32(room);
@@ -198,7 +169,7 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ParsedHeader&
     if (i < limit) store_once(dst + i, wl[i]);
   }
   wave_lds_sync();
-  finish_stream(sink, pl, tile, ntiles, base);
+  finish_stream(sink, pl, tile, ntiles, tb);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -218,6 +189,7 @@ constexpr int kSumChunk = 4;
 struct OperandMeta {
   u32 w;            // this lane's block width
   SegmentOffsetParts seg_off;   // payload word offset of the wave's segment (uniform)
+  u32 seg_end;                  // indexed streams: the payload word offset at which the segment ends (uniform)
   u32 payload_room;             // words between the start of the payload and the end of the caller's buffer (saturated)
 };
 
@@ -242,18 +214,19 @@ __device__ inline OperandMeta load_operand_tables(const ReduceArgs& a, int s, u3
   const u8* base = a.in[s].base;
   m.seg_off = SegmentOffsetParts{0, 0, 0};
   if (seg_ok) m.seg_off = load_segment_offset(a.index, s, seg, zero);
+  m.seg_end = 0;
   m.payload_room = 0;
   m.w = w_ok ? u32(*at_bytes(base, kHeaderBytes + b)) : 0u;
   return m;
 }
 
-__device__ inline i32 load_operand_outlier(const ReduceArgs& a, int s, const ParsedHeader& h, u32 b, bool active) {
+__device__ inline i32 load_operand_outlier(const ReduceArgs& a, int s, const ParsedHeader& h, u32 b, bool active, bool ix) {
   const u8* base = a.in[s].base;
-  return active ? *reinterpret_cast<const i32*>(at_bytes(base, kHeaderBytes + u32(pad16(h.nb)) + 4u * b)) : 0;
+  return active ? *reinterpret_cast<const i32*>(at_bytes(base, u32(outliers_begin(h.nb, ix)) + 4u * b)) : 0;
 }
 
-__device__ inline u32 payload_room(const ReduceArgs& a, int s, const ParsedHeader& h) {
-  const u64 tend = tables_end(h.nb);
+__device__ inline u32 payload_room(const ReduceArgs& a, int s, const ParsedHeader& h, bool ix) {
+  const u64 tend = tables_end(h.nb, ix);
   const u64 room = a.in[s].bytes > tend ? (a.in[s].bytes - tend) / 4 : 0;
   return room > 0xffffffffull ? 0xffffffffu : u32(room);   // a stream's payload has at most 2^31 words
 }
@@ -261,24 +234,44 @@ __device__ inline u32 payload_room(const ReduceArgs& a, int s, const ParsedHeade
 // The payload is fenced in by the size of the caller's buffer, which a validated stream does
 // not exceed (a 16-byte load may run up to 12 bytes past the stream's own end, inside the
 // buffer; nothing reads those words).
+// An indexed stream (ix) has the segment's position in its own index, and its width bytes
+// behind that index (every stream of a validated call has the header's nb).
 __device__ inline OperandMeta load_operand_meta(const ReduceArgs& a, int s, const ParsedHeader& h, u32 seg, u32 b,
-                                                bool active, bool seg_live) {
-  OperandMeta m = load_operand_tables(a, s, seg, b, active, seg_live);
-  m.payload_room = payload_room(a, s, h);
+                                                bool active, bool seg_live, bool ix) {
+  OperandMeta m;
+  if (ix) {
+    const u8* base = a.in[s].base;
+    m.seg_off = SegmentOffsetParts{0, 0, 0};
+    m.seg_end = 0;
+    if (seg_live) {
+      m.seg_off = load_segment_offset(a.index, s, seg, 0, base);
+      m.seg_end = load_segment_end(base, seg);
+    }
+    m.w = active ? u32(*at_bytes(base, u32(widths_begin(h.nb, true)) + b)) : 0u;
+  } else {
+    m = load_operand_tables(a, s, seg, b, active, seg_live);
+  }
+  m.payload_room = payload_room(a, s, h, ix);
   return m;
 }
 
-__device__ inline OperandPlace place_operand(const OperandMeta& m, const ParsedHeader& h) {
+// `err`: an indexed stream is checked as it is used: the widths of the segment must add up to
+// what the index says, and a stream that promised narrow blocks must have no other.
+__device__ inline OperandPlace place_operand(const OperandMeta& m, const ParsedHeader& h, bool ix, u32& err) {
   OperandPlace p;
   // the same in every lane, and long since loaded: into scalar registers, 32-bit arithmetic
-  const u64 seg_off64 = uniform64(segment_offset(m.seg_off));
+  const u64 seg_off64 = ix ? u64(uniform(m.seg_off.seg)) : uniform64(segment_offset(m.seg_off));
   const u32 seg_off = u32(seg_off64);
-  const u32 w = m.w > 15 ? 0u : m.w;           // cannot happen here; keeps every LDS access in range
+  const u32 w = m.w > 15 ? 0u : m.w;           // plain streams: cannot happen here; keeps every LDS access in range
   const u32 words = psize_words(w);
   const u32 incl = wave_inclusive_sum(words);
   const u32 wave_total = lane_value(incl, 63);
   // true on a validated stream
-  const bool inside = (seg_off64 >> 32) == 0 && seg_off <= m.payload_room && wave_total <= m.payload_room - seg_off;
+  bool inside = (seg_off64 >> 32) == 0 && seg_off <= m.payload_room && wave_total <= m.payload_room - seg_off;
+  if (ix && (__any(m.w > 15) || uniform(m.seg_end) - seg_off != wave_total)) {
+    err |= status_bit(ZC_ERR_FORMAT);
+    inside = false;
+  }
   const u32 mis = seg_off & 3u;
   p.src0 = seg_off - mis;
   p.room = m.payload_room - p.src0;
@@ -428,6 +421,7 @@ __device__ inline int fresh_lane() {
   return lane;
 }
 
+template <bool IX>
 __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWholeStage];   // also holds an operand's payload
   __shared__ u32 sh_tile;
@@ -438,8 +432,9 @@ __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
 
   // A workgroup that takes the tile of its own number asks for the first operand's tables
   // together with the control block and the header, before it knows the header: one memory
-  // round trip instead of two.  The loads are fenced in by sizes the host passed.
-  const bool early = !a.ticketed;
+  // round trip instead of two.  The loads are fenced in by sizes the host passed.  (Not for
+  // indexed streams: where their width bytes are is only known with the header.)
+  const bool early = !IX && !a.ticketed;
   const u32 zero = opaque_zero();
   OperandMeta meta;
   if (early) {
@@ -449,11 +444,11 @@ __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
   }
   const uint2 gate = load_gate(a.ctl, zero);
   const HeaderWords hw = load_header_words(a.in[0].base, zero);
-  const ParsedHeader h = parse_header(hw, a.in[0].bytes);
+  const ParsedHeader h = parse_header(hw, a.in[0].bytes, IX);
   if (gate_failed(gate) || gate_wide(gate) || !h.ok) return;
-  const u64 tend = tables_end(h.nb);
+  const u64 tend = tables_end(h.nb, IX);
   const u32 ntiles = u32(num_tiles(h.nb));
-  if (blockIdx.x == 0 && threadIdx.x == 0) write_reduce_header(a, h, ntiles);
+  if (blockIdx.x == 0 && threadIdx.x == 0) write_reduce_header(a, h, ntiles, IX);
   if (ntiles == 0) return;
 
   u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
@@ -470,6 +465,7 @@ __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
   OperandPlace next;
   OperandStage stage;
   i32 outlier_next;        // the outlier of the operand in `stage`: travels with the payload
+  u32 err = 0;             // uniform
   {
     const int lane = fresh_lane();
     const u32 b = seg * kWaveBlocks + u32(lane);
@@ -477,14 +473,14 @@ __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
     if (early) {
       if (!active) meta.w = 0;
       if (!seg_live) meta.seg_off = SegmentOffsetParts{0, 0, 0};
-      meta.payload_room = payload_room(a, 0, h);
+      meta.payload_room = payload_room(a, 0, h, IX);
     } else {
-      meta = load_operand_meta(a, 0, h, seg, b, active, seg_live);
+      meta = load_operand_meta(a, 0, h, seg, b, active, seg_live, IX);
     }
-    next = place_operand(meta, h);
-    if (a.k > 1) meta = load_operand_meta(a, 1, h, seg, b, active, seg_live);
+    next = place_operand(meta, h, IX, err);
+    if (a.k > 1) meta = load_operand_meta(a, 1, h, seg, b, active, seg_live, IX);
     stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[0].base + tend), next, lane);
-    outlier_next = load_operand_outlier(a, 0, h, b, active);
+    outlier_next = load_operand_outlier(a, 0, h, b, active, IX);
   }
 
   // ---- add the k operands' blocks in plane form; loads run ahead of the adds ----
@@ -503,10 +499,10 @@ __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
     wave_lds_sync();
     outlier += i64(outlier_next);
     if (s + 1 < a.k) {
-      next = place_operand(meta, h);
-      if (s + 2 < a.k) meta = load_operand_meta(a, s + 2, h, seg, b, active, seg_live);
+      next = place_operand(meta, h, IX, err);
+      if (s + 2 < a.k) meta = load_operand_meta(a, s + 2, h, seg, b, active, seg_live, IX);
       stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[s + 1].base + tend), next, lane);
-      outlier_next = load_operand_outlier(a, s + 1, h, b, active);
+      outlier_next = load_operand_outlier(a, s + 1, h, b, active, IX);
     }
     if (cur.wcap) {
       bound += (1u << cur.wcap) - 1u;
@@ -534,8 +530,9 @@ __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
   };
   const int lane = fresh_lane();
   const u32 b = seg * kWaveBlocks + u32(lane);
+  if (IX && err && lane == 0) atomicOr(&a.ctl->status, err);
   place_sum_staged<kSumPlanes>(a, h, acc, sgn, w, outlier, b < h.nb, b, tile, ntiles, word, wl, sh_wave_total, &sh_base,
-                               wave, lane);
+                               wave, lane, IX);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -585,6 +582,7 @@ __device__ inline void magnitude_planes(u32 (&acc)[kAccPlanes], u32 s, u32 carry
   }
 }
 
+template <bool IX>
 __global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
   __shared__ u32 sh_tile;
@@ -592,11 +590,11 @@ __global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a)
   __shared__ u64 sh_base;
 
   if (validation_failed(a.ctl) || !streams_are_wide(a.ctl)) return;
-  const ParsedHeader h = parse_header(a.in[0]);
+  const ParsedHeader h = parse_header(a.in[0], IX);
   if (!h.ok) return;
-  const u64 tend = tables_end(h.nb);
+  const u64 tend = tables_end(h.nb, IX);
   const u32 ntiles = u32(num_tiles(h.nb));
-  if (blockIdx.x == 0 && threadIdx.x == 0) write_reduce_header(a, h, ntiles);
+  if (blockIdx.x == 0 && threadIdx.x == 0) write_reduce_header(a, h, ntiles, IX);
   if (ntiles == 0) return;
 
   const int lane = lane_id();
@@ -625,14 +623,27 @@ __global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a)
     const u8* base = a.in[s].base;
     const u64 total_s = reinterpret_cast<const u64*>(base)[3];
     const u64 pw = (total_s - tend) / 4;
-    u32 w = active ? u32(base[kHeaderBytes + b]) : 0u;
+    u32 w = active ? u32(base[widths_begin(h.nb, IX) + b]) : 0u;
+    const bool bad_w = w > 31;                    // plain streams: cannot happen on a validated stream
+    if (bad_w) w = 0;
     const u32 words = psize_words(w);
     const u32 incl = wave_inclusive_sum(words);
     u64 off = 0;
-    if (seg_live) off = segment_offset(a.index, s, seg) + (incl - words);
+    if (IX) {
+      // the segment's place by the stream's own index, which must agree with the widths
+      const u32* index = reinterpret_cast<const u32*>(base + kHeaderBytes);
+      const u32 seg_off = seg_live ? index[seg] : 0u, seg_end = seg_live ? index[seg + 1] : 0u;
+      if (seg_end - seg_off != lane_value(incl, 63) || __any(bad_w) || (!parse_header(a.in[s], true).wide && __any(w > 15))) {
+        if (lane == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
+        w = 0;
+      }
+      off = u64(seg_off) + (incl - words);
+    } else if (seg_live) {
+      off = segment_offset(a.index, s, seg) + (incl - words);
+    }
     if (off + words > pw) w = 0;                  // cannot happen on a validated stream
     const u32 wmax = wave_max_u32(w);
-    if (active) outlier += i64(reinterpret_cast<const i32*>(base + kHeaderBytes + pad16(h.nb))[b]);
+    if (active) outlier += i64(reinterpret_cast<const i32*>(base + outliers_begin(h.nb, IX))[b]);
     if (wmax == 0) continue;
     const u32* src = reinterpret_cast<const u32*>(base + tend) + off;
     u32 pl[31];
@@ -656,7 +667,7 @@ __global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a)
     if constexpr (I == 0) return ext;
     else return acc[I - 1];
   };
-  place_sum<32>(a, h, acc, ext, w, outlier, active, b, tile, ntiles, word, wl, sh_wave_total, &sh_base, wave, lane);
+  place_sum<32>(a, h, acc, ext, w, outlier, active, b, tile, ntiles, word, wl, sh_wave_total, &sh_base, wave, lane, IX);
 }
 
 }  // namespace zc

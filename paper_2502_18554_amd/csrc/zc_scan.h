@@ -1,7 +1,10 @@
 // Block positions of an existing stream: header validation and the exclusive prefix sum of
 // the block sizes implied by its width table (Section 3.3 stores one code length per block;
 // a block's position is the sum of the sizes before it), kept per segment of 64 blocks, the
-// share of one wave.
+// share of one wave.  An indexed stream (Section 3.5.2) brings these positions along:
+// stream_index_kernel is not run for it, index_prep_kernel checks what can be checked in one
+// place (header, first and closing entry), and every wave of a consumer checks that its own
+// segment's entries agree with its width bytes, which together is the whole index.
 //
 // stream_index_kernel records the offset of every segment inside its scan group, of every
 // group inside its index span and the size of every span, and validates header and width
@@ -23,38 +26,41 @@ struct ParsedHeader {
   u64 n, nb, total;
   u32 eb_bits, nsum;
   bool ok;
+  bool wide;        // an indexed stream that may hold blocks wider than 15 bits
 };
 
 // Field checks that need nothing but the 32 header bytes and the buffer size.
-__device__ inline ParsedHeader parse_header_words(const u32 (&w)[8], u64 bytes) {
+__device__ inline ParsedHeader parse_header_words(const u32 (&w)[8], u64 bytes, bool ix) {
   ParsedHeader h;
   h.ok = false;
+  h.wide = false;
   h.nb = 0;
   h.n = u64(w[2]) | (u64(w[3]) << 32);
   h.eb_bits = w[4];
   h.nsum = w[5];
   h.total = u64(w[6]) | (u64(w[7]) << 32);
   if (bytes < kHeaderBytes) return h;
-  if (w[0] != kMagic || w[1] != (1u | (5u << 16) | (6u << 24))) return h;
+  if (w[0] != kMagic || (ix ? (w[1] | 1u) != (kVersionIndexed | 1u) : w[1] != kVersionPlain)) return h;
+  h.wide = ix && (w[1] & 1u) != 0;
   if (h.n > ZC_MAX_N) return h;
   // abs_eb must be a finite binary32 >= 2^-96: sign 0, biased exponent in [31, 254]
   const u32 e = h.eb_bits >> 23;
   if (e < 31 || e > 254) return h;
   if (h.nsum < 1) return h;
   h.nb = num_blocks(h.n);
-  if (h.total > bytes || h.total < tables_end(h.nb)) return h;
+  if (h.total > bytes || h.total < tables_end(h.nb, ix)) return h;
   h.ok = true;
   return h;
 }
 
-__device__ inline ParsedHeader parse_header(const StreamRef& s) {
+__device__ inline ParsedHeader parse_header(const StreamRef& s, bool ix) {
   u32 w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (s.bytes >= kHeaderBytes) {
     const u32* src = reinterpret_cast<const u32*>(s.base);
 #pragma unroll
     for (int i = 0; i < 8; ++i) w[i] = src[i];
   }
-  return parse_header_words(w, s.bytes);
+  return parse_header_words(w, s.bytes, ix);
 }
 
 // The same for a main kernel's first instructions: the header (and with load_gate the control
@@ -72,10 +78,10 @@ __device__ inline HeaderWords load_header_words(const u8* base, u32 zero) {
   return hw;
 }
 
-__device__ inline ParsedHeader parse_header(const HeaderWords& hw, u64 bytes) {
+__device__ inline ParsedHeader parse_header(const HeaderWords& hw, u64 bytes, bool ix) {
   const u32 w[8] = {uniform(hw.lo.x), uniform(hw.lo.y), uniform(hw.lo.z), uniform(hw.lo.w),
                     uniform(hw.hi.x), uniform(hw.hi.y), uniform(hw.hi.z), uniform(hw.hi.w)};
-  return parse_header_words(w, bytes);
+  return parse_header_words(w, bytes, ix);
 }
 
 // status and flags of the control block (final before a main kernel starts).
@@ -94,6 +100,7 @@ struct ScanArgs {
   Control* ctl;
   u64* desc;         // look-back descriptors to clear for the kernel that follows (may be null)
   u32 ndesc;
+  u32 ix;            // the streams are indexed: stream_index_kernel has not run
 };
 
 constexpr u32 kSpanBadWidth = 1u;   // per-span flags left by stream_index_kernel: a width byte above 31
@@ -114,8 +121,16 @@ struct SegmentOffsetParts {
 };
 
 // `zero`: 0, or opaque_zero() to have vector loads whatever the compiler knows about seg.
-__device__ inline SegmentOffsetParts load_segment_offset(const StreamIndex& ix, int s, u64 seg, u32 zero = 0) {
+// An indexed stream has the sum in its own index (`base`: the stream): one load.
+__device__ inline SegmentOffsetParts load_segment_offset(const StreamIndex& ix, int s, u64 seg, u32 zero = 0,
+                                                         const u8* base = nullptr) {
   SegmentOffsetParts p;
+  if (base) {
+    p.span = 0;
+    p.grp = 0;
+    p.seg = *reinterpret_cast<const u32*>(at_bytes(base, kHeaderBytes + 4u * u32(seg) + zero));
+    return p;
+  }
   p.span = ix.span_off[u64(s) * ix.spans_cap + seg / kSpanSegs + zero];
   p.grp = ix.grp_off[u64(s) * ix.groups_cap + seg / kScanGroupSegs + zero];
   p.seg = ix.seg_off[u64(s) * 4 * ix.tiles_cap + seg + zero];
@@ -131,6 +146,11 @@ __device__ inline u64 segment_offset(SegmentOffsetParts p) {
 
 __device__ inline u64 segment_offset(const StreamIndex& ix, int s, u64 seg) {
   return segment_offset(load_segment_offset(ix, s, seg));
+}
+
+// The entry after a segment's own in the index of an indexed stream: where the segment ends.
+__device__ inline u32 load_segment_end(const u8* base, u32 seg, u32 zero = 0) {
+  return *reinterpret_cast<const u32*>(at_bytes(base, kHeaderBytes + 4u + 4u * seg + zero));
 }
 
 // Payload words of the four blocks whose width bytes are packed in x, and whether any byte
@@ -151,7 +171,7 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
   __shared__ u32 sh_flags;
   const int s = blockIdx.y;
   const StreamRef st = a.streams[s];
-  const ParsedHeader h = parse_header(st);
+  const ParsedHeader h = parse_header(st, false);
   if (!h.ok || !stream_fits(h, a.index)) return;        // index_prep_kernel reports both
   const u64 ngroups = num_scan_groups(h.nb);
   const u64 group0 = u64(blockIdx.x) * kIndexGroups;
@@ -233,9 +253,9 @@ __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
   u32 status = 0, wide = 0;
   ParsedHeader h0;
   h0.ok = false;
-  if (a.check_match) h0 = parse_header(a.streams[0]);
+  if (a.check_match) h0 = parse_header(a.streams[0], a.ix);
   for (int s = wave; s < a.k; s += 4) {
-    const ParsedHeader h = parse_header(a.streams[s]);
+    const ParsedHeader h = parse_header(a.streams[s], a.ix);
     if (!h.ok) {
       status |= status_bit(ZC_ERR_FORMAT);
       continue;
@@ -245,6 +265,14 @@ __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
       continue;
     }
     if (a.check_match && h0.ok && (h0.n != h.n || h0.eb_bits != h.eb_bits)) status |= status_bit(ZC_ERR_MISMATCH);
+    if (a.ix) {
+      // the two ends of the stream's own index; the waves that use a segment check the rest
+      const u32* index = reinterpret_cast<const u32*>(a.streams[s].base + kHeaderBytes);
+      const u64 nseg = num_segments(h.nb);
+      if (index[0] != 0 || tables_end(h.nb, true) + 4 * u64(index[nseg]) != h.total) status |= status_bit(ZC_ERR_FORMAT);
+      if (h.wide) wide = kFlagWide;
+      continue;
+    }
     const u64 nspans = num_spans(h.nb);
     u32* spans = a.index.span_off + u64(s) * a.index.spans_cap;
     const u32* flags = a.index.span_flags + u64(s) * a.index.spans_cap;
@@ -260,7 +288,7 @@ __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
     }
     if (__any((seen & kSpanBadWidth) != 0)) status |= status_bit(ZC_ERR_FORMAT);
     if (__any((seen & kSpanWide) != 0)) wide = kFlagWide;
-    if (tables_end(h.nb) + 4 * carry != h.total) status |= status_bit(ZC_ERR_FORMAT);
+    if (tables_end(h.nb, false) + 4 * carry != h.total) status |= status_bit(ZC_ERR_FORMAT);
   }
   if (lane == 0) {
     sh_status[wave] = status;

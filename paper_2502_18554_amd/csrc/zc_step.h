@@ -42,31 +42,16 @@ constexpr int kStepStage = kWaveBlocks * kStageRow;     // 64 rows of 36 words =
 static_assert(kStepStage >= kWaveStage, "the payload staging of the decoder must fit too");
 
 // Header fields and table padding of the output stream; one thread.
-__device__ inline void write_step_header(const StepArgs& a, const ParsedHeader& h, u32 ntiles) {
-  const u64 tend = tables_end(h.nb);
+__device__ inline void write_step_header(const StepArgs& a, const ParsedHeader& h, u32 ntiles, bool ix) {
+  const u64 tend = tables_end(h.nb, ix);
   const u64 nsum = u64(h.nsum) + 1;
   if (nsum > 0xffffffffull) atomicOr(&a.ctl->status, status_bit(ZC_ERR_RANGE));
-  if (a.out_cap >= tend) {
-    u32* hw = reinterpret_cast<u32*>(a.out);
-    hw[0] = kMagic;
-    hw[1] = 1u | (5u << 16) | (6u << 24);
-    hw[2] = u32(h.n);
-    hw[3] = u32(h.n >> 32);
-    hw[4] = h.eb_bits;
-    hw[5] = u32(nsum);
-    if (ntiles == 0) {
-      hw[6] = u32(tend);
-      hw[7] = u32(tend >> 32);
-    }
-    for (u64 i = h.nb; i < pad16(h.nb); ++i) a.out[kHeaderBytes + i] = 0;
-    u8* ot = a.out + kHeaderBytes + pad16(h.nb);
-    for (u64 i = 4 * h.nb; i < pad16(4 * h.nb); ++i) ot[i] = 0;
-  } else {
-    atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
-  }
+  if (a.out_cap >= tend) write_stream_header(a.out, h.n, h.nb, h.eb_bits, u32(nsum), ix, ntiles == 0);
+  else atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
   if (ntiles == 0) a.ctl->result = tend;
 }
 
+template <bool IX>
 __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kStepStage];
   __shared__ u32 sh_tile;
@@ -86,7 +71,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
   const HeaderWords hw = load_header_words(a.in.base, zero);
   float4 x[8];
   SegmentOffsetParts seg_parts{0, 0, 0};
-  u32 w = 0;
+  u32 w = 0, seg_end = 0;
   if (early) {
     const u32 seg = blockIdx.x * kTileWaves + u32(wave);
     const u32 b = seg * kWaveBlocks + u32(lane);
@@ -104,19 +89,26 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
         x[i].w = idx + 3 < a.n_local ? a.local[idx + 3] : 0.0f;
       }
     }
-    if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, 0, seg, zero);
-    if (u64(kHeaderBytes) + b < a.in.bytes) w = u32(*at_bytes(a.in.base, kHeaderBytes + b));
+    if (IX) {                 // the width bytes sit behind the index, whose size the header tells
+      if (u64(kHeaderBytes) + 4 * u64(seg) + 8 <= a.in.bytes) {
+        seg_parts = load_segment_offset(a.index, 0, seg, zero, a.in.base);
+        seg_end = load_segment_end(a.in.base, seg, zero);
+      }
+    } else {
+      if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, 0, seg, zero);
+      if (u64(kHeaderBytes) + b < a.in.bytes) w = u32(*at_bytes(a.in.base, kHeaderBytes + b));
+    }
   }
 
-  const ParsedHeader h = parse_header(hw, a.in.bytes);
+  const ParsedHeader h = parse_header(hw, a.in.bytes, IX);
   if (gate_failed(gate) || !h.ok) return;
   if (a.n_local != h.n) {
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_MISMATCH));
     return;
   }
-  const u64 tend = tables_end(h.nb);
+  const u64 tend = tables_end(h.nb, IX);
   const u32 ntiles = u32(num_tiles(h.nb));
-  if (blockIdx.x == 0 && threadIdx.x == 0) write_step_header(a, h, ntiles);
+  if (blockIdx.x == 0 && threadIdx.x == 0) write_step_header(a, h, ntiles, IX);
   if (ntiles == 0) return;
 
   u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
@@ -146,18 +138,31 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
         x[i].w = idx + 3 < h.n ? a.local[idx + 3] : 0.0f;
       }
     }
-    if (seg_live) seg_parts = load_segment_offset(a.index, 0, seg);
-    w = active ? u32(*at_bytes(a.in.base, kHeaderBytes + b)) : 0u;
+    if (IX) {
+      if (seg_live) {
+        seg_parts = load_segment_offset(a.index, 0, seg, 0, a.in.base);
+        seg_end = load_segment_end(a.in.base, seg);
+      }
+    } else {
+      if (seg_live) seg_parts = load_segment_offset(a.index, 0, seg);
+      w = active ? u32(*at_bytes(a.in.base, kHeaderBytes + b)) : 0u;
+    }
   }
+  if (IX && active) w = u32(*at_bytes(a.in.base, u32(widths_begin(h.nb, true)) + b));
   if (!active) w = 0;
-  if (!seg_live) seg_parts = SegmentOffsetParts{0, 0, 0};
-  u32 cur = active ? u32(reinterpret_cast<const i32*>(a.in.base + kHeaderBytes + pad16(h.nb))[b]) : 0u;
+  if (!seg_live) {
+    seg_parts = SegmentOffsetParts{0, 0, 0};
+    seg_end = 0;
+  }
+  u32 cur = active ? u32(reinterpret_cast<const i32*>(a.in.base + outliers_begin(h.nb, IX))[b]) : 0u;
 
   // ---- the received block's sign and plane words; then the local values, one block per row
   //      of the same LDS area; then the received block's deltas ----
   u32 lo[16], hi[16];
-  const u32 wmax_in = wave_block_words(reinterpret_cast<const u32*>(a.in.base + tend), (h.total - tend) / 4, w,
-                                       segment_offset(seg_parts), wl, lane, lo, hi);
+  u32 err = 0;
+  const u64 seg_off = IX ? u64(uniform(seg_parts.seg)) : segment_offset(seg_parts);
+  const u32 wmax_in = wave_block_words(reinterpret_cast<const u32*>(a.in.base + tend), (h.total - tend) / 4, w, seg_off,
+                                       wl, lane, lo, hi, IX, uniform(seg_end) - u32(seg_off), h.wide, err);
 #pragma unroll
   for (int i = 0; i < 8; ++i) *reinterpret_cast<float4*>(wl + (8 * i + (lane >> 3)) * kStageRow + 4 * (lane & 7)) = x[i];
   wave_lds_sync();
@@ -171,7 +176,6 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
   qa.inv = 1.0 / qa.step;
   qa.eb = double(eb);
   qa.screen = eb * 131072.0f;
-  u32 err = 0;
   const u64 cnt64 = active ? h.n - u64(b) * kBlockValues : 0;      // values of this block that exist
   const u32 cnt = cnt64 < 32 ? u32(cnt64) : 32u;
   // first the sums (in place of the deltas) and their largest magnitude: a NaN or an infinity
@@ -226,28 +230,23 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
   pl.w = (active && any) ? 32u - u32(__builtin_clz(any)) : 0u;
   pl.wmax = wave_max_u32(pl.w);
   if (active && a.out_cap >= tend) {
-    a.out[kHeaderBytes + b] = u8(pl.w);
-    reinterpret_cast<i32*>(a.out + kHeaderBytes + pad16(h.nb))[b] = outlier;
+    a.out[widths_begin(h.nb, IX) + b] = u8(pl.w);
+    reinterpret_cast<i32*>(a.out + outliers_begin(h.nb, IX))[b] = outlier;
   }
   const u32 words = psize_words(pl.w);
   const u32 incl = wave_inclusive_sum(words);
   pl.wave_total = lane_value(incl, 63);
   pl.half0_total = lane_value(incl, 31);
   pl.off_in_wave = incl - words;
-  if (lane == 0) sh_wave_total[wave] = pl.wave_total;
+  if (lane == 0) sh_wave_total[wave] = pl.wave_total | (IX && pl.wmax > 15 ? kWaveWideMark : 0u);
   lds_barrier();                // the wave totals; the stores above stay in flight
-  pl.wave_off = 0;
-  pl.tile_total = 0;
-#pragma unroll
-  for (int i = 0; i < kTileWaves; ++i) {
-    const u32 t = sh_wave_total[i];
-    if (i < wave) pl.wave_off += t;
-    pl.tile_total += t;
-  }
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc};
-  if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total);
+  sum_wave_totals(sh_wave_total, wave, IX, pl);
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX};
+  if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) atomicOr(&a.ctl->status, err);
-  const u64 base = resolve_tile_base(sink, pl, tile, &sh_base, wave, lane);
+  const TileBase tb = resolve_tile_base(sink, pl, tile, &sh_base, wave, lane);
+  const u64 base = tb.words;
+  if (lane == 0) write_index_entry(sink, seg, base + pl.wave_off);
 
   // ---- deltas -> sign + plane words, out through LDS ----
   if (pl.wmax <= 15) {           // per wave: each wave copies its own words
@@ -268,7 +267,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
       else return hi[I - 17];
     }, pl, base, wl, lane);
   }
-  finish_stream(sink, pl, tile, ntiles, base);
+  finish_stream(sink, pl, tile, ntiles, tb);
 }
 
 }  // namespace zc

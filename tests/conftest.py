@@ -18,3 +18,12 @@ def zcref():
     from oracle import zcref as z
     z.lib()
     return z
+
+
+@pytest.fixture(params=["plain", "indexed"])
+def stream_variant(request, zcref):
+    """Runs a GPU test once per stream variant, with the library and the reference set alike."""
+    import gpuutil
+    gpuutil.set_variant(zcref, request.param == "indexed")
+    yield request.param
+    gpuutil.set_variant(zcref, False)

@@ -7,6 +7,37 @@ import paper_2502_18554_amd as zc
 
 DEV = "cuda:0"
 
+INDEXED = False          # the stream variant the library and the reference are set to
+
+
+def set_variant(zcref, indexed):
+    """Both codecs write and accept plain (False) or indexed (True) streams from here on."""
+    global INDEXED
+    INDEXED = bool(indexed)
+    zc.zc_set_indexed_streams(INDEXED)
+    if zcref is not None:
+        zcref.set_indexed(INDEXED)
+
+
+def pad16(v):
+    return (v + 15) // 16 * 16
+
+
+def index_bytes(nb):
+    return pad16(4 * ((nb + 63) // 64 + 1)) if INDEXED else 0
+
+
+def widths_begin(nb):
+    return 32 + index_bytes(nb)
+
+
+def tables_end(nb):
+    return widths_begin(nb) + pad16(nb) + pad16(4 * nb)
+
+
+def widths_of(s, nb):
+    return s[widths_begin(nb):widths_begin(nb) + nb]
+
 
 def to_dev(x):
     if isinstance(x, np.ndarray):

@@ -19,7 +19,7 @@ import paper_2502_18554_amd as zc
 from paper_2502_18554_amd import synth
 from paper_2502_18554_amd.binding import ZC_OK
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("stream_variant")]
 DEV = "cuda:0"
 
 

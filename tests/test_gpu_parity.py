@@ -10,7 +10,7 @@ from paper_2502_18554_amd import synth
 from paper_2502_18554_amd.binding import (ZC_ERR_ARG, ZC_ERR_BOUND, ZC_ERR_CAPACITY, ZC_ERR_FORMAT,
                                            ZC_ERR_MISMATCH, ZC_ERR_NONFINITE, ZC_ERR_RANGE, ZC_OK)
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("stream_variant")]
 
 TILE = 8192
 
@@ -57,7 +57,7 @@ def test_compress_stream_matches_reference(zcref, name, make, rel):
     assert st == ZC_OK and total == total_ref
     nb = (x.size + 31) // 32
     _, _, w_ref, off_ref = zcref.inspect(s_ref)
-    assert np.array_equal(s[32:32 + nb], w_ref), "widths: " + u.first_diff(s[32:32 + nb], w_ref)
+    assert np.array_equal(u.widths_of(s, nb), w_ref), "widths: " + u.first_diff(u.widths_of(s, nb), w_ref)
     assert s.tobytes() == s_ref.tobytes(), u.first_diff(s, s_ref)
     # stage 3: block offsets recomputed from the stream
     d_off = torch.empty(nb, dtype=torch.int32, device=u.DEV)
@@ -101,12 +101,12 @@ def test_constant_blocks_and_worked_example(zcref):
     x = np.full(3 * TILE + 5, 3.25, np.float32)
     st, s, total = u.gpu_compress(x, 1e-2)
     nb = (x.size + 31) // 32
-    assert st == ZC_OK and total == 32 + (nb + 15) // 16 * 16 + (4 * nb + 15) // 16 * 16
-    assert not s[32:32 + nb].any()
+    assert st == ZC_OK and total == u.tables_end(nb)
+    assert not u.widths_of(s, nb).any()
     assert s.tobytes() == zcref.compress(x, 1e-2)[1].tobytes()
     xw = np.array([10, 11, 13, 12, 12, 12, 9, 10] + [10] * 24, np.float32)
     st, s, total = u.gpu_compress(xw, 0.5)
-    assert total == 76 and s[64:76].tobytes() == bytes.fromhex("48000000CA00000044000000")
+    assert total == u.tables_end(1) + 12 and s[total - 12:total].tobytes() == bytes.fromhex("48000000CA00000044000000")
 
 
 def test_wide_widths_and_bound_status(zcref):
@@ -193,12 +193,13 @@ def test_decompress_error_paths(zcref):
     assert u.gpu_decompress(s[:16], x.size)[0] == ZC_ERR_FORMAT
     assert u.gpu_decompress(s[:-1], x.size)[0] == ZC_ERR_FORMAT == zcref.decompress(s[:-1])[0]
     for pos in (0, 4, 6, 7):
-        t = s.copy(); t[pos] ^= 1
-        assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT
-    t = s.copy(); t[32 + 300] = 32
-    assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT
-    t = s.copy(); t[32 + 300] ^= 1
-    assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT
+        t = s.copy(); t[pos] ^= 4
+        assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT == zcref.decompress(t)[0]
+    w0 = u.widths_begin((x.size + 31) // 32)
+    t = s.copy(); t[w0 + 300] = 32
+    assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT == zcref.decompress(t)[0]
+    t = s.copy(); t[w0 + 300] ^= 1
+    assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT == zcref.decompress(t)[0]
     t = s.copy(); t[20:24] = 0
     assert u.gpu_decompress(t, x.size)[0] == ZC_ERR_FORMAT
     t = s.copy(); t[16:20] = 0
@@ -257,7 +258,7 @@ def test_reduce_wide_and_cancelling_operands(zcref):
     # everything cancels: all widths zero
     st, r, total = u.gpu_reduce([streams[0], streams[5]], n)
     assert st == ZC_OK and r.tobytes() == zcref.reduce([streams[0], streams[5]])[1].tobytes()
-    assert not r[32:32 + (n + 31) // 32].any()
+    assert not u.widths_of(r, (n + 31) // 32).any()
 
 
 @pytest.mark.parametrize("k", [2, 9, 64])
@@ -280,7 +281,7 @@ def test_reduce_narrow_widths_all_classes(zcref, k):
         q[64:96:2] = 2 ** 14 - 1
         q[65:96:2] = -(2 ** 14)
     streams = [zcref.encode_codes(q, 1e-3)[1] for q in qs]
-    assert max(int(s[32:32 + nb].max()) for s in streams) <= 15
+    assert max(int(u.widths_of(s, nb).max()) for s in streams) <= 15
     st_ref, r_ref, total_ref = zcref.reduce(streams)
     st, r, total = u.gpu_reduce(streams, n)
     assert st == st_ref == ZC_OK and total == total_ref
@@ -355,7 +356,7 @@ def test_decompress_many_error_paths(zcref):
     for i in (0, 2):
         assert np.array_equal(outs[i][:n].view(np.uint32), zcref.decompress(streams[i])[1].view(np.uint32))
     assert np.isnan(outs[1]).all()
-    bad = streams[2].copy(); bad[4] ^= 1
+    bad = streams[2].copy(); bad[4] ^= 4
     st, outs, _ = u.gpu_decompress_many([streams[0], bad], [n, n])
     assert st == ZC_ERR_FORMAT and np.isnan(outs[0]).all()
     ws = u.workspace(n, 3)

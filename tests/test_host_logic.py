@@ -40,6 +40,9 @@ def test_size_helpers(libzc):
     for n in (0, 1, 31, 32, 33, 8192, 8193, 1 << 20, (1 << 27) + 5):
         nb = (n + 31) // 32
         assert libzc.zc_compress_bound(n) == 32 + pad16(nb) + pad16(4 * nb) + 128 * nb
+        assert libzc.zc_set_indexed_streams(1) == 0            # the bound follows the stream variant
+        assert libzc.zc_compress_bound(n) == 32 + pad16(4 * ((nb + 63) // 64 + 1)) + pad16(nb) + pad16(4 * nb) + 128 * nb
+        assert libzc.zc_set_indexed_streams(0) == 0
     assert libzc.zc_workspace_bytes(1 << 27, 1) < (1 << 22)      # under 1 % of the 512 MiB it serves
     assert libzc.zc_workspace_bytes(1 << 26, 8) < libzc.zc_workspace_bytes(1 << 27, 8)
     libzc.zc_strerror.restype = C.c_char_p
