@@ -226,14 +226,15 @@ __device__ inline void wide_tile(const CompressArgs& a, const PayloadSink& sink,
       if ((w_a | w_b) == 0) continue;
       const u32 off_a = lane_value(pl.off_in_wave, blk_a), off_b = lane_value(pl.off_in_wave, blk_a + 1);
       const int row = 2 * bp + (lane >> 5);                       // LDS row of this lane's block
-      int jj = j;
+      int jj = j, jp = j ? j - 1 : 0;                             // this value and the one before it
       if (!FULL) {                                                // the last block repeats its last code
         const u64 b = wblock0 + u64(32 * half + row);
         const u64 cnt = b < a.nb ? a.n - b * kBlockValues : 1;
         if (u64(jj) >= cnt) jj = int(cnt) - 1;
+        if (u64(jp) >= cnt) jp = int(cnt) - 1;
       }
       const i32 q = i32(wl[row * kStageRow + jj]);
-      const i32 qp = i32(wl[row * kStageRow + (jj ? jj - 1 : 0)]);
+      const i32 qp = i32(wl[row * kStageRow + jp]);
       const i32 d = j ? q - qp : 0;
       const u32 mag = u32(d < 0 ? -d : d);
       const bool first_lane = j == 0;

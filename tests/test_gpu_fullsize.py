@@ -31,6 +31,23 @@ def tables_end(nb):
     return 32 + pad16(nb) + pad16(4 * nb)
 
 
+INDEXED = False          # the stream variant the library is set to (the reference stays plain)
+
+
+@pytest.fixture(params=["plain", "indexed"], autouse=True)
+def gpu_stream_variant(request):
+    """Every test of this module runs on both stream variants of the library.  The reference
+    compresses slices of the input into plain streams; their tables and payload are compared
+    with the matching parts of the library's stream, whose index is checked against its own
+    width table."""
+    global INDEXED
+    INDEXED = request.param == "indexed"
+    zc.zc_set_indexed_streams(INDEXED)
+    yield request.param
+    INDEXED = False
+    zc.zc_set_indexed_streams(False)
+
+
 def u8(nbytes):
     return torch.empty(nbytes + 64, dtype=torch.uint8, device=DEV)
 
@@ -41,17 +58,21 @@ class Stream:
     def __init__(self, buf, total, n):
         self.buf, self.total, self.n = buf, total, n
         self.nb = (n + 31) // 32
-        self.widths = buf[32:32 + self.nb]
+        self.nseg = (self.nb + 63) // 64
+        w0 = 32 + (pad16(4 * (self.nseg + 1)) if INDEXED else 0)
+        self.index = buf[32:32 + 4 * (self.nseg + 1)].view(torch.int32) if INDEXED else None
+        self.widths = buf[w0:w0 + self.nb]
         words = torch.where(self.widths > 0, self.widths.to(torch.int64) + 1, torch.zeros((), dtype=torch.int64, device=DEV))
         self.off = torch.cumsum(words, 0) - words            # exclusive, in words
         self.payload_words = int(words.sum())
-        o0 = 32 + pad16(self.nb)
+        o0 = w0 + pad16(self.nb)
         self.outliers = buf[o0:o0 + 4 * self.nb].view(torch.int32)
-        self.tend = tables_end(self.nb)
+        self.tend = o0 + pad16(4 * self.nb)
 
     def header(self):
         h = self.buf[:32].cpu().numpy()
-        return dict(magic=int(h[0:4].view("<u4")[0]), n=int(h[8:16].view("<u8")[0]), eb_bits=int(h[16:20].view("<u4")[0]),
+        return dict(magic=int(h[0:4].view("<u4")[0]), version=int(h[4:6].view("<u2")[0]), n=int(h[8:16].view("<u8")[0]),
+                    eb_bits=int(h[16:20].view("<u4")[0]),
                     nsum=int(h[20:24].view("<u4")[0]), total=int(h[24:32].view("<u8")[0]))
 
     def payload_of(self, b0, b1):
@@ -91,6 +112,14 @@ def check_header_and_sizes(s, eb, nsum=1):
     assert h["eb_bits"] == int(np.float32(eb).view(np.uint32))
     assert s.total == s.tend + 4 * s.payload_words
     assert int(s.widths.max()) <= 31
+    if INDEXED:          # the index is the exclusive sum of the block sizes at every 64th block, then the total
+        assert h["version"] == (3 if int(s.widths.max()) > 15 else 2)
+        want = torch.cat([s.off[::64], torch.tensor([s.payload_words], device=DEV)])
+        assert torch.equal(s.index.to(torch.int64) & 0xFFFFFFFF, want), "segment index differs from the width table's sums"
+        pad = s.buf[32 + 4 * (s.nseg + 1):32 + pad16(4 * (s.nseg + 1))]
+        assert not bool(pad.any())
+    else:
+        assert h["version"] == 1
 
 
 def check_slices_against_reference(zcref, x, eb, s, y, rng, count=6):

@@ -607,3 +607,109 @@ def test_kernel_timing_hook(zcref):
     assert [name for name, _ in got] == ["compress", "decompress", "reduce"]
     assert all(0.0 < ms < 100.0 for _, ms in got)
     assert zc.zc_profile_collect() == []
+
+
+# ---------------- the index of indexed streams is checked by the kernels that use it ----------------
+def _all_consumers(u, zcref, bad, good, x):
+    """Status of every call that reads `bad` (a stream of x.size values), GPU and reference side by side."""
+    n = x.size
+    yield "decompress", u.gpu_decompress(bad, n)[0], zcref.decompress(bad)[0]
+    yield "decompress_many", u.gpu_decompress_many([good, bad, good], [n, n, n])[0], zcref.decompress(bad)[0]
+    yield "reduce operand 0", u.gpu_reduce([bad, good], n)[0], zcref.reduce([bad, good])[0]
+    yield "reduce operand 2", u.gpu_reduce([good, good, bad], n)[0], zcref.reduce([good, good, bad])[0]
+    yield "reduce_step", u.gpu_reduce_step(bad, x)[0], zcref.reduce_step(bad, x)[0]
+
+
+def test_indexed_stream_index_is_validated(zcref, stream_variant):
+    if stream_variant != "indexed":
+        pytest.skip("plain streams have no index")
+    u = _u()
+    x = synth.power_law_field((5, 64, 64), seed=120).numpy().ravel()[:5 * 4096 - 37]
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    _, s, total = zcref.compress(x, eb)
+    nseg = ((x.size + 31) // 32 + 63) // 64
+    ix = s[32:32 + 4 * (nseg + 1)].view("<u4")
+    assert nseg == 10 and ix[0] == 0 and np.all(np.diff(ix.astype(np.int64)) > 0)
+    for name, st, st_ref in _all_consumers(u, zcref, s, s, x):
+        assert st == st_ref == ZC_OK, name
+
+    def broken(edit):
+        t = s.copy()
+        edit(t[32:32 + 4 * (nseg + 1)].view("<u4"))
+        return t
+
+    cases = {
+        "first entry": lambda e: e.__setitem__(0, 4),
+        "entry 1 up": lambda e: e.__setitem__(1, e[1] + 1),
+        "entry 5 down": lambda e: e.__setitem__(5, e[5] - 4),
+        "entry 7 far": lambda e: e.__setitem__(7, e[7] ^ 0x80000000),
+        "last segment": lambda e: e.__setitem__(nseg - 1, e[nseg - 1] + 4),
+        "closing entry": lambda e: e.__setitem__(nseg, e[nseg] + 4),
+        "entries 3 and 4 shifted alike": lambda e: (e.__setitem__(3, e[3] + 4), e.__setitem__(4, e[4] + 4)),
+        "all zero": lambda e: e.fill(0),
+    }
+    for what, edit in cases.items():
+        t = broken(edit)
+        for name, st, st_ref in _all_consumers(u, zcref, t, s, x):
+            assert st == st_ref == ZC_ERR_FORMAT, f"{what}: {name}: {st} vs {st_ref}"
+    # width bytes that do not fit the stream's promise
+    nb = (x.size + 31) // 32
+    w0 = u.widths_begin(nb)
+    for pos, val in ((w0 + 70, 16), (w0 + 300, 32), (w0 + nb - 1, 255)):
+        t = s.copy(); t[pos] = val
+        for name, st, st_ref in _all_consumers(u, zcref, t, s, x):
+            assert st == st_ref == ZC_ERR_FORMAT, f"width {val}: {name}: {st} vs {st_ref}"
+
+
+def test_indexed_version_word(zcref, stream_variant):
+    if stream_variant != "indexed":
+        pytest.skip("plain streams are version 1")
+    u = _u()
+    n = 3 * TILE + 11
+    rng = np.random.default_rng(121)
+    q = np.cumsum(rng.integers(-40, 41, n)).astype(np.int32)
+    _, narrow, _ = zcref.encode_codes(q, 1e-3)
+    q2 = q.copy(); q2[2 * TILE + 5] += 1 << 20                   # one block of 21 bits in the last tile
+    _, wide, _ = zcref.encode_codes(q2, 1e-3)
+    assert narrow[4] == 2 and wide[4] == 3
+    x = zcref.decompress(narrow)[1]
+    # the GPU writes the same version words: a stream is wide iff one of its tiles is
+    for qq, ref in ((q, narrow), (q2, wide)):
+        xx = zcref.decompress(ref)[1]
+        st, s, _ = u.gpu_compress(xx, 1e-3)
+        assert st in (ZC_OK, ZC_ERR_BOUND) and s.tobytes() == ref.tobytes(), u.first_diff(s, ref)
+    # "may hold wide blocks" without one is accepted, and what is written says what is in it
+    t = narrow.copy(); t[4] = 3
+    for name, st, st_ref in _all_consumers(u, zcref, t, narrow, x):
+        assert st == st_ref == ZC_OK, name
+    st, r, _ = u.gpu_reduce([t, narrow], n)
+    assert r.tobytes() == zcref.reduce([t, narrow])[1].tobytes() and r[4] == 2
+    st, r, _ = u.gpu_reduce_step(t, x)
+    assert r.tobytes() == zcref.reduce_step(t, x)[1].tobytes()
+    # "no wide block" with one is refused
+    t = wide.copy(); t[4] = 2
+    xw = zcref.decompress(wide)[1]
+    for name, st, st_ref in _all_consumers(u, zcref, t, wide, xw):
+        assert st == st_ref == ZC_ERR_FORMAT, name
+    # a plain stream is refused, and the other way round
+    u.set_variant(zcref, False)
+    _, plain, _ = zcref.encode_codes(q, 1e-3)
+    assert u.gpu_decompress(narrow, n)[0] == ZC_ERR_FORMAT == zcref.decompress(narrow)[0]
+    u.set_variant(zcref, True)
+    assert u.gpu_decompress(plain, n)[0] == ZC_ERR_FORMAT == zcref.decompress(plain)[0]
+    assert u.gpu_reduce([narrow, plain], n)[0] == ZC_ERR_FORMAT == zcref.reduce([narrow, plain])[0]
+
+
+@pytest.mark.parametrize("tail", [1, 11, 31])
+def test_wide_block_in_the_ragged_last_tile(zcref, tail):
+    """The last block's padding repeats its last code, also in a tile that holds a block wider than 15 bits."""
+    u = _u()
+    n = 2 * TILE + 5 * 32 + tail
+    rng = np.random.default_rng(122 + tail)
+    q = np.cumsum(rng.integers(-40, 41, n)).astype(np.int32)
+    q[2 * TILE + 40] += 1 << 20
+    _, ref, _ = zcref.encode_codes(q, 1e-3)
+    x = zcref.decompress(ref)[1]
+    assert zcref.compress(x, 1e-3)[1].tobytes() == ref.tobytes()
+    st, s, _ = u.gpu_compress(x, 1e-3)
+    assert st == zcref.compress(x, 1e-3)[0] and s.tobytes() == ref.tobytes(), u.first_diff(s, ref)
