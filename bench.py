@@ -29,7 +29,8 @@ HBM_PEAK_GBS = 8000.0
 # summarised under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads on a plain
 # copy of the field in the same run).  Counters cannot be read from inside this script, so the figures are
 # carried here and reported only when the run is that workload.
-PROFILED_TRAFFIC = {"compress": 754.9e6, "decompress": 746.8e6, "reduce": 972.1e6}
+PROFILED_TRAFFIC = {"indexed": {"compress": 755.6e6, "decompress": 746.2e6, "reduce": 973.7e6},
+                    "plain": {"compress": 755.0e6, "decompress": 746.6e6, "reduce": 972.0e6}}
 
 
 def parse():
@@ -39,6 +40,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--rel", type=float, default=1e-4, help="value-range-relative error bound of the timed step")
     ap.add_argument("--side", type=int, default=512, help="field side; 512 is the benchmark configuration")
+    ap.add_argument("--streams", choices=("plain", "indexed"), default="indexed",
+                    help="stream variant of every call: indexed streams carry a segment index (zc_set_indexed_streams)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed sweep over the other error bounds")
     ap.add_argument("--copy-probe", action="store_true",
@@ -57,6 +60,8 @@ def main():
     from paper_2502_18554_amd.binding import ZC_OK
 
     zc.binding.lib()                      # fails loudly if the HIP library is missing
+    indexed = args.streams == "indexed"
+    zc.zc_set_indexed_streams(indexed)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     side = args.side
@@ -163,7 +168,7 @@ def main():
             "kernel_ms": round(kernel_ms[s], 4),
             "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": round(gbs / HBM_PEAK_GBS, 4),
-                         "traffic": PROFILED_TRAFFIC[s] if (side == 512 and args.rel == 1e-4) else None},
+                         "traffic": PROFILED_TRAFFIC[args.streams][s] if (side == 512 and args.rel == 1e-4) else None},
             "algorithmic_bytes": alg_bytes[s],
         }
     dominant = max(stage_names, key=lambda s: kernel_ms[s])
@@ -223,6 +228,39 @@ def main():
             check(st, what + " (graph replay)")
         extras["hip_graph"] = {"ms_per_step": round(ms_g, 4), "value_GBps": round(total_fp32 / ms_g / 1e6, 1)}
         del graph
+        # the same step on the other stream variant (plain <-> indexed), inputs compressed anew
+        other = not indexed
+        zc.zc_set_indexed_streams(other)
+        o_stream, o_red = u8(zc.zc_compress_bound(n)), u8(zc.zc_compress_bound(m))
+        o_chunks, o_bytes = [], []
+        for r in range(K):
+            st, total = zc.zc_compress(ranks[r], m, eb_r, o_red, ws_r)
+            check(st, "compress rank (other variant)")
+            o_chunks.append(o_red[:total].clone())
+            o_bytes.append(total)
+        st, oc_bytes = zc.zc_compress(x, n, eb, o_stream, ws_c)
+        check(st, "compress (other variant)")
+
+        def other_step():
+            zc.zc_compress(x, n, eb, o_stream, ws_c, sync=False)
+            zc.zc_decompress(o_stream, oc_bytes, d_y, ws_d, sync=False)
+            zc.zc_reduce_compressed(o_chunks, o_bytes, o_red, ws_r, sync=False)
+
+        for _ in range(args.warmup):
+            other_step()
+        torch.cuda.synchronize()
+        t0o = time.perf_counter()
+        for _ in range(args.steps):
+            other_step()
+        torch.cuda.synchronize()
+        ms_o = (time.perf_counter() - t0o) * 1e3 / args.steps
+        for ws, what in ((ws_c, "compress"), (ws_d, "decompress"), (ws_r, "reduce")):
+            st, _ = zc.zc_finish(ws)
+            check(st, what + " (other variant)")
+        extras["other_stream_variant"] = {"streams": "indexed" if other else "plain", "ms_per_step": round(ms_o, 4),
+                                          "value_GBps": round(total_fp32 / ms_o / 1e6, 1), "compressed_bytes": oc_bytes}
+        zc.zc_set_indexed_streams(indexed)
+        del o_stream, o_red, o_chunks
         # the tail of the compressed Allgather at the shape of the reduce above: the 8 rank streams
         # decompressed by 8 calls and by one call
         outs = [torch.empty(m, dtype=torch.float32, device=dev) for _ in range(K)]
@@ -297,9 +335,14 @@ def main():
         assert st == 0 and st_r == 0
         # the sample is a prefix, blocks are independent: reconstruction and widths must agree bit for bit
         assert np.array_equal(d_y[:ns].cpu().numpy().view(np.uint32), y_ref.view(np.uint32)), "GPU != reference"
+        # (the reference writes plain streams; an indexed stream has its width table behind the index)
+        def widths_at(n_values):
+            nb_all = (n_values + 31) // 32
+            return 32 + ((4 * ((nb_all + 63) // 64 + 1) + 15) // 16 * 16 if indexed else 0)
         nbs = ns // 32
-        assert np.array_equal(d_stream[32:32 + nbs].cpu().numpy(), s_ref[32:32 + nbs]), "widths differ"
-        assert np.array_equal(d_red[32:32 + mr // 32].cpu().numpy(), red_ref[32:32 + mr // 32]), "reduce widths differ"
+        assert np.array_equal(d_stream[widths_at(n):widths_at(n) + nbs].cpu().numpy(), s_ref[32:32 + nbs]), "widths differ"
+        assert np.array_equal(d_red[widths_at(m):widths_at(m) + mr // 32].cpu().numpy(), red_ref[32:32 + mr // 32]), \
+            "reduce widths differ"
         sample_bytes = 4 * ns + 4 * ns + 4 * mr * K
         cpu = {
             "value": round(sample_bytes / (t_c + t_d + t_r) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
@@ -316,7 +359,7 @@ def main():
         "dtype": "f64+u32", "data": "synthetic",
         "config": {"workload": f"{side}^3 fp32 power-law Gaussian field, rel eb {args.rel:g}: compress + decompress; "
                                f"fused reduce of {K} compressed rank buffers of {m} values",
-                   "block": 32, "abs_eb": eb, "compressed_bytes": c_bytes, "ratio": round(4 * n / c_bytes, 3),
+                   "streams": args.streams, "block": 32, "abs_eb": eb, "compressed_bytes": c_bytes, "ratio": round(4 * n / c_bytes, 3),
                    "reduce_in_bytes": sum(chunk_bytes), "reduce_out_bytes": r_bytes},
         "roofline": dict(stages[dominant]["roofline"], kernel=dominant + "_kernel"),
         "stages": stages,

@@ -89,11 +89,13 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
         x[i].w = idx + 3 < a.n_local ? a.local[idx + 3] : 0.0f;
       }
     }
-    if (IX) {                 // the width bytes sit behind the index, whose size the header tells
+    if (IX) {                 // the width bytes sit behind the index, whose size follows from n (= n_local, or the call fails)
       if (u64(kHeaderBytes) + 4 * u64(seg) + 8 <= a.in.bytes) {
         seg_parts = load_segment_offset(a.index, 0, seg, zero, a.in.base);
         seg_end = load_segment_end(a.in.base, seg, zero);
       }
+      const u64 w_at = widths_begin(num_blocks(a.n_local), true) + b;
+      if (w_at < a.in.bytes) w = u32(*at_bytes(a.in.base, u32(w_at)));
     } else {
       if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, 0, seg, zero);
       if (u64(kHeaderBytes) + b < a.in.bytes) w = u32(*at_bytes(a.in.base, kHeaderBytes + b));
@@ -148,7 +150,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
       w = active ? u32(*at_bytes(a.in.base, kHeaderBytes + b)) : 0u;
     }
   }
-  if (IX && active) w = u32(*at_bytes(a.in.base, u32(widths_begin(h.nb, true)) + b));
+  if (IX && !early && active) w = u32(*at_bytes(a.in.base, u32(widths_begin(h.nb, true)) + b));
   if (!active) w = 0;
   if (!seg_live) {
     seg_parts = SegmentOffsetParts{0, 0, 0};
