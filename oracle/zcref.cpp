@@ -374,11 +374,13 @@ int zcref_reduce(const void* const* chunks, const size_t* chunk_bytes, int k,
 // Section 3.2 adds one bounded error per such round).  The received stream is decoded to
 // binary32 values, the local uncompressed values are added in binary32, and the sums are
 // compressed under the stream's own bound.  nsum grows by one.
+// op: 0 Sum, 1 Max, 2 Min (the aggregation functions of Section 3.2; for Max and Min the
+// round keeps the larger, or smaller, of the decoded and the local value).
 // Status precedence: ARG, FORMAT, MISMATCH (n_local differs from the stream's n), NONFINITE,
-// RANGE, CAPACITY, BOUND (measured against the binary32 sums).
-int zcref_reduce_step(const void* in, size_t in_bytes, const float* local, size_t n_local,
-                      void* out, size_t out_cap, size_t* out_bytes) {
-  if (!in || !out) return ERR_ARG;
+// RANGE, CAPACITY, BOUND (measured against the binary32 values that were compressed).
+int zcref_reduce_step_op(const void* in, size_t in_bytes, const float* local, size_t n_local, int op,
+                         void* out, size_t out_cap, size_t* out_bytes) {
+  if (!in || !out || op < 0 || op > 2) return ERR_ARG;
   Parsed ps;
   int st = parse_stream(static_cast<const uint8_t*>(in), in_bytes, &ps);
   if (st != OK) return st;
@@ -391,7 +393,13 @@ int zcref_reduce_step(const void* in, size_t in_bytes, const float* local, size_
   std::vector<int32_t> q(n);
   decode_codes(ps, q.data());
   std::vector<float> y(n);
-  for (size_t i = 0; i < n; ++i) y[i] = dequantize_one(q[i], s) + local[i];
+  for (size_t i = 0; i < n; ++i) {
+    const float a = dequantize_one(q[i], s), b = local[i];
+    if (op == 0) y[i] = a + b;
+    else if (!std::isfinite(b)) y[i] = b;          // a NaN or an infinity is an error whatever the comparison says
+    else if (op == 1) y[i] = a > b ? a : b;
+    else y[i] = a < b ? a : b;
+  }
   st = zcref_quantize(y.data(), n, eb, q.data());
   if (st != OK) return st;
   st = encode_codes(q.data(), n, ps.eb_bits, ps.nsum + 1, static_cast<uint8_t*>(out), out_cap, out_bytes);
@@ -400,6 +408,30 @@ int zcref_reduce_step(const void* in, size_t in_bytes, const float* local, size_
     double err = std::fabs(double(y[i]) - double(dequantize_one(q[i], s)));
     if (!(err <= double(eb))) return ERR_BOUND;
   }
+  return OK;
+}
+
+int zcref_reduce_step(const void* in, size_t in_bytes, const float* local, size_t n_local,
+                      void* out, size_t out_cap, size_t* out_bytes) {
+  return zcref_reduce_step_op(in, in_bytes, local, n_local, 0, out, out_cap, out_bytes);
+}
+
+// The Average aggregation of Section 3.2: a stream that holds the sum of nsum buffers is
+// decoded to that sum divided by nsum.  x' = float((double(q) * s) * r) with r = 1.0 / nsum,
+// one binary64 division for the whole stream.  Status as zcref_decompress.
+int zcref_decompress_average(const void* in, size_t in_bytes, float* out, size_t out_cap_elems, size_t* n_out) {
+  if (!in) return ERR_ARG;
+  Parsed ps;
+  int st = parse_stream(static_cast<const uint8_t*>(in), in_bytes, &ps);
+  if (st != OK) return st;
+  if (n_out) *n_out = size_t(ps.n);
+  if (ps.n > out_cap_elems) return ERR_CAPACITY;
+  if (ps.n && !out) return ERR_ARG;
+  std::vector<int32_t> q(ps.n);
+  decode_codes(ps, q.data());
+  const double s = quant_step(bits_to_float(ps.eb_bits));
+  const double r = 1.0 / double(ps.nsum);
+  for (size_t i = 0; i < ps.n; ++i) out[i] = float((double(q[i]) * s) * r);
   return OK;
 }
 

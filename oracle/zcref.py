@@ -31,6 +31,9 @@ def lib():
                                        C.POINTER(C.c_size_t)]
         L.zcref_inspect.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         L.zcref_quality.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.zcref_decompress_average.argtypes = L.zcref_decompress.argtypes
+        L.zcref_reduce_step_op.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_size_t,
+                                           C.POINTER(C.c_size_t)]
         L.zcref_reduce_step.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                                         C.POINTER(C.c_size_t)]
         L.zcref_reduce.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_size_t), C.c_int, C.c_void_p,
@@ -79,17 +82,18 @@ def compress(x, abs_eb, out_cap=None):
     return st, stream, nbytes.value
 
 
-def decompress(stream, out_cap_elems=None):
-    """Returns (status, float32 array of n values, n reported)."""
+def decompress(stream, out_cap_elems=None, average=False):
+    """Returns (status, float32 array of n values, n reported).  average: the values divided by the stream's nsum."""
     stream = np.ascontiguousarray(stream, dtype=np.uint8)
     n = C.c_size_t(0)
+    fn = lib().zcref_decompress_average if average else lib().zcref_decompress
     if out_cap_elems is None:
-        st = lib().zcref_decompress(_ptr(stream), stream.size, None, 0, C.byref(n))
+        st = fn(_ptr(stream), stream.size, None, 0, C.byref(n))
         if st not in (OK, ERR_CAPACITY):
             return st, np.empty(0, np.float32), 0
         out_cap_elems = n.value
     out = np.empty(max(out_cap_elems, 1), dtype=np.float32)
-    st = lib().zcref_decompress(_ptr(stream), stream.size, _ptr(out), out_cap_elems, C.byref(n))
+    st = fn(_ptr(stream), stream.size, _ptr(out), out_cap_elems, C.byref(n))
     return st, (out[: n.value].copy() if st == OK else out[:0]), n.value
 
 
@@ -126,8 +130,11 @@ def reduce(streams, out_cap=None):
     return st, (out[: nbytes.value].copy() if st == OK else out[:0]), nbytes.value
 
 
-def reduce_step(stream, local, out_cap=None):
-    """One ring round: decompress `stream`, add `local` (binary32), compress again.
+OP_SUM, OP_MAX, OP_MIN = 0, 1, 2
+
+
+def reduce_step(stream, local, out_cap=None, op=OP_SUM):
+    """One ring round: decompress `stream`, combine with `local` (binary32 sum, max or min), compress again.
     Returns (status, stream bytes, total_bytes reported)."""
     stream = np.ascontiguousarray(stream, dtype=np.uint8)
     local = np.ascontiguousarray(local, dtype=np.float32)
@@ -135,7 +142,8 @@ def reduce_step(stream, local, out_cap=None):
         out_cap = compress_bound(local.size)
     out = np.zeros(max(out_cap, 1), dtype=np.uint8)
     nbytes = C.c_size_t(0)
-    st = lib().zcref_reduce_step(_ptr(stream), stream.size, _ptr(local), local.size, _ptr(out), out_cap, C.byref(nbytes))
+    st = lib().zcref_reduce_step_op(_ptr(stream), stream.size, _ptr(local), local.size, int(op), _ptr(out), out_cap,
+                                    C.byref(nbytes))
     return st, (out[: nbytes.value].copy() if st in (OK, ERR_BOUND) else out[:0]), nbytes.value
 
 

@@ -624,3 +624,86 @@ def test_indexed_reduce_and_step_carry_the_same_content(zcref):
         assert st == zcref.OK and stp.tobytes() == _to_indexed(step_plain).tobytes()
     finally:
         zcref.set_indexed(False)
+
+
+# ---------------- P12: Max, Min and Average (the other aggregation functions of Section 3.2) ----------------
+def _ring(zcref, xs, eb, op):
+    st, s, _ = zcref.compress(xs[0], eb)
+    assert st == zcref.OK
+    for x in xs[1:]:
+        st, s, _ = zcref.reduce_step(s, x, op=op)
+        assert st == zcref.OK
+    return s
+
+
+@pytest.mark.parametrize("n_ranks", [2, 3, 8])
+def test_ring_max_min_equal_compressing_the_elementwise_extreme(zcref, n_ranks):
+    """The quantiser is monotone and leaves grid points alone, so Q(max(Q(a), b)) = Q(max(a, b)): a ring
+    of Max rounds gives exactly the stream of numpy's elementwise maximum, whatever the order."""
+    xs = [synth.power_law_field((4, 33, 32), seed=200 + i).numpy().ravel() for i in range(n_ranks)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), 1e-3)
+    for op, extreme in ((zcref.OP_MAX, np.maximum), (zcref.OP_MIN, np.minimum)):
+        got = _ring(zcref, xs, eb, op)
+        want = zcref.compress(extreme.reduce(xs), eb)[1].copy()
+        want[20:24] = np.array([n_ranks], "<u4").view(np.uint8)          # nsum counts the buffers
+        assert got.tobytes() == want.tobytes()
+        again = _ring(zcref, xs[::-1], eb, op)
+        assert again.tobytes() == got.tobytes()
+        err = np.abs(zcref.decompress(got)[1].astype(np.float64) - extreme.reduce(xs))
+        assert err.max() <= eb
+        # Theorem 2's variance (2 - (n + 2) / 2^n) sigma^2 is met: one quantisation, sigma = step / sqrt(12)
+        sigma2 = lm.step(eb) ** 2 / 12
+        assert err.var() + err.mean() ** 2 <= (2 - (n_ranks + 2) / 2 ** n_ranks) * sigma2 * 1.1
+
+
+def test_ring_max_min_by_hand_and_symmetry(zcref):
+    eb = 0.5
+    s_ = lm.step(eb)
+    q = np.array([3, -2, 0, 7] * 16, np.int32)
+    _, s, _ = zcref.encode_codes(q, eb)
+    local = (np.array([2.2, -1.4, 0.2, 9.3] * 16) * s_).astype(np.float32)   # codes 2, -1, 0, 9 after rounding
+    st, r, _ = zcref.reduce_step(s, local, op=zcref.OP_MAX)
+    assert st == zcref.OK and list(zcref.inspect(r)[1][:4]) == [3, -1, 0, 9]
+    st, r, _ = zcref.reduce_step(s, local, op=zcref.OP_MIN)
+    assert st == zcref.OK and list(zcref.inspect(r)[1][:4]) == [2, -2, 0, 7]
+    assert int(r[20:24].view("<u4")[0]) == 2
+    # a local buffer that never wins leaves the codes alone
+    low = np.full(q.size, -100.0, np.float32)
+    st, r, _ = zcref.reduce_step(s, low, op=zcref.OP_MAX)
+    assert np.array_equal(zcref.inspect(r)[1], q)
+    # min(a, b) = -max(-a, -b), and rint is odd
+    x = synth.sinusoids(3000, seed=7).numpy(); loc = synth.sinusoids(3000, seed=8).numpy()
+    _, sx, _ = zcref.compress(x, 1e-3); _, snx, _ = zcref.compress(-x, 1e-3)
+    _, rmin, _ = zcref.reduce_step(sx, loc, op=zcref.OP_MIN)
+    _, rmax, _ = zcref.reduce_step(snx, -loc, op=zcref.OP_MAX)
+    assert np.array_equal(zcref.inspect(rmin)[1], -zcref.inspect(rmax)[1])
+    # errors: a NaN or an infinity in the local buffer, also one that the comparison would drop
+    for op in (zcref.OP_MAX, zcref.OP_MIN):
+        for bad in (np.nan, np.inf, -np.inf):
+            l2 = loc.copy(); l2[1234] = bad
+            assert zcref.reduce_step(sx, l2, op=op)[0] == zcref.ERR_NONFINITE
+    assert zcref.reduce_step(sx, loc, op=3)[0] == zcref.ERR_ARG
+    assert zcref.reduce_step(sx, loc, op=zcref.OP_SUM)[1].tobytes() == zcref.reduce_step(sx, loc)[1].tobytes()
+
+
+@pytest.mark.parametrize("k", [1, 2, 8, 64])
+def test_average_decompress(zcref, k):
+    xs, eb, streams = _rank_streams(zcref, k, (4, 32, 33), 1e-3, seed0=300)
+    st, red, _ = zcref.reduce(streams)
+    assert st == zcref.OK
+    st, avg, n = zcref.decompress(red, average=True)
+    assert st == zcref.OK and n == xs[0].size
+    # the definition, with numpy: codes summed exactly, one multiply by the step, one by 1/k
+    qsum = sum(zcref.inspect(s)[1].astype(np.int64) for s in streams)
+    want = ((qsum.astype(np.float64) * lm.step(eb)) * (1.0 / k)).astype(np.float32)
+    assert np.array_equal(avg, want)
+    if k == 1:
+        assert np.array_equal(avg, zcref.decompress(red)[1])
+    # against the float64 mean of the inputs: within eb, and the RMS error shrinks as sigma / sqrt(k) (Corollary 1)
+    mean = np.mean(np.stack([x.ravel().astype(np.float64) for x in xs]), axis=0)
+    err = avg.astype(np.float64) - mean
+    assert np.abs(err).max() <= eb * (1 + 1e-6)
+    sigma = lm.step(eb) / 12 ** 0.5
+    assert abs(np.sqrt(np.mean(err ** 2)) / (sigma / k ** 0.5) - 1) < 0.1
+    assert zcref.decompress(red, out_cap_elems=n - 1, average=True)[0] == zcref.ERR_CAPACITY
+    assert zcref.decompress(red[:-1], average=True)[0] == zcref.ERR_FORMAT
