@@ -312,6 +312,29 @@ def main():
                                  "ms": round(ms, 4), "kernel_ms": round(sum(kt) / len(kt), 4),
                                  "algorithmic_bytes": alg, "fp32_GBps": round(8 * m / ms / 1e6, 1),
                                  "hbm_frac": round(alg / (sum(kt) / len(kt)) / 1e6 / HBM_PEAK_GBS, 4)}
+        # the other aggregation functions: a Max round at the same shape, and the averaging
+        # decompression of the reduced stream of the step above
+        def timed(fn, reps=10):
+            for _ in range(3):
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        ms_max = timed(lambda: zc.zc_reduce_step_op(chunks[0], chunk_bytes[0], ranks[1], m, zc.binding.ZC_OP_MAX, scratch,
+                                                    ws_r, sync=False))
+        st, _ = zc.zc_finish(ws_r)
+        check(st, "reduce_step_op extra")
+        ms_avg = timed(lambda: zc.zc_decompress_average(d_red, r_bytes, d_y, ws_d, sync=False))
+        st, n_avg = zc.zc_finish(ws_d)
+        check(st, "decompress_average extra")
+        extras["other_ops"] = {"reduce_step_max_ms": round(ms_max, 4),
+                               "decompress_average": {"ms": round(ms_avg, 4), "values": n_avg,
+                                                      "hbm_frac": round((r_bytes + 4 * m) / ms_avg / 1e6 / HBM_PEAK_GBS, 4)}}
 
     # ---------------- reference CPU codec on a bounded sample (same mix as the step) ----------------
     cpu = None

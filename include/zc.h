@@ -85,6 +85,13 @@ int zc_decompress(const void* d_in, size_t in_bytes,
                   float* d_out, size_t out_cap_elems, size_t* n_out,
                   void* d_ws, size_t ws_bytes, void* hip_stream);
 
+/* zc_decompress for the Average aggregation of Section 3.2 (Corollary 1: the error of the
+ * average of n buffers has variance sigma^2 / n): the stream holds the sum of nsum buffers, and
+ * every value is divided by nsum on the way out, x' = (float)(((double)q * s) * r) with
+ * r = 1.0 / nsum (one binary64 division per wave).  Arguments and errors as zc_decompress. */
+int zc_decompress_average(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
+                          void* d_ws, size_t ws_bytes, void* hip_stream);
+
 /* Decompression of k streams in one call: the tail of the compressed Allgather (Section 3.5.1:
  * a rank decompresses all the chunks it has received at the end), one launch instead of k.
  * d_chunks, chunk_bytes, d_outs, out_cap_elems: HOST arrays of k entries (device pointers 16-byte
@@ -120,6 +127,20 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
 int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local,
                    void* d_out, size_t out_cap, size_t* out_bytes,
                    void* d_ws, size_t ws_bytes, void* hip_stream);
+
+/* The same round for the other aggregation functions of Section 3.2.  op: ZC_OP_SUM (what
+ * zc_reduce_step does), ZC_OP_MAX or ZC_OP_MIN: d_out receives the stream of the larger (smaller)
+ * of dequantised(received) and local.  Because the quantiser is monotone and maps its own
+ * grid points to themselves, a ring of such rounds yields exactly the stream of the elementwise
+ * maximum (minimum) of all buffers: the error stays within abs_eb however many rounds there are,
+ * inside Theorem 2's variance.  A NaN or an infinity among the local values is NONFINITE.
+ * Errors as zc_reduce_step, and ARG for an unknown op. */
+#define ZC_OP_SUM 0
+#define ZC_OP_MAX 1
+#define ZC_OP_MIN 2
+int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, int op,
+                      void* d_out, size_t out_cap, size_t* out_bytes,
+                      void* d_ws, size_t ws_bytes, void* hip_stream);
 
 /* Quality of a reconstruction d_test against its original d_ref (n binary32 values each,
  * 16-byte aligned): the sums behind the paper's quality figures (NRMSE in Section 3.3, PSNR

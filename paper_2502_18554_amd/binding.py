@@ -18,7 +18,7 @@ ZC_MAX_K = 64
 
 EXPORTS = [
     "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_decompress_many",
-    "zc_reduce_compressed", "zc_reduce_step", "zc_quality",
+    "zc_reduce_compressed", "zc_reduce_step", "zc_reduce_step_op", "zc_decompress_average", "zc_quality",
     "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
     "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out", "zc_set_indexed_streams",
 ]
@@ -49,6 +49,8 @@ def lib():
         L.zc_decompress.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_compressed.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_step.argtypes = [vp, sz, vp, sz, vp, sz, szp, vp, sz, vp]
+        L.zc_reduce_step_op.argtypes = [vp, sz, vp, sz, C.c_int, vp, sz, szp, vp, sz, vp]
+        L.zc_decompress_average.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
         L.zc_quality.argtypes = [vp, vp, sz, C.POINTER(C.c_double), vp, sz, vp]
         L.zc_decompress_many.argtypes = [C.POINTER(vp), szp, C.c_int, C.POINTER(vp), szp, szp, vp, sz, vp]
         L.zc_finish.argtypes = [vp, szp, vp]
@@ -105,6 +107,15 @@ def zc_decompress(d_in, in_bytes, d_out, d_ws, sync=True, stream=None, out_cap_e
     return st, (n.value if sync else None)
 
 
+def zc_decompress_average(d_in, in_bytes, d_out, d_ws, sync=True, stream=None, out_cap_elems=None):
+    """zc_decompress with every value divided by the stream's nsum.  Returns (status, n)."""
+    n = C.c_size_t(0)
+    cap = (d_out.numel() if d_out is not None else 0) if out_cap_elems is None else out_cap_elems
+    st = lib().zc_decompress_average(_p(d_in), in_bytes, _p(d_out), cap, C.byref(n) if sync else None,
+                                     _p(d_ws), d_ws.numel() * d_ws.element_size(), _stream(stream))
+    return st, (n.value if sync else None)
+
+
 def zc_reduce_compressed(d_chunks, chunk_bytes, d_out, d_ws, sync=True, stream=None, out_cap=None):
     """d_chunks: list of device tensors holding the k operand streams.  Returns (status, total_bytes)."""
     k = len(d_chunks)
@@ -138,6 +149,19 @@ def zc_reduce_step(d_chunk, chunk_bytes, d_local, n_local, d_out, d_ws, sync=Tru
     st = lib().zc_reduce_step(_p(d_chunk), int(chunk_bytes), _p(d_local), int(n_local), _p(d_out), cap,
                               C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
                               _stream(stream))
+    return st, (nbytes.value if sync else None)
+
+
+ZC_OP_SUM, ZC_OP_MAX, ZC_OP_MIN = 0, 1, 2
+
+
+def zc_reduce_step_op(d_chunk, chunk_bytes, d_local, n_local, op, d_out, d_ws, sync=True, stream=None, out_cap=None):
+    """zc_reduce_step for Sum, Max or Min.  Returns (status, total_bytes)."""
+    nbytes = C.c_size_t(0)
+    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
+    st = lib().zc_reduce_step_op(_p(d_chunk), int(chunk_bytes), _p(d_local), int(n_local), int(op), _p(d_out), cap,
+                                 C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
+                                 _stream(stream))
     return st, (nbytes.value if sync else None)
 
 

@@ -221,8 +221,9 @@ int zc_compress(const float* d_in, size_t n, float abs_eb, void* d_out, size_t o
   return finish(d_ws, out_bytes, stream);
 }
 
-int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
-                  void* d_ws, size_t ws_bytes, void* hip_stream) {
+// zc_decompress and zc_decompress_average.
+static int decompress_one(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out, void* d_ws,
+                   size_t ws_bytes, void* hip_stream, bool average) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (!d_in || !d_ws || (out_cap_elems && !d_out)) return ZC_ERR_ARG;
   if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
@@ -252,12 +253,23 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
   da.index = l.index;
   da.ctl = l.ctl;
   KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_DECOMPRESS, stream);
-  hipLaunchKernelGGL(g_indexed ? decompress_kernel<true> : decompress_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), 0,
-                     stream, da);
+  auto kernel = average ? (g_indexed ? decompress_kernel<true, true> : decompress_kernel<false, true>)
+                        : (g_indexed ? decompress_kernel<true, false> : decompress_kernel<false, false>);
+  hipLaunchKernelGGL(kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, da);
   g_timer.end(slot, stream);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!n_out) return ZC_OK;
   return finish(d_ws, n_out, stream);
+}
+
+int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
+                  void* d_ws, size_t ws_bytes, void* hip_stream) {
+  return decompress_one(d_in, in_bytes, d_out, out_cap_elems, n_out, d_ws, ws_bytes, hip_stream, false);
+}
+
+int zc_decompress_average(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
+                          void* d_ws, size_t ws_bytes, void* hip_stream) {
+  return decompress_one(d_in, in_bytes, d_out, out_cap_elems, n_out, d_ws, ws_bytes, hip_stream, true);
 }
 
 int zc_decompress_many(const void* const* d_chunks, const size_t* chunk_bytes, int k, float* const* d_outs,
@@ -365,7 +377,14 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
 
 int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, void* d_out,
                    size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
+  return zc_reduce_step_op(d_chunk, chunk_bytes, d_local, n_local, ZC_OP_SUM, d_out, out_cap, out_bytes, d_ws, ws_bytes,
+                           hip_stream);
+}
+
+int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, int op, void* d_out,
+                      size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (op != ZC_OP_SUM && op != ZC_OP_MAX && op != ZC_OP_MIN) return ZC_ERR_ARG;
   if (!d_chunk || !d_out || !d_ws || (n_local && !d_local) || n_local > ZC_MAX_N) return ZC_ERR_ARG;
   if (!aligned16(d_chunk) || !aligned16(d_local) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
   if (chunk_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
@@ -394,7 +413,11 @@ int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local
   ta.desc = l.desc;
   ta.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
   KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_REDUCE_STEP, stream);
-  hipLaunchKernelGGL(g_indexed ? step_kernel<true> : step_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ta);
+  void (*kernel)(StepArgs) = nullptr;
+  if (op == ZC_OP_SUM) kernel = g_indexed ? step_kernel<true, ZC_OP_SUM> : step_kernel<false, ZC_OP_SUM>;
+  else if (op == ZC_OP_MAX) kernel = g_indexed ? step_kernel<true, ZC_OP_MAX> : step_kernel<false, ZC_OP_MAX>;
+  else kernel = g_indexed ? step_kernel<true, ZC_OP_MIN> : step_kernel<false, ZC_OP_MIN>;
+  hipLaunchKernelGGL(kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ta);
   g_timer.end(slot, stream);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;

@@ -153,8 +153,10 @@ __device__ inline void deltas_from_block_words(u32 wmax, u32 (&lo)[16], u32 (&hi
 // added to the control block's result instead of stored there (several streams per call).
 // `ix`: the stream is indexed; its width bytes then sit behind the index, whose size only
 // the header tells, so they are asked for together with the outlier and the payload.
+// `average`: the values are divided by the stream's nsum (the Average aggregation of Section
+// 3.2 on a stream of sums): x' = float((double(q) * s) * r), r = 1.0 / nsum.
 __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u64 out_cap_elems, const StreamIndex& index,
-                                       int s, Control* ctl, bool counted, u32* lds, bool ix) {
+                                       int s, Control* ctl, bool counted, u32* lds, bool ix, bool average = false) {
   const DecompressArgs a{in, out_values, out_cap_elems, index, ctl};
 
   // Everything that can be asked for before the header is known goes out at once: the control
@@ -217,11 +219,13 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
 
   // ---- Lorenzo chain from the outlier, dequantise ----
   const double step = double(__uint_as_float(h.eb_bits)) * 63.0 / 32.0;
+  const double r = average ? __ddiv_rn(1.0, double(h.nsum)) : 1.0;
   float x[32];
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
     cur += u32(d[j]);
-    x[j] = float(__dmul_rn(double(i32(cur)), step));
+    const double v = __dmul_rn(double(i32(cur)), step);
+    x[j] = float(average ? __dmul_rn(v, r) : v);
   }
 
   // ---- transpose through LDS (two halves of 32 blocks), 16-byte coalesced stores ----
@@ -253,10 +257,10 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
   }
 }
 
-template <bool IX>
+template <bool IX, bool AVERAGE>
 __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
-  decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, false, lds, IX);
+  decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, false, lds, IX, AVERAGE);
 }
 
 // k streams in one launch (the tail of the compressed Allgather, Section 3.5.1: every rank

@@ -51,7 +51,20 @@ __device__ inline void write_step_header(const StepArgs& a, const ParsedHeader& 
   if (ntiles == 0) a.ctl->result = tend;
 }
 
-template <bool IX>
+// OP: what a round does with a decoded value a and the local value b (the aggregation functions
+// of Section 3.2): their binary32 sum, or the larger or the smaller of the two.  A NaN or an
+// infinity in the local buffer is an error whatever a comparison would make of it, so it is passed on.
+template <int OP>
+__device__ inline float combine(float a, float b) {
+  if constexpr (OP == ZC_OP_SUM) {
+    return a + b;
+  } else {
+    const float m = OP == ZC_OP_MAX ? (a > b ? a : b) : (a < b ? a : b);
+    return (__float_as_uint(b) & 0x7fffffffu) >= 0x7f800000u ? b : m;
+  }
+}
+
+template <bool IX, int OP>
 __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kStepStage];
   __shared__ u32 sh_tile;
@@ -191,7 +204,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
     for (int u = 0; u < 4; ++u) {
       const int j = 4 * t + u;
       cur += u32(d[j]);
-      const float y = float(__dmul_rn(double(i32(cur)), qa.step)) + lv[u];
+      const float y = combine<OP>(float(__dmul_rn(double(i32(cur)), qa.step)), lv[u]);
       amax = max(amax, __float_as_uint(y) & 0x7fffffffu);
       d[j] = i32(__float_as_uint(y));
     }

@@ -63,13 +63,14 @@ def gpu_compress(x, eb, out_cap=None, ws=None):
     return st, out, total
 
 
-def gpu_decompress(stream, n_cap, in_bytes=None, ws=None):
+def gpu_decompress(stream, n_cap, in_bytes=None, ws=None, average=False):
     """-> (status, float32 numpy array of n values, n)"""
     d_in = to_dev(stream)
     in_bytes = d_in.numel() if in_bytes is None else in_bytes
     d_out = torch.full((max(n_cap, 4),), float("nan"), dtype=torch.float32, device=DEV)
     ws = workspace(max(n_cap, 1)) if ws is None else ws
-    st, n = zc.zc_decompress(d_in, in_bytes, d_out, ws, out_cap_elems=n_cap)
+    fn = zc.zc_decompress_average if average else zc.zc_decompress
+    st, n = fn(d_in, in_bytes, d_out, ws, out_cap_elems=n_cap)
     torch.cuda.synchronize()
     return st, (d_out[:n].cpu().numpy() if st == zc.binding.ZC_OK else None), n
 
@@ -98,7 +99,7 @@ def gpu_decompress_many(streams, n_caps, ws=None):
     return st, [o.cpu().numpy() for o in d_outs], ns
 
 
-def gpu_reduce_step(stream, local, out_cap=None, ws=None, n_local=None):
+def gpu_reduce_step(stream, local, out_cap=None, ws=None, n_local=None, op=None):
     """-> (status, stream bytes, total_bytes)"""
     d_in = to_dev(stream)
     d_loc = to_dev(np.ascontiguousarray(local, dtype=np.float32)) if len(local) else torch.zeros(4, device=DEV)
@@ -106,7 +107,10 @@ def gpu_reduce_step(stream, local, out_cap=None, ws=None, n_local=None):
     cap = zc.zc_compress_bound(n) if out_cap is None else out_cap
     d_out = torch.full((cap + 64,), 0x3C, dtype=torch.uint8, device=DEV)
     ws = workspace(max(n, 1)) if ws is None else ws
-    st, total = zc.zc_reduce_step(d_in, d_in.numel(), d_loc, n, d_out, ws, out_cap=cap)
+    if op is None:
+        st, total = zc.zc_reduce_step(d_in, d_in.numel(), d_loc, n, d_out, ws, out_cap=cap)
+    else:
+        st, total = zc.zc_reduce_step_op(d_in, d_in.numel(), d_loc, n, op, d_out, ws, out_cap=cap)
     assert bool((d_out[cap:] == 0x3C).all()), "wrote past out_cap"
     torch.cuda.synchronize()
     ok = st in (zc.binding.ZC_OK, zc.binding.ZC_ERR_BOUND)

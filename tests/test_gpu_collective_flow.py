@@ -90,3 +90,43 @@ def test_ring_allreduce_and_direct_form(nranks, chunk):
     # the worst case, and neither is biased
     assert abs((torch.cat(outs).double() - exact).mean().item()) < eb / 50
     assert abs((results[0].double() - exact).mean().item()) < eb / 50
+
+
+@pytest.mark.parametrize("nranks,chunk", [(4, 2 * 8192 + 99)])
+def test_ring_allreduce_max_min_and_average(nranks, chunk):
+    """The other aggregation functions of Section 3.2 through the same ring: Max and Min by rounds of
+    zc_reduce_step_op (the result is within eb of the exact extreme however long the ring), Average by
+    summing on the codes and dividing on the way out (within eb of the exact mean)."""
+    N = nranks
+    eb = 1e-3
+    ws = torch.empty(zc.zc_workspace_bytes(chunk, N) + 16, dtype=torch.uint8, device=DEV)
+    local = [synth.power_law_field((N, 64, (chunk + 63) // 64 + 1), seed=300 + r, device=DEV).ravel()[:chunk].clone()
+             for r in range(N)]
+    stacked = torch.stack([x.double() for x in local])
+    for op, exact in ((zc.binding.ZC_OP_MAX, stacked.max(0).values), (zc.binding.ZC_OP_MIN, stacked.min(0).values)):
+        carried = _compress(local[0], eb, ws)
+        for r in range(1, N):
+            out = torch.empty(zc.zc_compress_bound(chunk), dtype=torch.uint8, device=DEV)
+            st, total = zc.zc_reduce_step_op(carried[0], carried[1], local[r], chunk, op, out, ws)
+            assert st == ZC_OK
+            carried = (out, total)
+        y = torch.empty(chunk, dtype=torch.float32, device=DEV)
+        st, n = zc.zc_decompress(carried[0], carried[1], y, ws)
+        assert st == ZC_OK and n == chunk
+        assert (y.double() - exact).abs().max().item() <= eb
+        # the ring's result is the stream of the exact extreme, compressed once
+        direct = _compress(exact.float(), eb, ws)
+        y2 = torch.empty(chunk, dtype=torch.float32, device=DEV)
+        zc.zc_decompress(direct[0], direct[1], y2, ws)
+        assert torch.equal(y.view(torch.int32), y2.view(torch.int32))
+    streams = [_compress(x, eb, ws) for x in local]
+    out = torch.empty(zc.zc_compress_bound(chunk), dtype=torch.uint8, device=DEV)
+    st, total = zc.zc_reduce_compressed([s for s, _ in streams], [t for _, t in streams], out, ws)
+    assert st == ZC_OK
+    y = torch.empty(chunk, dtype=torch.float32, device=DEV)
+    st, n = zc.zc_decompress_average(out, total, y, ws)
+    assert st == ZC_OK and n == chunk
+    err = y.double() - stacked.mean(0)
+    assert err.abs().max().item() <= eb * (1 + 1e-6)
+    sigma = eb * 63 / 32 / 12 ** 0.5
+    assert abs(err.pow(2).mean().sqrt().item() / (sigma / N ** 0.5) - 1) < 0.1        # Corollary 1

@@ -713,3 +713,72 @@ def test_wide_block_in_the_ragged_last_tile(zcref, tail):
     assert zcref.compress(x, 1e-3)[1].tobytes() == ref.tobytes()
     st, s, _ = u.gpu_compress(x, 1e-3)
     assert st == zcref.compress(x, 1e-3)[0] and s.tobytes() == ref.tobytes(), u.first_diff(s, ref)
+
+
+# ---------------- the other aggregation functions: Max, Min (ring round) and Average (decompress) ----------------
+@pytest.mark.parametrize("n,rel", [(1, 1e-3), (33, 1e-3), (TILE, 1e-4), (5 * TILE + 77, 1e-3), (16 * TILE - 5, 1e-2)])
+def test_reduce_step_max_min_match_reference(zcref, n, rel):
+    u = _u()
+    x = synth.power_law_field((n // 4096 + 1, 64, 64), seed=400).numpy().ravel()[:n]
+    loc = synth.power_law_field((n // 4096 + 1, 64, 64), seed=401).numpy().ravel()[:n]
+    eb = synth.abs_bound(torch.from_numpy(x), rel) if n > 1 else 1e-3
+    _, s, _ = zcref.compress(x, eb)
+    for op in (zcref.OP_SUM, zcref.OP_MAX, zcref.OP_MIN):
+        st_ref, r_ref, total_ref = zcref.reduce_step(s, loc, op=op)
+        st, r, total = u.gpu_reduce_step(s, loc, op=op)
+        assert st == st_ref == ZC_OK and total == total_ref
+        assert r.tobytes() == r_ref.tobytes(), f"op {op}: " + u.first_diff(r, r_ref)
+
+
+def test_ring_of_max_rounds_is_the_elementwise_maximum(zcref):
+    u = _u()
+    n = 3 * TILE + 123
+    xs = [synth.power_law_field((4, 64, 64), seed=410 + i).numpy().ravel()[:n] for i in range(5)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), 1e-3)
+    for op, extreme in ((zcref.OP_MAX, np.maximum), (zcref.OP_MIN, np.minimum)):
+        st, s, _ = u.gpu_compress(xs[0], eb)
+        for x in xs[1:]:
+            st, s, _ = u.gpu_reduce_step(s, x, op=op)
+            assert st == ZC_OK
+        want = zcref.compress(extreme.reduce(xs), eb)[1].copy()
+        want[20:24] = np.array([len(xs)], "<u4").view(np.uint8)
+        assert s.tobytes() == want.tobytes(), u.first_diff(s, want)
+
+
+def test_reduce_step_op_error_paths_and_wide(zcref):
+    u = _u()
+    x = synth.power_law_field((3, 64, 64), seed=420).numpy().ravel()
+    loc = synth.power_law_field((3, 64, 64), seed=421).numpy().ravel()
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    _, s, _ = zcref.compress(x, eb)
+    for op in (zcref.OP_MAX, zcref.OP_MIN):
+        for bad in (np.nan, np.inf, -np.inf):
+            l2 = loc.copy(); l2[7000] = bad
+            assert u.gpu_reduce_step(s, l2, op=op)[0] == ZC_ERR_NONFINITE == zcref.reduce_step(s, l2, op=op)[0]
+        l2 = loc.copy(); l2[5000] = np.float32(eb * 2.0 ** 32) * (1 if op == zcref.OP_MAX else -1)
+        assert u.gpu_reduce_step(s, l2, op=op)[0] == ZC_ERR_RANGE == zcref.reduce_step(s, l2, op=op)[0]
+        assert u.gpu_reduce_step(s, loc[:-1], op=op)[0] == ZC_ERR_MISMATCH == zcref.reduce_step(s, loc[:-1], op=op)[0]
+        # values far outside the guaranteed domain: wide blocks, BOUND status, stream still identical
+        l3 = loc.copy(); l3[::97] *= np.float32(3e5) * (1 if op == zcref.OP_MAX else -1)
+        st_ref, r_ref, _ = zcref.reduce_step(s, l3, op=op)
+        st, r, _ = u.gpu_reduce_step(s, l3, op=op)
+        assert st == st_ref and r.tobytes() == r_ref.tobytes(), u.first_diff(r, r_ref)
+        assert zcref.inspect(r_ref)[2].max() > 15
+    assert u.gpu_reduce_step(s, loc, op=3)[0] == ZC_ERR_ARG == zcref.reduce_step(s, loc, op=3)[0]
+
+
+@pytest.mark.parametrize("k,n", [(1, TILE + 5), (3, 4 * TILE + 1), (8, 16 * TILE), (64, 2 * TILE - 9)])
+def test_decompress_average_matches_reference(zcref, k, n):
+    u = _u()
+    xs, eb, streams = _rank_streams(zcref, k, 4096 * ((n + 4095) // 4096), 1e-3, seed0=430)
+    streams = [zcref.compress(x[:n], eb)[1] for x in xs]
+    st, red, _ = u.gpu_reduce(streams, n)
+    assert st == ZC_OK and red.tobytes() == zcref.reduce(streams)[1].tobytes()
+    st, y, m = u.gpu_decompress(red, n, average=True)
+    st_ref, y_ref, _ = zcref.decompress(red, average=True)
+    assert st == st_ref == ZC_OK and m == n
+    assert np.array_equal(y.view(np.uint32), y_ref.view(np.uint32)), u.first_diff(y, y_ref)
+    mean = np.mean(np.stack([x[:n].astype(np.float64) for x in xs]), axis=0)
+    assert np.abs(y.astype(np.float64) - mean).max() <= eb * (1 + 1e-6)
+    assert u.gpu_decompress(red, n - 1, average=True)[0] == ZC_ERR_CAPACITY
+    assert u.gpu_decompress(red[:-1], n, average=True)[0] == ZC_ERR_FORMAT

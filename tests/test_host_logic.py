@@ -70,6 +70,13 @@ def test_argument_checks_without_gpu(libzc):
     assert libzc.zc_reduce_step(0x1000, 100, None, 8, 0x2000, 100, None, 0x3000, 4096, None) == 1      # no local values
     assert libzc.zc_reduce_step(0x1000, 100, 0x1008, 8, 0x2000, 100, None, 0x3000, 4096, None) == 1    # alignment
     assert libzc.zc_reduce_step(0x1000, 16, 0x4000, 8, 0x2000, 100, None, 0x3000, 4096, None) == 3     # shorter than a header
+    libzc.zc_reduce_step_op.argtypes = [vp, sz, vp, sz, C.c_int, vp, sz, C.POINTER(sz), vp, sz, vp]
+    for op in (-1, 3):
+        assert libzc.zc_reduce_step_op(0x1000, 100, 0x4000, 8, op, 0x2000, 100, None, 0x3000, 4096, None) == 1   # unknown op
+    assert libzc.zc_reduce_step_op(0x1000, 16, 0x4000, 8, 2, 0x2000, 100, None, 0x3000, 4096, None) == 3
+    libzc.zc_decompress_average.argtypes = [vp, sz, vp, sz, C.POINTER(sz), vp, sz, vp]
+    assert libzc.zc_decompress_average(None, 100, None, 0, None, None, 0, None) == 1
+    assert libzc.zc_decompress_average(0x1000, 16, 0x2000, 8, None, 0x3000, 4096, None) == 3
     assert libzc.zc_reduce_step(0x1000, 100, 0x4000, 1 << 20, 0x2000, 100, None, 0x3000, 64, None) == 1  # workspace
     libzc.zc_decompress_many.argtypes = [C.POINTER(vp), C.POINTER(sz), C.c_int, C.POINTER(vp), C.POINTER(sz), C.POINTER(sz),
                                          vp, sz, vp]
