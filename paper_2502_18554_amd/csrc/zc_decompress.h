@@ -62,6 +62,14 @@ __device__ inline WaveStage load_wave_stage(const u32* payload, u64 payload_word
   return st;
 }
 
+__device__ inline void store_wave_stage(const WaveStage& st, u32 span, u32* wl, int lane) {
+#pragma unroll
+  for (int i = 0; i < 5; ++i) {
+    const u32 idx = 4u * u32(lane) + 256u * u32(i);
+    if (idx < span) *reinterpret_cast<uint4*>(wl + idx) = st.v[i];
+  }
+}
+
 __device__ inline u32 wave_block_words(const u32* payload, u64 payload_words, u32 w, u64 seg_off, u32* wl, int lane,
                                        u32 (&lo)[16], u32 (&hi)[16], bool ix, u32 seg_words, bool may_be_wide,
                                        u32& err) {
@@ -73,6 +81,7 @@ __device__ inline u32 wave_block_words(const u32* payload, u64 payload_words, u3
     // at most 64 * 16 words when no block is wider than 15 bits
     if (seg_words <= 64u * 16u && seg_off + seg_words <= payload_words) span = mis + seg_words;
     st = load_wave_stage(payload, payload_words, src0, span, lane);
+    store_wave_stage(st, span, wl, lane);              // at once: the registers are free for what follows
   }
   bool unfit = false;
   if (ix) {
@@ -97,12 +106,7 @@ __device__ inline u32 wave_block_words(const u32* payload, u64 payload_words, u3
     if (!ix) {
       span = inside ? mis + wave_total : 0u;
       st = load_wave_stage(payload, payload_words, src0, span, lane);
-    }
-    const uint4 (&stage)[5] = st.v;
-#pragma unroll
-    for (int i = 0; i < 5; ++i) {
-      const u32 idx = 4u * u32(lane) + 256u * u32(i);
-      if (idx < span) *reinterpret_cast<uint4*>(wl + idx) = stage[i];
+      store_wave_stage(st, span, wl, lane);
     }
     wave_lds_sync();
     if (w && inside) {
