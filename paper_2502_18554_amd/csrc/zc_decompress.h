@@ -2,7 +2,8 @@
 //
 // Same geometry as compression: a tile is 256 blocks, one lane owns one block, and there is no
 // dependency between workgroups: a wave's payload offset comes from the stream index
-// (zc_scan.h), and a scan of the block sizes places each lane inside the wave.  The wave's
+// (computed by zc_scan.h for a plain stream, carried by an indexed one), and a scan of the
+// block sizes places each lane inside the wave.  The wave's
 // payload is contiguous, so it is copied into LDS with coalesced loads (each byte leaves the
 // L2 once) and every lane then picks its sign and plane words there.  A bit-matrix transpose
 // turns them back into deltas; the Lorenzo chain from the block's outlier and the

@@ -17,8 +17,12 @@
 // 16-byte loads, and the loads of the next operand fly while the current one is added; the
 // summed planes go to LDS in one pass and leave as coalesced stores.  Operand payloads are
 // read, and the output stream is written, with the non-temporal hint (see load_once).
-// reduce_wide_kernel takes any widths with per-lane loads.  The stream index records whether
-// any operand has a wider block; each kernel returns at once when the streams are not its.
+// reduce_wide_kernel takes any widths with per-lane loads.  The control block says whether
+// any operand has a wider block (from the stream index of plain streams, from the version
+// word of indexed ones); each kernel returns at once when the streams are not its.
+// IX = the streams are indexed (see index_bytes): operands bring the positions of their
+// segments along, which every wave checks against the widths it reads, and the output gets
+// its own index as it is placed.
 #pragma once
 
 #include "zc_common.h"

@@ -9,7 +9,8 @@
 // the compression kernel's back half (deltas -> width -> planes -> look-back placement) around
 // one addition, with nothing written to memory in between: 4 bytes per value of local input
 // plus the two streams, instead of the 12 more that separate decompress, add and compress
-// calls would move.
+// calls would move.  The other aggregation functions of Section 3.2 (Max, Min) take the
+// same round with a comparison in place of the addition (combine<OP>).
 //
 // Geometry: tiles of 256 blocks, one wave per 64 blocks, one lane per block.  The local
 // values arrive as coalesced 16-byte loads (lane = 4 consecutive values), asked for before
