@@ -1,8 +1,8 @@
 /* zc — fZ-light error-bounded lossy compression and the compressed-Allreduce local step,
  * hand-written for AMD MI355X (gfx950).  C ABI; every pointer named d_* is DEVICE memory,
  * everything else is host memory.  The library allocates no device memory and keeps no
- * state between calls (but see zc_profile_enable): the caller owns inputs, outputs and the
- * workspace.
+ * state between calls apart from three process-wide settings (zc_set_indexed_streams,
+ * zc_set_tile_hand_out, zc_profile_enable): the caller owns inputs, outputs and the workspace.
  *
  * Method: ZCCL, arXiv 2502.18554.  fZ-light is described in Section 3.3 (block partition,
  * fused quantisation + 1D Lorenzo prediction, first value kept as a 4-byte outlier, sign
@@ -48,7 +48,7 @@ typedef enum {
   ZC_OK = 0,
   ZC_ERR_ARG = 1,       /* null pointer, misaligned buffer, abs_eb not finite / < 2^-96, n > 2^31, k out of range, workspace too small */
   ZC_ERR_CAPACITY = 2,  /* output buffer too small; nothing is written past its end */
-  ZC_ERR_FORMAT = 3,    /* not a valid stream: header fields, truncated, width > 31, sizes do not add up */
+  ZC_ERR_FORMAT = 3,    /* not a valid stream: header fields, truncated, width > 31, sizes do not add up, the other stream variant, an index that contradicts the widths */
   ZC_ERR_NONFINITE = 4, /* NaN or Inf in the input */
   ZC_ERR_RANGE = 5,     /* a code (or a sum of codes) exceeds 2^30 - 1 in magnitude */
   ZC_ERR_BOUND = 6,     /* some |x - x'| > abs_eb: input outside max|x| <= 2^18 abs_eb; the stream is still complete and decodable */
