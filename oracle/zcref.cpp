@@ -41,6 +41,7 @@
 // words; zero padded to 16 bytes.  A reader accepts version 3 without a wide block, but not
 // version 2 with one.  zcref_set_indexed() chooses which variant is written and accepted.
 
+#include <algorithm>
 #include <cmath>
 #include <cstddef>
 #include <cstdint>
@@ -319,6 +320,30 @@ int zcref_decompress(const void* in, size_t in_bytes, float* out, size_t out_cap
   decode_codes(ps, q.data());
   const double s = quant_step(bits_to_float(ps.eb_bits));
   for (size_t i = 0; i < ps.n; ++i) out[i] = dequantize_one(q[i], s);
+  return OK;
+}
+
+// A chunk of a stream on its own (Section 3.5.2 handles a buffer chunk by chunk, so that one
+// chunk can be decompressed while the next is still on its way): the values
+// [first_value, first_value + count) of the stream, first_value a multiple of 2048 (a segment
+// of 64 blocks), cut off at the stream's end.  By definition the same values as a slice of
+// the whole decompression.  *n_out = how many values that is.
+// Status: ARG (first_value not a multiple of 2048, or beyond n), FORMAT, CAPACITY.
+int zcref_decompress_range(const void* in, size_t in_bytes, size_t first_value, size_t count, float* out,
+                           size_t out_cap_elems, size_t* n_out) {
+  if (!in || first_value % (kSegBlocks * kBlock) != 0) return ERR_ARG;
+  Parsed ps;
+  int st = parse_stream(static_cast<const uint8_t*>(in), in_bytes, &ps);
+  if (st != OK) return st;
+  if (first_value > ps.n) return ERR_ARG;
+  const size_t m = std::min<uint64_t>(count, ps.n - first_value);
+  if (n_out) *n_out = m;
+  if (m > out_cap_elems) return ERR_CAPACITY;
+  if (m && !out) return ERR_ARG;
+  std::vector<int32_t> q(ps.n);
+  decode_codes(ps, q.data());
+  const double s = quant_step(bits_to_float(ps.eb_bits));
+  for (size_t i = 0; i < m; ++i) out[i] = dequantize_one(q[first_value + i], s);
   return OK;
 }
 

@@ -32,6 +32,8 @@ def lib():
         L.zcref_inspect.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         L.zcref_quality.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.zcref_decompress_average.argtypes = L.zcref_decompress.argtypes
+        L.zcref_decompress_range.argtypes = [C.c_void_p, C.c_size_t, C.c_size_t, C.c_size_t, C.c_void_p, C.c_size_t,
+                                             C.POINTER(C.c_size_t)]
         L.zcref_reduce_step_op.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_size_t,
                                            C.POINTER(C.c_size_t)]
         L.zcref_reduce_step.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
@@ -94,6 +96,16 @@ def decompress(stream, out_cap_elems=None, average=False):
         out_cap_elems = n.value
     out = np.empty(max(out_cap_elems, 1), dtype=np.float32)
     st = fn(_ptr(stream), stream.size, _ptr(out), out_cap_elems, C.byref(n))
+    return st, (out[: n.value].copy() if st == OK else out[:0]), n.value
+
+
+def decompress_range(stream, first_value, count, out_cap_elems=None):
+    """Values [first_value, first_value + count) of the stream.  Returns (status, float32 array, n reported)."""
+    stream = np.ascontiguousarray(stream, dtype=np.uint8)
+    n = C.c_size_t(0)
+    cap = count if out_cap_elems is None else out_cap_elems
+    out = np.empty(max(cap, 1), dtype=np.float32)
+    st = lib().zcref_decompress_range(_ptr(stream), stream.size, int(first_value), int(count), _ptr(out), cap, C.byref(n))
     return st, (out[: n.value].copy() if st == OK else out[:0]), n.value
 
 

@@ -707,3 +707,28 @@ def test_average_decompress(zcref, k):
     assert abs(np.sqrt(np.mean(err ** 2)) / (sigma / k ** 0.5) - 1) < 0.1
     assert zcref.decompress(red, out_cap_elems=n - 1, average=True)[0] == zcref.ERR_CAPACITY
     assert zcref.decompress(red[:-1], average=True)[0] == zcref.ERR_FORMAT
+
+
+# ---------------- P13: one chunk of a stream on its own ----------------
+@pytest.mark.parametrize("variant", [False, True])
+def test_decompress_range_is_a_slice_of_the_whole(zcref, variant):
+    x = synth.power_law_field((5, 64, 33), seed=500).numpy().ravel()          # 10560 values: 5 segments and a bit
+    zcref.set_indexed(variant)
+    try:
+        st, s, _ = zcref.compress(x, 1e-3)
+        st, whole, n = zcref.decompress(s)
+        assert st == zcref.OK and n == x.size
+        for first, count in ((0, 2048), (2048, 2048), (4096, 5000), (8192, 10 ** 9), (10240, 1), (10240, 320), (0, 0), (0, x.size),
+                             (6144, 1), (10240, 321)):
+            st, part, m = zcref.decompress_range(s, first, count, out_cap_elems=x.size)
+            want = whole[first:first + count]
+            assert st == zcref.OK and m == want.size and np.array_equal(part.view(np.uint32), want.view(np.uint32)), (first, count)
+        # chunks put together are the whole
+        parts = [zcref.decompress_range(s, f, 4096)[1] for f in range(0, x.size, 4096)]
+        assert np.array_equal(np.concatenate(parts), whole)
+        assert zcref.decompress_range(s, 100, 10)[0] == zcref.ERR_ARG             # not at a segment
+        assert zcref.decompress_range(s, 12288, 10)[0] == zcref.ERR_ARG           # beyond the stream
+        assert zcref.decompress_range(s, 2048, 100, out_cap_elems=99)[0] == zcref.ERR_CAPACITY
+        assert zcref.decompress_range(s[:-1], 0, 10)[0] == zcref.ERR_FORMAT
+    finally:
+        zcref.set_indexed(False)
