@@ -92,6 +92,21 @@ int zc_decompress(const void* d_in, size_t in_bytes,
 int zc_decompress_average(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
                           void* d_ws, size_t ws_bytes, void* hip_stream);
 
+/* One chunk of a stream on its own (Section 3.5.2 handles a buffer chunk by chunk, so that a
+ * chunk can be decompressed while others are still on their way or being worked on, for
+ * instance by calls on several HIP streams, each with a workspace of its own): the values
+ * [first_value, first_value + count) of the stream, cut off at its end, go to d_out[0 ...].
+ * first_value must be a multiple of 2048 (a segment of 64 blocks).  Only the header, the tables
+ * and the payload of those segments are read; of an indexed stream (zc_set_indexed_streams)
+ * not even the whole width table, only the index entries and width bytes of the segments.
+ * The workspace must be large enough for the whole stream (zc_workspace_bytes(n, 1)).
+ * n_out (host, may be NULL): receives how many values that is.
+ * Errors: ARG (also: first_value not a multiple of 2048, or beyond the stream's n), FORMAT,
+ * CAPACITY (out_cap_elems smaller than the part), HIP. */
+int zc_decompress_range(const void* d_in, size_t in_bytes, size_t first_value, size_t count,
+                        float* d_out, size_t out_cap_elems, size_t* n_out,
+                        void* d_ws, size_t ws_bytes, void* hip_stream);
+
 /* Decompression of k streams in one call: the tail of the compressed Allgather (Section 3.5.1:
  * a rank decompresses all the chunks it has received at the end), one launch instead of k.
  * d_chunks, chunk_bytes, d_outs, out_cap_elems: HOST arrays of k entries (device pointers 16-byte

@@ -18,7 +18,7 @@ ZC_MAX_K = 64
 
 EXPORTS = [
     "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_decompress_many",
-    "zc_reduce_compressed", "zc_reduce_step", "zc_reduce_step_op", "zc_decompress_average", "zc_quality",
+    "zc_reduce_compressed", "zc_reduce_step", "zc_reduce_step_op", "zc_decompress_average", "zc_decompress_range", "zc_quality",
     "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
     "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out", "zc_set_indexed_streams",
 ]
@@ -51,6 +51,7 @@ def lib():
         L.zc_reduce_step.argtypes = [vp, sz, vp, sz, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_step_op.argtypes = [vp, sz, vp, sz, C.c_int, vp, sz, szp, vp, sz, vp]
         L.zc_decompress_average.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
+        L.zc_decompress_range.argtypes = [vp, sz, sz, sz, vp, sz, szp, vp, sz, vp]
         L.zc_quality.argtypes = [vp, vp, sz, C.POINTER(C.c_double), vp, sz, vp]
         L.zc_decompress_many.argtypes = [C.POINTER(vp), szp, C.c_int, C.POINTER(vp), szp, szp, vp, sz, vp]
         L.zc_finish.argtypes = [vp, szp, vp]
@@ -113,6 +114,16 @@ def zc_decompress_average(d_in, in_bytes, d_out, d_ws, sync=True, stream=None, o
     cap = (d_out.numel() if d_out is not None else 0) if out_cap_elems is None else out_cap_elems
     st = lib().zc_decompress_average(_p(d_in), in_bytes, _p(d_out), cap, C.byref(n) if sync else None,
                                      _p(d_ws), d_ws.numel() * d_ws.element_size(), _stream(stream))
+    return st, (n.value if sync else None)
+
+
+def zc_decompress_range(d_in, in_bytes, first_value, count, d_out, d_ws, sync=True, stream=None, out_cap_elems=None):
+    """Values [first_value, first_value + count) of the stream into d_out.  Returns (status, n)."""
+    n = C.c_size_t(0)
+    cap = (d_out.numel() if d_out is not None else 0) if out_cap_elems is None else out_cap_elems
+    st = lib().zc_decompress_range(_p(d_in), in_bytes, int(first_value), int(count), _p(d_out), cap,
+                                   C.byref(n) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
+                                   _stream(stream))
     return st, (n.value if sync else None)
 
 

@@ -252,6 +252,8 @@ static int decompress_one(const void* d_in, size_t in_bytes, float* d_out, size_
   da.out_cap_elems = out_cap_elems;
   da.index = l.index;
   da.ctl = l.ctl;
+  da.first_value = 0;
+  da.count = ~u64(0);
   KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_DECOMPRESS, stream);
   auto kernel = average ? (g_indexed ? decompress_kernel<true, true> : decompress_kernel<false, true>)
                         : (g_indexed ? decompress_kernel<true, false> : decompress_kernel<false, false>);
@@ -270,6 +272,54 @@ int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_ca
 int zc_decompress_average(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
                           void* d_ws, size_t ws_bytes, void* hip_stream) {
   return decompress_one(d_in, in_bytes, d_out, out_cap_elems, n_out, d_ws, ws_bytes, hip_stream, true);
+}
+
+int zc_decompress_range(const void* d_in, size_t in_bytes, size_t first_value, size_t count, float* d_out,
+                        size_t out_cap_elems, size_t* n_out, void* d_ws, size_t ws_bytes, void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  constexpr u64 kSegValues = u64(kWaveBlocks) * kBlockValues;
+  if (!d_in || !d_ws || (out_cap_elems && !d_out) || first_value % kSegValues != 0 || first_value > ZC_MAX_N) return ZC_ERR_ARG;
+  if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
+  if (in_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
+  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
+  if (l.tiles_cap < 1) return ZC_ERR_ARG;
+  // segments the part can have: no more than the buffers allow
+  u64 wanted = count < out_cap_elems ? count : out_cap_elems;
+  const u64 stream_bound = blocks_bound(in_bytes) * kBlockValues;
+  if (wanted > stream_bound) wanted = stream_bound;
+  u64 grid = (wanted + kTileValues - 1) / kTileValues;
+  if (grid > kMaxTiles) grid = kMaxTiles;
+  if (grid < 1) grid = 1;
+  // the index of a plain stream has to reach the end of the part
+  u64 tiles = first_value / kTileValues + 1 + grid;
+  const u64 tiles_in = num_tiles(blocks_bound(in_bytes));
+  if (tiles > tiles_in) tiles = tiles_in;
+  if (tiles > l.tiles_cap) tiles = l.tiles_cap;
+  if (tiles > kMaxTiles) tiles = kMaxTiles;
+  if (tiles < 1) tiles = 1;
+  ScanArgs sa;
+  sa.streams[0].base = static_cast<const u8*>(d_in);
+  sa.streams[0].bytes = in_bytes;
+  sa.k = 1;
+  sa.check_match = 0;
+  sa.index = l.index;
+  sa.ctl = l.ctl;
+  sa.desc = nullptr;
+  sa.ndesc = 0;
+  launch_index(sa, tiles, 1, stream);
+  DecompressArgs da;
+  da.in = sa.streams[0];
+  da.out = d_out;
+  da.out_cap_elems = out_cap_elems;
+  da.index = l.index;
+  da.ctl = l.ctl;
+  da.first_value = first_value;
+  da.count = count;
+  hipLaunchKernelGGL(g_indexed ? decompress_range_kernel<true> : decompress_range_kernel<false>, dim3(u32(grid)),
+                     dim3(kTileThreads), 0, stream, da);
+  if (!launch_ok()) return ZC_ERR_HIP;
+  if (!n_out) return ZC_OK;
+  return finish(d_ws, n_out, stream);
 }
 
 int zc_decompress_many(const void* const* d_chunks, const size_t* chunk_bytes, int k, float* const* d_outs,

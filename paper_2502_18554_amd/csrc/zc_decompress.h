@@ -23,6 +23,8 @@ struct DecompressArgs {
   u64 out_cap_elems;
   StreamIndex index;
   Control* ctl;
+  u64 first_value;   // decompress_range_kernel only: the part [first_value, first_value + count) of the
+  u64 count;         // stream, first_value a multiple of the values of a segment
 };
 
 // The sign and plane words of the lane's block (width w, 0 for a block that does not exist) out
@@ -160,17 +162,20 @@ __device__ inline void deltas_from_block_words(u32 wmax, u32 (&lo)[16], u32 (&hi
 // the header tells, so they are asked for together with the outlier and the payload.
 // `average`: the values are divided by the stream's nsum (the Average aggregation of Section
 // 3.2 on a stream of sums): x' = float((double(q) * s) * r), r = 1.0 / nsum.
+// first_value, count: only the values [first_value, first_value + count) of the stream, cut off
+// at its end, are produced, into out_values[0 ...] (a chunk handled on its own, Section 3.5.2);
+// first_value is a multiple of the 2048 values of a segment.  The whole stream: 0 and ~0.
 __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u64 out_cap_elems, const StreamIndex& index,
-                                       int s, Control* ctl, bool counted, u32* lds, bool ix, bool average = false) {
-  const DecompressArgs a{in, out_values, out_cap_elems, index, ctl};
+                                       int s, Control* ctl, bool counted, u32* lds, bool ix, bool average = false,
+                                       u64 first_value = 0, u64 count = ~u64(0)) {
+  const DecompressArgs a{in, out_values, out_cap_elems, index, ctl, first_value, count};
 
   // Everything that can be asked for before the header is known goes out at once: the control
   // block, the header, the segment's position and the width bytes.  The loads are fenced in
   // by sizes the host passed; what the header then rules out is dropped.
   const int lane = lane_id();
   const int wave = wave_id();
-  const u32 tile = blockIdx.x;
-  const u32 seg = tile * kTileWaves + u32(wave);       // < 2^22: the host launches at most 2^20 tiles
+  const u32 seg = u32(first_value / (kWaveBlocks * kBlockValues)) + blockIdx.x * kTileWaves + u32(wave);   // < 2^22: the host launches at most 2^20 tiles
   const u32 wblock0 = seg * kWaveBlocks;
   const u32 b = wblock0 + u32(lane);                   // a stream has at most 2^26 blocks
   const u32 zero = opaque_zero();
@@ -190,18 +195,24 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
 
   const ParsedHeader h = parse_header(hw, a.in.bytes, ix);
   if (gate_failed(gate) || !h.ok) return;
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    if (counted) atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->result), static_cast<unsigned long long>(h.n));
-    else a.ctl->result = h.n;
+  if (first_value > h.n) {                            // the part lies beyond the stream
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_ARG));
+    return;
   }
-  if (h.n > a.out_cap_elems) {
+  const u64 end_value = count < h.n - first_value ? first_value + count : h.n;     // one past the last value wanted
+  const u64 wanted = end_value - first_value;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (counted) atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->result), static_cast<unsigned long long>(wanted));
+    else a.ctl->result = wanted;
+  }
+  if (wanted > a.out_cap_elems) {
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
     return;
   }
-  if (u64(tile) >= num_tiles(h.nb) || u64(tile) >= a.index.tiles_cap) return;
+  if (u64(seg) >= 4 * a.index.tiles_cap) return;
 
   u32* const wl = lds + wave * kWaveStage;
-  if (seg >= num_segments(h.nb)) return;           // no barrier below: waves are independent
+  if (seg >= num_segments(h.nb) || u64(seg) * kWaveBlocks * kBlockValues >= end_value) return;   // no barrier below: waves are independent
   const bool active = b < h.nb;
   if (ix && active) w = u32(*at_bytes(a.in.base, u32(widths_begin(h.nb, true)) + b));
   if (!active) w = 0;
@@ -235,7 +246,8 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
 
   // ---- transpose through LDS (two halves of 32 blocks), 16-byte coalesced stores ----
   const u64 v0 = u64(wblock0) * kBlockValues;
-  const bool full = v0 + u64(kWaveBlocks) * kBlockValues <= h.n;
+  const bool full = v0 + u64(kWaveBlocks) * kBlockValues <= end_value;
+  float* const out = a.out - first_value;           // indexed by the value's number in the stream
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh) {
     if ((lane >> 5) == hh) {
@@ -250,12 +262,12 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
       const u64 idx = v0 + u64(1024 * hh + 256 * i + 4 * lane);
       const float4 v = *reinterpret_cast<const float4*>(wl + (8 * i + (lane >> 3)) * kStageRow + 4 * (lane & 7));
       if (full) {
-        store_once(reinterpret_cast<float4*>(a.out + idx), v);
+        store_once(reinterpret_cast<float4*>(out + idx), v);
       } else {
-        if (idx + 0 < h.n) a.out[idx + 0] = v.x;
-        if (idx + 1 < h.n) a.out[idx + 1] = v.y;
-        if (idx + 2 < h.n) a.out[idx + 2] = v.z;
-        if (idx + 3 < h.n) a.out[idx + 3] = v.w;
+        if (idx + 0 < end_value) out[idx + 0] = v.x;
+        if (idx + 1 < end_value) out[idx + 1] = v.y;
+        if (idx + 2 < end_value) out[idx + 2] = v.z;
+        if (idx + 3 < end_value) out[idx + 3] = v.w;
       }
     }
     wave_lds_sync();
@@ -266,6 +278,13 @@ template <bool IX, bool AVERAGE>
 __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
   decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, false, lds, IX, AVERAGE);
+}
+
+// A part of a stream (see decompress_tile).
+template <bool IX>
+__global__ __launch_bounds__(kTileThreads, 5) void decompress_range_kernel(DecompressArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
+  decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, false, lds, IX, false, a.first_value, a.count);
 }
 
 // k streams in one launch (the tail of the compressed Allgather, Section 3.5.1: every rank

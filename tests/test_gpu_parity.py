@@ -782,3 +782,57 @@ def test_decompress_average_matches_reference(zcref, k, n):
     assert np.abs(y.astype(np.float64) - mean).max() <= eb * (1 + 1e-6)
     assert u.gpu_decompress(red, n - 1, average=True)[0] == ZC_ERR_CAPACITY
     assert u.gpu_decompress(red[:-1], n, average=True)[0] == ZC_ERR_FORMAT
+
+
+# ---------------- one chunk of a stream on its own ----------------
+def _gpu_range(u, s, first, count, cap=None, ws_n=None):
+    d_in = u.to_dev(s)
+    cap = count if cap is None else cap
+    d_out = torch.full((max(min(cap, 1 << 22), 4) + 8,), float("nan"), dtype=torch.float32, device=u.DEV)
+    ws = u.workspace(ws_n)
+    st, n = zc.zc_decompress_range(d_in, d_in.numel(), first, count, d_out, ws, out_cap_elems=min(cap, 1 << 22))
+    torch.cuda.synchronize()
+    if st == ZC_OK:
+        assert bool(torch.isnan(d_out[n:]).all()), "wrote past the part"
+    return st, (d_out[:n].cpu().numpy() if st == ZC_OK else None), n
+
+
+def test_decompress_range_matches_reference(zcref):
+    u = _u()
+    n = 9 * TILE + 2048 + 77
+    x = synth.power_law_field((n // 4096 + 1, 64, 64), seed=600).numpy().ravel()[:n]
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    _, s, _ = zcref.compress(x, eb)
+    whole = zcref.decompress(s)[1]
+    cases = [(0, 2048), (2048, 2048), (2048, 3 * TILE), (6144, 5000), (4 * TILE, 1), (9 * TILE, 1 << 30), (9 * TILE + 2048, 77),
+             (9 * TILE + 2048, 78), (0, n), (0, 0), (TILE + 4096, 10 * TILE)]
+    for first, count in cases:
+        st_ref, ref, m_ref = zcref.decompress_range(s, first, count, out_cap_elems=n)
+        st, got, m = _gpu_range(u, s, first, count, ws_n=n)
+        assert st == st_ref == ZC_OK and m == m_ref, (first, count, st, st_ref, m, m_ref)
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (first, count)
+        assert np.array_equal(ref, whole[first:first + count])
+    # chunks decompressed one by one, each on a HIP stream and a workspace of its own, give the whole
+    d_in = u.to_dev(s)
+    out = torch.empty(n, dtype=torch.float32, device=u.DEV)
+    chunk = 2 * TILE + 2048
+    jobs = []
+    torch.cuda.synchronize()
+    for first in range(0, n, chunk):
+        hs = torch.cuda.Stream()
+        ws = u.workspace(n)
+        with torch.cuda.stream(hs):
+            st, _ = zc.zc_decompress_range(d_in, d_in.numel(), first, chunk, out[first:first + chunk], ws, sync=False,
+                                           stream=hs)
+        assert st == ZC_OK
+        jobs.append((hs, ws, min(chunk, n - first)))
+    for hs, ws, want in jobs:
+        st, m = zc.zc_finish(ws, stream=hs)
+        assert st == ZC_OK and m == want
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), whole.view(np.uint32))
+    # errors
+    assert _gpu_range(u, s, 100, 10, ws_n=n)[0] == ZC_ERR_ARG == zcref.decompress_range(s, 100, 10)[0]
+    assert _gpu_range(u, s, 10 * TILE, 10, ws_n=n)[0] == ZC_ERR_ARG == zcref.decompress_range(s, 10 * TILE, 10)[0]
+    assert _gpu_range(u, s, 2048, 100, cap=99, ws_n=n)[0] == ZC_ERR_CAPACITY == zcref.decompress_range(s, 2048, 100, out_cap_elems=99)[0]
+    bad = s.copy(); bad[0] ^= 1
+    assert _gpu_range(u, bad, 0, 10, ws_n=n)[0] == ZC_ERR_FORMAT

@@ -77,6 +77,10 @@ def test_argument_checks_without_gpu(libzc):
     libzc.zc_decompress_average.argtypes = [vp, sz, vp, sz, C.POINTER(sz), vp, sz, vp]
     assert libzc.zc_decompress_average(None, 100, None, 0, None, None, 0, None) == 1
     assert libzc.zc_decompress_average(0x1000, 16, 0x2000, 8, None, 0x3000, 4096, None) == 3
+    libzc.zc_decompress_range.argtypes = [vp, sz, sz, sz, vp, sz, C.POINTER(sz), vp, sz, vp]
+    assert libzc.zc_decompress_range(0x1000, 100, 100, 8, 0x2000, 8, None, 0x3000, 4096, None) == 1     # not at a segment
+    assert libzc.zc_decompress_range(0x1000, 16, 2048, 8, 0x2000, 8, None, 0x3000, 4096, None) == 3
+    assert libzc.zc_decompress_range(None, 100, 0, 8, 0x2000, 8, None, 0x3000, 4096, None) == 1
     assert libzc.zc_reduce_step(0x1000, 100, 0x4000, 1 << 20, 0x2000, 100, None, 0x3000, 64, None) == 1  # workspace
     libzc.zc_decompress_many.argtypes = [C.POINTER(vp), C.POINTER(sz), C.c_int, C.POINTER(vp), C.POINTER(sz), C.POINTER(sz),
                                          vp, sz, vp]
