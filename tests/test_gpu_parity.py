@@ -836,3 +836,62 @@ def test_decompress_range_matches_reference(zcref):
     assert _gpu_range(u, s, 2048, 100, cap=99, ws_n=n)[0] == ZC_ERR_CAPACITY == zcref.decompress_range(s, 2048, 100, out_cap_elems=99)[0]
     bad = s.copy(); bad[0] ^= 1
     assert _gpu_range(u, bad, 0, 10, ws_n=n)[0] == ZC_ERR_FORMAT
+
+
+# ---------------- random mixtures of block widths, constant, narrow and wide side by side ----------------
+def _random_codes(rng, n, p_const=0.4, p_wide=0.2):
+    """Codes whose blocks have widths drawn per block: 0, 1..15 or 16..27, signs chosen so the codes stay small."""
+    nb = (n + 31) // 32
+    q = np.zeros(nb * 32, np.int64)
+    kind = rng.random(nb)
+    for b in range(nb):
+        if kind[b] < p_const:
+            w = 0
+        elif kind[b] < 1 - p_wide:
+            w = int(rng.integers(1, 16))
+        else:
+            w = int(rng.integers(16, 28))
+        cur = int(rng.integers(-1000, 1001))
+        q[32 * b] = cur
+        if w == 0:
+            q[32 * b:32 * b + 32] = cur
+            continue
+        mags = rng.integers(0, 1 << w, 32)
+        mags[int(rng.integers(1, 32))] = (1 << w) - 1 if rng.random() < 0.5 else 1 << (w - 1)     # the block's width is exactly w
+        for j in range(1, 32):
+            cur += int(mags[j]) * (-1 if cur > 0 else 1)
+            q[32 * b + j] = cur
+    return q[:n].astype(np.int32)
+
+
+@pytest.mark.parametrize("seed,n,p_wide", [(1, 3 * TILE + 100, 0.2), (2, 7 * TILE - 31, 0.0), (3, TILE + 2048 + 1, 0.6), (4, 12 * TILE, 0.02)])
+def test_random_width_mixtures(zcref, seed, n, p_wide):
+    u = _u()
+    rng = np.random.default_rng(1000 + seed)
+    eb = 1e-3
+    qs = [_random_codes(rng, n, p_wide=p_wide) for _ in range(3)]
+    streams = [zcref.encode_codes(q, eb)[1] for q in qs]
+    for s in streams:
+        st, y, m = u.gpu_decompress(s, n)
+        st_ref, y_ref, _ = zcref.decompress(s)
+        assert st == st_ref == ZC_OK and m == n and np.array_equal(y.view(np.uint32), y_ref.view(np.uint32))
+        # back through the compressor: the values are grid points, the stream comes back unchanged
+        st, s2, _ = u.gpu_compress(y_ref, eb)
+        st_ref, s2_ref, _ = zcref.compress(y_ref, eb)
+        assert st == st_ref and s2.tobytes() == s2_ref.tobytes(), u.first_diff(s2, s2_ref)
+    st_ref, r_ref, total_ref = zcref.reduce(streams)
+    st, r, total = u.gpu_reduce(streams, n)
+    assert st == st_ref == ZC_OK and r.tobytes() == r_ref.tobytes(), u.first_diff(r, r_ref)
+    local = zcref.decompress(streams[1])[1]
+    for op in (zcref.OP_SUM, zcref.OP_MAX, zcref.OP_MIN):
+        st_ref, t_ref, _ = zcref.reduce_step(streams[0], local, op=op)
+        st, t, _ = u.gpu_reduce_step(streams[0], local, op=op)
+        assert st == st_ref and st in (ZC_OK, ZC_ERR_BOUND) and t.tobytes() == t_ref.tobytes(), u.first_diff(t, t_ref)
+    st, outs, ns = u.gpu_decompress_many(streams, [n, n, n])
+    assert st == ZC_OK
+    for o, s in zip(outs, streams):
+        assert np.array_equal(o[:n].view(np.uint32), zcref.decompress(s)[1].view(np.uint32))
+    first = 2048 * int(rng.integers(0, n // 2048 + 1))
+    st_ref, part_ref, m_ref = zcref.decompress_range(streams[2], first, 5000, out_cap_elems=5000)
+    st, part, m = _gpu_range(u, streams[2], first, 5000, ws_n=n)
+    assert st == st_ref == ZC_OK and m == m_ref and np.array_equal(part.view(np.uint32), part_ref.view(np.uint32))
