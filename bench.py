@@ -333,6 +333,26 @@ def main():
         ms_avg = timed(lambda: zc.zc_decompress_average(d_red, r_bytes, d_avg, ws_d, sync=False))
         st, n_avg = zc.zc_finish(ws_d)
         check(st, "decompress_average extra")
+        # the field compressed in 8 parts (zc_compress_part), and decompressed in 8 chunks (zc_decompress_range)
+        part = n // 8
+
+        def in_parts():
+            for i in range(8):
+                zc.zc_compress_part(x, n, eb, i * part, part if i < 7 else n - 7 * part, d_stream, ws_c, sync=False)
+
+        def in_chunks():
+            for i in range(8):
+                zc.zc_decompress_range(d_stream, c_bytes, i * part, part, d_y[i * part:(i + 1) * part], ws_d, sync=False)
+
+        if part % 16384 == 0:
+            ms_parts = timed(in_parts)
+            st, b_parts = zc.zc_finish(ws_c)
+            check(st, "compress_part extra")
+            assert b_parts == c_bytes
+            ms_chunks = timed(in_chunks)
+            st, _ = zc.zc_finish(ws_d)
+            check(st, "decompress_range extra")
+            extras["pipelined"] = {"compress_in_8_parts_ms": round(ms_parts, 4), "decompress_in_8_chunks_ms": round(ms_chunks, 4)}
         extras["other_ops"] = {"reduce_step_max_ms": round(ms_max, 4),
                                "decompress_average": {"ms": round(ms_avg, 4), "values": n_avg,
                                                       "hbm_frac": round((r_bytes + 4 * m) / ms_avg / 1e6 / HBM_PEAK_GBS, 4)}}

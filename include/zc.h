@@ -77,6 +77,23 @@ int zc_compress(const float* d_in, size_t n, float abs_eb,
                 void* d_out, size_t out_cap, size_t* out_bytes,
                 void* d_ws, size_t ws_bytes, void* hip_stream);
 
+/* zc_compress in parts (Section 3.5.2 produces a buffer chunk by chunk, so that a chunk can be
+ * sent while the next one is being compressed): this call compresses the values
+ * [first_value, first_value + count) of the n values at d_in into the stream at d_out.  The
+ * parts of one stream are given in ascending order, without gaps, to the same d_out and d_ws,
+ * on one HIP stream (or ordered by events), starting with first_value = 0, which also writes
+ * header and table padding; first_value and count are multiples of 16384, except that the
+ * last part ends at n.  n and abs_eb are the same in every part; only the values of the
+ * part need to be in place at d_in when it is given.  After a part has run, the stream's tables
+ * and payload up to its end are final, and out_bytes (or zc_finish) tells how many bytes of the
+ * stream that is; of an indexed stream (zc_set_indexed_streams) header and index then describe
+ * a stream that can be read up to there (zc_decompress_range) while later parts are produced.
+ * After the last part the stream is the one zc_compress writes.  Errors of all parts
+ * accumulate in the workspace.  Errors: as zc_compress, and ARG for a part that is not as above. */
+int zc_compress_part(const float* d_in, size_t n, float abs_eb, size_t first_value, size_t count,
+                     void* d_out, size_t out_cap, size_t* out_bytes,
+                     void* d_ws, size_t ws_bytes, void* hip_stream);
+
 /* fZ-light decompression (inverse of the stages of Section 3.3).  d_in: stream of in_bytes
  * bytes (trailing bytes beyond total_bytes are ignored), 16-byte aligned.  d_out: room for
  * out_cap_elems binary32 values, 16-byte aligned.  n_out (host, may be NULL): receives n.

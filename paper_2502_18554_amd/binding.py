@@ -17,7 +17,7 @@ ZC_OK, ZC_ERR_ARG, ZC_ERR_CAPACITY, ZC_ERR_FORMAT, ZC_ERR_NONFINITE, ZC_ERR_RANG
 ZC_MAX_K = 64
 
 EXPORTS = [
-    "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_decompress", "zc_decompress_many",
+    "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_compress_part", "zc_decompress", "zc_decompress_many",
     "zc_reduce_compressed", "zc_reduce_step", "zc_reduce_step_op", "zc_decompress_average", "zc_decompress_range", "zc_quality",
     "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
     "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out", "zc_set_indexed_streams",
@@ -46,6 +46,7 @@ def lib():
         L.zc_workspace_bytes.restype = sz
         L.zc_workspace_bytes.argtypes = [sz, C.c_int]
         L.zc_compress.argtypes = [vp, sz, C.c_float, vp, sz, szp, vp, sz, vp]
+        L.zc_compress_part.argtypes = [vp, sz, C.c_float, sz, sz, vp, sz, szp, vp, sz, vp]
         L.zc_decompress.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_compressed.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_step.argtypes = [vp, sz, vp, sz, vp, sz, szp, vp, sz, vp]
@@ -96,6 +97,16 @@ def zc_compress(d_in, n, abs_eb, d_out, d_ws, sync=True, stream=None, out_cap=No
     st = lib().zc_compress(_p(d_in), n, abs_eb, _p(d_out), cap,
                            C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
                            _stream(stream))
+    return st, (nbytes.value if sync else None)
+
+
+def zc_compress_part(d_in, n, abs_eb, first_value, count, d_out, d_ws, sync=True, stream=None, out_cap=None):
+    """One part of a stream compressed in parts.  Returns (status, bytes of the stream final so far)."""
+    nbytes = C.c_size_t(0)
+    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
+    st = lib().zc_compress_part(_p(d_in), int(n), float(abs_eb), int(first_value), int(count), _p(d_out), cap,
+                                C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
+                                _stream(stream))
     return st, (nbytes.value if sync else None)
 
 

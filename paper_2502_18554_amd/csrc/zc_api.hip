@@ -164,6 +164,7 @@ void fill_compress_args(CompressArgs& ca, const float* d_in, u64 n, float abs_eb
   ca.desc = l.desc;
   ca.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
   ca.ix = g_indexed;
+  ca.part_end = 0;
 }
 
 }  // namespace
@@ -262,6 +263,36 @@ static int decompress_one(const void* d_in, size_t in_bytes, float* d_out, size_
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!n_out) return ZC_OK;
   return finish(d_ws, n_out, stream);
+}
+
+int zc_compress_part(const float* d_in, size_t n, float abs_eb, size_t first_value, size_t count, void* d_out,
+                     size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (!eb_valid(abs_eb) || n > ZC_MAX_N || (n && !d_in) || !d_out || !d_ws) return ZC_ERR_ARG;
+  if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
+  if (first_value > n || count > n - first_value || first_value % kPackValues != 0) return ZC_ERR_ARG;
+  const bool to_the_end = first_value + count == n;
+  if (!to_the_end && count % kPackValues != 0) return ZC_ERR_ARG;
+  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
+  const u64 nb = num_blocks(n);
+  const u64 ntiles = num_pack_tiles(nb);
+  if (l.tiles_cap < 1 || num_tiles(nb) > l.tiles_cap) return ZC_ERR_ARG;
+  CompressArgs ca;
+  fill_compress_args(ca, d_in, n, abs_eb, d_out, out_cap, l);
+  if (first_value == 0) launch_init(l, u32(ntiles), ca.out, out_cap, n, ca.eb_bits, stream);
+  else if (ca.ticketed) hipLaunchKernelGGL(clear_tickets_kernel, dim3(1), dim3(64), 0, stream, l.ctl);
+  const u32 first_tile = u32(first_value / kPackValues);
+  const u32 full_tiles = u32(n / kPackValues);                          // tiles whose values all exist
+  const u32 end_tile = to_the_end ? u32(ntiles) : u32((first_value + count) / kPackValues);
+  const u32 end_full = end_tile < full_tiles ? end_tile : full_tiles;
+  ca.part_end = end_tile;
+  if (end_full > first_tile)
+    hipLaunchKernelGGL(compress_kernel<true>, dim3(end_full - first_tile), dim3(kPackThreads), 0, stream, ca, first_tile, end_full);
+  if (end_tile > full_tiles)                                            // the ragged last tile of the stream
+    hipLaunchKernelGGL(compress_kernel<false>, dim3(1), dim3(kPackThreads), 0, stream, ca, full_tiles, u32(ntiles));
+  if (!launch_ok()) return ZC_ERR_HIP;
+  if (!out_bytes) return ZC_OK;
+  return finish(d_ws, out_bytes, stream);
 }
 
 int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,

@@ -40,6 +40,7 @@ struct CompressArgs {
   u64* desc;
   u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
   u32 ix;            // write an indexed stream (see index_bytes)
+  u32 part_end;      // zc_compress_part: one past the last tile of this call; else 0
 };
 
 // Round-to-nearest-even of r for |r| < 2^31 as the low word of r + 1.5 * 2^52.
@@ -255,10 +256,10 @@ __device__ inline void wide_tile(const CompressArgs& a, const PayloadSink& sink,
   finish_stream(sink, pl, tile, ntiles, tb);
 }
 
-// One workgroup per tile.  FULL = the launch covers the tiles whose 16384 values all exist
-// (pure 16-byte loads, no tail), tile = workgroup id or a ticket (see take_tile) over
-// [0, end_tile); the ragged last tile of an input runs as a second launch of one workgroup
-// with FULL = false on tile first_tile.
+// One workgroup per tile.  FULL = the launch covers tiles whose 16384 values all exist
+// (pure 16-byte loads, no tail), tile = first_tile + workgroup id, or + a ticket (see
+// take_tile), over [first_tile, end_tile); the ragged last tile of an input runs as a launch
+// of its own, of one workgroup, with FULL = false on tile first_tile.
 template <bool FULL>
 __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
   __shared__ __attribute__((aligned(16))) u32 lds[kPackWaves * kWaveStage];
@@ -276,9 +277,12 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
 
   u32 tile = first_tile;
   if (FULL) {
-    tile = blockIdx.x;                       // tiles in the order in which workgroups start
+    tile = first_tile + blockIdx.x;          // tiles in the order in which workgroups start
     if (a.ticketed) {                        // ... or handed out by tickets, see take_tile
-      if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, end_tile, xcc_id());
+      if (threadIdx.x == 0) {
+        const u32 t = take_tile(a.ctl, end_tile - first_tile, xcc_id());
+        sh_tile = t == kNoTile ? kNoTile : first_tile + t;
+      }
       __syncthreads();
       tile = uniform(sh_tile);
     }
@@ -325,7 +329,7 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
     tile_wmax = uniform(tile_wmax);
     // publish the tile's size as early as possible: the tiles after this one wait for it
     pl.tile_wide = a.ix && tile_wmax > 15;
-    const PayloadSink sink{a.out, a.out_cap, a.nb, a.ctl, a.desc, a.ix != 0};
+    const PayloadSink sink{a.out, a.out_cap, a.nb, a.ctl, a.desc, a.ix != 0, a.part_end};
     if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
 
     // ---- fields -> sign + plane words in registers, then the back half ----
@@ -365,6 +369,11 @@ struct InitArgs {
   u32 eb_bits, nsum;
   bool ix;
 };
+
+// Tile tickets start from zero again for the next part of a stream produced in parts.
+__global__ void clear_tickets_kernel(Control* ctl) {
+  if (threadIdx.x < u32(kTicketShards)) *ticket_counter(ctl, threadIdx.x) = 0;
+}
 
 __global__ void init_kernel(InitArgs a) {
   const u64 gid = u64(blockIdx.x) * blockDim.x + threadIdx.x;

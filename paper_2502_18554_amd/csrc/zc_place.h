@@ -19,6 +19,7 @@ struct PayloadSink {
   Control* ctl;
   u64* desc;        // look-back descriptors
   bool ix;          // the stream carries a segment index (see index_bytes)
+  u32 part_end;     // a stream produced in parts (zc_compress_part): one past the last tile of this part; else 0
 };
 
 // Per-wave view of where its payload goes.
@@ -153,8 +154,10 @@ __device__ inline void write_index_entry(const PayloadSink& s, u32 seg, u64 seg_
 }
 
 // The last tile knows the size of the stream, and of an indexed one whether it holds wide blocks.
+// The last tile of a part of a stream that is produced in parts writes the same for the stream
+// so far: what has been produced is then a stream that can be read up to there.
 __device__ inline void finish_stream(const PayloadSink& s, const Placement& pl, u32 tile, u32 ntiles, const TileBase& tb) {
-  if (tile == ntiles - 1 && threadIdx.x == 0) {
+  if ((tile == ntiles - 1 || tile + 1 == s.part_end) && threadIdx.x == 0) {
     const u64 words = tb.words + pl.tile_total;
     const u64 total = tables_end(s.nb, s.ix) + 4 * words;
     s.ctl->result = total;
@@ -164,6 +167,10 @@ __device__ inline void finish_stream(const PayloadSink& s, const Placement& pl, 
       u32* hw = reinterpret_cast<u32*>(s.out);
       hw[1] = kVersionIndexed | (tb.wide_so_far ? 1u : 0u);
       hw[kHeaderBytes / 4 + num_segments(s.nb)] = u32(words);      // the closing entry of the index
+      // the end of a part is where the next part's first segment will start: its entry, ahead of time,
+      // lets the last segment of this part be checked and read before the next part exists
+      const u64 next_seg = u64(tile + 1) * (blockDim.x >> 6);
+      if (next_seg < num_segments(s.nb)) hw[kHeaderBytes / 4 + next_seg] = u32(words);
     }
   }
 }

@@ -895,3 +895,64 @@ def test_random_width_mixtures(zcref, seed, n, p_wide):
     st_ref, part_ref, m_ref = zcref.decompress_range(streams[2], first, 5000, out_cap_elems=5000)
     st, part, m = _gpu_range(u, streams[2], first, 5000, ws_n=n)
     assert st == st_ref == ZC_OK and m == m_ref and np.array_equal(part.view(np.uint32), part_ref.view(np.uint32))
+
+
+# ---------------- a stream produced in parts ----------------
+PACK = 16384          # values of a tile of the compression kernel
+
+
+def test_compress_in_parts_matches_reference(zcref, stream_variant):
+    u = _u()
+    n = 5 * PACK + 1000
+    x = synth.power_law_field((n // 4096 + 1, 64, 64), seed=700).numpy().ravel()[:n]
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    st_ref, s_ref, total_ref = zcref.compress(x, eb)
+    _, _, _, off = zcref.inspect(s_ref)
+    nb = (n + 31) // 32
+    d_in = u.to_dev(x)
+    cap = zc.zc_compress_bound(n)
+    d_out = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device=u.DEV)
+    ws = u.workspace(n)
+    parts = [(0, PACK), (PACK, 2 * PACK), (3 * PACK, n - 3 * PACK)]
+    for first, count in parts:
+        st, so_far = zc.zc_compress_part(d_in, n, eb, first, count, d_out, ws, out_cap=cap)
+        assert st == ZC_OK
+        end_block = (first + count + 31) // 32
+        want = u.tables_end(nb) + (int(off[end_block]) if end_block < nb else total_ref - u.tables_end(nb))
+        assert so_far == want, (first, count, so_far, want)
+        if stream_variant == "indexed" and first + count < n:
+            # what exists so far can be read: the first part alone, then a range that ends with the part
+            part = torch.full((first + count,), float("nan"), dtype=torch.float32, device=u.DEV)
+            st, m = zc.zc_decompress_range(d_out, so_far, 0, first + count, part, u.workspace(n))
+            assert st == ZC_OK and m == first + count
+            assert np.array_equal(part.cpu().numpy().view(np.uint32), zcref.decompress(s_ref)[1][:first + count].view(np.uint32))
+            big = torch.empty(n, dtype=torch.float32, device=u.DEV)
+            st, m = zc.zc_decompress_range(d_out, so_far, first + count - 2048, 10 ** 6, big, u.workspace(n))
+            assert st == ZC_ERR_FORMAT          # ... and not beyond
+    got = d_out[:total_ref].cpu().numpy()
+    assert so_far == total_ref and got.tobytes() == s_ref.tobytes(), u.first_diff(got, s_ref)
+    assert bool((d_out[cap:] == 0xA5).all())
+    # one part that is everything; a part of nothing; the asynchronous form
+    d_out.fill_(0x5A)
+    st, total = zc.zc_compress_part(d_in, n, eb, 0, n, d_out, ws, out_cap=cap)
+    assert st == ZC_OK and d_out[:total].cpu().numpy().tobytes() == s_ref.tobytes()
+    d_out.fill_(0x5A)
+    for first, count in parts:
+        st, _ = zc.zc_compress_part(d_in, n, eb, first, count, d_out, ws, sync=False, out_cap=cap)
+        assert st == ZC_OK
+    st, total = zc.zc_finish(ws)
+    assert st == ZC_OK and d_out[:total].cpu().numpy().tobytes() == s_ref.tobytes()
+    st, total = zc.zc_compress_part(d_in[:0], 0, eb, 0, 0, d_out, ws, out_cap=cap)
+    assert st == ZC_OK and d_out[:total].cpu().numpy().tobytes() == zcref.compress(x[:0], eb)[1].tobytes()
+    # errors of a part show at the end, and parts that do not fit the rules are refused
+    bad = x.copy(); bad[PACK + 5] = np.nan
+    d_bad = u.to_dev(bad)
+    assert zc.zc_compress_part(d_bad, n, eb, 0, PACK, d_out, ws, out_cap=cap)[0] == ZC_OK
+    assert zc.zc_compress_part(d_bad, n, eb, PACK, PACK, d_out, ws, out_cap=cap)[0] == ZC_ERR_NONFINITE
+    assert zc.zc_compress_part(d_bad, n, eb, 2 * PACK, n - 2 * PACK, d_out, ws, out_cap=cap)[0] == ZC_ERR_NONFINITE
+    assert zc.zc_compress_part(d_in, n, eb, 100, PACK, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
+    assert zc.zc_compress_part(d_in, n, eb, 0, 100, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
+    assert zc.zc_compress_part(d_in, n, eb, 5 * PACK, 1001, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
+    assert zc.zc_compress_part(d_in, n, eb, 6 * PACK, 0, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
+    st, need = zc.zc_compress_part(d_in, n, eb, 0, n, d_out, ws, out_cap=total_ref - 4)
+    assert st == ZC_ERR_CAPACITY and need == total_ref

@@ -58,6 +58,10 @@ def test_argument_checks_without_gpu(libzc):
     assert libzc.zc_compress(0x1000, 10, 0.0, 0x2000, 100, None, 0x3000, 4096, None) == 1      # eb
     assert libzc.zc_compress(0x1004, 10, 1e-3, 0x2000, 100, None, 0x3000, 4096, None) == 1     # alignment
     assert libzc.zc_compress(0x1000, 1 << 20, 1e-3, 0x2000, 100, None, 0x3000, 64, None) == 1  # workspace
+    libzc.zc_compress_part.argtypes = [vp, sz, C.c_float, sz, sz, vp, sz, C.POINTER(sz), vp, sz, vp]
+    assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 100, 16384, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None) == 1   # not at a tile
+    assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 0, 100, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None) == 1       # not a whole tile
+    assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 1 << 20, 16384, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None) == 1  # past the end
     assert libzc.zc_set_tile_hand_out(7) == 1 and libzc.zc_set_tile_hand_out(1) == 0 and libzc.zc_set_tile_hand_out(0) == 0
     assert libzc.zc_decompress(None, 100, None, 0, None, None, 0, None) == 1
     assert libzc.zc_decompress(0x1000, 16, 0x2000, 8, None, 0x3000, 4096, None) == 3           # shorter than a header
