@@ -115,7 +115,8 @@ int zc_decompress_average(const void* d_in, size_t in_bytes, float* d_out, size_
  * [first_value, first_value + count) of the stream, cut off at its end, go to d_out[0 ...].
  * first_value must be a multiple of 2048 (a segment of 64 blocks).  Only the header, the tables
  * and the payload of those segments are read; of an indexed stream (zc_set_indexed_streams)
- * not even the whole width table, only the index entries and width bytes of the segments.
+ * not even the whole width table, only the index entries and width bytes of the segments
+ * (of a plain stream the whole width table is summed first, in every call).
  * The workspace must be large enough for the whole stream (zc_workspace_bytes(n, 1)).
  * n_out (host, may be NULL): receives how many values that is.
  * Errors: ARG (also: first_value not a multiple of 2048, or beyond the stream's n), FORMAT,

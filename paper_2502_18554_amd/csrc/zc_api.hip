@@ -321,10 +321,9 @@ int zc_decompress_range(const void* d_in, size_t in_bytes, size_t first_value, s
   u64 grid = (wanted + kTileValues - 1) / kTileValues;
   if (grid > kMaxTiles) grid = kMaxTiles;
   if (grid < 1) grid = 1;
-  // the index of a plain stream has to reach the end of the part
-  u64 tiles = first_value / kTileValues + 1 + grid;
-  const u64 tiles_in = num_tiles(blocks_bound(in_bytes));
-  if (tiles > tiles_in) tiles = tiles_in;
+  // the positions of a plain stream come from sums over its whole width table, which the
+  // validation of total_bytes needs in any case
+  u64 tiles = num_tiles(blocks_bound(in_bytes));
   if (tiles > l.tiles_cap) tiles = l.tiles_cap;
   if (tiles > kMaxTiles) tiles = kMaxTiles;
   if (tiles < 1) tiles = 1;

@@ -184,6 +184,50 @@ def test_field_512cube(zcref, rel):
     assert st == ZC_OK and total2 == total and torch.equal(buf2[:total], buf[:total])
 
 
+def test_field_512cube_in_parts_and_chunks(zcref):
+    """Configuration 2 produced by zc_compress_part in 8 parts and read back by zc_decompress_range in 8
+    chunks: the stream is byte for byte that of zc_compress (whose slices the test above compares with the
+    reference), every chunk holds the values of the whole decompression, and slices of both agree with
+    the reference once more."""
+    rng = np.random.default_rng(77)
+    x = synth.power_law_field((512, 512, 512), seed=0, device=DEV)
+    n = x.numel()
+    eb = synth.abs_bound(x, 1e-3)
+    ws = u8(zc.zc_workspace_bytes(n, 1))
+    st, whole, total = compress_async(x, eb, ws)
+    assert st == ZC_OK
+    buf = u8(zc.zc_compress_bound(n))
+    buf.fill_(0xA5)
+    part = n // 8
+    so_far = []
+    for i in range(8):
+        st, b = zc.zc_compress_part(x, n, eb, i * part, part, buf, ws)
+        assert st == ZC_OK
+        so_far.append(b)
+    assert so_far == sorted(so_far) and so_far[-1] == total
+    assert torch.equal(buf[:total], whole[:total])
+    s = Stream(buf, total, n)
+    check_header_and_sizes(s, eb)
+    # the size after part i is where block i * part / 32 starts
+    for i in range(7):
+        assert so_far[i] == s.tend + 4 * int(s.off[(i + 1) * part // 32])
+    y = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    y_whole = torch.empty(n, dtype=torch.float32, device=DEV)
+    st, _ = decompress_async(buf, total, y_whole, ws)
+    assert st == ZC_OK
+    for i in range(8):
+        st, m = zc.zc_decompress_range(buf, total, i * part, part, y[i * part:(i + 1) * part], ws)
+        assert st == ZC_OK and m == part, (i, st, m)
+    assert torch.equal(y.view(torch.int32), y_whole.view(torch.int32))
+    # an odd chunk: starts at a segment that is not a tile's first, ends inside a block
+    first, count = 2048 * 12345, 3 * 8192 + 17
+    z = torch.full((count + 8,), float("nan"), dtype=torch.float32, device=DEV)
+    st, m = zc.zc_decompress_range(buf, total, first, count, z, ws, out_cap_elems=count)
+    assert st == ZC_OK and m == count
+    assert torch.equal(z[:count].view(torch.int32), y_whole[first:first + count].view(torch.int32)) and bool(torch.isnan(z[count:]).all())
+    check_slices_against_reference(zcref, x, eb, s, y, rng, count=3)
+
+
 def _rank_buffers(k=8):
     return [synth.power_law_field((256, 512, 512), seed=100 + r, device=DEV) for r in range(k)]
 
