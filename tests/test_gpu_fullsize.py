@@ -303,7 +303,21 @@ def _allreduce_8x64M(zcref):
     for x in xs:
         exact += x.double()
     assert float((y.double() - exact).abs().max()) <= 8 * eb
+    # the Average aggregation: the same stream decoded and divided by its nsum; within eb of the exact
+    # mean, and bit for bit the reference's averaging decompression on a sampled slice
+    ya = torch.full((m,), float("nan"), dtype=torch.float32, device=DEV)
+    st, _ = zc.zc_decompress_average(red, total, ya, ws, sync=False)
+    assert st == ZC_OK
+    st, n_avg = zc.zc_finish(ws)
+    assert st == ZC_OK and n_avg == m
+    assert float((ya.double() - exact / 8).abs().max()) <= eb * (1 + 1e-6)
     del exact
+    b0 = sample_starts(m, rng, 3)[1]
+    v0, v1 = 32 * b0, min(m, 32 * b0 + SLICE)
+    st, ref, _ = zcref.reduce([zcref.compress(x[v0:v1].cpu().numpy(), eb)[1] for x in xs])
+    assert st == 0
+    st, ya_ref, _ = zcref.decompress(ref, average=True)
+    assert st == 0 and np.array_equal(ya[v0:v1].cpu().numpy().view(np.uint32), ya_ref.view(np.uint32))
     # sampled slices: the reference reduce of the operands' slices reproduces the GPU stream there
     for b0 in sample_starts(m, rng, 4):
         v0, v1 = 32 * b0, min(m, 32 * b0 + SLICE)
