@@ -379,6 +379,23 @@ def test_ring_rounds_64M(zcref):
     for x in xs:
         exact += x.double()
     assert float((y_prev.double() - exact).abs().max()) <= 4 * eb
+    del exact
+    # the same ring with Max rounds: the result is the stream of the elementwise maximum compressed once
+    st, buf, total = compress_async(xs[0], eb, ws)
+    assert st == ZC_OK
+    for i in range(1, 4):
+        out = u8(zc.zc_compress_bound(m))
+        st, _ = zc.zc_reduce_step_op(buf, total, xs[i], m, zc.binding.ZC_OP_MAX, out, ws, sync=False)
+        assert st == ZC_OK
+        st, total = zc.zc_finish(ws)
+        assert st == ZC_OK
+        buf = out
+    top = torch.maximum(torch.maximum(xs[0], xs[1]), torch.maximum(xs[2], xs[3]))
+    st, direct, total_d = compress_async(top, eb, ws)
+    assert st == ZC_OK and total_d == total
+    assert torch.equal(buf[:20], direct[:20]) and torch.equal(buf[24:total], direct[24:total])      # all but nsum (4 against 1)
+    st, _ = decompress_async(buf, total, y_next, ws)
+    assert st == ZC_OK and max_abs_err(top, y_next) <= eb
 
 
 def test_hard_mix_256M(zcref):
