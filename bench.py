@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--side", type=int, default=512, help="field side; 512 is the benchmark configuration")
     ap.add_argument("--streams", choices=("plain", "indexed"), default="indexed",
                     help="stream variant of every call: indexed streams carry a segment index (zc_set_indexed_streams)")
+    ap.add_argument("--settle-ms", type=float, default=100.0,
+                    help="untimed steps run for this long before the warmup steps: the first milliseconds of work on an "
+                         "idle GPU run several percent slow")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed sweep over the other error bounds")
     ap.add_argument("--copy-probe", action="store_true",
@@ -134,6 +137,11 @@ def main():
         if events:
             events[3].record()
 
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:      # untimed, before the warmup steps
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -410,7 +418,7 @@ def main():
         "dtype": "f64+u32", "data": "synthetic",
         "config": {"workload": f"{side}^3 fp32 power-law Gaussian field, rel eb {args.rel:g}: compress + decompress; "
                                f"fused reduce of {K} compressed rank buffers of {m} values",
-                   "streams": args.streams, "block": 32, "abs_eb": eb, "compressed_bytes": c_bytes, "ratio": round(4 * n / c_bytes, 3),
+                   "streams": args.streams, "settle_ms": args.settle_ms, "block": 32, "abs_eb": eb, "compressed_bytes": c_bytes, "ratio": round(4 * n / c_bytes, 3),
                    "reduce_in_bytes": sum(chunk_bytes), "reduce_out_bytes": r_bytes},
         "roofline": dict(stages[dominant]["roofline"], kernel=dominant + "_kernel"),
         "stages": stages,
