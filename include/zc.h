@@ -236,13 +236,15 @@ int zc_set_indexed_streams(int on);
 int zc_set_tile_hand_out(int mode);
 
 /* Measurement aid (not part of the method).  While enabled, zc_compress, zc_decompress,
- * zc_decompress_many, zc_reduce_compressed and zc_reduce_step record a pair of HIP events on the call's stream around
- * their main kernel (the compress kernel over the full tiles, the decompress, reduce or step kernel;
- * not the small set-up kernels before it).  zc_profile_collect waits for the recorded pairs,
+ * zc_decompress_average, zc_decompress_many, zc_reduce_compressed, zc_reduce_step and
+ * zc_reduce_step_op hand a pair of HIP events to the launch of their main kernel on the call's
+ * stream (hipExtLaunchKernelGGL), which stamps them with that kernel's start and end (the
+ * compress kernel over the full tiles, the decompress, reduce or step kernel; not the small
+ * set-up kernels before it).  zc_profile_collect waits for the recorded pairs,
  * stores up to cap elapsed times in milliseconds in ms[] and the matching ZC_KERNEL_* ids in
  * kernel[] (host arrays, either may be NULL) in call order, forgets them, and returns how
  * many it stored (a negative status on a HIP error).  The events are host objects created on
- * first use and reused; with the hand-out mode above this is the only state the library keeps.  Enabling or disabling
+ * first use and reused.  Enabling or disabling
  * forgets the pairs recorded so far. */
 #define ZC_KERNEL_COMPRESS 1
 #define ZC_KERNEL_DECOMPRESS 2

@@ -1,6 +1,7 @@
 // C ABI of the zc library: argument checks and kernel launches.  All arithmetic of the
 // method runs in the kernels; the host only divides once (1 / step) and launches.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstring>
@@ -41,7 +42,8 @@ struct KernelTimer {
   struct Slot { hipEvent_t a, b; int kind; };
   std::vector<Slot> pool;   // events are created once and reused
   size_t used = 0;
-  Slot* begin(int kind, hipStream_t stream) {
+  // A pair of events for one launch, or null when timing is off.
+  Slot* take(int kind) {
     std::lock_guard<std::mutex> g(mu);
     if (!on) return nullptr;
     if (used == pool.size()) {
@@ -53,14 +55,20 @@ struct KernelTimer {
     }
     Slot* s = &pool[used++];
     s->kind = kind;
-    (void)hipEventRecord(s->a, stream);
     return s;
-  }
-  void end(Slot* s, hipStream_t stream) {
-    if (s) (void)hipEventRecord(s->b, stream);
   }
 };
 KernelTimer g_timer;
+
+// Launch of an entry point's main kernel.  When timing is on the two events are handed to the
+// launch itself, which stamps them with the kernel's own start and end on its stream: no
+// separate event records, which would each hold back the launch behind them.
+template <typename... Args>
+void launch_main(int kind, void (*kernel)(Args...), dim3 grid, dim3 block, hipStream_t stream, Args... args) {
+  KernelTimer::Slot* slot = g_timer.take(kind);
+  if (slot) hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, slot->a, slot->b, 0, args...);
+  else hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
+}
 
 // How the kernels that write a stream hand out their tiles (zc_set_tile_hand_out).
 int g_hand_out = ZC_HAND_OUT_DISPATCH_ORDER;
@@ -211,10 +219,8 @@ int zc_compress(const float* d_in, size_t n, float abs_eb, void* d_out, size_t o
   fill_compress_args(ca, d_in, n, abs_eb, d_out, out_cap, l);
   launch_init(l, u32(ntiles), ca.out, out_cap, n, ca.eb_bits, stream);
   const u32 full_tiles = u32(n / kPackValues);      // tiles whose values all exist
-  KernelTimer::Slot* slot = full_tiles ? g_timer.begin(ZC_KERNEL_COMPRESS, stream) : nullptr;
   if (full_tiles)
-    hipLaunchKernelGGL(compress_kernel<true>, dim3(full_tiles), dim3(kPackThreads), 0, stream, ca, 0u, full_tiles);
-  g_timer.end(slot, stream);
+    launch_main(ZC_KERNEL_COMPRESS, compress_kernel<true>, dim3(full_tiles), dim3(kPackThreads), stream, ca, 0u, full_tiles);
   if (ntiles > full_tiles)                          // the ragged last tile
     hipLaunchKernelGGL(compress_kernel<false>, dim3(1), dim3(kPackThreads), 0, stream, ca, full_tiles, u32(ntiles));
   if (!launch_ok()) return ZC_ERR_HIP;
@@ -255,11 +261,9 @@ static int decompress_one(const void* d_in, size_t in_bytes, float* d_out, size_
   da.ctl = l.ctl;
   da.first_value = 0;
   da.count = ~u64(0);
-  KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_DECOMPRESS, stream);
-  auto kernel = average ? (g_indexed ? decompress_kernel<true, true> : decompress_kernel<false, true>)
-                        : (g_indexed ? decompress_kernel<true, false> : decompress_kernel<false, false>);
-  hipLaunchKernelGGL(kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, da);
-  g_timer.end(slot, stream);
+  void (*kernel)(DecompressArgs) = average ? (g_indexed ? decompress_kernel<true, true> : decompress_kernel<false, true>)
+                                           : (g_indexed ? decompress_kernel<true, false> : decompress_kernel<false, false>);
+  launch_main(ZC_KERNEL_DECOMPRESS, kernel, dim3(u32(tiles)), dim3(kTileThreads), stream, da);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!n_out) return ZC_OK;
   return finish(d_ws, n_out, stream);
@@ -388,10 +392,8 @@ int zc_decompress_many(const void* const* d_chunks, const size_t* chunk_bytes, i
   launch_index(sa, tiles, 1, stream);
   da.index = l.index;
   da.ctl = l.ctl;
-  KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_DECOMPRESS, stream);
-  hipLaunchKernelGGL(g_indexed ? decompress_many_kernel<true> : decompress_many_kernel<false>, dim3(u32(tiles), u32(k)),
-                     dim3(kTileThreads), 0, stream, da);
-  g_timer.end(slot, stream);
+  void (*kernel)(DecompressManyArgs) = g_indexed ? decompress_many_kernel<true> : decompress_many_kernel<false>;
+  launch_main(ZC_KERNEL_DECOMPRESS, kernel, dim3(u32(tiles), u32(k)), dim3(kTileThreads), stream, da);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!n_out) return ZC_OK;
   size_t total = 0;
@@ -444,9 +446,8 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   ra.ctl = l.ctl;
   ra.desc = l.desc;
   ra.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
-  KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_REDUCE, stream);
-  hipLaunchKernelGGL(g_indexed ? reduce_kernel<true> : reduce_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
-  g_timer.end(slot, stream);
+  void (*narrow)(ReduceArgs) = g_indexed ? reduce_kernel<true> : reduce_kernel<false>;
+  launch_main(ZC_KERNEL_REDUCE, narrow, dim3(u32(tiles)), dim3(kTileThreads), stream, ra);
   // for operands with blocks wider than 15 bits; returns at once otherwise
   hipLaunchKernelGGL(g_indexed ? reduce_wide_kernel<true> : reduce_wide_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), 0,
                      stream, ra);
@@ -492,13 +493,11 @@ int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_lo
   ta.ctl = l.ctl;
   ta.desc = l.desc;
   ta.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
-  KernelTimer::Slot* slot = g_timer.begin(ZC_KERNEL_REDUCE_STEP, stream);
   void (*kernel)(StepArgs) = nullptr;
   if (op == ZC_OP_SUM) kernel = g_indexed ? step_kernel<true, ZC_OP_SUM> : step_kernel<false, ZC_OP_SUM>;
   else if (op == ZC_OP_MAX) kernel = g_indexed ? step_kernel<true, ZC_OP_MAX> : step_kernel<false, ZC_OP_MAX>;
   else kernel = g_indexed ? step_kernel<true, ZC_OP_MIN> : step_kernel<false, ZC_OP_MIN>;
-  hipLaunchKernelGGL(kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ta);
-  g_timer.end(slot, stream);
+  launch_main(ZC_KERNEL_REDUCE_STEP, kernel, dim3(u32(tiles)), dim3(kTileThreads), stream, ta);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
