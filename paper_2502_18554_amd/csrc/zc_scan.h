@@ -238,9 +238,10 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
 }
 
 // Second step of the index, and set-up of the kernel that follows; one launch for all streams.
-// Workgroup 0: each wave takes streams (wave, wave + 4, ...): validates the header, turns the
-// span sizes into exclusive offsets in place, collects the spans' flags and checks that the
-// header's total_bytes equals tables + payload; thread 0 then writes the control block, so
+// Workgroup 0, plain streams: each wave takes streams (wave, wave + 4, ...): validates the
+// header, turns the span sizes into exclusive offsets in place, collects the spans' flags and
+// checks that the header's total_bytes equals tables + payload; indexed streams: one thread
+// per stream looks at header and index ends.  Thread 0 then writes the control block, so
 // nothing has to clear it beforehand.  All workgroups clear the look-back descriptors and the
 // tile tickets for the kernel that writes a stream (reduce).
 __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
@@ -254,8 +255,34 @@ __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
   ParsedHeader h0;
   h0.ok = false;
   if (a.check_match) h0 = parse_header(a.streams[0], a.ix);
-  for (int s = wave; s < a.k; s += 4) {
-    const ParsedHeader h = parse_header(a.streams[s], a.ix);
+  if (a.ix) {
+    // Indexed streams need no sums here, only a look at each header and at the two ends of each
+    // index (the waves that use a segment check the rest): one thread per stream, so that the
+    // dependent loads of all streams are in flight together, then the findings are folded.
+    for (int s = int(threadIdx.x); s < a.k; s += int(blockDim.x)) {
+      const ParsedHeader h = parse_header(a.streams[s], true);
+      if (!h.ok) {
+        status |= status_bit(ZC_ERR_FORMAT);
+        continue;
+      }
+      if (!stream_fits(h, a.index)) {
+        status |= status_bit(ZC_ERR_ARG);
+        continue;
+      }
+      if (a.check_match && h0.ok && (h0.n != h.n || h0.eb_bits != h.eb_bits)) status |= status_bit(ZC_ERR_MISMATCH);
+      const u32* index = reinterpret_cast<const u32*>(a.streams[s].base + kHeaderBytes);
+      const u64 nseg = num_segments(h.nb);
+      if (index[0] != 0 || tables_end(h.nb, true) + 4 * u64(index[nseg]) != h.total) status |= status_bit(ZC_ERR_FORMAT);
+      if (h.wide) wide = kFlagWide;
+    }
+    u32 folded = 0;
+    for (int code : {ZC_ERR_ARG, ZC_ERR_FORMAT, ZC_ERR_MISMATCH})
+      if (__any((status & status_bit(code)) != 0)) folded |= status_bit(code);
+    status = folded;
+    wide = __any(wide != 0) ? kFlagWide : 0u;
+  }
+  for (int s = wave; !a.ix && s < a.k; s += 4) {
+    const ParsedHeader h = parse_header(a.streams[s], false);
     if (!h.ok) {
       status |= status_bit(ZC_ERR_FORMAT);
       continue;
@@ -265,14 +292,6 @@ __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
       continue;
     }
     if (a.check_match && h0.ok && (h0.n != h.n || h0.eb_bits != h.eb_bits)) status |= status_bit(ZC_ERR_MISMATCH);
-    if (a.ix) {
-      // the two ends of the stream's own index; the waves that use a segment check the rest
-      const u32* index = reinterpret_cast<const u32*>(a.streams[s].base + kHeaderBytes);
-      const u64 nseg = num_segments(h.nb);
-      if (index[0] != 0 || tables_end(h.nb, true) + 4 * u64(index[nseg]) != h.total) status |= status_bit(ZC_ERR_FORMAT);
-      if (h.wide) wide = kFlagWide;
-      continue;
-    }
     const u64 nspans = num_spans(h.nb);
     u32* spans = a.index.span_off + u64(s) * a.index.spans_cap;
     const u32* flags = a.index.span_flags + u64(s) * a.index.spans_cap;
