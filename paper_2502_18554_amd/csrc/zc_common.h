@@ -65,7 +65,8 @@ struct Control {
   u32 status;                  // OR of status_bit()s
   u32 flags;                   // kFlagWide: some input stream has a block wider than 15 bits
   u64 result;                  // total_bytes, or n for decompress
-  u32 pad[12];
+  u64 nsum;                    // sum of the input streams' nsum fields (set by index_prep_kernel)
+  u32 pad[10];
 };
 static_assert(sizeof(Control) == 64, "control block is 64 bytes");
 

@@ -45,8 +45,7 @@ struct ReduceArgs {
 // Header fields and table padding of the output stream; one thread.
 __device__ inline void write_reduce_header(const ReduceArgs& a, const ParsedHeader& h, u32 ntiles, bool ix) {
   const u64 tend = tables_end(h.nb, ix);
-  u64 nsum = 0;
-  for (int s = 0; s < a.k; ++s) nsum += parse_header(a.in[s], ix).nsum;
+  const u64 nsum = a.ctl->nsum;            // of all operands, summed by the set-up kernel (every operand is valid here)
   if (nsum > 0xffffffffull) atomicOr(&a.ctl->status, status_bit(ZC_ERR_RANGE));
   if (a.out_cap >= tend) write_stream_header(a.out, h.n, h.nb, h.eb_bits, u32(nsum), ix, ntiles == 0);
   else atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));

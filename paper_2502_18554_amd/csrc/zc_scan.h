@@ -246,6 +246,9 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
 // tile tickets for the kernel that writes a stream (reduce).
 __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
   __shared__ u32 sh_status[4], sh_wide[4];
+  __shared__ unsigned long long sh_nsum;        // sum of the valid streams' nsum, for the kernel that writes a stream
+  if (threadIdx.x == 0) sh_nsum = 0;
+  __syncthreads();
   for (u64 i = u64(blockIdx.x) * blockDim.x + threadIdx.x; i < a.ndesc; i += u64(gridDim.x) * blockDim.x)
     a.desc[desc_slot(i)] = 0;
   if (blockIdx.x != 0) return;
@@ -274,6 +277,7 @@ __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
       const u64 nseg = num_segments(h.nb);
       if (index[0] != 0 || tables_end(h.nb, true) + 4 * u64(index[nseg]) != h.total) status |= status_bit(ZC_ERR_FORMAT);
       if (h.wide) wide = kFlagWide;
+      atomicAdd(&sh_nsum, static_cast<unsigned long long>(h.nsum));
     }
     u32 folded = 0;
     for (int code : {ZC_ERR_ARG, ZC_ERR_FORMAT, ZC_ERR_MISMATCH})
@@ -292,6 +296,7 @@ __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
       continue;
     }
     if (a.check_match && h0.ok && (h0.n != h.n || h0.eb_bits != h.eb_bits)) status |= status_bit(ZC_ERR_MISMATCH);
+    if (lane == 0) atomicAdd(&sh_nsum, static_cast<unsigned long long>(h.nsum));
     const u64 nspans = num_spans(h.nb);
     u32* spans = a.index.span_off + u64(s) * a.index.spans_cap;
     const u32* flags = a.index.span_flags + u64(s) * a.index.spans_cap;
@@ -318,6 +323,7 @@ __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
     a.ctl->status = sh_status[0] | sh_status[1] | sh_status[2] | sh_status[3];
     a.ctl->flags = sh_wide[0] | sh_wide[1] | sh_wide[2] | sh_wide[3];
     a.ctl->result = 0;
+    a.ctl->nsum = sh_nsum;
     for (int i = 0; i < kTicketShards; ++i) *ticket_counter(a.ctl, u32(i)) = 0;
   }
 }
