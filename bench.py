@@ -137,40 +137,56 @@ def main():
         if events:
             events[3].record()
 
+    def kernel_averages(records):
+        return {s: (sum(ms for name, ms in records if name == s) / max(1, sum(1 for name, _ in records if name == s)))
+                for s in stage_names}
+
+    # untimed, before the warmup steps; the kernels are timed here to learn which one runs longest
+    zc.zc_profile_enable(True)
     t_settle = time.perf_counter()
-    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:      # untimed, before the warmup steps
+    while True:
         for _ in range(10):
             step()
         torch.cuda.synchronize()
+        if (time.perf_counter() - t_settle) * 1e3 >= args.settle_ms:
+            break
+    settled = kernel_averages(zc.zc_profile_collect())
+    zc.zc_profile_enable(False)
+    dominant = max(stage_names, key=lambda s: settled[s])
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    zc.zc_profile_enable(True)            # HIP events around each main kernel, on the stream it runs on
+    # The timed region carries the timing of the dominant kernel only (HIP events handed to its launch, on
+    # the stream it runs on): every timed launch costs the step a few microseconds.
+    zc.zc_profile_enable(True, only=(dominant,))
     t0 = time.perf_counter()
     for i in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kernel_times = zc.zc_profile_collect()
+    timed_records = zc.zc_profile_collect()
     zc.zc_profile_enable(False)
     for ws, what in ((ws_c, "compress"), (ws_d, "decompress"), (ws_r, "reduce")):
         st, _ = zc.zc_finish(ws)
         check(st, what + " (timed loop)")
-    # per-call times (set-up kernels included) come from a second pass over the same steps with an
-    # event between the calls: an event record holds back the launch behind it by a few microseconds,
-    # which the timed region above should not pay
+    assert len(timed_records) == args.steps and all(name == dominant for name, _ in timed_records), len(timed_records)
+    # Per-call times (set-up kernels included) and the other kernels' times come from two more passes over
+    # the same steps, one with an event between the calls, one with every main kernel timed: an event record
+    # holds back the launch behind it by a few microseconds, which the timed region above should not pay.
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     for i in range(args.steps):
         step(evs[i])
     torch.cuda.synchronize()
+    zc.zc_profile_enable(True)
+    for i in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    kernel_ms = kernel_averages(zc.zc_profile_collect())
+    zc.zc_profile_enable(False)
+    kernel_ms[dominant] = sum(ms for _, ms in timed_records) / len(timed_records)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     stage_ms = {s: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, s in enumerate(stage_names)}
-    kernel_ms = {}
-    for s in stage_names:
-        ts = [ms for name, ms in kernel_times if name == s]
-        assert len(ts) == args.steps, (s, len(ts))
-        kernel_ms[s] = sum(ts) / len(ts)
     stages = {}
     for s in stage_names:
         # stage = the whole call (set-up kernels included); roofline = its main kernel alone
@@ -184,7 +200,6 @@ def main():
                          "traffic": PROFILED_TRAFFIC[args.streams][s] if (side == 512 and args.rel == 1e-4) else None},
             "algorithmic_bytes": alg_bytes[s],
         }
-    dominant = max(stage_names, key=lambda s: kernel_ms[s])
     total_fp32 = sum(fp32_bytes.values())
     value = total_fp32 / ms_per_step / 1e6
 

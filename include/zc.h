@@ -244,7 +244,8 @@ int zc_set_tile_hand_out(int mode);
  * stores up to cap elapsed times in milliseconds in ms[] and the matching ZC_KERNEL_* ids in
  * kernel[] (host arrays, either may be NULL) in call order, forgets them, and returns how
  * many it stored (a negative status on a HIP error).  The events are host objects created on
- * first use and reused.  Leave it disabled while a stream is being captured into a HIP graph.  Enabling or disabling
+ * first use and reused.  on: 0 off, 1 every kind of main kernel, or a sum of (1 << ZC_KERNEL_x) to time
+ * only those kinds (a timed launch costs a few microseconds).  Leave it disabled while a stream is being captured into a HIP graph.  Enabling or disabling
  * forgets the pairs recorded so far. */
 #define ZC_KERNEL_COMPRESS 1
 #define ZC_KERNEL_DECOMPRESS 2

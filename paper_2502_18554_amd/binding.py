@@ -223,7 +223,11 @@ def zc_debug_block_offsets(d_in, in_bytes, d_off_words, d_ws, stream=None):
 KERNEL_NAMES = {1: "compress", 2: "decompress", 3: "reduce", 4: "reduce_step"}
 
 
-def zc_profile_enable(on):
+def zc_profile_enable(on, only=None):
+    """Times the main kernels from now on (on=True), or stops (False).  only: names from KERNEL_NAMES to time just those."""
+    if on and only:
+        code = sum(1 << k for k, name in KERNEL_NAMES.items() if name in only)
+        return lib().zc_profile_enable(code)
     return lib().zc_profile_enable(1 if on else 0)
 
 

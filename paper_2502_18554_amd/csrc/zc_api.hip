@@ -38,14 +38,14 @@ bool launch_ok() { return hipGetLastError() == hipSuccess; }
 // Optional timing of the main kernel of each entry point (zc_profile_*): host-side state only.
 struct KernelTimer {
   std::mutex mu;
-  bool on = false;
+  unsigned kinds = 0;       // bit ZC_KERNEL_x set: the main kernels of that kind are timed
   struct Slot { hipEvent_t a, b; int kind; };
   std::vector<Slot> pool;   // events are created once and reused
   size_t used = 0;
   // A pair of events for one launch, or null when timing is off.
   Slot* take(int kind) {
     std::lock_guard<std::mutex> g(mu);
-    if (!on) return nullptr;
+    if (!(kinds & (1u << kind))) return nullptr;
     if (used == pool.size()) {
       Slot s;
       s.kind = 0;
@@ -548,7 +548,7 @@ int zc_set_tile_hand_out(int mode) {
 
 int zc_profile_enable(int on) {
   std::lock_guard<std::mutex> g(g_timer.mu);
-  g_timer.on = on != 0;
+  g_timer.kinds = on == 1 ? ~0u : unsigned(on) & ~1u;      // 1: every kind; else a set of (1 << ZC_KERNEL_x)
   g_timer.used = 0;
   return ZC_OK;
 }
