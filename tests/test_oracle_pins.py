@@ -732,3 +732,20 @@ def test_decompress_range_is_a_slice_of_the_whole(zcref, variant):
         assert zcref.decompress_range(s[:-1], 0, 10)[0] == zcref.ERR_FORMAT
     finally:
         zcref.set_indexed(False)
+
+
+# ---------------- P14: corrupted streams under the sanitizers ----------------
+def test_readers_survive_corrupted_streams_under_sanitizers(tmp_path):
+    """Every reader of the reference codec on thousands of corrupted and truncated streams, both variants,
+    compiled with -fsanitize=address,undefined: each call must end with a status and touch no byte outside
+    the buffers it was given (the streams sit in allocations of exactly their size)."""
+    import subprocess
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "host", "zcref_fuzz.cpp")
+    exe = str(tmp_path / "zcref_fuzz")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                    "-static-libasan", "-static-libubsan", src, "-o", exe], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:verify_asan_link_order=0")
+    run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert run.returncode == 0, run.stdout + run.stderr
+    calls, valid = [int(t) for t in run.stdout.split() if t.isdigit()]
+    assert calls > 10000 and 0 < valid < calls
