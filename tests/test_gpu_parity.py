@@ -956,3 +956,53 @@ def test_compress_in_parts_matches_reference(zcref, stream_variant):
     assert zc.zc_compress_part(d_in, n, eb, 6 * PACK, 0, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
     st, need = zc.zc_compress_part(d_in, n, eb, 0, n, d_out, ws, out_cap=total_ref - 4)
     assert st == ZC_ERR_CAPACITY and need == total_ref
+
+
+# ---------------- corrupted streams: the same verdict as the reference, whatever the bytes ----------------
+@pytest.mark.parametrize("seed", [0, 1])
+def test_corrupted_streams_get_the_reference_verdict(zcref, seed):
+    """Random edits of header, index, width table and payload, and truncations: every consuming call ends
+    with the status the reference gives (every access of the kernels is fenced by sizes the host passed or
+    the header proved), and where both accept the stream the results are the reference's."""
+    u = _u()
+    rng = np.random.default_rng(900 + seed)
+    n = 3 * TILE + 2048 * int(rng.integers(0, 4)) + int(rng.integers(0, 2048))
+    x = synth.power_law_field((n // 4096 + 1, 64, 64), seed=900 + seed).numpy().ravel()[:n]
+    x[:: 997] *= np.float32(300.0)                                   # a few wide blocks
+    eb = 1e-3
+    st, good, total = zcref.compress(x, eb)
+    assert st in (ZC_OK, ZC_ERR_BOUND)
+    nb = (n + 31) // 32
+    tables = u.tables_end(nb)
+    verdicts = {}
+    for trial in range(40):
+        s = good.copy()
+        kind = trial % 4
+        if kind == 0:                                                # header
+            s[int(rng.integers(0, 32))] ^= np.uint8(1 << int(rng.integers(0, 8)))
+        elif kind == 1:                                              # index and tables
+            for _ in range(int(rng.integers(1, 4))):
+                s[int(rng.integers(32, tables))] = np.uint8(rng.integers(0, 256))
+        elif kind == 2:                                              # payload: still a valid stream
+            s[int(rng.integers(tables, total))] ^= np.uint8(1 << int(rng.integers(0, 8)))
+        else:                                                        # truncated
+            s = s[: int(rng.integers(0, total))]
+        if s.size < 16:
+            continue
+        ref = zcref.decompress(s, out_cap_elems=n)
+        st, y, m = u.gpu_decompress(s, n)
+        assert st == ref[0], (trial, kind, "decompress", st, ref[0])
+        if st == ZC_OK:
+            assert np.array_equal(y.view(np.uint32), ref[1].view(np.uint32))
+        ref = zcref.reduce([good, s])
+        st, r, _ = u.gpu_reduce([good, s], n)
+        assert st == ref[0], (trial, kind, "reduce", st, ref[0])
+        if st == ZC_OK:
+            assert r.tobytes() == ref[1].tobytes()
+        ref = zcref.reduce_step(s, x)
+        st, r, _ = u.gpu_reduce_step(s, x)
+        assert st == ref[0], (trial, kind, "reduce_step", st, ref[0])
+        if st in (ZC_OK, ZC_ERR_BOUND):
+            assert r.tobytes() == ref[1].tobytes()
+        verdicts[ref[0]] = verdicts.get(ref[0], 0) + 1
+    assert len(verdicts) >= 2                                        # some accepted, some refused
