@@ -607,6 +607,17 @@ def test_kernel_timing_hook(zcref):
     assert [name for name, _ in got] == ["compress", "decompress", "reduce"]
     assert all(0.0 < ms < 100.0 for _, ms in got)
     assert zc.zc_profile_collect() == []
+    # a chosen kind only
+    zc.zc_profile_enable(True, only=("reduce",))
+    u.gpu_compress(x, eb)
+    u.gpu_reduce([s, s], x.size)
+    u.gpu_decompress(s, x.size)
+    u.gpu_reduce([s, s, s], x.size)
+    got = zc.zc_profile_collect()
+    zc.zc_profile_enable(False)
+    assert [name for name, _ in got] == ["reduce", "reduce"] and all(0.0 < ms < 100.0 for _, ms in got)
+    u.gpu_reduce([s, s], x.size)
+    assert zc.zc_profile_collect() == []
 
 
 # ---------------- the index of indexed streams is checked by the kernels that use it ----------------
