@@ -77,6 +77,21 @@ int zc_compress(const float* d_in, size_t n, float abs_eb,
                 void* d_out, size_t out_cap, size_t* out_bytes,
                 void* d_ws, size_t ws_bytes, void* hip_stream);
 
+/* zc_compress for callers that cannot allocate device memory or bring a workspace along: code
+ * whose stream is being captured into a HIP graph, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and errors as zc_compress, without d_ws and ws_bytes: the
+ * workspace is an array in the library's own device image (about 2.4 MB on every GPU the library
+ * runs on, held until the process ends), sized for n <= ZC_NOALLOC_MAX_N; a larger n is
+ * ZC_ERR_ARG.  The call allocates nothing, on the device or through any library.  The GPU of
+ * hip_stream must be the current device.  All calls on one GPU share that one array: calls that
+ * overlap in time on one GPU (two host threads, two HIP streams) race on it and are not
+ * allowed; calls one after the other on one stream are fine, every call clears what it needs.
+ * The first call on a GPU looks up the array's address (hipGetSymbolAddress): make it before a
+ * capture starts.  The asynchronous form (out_bytes NULL) is completed by zc_finish(NULL, ...). */
+#define ZC_NOALLOC_MAX_N (1ull << 27)
+int zc_compress_noalloc(const float* d_in, size_t n, float abs_eb,
+                        void* d_out, size_t out_cap, size_t* out_bytes, void* hip_stream);
+
 /* zc_compress in parts (Section 3.5.2 produces a buffer chunk by chunk, so that a chunk can be
  * sent while the next one is being compressed): this call compresses the values
  * [first_value, first_value + count) of the n values at d_in into the stream at d_out.  The
@@ -187,7 +202,7 @@ int zc_quality(const float* d_ref, const float* d_test, size_t n, double* out4,
 
 /* Completes an asynchronous call: synchronises hip_stream, returns the status of the last
  * call that used d_ws and stores its size result (total_bytes, or n for zc_decompress) in
- * *result (host, may be NULL). */
+ * *result (host, may be NULL).  d_ws NULL: the call was zc_compress_noalloc on the current device. */
 int zc_finish(const void* d_ws, size_t* result, void* hip_stream);
 
 /* Reads and validates a stream header (synchronises hip_stream).  Any output may be NULL. */

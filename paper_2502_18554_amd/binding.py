@@ -21,6 +21,7 @@ EXPORTS = [
     "zc_reduce_compressed", "zc_reduce_step", "zc_reduce_step_op", "zc_decompress_average", "zc_decompress_range", "zc_quality",
     "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
     "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out", "zc_set_indexed_streams",
+    "zc_compress_noalloc",
 ]
 
 _lib = None
@@ -46,6 +47,7 @@ def lib():
         L.zc_workspace_bytes.restype = sz
         L.zc_workspace_bytes.argtypes = [sz, C.c_int]
         L.zc_compress.argtypes = [vp, sz, C.c_float, vp, sz, szp, vp, sz, vp]
+        L.zc_compress_noalloc.argtypes = [vp, sz, C.c_float, vp, sz, szp, vp]
         L.zc_compress_part.argtypes = [vp, sz, C.c_float, sz, sz, vp, sz, szp, vp, sz, vp]
         L.zc_decompress.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_compressed.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp]
@@ -97,6 +99,18 @@ def zc_compress(d_in, n, abs_eb, d_out, d_ws, sync=True, stream=None, out_cap=No
     st = lib().zc_compress(_p(d_in), n, abs_eb, _p(d_out), cap,
                            C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
                            _stream(stream))
+    return st, (nbytes.value if sync else None)
+
+
+ZC_NOALLOC_MAX_N = 1 << 27
+
+
+def zc_compress_noalloc(d_in, n, abs_eb, d_out, sync=True, stream=None, out_cap=None):
+    """zc_compress on the library's own static workspace.  Returns (status, total_bytes)."""
+    nbytes = C.c_size_t(0)
+    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
+    st = lib().zc_compress_noalloc(_p(d_in), n, abs_eb, _p(d_out), cap, C.byref(nbytes) if sync else None,
+                                   _stream(stream))
     return st, (nbytes.value if sync else None)
 
 
@@ -197,7 +211,7 @@ def zc_quality(d_ref, d_test, n, d_ws, stream=None):
 
 def zc_finish(d_ws, stream=None):
     """Returns (status, size result) of the last asynchronous call that used d_ws."""
-    r = C.c_size_t(0)
+    r = C.c_size_t(0)      # d_ws None: the call was zc_compress_noalloc
     st = lib().zc_finish(_p(d_ws), C.byref(r), _stream(stream))
     return st, r.value
 

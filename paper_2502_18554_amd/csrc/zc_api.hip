@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -175,6 +176,27 @@ void fill_compress_args(CompressArgs& ca, const float* d_in, u64 n, float abs_eb
   ca.part_end = 0;
 }
 
+// Workspace of zc_compress_noalloc: a device array of the library itself, one copy per GPU,
+// held until the process ends.  Host code never uses the array's name as an address (there it
+// is only a stand-in for the symbol): the device address is asked for once per device and kept.
+constexpr u64 kScratchBytes = (workspace_bytes(ZC_NOALLOC_MAX_N, 1) + 255) / 256 * 256;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, or null when it cannot be had.
+void* scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);      // every thread finds the same address
+  }
+  return p;
+}
+
 }  // namespace
 
 extern "C" {
@@ -202,7 +224,8 @@ const char* zc_strerror(int status) {
 }
 
 int zc_finish(const void* d_ws, size_t* result, void* hip_stream) {
-  if (!d_ws) return ZC_ERR_ARG;
+  if (!d_ws) d_ws = scratch_of_current_device();     // the call to complete was zc_compress_noalloc
+  if (!d_ws) return ZC_ERR_HIP;
   return finish(d_ws, result, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -226,6 +249,16 @@ int zc_compress(const float* d_in, size_t n, float abs_eb, void* d_out, size_t o
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
+}
+
+int zc_compress_noalloc(const float* d_in, size_t n, float abs_eb, void* d_out, size_t out_cap, size_t* out_bytes,
+                        void* hip_stream) {
+  if (n > ZC_NOALLOC_MAX_N) return ZC_ERR_ARG;       // the static workspace is sized for that many values
+  void* ws = scratch_of_current_device();
+  if (!ws) return ZC_ERR_HIP;
+  // init_kernel clears what must start at zero (control block, tile descriptors, tickets) on the
+  // call's stream, so what the previous call left in the array does not matter
+  return zc_compress(d_in, n, abs_eb, d_out, out_cap, out_bytes, ws, kScratchBytes, hip_stream);
 }
 
 // zc_decompress and zc_decompress_average.

@@ -29,9 +29,9 @@ constexpr int kTileValues = kTileBlocks * kBlockValues;      // 8192 values = 32
 constexpr i64 kMaxCode = (i64(1) << 30) - 1;
 constexpr u32 kSpinLimit = 1u << 20;       // bound on every look-back wait
 
-__host__ __device__ inline u64 pad16(u64 v) { return (v + 15) / 16 * 16; }
-__host__ __device__ inline u64 num_blocks(u64 n) { return (n + kBlockValues - 1) / kBlockValues; }
-__host__ __device__ inline u64 num_tiles(u64 nb) { return (nb + kTileBlocks - 1) / kTileBlocks; }
+__host__ __device__ constexpr u64 pad16(u64 v) { return (v + 15) / 16 * 16; }
+__host__ __device__ constexpr u64 num_blocks(u64 n) { return (n + kBlockValues - 1) / kBlockValues; }
+__host__ __device__ constexpr u64 num_tiles(u64 nb) { return (nb + kTileBlocks - 1) / kTileBlocks; }
 // No stream has more tiles than this (n <= ZC_MAX_N), so block and segment numbers fit 32 bits.
 constexpr u64 kMaxTiles = (ZC_MAX_N / kBlockValues + kTileBlocks - 1) / kTileBlocks;
 __host__ __device__ inline u32 psize_words(u32 w) { return w ? 1 + w : 0; }
@@ -117,7 +117,7 @@ struct WorkspaceLayout {
 constexpr u64 kDescBytes = 128;           // per tile, see kDescStride
 constexpr u64 kWsFixed = sizeof(Control) + kTicketBytes + 12 * ZC_MAX_K + 64;   // control, tickets, the +1 of every grp_off, span_off and span_flags row, padding
 
-__host__ inline u64 workspace_bytes(u64 n_max, int k_max) {
+__host__ constexpr u64 workspace_bytes(u64 n_max, int k_max) {
   if (k_max < 1) k_max = 1;
   const u64 t = num_tiles(num_blocks(n_max)) + 16;
   return kWsFixed + t * (kDescBytes + 17 * u64(k_max));      // 17 >= segment offsets (16) + the tile's share of the two coarser levels
