@@ -1,8 +1,9 @@
 /* zc — fZ-light error-bounded lossy compression and the compressed-Allreduce local step,
  * hand-written for AMD MI355X (gfx950).  C ABI; every pointer named d_* is DEVICE memory,
  * everything else is host memory.  The library allocates no device memory and keeps no
- * state between calls apart from three process-wide settings (zc_set_indexed_streams,
- * zc_set_tile_hand_out, zc_profile_enable): the caller owns inputs, outputs and the workspace.
+ * settings: what varies between calls is said by each call's arguments (`flags`), and the
+ * caller owns inputs, outputs and the workspace.  (The only thing that lives between calls is
+ * the optional kernel timer of zc_profile_enable, a measurement aid.)
  *
  * Method: ZCCL, arXiv 2502.18554.  fZ-light is described in Section 3.3 (block partition,
  * fused quantisation + 1D Lorenzo prediction, first value kept as a 4-byte outlier, sign
@@ -10,7 +11,7 @@
  * blocks).  The reduce step is the per-round "decompress, reduce, recompress" of the
  * collective computation framework (Section 3.1.2) with the Sum aggregation of Section 3.2.
  *
- * Stream layout (little endian), n values, nb = ceil(n / 32) blocks of 32 values:
+ * Plain stream (little endian), n values, nb = ceil(n / 32) blocks of 32 values:
  *    0  u32 magic 0x314C435A   4  u16 version 1   6  u8 block_log2 5   7  u8 guard_log2 6
  *    8  u64 n                 16  u32 eb_bits (binary32 pattern of abs_eb)
  *   20  u32 nsum (1 after zc_compress, sum of the operands' nsum after a reduce)
@@ -24,15 +25,41 @@
  *  deltas: d0 = 0, dj = qj - q(j-1) inside a block; the last block is padded with its last
  *  code; width = bit count of max |dj|; reconstruction x' = (float)((double)q * s).
  *
- * Indexed streams (zc_set_indexed_streams): version is 2, or 3 when some block is wider than
- * 15 bits, and between the header and the width table sits an index of nseg + 1 u32,
+ * Indexed stream (the default of every call): the same with the chunk size table of Section
+ * 3.5.2 in front of the data (the compressed size of every chunk is kept ahead of the data so
+ * that a chunk can be taken up without looking at the rest).  Here a chunk is a segment of 64
+ * blocks (2048 values), the share of one wave.  Version is 2, or 3 when some block is wider
+ * than 15 bits, and between the header and the width table sits an index of nseg + 1 u32,
  * nseg = ceil(nb / 64), zero padded to a multiple of 16 bytes: entry i is the payload word
  * offset of block 64 i, entry nseg the number of payload words.  Everything else is as above.
+ * Producers write the index as a by-product of placing their payload; consumers read their
+ * segments' positions from it instead of first summing the width table, which makes every
+ * call on indexed streams a single kernel launch.  Costs 4 bytes per 2048 values.
+ *
+ * flags (an OR of the flag bits below; 0 = the defaults):
+ *   ZC_STREAM_PLAIN     every stream of this call, read or written, is a plain stream.  A
+ *                       stream of the other variant is ZC_ERR_FORMAT.  Consumers of plain
+ *                       streams run two small kernels ahead of their main kernel to sum the
+ *                       width table.
+ *   ZC_TILES_BY_TICKET  (calls that write a stream) tiles of 256 or 512 blocks are claimed by
+ *                       workgroups with atomic tickets instead of being taken by workgroup id.
+ *                       The single-pass placement of the output (a device-wide exclusive sum of
+ *                       block sizes by look-back) needs every tile before a tile in work to be
+ *                       in work or finished.  By workgroup id that rests on the GPU starting the
+ *                       workgroups of a launch in increasing id order, which is how its
+ *                       dispatcher works but not an architectural promise; tickets need no
+ *                       such assumption and cost a few percent.  Either way a wait that does
+ *                       not end within 2^20 polls ends the call with ZC_ERR_HIP, never in a hang.
+ * An index that contradicts the width table, a width above 31, or a width above 15 in a
+ * version-2 stream is ZC_ERR_FORMAT, which the kernels find as they use each segment: the
+ * output of such a call is unspecified.
  *
  * Calls are asynchronous on the given HIP stream unless the last size pointer is non-NULL,
  * in which case the call synchronises the stream and returns the final status and size.
  * In the asynchronous form the status and size are collected later with zc_finish on the
- * same workspace.  One workspace serves one call at a time.
+ * same workspace.  One workspace serves one call at a time; its content between calls is
+ * irrelevant (nothing in it ever needs clearing).  Calls on different workspaces may run
+ * concurrently, on several HIP streams or from several host threads.
  */
 #ifndef ZC_H
 #define ZC_H
@@ -46,7 +73,7 @@ extern "C" {
 
 typedef enum {
   ZC_OK = 0,
-  ZC_ERR_ARG = 1,       /* null pointer, misaligned buffer, abs_eb not finite / < 2^-96, n > 2^31, k out of range, workspace too small */
+  ZC_ERR_ARG = 1,       /* null pointer, misaligned buffer, abs_eb not finite / < 2^-96, n > 2^31, k out of range, unknown flag or op, workspace too small */
   ZC_ERR_CAPACITY = 2,  /* output buffer too small; nothing is written past its end */
   ZC_ERR_FORMAT = 3,    /* not a valid stream: header fields, truncated, width > 31, sizes do not add up, the other stream variant, an index that contradicts the widths */
   ZC_ERR_NONFINITE = 4, /* NaN or Inf in the input */
@@ -59,9 +86,13 @@ typedef enum {
 #define ZC_MAX_N (1ull << 31)
 #define ZC_MAX_K 64
 
-/* Worst-case stream size in bytes for n values (every block at width 31: 133 B per 128 B),
- * for the stream variant in force when it is called. */
+#define ZC_STREAM_PLAIN 1u
+#define ZC_TILES_BY_TICKET 2u
+
+/* Worst-case stream size in bytes for n values (every block at width 31: 133 B per 128 B):
+ * of the default (indexed) variant, or of the variant that flags name. */
 size_t zc_compress_bound(size_t n);
+size_t zc_compress_bound_ex(size_t n, unsigned flags);
 
 /* Workspace bytes needed by any call on at most n_max values with at most k_max reduce
  * operands (k_max < 1 is taken as 1).  The workspace is device memory, 16-byte aligned;
@@ -72,10 +103,14 @@ size_t zc_workspace_bytes(size_t n_max, int k_max);
  * d_out: out_cap bytes, 16-byte aligned, receives the stream.  out_bytes (host, may be NULL):
  * receives total_bytes, also when the status is ZC_ERR_CAPACITY or ZC_ERR_BOUND.
  * Errors: ARG, NONFINITE, RANGE, CAPACITY, BOUND (in this order of precedence), HIP.
- * On any error except BOUND the content of d_out is unspecified. */
+ * On any error except BOUND the content of d_out is unspecified.
+ * zc_compress is zc_compress_ex with flags 0. */
 int zc_compress(const float* d_in, size_t n, float abs_eb,
                 void* d_out, size_t out_cap, size_t* out_bytes,
                 void* d_ws, size_t ws_bytes, void* hip_stream);
+int zc_compress_ex(const float* d_in, size_t n, float abs_eb,
+                   void* d_out, size_t out_cap, size_t* out_bytes,
+                   void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
 /* zc_compress for callers that cannot allocate device memory or bring a workspace along: code
  * whose stream is being captured into a HIP graph, tight serving loops, harnesses that forbid
@@ -85,7 +120,7 @@ int zc_compress(const float* d_in, size_t n, float abs_eb,
  * ZC_ERR_ARG.  The call allocates nothing, on the device or through any library.  The GPU of
  * hip_stream must be the current device.  All calls on one GPU share that one array: calls that
  * overlap in time on one GPU (two host threads, two HIP streams) race on it and are not
- * allowed; calls one after the other on one stream are fine, every call clears what it needs.
+ * allowed; calls one after the other on one stream are fine, nothing in the array needs clearing.
  * The first call on a GPU looks up the array's address (hipGetSymbolAddress): make it before a
  * capture starts.  The asynchronous form (out_bytes NULL) is completed by zc_finish(NULL, ...). */
 #define ZC_NOALLOC_MAX_N (1ull << 27)
@@ -95,72 +130,81 @@ int zc_compress_noalloc(const float* d_in, size_t n, float abs_eb,
 /* zc_compress in parts (Section 3.5.2 produces a buffer chunk by chunk, so that a chunk can be
  * sent while the next one is being compressed): this call compresses the values
  * [first_value, first_value + count) of the n values at d_in into the stream at d_out.  The
- * parts of one stream are given in ascending order, without gaps, to the same d_out and d_ws,
- * on one HIP stream (or ordered by events), starting with first_value = 0, which also writes
- * header and table padding; first_value and count are multiples of 16384, except that the
+ * parts of one stream are given in ascending order, without gaps, to the same d_out and d_ws
+ * with the same flags, on one HIP stream (or ordered by events), starting with first_value = 0,
+ * which also writes the header; first_value and count are multiples of 16384, except that the
  * last part ends at n.  n and abs_eb are the same in every part; only the values of the
- * part need to be in place at d_in when it is given.  After a part has run, the stream's tables
+ * part need to be in place at d_in when it is given.  Between the parts the workspace must not
+ * be used for anything else.  After a part has run, the stream's tables
  * and payload up to its end are final, and out_bytes (or zc_finish) tells how many bytes of the
- * stream that is; of an indexed stream (zc_set_indexed_streams) header and index then describe
+ * stream that is; of an indexed stream header and index then describe
  * a stream that can be read up to there (zc_decompress_range) while later parts are produced.
  * After the last part the stream is the one zc_compress writes.  Errors of all parts
  * accumulate in the workspace.  Errors: as zc_compress, and ARG for a part that is not as above. */
 int zc_compress_part(const float* d_in, size_t n, float abs_eb, size_t first_value, size_t count,
                      void* d_out, size_t out_cap, size_t* out_bytes,
-                     void* d_ws, size_t ws_bytes, void* hip_stream);
+                     void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
 /* fZ-light decompression (inverse of the stages of Section 3.3).  d_in: stream of in_bytes
  * bytes (trailing bytes beyond total_bytes are ignored), 16-byte aligned.  d_out: room for
  * out_cap_elems binary32 values, 16-byte aligned.  n_out (host, may be NULL): receives n.
- * Errors: ARG, FORMAT, CAPACITY (nothing is written), HIP. */
+ * Errors: ARG, FORMAT, CAPACITY (nothing is written), HIP.
+ * zc_decompress is zc_decompress_ex with flags 0 (it reads what zc_compress writes). */
 int zc_decompress(const void* d_in, size_t in_bytes,
                   float* d_out, size_t out_cap_elems, size_t* n_out,
                   void* d_ws, size_t ws_bytes, void* hip_stream);
+int zc_decompress_ex(const void* d_in, size_t in_bytes,
+                     float* d_out, size_t out_cap_elems, size_t* n_out,
+                     void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
 /* zc_decompress for the Average aggregation of Section 3.2 (Corollary 1: the error of the
  * average of n buffers has variance sigma^2 / n): the stream holds the sum of nsum buffers, and
  * every value is divided by nsum on the way out, x' = (float)(((double)q * s) * r) with
- * r = 1.0 / nsum (one binary64 division per wave).  Arguments and errors as zc_decompress. */
+ * r = 1.0 / nsum (one binary64 division per wave).  Arguments and errors as zc_decompress_ex. */
 int zc_decompress_average(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
-                          void* d_ws, size_t ws_bytes, void* hip_stream);
+                          void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
 /* One chunk of a stream on its own (Section 3.5.2 handles a buffer chunk by chunk, so that a
  * chunk can be decompressed while others are still on their way or being worked on, for
  * instance by calls on several HIP streams, each with a workspace of its own): the values
  * [first_value, first_value + count) of the stream, cut off at its end, go to d_out[0 ...].
  * first_value must be a multiple of 2048 (a segment of 64 blocks).  Only the header, the tables
- * and the payload of those segments are read; of an indexed stream (zc_set_indexed_streams)
+ * and the payload of those segments are read; of an indexed stream
  * not even the whole width table, only the index entries and width bytes of the segments
- * (of a plain stream the whole width table is summed first, in every call).
- * The workspace must be large enough for the whole stream (zc_workspace_bytes(n, 1)).
+ * (of a plain stream the whole width table is summed first, in every call, and the workspace
+ * must be large enough for the whole stream, zc_workspace_bytes(n, 1)).
  * n_out (host, may be NULL): receives how many values that is.
  * Errors: ARG (also: first_value not a multiple of 2048, or beyond the stream's n), FORMAT,
  * CAPACITY (out_cap_elems smaller than the part), HIP. */
 int zc_decompress_range(const void* d_in, size_t in_bytes, size_t first_value, size_t count,
                         float* d_out, size_t out_cap_elems, size_t* n_out,
-                        void* d_ws, size_t ws_bytes, void* hip_stream);
+                        void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
 /* Decompression of k streams in one call: the tail of the compressed Allgather (Section 3.5.1:
  * a rank decompresses all the chunks it has received at the end), one launch instead of k.
  * d_chunks, chunk_bytes, d_outs, out_cap_elems: HOST arrays of k entries (device pointers 16-byte
- * aligned); stream i is decoded into d_outs[i] exactly as zc_decompress would.  The streams need
+ * aligned); stream i is decoded into d_outs[i] exactly as zc_decompress_ex would.  The streams need
  * not agree in n or bound.  n_out (host array of k entries, may be NULL): receives every
  * stream's n.  In the asynchronous form zc_finish reports the sum of the k values of n.
- * Errors: ARG, FORMAT (any stream; nothing is written then), CAPACITY (that stream is not
- * written, the others are), HIP. */
+ * Errors: ARG, FORMAT (a malformed header in any stream: nothing is written then), CAPACITY (that
+ * stream is not written, the others are), HIP. */
 int zc_decompress_many(const void* const* d_chunks, const size_t* chunk_bytes, int k,
                        float* const* d_outs, const size_t* out_cap_elems, size_t* n_out,
-                       void* d_ws, size_t ws_bytes, void* hip_stream);
+                       void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
 /* Local step of the compressed Allreduce (Section 3.1.2, Sum of Section 3.2): k compressed
  * operands of the same n and abs_eb -> the compressed sum, computed on the integer codes, so
  * no new quantisation error appears and decompress(out) is within nsum * abs_eb of the exact
  * sum of the original buffers.  d_chunks: HOST array of k device pointers (16-byte aligned
  * streams); chunk_bytes: HOST array of their sizes; 1 <= k <= ZC_MAX_K.
- * Errors: ARG, FORMAT, MISMATCH, RANGE, CAPACITY, HIP. */
+ * Errors: ARG, FORMAT, MISMATCH, RANGE, CAPACITY, HIP.
+ * zc_reduce_compressed is zc_reduce_compressed_ex with flags 0. */
 int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes, int k,
                          void* d_out, size_t out_cap, size_t* out_bytes,
                          void* d_ws, size_t ws_bytes, void* hip_stream);
+int zc_reduce_compressed_ex(const void* const* d_chunks, const size_t* chunk_bytes, int k,
+                            void* d_out, size_t out_cap, size_t* out_bytes,
+                            void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
 /* One round of the ring reduce-scatter (Section 3.1.2: a received compressed chunk is
  * decompressed, reduced with the local chunk and compressed again; Section 3.2, Sum: each such
@@ -171,13 +215,14 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
  * out_bytes (host, may be NULL): receives total_bytes.  Nothing but the two streams and the
  * local values moves through memory.
  * Errors: ARG, FORMAT, MISMATCH, NONFINITE, RANGE, CAPACITY, BOUND (against the binary32
- * sums; the stream is complete then), HIP. */
+ * sums; the stream is complete then), HIP.
+ * zc_reduce_step is zc_reduce_step_op with ZC_OP_SUM and flags 0. */
 int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local,
                    void* d_out, size_t out_cap, size_t* out_bytes,
                    void* d_ws, size_t ws_bytes, void* hip_stream);
 
-/* The same round for the other aggregation functions of Section 3.2.  op: ZC_OP_SUM (what
- * zc_reduce_step does), ZC_OP_MAX or ZC_OP_MIN: d_out receives the stream of the larger (smaller)
+/* The same round for the other aggregation functions of Section 3.2.  op: ZC_OP_SUM,
+ * ZC_OP_MAX or ZC_OP_MIN: d_out receives the stream of the larger (smaller)
  * of dequantised(received) and local.  Because the quantiser is monotone and maps its own
  * grid points to themselves, a ring of such rounds yields exactly the stream of the elementwise
  * maximum (minimum) of all buffers: the error stays within abs_eb however many rounds there are,
@@ -188,7 +233,7 @@ int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local
 #define ZC_OP_MIN 2
 int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, int op,
                       void* d_out, size_t out_cap, size_t* out_bytes,
-                      void* d_ws, size_t ws_bytes, void* hip_stream);
+                      void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
 /* Quality of a reconstruction d_test against its original d_ref (n binary32 values each,
  * 16-byte aligned): the sums behind the paper's quality figures (NRMSE in Section 3.3, PSNR
@@ -205,9 +250,11 @@ int zc_quality(const float* d_ref, const float* d_test, size_t n, double* out4,
  * *result (host, may be NULL).  d_ws NULL: the call was zc_compress_noalloc on the current device. */
 int zc_finish(const void* d_ws, size_t* result, void* hip_stream);
 
-/* Reads and validates a stream header (synchronises hip_stream).  Any output may be NULL. */
+/* Reads and validates a stream header (synchronises hip_stream); the variant is told by the
+ * header's version word.  Any output may be NULL.  flags: ZC_STREAM_PLAIN for a plain stream,
+ * 0 for an indexed one: what the calls that read this stream must be given. */
 int zc_peek_header(const void* d_in, size_t in_bytes, size_t* n, float* abs_eb,
-                   unsigned* nsum, size_t* total_bytes, void* hip_stream);
+                   unsigned* nsum, size_t* total_bytes, unsigned* flags, void* hip_stream);
 
 const char* zc_strerror(int status);
 
@@ -219,49 +266,24 @@ int zc_debug_quantize(const float* d_in, size_t n, float abs_eb, int32_t* d_q,
                       void* d_ws, size_t ws_bytes, void* hip_stream);
 
 /* Payload offset of every block, in 4-byte words, recomputed from a stream's width table
- * into d_off_words[nb].  Synchronous.  Errors: ARG, FORMAT, HIP. */
+ * (and, of an indexed stream, its index) into d_off_words[nb].  Synchronous.
+ * Errors: ARG, FORMAT, CAPACITY (off_cap < nb), HIP. */
 int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_words, size_t off_cap,
-                           void* d_ws, size_t ws_bytes, void* hip_stream);
-
-/* Which stream variant every entry point writes and accepts from now on: 0 (default) the plain
- * stream, non-zero the indexed one.  The index is the chunk size table of Section 3.5.2: the
- * compressed size of every chunk is kept in front of the data so that a chunk can be taken up
- * without looking at the rest.  Here a chunk is 64 blocks (2048 values), the share of one
- * wave: zc_compress, zc_reduce_compressed and zc_reduce_step write the table as a by-product
- * of placing their payload, and zc_decompress, zc_decompress_many, zc_reduce_compressed and
- * zc_reduce_step read their segments' positions from it instead of first summing the width
- * table, which saves one kernel per call.  A stream of the other variant is ZC_ERR_FORMAT; so
- * is an index that contradicts the width table, a width above 31, or a width above 15 in a
- * version-2 stream, which the kernels find as they use each segment: the output of such a
- * call is unspecified.  Costs 4 bytes per 2048 values.  Process-wide; applies to calls made
- * afterwards (zc_compress_bound included).  Returns ZC_OK. */
-int zc_set_indexed_streams(int on);
-
-/* How zc_compress, zc_reduce_compressed and zc_reduce_step hand out their tiles (256 or 512 blocks each) to
- * workgroups.  Their single-pass placement (a device-wide exclusive sum of block sizes by
- * look-back) needs every tile before a tile in work to be in work or finished.
- * ZC_HAND_OUT_DISPATCH_ORDER (default): tile = workgroup id; relies on the GPU starting the
- * workgroups of a launch in increasing id order, which is how its dispatcher works but not an
- * architectural promise.  ZC_HAND_OUT_TICKETS: tiles are claimed with atomic tickets, which
- * needs no assumption and costs a few percent.  In both modes a wait that does not end within
- * 2^20 polls ends the call with ZC_ERR_HIP.  Process-wide; applies to calls made afterwards.
- * Returns ZC_OK or ZC_ERR_ARG. */
-#define ZC_HAND_OUT_DISPATCH_ORDER 0
-#define ZC_HAND_OUT_TICKETS 1
-int zc_set_tile_hand_out(int mode);
+                           void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
 /* Measurement aid (not part of the method).  While enabled, zc_compress, zc_decompress,
  * zc_decompress_average, zc_decompress_many, zc_reduce_compressed, zc_reduce_step and
- * zc_reduce_step_op hand a pair of HIP events to the launch of their main kernel on the call's
- * stream (hipExtLaunchKernelGGL), which stamps them with that kernel's start and end (the
- * compress kernel over the full tiles, the decompress, reduce or step kernel; not the small
- * set-up kernels before it).  zc_profile_collect waits for the recorded pairs,
- * stores up to cap elapsed times in milliseconds in ms[] and the matching ZC_KERNEL_* ids in
- * kernel[] (host arrays, either may be NULL) in call order, forgets them, and returns how
- * many it stored (a negative status on a HIP error).  The events are host objects created on
- * first use and reused.  on: 0 off, 1 every kind of main kernel, or a sum of (1 << ZC_KERNEL_x) to time
- * only those kinds (a timed launch costs a few microseconds).  Leave it disabled while a stream is being captured into a HIP graph.  Enabling or disabling
- * forgets the pairs recorded so far. */
+ * zc_reduce_step_op (and their _ex forms) hand a pair of HIP events to the launch of their
+ * main kernel on the call's stream (hipExtLaunchKernelGGL), which stamps them with that
+ * kernel's start and end (the compress kernel over the full tiles, the decompress, reduce or
+ * step kernel; not the small kernels that run ahead of it for plain streams).
+ * zc_profile_collect waits for the recorded pairs, stores up to cap elapsed times in
+ * milliseconds in ms[] and the matching ZC_KERNEL_* ids in kernel[] (host arrays, either may
+ * be NULL) in call order, forgets them, and returns how many it stored (a negative status on
+ * a HIP error).  The events are host objects created on first use and reused.  on: 0 off,
+ * 1 every kind of main kernel, or a sum of (1 << ZC_KERNEL_x) to time only those kinds (a
+ * timed launch costs a few microseconds).  Leave it disabled while a stream is being
+ * captured into a HIP graph.  Enabling or disabling forgets the pairs recorded so far. */
 #define ZC_KERNEL_COMPRESS 1
 #define ZC_KERNEL_DECOMPRESS 2
 #define ZC_KERNEL_REDUCE 3

@@ -16,12 +16,14 @@ ZC_OK, ZC_ERR_ARG, ZC_ERR_CAPACITY, ZC_ERR_FORMAT, ZC_ERR_NONFINITE, ZC_ERR_RANG
     ZC_ERR_MISMATCH, ZC_ERR_HIP = range(9)
 ZC_MAX_K = 64
 
+ZC_STREAM_PLAIN, ZC_TILES_BY_TICKET = 1, 2
+
 EXPORTS = [
-    "zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_compress_part", "zc_decompress", "zc_decompress_many",
-    "zc_reduce_compressed", "zc_reduce_step", "zc_reduce_step_op", "zc_decompress_average", "zc_decompress_range", "zc_quality",
-    "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
-    "zc_profile_enable", "zc_profile_collect", "zc_set_tile_hand_out", "zc_set_indexed_streams",
-    "zc_compress_noalloc",
+    "zc_compress_bound", "zc_compress_bound_ex", "zc_workspace_bytes", "zc_compress", "zc_compress_ex", "zc_compress_noalloc",
+    "zc_compress_part", "zc_decompress", "zc_decompress_ex", "zc_decompress_many", "zc_reduce_compressed",
+    "zc_reduce_compressed_ex", "zc_reduce_step", "zc_reduce_step_op", "zc_decompress_average", "zc_decompress_range",
+    "zc_quality", "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
+    "zc_profile_enable", "zc_profile_collect",
 ]
 
 _lib = None
@@ -42,29 +44,33 @@ def lib():
                                "(there is no CPU fallback)")
         L = C.CDLL(_LIB_PATH)
         vp, sz, szp = C.c_void_p, C.c_size_t, C.POINTER(C.c_size_t)
+        u = C.c_uint
         L.zc_compress_bound.restype = sz
         L.zc_compress_bound.argtypes = [sz]
+        L.zc_compress_bound_ex.restype = sz
+        L.zc_compress_bound_ex.argtypes = [sz, u]
         L.zc_workspace_bytes.restype = sz
         L.zc_workspace_bytes.argtypes = [sz, C.c_int]
         L.zc_compress.argtypes = [vp, sz, C.c_float, vp, sz, szp, vp, sz, vp]
+        L.zc_compress_ex.argtypes = [vp, sz, C.c_float, vp, sz, szp, vp, sz, vp, u]
         L.zc_compress_noalloc.argtypes = [vp, sz, C.c_float, vp, sz, szp, vp]
-        L.zc_compress_part.argtypes = [vp, sz, C.c_float, sz, sz, vp, sz, szp, vp, sz, vp]
+        L.zc_compress_part.argtypes = [vp, sz, C.c_float, sz, sz, vp, sz, szp, vp, sz, vp, u]
         L.zc_decompress.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
+        L.zc_decompress_ex.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp, u]
         L.zc_reduce_compressed.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp]
+        L.zc_reduce_compressed_ex.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp, u]
         L.zc_reduce_step.argtypes = [vp, sz, vp, sz, vp, sz, szp, vp, sz, vp]
-        L.zc_reduce_step_op.argtypes = [vp, sz, vp, sz, C.c_int, vp, sz, szp, vp, sz, vp]
-        L.zc_decompress_average.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp]
-        L.zc_decompress_range.argtypes = [vp, sz, sz, sz, vp, sz, szp, vp, sz, vp]
+        L.zc_reduce_step_op.argtypes = [vp, sz, vp, sz, C.c_int, vp, sz, szp, vp, sz, vp, u]
+        L.zc_decompress_average.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp, u]
+        L.zc_decompress_range.argtypes = [vp, sz, sz, sz, vp, sz, szp, vp, sz, vp, u]
         L.zc_quality.argtypes = [vp, vp, sz, C.POINTER(C.c_double), vp, sz, vp]
-        L.zc_decompress_many.argtypes = [C.POINTER(vp), szp, C.c_int, C.POINTER(vp), szp, szp, vp, sz, vp]
+        L.zc_decompress_many.argtypes = [C.POINTER(vp), szp, C.c_int, C.POINTER(vp), szp, szp, vp, sz, vp, u]
         L.zc_finish.argtypes = [vp, szp, vp]
-        L.zc_peek_header.argtypes = [vp, sz, szp, C.POINTER(C.c_float), C.POINTER(C.c_uint), szp, vp]
+        L.zc_peek_header.argtypes = [vp, sz, szp, C.POINTER(C.c_float), C.POINTER(C.c_uint), szp, C.POINTER(C.c_uint), vp]
         L.zc_strerror.restype = C.c_char_p
         L.zc_strerror.argtypes = [C.c_int]
         L.zc_debug_quantize.argtypes = [vp, sz, C.c_float, vp, vp, sz, vp]
-        L.zc_debug_block_offsets.argtypes = [vp, sz, vp, sz, vp, sz, vp]
-        L.zc_set_tile_hand_out.argtypes = [C.c_int]
-        L.zc_set_indexed_streams.argtypes = [C.c_int]
+        L.zc_debug_block_offsets.argtypes = [vp, sz, vp, sz, vp, sz, vp, u]
         L.zc_profile_enable.argtypes = [C.c_int]
         L.zc_profile_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int), C.c_int]
         _lib = L
@@ -84,21 +90,25 @@ def zc_strerror(status):
     return lib().zc_strerror(int(status)).decode()
 
 
-def zc_compress_bound(n):
-    return int(lib().zc_compress_bound(int(n)))
+def zc_compress_bound(n, flags=0):
+    return int(lib().zc_compress_bound_ex(int(n), int(flags))) if flags else int(lib().zc_compress_bound(int(n)))
 
 
 def zc_workspace_bytes(n_max, k_max=1):
     return int(lib().zc_workspace_bytes(int(n_max), int(k_max)))
 
 
-def zc_compress(d_in, n, abs_eb, d_out, d_ws, sync=True, stream=None, out_cap=None):
-    """Returns (status, total_bytes); total_bytes is None in the asynchronous form."""
+def _size(t):
+    return t.numel() * t.element_size()
+
+
+def zc_compress(d_in, n, abs_eb, d_out, d_ws, sync=True, stream=None, out_cap=None, flags=0):
+    """Returns (status, total_bytes); total_bytes is None in the asynchronous form.  flags 0 goes through
+    zc_compress, anything else through zc_compress_ex."""
     nbytes = C.c_size_t(0)
-    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
-    st = lib().zc_compress(_p(d_in), n, abs_eb, _p(d_out), cap,
-                           C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
-                           _stream(stream))
+    cap = _size(d_out) if out_cap is None else out_cap
+    args = [_p(d_in), n, abs_eb, _p(d_out), cap, C.byref(nbytes) if sync else None, _p(d_ws), _size(d_ws), _stream(stream)]
+    st = lib().zc_compress_ex(*args, int(flags)) if flags else lib().zc_compress(*args)
     return st, (nbytes.value if sync else None)
 
 
@@ -108,64 +118,64 @@ ZC_NOALLOC_MAX_N = 1 << 27
 def zc_compress_noalloc(d_in, n, abs_eb, d_out, sync=True, stream=None, out_cap=None):
     """zc_compress on the library's own static workspace.  Returns (status, total_bytes)."""
     nbytes = C.c_size_t(0)
-    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
+    cap = _size(d_out) if out_cap is None else out_cap
     st = lib().zc_compress_noalloc(_p(d_in), n, abs_eb, _p(d_out), cap, C.byref(nbytes) if sync else None,
                                    _stream(stream))
     return st, (nbytes.value if sync else None)
 
 
-def zc_compress_part(d_in, n, abs_eb, first_value, count, d_out, d_ws, sync=True, stream=None, out_cap=None):
+def zc_compress_part(d_in, n, abs_eb, first_value, count, d_out, d_ws, sync=True, stream=None, out_cap=None, flags=0):
     """One part of a stream compressed in parts.  Returns (status, bytes of the stream final so far)."""
     nbytes = C.c_size_t(0)
-    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
+    cap = _size(d_out) if out_cap is None else out_cap
     st = lib().zc_compress_part(_p(d_in), int(n), float(abs_eb), int(first_value), int(count), _p(d_out), cap,
-                                C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
-                                _stream(stream))
+                                C.byref(nbytes) if sync else None, _p(d_ws), _size(d_ws), _stream(stream), int(flags))
     return st, (nbytes.value if sync else None)
 
 
-def zc_decompress(d_in, in_bytes, d_out, d_ws, sync=True, stream=None, out_cap_elems=None):
-    """Returns (status, n); n is None in the asynchronous form."""
+def zc_decompress(d_in, in_bytes, d_out, d_ws, sync=True, stream=None, out_cap_elems=None, flags=0):
+    """Returns (status, n); n is None in the asynchronous form.  flags 0 goes through zc_decompress,
+    anything else through zc_decompress_ex."""
     n = C.c_size_t(0)
     cap = (d_out.numel() if d_out is not None else 0) if out_cap_elems is None else out_cap_elems
-    st = lib().zc_decompress(_p(d_in), in_bytes, _p(d_out), cap, C.byref(n) if sync else None,
-                             _p(d_ws), d_ws.numel() * d_ws.element_size(), _stream(stream))
+    args = [_p(d_in), in_bytes, _p(d_out), cap, C.byref(n) if sync else None, _p(d_ws), _size(d_ws), _stream(stream)]
+    st = lib().zc_decompress_ex(*args, int(flags)) if flags else lib().zc_decompress(*args)
     return st, (n.value if sync else None)
 
 
-def zc_decompress_average(d_in, in_bytes, d_out, d_ws, sync=True, stream=None, out_cap_elems=None):
+def zc_decompress_average(d_in, in_bytes, d_out, d_ws, sync=True, stream=None, out_cap_elems=None, flags=0):
     """zc_decompress with every value divided by the stream's nsum.  Returns (status, n)."""
     n = C.c_size_t(0)
     cap = (d_out.numel() if d_out is not None else 0) if out_cap_elems is None else out_cap_elems
     st = lib().zc_decompress_average(_p(d_in), in_bytes, _p(d_out), cap, C.byref(n) if sync else None,
-                                     _p(d_ws), d_ws.numel() * d_ws.element_size(), _stream(stream))
+                                     _p(d_ws), _size(d_ws), _stream(stream), int(flags))
     return st, (n.value if sync else None)
 
 
-def zc_decompress_range(d_in, in_bytes, first_value, count, d_out, d_ws, sync=True, stream=None, out_cap_elems=None):
+def zc_decompress_range(d_in, in_bytes, first_value, count, d_out, d_ws, sync=True, stream=None, out_cap_elems=None,
+                        flags=0):
     """Values [first_value, first_value + count) of the stream into d_out.  Returns (status, n)."""
     n = C.c_size_t(0)
     cap = (d_out.numel() if d_out is not None else 0) if out_cap_elems is None else out_cap_elems
     st = lib().zc_decompress_range(_p(d_in), in_bytes, int(first_value), int(count), _p(d_out), cap,
-                                   C.byref(n) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
-                                   _stream(stream))
+                                   C.byref(n) if sync else None, _p(d_ws), _size(d_ws), _stream(stream), int(flags))
     return st, (n.value if sync else None)
 
 
-def zc_reduce_compressed(d_chunks, chunk_bytes, d_out, d_ws, sync=True, stream=None, out_cap=None):
-    """d_chunks: list of device tensors holding the k operand streams.  Returns (status, total_bytes)."""
+def zc_reduce_compressed(d_chunks, chunk_bytes, d_out, d_ws, sync=True, stream=None, out_cap=None, flags=0):
+    """d_chunks: list of device tensors holding the k operand streams.  Returns (status, total_bytes).
+    flags 0 goes through zc_reduce_compressed, anything else through zc_reduce_compressed_ex."""
     k = len(d_chunks)
     ptrs = (C.c_void_p * max(k, 1))(*[t.data_ptr() for t in d_chunks])
     sizes = (C.c_size_t * max(k, 1))(*[int(b) for b in chunk_bytes])
     nbytes = C.c_size_t(0)
-    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
-    st = lib().zc_reduce_compressed(ptrs, sizes, k, _p(d_out), cap,
-                                    C.byref(nbytes) if sync else None, _p(d_ws),
-                                    d_ws.numel() * d_ws.element_size(), _stream(stream))
+    cap = _size(d_out) if out_cap is None else out_cap
+    args = [ptrs, sizes, k, _p(d_out), cap, C.byref(nbytes) if sync else None, _p(d_ws), _size(d_ws), _stream(stream)]
+    st = lib().zc_reduce_compressed_ex(*args, int(flags)) if flags else lib().zc_reduce_compressed(*args)
     return st, (nbytes.value if sync else None)
 
 
-def zc_decompress_many(d_chunks, chunk_bytes, d_outs, d_ws, sync=True, stream=None, out_cap_elems=None):
+def zc_decompress_many(d_chunks, chunk_bytes, d_outs, d_ws, sync=True, stream=None, out_cap_elems=None, flags=0):
     """d_chunks / d_outs: lists of k device tensors.  Returns (status, [n of every stream]) (None when not sync)."""
     k = len(d_chunks)
     ptrs = (C.c_void_p * max(k, 1))(*[t.data_ptr() for t in d_chunks])
@@ -173,31 +183,33 @@ def zc_decompress_many(d_chunks, chunk_bytes, d_outs, d_ws, sync=True, stream=No
     outs = (C.c_void_p * max(k, 1))(*[t.data_ptr() for t in d_outs])
     caps = (C.c_size_t * max(k, 1))(*([t.numel() for t in d_outs] if out_cap_elems is None else [int(c) for c in out_cap_elems]))
     ns = (C.c_size_t * max(k, 1))()
-    st = lib().zc_decompress_many(ptrs, sizes, k, outs, caps, ns if sync else None, _p(d_ws),
-                                  d_ws.numel() * d_ws.element_size(), _stream(stream))
+    st = lib().zc_decompress_many(ptrs, sizes, k, outs, caps, ns if sync else None, _p(d_ws), _size(d_ws),
+                                  _stream(stream), int(flags))
     return st, ([int(ns[i]) for i in range(k)] if sync else None)
-
-
-def zc_reduce_step(d_chunk, chunk_bytes, d_local, n_local, d_out, d_ws, sync=True, stream=None, out_cap=None):
-    """One ring round: received stream + local fp32 values -> stream of the sums.  Returns (status, total_bytes)."""
-    nbytes = C.c_size_t(0)
-    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
-    st = lib().zc_reduce_step(_p(d_chunk), int(chunk_bytes), _p(d_local), int(n_local), _p(d_out), cap,
-                              C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
-                              _stream(stream))
-    return st, (nbytes.value if sync else None)
 
 
 ZC_OP_SUM, ZC_OP_MAX, ZC_OP_MIN = 0, 1, 2
 
 
-def zc_reduce_step_op(d_chunk, chunk_bytes, d_local, n_local, op, d_out, d_ws, sync=True, stream=None, out_cap=None):
+def zc_reduce_step(d_chunk, chunk_bytes, d_local, n_local, d_out, d_ws, sync=True, stream=None, out_cap=None, flags=0):
+    """One ring round: received stream + local fp32 values -> stream of the sums.  Returns (status, total_bytes).
+    flags 0 goes through zc_reduce_step, anything else through zc_reduce_step_op."""
+    if flags:
+        return zc_reduce_step_op(d_chunk, chunk_bytes, d_local, n_local, ZC_OP_SUM, d_out, d_ws, sync, stream, out_cap, flags)
+    nbytes = C.c_size_t(0)
+    cap = _size(d_out) if out_cap is None else out_cap
+    st = lib().zc_reduce_step(_p(d_chunk), int(chunk_bytes), _p(d_local), int(n_local), _p(d_out), cap,
+                              C.byref(nbytes) if sync else None, _p(d_ws), _size(d_ws), _stream(stream))
+    return st, (nbytes.value if sync else None)
+
+
+def zc_reduce_step_op(d_chunk, chunk_bytes, d_local, n_local, op, d_out, d_ws, sync=True, stream=None, out_cap=None,
+                      flags=0):
     """zc_reduce_step for Sum, Max or Min.  Returns (status, total_bytes)."""
     nbytes = C.c_size_t(0)
-    cap = d_out.numel() * d_out.element_size() if out_cap is None else out_cap
+    cap = _size(d_out) if out_cap is None else out_cap
     st = lib().zc_reduce_step_op(_p(d_chunk), int(chunk_bytes), _p(d_local), int(n_local), int(op), _p(d_out), cap,
-                                 C.byref(nbytes) if sync else None, _p(d_ws), d_ws.numel() * d_ws.element_size(),
-                                 _stream(stream))
+                                 C.byref(nbytes) if sync else None, _p(d_ws), _size(d_ws), _stream(stream), int(flags))
     return st, (nbytes.value if sync else None)
 
 
@@ -217,21 +229,20 @@ def zc_finish(d_ws, stream=None):
 
 
 def zc_peek_header(d_in, in_bytes, stream=None):
-    """Returns (status, n, abs_eb, nsum, total_bytes)."""
-    n, eb, nsum, total = C.c_size_t(0), C.c_float(0), C.c_uint(0), C.c_size_t(0)
+    """Returns (status, n, abs_eb, nsum, total_bytes, flags of the stream's variant)."""
+    n, eb, nsum, total, flags = C.c_size_t(0), C.c_float(0), C.c_uint(0), C.c_size_t(0), C.c_uint(0)
     st = lib().zc_peek_header(_p(d_in), in_bytes, C.byref(n), C.byref(eb), C.byref(nsum), C.byref(total),
-                              _stream(stream))
-    return st, n.value, eb.value, nsum.value, total.value
+                              C.byref(flags), _stream(stream))
+    return st, n.value, eb.value, nsum.value, total.value, flags.value
 
 
 def zc_debug_quantize(d_in, n, abs_eb, d_q, d_ws, stream=None):
-    return lib().zc_debug_quantize(_p(d_in), n, abs_eb, _p(d_q), _p(d_ws), d_ws.numel() * d_ws.element_size(),
-                                   _stream(stream))
+    return lib().zc_debug_quantize(_p(d_in), n, abs_eb, _p(d_q), _p(d_ws), _size(d_ws), _stream(stream))
 
 
-def zc_debug_block_offsets(d_in, in_bytes, d_off_words, d_ws, stream=None):
+def zc_debug_block_offsets(d_in, in_bytes, d_off_words, d_ws, stream=None, flags=0):
     return lib().zc_debug_block_offsets(_p(d_in), in_bytes, _p(d_off_words), d_off_words.numel(), _p(d_ws),
-                                        d_ws.numel() * d_ws.element_size(), _stream(stream))
+                                        _size(d_ws), _stream(stream), int(flags))
 
 
 KERNEL_NAMES = {1: "compress", 2: "decompress", 3: "reduce", 4: "reduce_step"}
@@ -253,14 +264,3 @@ def zc_profile_collect(cap=65536):
     if count < 0:
         raise ZcError(-count, "zc_profile_collect")
     return [(KERNEL_NAMES.get(kind[i], str(kind[i])), float(ms[i])) for i in range(count)]
-
-
-ZC_HAND_OUT_DISPATCH_ORDER, ZC_HAND_OUT_TICKETS = 0, 1
-
-
-def zc_set_tile_hand_out(mode):
-    return lib().zc_set_tile_hand_out(int(mode))
-
-
-def zc_set_indexed_streams(on):
-    return lib().zc_set_indexed_streams(1 if on else 0)

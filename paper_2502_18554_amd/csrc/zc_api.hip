@@ -4,7 +4,9 @@
 #include <hip/hip_ext.h>
 
 #include <atomic>
+#include <chrono>
 #include <cmath>
+#include <limits>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -43,20 +45,20 @@ struct KernelTimer {
   struct Slot { hipEvent_t a, b; int kind; };
   std::vector<Slot> pool;   // events are created once and reused
   size_t used = 0;
-  // A pair of events for one launch, or null when timing is off.
-  Slot* take(int kind) {
+  // A pair of events for one launch (by value: the pool may grow under another thread); false when timing is off.
+  bool take(int kind, Slot& out) {
     std::lock_guard<std::mutex> g(mu);
-    if (!(kinds & (1u << kind))) return nullptr;
+    if (!(kinds & (1u << kind))) return false;
     if (used == pool.size()) {
       Slot s;
       s.kind = 0;
-      if (hipEventCreate(&s.a) != hipSuccess) return nullptr;
-      if (hipEventCreate(&s.b) != hipSuccess) { (void)hipEventDestroy(s.a); return nullptr; }
+      if (hipEventCreate(&s.a) != hipSuccess) return false;
+      if (hipEventCreate(&s.b) != hipSuccess) { (void)hipEventDestroy(s.a); return false; }
       pool.push_back(s);
     }
-    Slot* s = &pool[used++];
-    s->kind = kind;
-    return s;
+    pool[used].kind = kind;
+    out = pool[used++];
+    return true;
   }
 };
 KernelTimer g_timer;
@@ -66,16 +68,17 @@ KernelTimer g_timer;
 // separate event records, which would each hold back the launch behind them.
 template <typename... Args>
 void launch_main(int kind, void (*kernel)(Args...), dim3 grid, dim3 block, hipStream_t stream, Args... args) {
-  KernelTimer::Slot* slot = g_timer.take(kind);
-  if (slot) hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, slot->a, slot->b, 0, args...);
+  KernelTimer::Slot slot;
+  if (g_timer.take(kind, slot)) hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, slot.a, slot.b, 0, args...);
   else hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
 }
 
-// How the kernels that write a stream hand out their tiles (zc_set_tile_hand_out).
-int g_hand_out = ZC_HAND_OUT_DISPATCH_ORDER;
+bool flags_valid(unsigned flags) { return (flags & ~(ZC_STREAM_PLAIN | ZC_TILES_BY_TICKET)) == 0; }
+bool is_indexed(unsigned flags) { return (flags & ZC_STREAM_PLAIN) == 0; }
 
-// Which stream variant the entry points write and accept (zc_set_indexed_streams).
-bool g_indexed = false;
+// A number per call for its tag (see launch_tag): the host's monotonic clock.  One workspace
+// serves one call at a time, and two calls are never issued within the same nanosecond.
+u64 call_nonce() { return u64(std::chrono::steady_clock::now().time_since_epoch().count()); }
 
 // Most blocks a stream of `bytes` bytes can describe: each costs at least 5 table bytes.
 u64 blocks_bound(u64 bytes) { return bytes > kHeaderBytes ? (bytes - kHeaderBytes) / 5 : 0; }
@@ -84,49 +87,42 @@ u64 blocks_bound(u64 bytes) { return bytes > kHeaderBytes ? (bytes - kHeaderByte
 u32 index_grid(u64 tiles) { return u32(((tiles + 15) / 16 + kIndexGroups - 1) / kIndexGroups); }   // spans
 
 int finish(const void* d_ws, size_t* result, hipStream_t stream) {
-  struct { u32 status, reserved; u64 result; } host;
+  struct { u64 status, call_tag, result; } host;
   if (hipMemcpyAsync(&host, d_ws, sizeof(host), hipMemcpyDeviceToHost, stream) != hipSuccess) return ZC_ERR_HIP;
   if (hipStreamSynchronize(stream) != hipSuccess) return ZC_ERR_HIP;
   if (result) *result = size_t(host.result);
-  return status_from_bits(host.status);
+  // status bits count only under the tag of the last call
+  return status_from_bits((host.status >> 32) == (host.call_tag >> 32) ? u32(host.status) : 0u);
 }
 
-// Validation and positions of the input streams ahead of a kernel that reads them.  A plain
-// stream has its block positions computed here; an indexed one brings them along.
-void launch_index(ScanArgs& sa, u64 tiles, u32 prep_grid, hipStream_t stream) {
-  sa.ix = g_indexed;
-  if (!g_indexed)
-    hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), u32(sa.k)), dim3(256), 0, stream, sa);
-  hipLaunchKernelGGL(index_prep_kernel, dim3(prep_grid), dim3(256), 0, stream, sa);
+// Validation and block positions of plain input streams, ahead of the kernel that reads them
+// (indexed streams bring their positions along and are judged by that kernel itself).
+// `tiles`: enough for the largest stream.  Returns the nonce the main kernel must be given.
+void launch_plain_index(ScanArgs& sa, u64 tiles, hipStream_t stream) {
+  hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), u32(sa.k)), dim3(256), 0, stream, sa);
+  hipLaunchKernelGGL(index_prep_kernel, dim3(1), dim3(256), 0, stream, sa);
 }
 
-// Workgroups of index_prep_kernel when it also clears `tiles` look-back descriptors.
-u32 prep_grid_for(u64 tiles) { return u32((tiles + 255) / 256 > 64 ? 64 : (tiles + 255) / 256); }
-
-void launch_init(const WorkspaceLayout& l, u32 ntiles, u8* out, u64 out_cap, u64 n, u32 eb_bits, hipStream_t stream) {
-  InitArgs ia;
-  ia.ctl = l.ctl;
-  ia.desc = l.desc;
-  ia.ntiles = ntiles;
-  ia.out = out;
-  ia.out_cap = out_cap;
-  ia.n = n;
-  ia.nb = num_blocks(n);
-  ia.eb_bits = eb_bits;
-  ia.nsum = 1;
-  ia.ix = g_indexed;
-  u32 grid = (ntiles + 255) / 256;
-  if (grid < 1) grid = 1;
-  if (grid > 1024) grid = 1024;
-  hipLaunchKernelGGL(init_kernel, dim3(grid), dim3(256), 0, stream, ia);
+// Tiles that a stream of in_bytes bytes can have, as far as the workspace goes.
+u64 tiles_of_stream(u64 in_bytes, const WorkspaceLayout& l, bool ix) {
+  u64 tiles = num_tiles(blocks_bound(in_bytes));
+  if (!ix && tiles > l.tiles_cap) tiles = l.tiles_cap;
+  if (tiles > kMaxTiles) tiles = kMaxTiles;
+  return tiles < 1 ? 1 : tiles;
 }
 
-__global__ void quantize_kernel(CompressArgs a, i32* q) {
+struct QuantizeArgs {
+  CompressArgs c;
+  i32* q;
+};
+
+__global__ void quantize_kernel(QuantizeArgs a) {
+  const u64 tag = call_tag(a.c.ctl, launch_tag(a.c.nonce, a.c.ctl), false);
   const u64 i = u64(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (i >= a.n) return;
+  if (i >= a.c.n) return;
   u32 err = 0;
-  q[i] = quantize_value(a.in[i], a, err);
-  if (err) atomicOr(&a.ctl->status, err);
+  a.q[i] = quantize_value(a.c.in[i], a.c, err);
+  if (err) raise_status(a.c.ctl, tag, err);
 }
 
 struct OffsetsArgs {
@@ -135,20 +131,31 @@ struct OffsetsArgs {
   u32* off_words;
   u64 off_cap;
   Control* ctl;
+  u64 nonce;
   bool ix;
 };
 
 __global__ __launch_bounds__(256) void block_offsets_kernel(OffsetsArgs a) {
-  if (validation_failed(a.ctl)) return;
   const ParsedHeader h = parse_header(a.in, a.ix);
-  if (!h.ok) return;
+  u64 tag;
+  if (a.ix) {
+    tag = call_tag(a.ctl, launch_tag(a.nonce, a.ctl), false);
+    if (!h.ok) {
+      if (blockIdx.x == 0 && threadIdx.x == 0) raise_status(a.ctl, tag, status_bit(ZC_ERR_FORMAT));
+      return;
+    }
+  } else {
+    const Gate gate = parse_gate(load_gate(a.ctl, 0));
+    tag = gate.tag;
+    if (gate_failed(gate) || !h.ok) return;
+  }
   if (h.nb > a.off_cap) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
+    if (blockIdx.x == 0 && threadIdx.x == 0) raise_status(a.ctl, tag, status_bit(ZC_ERR_CAPACITY));
     return;
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) a.ctl->result = h.nb;
   const u64 seg = u64(blockIdx.x) * 4 + (threadIdx.x >> 6);
-  if (seg >= num_segments(h.nb) || seg >= 4 * a.index.tiles_cap) return;
+  if (seg >= num_segments(h.nb) || (!a.ix && seg >= 4 * a.index.tiles_cap)) return;
   const u64 b = seg * kWaveBlocks + u64(lane_id());
   const u32 w = b < h.nb ? u32(a.in.base[widths_begin(h.nb, a.ix) + b]) : 0u;
   const u32 words = psize_words(w);
@@ -158,22 +165,46 @@ __global__ __launch_bounds__(256) void block_offsets_kernel(OffsetsArgs a) {
 }
 
 void fill_compress_args(CompressArgs& ca, const float* d_in, u64 n, float abs_eb, void* d_out, u64 out_cap,
-                        const WorkspaceLayout& l) {
+                        const WorkspaceLayout& l, unsigned flags) {
   ca.in = d_in;
   ca.n = n;
   ca.nb = num_blocks(n);
   ca.step = double(abs_eb) * 63.0 / 32.0;
   ca.inv = 1.0 / ca.step;
   ca.eb = double(abs_eb);
-  ca.screen = abs_eb * 131072.0f;   // 2^17 * eb; +inf when it overflows, which is still a valid screen
+  ca.screen = std::fmin(abs_eb * 131072.0f, std::numeric_limits<float>::max());   // 2^17 * eb, kept finite: an infinite input must fail the screen
   std::memcpy(&ca.eb_bits, &abs_eb, 4);
   ca.out = static_cast<u8*>(d_out);
   ca.out_cap = out_cap;
   ca.ctl = l.ctl;
   ca.desc = l.desc;
-  ca.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
-  ca.ix = g_indexed;
+  ca.ticketed = (flags & ZC_TILES_BY_TICKET) != 0;
+  ca.ix = is_indexed(flags);
   ca.part_end = 0;
+  ca.adopt = 0;
+  ca.nonce = call_nonce();
+}
+
+// The launches of zc_compress / zc_compress_part over the tiles [first_tile, end_tile) of the stream.
+// `adopt`: the call continues one whose tag is in the control block (a later part).
+void launch_compress(CompressArgs& ca, u32 first_tile, u32 end_tile, bool timed, hipStream_t stream) {
+  const u32 ntiles = u32(num_pack_tiles(ca.nb));
+  const u32 full_tiles = u32(ca.n / kPackValues);                       // tiles whose values all exist
+  const u32 end_full = end_tile < full_tiles ? end_tile : full_tiles;
+  if (ca.nb == 0) {                                                     // the stream of no values
+    EmptyStreamArgs ea{ca.ctl, ca.out, ca.out_cap, ca.eb_bits, ca.ix, ca.nonce};
+    hipLaunchKernelGGL(empty_stream_kernel, dim3(1), dim3(64), 0, stream, ea);
+    return;
+  }
+  if (end_full > first_tile) {
+    if (timed)
+      launch_main(ZC_KERNEL_COMPRESS, compress_kernel<true>, dim3(end_full - first_tile), dim3(kPackThreads), stream, ca, first_tile, end_full);
+    else
+      hipLaunchKernelGGL(compress_kernel<true>, dim3(end_full - first_tile), dim3(kPackThreads), 0, stream, ca, first_tile, end_full);
+    ca.adopt = 1;
+  }
+  if (end_tile > full_tiles)                                            // the ragged last tile of the stream
+    hipLaunchKernelGGL(compress_kernel<false>, dim3(1), dim3(kPackThreads), 0, stream, ca, full_tiles, ntiles);
 }
 
 // Workspace of zc_compress_noalloc: a device array of the library itself, one copy per GPU,
@@ -201,10 +232,12 @@ void* scratch_of_current_device() {
 
 extern "C" {
 
-size_t zc_compress_bound(size_t n) {
+size_t zc_compress_bound_ex(size_t n, unsigned flags) {
   const u64 nb = num_blocks(n);
-  return size_t(tables_end(nb, g_indexed) + 128 * nb);
+  return size_t(tables_end(nb, is_indexed(flags)) + 128 * nb);
 }
+
+size_t zc_compress_bound(size_t n) { return zc_compress_bound_ex(n, 0); }
 
 size_t zc_workspace_bytes(size_t n_max, int k_max) { return size_t(workspace_bytes(n_max, k_max)); }
 
@@ -229,26 +262,25 @@ int zc_finish(const void* d_ws, size_t* result, void* hip_stream) {
   return finish(d_ws, result, static_cast<hipStream_t>(hip_stream));
 }
 
-int zc_compress(const float* d_in, size_t n, float abs_eb, void* d_out, size_t out_cap, size_t* out_bytes,
-                void* d_ws, size_t ws_bytes, void* hip_stream) {
+int zc_compress_ex(const float* d_in, size_t n, float abs_eb, void* d_out, size_t out_cap, size_t* out_bytes,
+                   void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (!eb_valid(abs_eb) || n > ZC_MAX_N || (n && !d_in) || !d_out || !d_ws) return ZC_ERR_ARG;
+  if (!flags_valid(flags) || !eb_valid(abs_eb) || n > ZC_MAX_N || (n && !d_in) || !d_out || !d_ws) return ZC_ERR_ARG;
   if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
   const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
   const u64 nb = num_blocks(n);
-  const u64 ntiles = num_pack_tiles(nb);
   if (l.tiles_cap < 1 || num_tiles(nb) > l.tiles_cap) return ZC_ERR_ARG;
   CompressArgs ca;
-  fill_compress_args(ca, d_in, n, abs_eb, d_out, out_cap, l);
-  launch_init(l, u32(ntiles), ca.out, out_cap, n, ca.eb_bits, stream);
-  const u32 full_tiles = u32(n / kPackValues);      // tiles whose values all exist
-  if (full_tiles)
-    launch_main(ZC_KERNEL_COMPRESS, compress_kernel<true>, dim3(full_tiles), dim3(kPackThreads), stream, ca, 0u, full_tiles);
-  if (ntiles > full_tiles)                          // the ragged last tile
-    hipLaunchKernelGGL(compress_kernel<false>, dim3(1), dim3(kPackThreads), 0, stream, ca, full_tiles, u32(ntiles));
+  fill_compress_args(ca, d_in, n, abs_eb, d_out, out_cap, l, flags);
+  launch_compress(ca, 0, u32(num_pack_tiles(nb)), true, stream);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
+}
+
+int zc_compress(const float* d_in, size_t n, float abs_eb, void* d_out, size_t out_cap, size_t* out_bytes,
+                void* d_ws, size_t ws_bytes, void* hip_stream) {
+  return zc_compress_ex(d_in, n, abs_eb, d_out, out_cap, out_bytes, d_ws, ws_bytes, hip_stream, 0);
 }
 
 int zc_compress_noalloc(const float* d_in, size_t n, float abs_eb, void* d_out, size_t out_cap, size_t* out_bytes,
@@ -256,56 +288,15 @@ int zc_compress_noalloc(const float* d_in, size_t n, float abs_eb, void* d_out, 
   if (n > ZC_NOALLOC_MAX_N) return ZC_ERR_ARG;       // the static workspace is sized for that many values
   void* ws = scratch_of_current_device();
   if (!ws) return ZC_ERR_HIP;
-  // init_kernel clears what must start at zero (control block, tile descriptors, tickets) on the
-  // call's stream, so what the previous call left in the array does not matter
-  return zc_compress(d_in, n, abs_eb, d_out, out_cap, out_bytes, ws, kScratchBytes, hip_stream);
-}
-
-// zc_decompress and zc_decompress_average.
-static int decompress_one(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out, void* d_ws,
-                   size_t ws_bytes, void* hip_stream, bool average) {
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (!d_in || !d_ws || (out_cap_elems && !d_out)) return ZC_ERR_ARG;
-  if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
-  if (in_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
-  const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
-  if (l.tiles_cap < 1) return ZC_ERR_ARG;
-  u64 tiles = num_tiles(blocks_bound(in_bytes));
-  const u64 tiles_out = num_tiles(num_blocks(out_cap_elems));
-  if (tiles > tiles_out) tiles = tiles_out;
-  if (tiles > l.tiles_cap) tiles = l.tiles_cap;
-  if (tiles > kMaxTiles) tiles = kMaxTiles;
-  if (tiles < 1) tiles = 1;
-  ScanArgs sa;
-  sa.streams[0].base = static_cast<const u8*>(d_in);
-  sa.streams[0].bytes = in_bytes;
-  sa.k = 1;
-  sa.check_match = 0;
-  sa.index = l.index;
-  sa.ctl = l.ctl;
-  sa.desc = nullptr;
-  sa.ndesc = 0;
-  launch_index(sa, tiles, 1, stream);
-  DecompressArgs da;
-  da.in = sa.streams[0];
-  da.out = d_out;
-  da.out_cap_elems = out_cap_elems;
-  da.index = l.index;
-  da.ctl = l.ctl;
-  da.first_value = 0;
-  da.count = ~u64(0);
-  void (*kernel)(DecompressArgs) = average ? (g_indexed ? decompress_kernel<true, true> : decompress_kernel<false, true>)
-                                           : (g_indexed ? decompress_kernel<true, false> : decompress_kernel<false, false>);
-  launch_main(ZC_KERNEL_DECOMPRESS, kernel, dim3(u32(tiles)), dim3(kTileThreads), stream, da);
-  if (!launch_ok()) return ZC_ERR_HIP;
-  if (!n_out) return ZC_OK;
-  return finish(d_ws, n_out, stream);
+  // nothing in a workspace needs clearing (every call tags what it shares), so what the
+  // previous call left in the array does not matter
+  return zc_compress_ex(d_in, n, abs_eb, d_out, out_cap, out_bytes, ws, kScratchBytes, hip_stream, 0);
 }
 
 int zc_compress_part(const float* d_in, size_t n, float abs_eb, size_t first_value, size_t count, void* d_out,
-                     size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
+                     size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (!eb_valid(abs_eb) || n > ZC_MAX_N || (n && !d_in) || !d_out || !d_ws) return ZC_ERR_ARG;
+  if (!flags_valid(flags) || !eb_valid(abs_eb) || n > ZC_MAX_N || (n && !d_in) || !d_out || !d_ws) return ZC_ERR_ARG;
   if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
   if (first_value > n || count > n - first_value || first_value % kPackValues != 0) return ZC_ERR_ARG;
   const bool to_the_end = first_value + count == n;
@@ -315,149 +306,176 @@ int zc_compress_part(const float* d_in, size_t n, float abs_eb, size_t first_val
   const u64 ntiles = num_pack_tiles(nb);
   if (l.tiles_cap < 1 || num_tiles(nb) > l.tiles_cap) return ZC_ERR_ARG;
   CompressArgs ca;
-  fill_compress_args(ca, d_in, n, abs_eb, d_out, out_cap, l);
-  if (first_value == 0) launch_init(l, u32(ntiles), ca.out, out_cap, n, ca.eb_bits, stream);
-  else if (ca.ticketed) hipLaunchKernelGGL(clear_tickets_kernel, dim3(1), dim3(64), 0, stream, l.ctl);
+  fill_compress_args(ca, d_in, n, abs_eb, d_out, out_cap, l, flags);
   const u32 first_tile = u32(first_value / kPackValues);
-  const u32 full_tiles = u32(n / kPackValues);                          // tiles whose values all exist
   const u32 end_tile = to_the_end ? u32(ntiles) : u32((first_value + count) / kPackValues);
-  const u32 end_full = end_tile < full_tiles ? end_tile : full_tiles;
   ca.part_end = end_tile;
-  if (end_full > first_tile)
-    hipLaunchKernelGGL(compress_kernel<true>, dim3(end_full - first_tile), dim3(kPackThreads), 0, stream, ca, first_tile, end_full);
-  if (end_tile > full_tiles)                                            // the ragged last tile of the stream
-    hipLaunchKernelGGL(compress_kernel<false>, dim3(1), dim3(kPackThreads), 0, stream, ca, full_tiles, u32(ntiles));
+  ca.adopt = first_value != 0;          // later parts belong to the call that the first part opened
+  if (end_tile > first_tile || nb == 0) launch_compress(ca, first_tile, end_tile, false, stream);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
 }
 
-int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
-                  void* d_ws, size_t ws_bytes, void* hip_stream) {
-  return decompress_one(d_in, in_bytes, d_out, out_cap_elems, n_out, d_ws, ws_bytes, hip_stream, false);
-}
-
-int zc_decompress_average(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
-                          void* d_ws, size_t ws_bytes, void* hip_stream) {
-  return decompress_one(d_in, in_bytes, d_out, out_cap_elems, n_out, d_ws, ws_bytes, hip_stream, true);
-}
-
-int zc_decompress_range(const void* d_in, size_t in_bytes, size_t first_value, size_t count, float* d_out,
-                        size_t out_cap_elems, size_t* n_out, void* d_ws, size_t ws_bytes, void* hip_stream) {
+// zc_decompress, zc_decompress_average, zc_decompress_range.
+static int decompress_one(const void* d_in, size_t in_bytes, size_t first_value, size_t count, bool ranged, float* d_out,
+                          size_t out_cap_elems, size_t* n_out, void* d_ws, size_t ws_bytes, void* hip_stream, bool average,
+                          unsigned flags) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   constexpr u64 kSegValues = u64(kWaveBlocks) * kBlockValues;
-  if (!d_in || !d_ws || (out_cap_elems && !d_out) || first_value % kSegValues != 0 || first_value > ZC_MAX_N) return ZC_ERR_ARG;
+  if ((flags & ~ZC_STREAM_PLAIN) != 0 || !d_in || !d_ws || (out_cap_elems && !d_out)) return ZC_ERR_ARG;
+  if (first_value % kSegValues != 0 || first_value > ZC_MAX_N) return ZC_ERR_ARG;
   if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
   if (in_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
+  const bool ix = is_indexed(flags);
   const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
   if (l.tiles_cap < 1) return ZC_ERR_ARG;
-  // segments the part can have: no more than the buffers allow
+  // Tiles of the main kernel: no more than the buffers allow.  (The index of a plain stream is
+  // built over the whole stream whatever the output's size: its sums validate total_bytes.)
   u64 wanted = count < out_cap_elems ? count : out_cap_elems;
   const u64 stream_bound = blocks_bound(in_bytes) * kBlockValues;
   if (wanted > stream_bound) wanted = stream_bound;
   u64 grid = (wanted + kTileValues - 1) / kTileValues;
+  if (!ix && grid > l.tiles_cap) grid = l.tiles_cap;
   if (grid > kMaxTiles) grid = kMaxTiles;
   if (grid < 1) grid = 1;
-  // the positions of a plain stream come from sums over its whole width table, which the
-  // validation of total_bytes needs in any case
-  u64 tiles = num_tiles(blocks_bound(in_bytes));
-  if (tiles > l.tiles_cap) tiles = l.tiles_cap;
-  if (tiles > kMaxTiles) tiles = kMaxTiles;
-  if (tiles < 1) tiles = 1;
-  ScanArgs sa;
-  sa.streams[0].base = static_cast<const u8*>(d_in);
-  sa.streams[0].bytes = in_bytes;
-  sa.k = 1;
-  sa.check_match = 0;
-  sa.index = l.index;
-  sa.ctl = l.ctl;
-  sa.desc = nullptr;
-  sa.ndesc = 0;
-  launch_index(sa, tiles, 1, stream);
+  const u64 nonce = call_nonce();
+  if (!ix) {
+    ScanArgs sa;
+    sa.streams[0].base = static_cast<const u8*>(d_in);
+    sa.streams[0].bytes = in_bytes;
+    sa.k = 1;
+    sa.check_match = 0;
+    sa.index = l.index;
+    sa.ctl = l.ctl;
+    sa.nonce = nonce;
+    launch_plain_index(sa, tiles_of_stream(in_bytes, l, false), stream);
+  }
   DecompressArgs da;
-  da.in = sa.streams[0];
+  da.in.base = static_cast<const u8*>(d_in);
+  da.in.bytes = in_bytes;
   da.out = d_out;
   da.out_cap_elems = out_cap_elems;
   da.index = l.index;
   da.ctl = l.ctl;
   da.first_value = first_value;
   da.count = count;
-  hipLaunchKernelGGL(g_indexed ? decompress_range_kernel<true> : decompress_range_kernel<false>, dim3(u32(grid)),
-                     dim3(kTileThreads), 0, stream, da);
+  da.nonce = nonce;
+  if (ranged) {
+    hipLaunchKernelGGL(ix ? decompress_range_kernel<true> : decompress_range_kernel<false>, dim3(u32(grid)),
+                       dim3(kTileThreads), 0, stream, da);
+  } else {
+    void (*kernel)(DecompressArgs) = average ? (ix ? decompress_kernel<true, true> : decompress_kernel<false, true>)
+                                             : (ix ? decompress_kernel<true, false> : decompress_kernel<false, false>);
+    launch_main(ZC_KERNEL_DECOMPRESS, kernel, dim3(u32(grid)), dim3(kTileThreads), stream, da);
+  }
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!n_out) return ZC_OK;
   return finish(d_ws, n_out, stream);
 }
 
+int zc_decompress_ex(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
+                     void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
+  return decompress_one(d_in, in_bytes, 0, ~size_t(0), false, d_out, out_cap_elems, n_out, d_ws, ws_bytes, hip_stream, false, flags);
+}
+
+int zc_decompress(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
+                  void* d_ws, size_t ws_bytes, void* hip_stream) {
+  return zc_decompress_ex(d_in, in_bytes, d_out, out_cap_elems, n_out, d_ws, ws_bytes, hip_stream, 0);
+}
+
+int zc_decompress_average(const void* d_in, size_t in_bytes, float* d_out, size_t out_cap_elems, size_t* n_out,
+                          void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
+  return decompress_one(d_in, in_bytes, 0, ~size_t(0), false, d_out, out_cap_elems, n_out, d_ws, ws_bytes, hip_stream, true, flags);
+}
+
+int zc_decompress_range(const void* d_in, size_t in_bytes, size_t first_value, size_t count, float* d_out,
+                        size_t out_cap_elems, size_t* n_out, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
+  return decompress_one(d_in, in_bytes, first_value, count, true, d_out, out_cap_elems, n_out, d_ws, ws_bytes, hip_stream, false,
+                        flags);
+}
+
 int zc_decompress_many(const void* const* d_chunks, const size_t* chunk_bytes, int k, float* const* d_outs,
-                       const size_t* out_cap_elems, size_t* n_out, void* d_ws, size_t ws_bytes, void* hip_stream) {
+                       const size_t* out_cap_elems, size_t* n_out, void* d_ws, size_t ws_bytes, void* hip_stream,
+                       unsigned flags) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if ((flags & ~ZC_STREAM_PLAIN) != 0) return ZC_ERR_ARG;
   if (k < 1 || k > ZC_MAX_K || !d_chunks || !chunk_bytes || !d_outs || !out_cap_elems || !d_ws) return ZC_ERR_ARG;
   if (!aligned16(d_ws)) return ZC_ERR_ARG;
   for (int i = 0; i < k; ++i)
     if (!d_chunks[i] || !aligned16(d_chunks[i]) || !aligned16(d_outs[i]) || (out_cap_elems[i] && !d_outs[i])) return ZC_ERR_ARG;
   for (int i = 0; i < k; ++i)
     if (chunk_bytes[i] < kHeaderBytes) return ZC_ERR_FORMAT;
+  const bool ix = is_indexed(flags);
   const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, k);
   if (l.tiles_cap < 1) return ZC_ERR_ARG;
   ScanArgs sa;
   DecompressManyArgs da;
-  u64 tiles = 1;
+  u64 tiles = 1, tiles_in = 1;
   for (int i = 0; i < k; ++i) {
     sa.streams[i].base = static_cast<const u8*>(d_chunks[i]);
     sa.streams[i].bytes = chunk_bytes[i];
     da.in[i] = sa.streams[i];
     da.out[i] = d_outs[i];
     da.out_cap_elems[i] = out_cap_elems[i];
-    u64 t = num_tiles(blocks_bound(chunk_bytes[i]));
+    const u64 t_in = tiles_of_stream(chunk_bytes[i], l, ix);
     const u64 t_out = num_tiles(num_blocks(out_cap_elems[i]));
-    if (t > t_out) t = t_out;
+    const u64 t = t_in < t_out ? t_in : t_out;
     if (t > tiles) tiles = t;
+    if (t_in > tiles_in) tiles_in = t_in;
   }
-  if (tiles > l.tiles_cap) tiles = l.tiles_cap;
-  if (tiles > kMaxTiles) tiles = kMaxTiles;
-  sa.k = k;
-  sa.check_match = 0;
-  sa.index = l.index;
-  sa.ctl = l.ctl;
-  sa.desc = nullptr;
-  sa.ndesc = 0;
-  launch_index(sa, tiles, 1, stream);
+  const u64 nonce = call_nonce();
+  if (!ix) {
+    sa.k = k;
+    sa.check_match = 0;
+    sa.index = l.index;
+    sa.ctl = l.ctl;
+    sa.nonce = nonce;
+    launch_plain_index(sa, tiles_in, stream);
+  }
+  da.k = k;
   da.index = l.index;
   da.ctl = l.ctl;
-  void (*kernel)(DecompressManyArgs) = g_indexed ? decompress_many_kernel<true> : decompress_many_kernel<false>;
+  da.nonce = nonce;
+  void (*kernel)(DecompressManyArgs) = ix ? decompress_many_kernel<true> : decompress_many_kernel<false>;
   launch_main(ZC_KERNEL_DECOMPRESS, kernel, dim3(u32(tiles), u32(k)), dim3(kTileThreads), stream, da);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!n_out) return ZC_OK;
+  // every header that passes validation holds its stream's n: fetch them along with the status
+  u64 ns[ZC_MAX_K];
+  for (int i = 0; i < k; ++i)
+    if (hipMemcpyAsync(&ns[i], static_cast<const u8*>(d_chunks[i]) + 8, 8, hipMemcpyDeviceToHost, stream) != hipSuccess)
+      return ZC_ERR_HIP;
   size_t total = 0;
   const int st = finish(d_ws, &total, stream);
   if (st == ZC_ERR_HIP || st == ZC_ERR_ARG || st == ZC_ERR_FORMAT) return st;
-  for (int i = 0; i < k; ++i) {          // every header passed validation: its n is the stream's
-    u64 n = 0;
-    if (hipMemcpy(&n, static_cast<const u8*>(d_chunks[i]) + 8, 8, hipMemcpyDeviceToHost) != hipSuccess) return ZC_ERR_HIP;
-    n_out[i] = size_t(n);
-  }
+  for (int i = 0; i < k; ++i) n_out[i] = size_t(ns[i]);
   return st;
 }
 
-int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes, int k, void* d_out, size_t out_cap,
-                         size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
+int zc_reduce_compressed_ex(const void* const* d_chunks, const size_t* chunk_bytes, int k, void* d_out, size_t out_cap,
+                            size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (!flags_valid(flags)) return ZC_ERR_ARG;
   if (k < 1 || k > ZC_MAX_K || !d_chunks || !chunk_bytes || !d_out || !d_ws) return ZC_ERR_ARG;
   if (!aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
   for (int i = 0; i < k; ++i)
     if (!d_chunks[i] || !aligned16(d_chunks[i])) return ZC_ERR_ARG;
   for (int i = 0; i < k; ++i)
     if (chunk_bytes[i] < kHeaderBytes) return ZC_ERR_FORMAT;
+  const bool ix = is_indexed(flags);
   const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, k);
   if (l.tiles_cap < 1) return ZC_ERR_ARG;
-  u64 tiles = l.tiles_cap;
+  // the output's tiles need a look-back descriptor each, whatever the variant
+  u64 tiles = l.tiles_cap, tiles_in = 1;
   for (int i = 0; i < k; ++i) {
     const u64 t = num_tiles(blocks_bound(chunk_bytes[i]));
     if (t < tiles) tiles = t;
+    if (t > tiles_in) tiles_in = t;
   }
   if (tiles > kMaxTiles) tiles = kMaxTiles;
   if (tiles < 1) tiles = 1;
+  if (tiles_in > l.tiles_cap) tiles_in = l.tiles_cap;
   ScanArgs sa;
   ReduceArgs ra;
   for (int i = 0; i < k; ++i) {
@@ -465,59 +483,68 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
     sa.streams[i].bytes = chunk_bytes[i];
     ra.in[i] = sa.streams[i];
   }
-  sa.k = k;
-  sa.check_match = 1;
-  sa.index = l.index;
-  sa.ctl = l.ctl;
-  sa.desc = l.desc;
-  sa.ndesc = u32(tiles);
-  launch_index(sa, tiles, prep_grid_for(tiles), stream);
+  const u64 nonce = call_nonce();
+  if (!ix) {
+    sa.k = k;
+    sa.check_match = 1;
+    sa.index = l.index;
+    sa.ctl = l.ctl;
+    sa.nonce = nonce;
+    launch_plain_index(sa, tiles_in, stream);
+  }
   ra.k = k;
   ra.index = l.index;
   ra.out = static_cast<u8*>(d_out);
   ra.out_cap = out_cap;
   ra.ctl = l.ctl;
   ra.desc = l.desc;
-  ra.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
-  void (*narrow)(ReduceArgs) = g_indexed ? reduce_kernel<true> : reduce_kernel<false>;
-  launch_main(ZC_KERNEL_REDUCE, narrow, dim3(u32(tiles)), dim3(kTileThreads), stream, ra);
-  // for operands with blocks wider than 15 bits; returns at once otherwise
-  hipLaunchKernelGGL(g_indexed ? reduce_wide_kernel<true> : reduce_wide_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), 0,
-                     stream, ra);
+  ra.ticketed = (flags & ZC_TILES_BY_TICKET) != 0;
+  ra.nonce = nonce;
+  launch_main(ZC_KERNEL_REDUCE, ix ? reduce_kernel<true> : reduce_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), stream, ra);
+  // plain streams with blocks wider than 15 bits have a kernel of their own, which returns at once otherwise
+  if (!ix) hipLaunchKernelGGL(reduce_wide_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
 }
 
+int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes, int k, void* d_out, size_t out_cap,
+                         size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
+  return zc_reduce_compressed_ex(d_chunks, chunk_bytes, k, d_out, out_cap, out_bytes, d_ws, ws_bytes, hip_stream, 0);
+}
+
 int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, void* d_out,
                    size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
   return zc_reduce_step_op(d_chunk, chunk_bytes, d_local, n_local, ZC_OP_SUM, d_out, out_cap, out_bytes, d_ws, ws_bytes,
-                           hip_stream);
+                           hip_stream, 0);
 }
 
 int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, int op, void* d_out,
-                      size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
+                      size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (op != ZC_OP_SUM && op != ZC_OP_MAX && op != ZC_OP_MIN) return ZC_ERR_ARG;
+  if (!flags_valid(flags) || (op != ZC_OP_SUM && op != ZC_OP_MAX && op != ZC_OP_MIN)) return ZC_ERR_ARG;
   if (!d_chunk || !d_out || !d_ws || (n_local && !d_local) || n_local > ZC_MAX_N) return ZC_ERR_ARG;
   if (!aligned16(d_chunk) || !aligned16(d_local) || !aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
   if (chunk_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
+  const bool ix = is_indexed(flags);
   const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
   u64 tiles = num_tiles(num_blocks(n_local));
   if (l.tiles_cap < 1 || tiles > l.tiles_cap) return ZC_ERR_ARG;
   if (tiles < 1) tiles = 1;
-  ScanArgs sa;
-  sa.streams[0].base = static_cast<const u8*>(d_chunk);
-  sa.streams[0].bytes = chunk_bytes;
-  sa.k = 1;
-  sa.check_match = 0;
-  sa.index = l.index;
-  sa.ctl = l.ctl;
-  sa.desc = l.desc;
-  sa.ndesc = u32(tiles);
-  launch_index(sa, tiles, prep_grid_for(tiles), stream);
+  const u64 nonce = call_nonce();
   StepArgs ta;
-  ta.in = sa.streams[0];
+  ta.in.base = static_cast<const u8*>(d_chunk);
+  ta.in.bytes = chunk_bytes;
+  if (!ix) {
+    ScanArgs sa;
+    sa.streams[0] = ta.in;
+    sa.k = 1;
+    sa.check_match = 0;
+    sa.index = l.index;
+    sa.ctl = l.ctl;
+    sa.nonce = nonce;
+    launch_plain_index(sa, tiles_of_stream(chunk_bytes, l, false), stream);
+  }
   ta.local = d_local;
   ta.n_local = n_local;
   ta.index = l.index;
@@ -525,11 +552,12 @@ int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_lo
   ta.out_cap = out_cap;
   ta.ctl = l.ctl;
   ta.desc = l.desc;
-  ta.ticketed = g_hand_out == ZC_HAND_OUT_TICKETS;
+  ta.ticketed = (flags & ZC_TILES_BY_TICKET) != 0;
+  ta.nonce = nonce;
   void (*kernel)(StepArgs) = nullptr;
-  if (op == ZC_OP_SUM) kernel = g_indexed ? step_kernel<true, ZC_OP_SUM> : step_kernel<false, ZC_OP_SUM>;
-  else if (op == ZC_OP_MAX) kernel = g_indexed ? step_kernel<true, ZC_OP_MAX> : step_kernel<false, ZC_OP_MAX>;
-  else kernel = g_indexed ? step_kernel<true, ZC_OP_MIN> : step_kernel<false, ZC_OP_MIN>;
+  if (op == ZC_OP_SUM) kernel = ix ? step_kernel<true, ZC_OP_SUM> : step_kernel<false, ZC_OP_SUM>;
+  else if (op == ZC_OP_MAX) kernel = ix ? step_kernel<true, ZC_OP_MAX> : step_kernel<false, ZC_OP_MAX>;
+  else kernel = ix ? step_kernel<true, ZC_OP_MIN> : step_kernel<false, ZC_OP_MIN>;
   launch_main(ZC_KERNEL_REDUCE_STEP, kernel, dim3(u32(tiles)), dim3(kTileThreads), stream, ta);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
@@ -567,18 +595,6 @@ int zc_quality(const float* d_ref, const float* d_test, size_t n, double* out4, 
   return ZC_OK;
 }
 
-
-int zc_set_indexed_streams(int on) {
-  g_indexed = on != 0;
-  return ZC_OK;
-}
-
-int zc_set_tile_hand_out(int mode) {
-  if (mode != ZC_HAND_OUT_DISPATCH_ORDER && mode != ZC_HAND_OUT_TICKETS) return ZC_ERR_ARG;
-  g_hand_out = mode;
-  return ZC_OK;
-}
-
 int zc_profile_enable(int on) {
   std::lock_guard<std::mutex> g(g_timer.mu);
   g_timer.kinds = on == 1 ? ~0u : unsigned(on) & ~1u;      // 1: every kind; else a set of (1 << ZC_KERNEL_x)
@@ -605,7 +621,7 @@ int zc_profile_collect(float* ms, int* kernel, int cap) {
 }
 
 int zc_peek_header(const void* d_in, size_t in_bytes, size_t* n, float* abs_eb, unsigned* nsum,
-                   size_t* total_bytes, void* hip_stream) {
+                   size_t* total_bytes, unsigned* flags, void* hip_stream) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (!d_in) return ZC_ERR_ARG;
   if (in_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
@@ -616,14 +632,16 @@ int zc_peek_header(const void* d_in, size_t in_bytes, size_t* n, float* abs_eb, 
   const u64 total = u64(w[6]) | (u64(w[7]) << 32);
   float eb;
   std::memcpy(&eb, &w[4], 4);
-  const bool version_ok = g_indexed ? (w[1] | 1u) == (kVersionIndexed | 1u) : w[1] == kVersionPlain;
-  if (w[0] != kMagic || !version_ok || nn > ZC_MAX_N || !eb_valid(eb) || w[5] < 1 || total > in_bytes ||
-      total < tables_end(num_blocks(nn), g_indexed))
+  // the version word tells the variant
+  const bool plain = w[1] == kVersionPlain, indexed = (w[1] | 1u) == (kVersionIndexed | 1u);
+  if (w[0] != kMagic || !(plain || indexed) || nn > ZC_MAX_N || !eb_valid(eb) || w[5] < 1 || total > in_bytes ||
+      total < tables_end(num_blocks(nn), indexed))
     return ZC_ERR_FORMAT;
   if (n) *n = size_t(nn);
   if (abs_eb) *abs_eb = eb;
   if (nsum) *nsum = w[5];
   if (total_bytes) *total_bytes = size_t(total);
+  if (flags) *flags = plain ? ZC_STREAM_PLAIN : 0u;
   return ZC_OK;
 }
 
@@ -633,42 +651,46 @@ int zc_debug_quantize(const float* d_in, size_t n, float abs_eb, int32_t* d_q, v
   if (!eb_valid(abs_eb) || n > ZC_MAX_N || (n && (!d_in || !d_q)) || !d_ws || ws_bytes < sizeof(Control))
     return ZC_ERR_ARG;
   const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
-  CompressArgs ca;
-  fill_compress_args(ca, d_in, n, abs_eb, nullptr, 0, l);
-  launch_init(l, 0, nullptr, 0, 0, 0, stream);
-  if (n) hipLaunchKernelGGL(quantize_kernel, dim3(u32((n + 255) / 256)), dim3(256), 0, stream, ca, d_q);
+  QuantizeArgs qa;
+  fill_compress_args(qa.c, d_in, n, abs_eb, nullptr, 0, l, 0);
+  qa.q = d_q;
+  // (at least one workgroup: the first one opens the call, which zc_finish reads back)
+  hipLaunchKernelGGL(quantize_kernel, dim3(u32(n ? (n + 255) / 256 : 1)), dim3(256), 0, stream, qa);
   if (!launch_ok()) return ZC_ERR_HIP;
   return finish(d_ws, nullptr, stream);
 }
 
 int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_words, size_t off_cap, void* d_ws,
-                           size_t ws_bytes, void* hip_stream) {
+                           size_t ws_bytes, void* hip_stream, unsigned flags) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if ((flags & ~ZC_STREAM_PLAIN) != 0) return ZC_ERR_ARG;
   if (!d_in || !d_ws || (off_cap && !d_off_words) || !aligned16(d_in) || !aligned16(d_ws)) return ZC_ERR_ARG;
   if (in_bytes < kHeaderBytes) return ZC_ERR_FORMAT;
+  const bool ix = is_indexed(flags);
   const WorkspaceLayout l = workspace_layout(d_ws, ws_bytes, 1);
   if (l.tiles_cap < 1) return ZC_ERR_ARG;
-  u64 tiles = num_tiles(blocks_bound(in_bytes));
-  if (tiles > l.tiles_cap) tiles = l.tiles_cap;
-  if (tiles > kMaxTiles) tiles = kMaxTiles;
-  if (tiles < 1) tiles = 1;
-  ScanArgs sa;
-  sa.streams[0].base = static_cast<const u8*>(d_in);
-  sa.streams[0].bytes = in_bytes;
-  sa.k = 1;
-  sa.check_match = 0;
-  sa.index = l.index;
-  sa.ctl = l.ctl;
-  sa.desc = nullptr;
-  sa.ndesc = 0;
-  launch_index(sa, tiles, 1, stream);
+  const u64 tiles = tiles_of_stream(in_bytes, l, ix);
+  const u64 nonce = call_nonce();
+  if (!ix) {
+    ScanArgs sa;
+    sa.streams[0].base = static_cast<const u8*>(d_in);
+    sa.streams[0].bytes = in_bytes;
+    sa.k = 1;
+    sa.check_match = 0;
+    sa.index = l.index;
+    sa.ctl = l.ctl;
+    sa.nonce = nonce;
+    launch_plain_index(sa, tiles, stream);
+  }
   OffsetsArgs oa;
-  oa.in = sa.streams[0];
+  oa.in.base = static_cast<const u8*>(d_in);
+  oa.in.bytes = in_bytes;
   oa.index = l.index;
   oa.off_words = d_off_words;
   oa.off_cap = off_cap;
   oa.ctl = l.ctl;
-  oa.ix = g_indexed;
+  oa.nonce = nonce;
+  oa.ix = ix;
   hipLaunchKernelGGL(block_offsets_kernel, dim3(u32(tiles)), dim3(256), 0, stream, oa);
   if (!launch_ok()) return ZC_ERR_HIP;
   return finish(d_ws, nullptr, stream);

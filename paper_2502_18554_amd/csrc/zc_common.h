@@ -17,6 +17,8 @@ using u32 = uint32_t;
 using u64 = uint64_t;
 using i32 = int32_t;
 using i64 = int64_t;
+typedef u32 u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr u32 kMagic = 0x314C435Au;
 constexpr u32 kHeaderBytes = 32;
@@ -43,7 +45,7 @@ __host__ __device__ inline u32 psize_words(u32 w) { return w ? 1 + w : 0; }
 // than 15 bits, and between header and width table an index of nseg + 1 u32: entry i is the
 // payload word offset of segment i, entry nseg the number of payload words; zero padded to 16
 // bytes.  `ix` says which of the two a kernel reads and writes; it is the same for every
-// stream of a process at any one time (zc_set_indexed_streams).
+// stream of one call (the call's flags say which).
 __host__ __device__ inline u64 num_segments(u64 nb) { return (nb + kWaveBlocks - 1) / kWaveBlocks; }
 __host__ __device__ inline u64 index_bytes(u64 nb, bool ix) { return ix ? pad16(4 * (num_segments(nb) + 1)) : 0; }
 __host__ __device__ inline u64 widths_begin(u64 nb, bool ix) { return kHeaderBytes + index_bytes(nb, ix); }
@@ -55,18 +57,23 @@ constexpr u32 kVersionIndexed = 2u | (5u << 16) | (6u << 24);   // | 1 when some
 // Device status word: bit i set <=> error code i was raised.
 __host__ __device__ constexpr u32 status_bit(int code) { return 1u << code; }
 
-// Errors that only the validation kernels (zc_scan.h) raise.  They are final before a main
-// kernel starts, so every workgroup of a main kernel takes the same decision on them.
+// Errors that stop a call before it writes anything: bad arguments, malformed or mismatched
+// input streams.  Every workgroup of a main kernel takes the same decision on them, either
+// from the verdict the validation kernel of plain streams left (zc_scan.h) or from the same
+// header bytes (indexed streams).
 constexpr u32 kGateBits = status_bit(ZC_ERR_ARG) | status_bit(ZC_ERR_FORMAT) | status_bit(ZC_ERR_MISMATCH);
 
-// Control part of the caller's workspace.  Tile descriptors and segment-offset tables follow.
+// Control part of the caller's workspace.  Tile tickets, tile descriptors and segment-offset
+// tables follow.  Nothing in a workspace is ever cleared: whatever one call shares between its
+// workgroups or its launches carries the call's tag (below), and a word with another tag counts
+// as empty, so a workspace may hold anything when a call starts.
 constexpr int kTicketShards = 8;
 struct Control {
-  u32 status;                  // OR of status_bit()s
-  u32 flags;                   // kFlagWide: some input stream has a block wider than 15 bits
+  u64 status;                  // bits 63..32: high half of the tag of the call that raised them; bits 31..0: OR of status_bit()s and kStatusWide
+  u64 call_tag;                // tag of the last call's first launch; its later launches take it from here
   u64 result;                  // total_bytes, or n for decompress
-  u64 nsum;                    // sum of the input streams' nsum fields (set by index_prep_kernel)
-  u32 pad[10];
+  u64 nsum;                    // sum of the input streams' nsum fields (plain streams: set by index_prep_kernel)
+  u32 pad[8];
 };
 static_assert(sizeof(Control) == 64, "control block is 64 bytes");
 
@@ -74,10 +81,10 @@ static_assert(sizeof(Control) == 64, "control block is 64 bytes");
 // in a 128-byte line of its own, and none shares the line of the control block: accesses to
 // one line retire one after the other even when they address different words of it, and every
 // workgroup reads the control block when it starts.
-constexpr int kTicketStride = 32;            // in u32
-constexpr u64 kTicketBytes = u64(kTicketShards + 1) * kTicketStride * 4;
-__host__ __device__ inline u32* ticket_counter(Control* ctl, u32 shard) {
-  return reinterpret_cast<u32*>(ctl + 1) + (shard + 1) * kTicketStride;
+constexpr int kTicketStride = 16;            // in u64
+constexpr u64 kTicketBytes = u64(kTicketShards + 1) * kTicketStride * 8;
+__host__ __device__ inline u64* ticket_counter(Control* ctl, u32 shard) {
+  return reinterpret_cast<u64*>(ctl + 1) + (shard + 1) * kTicketStride;
 }
 
 // A segment is the 64 blocks owned by one wave; a tile is 4 segments.
@@ -150,14 +157,9 @@ __host__ inline WorkspaceLayout workspace_layout(void* d_ws, u64 ws_bytes, int k
 // ---------------------------------------------------------------------------------------
 __device__ inline int lane_id() { return int(threadIdx.x) & 63; }
 
-constexpr u32 kFlagWide = 1u;
-// (flags and the gate bits of status are final before a main kernel starts: plain loads)
-__device__ inline bool streams_are_wide(const Control* ctl) { return (ctl->flags & kFlagWide) != 0; }
-
-// True when validation failed and the main kernel must not touch the stream.
-__device__ inline bool validation_failed(const Control* ctl) {
-  return (ctl->status & kGateBits) != 0;
-}
+// Not an error: the validation kernel of plain streams found a block wider than 15 bits (the
+// host ignores the bit).
+constexpr u32 kStatusWide = 1u << 16;
 
 // Tile hand-out.  A kernel that places its output by look-back needs every tile below a tile
 // in work to be in work too, or finished.  Two ways to get that:
@@ -188,12 +190,35 @@ __device__ inline u32 tile_of_ticket(u32 shard, u32 ticket, u32 ntiles) {
   return t < ntiles ? u32(t) : kNoTile;
 }
 
+// A ticket counter is a 64-bit word: the top 40 bits of the tag of the launch that counts in it,
+// then 24 bits of count.  A word with another tag is a counter at zero.  The common case is one
+// atomic add; the first workgroups of a launch to reach a counter find the tag of an older
+// launch (or anything at all) in it and install their own by compare-and-swap.
+constexpr u64 kTicketCountMask = (u64(1) << 24) - 1;
+
+__device__ inline u32 take_ticket(u64* counter, u64 ltag) {
+  const u64 mine = ltag & ~kTicketCountMask;
+  u64 old = atomicAdd(reinterpret_cast<unsigned long long*>(counter), 1ull);
+  if ((old & ~kTicketCountMask) == mine) return u32(old & kTicketCountMask);
+  old = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (u32 tries = 0; tries < kSpinLimit; ++tries) {
+    if ((old & ~kTicketCountMask) == mine) {
+      old = atomicAdd(reinterpret_cast<unsigned long long*>(counter), 1ull);
+      if ((old & ~kTicketCountMask) == mine) return u32(old & kTicketCountMask);
+    } else if (__hip_atomic_compare_exchange_strong(counter, &old, mine | 1ull, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT)) {
+      return 0u;
+    }
+  }
+  return u32(kTicketCountMask);            // never handed out as a tile: the caller finds no tile
+}
+
 // Claims the next tile (called by one thread of a workgroup).  kNoTile when none is left.
-__device__ inline u32 take_tile(Control* ctl, u32 ntiles, u32 first_shard) {
+__device__ inline u32 take_tile(Control* ctl, u64 ltag, u32 ntiles, u32 first_shard) {
   for (u32 i = 0; i < u32(kTicketShards); ++i) {
     const u32 y = (first_shard + i) & (kTicketShards - 1);
     if (y >= ntiles) continue;
-    const u32 t = tile_of_ticket(y, atomicAdd(ticket_counter(ctl, y), 1u), ntiles);
+    const u32 t = tile_of_ticket(y, take_ticket(ticket_counter(ctl, y), ltag), ntiles);
     if (t != kNoTile) return t;
   }
   return kNoTile;
@@ -216,6 +241,60 @@ __device__ inline u32 lane_value(u32 v, int lane) { return u32(__builtin_amdgcn_
 // it are scalar branches.
 __device__ inline u32 uniform(u32 v) { return u32(__builtin_amdgcn_readfirstlane(int(v))); }
 __device__ inline u64 uniform64(u64 v) { return u64(uniform(u32(v))) | (u64(uniform(u32(v >> 32))) << 32); }
+
+// ---------------------------------------------------------------------------------------
+// Call tags.  A tag is a 64-bit number that is the same in every workgroup of one launch and
+// that no earlier launch on the same workspace has had: the packet number of the dispatch in
+// its hardware queue (which a replay of a captured graph renews as well), the queue, a number
+// the host draws per call (its clock), and the workspace address, mixed.  A call of several
+// launches (a stream compressed in parts, the ragged last tile, the validation kernels of plain
+// streams) uses the tag of its first launch throughout: that launch leaves it in the control
+// block, the later ones pick it up there (`adopt`).
+// ---------------------------------------------------------------------------------------
+extern "C" __device__ u64 zc_dispatch_id(void) __asm("llvm.amdgcn.dispatch.id");
+
+__device__ inline u64 mix64(u64 x) {
+  x ^= x >> 31;
+  x *= 0x9E3779B97F4A7C15ull;
+  x ^= x >> 29;
+  return x;
+}
+
+__device__ inline u64 launch_tag(u64 nonce, const void* ws) {
+  const u64 queue = u64(reinterpret_cast<uintptr_t>(__builtin_amdgcn_queue_ptr()));
+  u64 t = mix64(zc_dispatch_id() + 0x632BE59BD9B4E019ull * (queue >> 6));
+  t = mix64(t ^ nonce);
+  t = mix64(t + u64(reinterpret_cast<uintptr_t>(ws)));
+  return uniform64(t);
+}
+
+// The tag of the call this launch belongs to; the first launch of a call also records it.
+__device__ inline u64 call_tag(Control* ctl, u64 ltag, bool adopt) {
+  if (adopt) return uniform64(*reinterpret_cast<volatile const u64*>(&ctl->call_tag));
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) ctl->call_tag = ltag;
+  return ltag;
+}
+
+// Status bits are raised under the call's tag: the first raise of a call replaces whatever an
+// earlier call left, later ones add to it.  Rare, so a compare-and-swap loop will do.
+__device__ inline void raise_status(Control* ctl, u64 tag, u32 bits) {
+  const u64 mine = tag & 0xffffffff00000000ull;
+  u64 old = __hip_atomic_load(&ctl->status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int tries = 0; tries < 4096; ++tries) {
+    const u64 want = ((old & 0xffffffff00000000ull) == mine ? old : mine) | bits;
+    if (want == old) return;
+    if (__hip_atomic_compare_exchange_strong(&ctl->status, &old, want, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT))
+      return;
+  }
+}
+
+// The bits raised so far under this tag.
+__device__ inline u32 status_bits(const Control* ctl, u64 tag) {
+  const u64 v = __hip_atomic_load(&ctl->status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return (v >> 32) == (tag >> 32) ? u32(v) : 0u;
+}
+
 // Loads and stores of data that a kernel touches once, with the non-temporal hint.  Such data
 // then neither pushes the lines that are used again (the stream index, tables shared by
 // neighbouring waves, tile descriptors) out of the L2, nor stays behind as dirty lines that
@@ -226,8 +305,6 @@ __device__ inline u64 uniform64(u64 v) { return u64(uniform(u32(v))) | (u64(unif
 // streams side by side) and the payload it writes (-14 us).  It costs time on the payload the
 // compression writes (the decompression that follows finds it in the memory-side cache
 // otherwise) and on the payload and outlier loads of the decompression.
-typedef u32 u32x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
 __device__ inline uint4 load_once(const uint4* p) {
   const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(t.x, t.y, t.z, t.w);
@@ -305,26 +382,48 @@ __device__ inline u32 wave_inclusive_sum(u32 v) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Decoupled look-back over tile descriptors.  A descriptor is one 64-bit word:
-// bits 63..62 = state (0 empty, 1 tile aggregate, 2 inclusive prefix), bit 61 = the tile (or,
-// in a prefix, some tile up to this one) holds a block wider than 15 bits, bits 60..0 = value.
-// Only the descriptor word itself is communicated, so relaxed device-scope atomics suffice.
+// Decoupled look-back over tile descriptors.  A descriptor is two 64-bit words in a 128-byte
+// line of its own.  Word 0: bits 63..62 = state (0 empty, 1 tile aggregate, 2 inclusive
+// prefix), bit 61 = the tile (or, in a prefix, some tile up to this one) holds a block wider
+// than 15 bits, bits 60..32 = the low 29 bits of the call's tag, bits 31..0 = value (payload
+// words: a stream has fewer than 2^32).  Word 1: the call's tag.  A descriptor counts only
+// when both words carry the reader's tag; anything else is an empty descriptor, so nothing has
+// to be cleared before a call.  A reader that catches one new and one old word sees a
+// mismatch and polls again.
+// Only the descriptor itself is communicated, so relaxed device-scope atomics suffice.
 // ---------------------------------------------------------------------------------------
 constexpr u64 kDescAggregate = u64(1) << 62;
 constexpr u64 kDescPrefix = u64(2) << 62;
 constexpr u64 kDescWide = u64(1) << 61;
-constexpr u64 kDescValueMask = (u64(1) << 61) - 1;
+constexpr u64 kDescValueMask = (u64(1) << 32) - 1;
+constexpr u64 kDescTagMask = ((u64(1) << 29) - 1) << 32;
 
 // Descriptors are polled by every tile in flight, so neighbours must not share a memory
 // line (polls of one line queue up behind each other): one descriptor per 128 bytes.
 constexpr int kDescStride = 16;            // in u64
 __host__ __device__ inline u64 desc_slot(u64 tile) { return tile * kDescStride; }
 
-__device__ inline void desc_store(u64* d, u64 v) {
-  __hip_atomic_store(d, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Both words travel in one 16-byte access (a hot line serves its requests one after the other,
+// so a second access per poll or publication would double the time the look-back chain takes),
+// device-coherent (sc1).  Nothing depends on that access being indivisible: torn halves fail
+// the tag check above.
+__device__ inline __amdgpu_buffer_rsrc_t desc_resource(const u64* desc) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<u64*>(desc), 0, 0x7fffffff, 0x00020000);
 }
-__device__ inline u64 desc_load(const u64* d) {
-  return __hip_atomic_load(d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+constexpr int kCoherentAccess = 16;        // cache policy bits of the buffer builtins: sc1
+
+// v = state | wide mark | value.
+__device__ inline void desc_store(u64* desc, u32 tile, u64 v, u64 tag) {
+  const u64 a = v | ((tag << 32) & kDescTagMask);
+  const u32x4_t words = {u32(a), u32(a >> 32), u32(tag), u32(tag >> 32)};
+  __builtin_amdgcn_raw_buffer_store_b128(words, desc_resource(desc), tile * u32(kDescStride * 8), 0, kCoherentAccess);
+}
+// state | wide mark | value of a descriptor of this call; 0 (empty) for anything else.
+__device__ inline u64 desc_load(const u64* desc, u32 tile, u64 tag) {
+  const u32x4_t w = __builtin_amdgcn_raw_buffer_load_b128(desc_resource(desc), tile * u32(kDescStride * 8), 0, kCoherentAccess);
+  const u64 v = u64(w.x) | (u64(w.y) << 32);
+  const u64 t = u64(w.z) | (u64(w.w) << 32);
+  return (t == tag && (v & kDescTagMask) == ((tag << 32) & kDescTagMask)) ? (v & ~kDescTagMask) : 0ull;
 }
 
 // LDS of one wave: 32 rows (blocks) of 32 codes + 4 words of padding, which keeps the 128-bit
@@ -349,14 +448,6 @@ __device__ inline void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// 32-bit values passed between workgroups of one kernel (group sums of the stream index).
-__device__ inline void desc32_store(u32* d, u32 v) {
-  __hip_atomic_store(d, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline u32 desc32_load(const u32* d) {
-  return __hip_atomic_load(d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // Called by all 64 lanes of one wave.  Returns the sum of the values of tiles [0, tile), with
 // kDescWide set if one of those tiles has it set.
 // Every tile below `tile` is in work on a resident workgroup (or done), and a workgroup
@@ -367,16 +458,16 @@ __device__ inline u32 desc32_load(const u32* d) {
 constexpr int kLookLanes = 32;
 
 // One poll: lane l < kLookLanes fetches the descriptor of tile `look` - l.
-__device__ inline u64 lookback_poll(const u64* desc, i64 look) {
+__device__ inline u64 lookback_poll(const u64* desc, i64 look, u64 tag) {
   const i64 idx = look - lane_id();
   u64 d = kDescPrefix;                       // "tile -1" has prefix 0
-  if (lane_id() < kLookLanes && idx >= 0) d = desc_load(desc + desc_slot(u64(idx)));
+  if (lane_id() < kLookLanes && idx >= 0) d = desc_load(desc, u32(idx), tag);
   return d;
 }
 
-// `first` = lookback_poll(desc, tile - 1), issued by the caller, who may put other memory
+// `first` = lookback_poll(desc, tile - 1, tag), issued by the caller, who may put other memory
 // operations between that poll and this call so that they overlap with its round trip.
-__device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status, u64 first) {
+__device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, Control* ctl, u64 tag, u64 first) {
   const int lane = lane_id();
   const u64 lanes_mask = kLookLanes == 64 ? ~u64(0) : ((u64(1) << kLookLanes) - 1);
   u64 excl = 0;
@@ -387,35 +478,27 @@ __device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status,
   while (true) {
     const u32 state = u32(d >> 62);
     const u64 has_prefix = __ballot(state == 2) & lanes_mask;
-    const u64 is_empty = __ballot(state == 0) & lanes_mask;
+    const u64 is_empty = __ballot(state == 0 || state == 3) & lanes_mask;
     const int first_prefix = has_prefix ? __builtin_ctzll(has_prefix) : kLookLanes - 1;
     const u64 needed = first_prefix == 63 ? ~u64(0) : ((u64(2) << first_prefix) - 1);   // lanes 0..first_prefix
     if (is_empty & needed) {
       // give up after kSpinLimit polls, or as soon as another tile has given up
-      const bool lost = (++spins & 1023u) == 0 &&
-                        (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & status_bit(ZC_ERR_HIP)) != 0;
+      const bool lost = (++spins & 1023u) == 0 && (status_bits(ctl, tag) & status_bit(ZC_ERR_HIP)) != 0;
       if (spins > kSpinLimit || lost) {
-        if (lane == 0) atomicOr(status, status_bit(ZC_ERR_HIP));
+        if (lane == 0) raise_status(ctl, tag, status_bit(ZC_ERR_HIP));
         return excl | wide;
       }
       __builtin_amdgcn_s_sleep(1);
-      d = lookback_poll(desc, look);
+      d = lookback_poll(desc, look, tag);
       continue;
     }
     if (__ballot((d & kDescWide) != 0) & lanes_mask & needed) wide = kDescWide;
-    // lanes before `first_prefix` hold tile aggregates (small); lane `first_prefix` may hold a prefix (64-bit)
+    // lanes before `first_prefix` hold tile aggregates (small); lane `first_prefix` may hold a prefix
     excl += wave_sum_u32(lane < first_prefix || (lane == first_prefix && !has_prefix) ? u32(d) : 0u);
-    if (has_prefix) {
-      const u64 p = u64(lane_value(u32(d), first_prefix)) | (u64(lane_value(u32(d >> 32), first_prefix)) << 32);
-      return (excl + (p & kDescValueMask)) | wide;
-    }
+    if (has_prefix) return (excl + u64(lane_value(u32(d), first_prefix))) | wide;
     look -= kLookLanes;                      // a complete window is final: aggregates never change
-    d = lookback_poll(desc, look);
+    d = lookback_poll(desc, look, tag);
   }
-}
-
-__device__ inline u64 lookback_exclusive(const u64* desc, u32 tile, u32* status) {
-  return lookback_exclusive(desc, tile, status, lookback_poll(desc, i64(tile) - 1));
 }
 
 }  // namespace zc

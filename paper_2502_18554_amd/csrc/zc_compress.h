@@ -41,6 +41,8 @@ struct CompressArgs {
   u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
   u32 ix;            // write an indexed stream (see index_bytes)
   u32 part_end;      // zc_compress_part: one past the last tile of this call; else 0
+  u32 adopt;         // this launch continues a call (a later part, the ragged last tile): its tag is in the control block
+  u64 nonce;         // drawn by the host per call, goes into the tag (see launch_tag)
 };
 
 // Round-to-nearest-even of r for |r| < 2^31 as the low word of r + 1.5 * 2^52.
@@ -259,7 +261,8 @@ __device__ inline void wide_tile(const CompressArgs& a, const PayloadSink& sink,
 // One workgroup per tile.  FULL = the launch covers tiles whose 16384 values all exist
 // (pure 16-byte loads, no tail), tile = first_tile + workgroup id, or + a ticket (see
 // take_tile), over [first_tile, end_tile); the ragged last tile of an input runs as a launch
-// of its own, of one workgroup, with FULL = false on tile first_tile.
+// of its own, of one workgroup, with FULL = false on tile first_tile.  There is no set-up
+// launch: tile 0 writes the header, and nothing in the workspace needs clearing (see launch_tag).
 template <bool FULL>
 __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
   __shared__ __attribute__((aligned(16))) u32 lds[kPackWaves * kWaveStage];
@@ -275,18 +278,25 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
   const bool tables_fit = a.out_cap >= tables_end(a.nb, a.ix);
   u32 err = 0;
 
+  const u64 ltag = launch_tag(a.nonce, a.ctl);
+  const u64 tag = call_tag(a.ctl, ltag, a.adopt != 0);
   u32 tile = first_tile;
   if (FULL) {
     tile = first_tile + blockIdx.x;          // tiles in the order in which workgroups start
     if (a.ticketed) {                        // ... or handed out by tickets, see take_tile
       if (threadIdx.x == 0) {
-        const u32 t = take_tile(a.ctl, end_tile - first_tile, xcc_id());
+        const u32 t = take_tile(a.ctl, ltag, end_tile - first_tile, xcc_id());
         sh_tile = t == kNoTile ? kNoTile : first_tile + t;
       }
       __syncthreads();
       tile = uniform(sh_tile);
     }
     if (tile >= end_tile) return;
+  }
+  // the first tile also writes the fixed header fields and the padding of the tables
+  if (tile == 0 && threadIdx.x == 0) {
+    if (tables_fit) write_stream_header(a.out, a.n, a.nb, a.eb_bits, 1u, a.ix != 0, false);
+    else raise_status(a.ctl, tag, status_bit(ZC_ERR_CAPACITY));
   }
   {
     const u64 wblock0 = u64(tile) * kPackBlocks + u64(wave) * kWaveBlocks;
@@ -329,7 +339,7 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
     tile_wmax = uniform(tile_wmax);
     // publish the tile's size as early as possible: the tiles after this one wait for it
     pl.tile_wide = a.ix && tile_wmax > 15;
-    const PayloadSink sink{a.out, a.out_cap, a.nb, a.ctl, a.desc, a.ix != 0, a.part_end};
+    const PayloadSink sink{a.out, a.out_cap, a.nb, a.ctl, a.desc, a.ix != 0, a.part_end, tag};
     if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
 
     // ---- fields -> sign + plane words in registers, then the back half ----
@@ -354,46 +364,26 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
       wide_tile<FULL>(a, sink, pl, tile, ntiles, wblock0, wl, &sh_base, wave, lane);
     }
   }
-  if (err) atomicOr(&a.ctl->status, err);
+  if (err) raise_status(a.ctl, tag, err);
 }
 
-// Clears the control block and the tile descriptors, and writes the fixed header fields and
-// the zero padding of the two tables.  Runs before compress_kernel / reduce_kernel.
-struct InitArgs {
+// The stream of no values: a header (and the one closing entry of an indexed stream's index).
+struct EmptyStreamArgs {
   Control* ctl;
-  u64* desc;
-  u32 ntiles;
-  u8* out;          // may be null (decompress has no output stream)
+  u8* out;
   u64 out_cap;
-  u64 n, nb;
-  u32 eb_bits, nsum;
-  bool ix;
+  u32 eb_bits;
+  u32 ix;
+  u64 nonce;
 };
 
-// Tile tickets start from zero again for the next part of a stream produced in parts.
-__global__ void clear_tickets_kernel(Control* ctl) {
-  if (threadIdx.x < u32(kTicketShards)) *ticket_counter(ctl, threadIdx.x) = 0;
-}
-
-__global__ void init_kernel(InitArgs a) {
-  const u64 gid = u64(blockIdx.x) * blockDim.x + threadIdx.x;
-  const u64 stride = u64(gridDim.x) * blockDim.x;
-  for (u64 i = gid; i < a.ntiles; i += stride) a.desc[desc_slot(i)] = 0;
-  if (gid == 0) {
-    for (int i = 0; i < kTicketShards; ++i) *ticket_counter(a.ctl, u32(i)) = 0;
-    a.ctl->status = 0;
-    a.ctl->flags = 0;
-    a.ctl->result = 0;
-    if (a.out) {
-      const u64 tend = tables_end(a.nb, a.ix);
-      if (a.out_cap >= tend) {
-        write_stream_header(a.out, a.n, a.nb, a.eb_bits, a.nsum, a.ix, true);
-      } else {
-        a.ctl->status = status_bit(ZC_ERR_CAPACITY);
-      }
-      if (a.nb == 0) a.ctl->result = tend;
-    }
-  }
+__global__ void empty_stream_kernel(EmptyStreamArgs a) {
+  const u64 tag = call_tag(a.ctl, launch_tag(a.nonce, a.ctl), false);
+  if (threadIdx.x != 0) return;
+  const u64 tend = tables_end(0, a.ix != 0);
+  a.ctl->result = tend;
+  if (a.out_cap >= tend) write_stream_header(a.out, 0, 0, a.eb_bits, 1u, a.ix != 0, true);
+  else raise_status(a.ctl, tag, status_bit(ZC_ERR_CAPACITY));
 }
 
 }  // namespace zc

@@ -25,6 +25,7 @@ struct DecompressArgs {
   Control* ctl;
   u64 first_value;   // decompress_range_kernel only: the part [first_value, first_value + count) of the
   u64 count;         // stream, first_value a multiple of the values of a segment
+  u64 nonce;         // drawn by the host per call, goes into the call's tag (see launch_tag)
 };
 
 // The sign and plane words of the lane's block (width w, 0 for a block that does not exist) out
@@ -156,19 +157,22 @@ __device__ inline void deltas_from_block_words(u32 wmax, u32 (&lo)[16], u32 (&hi
   }
 }
 
-// One tile (blockIdx.x) of stream `s` of the index, into `out`.  `counted`: the stream's n is
-// added to the control block's result instead of stored there (several streams per call).
-// `ix`: the stream is indexed; its width bytes then sit behind the index, whose size only
-// the header tells, so they are asked for together with the outlier and the payload.
+// One tile (blockIdx.x) of stream `s` of the index, into `out`.  `many`: one of several streams
+// of a call (blockIdx.y); `others_ok`: the headers of the other streams are in order.
+// `ix`: the stream is indexed: no kernel has run ahead of this one, the header and the index
+// are judged here (see judge_indexed_streams, index_ends_ok), and the call's tag is this
+// launch's; its width bytes sit behind the index, whose size only the header tells, so they
+// are asked for together with the outlier and the payload.  A plain stream has been validated
+// and indexed by the kernels of zc_scan.h, whose verdict and tag are in the control block.
 // `average`: the values are divided by the stream's nsum (the Average aggregation of Section
 // 3.2 on a stream of sums): x' = float((double(q) * s) * r), r = 1.0 / nsum.
 // first_value, count: only the values [first_value, first_value + count) of the stream, cut off
 // at its end, are produced, into out_values[0 ...] (a chunk handled on its own, Section 3.5.2);
 // first_value is a multiple of the 2048 values of a segment.  The whole stream: 0 and ~0.
 __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u64 out_cap_elems, const StreamIndex& index,
-                                       int s, Control* ctl, bool counted, u32* lds, bool ix, bool average = false,
-                                       u64 first_value = 0, u64 count = ~u64(0)) {
-  const DecompressArgs a{in, out_values, out_cap_elems, index, ctl, first_value, count};
+                                       int s, Control* ctl, u64 nonce, bool many, bool others_ok, u64 sum_n, u32* lds,
+                                       bool ix, bool average = false, u64 first_value = 0, u64 count = ~u64(0)) {
+  const DecompressArgs a{in, out_values, out_cap_elems, index, ctl, first_value, count, nonce};
 
   // Everything that can be asked for before the header is known goes out at once: the control
   // block, the header, the segment's position and the width bytes.  The loads are fenced in
@@ -179,7 +183,9 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
   const u32 wblock0 = seg * kWaveBlocks;
   const u32 b = wblock0 + u32(lane);                   // a stream has at most 2^26 blocks
   const u32 zero = opaque_zero();
-  const uint2 gate = load_gate(a.ctl, zero);
+  const bool first_group = blockIdx.x == 0 && blockIdx.y == 0;
+  uint4 gate_raw = make_uint4(0, 0, 0, 0);
+  if (!ix) gate_raw = load_gate(a.ctl, zero);
   const HeaderWords hw = load_header_words(a.in.base, zero);
   SegmentOffsetParts seg_parts{0, 0, 0};
   u32 seg_end = 0, w = 0;
@@ -194,22 +200,41 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
   }
 
   const ParsedHeader h = parse_header(hw, a.in.bytes, ix);
-  if (gate_failed(gate) || !h.ok) return;
+  u64 tag;
+  if (ix) {
+    tag = call_tag(a.ctl, launch_tag(a.nonce, a.ctl), false);
+    if (!h.ok || !others_ok) {
+      if (first_group && threadIdx.x == 0) {
+        a.ctl->result = 0;
+        raise_status(a.ctl, tag, status_bit(ZC_ERR_FORMAT));
+      }
+      return;
+    }
+    // a stream without blocks: nobody looks at its index, which is one closing entry of 0
+    if (h.nb == 0 && blockIdx.x == 0 && threadIdx.x == 0 &&
+        (h.total != tables_end(0, true) || *reinterpret_cast<const u32*>(a.in.base + kHeaderBytes) != 0))
+      raise_status(a.ctl, tag, status_bit(ZC_ERR_FORMAT));
+  } else {
+    const Gate gate = parse_gate(gate_raw);
+    tag = gate.tag;
+    if (gate_failed(gate) || !h.ok) return;
+  }
   if (first_value > h.n) {                            // the part lies beyond the stream
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_ARG));
+    if (blockIdx.x == 0 && threadIdx.x == 0) raise_status(a.ctl, tag, status_bit(ZC_ERR_ARG));
     return;
   }
   const u64 end_value = count < h.n - first_value ? first_value + count : h.n;     // one past the last value wanted
   const u64 wanted = end_value - first_value;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
-    if (counted) atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->result), static_cast<unsigned long long>(wanted));
-    else a.ctl->result = wanted;
+    if (!many) a.ctl->result = wanted;
+    else if (ix) { if (blockIdx.y == 0) a.ctl->result = sum_n; }
+    else atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->result), static_cast<unsigned long long>(wanted));
   }
   if (wanted > a.out_cap_elems) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
+    if (blockIdx.x == 0 && threadIdx.x == 0) raise_status(a.ctl, tag, status_bit(ZC_ERR_CAPACITY));
     return;
   }
-  if (u64(seg) >= 4 * a.index.tiles_cap) return;
+  if (!ix && u64(seg) >= 4 * a.index.tiles_cap) return;
 
   u32* const wl = lds + wave * kWaveStage;
   if (seg >= num_segments(h.nb) || u64(seg) * kWaveBlocks * kBlockValues >= end_value) return;   // no barrier below: waves are independent
@@ -229,7 +254,8 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
     u32 err = 0;
     const u32 wmax = wave_block_words(payload, payload_words, w, seg_off, wl, lane, lo, hi, ix,
                                       uniform(seg_end) - u32(seg_off), h.wide, err);
-    if (err && lane == 0) atomicOr(&a.ctl->status, err);
+    if (ix && !index_ends_ok(h, seg, u32(seg_off), uniform(seg_end))) err |= status_bit(ZC_ERR_FORMAT);
+    if (err && lane == 0) raise_status(a.ctl, tag, err);
     deltas_from_block_words(wmax, lo, hi, d);
   }
 
@@ -277,14 +303,15 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
 template <bool IX, bool AVERAGE>
 __global__ __launch_bounds__(kTileThreads, 5) void decompress_kernel(DecompressArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
-  decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, false, lds, IX, AVERAGE);
+  decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, a.nonce, false, true, 0, lds, IX, AVERAGE);
 }
 
 // A part of a stream (see decompress_tile).
 template <bool IX>
 __global__ __launch_bounds__(kTileThreads, 5) void decompress_range_kernel(DecompressArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
-  decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, false, lds, IX, false, a.first_value, a.count);
+  decompress_tile(a.in, a.out, a.out_cap_elems, a.index, 0, a.ctl, a.nonce, false, true, 0, lds, IX, false, a.first_value,
+                  a.count);
 }
 
 // k streams in one launch (the tail of the compressed Allgather, Section 3.5.1: every rank
@@ -293,15 +320,24 @@ struct DecompressManyArgs {
   StreamRef in[ZC_MAX_K];
   float* out[ZC_MAX_K];
   u64 out_cap_elems[ZC_MAX_K];
+  int k;
   StreamIndex index;
   Control* ctl;
+  u64 nonce;
 };
 
 template <bool IX>
 __global__ __launch_bounds__(kTileThreads, 5) void decompress_many_kernel(DecompressManyArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
   const int s = blockIdx.y;
-  decompress_tile(a.in[s], a.out[s], a.out_cap_elems[s], a.index, s, a.ctl, true, lds, IX);
+  bool all_ok = true;
+  u64 sum_n = 0;
+  if (IX) {                      // any malformed header stops the whole call
+    const StreamsVerdict v = judge_indexed_streams(a.in, a.k, false);
+    all_ok = v.err == 0;
+    sum_n = v.sum_n;
+  }
+  decompress_tile(a.in[s], a.out[s], a.out_cap_elems[s], a.index, s, a.ctl, a.nonce, true, all_ok, sum_n, lds, IX);
 }
 
 }  // namespace zc

@@ -20,6 +20,7 @@ struct PayloadSink {
   u64* desc;        // look-back descriptors
   bool ix;          // the stream carries a segment index (see index_bytes)
   u32 part_end;     // a stream produced in parts (zc_compress_part): one past the last tile of this part; else 0
+  u64 tag;          // the call's tag (see launch_tag): descriptors and status bits carry it
 };
 
 // Per-wave view of where its payload goes.
@@ -115,8 +116,8 @@ __device__ inline void stage_and_copy_half(WordFn word, u32 w, bool in_half, u32
 // Publishes the tile's payload size; called by one thread as soon as the size is known,
 // because the tiles after this one wait for it.
 __device__ inline void publish_tile_size(const PayloadSink& s, u32 tile, u32 tile_total, bool tile_wide) {
-  desc_store(s.desc + desc_slot(tile),
-             (tile == 0 ? kDescPrefix : kDescAggregate) | (tile_wide ? kDescWide : 0) | u64(tile_total));
+  desc_store(s.desc, tile,
+             (tile == 0 ? kDescPrefix : kDescAggregate) | (tile_wide ? kDescWide : 0) | u64(tile_total), s.tag);
 }
 
 // Base offset of the tile, in payload words: wave 0 looks back, everyone meets at one barrier.
@@ -127,13 +128,13 @@ template <typename MeanwhileFn>
 __device__ inline TileBase resolve_tile_base(const PayloadSink& s, const Placement& pl, u32 tile, u64* sh_base, int wave,
                                              int lane, MeanwhileFn meanwhile) {
   u64 first = 0;
-  if (wave == 0 && tile) first = lookback_poll(s.desc, i64(tile) - 1);
+  if (wave == 0 && tile) first = lookback_poll(s.desc, i64(tile) - 1, s.tag);
   meanwhile();
   if (wave == 0) {
     // words of the tiles before this one, and kDescWide if one of them, or this one, is wide
-    const u64 before = (tile ? lookback_exclusive(s.desc, tile, &s.ctl->status, first) : 0) | (pl.tile_wide ? kDescWide : 0);
+    const u64 before = (tile ? lookback_exclusive(s.desc, tile, s.ctl, s.tag, first) : 0) | (pl.tile_wide ? kDescWide : 0);
     if (lane == 0) {
-      if (tile) desc_store(s.desc + desc_slot(tile), kDescPrefix | (before + pl.tile_total));
+      if (tile) desc_store(s.desc, tile, kDescPrefix | (before + pl.tile_total), s.tag);
       *sh_base = before;
     }
   }
@@ -161,7 +162,7 @@ __device__ inline void finish_stream(const PayloadSink& s, const Placement& pl, 
     const u64 words = tb.words + pl.tile_total;
     const u64 total = tables_end(s.nb, s.ix) + 4 * words;
     s.ctl->result = total;
-    if (total > s.out_cap) atomicOr(&s.ctl->status, status_bit(ZC_ERR_CAPACITY));
+    if (total > s.out_cap) raise_status(s.ctl, s.tag, status_bit(ZC_ERR_CAPACITY));
     if (s.out_cap >= kHeaderBytes) reinterpret_cast<u64*>(s.out)[3] = total;
     if (s.ix && s.out_cap >= tables_end(s.nb, true)) {
       u32* hw = reinterpret_cast<u32*>(s.out);

@@ -17,9 +17,10 @@
 // 16-byte loads, and the loads of the next operand fly while the current one is added; the
 // summed planes go to LDS in one pass and leave as coalesced stores.  Operand payloads are
 // read, and the output stream is written, with the non-temporal hint (see load_once).
-// reduce_wide_kernel takes any widths with per-lane loads.  The control block says whether
-// any operand has a wider block (from the stream index of plain streams, from the version
-// word of indexed ones); each kernel returns at once when the streams are not its.
+// The other path of the same kernel (reduce_wide_tile) takes any widths with per-lane loads,
+// a few planes at a time so that it needs no more registers than the common path.  Whether any
+// operand has a wider block is known when a workgroup starts (from the stream index of plain
+// streams, from the version words of indexed ones), so the whole call takes one path.
 // IX = the streams are indexed (see index_bytes): operands bring the positions of their
 // segments along, which every wave checks against the widths it reads, and the output gets
 // its own index as it is placed.
@@ -40,15 +41,24 @@ struct ReduceArgs {
   Control* ctl;
   u64* desc;
   u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
+  u64 nonce;         // drawn by the host per call, goes into the call's tag (see launch_tag)
+};
+
+// What a workgroup knows about the call once the headers are judged.
+struct ReduceCall {
+  ParsedHeader h;    // header of operand 0 (all operands have its n and bound)
+  u64 tag;           // the call's tag
+  u64 ltag;          // this launch's tag (tile tickets)
+  u64 nsum;          // sum of the operands' nsum
 };
 
 // Header fields and table padding of the output stream; one thread.
-__device__ inline void write_reduce_header(const ReduceArgs& a, const ParsedHeader& h, u32 ntiles, bool ix) {
+__device__ inline void write_reduce_header(const ReduceArgs& a, const ReduceCall& c, u32 ntiles, bool ix) {
+  const ParsedHeader& h = c.h;
   const u64 tend = tables_end(h.nb, ix);
-  const u64 nsum = a.ctl->nsum;            // of all operands, summed by the set-up kernel (every operand is valid here)
-  if (nsum > 0xffffffffull) atomicOr(&a.ctl->status, status_bit(ZC_ERR_RANGE));
-  if (a.out_cap >= tend) write_stream_header(a.out, h.n, h.nb, h.eb_bits, u32(nsum), ix, ntiles == 0);
-  else atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
+  if (c.nsum > 0xffffffffull) raise_status(a.ctl, c.tag, status_bit(ZC_ERR_RANGE));
+  if (a.out_cap >= tend) write_stream_header(a.out, h.n, h.nb, h.eb_bits, u32(c.nsum), ix, ntiles == 0);
+  else raise_status(a.ctl, c.tag, status_bit(ZC_ERR_CAPACITY));
   if (ntiles == 0) a.ctl->result = tend;
 }
 
@@ -72,9 +82,10 @@ __device__ inline bool block_out_of_range(const u32 (&mag)[NP], u32 sign, i64 ou
 // back half.  mag[0..NP) = magnitude planes, sign = sign word, w = highest non-zero plane + 1;
 // `word(i)` hands out the sign word (i = 0) and plane i - 1, for at most NW words.
 template <int NW, int NP, typename WordFn>
-__device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, const u32 (&mag)[NP], u32 sign, u32 w,
-                                 i64 outlier, bool active, u64 b, u32 tile, u32 ntiles, WordFn word, u32* wl,
+__device__ inline void place_sum(const ReduceArgs& a, const ReduceCall& c, const u32 (&mag)[NP], u32 sign, u32 w,
+                                 i64 outlier, bool active, u32 b, u32 tile, u32 ntiles, WordFn word, u32* wl,
                                  u32* sh_wave_total, u64* sh_base, int wave, int lane, bool ix) {
+  const ParsedHeader& h = c.h;
   const u64 tend = tables_end(h.nb, ix);
   if (!active) w = 0;
   u32 err = 0;
@@ -103,9 +114,9 @@ __device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, con
   }
   lds_barrier();                // the wave totals; the stores above stay in flight
   sum_wave_totals(sh_wave_total, wave, ix, pl);
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix};
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix, 0u, c.tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
-  if (err) atomicOr(&a.ctl->status, err);
+  if (err) raise_status(a.ctl, c.tag, err);
   finish_tile<NW>(sink, word, pl, tile, ntiles, wl, sh_base, wave, lane);
 }
 
@@ -116,10 +127,11 @@ __device__ inline void place_sum(const ReduceArgs& a, const ParsedHeader& h, con
 constexpr int kWholeStage = 64 * 24;
 
 template <int NW, int NP, typename WordFn>
-__device__ inline void place_sum_staged(const ReduceArgs& a, const ParsedHeader& h, const u32 (&mag)[NP], u32 sign, u32 w,
-                                        i64 outlier, bool active, u64 b, u32 tile, u32 ntiles, WordFn word, u32* wl,
+__device__ inline void place_sum_staged(const ReduceArgs& a, const ReduceCall& c, const u32 (&mag)[NP], u32 sign, u32 w,
+                                        i64 outlier, bool active, u32 b, u32 tile, u32 ntiles, WordFn word, u32* wl,
                                         u32* sh_wave_total, u64* sh_base, int wave, int lane, bool ix) {
   static_assert(64 * NW <= kWholeStage, "a wave of widest blocks must fit the staging area");
+  const ParsedHeader& h = c.h;
   const u64 tend = tables_end(h.nb, ix);
   if (!active) w = 0;
   u32 err = 0;
@@ -155,9 +167,9 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ParsedHeader&
   }
   lds_barrier();                // the wave totals (and the words above); the stores stay in flight
   sum_wave_totals(sh_wave_total, wave, ix, pl);
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix};
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix, 0u, c.tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
-  if (err) atomicOr(&a.ctl->status, err);
+  if (err) raise_status(a.ctl, c.tag, err);
   const TileBase tb = resolve_tile_base(sink, pl, tile, sh_base, wave, lane);
   const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
   const u64 d0 = tb.words + pl.wave_off;
@@ -424,44 +436,14 @@ __device__ inline int fresh_lane() {
   return lane;
 }
 
+// One tile of a call whose operands have no block wider than 15 bits.  `meta`: the tables of
+// operand 0 if the workgroup asked for them early (`early`).
 template <bool IX>
-__global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
-  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWholeStage];   // also holds an operand's payload
-  __shared__ u32 sh_tile;
-  __shared__ u32 sh_wave_total[kTileWaves];
-  __shared__ u64 sh_base;
-
+__device__ inline void reduce_narrow_tile(const ReduceArgs& a, const ReduceCall& c, u32 tile, u32 ntiles, OperandMeta meta,
+                                          bool early, u32* lds, u32* sh_wave_total, u64* sh_base) {
+  const ParsedHeader& h = c.h;
   const int wave = wave_id();
-
-  // A workgroup that takes the tile of its own number asks for the first operand's tables
-  // together with the control block and the header, before it knows the header: one memory
-  // round trip instead of two.  The loads are fenced in by sizes the host passed.  (Not for
-  // indexed streams: where their width bytes are is only known with the header.)
-  const bool early = !IX && !a.ticketed;
-  const u32 zero = opaque_zero();
-  OperandMeta meta;
-  if (early) {
-    const u32 seg = blockIdx.x * kTileWaves + u32(wave);     // < 2^22: the host launches at most 2^18 tiles
-    const u32 b = seg * kWaveBlocks + u32(fresh_lane());
-    meta = load_operand_tables(a, 0, seg, b, u64(kHeaderBytes) + b < a.in[0].bytes, seg < 4 * a.index.tiles_cap, zero);
-  }
-  const uint2 gate = load_gate(a.ctl, zero);
-  const HeaderWords hw = load_header_words(a.in[0].base, zero);
-  const ParsedHeader h = parse_header(hw, a.in[0].bytes, IX);
-  if (gate_failed(gate) || gate_wide(gate) || !h.ok) return;
   const u64 tend = tables_end(h.nb, IX);
-  const u32 ntiles = u32(num_tiles(h.nb));
-  if (blockIdx.x == 0 && threadIdx.x == 0) write_reduce_header(a, h, ntiles, IX);
-  if (ntiles == 0) return;
-
-  u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
-  if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
-    if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
-    __syncthreads();
-    tile = uniform(sh_tile);
-  }
-  if (tile >= ntiles) return;
-
   u32* const wl = lds + wave * kWholeStage;
   const u32 seg = tile * kTileWaves + u32(wave);
   const bool seg_live = seg < num_segments(h.nb);
@@ -485,6 +467,8 @@ __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
     stage = load_operand_payload(reinterpret_cast<const u32*>(a.in[0].base + tend), next, lane);
     outlier_next = load_operand_outlier(a, 0, h, b, active, IX);
   }
+  // the ends of every operand's index, by the waves that hold them
+  if (IX && seg_live && !index_ends_consistent(a.in, a.k, h, seg)) err |= status_bit(ZC_ERR_FORMAT);
 
   // ---- add the k operands' blocks in plane form; loads run ahead of the adds ----
   u32 acc[kSumPlanes];
@@ -533,42 +517,46 @@ __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
   };
   const int lane = fresh_lane();
   const u32 b = seg * kWaveBlocks + u32(lane);
-  if (IX && err && lane == 0) atomicOr(&a.ctl->status, err);
-  place_sum_staged<kSumPlanes>(a, h, acc, sgn, w, outlier, b < h.nb, b, tile, ntiles, word, wl, sh_wave_total, &sh_base,
+  if (IX && err && lane == 0) raise_status(a.ctl, c.tag, err);
+  place_sum_staged<kSumPlanes>(a, c, acc, sgn, w, outlier, b < h.nb, b, tile, ntiles, word, wl, sh_wave_total, sh_base,
                                wave, lane, IX);
 }
 
 // ---------------------------------------------------------------------------------------
 // Any widths.
 // ---------------------------------------------------------------------------------------
-constexpr int kAccPlanes = 39;   // |sum of 64 deltas| < 2^37: 38 magnitude bits + sign
+constexpr int kAccPlanes = 38;   // |sum of 64 deltas| < 2^37: 37 magnitude bits + sign
+constexpr int kWideChunk = 2;    // operand planes fetched at a time
 
-// acc (two's complement, `top` planes valid, `ext` = its sign plane) += operand given as
-// sign word s and magnitude planes a[0..31) (zero above the operand's width).
-// Planes [0, new_top) are valid afterwards.  top and new_top are wave-uniform.
-template <int P>
-__device__ inline void ripple_add(u32 (&acc)[kAccPlanes], const u32 (&a)[31], u32 s, u32 carry,
-                                  u32 ext, u32 top, u32 new_top, u32& ext_out) {
-  if constexpr (P < kAccPlanes) {
-    if (u32(P) >= new_top) return;
-    const u32 cur = u32(P) < top ? acc[P] : ext;
-    u32 x = s;                                  // two's complement of the operand: (mag ^ s) + s
-    if constexpr (P < 31) x ^= a[P];
-    const u32 t = cur ^ x;
-    const u32 sum = t ^ carry;
-    const u32 cout = (t & carry) | (~t & cur);  // majority(cur, x, carry)
-    acc[P] = sum;
-    ext_out = sum;
-    ripple_add<P + 1>(acc, a, s, cout, ext, top, new_top, ext_out);
-  }
-}
-
-template <int P, typename Ptr>
-__device__ inline void load_operand_planes(u32 (&a)[31], u32 w, u32 wmax, Ptr src) {
-  if constexpr (P < 31) {
-    if (u32(P) >= wmax) return;
-    a[P] = u32(P) < w ? src[1 + P] : 0u;
-    load_operand_planes<P + 1>(a, w, wmax, src);
+// acc (two's complement, `top` planes valid, `ext` = its sign plane) += operand given as sign
+// word s and the magnitude planes at src[1 ...] (w of them; zero above), kWideChunk planes at
+// a time: their loads are in flight together, then they are added.  Planes [0, new_top) are
+// valid afterwards.  top and new_top are wave-uniform.
+template <int P0>
+__device__ inline void ripple_add(u32 (&acc)[kAccPlanes], const u32* src, u32 w, u32 s, u32 carry, u32 ext, u32 top,
+                                  u32 new_top, u32& ext_out) {
+  if constexpr (P0 < kAccPlanes) {
+    if (u32(P0) >= new_top) return;             // uniform
+    u32 x[kWideChunk];
+#pragma unroll
+    for (int i = 0; i < kWideChunk; ++i) {
+      const int P = P0 + i;
+      x[i] = (P < 31 && u32(P) < w) ? src[1 + P] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < kWideChunk; ++i) {
+      const int P = P0 + i;
+      if (P < kAccPlanes && u32(P) < new_top) {
+        const u32 cur = u32(P) < top ? acc[P] : ext;
+        const u32 xx = s ^ x[i];                // two's complement of the operand: (mag ^ s) + s
+        const u32 t = cur ^ xx;
+        const u32 sum = t ^ carry;
+        carry = (t & carry) | (~t & cur);       // majority(cur, xx, carry)
+        acc[P] = sum;
+        ext_out = sum;
+      }
+    }
+    ripple_add<P0 + kWideChunk>(acc, src, w, s, carry, ext, top, new_top, ext_out);
   }
 }
 
@@ -586,35 +574,19 @@ __device__ inline void magnitude_planes(u32 (&acc)[kAccPlanes], u32 s, u32 carry
 }
 
 template <bool IX>
-__global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a) {
-  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWaveStage];
-  __shared__ u32 sh_tile;
-  __shared__ u32 sh_wave_total[kTileWaves];
-  __shared__ u64 sh_base;
-
-  if (validation_failed(a.ctl) || !streams_are_wide(a.ctl)) return;
-  const ParsedHeader h = parse_header(a.in[0], IX);
-  if (!h.ok) return;
+__device__ inline void reduce_wide_tile(const ReduceArgs& a, const ReduceCall& c, u32 tile, u32 ntiles, u32* lds,
+                                        u32* sh_wave_total, u64* sh_base) {
+  const ParsedHeader& h = c.h;
   const u64 tend = tables_end(h.nb, IX);
-  const u32 ntiles = u32(num_tiles(h.nb));
-  if (blockIdx.x == 0 && threadIdx.x == 0) write_reduce_header(a, h, ntiles, IX);
-  if (ntiles == 0) return;
-
   const int lane = lane_id();
-  const int wave = int(threadIdx.x) >> 6;
-  u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
-  if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
-    if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
-    __syncthreads();
-    tile = uniform(sh_tile);
-  }
-  if (tile >= ntiles) return;
-
-  u32* const wl = lds + wave * kWaveStage;
-  const u64 seg = u64(tile) * kTileWaves + u64(wave);
+  const int wave = wave_id();
+  u32* const wl = lds + wave * kWholeStage;
+  const u32 seg = tile * kTileWaves + u32(wave);           // a stream has at most 2^26 blocks
   const bool seg_live = seg < num_segments(h.nb);
-  const u64 b = seg * kWaveBlocks + u64(lane);
+  const u32 b = seg * kWaveBlocks + u32(lane);
   const bool active = b < h.nb;
+  if (IX && seg_live && !index_ends_consistent(a.in, a.k, h, seg) && lane == 0)
+    raise_status(a.ctl, c.tag, status_bit(ZC_ERR_FORMAT));
 
   u32 acc[kAccPlanes];
 #pragma unroll
@@ -622,43 +594,46 @@ __global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a)
   u32 ext = 0, top = 0;
   u64 bound = 0;          // wave-uniform bound on |sum of deltas| so far
   i64 outlier = 0;
+#pragma nounroll
   for (int s = 0; s < a.k; ++s) {
     const u8* base = a.in[s].base;
     const u64 total_s = reinterpret_cast<const u64*>(base)[3];
-    const u64 pw = (total_s - tend) / 4;
-    u32 w = active ? u32(base[widths_begin(h.nb, IX) + b]) : 0u;
+    const u64 pw64 = total_s >= tend ? (total_s - tend) / 4 : 0;
+    const u32 pw = pw64 > 0xffffffffull ? 0xffffffffu : u32(pw64);   // payload words (a stream has at most 2^31)
+    u32 w = active ? u32(*at_bytes(base, u32(widths_begin(h.nb, IX)) + b)) : 0u;
     const bool bad_w = w > 31;                    // plain streams: cannot happen on a validated stream
     if (bad_w) w = 0;
     const u32 words = psize_words(w);
     const u32 incl = wave_inclusive_sum(words);
-    u64 off = 0;
+    u32 seg_off = 0;
+    bool fits = seg_live;
     if (IX) {
       // the segment's place by the stream's own index, which must agree with the widths
       const u32* index = reinterpret_cast<const u32*>(base + kHeaderBytes);
-      const u32 seg_off = seg_live ? index[seg] : 0u, seg_end = seg_live ? index[seg + 1] : 0u;
-      if (seg_end - seg_off != lane_value(incl, 63) || __any(bad_w) || (!parse_header(a.in[s], true).wide && __any(w > 15))) {
-        if (lane == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_FORMAT));
-        w = 0;
+      const u32 seg_end = seg_live ? index[seg + 1] : 0u;
+      seg_off = seg_live ? index[seg] : 0u;
+      const bool narrow_promised = (reinterpret_cast<const u32*>(base)[1] & 1u) == 0;
+      if (seg_end - seg_off != lane_value(incl, 63) || __any(bad_w) || (narrow_promised && __any(w > 15))) {
+        if (lane == 0) raise_status(a.ctl, c.tag, status_bit(ZC_ERR_FORMAT));
+        fits = false;
       }
-      off = u64(seg_off) + (incl - words);
     } else if (seg_live) {
-      off = segment_offset(a.index, s, seg) + (incl - words);
+      const u64 so = segment_offset(a.index, s, seg);
+      fits = so <= pw;
+      seg_off = u32(so);
     }
-    if (off + words > pw) w = 0;                  // cannot happen on a validated stream
+    // (cannot fail on a validated stream) the segment lies inside the payload
+    if (!fits || seg_off > pw || lane_value(incl, 63) > pw - seg_off) w = 0;
     const u32 wmax = wave_max_u32(w);
-    if (active) outlier += i64(reinterpret_cast<const i32*>(base + outliers_begin(h.nb, IX))[b]);
+    if (active) outlier += i64(*reinterpret_cast<const i32*>(at_bytes(base, u32(outliers_begin(h.nb, IX)) + 4u * b)));
     if (wmax == 0) continue;
-    const u32* src = reinterpret_cast<const u32*>(base + tend) + off;
-    u32 pl[31];
-#pragma unroll
-    for (int p = 0; p < 31; ++p) pl[p] = 0;
+    const u32* src = reinterpret_cast<const u32*>(base + tend) + seg_off + (incl - words);
     const u32 sgn = w ? src[0] : 0u;
-    load_operand_planes<0>(pl, w, wmax, src);
     bound += (u64(1) << wmax) - 1;
     u32 new_top = 64u - u32(__builtin_clzll(bound)) + 1u;
     if (new_top > u32(kAccPlanes)) new_top = kAccPlanes;
     u32 ext_out = ext;
-    ripple_add<0>(acc, pl, sgn, sgn, ext, top, new_top, ext_out);
+    ripple_add<0>(acc, src, w, sgn, sgn, ext, top, new_top, ext_out);
     ext = ext_out;
     top = new_top;
   }
@@ -670,7 +645,105 @@ __global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a)
     if constexpr (I == 0) return ext;
     else return acc[I - 1];
   };
-  place_sum<32>(a, h, acc, ext, w, outlier, active, b, tile, ntiles, word, wl, sh_wave_total, &sh_base, wave, lane, IX);
+  place_sum<32>(a, c, acc, ext, w, outlier, active, b, tile, ntiles, word, wl, sh_wave_total, sh_base, wave, lane, IX);
+}
+
+// What every workgroup of a reduce kernel does first: the call's verdict, tag and header, and its tile.
+// Returns false when the workgroup has nothing (more) to do.  Plain streams (IX false) have
+// been validated and indexed by the kernels of zc_scan.h, whose verdict and tag are in the
+// control block; indexed streams are judged here, by every workgroup alike, from their headers.
+// `meta`, `early`: see reduce_narrow_tile.  `for_wide`: the caller is the kernel that serves
+// plain streams with blocks wider than 15 bits (the narrow one returns at once on those, and
+// the other way round; either writes the header of its own calls).
+template <bool IX>
+__device__ inline bool open_reduce(const ReduceArgs& a, bool for_wide, ReduceCall& c, bool& wide, OperandMeta& meta, bool early,
+                                   u32& tile, u32& ntiles, u32* sh_tile) {
+  c.ltag = launch_tag(a.nonce, a.ctl);
+  if (IX) {
+    const StreamsVerdict v = judge_indexed_streams(a.in, a.k, true);
+    c.tag = call_tag(a.ctl, c.ltag, false);
+    c.h = v.h0;
+    c.nsum = v.nsum;
+    wide = v.wide;
+    if (v.err) {
+      if (blockIdx.x == 0 && threadIdx.x == 0) {
+        a.ctl->result = 0;
+        raise_status(a.ctl, c.tag, v.err);
+      }
+      return false;
+    }
+  } else {
+    const u32 zero = opaque_zero();
+    if (early) {
+      const u32 seg = blockIdx.x * kTileWaves + u32(wave_id());     // < 2^22: the host launches at most 2^18 tiles
+      const u32 b = seg * kWaveBlocks + u32(fresh_lane());
+      meta = load_operand_tables(a, 0, seg, b, u64(kHeaderBytes) + b < a.in[0].bytes, seg < 4 * a.index.tiles_cap, zero);
+    }
+    const uint4 gate_raw = load_gate(a.ctl, zero);
+    const HeaderWords hw = load_header_words(a.in[0].base, zero);
+    c.h = parse_header(hw, a.in[0].bytes, false);
+    const Gate gate = parse_gate(gate_raw);
+    c.tag = gate.tag;
+    if (gate_failed(gate) || !c.h.ok) return false;
+    wide = gate_wide(gate);
+    if (wide != for_wide) return false;
+    c.nsum = 0;
+  }
+  ntiles = u32(num_tiles(c.h.nb));
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (!IX) c.nsum = a.ctl->nsum;           // of all operands, summed by the validation kernel
+    write_reduce_header(a, c, ntiles, IX);
+  }
+  if (ntiles == 0) {                         // streams without blocks: their one index entry must say so
+    if (IX && blockIdx.x == 0 && wave_id() == 0 && !index_ends_consistent(a.in, a.k, c.h, 0) && lane_id() == 0)
+      raise_status(a.ctl, c.tag, status_bit(ZC_ERR_FORMAT));
+    return false;
+  }
+  tile = blockIdx.x;                         // tiles in the order in which workgroups start
+  if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
+    if (threadIdx.x == 0) *sh_tile = take_tile(a.ctl, c.ltag, ntiles, xcc_id());
+    __syncthreads();
+    tile = uniform(*sh_tile);
+  }
+  return tile < ntiles;
+}
+
+// Indexed streams: one launch per call, whatever the widths.  Plain streams: the common case;
+// reduce_wide_kernel, launched behind it, takes the calls with wider blocks.
+template <bool IX>
+__global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWholeStage];   // also holds an operand's payload
+  __shared__ u32 sh_tile;
+  __shared__ u32 sh_wave_total[kTileWaves];
+  __shared__ u64 sh_base;
+
+  ReduceCall c;
+  bool wide = false;
+  OperandMeta meta{};
+  // A workgroup that takes the tile of its own number asks for the first operand's tables
+  // together with the control block and the header, before it knows the header: one memory
+  // round trip instead of two.  The loads are fenced in by sizes the host passed.  (Not for
+  // indexed streams: where their width bytes are is only known with the header.)
+  const bool early = !IX && !a.ticketed;
+  u32 tile = 0, ntiles = 0;
+  if (!open_reduce<IX>(a, false, c, wide, meta, early, tile, ntiles, &sh_tile)) return;
+  if (IX && wide) reduce_wide_tile<true>(a, c, tile, ntiles, lds, sh_wave_total, &sh_base);
+  else reduce_narrow_tile<IX>(a, c, tile, ntiles, meta, early, lds, sh_wave_total, &sh_base);
+}
+
+// Plain streams with blocks wider than 15 bits.
+__global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a) {
+  __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWholeStage];
+  __shared__ u32 sh_tile;
+  __shared__ u32 sh_wave_total[kTileWaves];
+  __shared__ u64 sh_base;
+
+  ReduceCall c;
+  bool wide = false;
+  OperandMeta meta{};
+  u32 tile = 0, ntiles = 0;
+  if (!open_reduce<false>(a, true, c, wide, meta, false, tile, ntiles, &sh_tile)) return;
+  reduce_wide_tile<false>(a, c, tile, ntiles, lds, sh_wave_total, &sh_base);
 }
 
 }  // namespace zc

@@ -1,10 +1,10 @@
 // Block positions of an existing stream: header validation and the exclusive prefix sum of
 // the block sizes implied by its width table (Section 3.3 stores one code length per block;
 // a block's position is the sum of the sizes before it), kept per segment of 64 blocks, the
-// share of one wave.  An indexed stream (Section 3.5.2) brings these positions along:
-// stream_index_kernel is not run for it, index_prep_kernel checks what can be checked in one
-// place (header, first and closing entry), and every wave of a consumer checks that its own
-// segment's entries agree with its width bytes, which together is the whole index.
+// share of one wave.  An indexed stream (Section 3.5.2) brings these positions along: neither
+// kernel of this file runs for it; the main kernels judge the headers themselves
+// (judge_indexed_streams) and every wave of a consumer checks that its own segment's entries
+// agree with its width bytes and with the ends of the index, which together is the whole index.
 //
 // stream_index_kernel records the offset of every segment inside its scan group, of every
 // group inside its index span and the size of every span, and validates header and width
@@ -84,13 +84,26 @@ __device__ inline ParsedHeader parse_header(const HeaderWords& hw, u64 bytes, bo
   return parse_header_words(w, bytes, ix);
 }
 
-// status and flags of the control block (final before a main kernel starts).
-__device__ inline uint2 load_gate(const Control* ctl, u32 zero) {
-  return *reinterpret_cast<const uint2*>(at_bytes(reinterpret_cast<const u8*>(ctl), zero));
+// What a main kernel that reads plain streams finds in the control block: the call's tag and
+// the verdict of the validation kernel that ran ahead of it (final before the main kernel starts).
+struct Gate {
+  u64 tag;
+  u32 bits;
+};
+
+__device__ inline uint4 load_gate(const Control* ctl, u32 zero) {
+  return *reinterpret_cast<const uint4*>(at_bytes(reinterpret_cast<const u8*>(ctl), zero));
 }
 
-__device__ inline bool gate_failed(uint2 gate) { return (uniform(gate.x) & kGateBits) != 0; }
-__device__ inline bool gate_wide(uint2 gate) { return (uniform(gate.y) & kFlagWide) != 0; }
+__device__ inline Gate parse_gate(uint4 raw) {
+  Gate g;
+  g.tag = u64(uniform(raw.z)) | (u64(uniform(raw.w)) << 32);
+  g.bits = uniform(raw.y) == u32(g.tag >> 32) ? uniform(raw.x) : 0u;
+  return g;
+}
+
+__device__ inline bool gate_failed(const Gate& g) { return (g.bits & kGateBits) != 0; }
+__device__ inline bool gate_wide(const Gate& g) { return (g.bits & kStatusWide) != 0; }
 
 struct ScanArgs {
   StreamRef streams[ZC_MAX_K];
@@ -98,9 +111,7 @@ struct ScanArgs {
   int check_match;   // reduce: every stream must have the n and eb_bits of stream 0
   StreamIndex index;
   Control* ctl;
-  u64* desc;         // look-back descriptors to clear for the kernel that follows (may be null)
-  u32 ndesc;
-  u32 ix;            // the streams are indexed: stream_index_kernel has not run
+  u64 nonce;         // drawn by the host per call, goes into the call's tag (see launch_tag)
 };
 
 constexpr u32 kSpanBadWidth = 1u;   // per-span flags left by stream_index_kernel: a width byte above 31
@@ -237,55 +248,24 @@ __global__ __launch_bounds__(256) void stream_index_kernel(ScanArgs a) {
   }
 }
 
-// Second step of the index, and set-up of the kernel that follows; one launch for all streams.
-// Workgroup 0, plain streams: each wave takes streams (wave, wave + 4, ...): validates the
-// header, turns the span sizes into exclusive offsets in place, collects the spans' flags and
-// checks that the header's total_bytes equals tables + payload; indexed streams: one thread
-// per stream looks at header and index ends.  Thread 0 then writes the control block, so
-// nothing has to clear it beforehand.  All workgroups clear the look-back descriptors and the
-// tile tickets for the kernel that writes a stream (reduce).
+// Second step of the index of plain streams, and the first launch of the call as far as its
+// tag goes; one workgroup for all streams.  Each wave takes streams (wave, wave + 4, ...):
+// validates the header, turns the span sizes into exclusive offsets in place, collects the
+// spans' flags and checks that the header's total_bytes equals tables + payload.  Thread 0 then
+// writes the control block: the call's tag, the verdict under that tag, the operands' nsum.
 __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
   __shared__ u32 sh_status[4], sh_wide[4];
   __shared__ unsigned long long sh_nsum;        // sum of the valid streams' nsum, for the kernel that writes a stream
   if (threadIdx.x == 0) sh_nsum = 0;
   __syncthreads();
-  for (u64 i = u64(blockIdx.x) * blockDim.x + threadIdx.x; i < a.ndesc; i += u64(gridDim.x) * blockDim.x)
-    a.desc[desc_slot(i)] = 0;
-  if (blockIdx.x != 0) return;
+  const u64 tag = launch_tag(a.nonce, a.ctl);
   const int lane = lane_id();
   const int wave = int(threadIdx.x) >> 6;
   u32 status = 0, wide = 0;
   ParsedHeader h0;
   h0.ok = false;
-  if (a.check_match) h0 = parse_header(a.streams[0], a.ix);
-  if (a.ix) {
-    // Indexed streams need no sums here, only a look at each header and at the two ends of each
-    // index (the waves that use a segment check the rest): one thread per stream, so that the
-    // dependent loads of all streams are in flight together, then the findings are folded.
-    for (int s = int(threadIdx.x); s < a.k; s += int(blockDim.x)) {
-      const ParsedHeader h = parse_header(a.streams[s], true);
-      if (!h.ok) {
-        status |= status_bit(ZC_ERR_FORMAT);
-        continue;
-      }
-      if (!stream_fits(h, a.index)) {
-        status |= status_bit(ZC_ERR_ARG);
-        continue;
-      }
-      if (a.check_match && h0.ok && (h0.n != h.n || h0.eb_bits != h.eb_bits)) status |= status_bit(ZC_ERR_MISMATCH);
-      const u32* index = reinterpret_cast<const u32*>(a.streams[s].base + kHeaderBytes);
-      const u64 nseg = num_segments(h.nb);
-      if (index[0] != 0 || tables_end(h.nb, true) + 4 * u64(index[nseg]) != h.total) status |= status_bit(ZC_ERR_FORMAT);
-      if (h.wide) wide = kFlagWide;
-      atomicAdd(&sh_nsum, static_cast<unsigned long long>(h.nsum));
-    }
-    u32 folded = 0;
-    for (int code : {ZC_ERR_ARG, ZC_ERR_FORMAT, ZC_ERR_MISMATCH})
-      if (__any((status & status_bit(code)) != 0)) folded |= status_bit(code);
-    status = folded;
-    wide = __any(wide != 0) ? kFlagWide : 0u;
-  }
-  for (int s = wave; !a.ix && s < a.k; s += 4) {
+  if (a.check_match) h0 = parse_header(a.streams[0], false);
+  for (int s = wave; s < a.k; s += 4) {
     const ParsedHeader h = parse_header(a.streams[s], false);
     if (!h.ok) {
       status |= status_bit(ZC_ERR_FORMAT);
@@ -311,7 +291,7 @@ __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
       carry += lane_value(inc, 63);
     }
     if (__any((seen & kSpanBadWidth) != 0)) status |= status_bit(ZC_ERR_FORMAT);
-    if (__any((seen & kSpanWide) != 0)) wide = kFlagWide;
+    if (__any((seen & kSpanWide) != 0)) wide = kStatusWide;
     if (tables_end(h.nb, false) + 4 * carry != h.total) status |= status_bit(ZC_ERR_FORMAT);
   }
   if (lane == 0) {
@@ -320,12 +300,98 @@ __global__ __launch_bounds__(256) void index_prep_kernel(ScanArgs a) {
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    a.ctl->status = sh_status[0] | sh_status[1] | sh_status[2] | sh_status[3];
-    a.ctl->flags = sh_wide[0] | sh_wide[1] | sh_wide[2] | sh_wide[3];
+    const u32 bits = sh_status[0] | sh_status[1] | sh_status[2] | sh_status[3] | sh_wide[0] | sh_wide[1] | sh_wide[2] | sh_wide[3];
+    a.ctl->status = (tag & 0xffffffff00000000ull) | bits;
+    a.ctl->call_tag = tag;
     a.ctl->result = 0;
     a.ctl->nsum = sh_nsum;
-    for (int i = 0; i < kTicketShards; ++i) *ticket_counter(a.ctl, u32(i)) = 0;
   }
+}
+
+// ---------------------------------------------------------------------------------------
+// Indexed streams need no launch ahead of the main kernel: every workgroup reads the headers
+// of all input streams itself and comes to the same verdict, and every wave checks the part
+// of the index it uses (the entries of its segment against its width bytes; the wave of the
+// first segment that entry 0 is 0, the wave of the last that the closing entry accounts for
+// total_bytes), which together is the whole index.
+// ---------------------------------------------------------------------------------------
+
+// Verdict on the k <= 64 input streams of a call, from their headers alone.  Lane s of the
+// calling wave reads and judges the header of stream s, so that all headers are in flight at
+// once; every wave of every workgroup comes to the same verdict.
+struct StreamsVerdict {
+  ParsedHeader h0;      // header of stream 0 (uniform)
+  u32 err;              // status bits: FORMAT, MISMATCH (uniform)
+  u64 nsum;             // sum of the nsum fields of the valid streams
+  u64 sum_n;            // sum of their n fields
+  bool wide;            // some stream may hold blocks wider than 15 bits
+};
+
+__device__ inline StreamsVerdict judge_indexed_streams(const StreamRef* streams, int k, bool check_match) {
+  const int lane = lane_id();
+  const bool mine = lane < k;
+  u32 w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  u64 bytes = 0;
+  if (mine) {
+    bytes = streams[lane].bytes;                       // >= kHeaderBytes: the host has checked
+    const uint4* src = reinterpret_cast<const uint4*>(streams[lane].base);
+    const uint4 lo = src[0], hi = src[1];
+    w[0] = lo.x; w[1] = lo.y; w[2] = lo.z; w[3] = lo.w;
+    w[4] = hi.x; w[5] = hi.y; w[6] = hi.z; w[7] = hi.w;
+  }
+  const ParsedHeader h = parse_header_words(w, bytes, true);
+  StreamsVerdict v;
+  v.h0.n = u64(lane_value(u32(h.n), 0)) | (u64(lane_value(u32(h.n >> 32), 0)) << 32);
+  v.h0.nb = num_blocks(v.h0.n);
+  v.h0.total = u64(lane_value(u32(h.total), 0)) | (u64(lane_value(u32(h.total >> 32), 0)) << 32);
+  v.h0.eb_bits = lane_value(h.eb_bits, 0);
+  v.h0.nsum = lane_value(h.nsum, 0);
+  v.h0.ok = lane_value(u32(h.ok), 0) != 0;
+  v.h0.wide = lane_value(u32(h.wide), 0) != 0;
+  if (!v.h0.ok) v.h0.nb = 0;
+  v.err = 0;
+  if (__any(mine && !h.ok)) v.err |= status_bit(ZC_ERR_FORMAT);
+  if (check_match && v.h0.ok && __any(mine && h.ok && (h.n != v.h0.n || h.eb_bits != v.h0.eb_bits)))
+    v.err |= status_bit(ZC_ERR_MISMATCH);
+  v.wide = __any(mine && h.ok && h.wide);
+  const u32 ns = mine && h.ok ? h.nsum : 0u;
+  v.nsum = u64(wave_sum_u32(ns & 0xffffu)) + (u64(wave_sum_u32(ns >> 16)) << 16);
+  const u64 nn = mine && h.ok ? h.n : 0;              // <= 2^31
+  v.sum_n = u64(wave_sum_u32(u32(nn) & 0xffffu)) + (u64(wave_sum_u32(u32(nn >> 16))) << 16);
+  return v;
+}
+
+// The checks on the two ends of the index that fall to the wave that holds segment `seg`:
+// seg_off and seg_end are its two entries.  (A stream without blocks has a single entry, which
+// nobody uses: see index_ends_consistent.)
+__device__ inline bool index_ends_ok(const ParsedHeader& h, u32 seg, u32 seg_off, u32 seg_end) {
+  const u64 nseg = num_segments(h.nb);
+  if (seg == 0 && seg_off != 0) return false;
+  if (u64(seg) + 1 == nseg && tables_end(h.nb, true) + 4 * u64(seg_end) != h.total) return false;
+  return true;
+}
+
+// The same for a kernel with k <= 64 input streams of the same n (headers judged already):
+// called by the wave that holds segment `seg`, it does something only for the first and the
+// last segment (and for a stream without blocks, whose one entry must be 0): lane s looks at
+// stream s.  Uniform result.
+__device__ inline bool index_ends_consistent(const StreamRef* streams, int k, const ParsedHeader& h, u32 seg) {
+  const u64 nseg = num_segments(h.nb);
+  const bool first = seg == 0;
+  const bool last = nseg == 0 || u64(seg) + 1 == nseg;
+  if (!first && !last) return true;                    // uniform
+  const int lane = lane_id();
+  bool bad = false;
+  if (lane < k) {
+    const u8* base = streams[lane].base;
+    const u32* index = reinterpret_cast<const u32*>(base + kHeaderBytes);
+    if (first && index[0] != 0) bad = true;
+    if (last) {
+      const u64 total = reinterpret_cast<const u64*>(base)[3];
+      if (tables_end(h.nb, true) + 4 * u64(index[nseg]) != total) bad = true;
+    }
+  }
+  return !__any(bad);
 }
 
 }  // namespace zc

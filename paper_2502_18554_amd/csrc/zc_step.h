@@ -37,18 +37,19 @@ struct StepArgs {
   Control* ctl;
   u64* desc;
   u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
+  u64 nonce;         // drawn by the host per call, goes into the call's tag (see launch_tag)
 };
 
 constexpr int kStepStage = kWaveBlocks * kStageRow;     // 64 rows of 36 words = 9 KiB per wave
 static_assert(kStepStage >= kWaveStage, "the payload staging of the decoder must fit too");
 
 // Header fields and table padding of the output stream; one thread.
-__device__ inline void write_step_header(const StepArgs& a, const ParsedHeader& h, u32 ntiles, bool ix) {
+__device__ inline void write_step_header(const StepArgs& a, const ParsedHeader& h, u64 tag, u32 ntiles, bool ix) {
   const u64 tend = tables_end(h.nb, ix);
   const u64 nsum = u64(h.nsum) + 1;
-  if (nsum > 0xffffffffull) atomicOr(&a.ctl->status, status_bit(ZC_ERR_RANGE));
+  if (nsum > 0xffffffffull) raise_status(a.ctl, tag, status_bit(ZC_ERR_RANGE));
   if (a.out_cap >= tend) write_stream_header(a.out, h.n, h.nb, h.eb_bits, u32(nsum), ix, ntiles == 0);
-  else atomicOr(&a.ctl->status, status_bit(ZC_ERR_CAPACITY));
+  else raise_status(a.ctl, tag, status_bit(ZC_ERR_CAPACITY));
   if (ntiles == 0) a.ctl->result = tend;
 }
 
@@ -81,7 +82,8 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
   // position and its width bytes (fenced in by sizes the host passed).
   const bool early = !a.ticketed;
   const u32 zero = opaque_zero();
-  const uint2 gate = load_gate(a.ctl, zero);
+  uint4 gate_raw = make_uint4(0, 0, 0, 0);
+  if (!IX) gate_raw = load_gate(a.ctl, zero);
   const HeaderWords hw = load_header_words(a.in.base, zero);
   float4 x[8];
   SegmentOffsetParts seg_parts{0, 0, 0};
@@ -116,20 +118,41 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
     }
   }
 
+  // Plain streams: validated and indexed by the kernels of zc_scan.h, whose verdict and tag are in
+  // the control block.  Indexed streams: judged here, by every workgroup alike.
   const ParsedHeader h = parse_header(hw, a.in.bytes, IX);
-  if (gate_failed(gate) || !h.ok) return;
+  const u64 ltag = launch_tag(a.nonce, a.ctl);
+  u64 tag;
+  if (IX) {
+    tag = call_tag(a.ctl, ltag, false);
+    if (!h.ok) {
+      if (blockIdx.x == 0 && threadIdx.x == 0) {
+        a.ctl->result = 0;
+        raise_status(a.ctl, tag, status_bit(ZC_ERR_FORMAT));
+      }
+      return;
+    }
+  } else {
+    const Gate gate = parse_gate(gate_raw);
+    tag = gate.tag;
+    if (gate_failed(gate) || !h.ok) return;
+  }
   if (a.n_local != h.n) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&a.ctl->status, status_bit(ZC_ERR_MISMATCH));
+    if (blockIdx.x == 0 && threadIdx.x == 0) raise_status(a.ctl, tag, status_bit(ZC_ERR_MISMATCH));
     return;
   }
   const u64 tend = tables_end(h.nb, IX);
   const u32 ntiles = u32(num_tiles(h.nb));
-  if (blockIdx.x == 0 && threadIdx.x == 0) write_step_header(a, h, ntiles, IX);
-  if (ntiles == 0) return;
+  if (blockIdx.x == 0 && threadIdx.x == 0) write_step_header(a, h, tag, ntiles, IX);
+  if (ntiles == 0) {                         // a stream without blocks: its one index entry must say so
+    if (IX && blockIdx.x == 0 && wave == 0 && !index_ends_consistent(&a.in, 1, h, 0) && lane == 0)
+      raise_status(a.ctl, tag, status_bit(ZC_ERR_FORMAT));
+    return;
+  }
 
   u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
   if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
-    if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ntiles, xcc_id());
+    if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ltag, ntiles, xcc_id());
     __syncthreads();
     tile = uniform(sh_tile);
   }
@@ -179,6 +202,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
   const u64 seg_off = IX ? u64(uniform(seg_parts.seg)) : segment_offset(seg_parts);
   const u32 wmax_in = wave_block_words(reinterpret_cast<const u32*>(a.in.base + tend), (h.total - tend) / 4, w, seg_off,
                                        wl, lane, lo, hi, IX, uniform(seg_end) - u32(seg_off), h.wide, err);
+  if (IX && seg_live && !index_ends_ok(h, seg, u32(seg_off), uniform(seg_end))) err |= status_bit(ZC_ERR_FORMAT);
 #pragma unroll
   for (int i = 0; i < 8; ++i) *reinterpret_cast<float4*>(wl + (8 * i + (lane >> 3)) * kStageRow + 4 * (lane & 7)) = x[i];
   wave_lds_sync();
@@ -257,9 +281,9 @@ __global__ __launch_bounds__(kTileThreads, 4) void step_kernel(StepArgs a) {
   if (lane == 0) sh_wave_total[wave] = pl.wave_total | (IX && pl.wmax > 15 ? kWaveWideMark : 0u);
   lds_barrier();                // the wave totals; the stores above stay in flight
   sum_wave_totals(sh_wave_total, wave, IX, pl);
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX};
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX, 0u, tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
-  if (err) atomicOr(&a.ctl->status, err);
+  if (err) raise_status(a.ctl, tag, err);
   const TileBase tb = resolve_tile_base(sink, pl, tile, &sh_base, wave, lane);
   const u64 base = tb.words;
   if (lane == 0) write_index_entry(sink, seg, base + pl.wave_off);

@@ -3,20 +3,55 @@ and hand back numpy arrays that can be compared with the reference CPU codec."""
 import numpy as np
 import torch
 
-import paper_2502_18554_amd as zc
+import paper_2502_18554_amd as _zc
+from paper_2502_18554_amd.binding import ZC_STREAM_PLAIN, ZC_TILES_BY_TICKET
 
 DEV = "cuda:0"
 
-INDEXED = False          # the stream variant the library and the reference are set to
+INDEXED = False          # the stream variant the tests are run on (the reference is set to the same; it starts out plain)
+TICKETS = False          # tiles handed out by tickets
+
+# calls that take the stream variant only, and calls that also take the way tiles are handed out
+_READERS = {"zc_compress_bound", "zc_decompress", "zc_decompress_average", "zc_decompress_range", "zc_decompress_many",
+            "zc_debug_block_offsets"}
+_WRITERS = {"zc_compress", "zc_compress_part", "zc_reduce_compressed", "zc_reduce_step", "zc_reduce_step_op"}
+
+
+def flags(writer=True):
+    """The flags argument for the stream variant (and tile hand-out) the tests are running under."""
+    return (0 if INDEXED else ZC_STREAM_PLAIN) | (ZC_TILES_BY_TICKET if writer and TICKETS else 0)
+
+
+class _Library:
+    """The package, with the flags of the variant under test filled in wherever a call takes flags: the
+    library itself has no setting for them."""
+
+    def __getattr__(self, name):
+        f = getattr(_zc, name)
+        if name not in _READERS and name not in _WRITERS:
+            return f
+
+        def call(*args, **kwargs):
+            kwargs.setdefault("flags", flags(name in _WRITERS))
+            return f(*args, **kwargs)
+        return call
+
+
+zc = _Library()
 
 
 def set_variant(zcref, indexed):
-    """Both codecs write and accept plain (False) or indexed (True) streams from here on."""
+    """The library calls made through `zc` and the reference codec write and accept plain (False) or
+    indexed (True) streams from here on."""
     global INDEXED
     INDEXED = bool(indexed)
-    zc.zc_set_indexed_streams(INDEXED)
     if zcref is not None:
         zcref.set_indexed(INDEXED)
+
+
+def set_tickets(on):
+    global TICKETS
+    TICKETS = bool(on)
 
 
 def pad16(v):
@@ -59,7 +94,7 @@ def gpu_compress(x, eb, out_cap=None, ws=None):
     st, total = zc.zc_compress(d_in, n, float(eb), d_out, ws, out_cap=cap)
     assert bool((d_out[cap:] == 0xA5).all()), "wrote past out_cap"
     torch.cuda.synchronize()
-    out = d_out[: min(total, cap)].cpu().numpy() if st in (zc.binding.ZC_OK, zc.binding.ZC_ERR_BOUND) else None
+    out = d_out[: min(total, cap)].cpu().numpy() if st in (_zc.binding.ZC_OK, _zc.binding.ZC_ERR_BOUND) else None
     return st, out, total
 
 
@@ -72,7 +107,7 @@ def gpu_decompress(stream, n_cap, in_bytes=None, ws=None, average=False):
     fn = zc.zc_decompress_average if average else zc.zc_decompress
     st, n = fn(d_in, in_bytes, d_out, ws, out_cap_elems=n_cap)
     torch.cuda.synchronize()
-    return st, (d_out[:n].cpu().numpy() if st == zc.binding.ZC_OK else None), n
+    return st, (d_out[:n].cpu().numpy() if st == _zc.binding.ZC_OK else None), n
 
 
 def gpu_reduce(streams, n, out_cap=None, ws=None):
@@ -84,7 +119,7 @@ def gpu_reduce(streams, n, out_cap=None, ws=None):
     st, total = zc.zc_reduce_compressed(d_chunks, [c.numel() for c in d_chunks], d_out, ws, out_cap=cap)
     assert bool((d_out[cap:] == 0x5A).all()), "wrote past out_cap"
     torch.cuda.synchronize()
-    return st, (d_out[: min(total, cap)].cpu().numpy() if st == zc.binding.ZC_OK else None), total
+    return st, (d_out[: min(total, cap)].cpu().numpy() if st == _zc.binding.ZC_OK else None), total
 
 
 def gpu_decompress_many(streams, n_caps, ws=None):
@@ -113,7 +148,7 @@ def gpu_reduce_step(stream, local, out_cap=None, ws=None, n_local=None, op=None)
         st, total = zc.zc_reduce_step_op(d_in, d_in.numel(), d_loc, n, op, d_out, ws, out_cap=cap)
     assert bool((d_out[cap:] == 0x3C).all()), "wrote past out_cap"
     torch.cuda.synchronize()
-    ok = st in (zc.binding.ZC_OK, zc.binding.ZC_ERR_BOUND)
+    ok = st in (_zc.binding.ZC_OK, _zc.binding.ZC_ERR_BOUND)
     return st, (d_out[: min(total, cap)].cpu().numpy() if ok else None), total
 
 

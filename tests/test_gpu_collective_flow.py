@@ -15,7 +15,7 @@ import numpy as np
 import pytest
 import torch
 
-import paper_2502_18554_amd as zc
+from gpuutil import zc
 from paper_2502_18554_amd import synth
 from paper_2502_18554_amd.binding import ZC_OK
 

@@ -13,7 +13,8 @@ import numpy as np
 import pytest
 import torch
 
-import paper_2502_18554_amd as zc
+import gpuutil
+from gpuutil import zc
 from paper_2502_18554_amd import synth
 from paper_2502_18554_amd.binding import ZC_OK
 
@@ -42,10 +43,10 @@ def gpu_stream_variant(request):
     width table."""
     global INDEXED
     INDEXED = request.param == "indexed"
-    zc.zc_set_indexed_streams(INDEXED)
+    gpuutil.set_variant(None, INDEXED)
     yield request.param
     INDEXED = False
-    zc.zc_set_indexed_streams(False)
+    gpuutil.set_variant(None, False)
 
 
 def u8(nbytes):
@@ -270,12 +271,11 @@ def test_allgather_8x64M(zcref):
 def test_allreduce_8x64M(zcref, hand_out):
     """Configuration 4: fused reduce of 8 compressed rank buffers at a common bound; error <= 8 eb.
     Run with both ways of handing out tiles (the other tests of this file use the default)."""
-    mode = zc.binding.ZC_HAND_OUT_TICKETS if hand_out == "tickets" else zc.binding.ZC_HAND_OUT_DISPATCH_ORDER
-    assert zc.zc_set_tile_hand_out(mode) == ZC_OK
+    gpuutil.set_tickets(hand_out == "tickets")
     try:
         _allreduce_8x64M(zcref)
     finally:
-        zc.zc_set_tile_hand_out(zc.binding.ZC_HAND_OUT_DISPATCH_ORDER)
+        gpuutil.set_tickets(False)
 
 
 def _allreduce_8x64M(zcref):

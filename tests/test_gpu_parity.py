@@ -5,7 +5,8 @@ import numpy as np
 import pytest
 import torch
 
-import paper_2502_18554_amd as zc
+import gpuutil
+from gpuutil import zc
 from paper_2502_18554_amd import synth
 from paper_2502_18554_amd.binding import (ZC_ERR_ARG, ZC_ERR_BOUND, ZC_ERR_CAPACITY, ZC_ERR_FORMAT,
                                            ZC_ERR_MISMATCH, ZC_ERR_NONFINITE, ZC_ERR_RANGE, ZC_OK)
@@ -18,10 +19,9 @@ TILE = 8192
 @pytest.fixture(params=["dispatch_order", "tickets"], autouse=True)
 def tile_hand_out(request):
     """Every test of this module runs with both ways of handing out tiles to workgroups."""
-    mode = zc.binding.ZC_HAND_OUT_TICKETS if request.param == "tickets" else zc.binding.ZC_HAND_OUT_DISPATCH_ORDER
-    assert zc.zc_set_tile_hand_out(mode) == ZC_OK
+    gpuutil.set_tickets(request.param == "tickets")
     yield request.param
-    zc.zc_set_tile_hand_out(zc.binding.ZC_HAND_OUT_DISPATCH_ORDER)
+    gpuutil.set_tickets(False)
 
 
 def _u():
@@ -209,7 +209,7 @@ def test_decompress_error_paths(zcref):
     longer = np.concatenate([s, np.zeros(7, np.uint8)])
     st, y, n = u.gpu_decompress(longer, x.size + 1000)
     assert st == ZC_OK and n == x.size and np.array_equal(y, zcref.decompress(s)[1])
-    st, h_n, h_eb, h_nsum, h_total = zc.zc_peek_header(u.to_dev(s), s.size)
+    st, h_n, h_eb, h_nsum, h_total, h_flags = zc.zc_peek_header(u.to_dev(s), s.size)
     assert (st, h_n, h_nsum, h_total) == (ZC_OK, x.size, 1, total) and h_eb == np.float32(1e-4)
 
 

@@ -34,15 +34,16 @@ def test_library_exports_every_declared_symbol(libzc):
 def test_size_helpers(libzc):
     libzc.zc_compress_bound.restype = C.c_size_t
     libzc.zc_compress_bound.argtypes = [C.c_size_t]
+    libzc.zc_compress_bound_ex.restype = C.c_size_t
+    libzc.zc_compress_bound_ex.argtypes = [C.c_size_t, C.c_uint]
     libzc.zc_workspace_bytes.restype = C.c_size_t
     libzc.zc_workspace_bytes.argtypes = [C.c_size_t, C.c_int]
     pad16 = lambda v: (v + 15) // 16 * 16
     for n in (0, 1, 31, 32, 33, 8192, 8193, 1 << 20, (1 << 27) + 5):
         nb = (n + 31) // 32
-        assert libzc.zc_compress_bound(n) == 32 + pad16(nb) + pad16(4 * nb) + 128 * nb
-        assert libzc.zc_set_indexed_streams(1) == 0            # the bound follows the stream variant
-        assert libzc.zc_compress_bound(n) == 32 + pad16(4 * ((nb + 63) // 64 + 1)) + pad16(nb) + pad16(4 * nb) + 128 * nb
-        assert libzc.zc_set_indexed_streams(0) == 0
+        indexed = 32 + pad16(4 * ((nb + 63) // 64 + 1)) + pad16(nb) + pad16(4 * nb) + 128 * nb
+        assert libzc.zc_compress_bound(n) == indexed == libzc.zc_compress_bound_ex(n, 0)     # the default variant
+        assert libzc.zc_compress_bound_ex(n, 1) == 32 + pad16(nb) + pad16(4 * nb) + 128 * nb  # ZC_STREAM_PLAIN
     assert libzc.zc_workspace_bytes(1 << 27, 1) < (1 << 22)      # under 1 % of the 512 MiB it serves
     assert libzc.zc_workspace_bytes(1 << 26, 8) < libzc.zc_workspace_bytes(1 << 27, 8)
     libzc.zc_strerror.restype = C.c_char_p
@@ -58,11 +59,12 @@ def test_argument_checks_without_gpu(libzc):
     assert libzc.zc_compress(0x1000, 10, 0.0, 0x2000, 100, None, 0x3000, 4096, None) == 1      # eb
     assert libzc.zc_compress(0x1004, 10, 1e-3, 0x2000, 100, None, 0x3000, 4096, None) == 1     # alignment
     assert libzc.zc_compress(0x1000, 1 << 20, 1e-3, 0x2000, 100, None, 0x3000, 64, None) == 1  # workspace
-    libzc.zc_compress_part.argtypes = [vp, sz, C.c_float, sz, sz, vp, sz, C.POINTER(sz), vp, sz, vp]
-    assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 100, 16384, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None) == 1   # not at a tile
-    assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 0, 100, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None) == 1       # not a whole tile
-    assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 1 << 20, 16384, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None) == 1  # past the end
-    assert libzc.zc_set_tile_hand_out(7) == 1 and libzc.zc_set_tile_hand_out(1) == 0 and libzc.zc_set_tile_hand_out(0) == 0
+    libzc.zc_compress_part.argtypes = [vp, sz, C.c_float, sz, sz, vp, sz, C.POINTER(sz), vp, sz, vp, C.c_uint]
+    assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 100, 16384, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None, 0) == 1   # not at a tile
+    assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 0, 100, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None, 0) == 1       # not a whole tile
+    assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 1 << 20, 16384, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None, 0) == 1  # past the end
+    libzc.zc_compress_ex.argtypes = [vp, sz, C.c_float, vp, sz, C.POINTER(sz), vp, sz, vp, C.c_uint]
+    assert libzc.zc_compress_ex(0x1000, 10, 1e-3, 0x2000, 100, None, 0x3000, 4096, None, 4) == 1   # unknown flag
     assert libzc.zc_decompress(None, 100, None, 0, None, None, 0, None) == 1
     assert libzc.zc_decompress(0x1000, 16, 0x2000, 8, None, 0x3000, 4096, None) == 3           # shorter than a header
     assert libzc.zc_reduce_compressed(None, None, 0, None, 0, None, None, 0, None) == 1
@@ -74,26 +76,28 @@ def test_argument_checks_without_gpu(libzc):
     assert libzc.zc_reduce_step(0x1000, 100, None, 8, 0x2000, 100, None, 0x3000, 4096, None) == 1      # no local values
     assert libzc.zc_reduce_step(0x1000, 100, 0x1008, 8, 0x2000, 100, None, 0x3000, 4096, None) == 1    # alignment
     assert libzc.zc_reduce_step(0x1000, 16, 0x4000, 8, 0x2000, 100, None, 0x3000, 4096, None) == 3     # shorter than a header
-    libzc.zc_reduce_step_op.argtypes = [vp, sz, vp, sz, C.c_int, vp, sz, C.POINTER(sz), vp, sz, vp]
+    libzc.zc_reduce_step_op.argtypes = [vp, sz, vp, sz, C.c_int, vp, sz, C.POINTER(sz), vp, sz, vp, C.c_uint]
     for op in (-1, 3):
-        assert libzc.zc_reduce_step_op(0x1000, 100, 0x4000, 8, op, 0x2000, 100, None, 0x3000, 4096, None) == 1   # unknown op
-    assert libzc.zc_reduce_step_op(0x1000, 16, 0x4000, 8, 2, 0x2000, 100, None, 0x3000, 4096, None) == 3
-    libzc.zc_decompress_average.argtypes = [vp, sz, vp, sz, C.POINTER(sz), vp, sz, vp]
-    assert libzc.zc_decompress_average(None, 100, None, 0, None, None, 0, None) == 1
-    assert libzc.zc_decompress_average(0x1000, 16, 0x2000, 8, None, 0x3000, 4096, None) == 3
-    libzc.zc_decompress_range.argtypes = [vp, sz, sz, sz, vp, sz, C.POINTER(sz), vp, sz, vp]
-    assert libzc.zc_decompress_range(0x1000, 100, 100, 8, 0x2000, 8, None, 0x3000, 4096, None) == 1     # not at a segment
-    assert libzc.zc_decompress_range(0x1000, 16, 2048, 8, 0x2000, 8, None, 0x3000, 4096, None) == 3
-    assert libzc.zc_decompress_range(None, 100, 0, 8, 0x2000, 8, None, 0x3000, 4096, None) == 1
+        assert libzc.zc_reduce_step_op(0x1000, 100, 0x4000, 8, op, 0x2000, 100, None, 0x3000, 4096, None, 0) == 1   # unknown op
+    assert libzc.zc_reduce_step_op(0x1000, 16, 0x4000, 8, 2, 0x2000, 100, None, 0x3000, 4096, None, 0) == 3
+    assert libzc.zc_reduce_step_op(0x1000, 100, 0x4000, 8, 2, 0x2000, 100, None, 0x3000, 4096, None, 8) == 1   # unknown flag
+    libzc.zc_decompress_average.argtypes = [vp, sz, vp, sz, C.POINTER(sz), vp, sz, vp, C.c_uint]
+    assert libzc.zc_decompress_average(None, 100, None, 0, None, None, 0, None, 0) == 1
+    assert libzc.zc_decompress_average(0x1000, 16, 0x2000, 8, None, 0x3000, 4096, None, 1) == 3
+    assert libzc.zc_decompress_average(0x1000, 100, 0x2000, 8, None, 0x3000, 4096, None, 2) == 1      # a flag for writers only
+    libzc.zc_decompress_range.argtypes = [vp, sz, sz, sz, vp, sz, C.POINTER(sz), vp, sz, vp, C.c_uint]
+    assert libzc.zc_decompress_range(0x1000, 100, 100, 8, 0x2000, 8, None, 0x3000, 4096, None, 0) == 1     # not at a segment
+    assert libzc.zc_decompress_range(0x1000, 16, 2048, 8, 0x2000, 8, None, 0x3000, 4096, None, 0) == 3
+    assert libzc.zc_decompress_range(None, 100, 0, 8, 0x2000, 8, None, 0x3000, 4096, None, 0) == 1
     assert libzc.zc_reduce_step(0x1000, 100, 0x4000, 1 << 20, 0x2000, 100, None, 0x3000, 64, None) == 1  # workspace
     libzc.zc_decompress_many.argtypes = [C.POINTER(vp), C.POINTER(sz), C.c_int, C.POINTER(vp), C.POINTER(sz), C.POINTER(sz),
-                                         vp, sz, vp]
+                                         vp, sz, vp, C.c_uint]
     outs = (vp * 1)(0x4000)
     caps = (sz * 1)(8)
-    assert libzc.zc_decompress_many(ptrs, sizes, 0, outs, caps, None, 0x3000, 4096, None) == 1
-    assert libzc.zc_decompress_many(ptrs, sizes, 1, None, caps, None, 0x3000, 4096, None) == 1
-    assert libzc.zc_decompress_many(ptrs, (sz * 1)(16), 1, outs, caps, None, 0x3000, 4096, None) == 3
-    assert libzc.zc_decompress_many(ptrs, sizes, 1, (vp * 1)(0x4004), caps, None, 0x3000, 4096, None) == 1
+    assert libzc.zc_decompress_many(ptrs, sizes, 0, outs, caps, None, 0x3000, 4096, None, 0) == 1
+    assert libzc.zc_decompress_many(ptrs, sizes, 1, None, caps, None, 0x3000, 4096, None, 0) == 1
+    assert libzc.zc_decompress_many(ptrs, (sz * 1)(16), 1, outs, caps, None, 0x3000, 4096, None, 0) == 3
+    assert libzc.zc_decompress_many(ptrs, sizes, 1, (vp * 1)(0x4004), caps, None, 0x3000, 4096, None, 0) == 1
     libzc.zc_quality.argtypes = [vp, vp, sz, C.POINTER(C.c_double), vp, sz, vp]
     out4 = (C.c_double * 4)()
     assert libzc.zc_quality(0x1000, 0x2000, 8, None, 0x3000, 4096, None) == 1

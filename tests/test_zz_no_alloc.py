@@ -16,11 +16,11 @@ DEV = "cuda:0"
 TILE = 16384          # values of one tile of the compression kernel
 
 
-def _with_workspace(x, eb):
+def _with_workspace(x, eb, flags=0):
     n = x.numel()
     out = torch.full((zc.zc_compress_bound(n) + 64,), 0xA5, dtype=torch.uint8, device=DEV)
     ws = torch.empty(zc.zc_workspace_bytes(n, 1) + 16, dtype=torch.uint8, device=DEV)
-    st, total = zc.zc_compress(x, n, eb, out, ws, out_cap=out.numel() - 64)
+    st, total = zc.zc_compress(x, n, eb, out, ws, out_cap=out.numel() - 64, flags=flags)
     assert st == ZC_OK
     return out[:total].cpu().numpy()
 
@@ -38,17 +38,15 @@ def _no_alloc(x, eb, sync=True):
     return out[:total].cpu().numpy()
 
 
-@pytest.mark.parametrize("indexed", [False, True], ids=["plain", "indexed"])
-@pytest.mark.parametrize("hand_out", [zc.binding.ZC_HAND_OUT_DISPATCH_ORDER, zc.binding.ZC_HAND_OUT_TICKETS],
-                         ids=["dispatch_order", "tickets"])
-def test_two_calls_in_a_row_match_the_workspace_form(indexed, hand_out):
-    zc.zc_set_indexed_streams(indexed)
-    zc.zc_set_tile_hand_out(hand_out)
-    try:
+@pytest.mark.parametrize("hand_out", [0, zc.binding.ZC_TILES_BY_TICKET], ids=["dispatch_order", "tickets"])
+def test_two_calls_in_a_row_match_the_workspace_form(hand_out):
+    """The entry point takes no flags (the default stream variant and tile hand-out); the stream it is compared
+    with comes from zc_compress on a workspace of the caller, in either hand-out mode."""
+    if True:
         big = synth.power_law_field((40, 64, 64), seed=11, device=DEV)[: 9 * TILE + 4321].contiguous()
         small = synth.sinusoids(2 * TILE + 77, seed=5).to(DEV)
         eb_big, eb_small = synth.abs_bound(big, 1e-3), synth.abs_bound(small, 1e-4)
-        want_big, want_small = _with_workspace(big, eb_big), _with_workspace(small, eb_small)
+        want_big, want_small = _with_workspace(big, eb_big, hand_out), _with_workspace(small, eb_small, hand_out)
         # first call, then a smaller input on the array as the first call left it, then both again in the
         # asynchronous form (completed by zc_finish with a null workspace)
         for sync in (True, False):
@@ -65,9 +63,6 @@ def test_two_calls_in_a_row_match_the_workspace_form(indexed, hand_out):
                 assert got.tobytes() == want.tobytes()
             else:
                 assert got.size == zc.zc_compress_bound(0)
-    finally:
-        zc.zc_set_indexed_streams(False)
-        zc.zc_set_tile_hand_out(zc.binding.ZC_HAND_OUT_DISPATCH_ORDER)
 
 
 def test_size_limit_and_errors():
