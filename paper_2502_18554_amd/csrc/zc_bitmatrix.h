@@ -35,10 +35,23 @@ ZC_HD inline void swap_bits(uint32_t& a, uint32_t& b, int s, uint32_t m) {
 
 // Transposes the 16 x 16 bit matrix in the low halves of r[0..16) and, independently, the
 // one in the high halves: afterwards bit j of half h of r[p] is what bit p of half h of r[j] was.
+// The stage that exchanges whole bytes (shift 8, mask 0x00FF00FF): bytes 1 and 3 of a with bytes 0
+// and 2 of b.  On the GPU that is two byte permutes instead of five bit operations.
+ZC_HD inline void swap_bytes_stage(uint32_t& a, uint32_t& b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  const uint32_t na = __builtin_amdgcn_perm(b, a, 0x06020400u);     // a0 b0 a2 b2
+  const uint32_t nb = __builtin_amdgcn_perm(b, a, 0x07030501u);     // a1 b1 a3 b3
+  a = na;
+  b = nb;
+#else
+  swap_bits(a, b, 8, 0x00FF00FFu);
+#endif
+}
+
 ZC_HD inline void transpose16x16_pairs(uint32_t (&r)[16]) {
 #pragma unroll
   for (int j = 0; j < 16; ++j)
-    if ((j & 8) == 0) swap_bits(r[j], r[j + 8], 8, 0x00FF00FFu);
+    if ((j & 8) == 0) swap_bytes_stage(r[j], r[j + 8]);
 #pragma unroll
   for (int j = 0; j < 16; ++j)
     if ((j & 4) == 0) swap_bits(r[j], r[j + 4], 4, 0x0F0F0F0Fu);

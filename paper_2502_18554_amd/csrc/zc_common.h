@@ -215,6 +215,7 @@ __device__ inline u32 take_ticket(u64* counter, u64 ltag) {
 
 // Claims the next tile (called by one thread of a workgroup).  kNoTile when none is left.
 __device__ inline u32 take_tile(Control* ctl, u64 ltag, u32 ntiles, u32 first_shard) {
+#pragma nounroll
   for (u32 i = 0; i < u32(kTicketShards); ++i) {
     const u32 y = (first_shard + i) & (kTicketShards - 1);
     if (y >= ntiles) continue;

@@ -74,9 +74,18 @@ __device__ inline void store_wave_stage(const WaveStage& st, u32 span, u32* wl, 
   }
 }
 
-__device__ inline u32 wave_block_words(const u32* payload, u64 payload_words, u32 w, u64 seg_off, u32* wl, int lane,
-                                       u32 (&lo)[16], u32 (&hi)[16], bool ix, u32 seg_words, bool may_be_wide,
-                                       u32& err) {
+// What a wave knows about its segment's payload once the widths are scanned.
+struct WavePayload {
+  u32 w;            // this lane's block width (0 if the block must be skipped)
+  u32 off_in_wave;  // payload word offset of this lane's block inside the segment
+  u32 wmax;         // the widest block of the wave (uniform)
+  bool inside;      // the segment lies inside the payload and agrees with the index (uniform)
+};
+
+// First half of wave_block_words: scan of the widths, the checks, and the staged copy of the
+// segment's payload into `wl` when no block is wider than 15 bits.
+__device__ inline WavePayload stage_wave_payload(const u32* payload, u64 payload_words, u32 w, u64 seg_off, u32* wl, int lane,
+                                                 bool ix, u32 seg_words, bool may_be_wide, u32& err) {
   const u32 mis = u32(seg_off) & 3u;
   const u64 src0 = seg_off - mis;                      // in words, multiple of 4
   WaveStage st;
@@ -92,54 +101,70 @@ __device__ inline u32 wave_block_words(const u32* payload, u64 payload_words, u3
     unfit = __any(w > (may_be_wide ? 31u : 15u));
     if (unfit) w = 0;
   }
+  WavePayload wp;
   const u32 words = psize_words(w);
   const u32 incl = wave_inclusive_sum(words);
-  const u32 off_in_wave = incl - words;
+  wp.off_in_wave = incl - words;
   const u32 wave_total = lane_value(incl, 63);
-  const u32 wmax = wave_max_u32(w);
+  wp.wmax = wave_max_u32(w);
+  wp.w = w;
   // a validated stream keeps every segment inside the payload; refuse to read outside anyway
-  bool inside = seg_off + wave_total <= payload_words;
+  wp.inside = seg_off + wave_total <= payload_words;
   if (ix && (unfit || wave_total != seg_words)) {
     err |= status_bit(ZC_ERR_FORMAT);
-    inside = false;
+    wp.inside = false;
   }
+  if (wp.wmax <= 15 && !ix) {
+    span = wp.inside ? mis + wave_total : 0u;
+    st = load_wave_stage(payload, payload_words, src0, span, lane);
+    store_wave_stage(st, span, wl, lane);
+  }
+  return wp;
+}
+
+// Second half, widths up to 15: every lane picks its block's words out of the staged copy.
+// lo[0..15) = planes 0..14, lo[15] = sign word.  `wl` is free again on return.
+__device__ inline void pick_block_words(const WavePayload& wp, u64 seg_off, const u32* wl, u32 (&lo)[16]) {
 #pragma unroll
   for (int p = 0; p < 16; ++p) lo[p] = 0;
-
-  if (wmax <= 15) {
-    if (!ix) {
-      span = inside ? mis + wave_total : 0u;
-      st = load_wave_stage(payload, payload_words, src0, span, lane);
-      store_wave_stage(st, span, wl, lane);
-    }
-    wave_lds_sync();
-    if (w && inside) {
-      const u32* mine = wl + mis + off_in_wave;
-      lo[15] = mine[0];
+  wave_lds_sync();
+  if (wp.w && wp.inside) {
+    const u32* mine = wl + (u32(seg_off) & 3u) + wp.off_in_wave;
+    lo[15] = mine[0];
 #pragma unroll
-      for (int p = 0; p < 15; ++p) {
-        if (u32(p) >= wmax) break;
-        if (u32(p) < w) lo[p] = mine[1 + p];
-      }
+    for (int p = 0; p < 15; ++p) {
+      if (u32(p) >= wp.wmax) break;
+      if (u32(p) < wp.w) lo[p] = mine[1 + p];
     }
-    wave_lds_sync();
+  }
+  wave_lds_sync();
+}
+
+__device__ inline u32 wave_block_words(const u32* payload, u64 payload_words, u32 w, u64 seg_off, u32* wl, int lane,
+                                       u32 (&lo)[16], u32 (&hi)[16], bool ix, u32 seg_words, bool may_be_wide,
+                                       u32& err) {
+  const WavePayload wp = stage_wave_payload(payload, payload_words, w, seg_off, wl, lane, ix, seg_words, may_be_wide, err);
+  if (wp.wmax <= 15) {
+    pick_block_words(wp, seg_off, wl, lo);
   } else {
     // a block wider than 15 bits (stream of an input outside the guaranteed domain): each lane
     // fetches its words straight from global memory
 #pragma unroll
+    for (int p = 0; p < 16; ++p) lo[p] = 0;
+#pragma unroll
     for (int p = 0; p < 16; ++p) hi[p] = 0;
-    if (w && inside) {
-      const u32* mine = payload + seg_off + off_in_wave;
+    if (wp.w && wp.inside) {
+      const u32* mine = payload + seg_off + wp.off_in_wave;
       hi[15] = mine[0];
 #pragma unroll
       for (int p = 0; p < 16; ++p)
-        if (u32(p) < w) lo[p] = mine[1 + p];
+        if (u32(p) < wp.w) lo[p] = mine[1 + p];
 #pragma unroll
       for (int p = 0; p < 15; ++p)
-        if (u32(16 + p) < w) hi[p] = mine[17 + p];
+        if (u32(16 + p) < wp.w) hi[p] = mine[17 + p];
     }
   }
-  return wmax;
+  return wp.wmax;
 }
 
 // ... and from those words the block's Lorenzo deltas (bit-matrix transposes back).

@@ -195,6 +195,32 @@ __device__ inline void copy_wave_out(const PayloadSink& s, WordFn word, const Pl
   }
 }
 
+// The same in one pass, for a wave whose whole payload fits its staging area (64 * NW words): every
+// lane writes its block's words once, and the copy-out is a plain LDS-to-memory copy of the wave's words.
+template <int NW, typename WordFn>
+__device__ inline void copy_wave_out_whole(const PayloadSink& s, WordFn word, const Placement& pl, u64 base, u32* wl, int lane) {
+  if (pl.w) {
+    wl[pl.off_in_wave] = word(std::integral_constant<int, 0>{});
+    [&]<int... P>(std::integer_sequence<int, P...>) {
+      ((u32(P) < pl.w ? void(wl[pl.off_in_wave + 1 + P] = word(std::integral_constant<int, 1 + P>{})) : void()), ...);
+    }(std::make_integer_sequence<int, NW - 1>{});
+  }
+  wave_lds_sync();
+  const u64 tend = tables_end(s.nb, s.ix);
+  const u64 cap_words = s.out_cap > tend ? (s.out_cap - tend) / 4 : 0;
+  const u64 d0 = base + pl.wave_off;
+  u32* const dst = reinterpret_cast<u32*>(s.out + tend) + d0;
+  const u64 room = cap_words > d0 ? cap_words - d0 : 0;
+  const u32 limit = u64(pl.wave_total) < room ? pl.wave_total : u32(room);
+#pragma unroll 4
+  for (u32 r = 0; r < u32(NW); ++r) {
+    const u32 i = u32(lane) + 64u * r;
+    if (64u * r >= limit) break;             // uniform
+    if (i < limit) dst[i] = wl[i];
+  }
+  wave_lds_sync();
+}
+
 // Back half of a tile once the plane words sit in registers (`word(i)`: 0 = sign, 1 + p =
 // plane p) and its size is published: look back for the base offset, then move the payload
 // out.  Called by every wave of the workgroup; one barrier.
