@@ -1,10 +1,12 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration
 bench.py times (asynchronous calls on device-resident buffers).
 
-The reference CPU codec cannot run whole buffers of this size inside a test, but blocks are
-independent: a block-aligned slice of the input, compressed alone by the reference codec, must
-reproduce the GPU stream's width bytes, outliers and payload bytes of those blocks (found
-through the exclusive sum of the GPU stream's own width table, computed with torch), and its
+The two graded configurations (the 512^3 field at rel 1e-4, and the fused reduce of 8 x 2^26 values) are
+compared with the reference CPU codec as wholes: stream bytes and reconstruction, bit for bit, in both
+stream variants.  The reference cannot run every buffer of this size inside a test, but blocks are
+independent: for the other configurations a block-aligned slice of the input, compressed alone by the
+reference codec, must reproduce the GPU stream's width bytes, outliers and payload bytes of those blocks
+(found through the exclusive sum of the GPU stream's own width table, computed with torch), and its
 reconstruction must equal the GPU's bit for bit.  Slices are drawn with a fixed seed and always
 include the first blocks and the ragged end.  On top of that come the properties that hold at
 any size: error bound on every value, idempotence on the grid, header fields, sizes that add up.
@@ -155,6 +157,30 @@ def check_quality(zcref, x, y, eb, rng):
     assert abs(part[1] / want["sse"] - 1) < 1e-10
 
 
+class reference_variant:
+    """Inside the block the reference writes and accepts the stream variant the library is being run on
+    (outside it stays on plain streams, which is what the slice comparisons expect)."""
+
+    def __init__(self, zcref):
+        self.zcref = zcref
+
+    def __enter__(self):
+        self.zcref.set_indexed(INDEXED)
+
+    def __exit__(self, *exc):
+        self.zcref.set_indexed(False)
+
+
+def assert_same_bytes(d_buf, ref, what, chunk=1 << 26):
+    """A device buffer against a numpy array, byte for byte, without a second copy of either."""
+    assert d_buf.numel() == ref.size, f"{what}: {d_buf.numel()} bytes, reference {ref.size}"
+    for i in range(0, ref.size, chunk):
+        got = d_buf[i:i + chunk].cpu().numpy()
+        if not np.array_equal(got, ref[i:i + chunk]):
+            at = i + int(np.nonzero(got != ref[i:i + chunk])[0][0])
+            raise AssertionError(f"{what} differs from the reference at byte {at}")
+
+
 def max_abs_err(x, y, chunk=1 << 27):
     worst = 0.0
     for i in range(0, x.numel(), chunk):
@@ -183,6 +209,15 @@ def test_field_512cube(zcref, rel):
     # idempotence on the grid: the reconstruction compresses to the same bytes
     st, buf2, total2 = compress_async(y, eb, ws)
     assert st == ZC_OK and total2 == total and torch.equal(buf2[:total], buf[:total])
+    if rel == 1e-4:
+        # the graded configuration: the whole stream and the whole reconstruction against the reference
+        # run on the whole field (the index levels above one span only exist at this size)
+        with reference_variant(zcref):
+            st, ref, ref_total = zcref.compress(x.cpu().numpy(), eb)
+            assert st == 0 and ref_total == total
+            assert_same_bytes(buf[:total], ref, "compressed stream")
+            st, y_ref, _ = zcref.decompress(ref)
+        assert st == 0 and np.array_equal(y.cpu().numpy().view(np.uint32), y_ref.view(np.uint32))
 
 
 def test_field_512cube_in_parts_and_chunks(zcref):
@@ -318,6 +353,17 @@ def _allreduce_8x64M(zcref):
     assert st == 0
     st, ya_ref, _ = zcref.decompress(ref, average=True)
     assert st == 0 and np.array_equal(ya[v0:v1].cpu().numpy().view(np.uint32), ya_ref.view(np.uint32))
+    if not gpuutil.TICKETS:
+        # the graded configuration: the whole reduced stream against the reference's reduce of the whole operands
+        with reference_variant(zcref):
+            refs = [zcref.compress(x.cpu().numpy(), eb)[1] for x in xs]
+            for s_gpu, ref in zip(streams, refs):
+                assert_same_bytes(s_gpu.buf[:s_gpu.total], ref, "operand stream")
+            st, ref, ref_total = zcref.reduce(refs)
+            del refs
+        assert st == 0 and ref_total == total
+        assert_same_bytes(red[:total], ref, "reduced stream")
+        del ref
     # sampled slices: the reference reduce of the operands' slices reproduces the GPU stream there
     for b0 in sample_starts(m, rng, 4):
         v0, v1 = 32 * b0, min(m, 32 * b0 + SLICE)

@@ -1017,3 +1017,157 @@ def test_corrupted_streams_get_the_reference_verdict(zcref, seed):
             assert r.tobytes() == ref[1].tobytes()
         verdicts[ref[0]] = verdicts.get(ref[0], 0) + 1
     assert len(verdicts) >= 2                                        # some accepted, some refused
+
+
+def test_both_stream_variants_in_one_process_without_any_setting(zcref):
+    """The variant is an argument of each call: plain and indexed streams are written and read side by
+    side, by the library called directly (no test-side defaults), and the other variant's flag is FORMAT."""
+    import paper_2502_18554_amd as lib
+    from paper_2502_18554_amd.binding import ZC_STREAM_PLAIN
+    u = _u()
+    n = 3 * TILE + 123
+    xs = [synth.power_law_field((8, 64, 64), seed=60 + i).numpy()[:n] for i in range(3)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), 1e-3)
+    ws = u.workspace(n, 3)
+    streams = {}
+    for flags in (0, ZC_STREAM_PLAIN, 0, ZC_STREAM_PLAIN):          # interleaved on one workspace
+        zcref.set_indexed(flags == 0)
+        got = []
+        for x in xs:
+            out = torch.empty(lib.zc_compress_bound(n, flags), dtype=torch.uint8, device=u.DEV)
+            st, total = lib.zc_compress(u.to_dev(x), n, eb, out, ws, flags=flags)
+            assert st == ZC_OK and out[:total].cpu().numpy().tobytes() == zcref.compress(x, eb)[1].tobytes()
+            got.append((out, total))
+        streams[flags] = got
+    y = torch.empty(n, dtype=torch.float32, device=u.DEV)
+    red = torch.empty(lib.zc_compress_bound(n), dtype=torch.uint8, device=u.DEV)
+    for flags, other in ((0, ZC_STREAM_PLAIN), (ZC_STREAM_PLAIN, 0)):
+        zcref.set_indexed(flags == 0)
+        s, total = streams[flags][0]
+        st, m = lib.zc_decompress(s, total, y, ws, flags=flags)
+        assert st == ZC_OK and m == n
+        assert np.array_equal(y.cpu().numpy(), zcref.decompress(s[:total].cpu().numpy())[1])
+        assert lib.zc_decompress(s, total, y, ws, flags=other)[0] == ZC_ERR_FORMAT
+        assert lib.zc_peek_header(s, total)[5] == flags
+        st, rt = lib.zc_reduce_compressed([a for a, _ in streams[flags]], [b for _, b in streams[flags]], red, ws, flags=flags)
+        ref = zcref.reduce([a[:b].cpu().numpy() for a, b in streams[flags]])[1]
+        assert st == ZC_OK and red[:rt].cpu().numpy().tobytes() == ref.tobytes()
+        mixed = [streams[flags][0], streams[other][1], streams[flags][2]]
+        assert lib.zc_reduce_compressed([a for a, _ in mixed], [b for _, b in mixed], red, ws, flags=flags)[0] == ZC_ERR_FORMAT
+    zcref.set_indexed(u.INDEXED)
+
+
+def test_workspace_content_is_irrelevant(zcref):
+    """Nothing in a workspace is ever cleared: a call must not care what it finds there: noise, all ones,
+    or what an earlier call left behind, seen at another offset (a workspace carved out of recycled memory)."""
+    u = _u()
+    n = 5 * TILE + 1000
+    xs = [synth.power_law_field((11, 64, 64), seed=70 + i).numpy()[:n] for i in range(3)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), 1e-3)
+    refs = [zcref.compress(x, eb)[1] for x in xs]
+    red_ref = zcref.reduce(refs)[1]
+    step_ref = zcref.reduce_step(refs[0], xs[1])[1]
+    size = zc.zc_workspace_bytes(n, 3) + 16
+    arena = torch.empty(size + 4096, dtype=torch.uint8, device=u.DEV)
+    gen = torch.Generator(device=u.DEV)
+    gen.manual_seed(7)
+    for fill in ("noise", "ones", "used", "shifted", "shifted again"):
+        shift = {"shifted": 128, "shifted again": 1152}.get(fill, 0)
+        ws = arena[shift:shift + size]
+        if fill == "noise":
+            arena.copy_(torch.randint(0, 256, arena.shape, dtype=torch.uint8, device=u.DEV, generator=gen))
+        elif fill == "ones":
+            arena.fill_(0xFF)
+        st, s, _ = u.gpu_compress(xs[0], eb, ws=ws)
+        assert st == ZC_OK and s.tobytes() == refs[0].tobytes(), fill
+        st, r, _ = u.gpu_reduce(refs, n, ws=ws)
+        assert st == ZC_OK and r.tobytes() == red_ref.tobytes(), fill
+        st, t, _ = u.gpu_reduce_step(refs[0], xs[1], ws=ws)
+        assert st == ZC_OK and t.tobytes() == step_ref.tobytes(), fill
+        st, y, m = u.gpu_decompress(refs[0], n, ws=ws)
+        assert st == ZC_OK and np.array_equal(y, zcref.decompress(refs[0])[1]), fill
+        # an error of one call must not show in the next
+        assert u.gpu_decompress(refs[0], n - 1, ws=ws)[0] == ZC_ERR_CAPACITY
+        st, s, _ = u.gpu_compress(xs[2], eb, ws=ws)
+        assert st == ZC_OK and s.tobytes() == refs[2].tobytes(), fill
+
+
+def test_concurrent_calls_on_several_streams(zcref):
+    """Calls that write streams (compress, k-way reduce, ring round) run at the same time on three HIP
+    streams with a workspace each, while a long elementwise kernel keeps a fourth stream busy; every output
+    is the reference's, byte for byte.  All waits inside the kernels are bounded."""
+    u = _u()
+    n = 48 * TILE + 77
+    xs = [synth.power_law_field((97, 64, 64), seed=80 + i).numpy()[:n] for i in range(4)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), 1e-3)
+    refs = [zcref.compress(x, eb)[1] for x in xs]
+    want = {"compress": refs[3], "reduce": zcref.reduce(refs[:3])[1], "round": zcref.reduce_step(refs[0], xs[1])[1]}
+    d_x = [u.to_dev(x) for x in xs]
+    d_s = [u.to_dev(s) for s in refs]
+    cap = zc.zc_compress_bound(n)
+    outs = {k: torch.empty(cap, dtype=torch.uint8, device=u.DEV) for k in want}
+    wss = {k: u.workspace(n, 3) for k in want}
+    streams = {k: torch.cuda.Stream() for k in want}
+    busy_stream = torch.cuda.Stream()
+    big = torch.ones(1 << 28, dtype=torch.float32, device=u.DEV)
+    torch.cuda.synchronize()
+    for rep in range(6):
+        for o in outs.values():
+            o.fill_(0x11)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(busy_stream):
+            for _ in range(4):
+                big.mul_(1.0000001).add_(1e-9)
+        for _ in range(3):                         # several rounds of the three calls in flight together
+            assert zc.zc_compress(d_x[3], n, eb, outs["compress"], wss["compress"], sync=False, stream=streams["compress"])[0] == ZC_OK
+            assert zc.zc_reduce_compressed(d_s[:3], [s.numel() for s in d_s[:3]], outs["reduce"], wss["reduce"], sync=False,
+                                           stream=streams["reduce"])[0] == ZC_OK
+            assert zc.zc_reduce_step(d_s[0], d_s[0].numel(), d_x[1], n, outs["round"], wss["round"], sync=False,
+                                     stream=streams["round"])[0] == ZC_OK
+        for k in want:
+            st, total = zc.zc_finish(wss[k], stream=streams[k])
+            assert st == ZC_OK and total == want[k].size, (k, rep, st)
+            assert outs[k][:total].cpu().numpy().tobytes() == want[k].tobytes(), (k, rep)
+        torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("short_by", ["all", "more than an index span"])
+def test_output_too_small_by_a_lot_is_capacity(zcref, short_by):
+    """A stream that is in order and an output buffer that is much too small: CAPACITY and the stream's n,
+    also when the buffer is short by more than the 2^20 values that one workgroup of the index kernel covers."""
+    u = _u()
+    n = (1 << 21) + 4097
+    x = synth.sinusoids(n, seed=9).numpy()
+    eb = synth.abs_bound(torch.from_numpy(x), 1e-3)
+    _, s, _ = zcref.compress(x, eb)
+    cap = 0 if short_by == "all" else n - (1 << 20) - 1
+    ws = u.workspace(n, 2)
+    ws.fill_(0x5A)
+    st, _, m = u.gpu_decompress(s, cap, ws=ws)
+    assert (st, m) == (ZC_ERR_CAPACITY, n)
+    assert zcref.decompress(s, out_cap_elems=cap)[0] == ZC_ERR_CAPACITY
+    st, _, ns = u.gpu_decompress_many([s, s], [cap, n], ws=ws)
+    assert st == ZC_ERR_CAPACITY and ns == [n, n]
+    st, outs, ns = u.gpu_decompress_many([s, s], [n, n], ws=ws)
+    assert st == ZC_OK and np.array_equal(outs[1][:n], zcref.decompress(s)[1])
+
+
+def test_infinity_under_a_huge_bound_is_nonfinite(zcref):
+    """With a bound above 2^111 the quantiser's screen 2^17 eb is no binary32 number any more; an infinite
+    input must still end as NONFINITE, in the compression, the staged quantiser and the ring round."""
+    u = _u()
+    eb = np.float32(1e34)
+    x = np.zeros(2 * TILE + 5, np.float32)
+    x[TILE + 3] = np.inf
+    assert zcref.compress(x, eb)[0] == ZC_ERR_NONFINITE
+    assert u.gpu_compress(x, eb)[0] == ZC_ERR_NONFINITE
+    d_q = torch.empty(x.size, dtype=torch.int32, device=u.DEV)
+    assert zc.zc_debug_quantize(u.to_dev(x), x.size, float(eb), d_q, u.workspace(x.size)) == ZC_ERR_NONFINITE
+    zeros = np.zeros_like(x)
+    _, s0, _ = zcref.compress(zeros, eb)
+    assert zcref.reduce_step(s0, x)[0] == ZC_ERR_NONFINITE
+    assert u.gpu_reduce_step(s0, x)[0] == ZC_ERR_NONFINITE
+    x[TILE + 3] = np.float32(3e38)             # finite, and inside the bound's domain: nothing to report
+    st, s, _ = u.gpu_compress(x, eb)
+    st_ref, s_ref, _ = zcref.compress(x, eb)
+    assert st == st_ref and (s is None or s.tobytes() == s_ref.tobytes())

@@ -136,3 +136,38 @@ def test_bit_matrix_transposes_match_packbits(bm, cls, maxw):
         d2 = np.zeros(32, np.int32)
         bm.bm_deltas_from_planes(out.ctypes.data_as(p32), 8 if cls == 816 else cls, d2.ctypes.data_as(pi32))
         assert np.array_equal(d2, d)
+
+
+def test_calls_from_two_threads_share_no_setting(libzc):
+    """The library keeps no settings: two host threads that want different stream variants and tile
+    hand-outs say so in their calls and never see each other's choice.  (Without a GPU only the
+    host side of the calls can run: the size helpers and the argument checks.)"""
+    import threading
+    vp, sz = C.c_void_p, C.c_size_t
+    libzc.zc_compress_bound_ex.restype = sz
+    libzc.zc_compress_bound_ex.argtypes = [sz, C.c_uint]
+    libzc.zc_compress_ex.argtypes = [vp, sz, C.c_float, vp, sz, C.POINTER(sz), vp, sz, vp, C.c_uint]
+    libzc.zc_decompress_ex.argtypes = [vp, sz, vp, sz, C.POINTER(sz), vp, sz, vp, C.c_uint]
+    pad16 = lambda v: (v + 15) // 16 * 16
+    failures = []
+
+    def worker(flags, rounds):
+        plain = bool(flags & 1)
+        for i in range(rounds):
+            n = 1000 + 37 * i
+            nb = (n + 31) // 32
+            want = 32 + (0 if plain else pad16(4 * ((nb + 63) // 64 + 1))) + pad16(nb) + pad16(4 * nb) + 128 * nb
+            if libzc.zc_compress_bound_ex(n, flags) != want:
+                failures.append(("bound", flags, n))
+            # argument checks only (a misaligned input): no launch, whatever the flags say
+            if libzc.zc_compress_ex(0x1004, n, 1e-3, 0x2000, 100, None, 0x3000, 1 << 20, None, flags) != 1:
+                failures.append(("compress", flags, n))
+            if libzc.zc_decompress_ex(0x1000, 16, 0x2000, 8, None, 0x3000, 4096, None, flags & 1) != 3:
+                failures.append(("decompress", flags, n))
+
+    threads = [threading.Thread(target=worker, args=(f, 2000)) for f in (0, 1, 2, 3)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not failures, failures[:5]
