@@ -360,14 +360,19 @@ int zcref_inspect(const void* in, size_t in_bytes, int32_t* q, uint8_t* widths, 
   return OK;
 }
 
-// Local step of the compressed Allreduce (Section 3.1.2; Sum aggregation, Section 3.2):
-// k compressed operands on one common grid -> the compressed sum.  Decode every operand to
-// its integer codes, add them, encode the sums.  Because all operands share the step, the
-// sum of grid points is a grid point and no new quantisation error appears.
+// Local step of the compressed Allreduce (Section 3.1.2; aggregation functions of Section 3.2):
+// k compressed operands on one common grid -> the compressed aggregate.  Decode every operand
+// to its integer codes, combine them value by value, encode the results.
+// op 0, Sum: the codes are added.  Because all operands share the step, the sum of grid points
+// is a grid point and no new quantisation error appears.
+// op 1 / 2, Max / Min: the largest / smallest code.  The quantiser is monotone, so the largest
+// code is the code of the largest value: the result is the stream of the elementwise maximum
+// (minimum) of the original buffers compressed once, within one error bound of it whatever k is.
+// nsum of the result is the sum of the operands' nsum (the number of buffers it stands for).
 // Status precedence: ARG, FORMAT, MISMATCH, RANGE, CAPACITY.
-int zcref_reduce(const void* const* chunks, const size_t* chunk_bytes, int k,
-                 void* out, size_t out_cap, size_t* out_bytes) {
-  if (k < 1 || !chunks || !chunk_bytes || !out) return ERR_ARG;
+int zcref_reduce_op(const void* const* chunks, const size_t* chunk_bytes, int k, int op,
+                    void* out, size_t out_cap, size_t* out_bytes) {
+  if (k < 1 || !chunks || !chunk_bytes || !out || op < 0 || op > 2) return ERR_ARG;
   for (int i = 0; i < k; ++i) if (!chunks[i]) return ERR_ARG;
   std::vector<Parsed> ps(k);
   for (int i = 0; i < k; ++i) {
@@ -385,13 +390,23 @@ int zcref_reduce(const void* const* chunks, const size_t* chunk_bytes, int k,
   std::vector<int32_t> q(n);
   for (int i = 0; i < k; ++i) {
     decode_codes(ps[i], q.data());
-    for (size_t j = 0; j < n; ++j) total[j] += q[j];
+    for (size_t j = 0; j < n; ++j) {
+      if (op == 0) total[j] += q[j];
+      else if (i == 0) total[j] = q[j];
+      else if (op == 1) total[j] = std::max<int64_t>(total[j], q[j]);
+      else total[j] = std::min<int64_t>(total[j], q[j]);
+    }
   }
   for (size_t j = 0; j < n; ++j) {
     if (total[j] > kMaxCode || total[j] < -kMaxCode) return ERR_RANGE;
     q[j] = int32_t(total[j]);
   }
   return encode_codes(q.data(), n, ps[0].eb_bits, uint32_t(nsum), static_cast<uint8_t*>(out), out_cap, out_bytes);
+}
+
+int zcref_reduce(const void* const* chunks, const size_t* chunk_bytes, int k,
+                 void* out, size_t out_cap, size_t* out_bytes) {
+  return zcref_reduce_op(chunks, chunk_bytes, k, 0, out, out_cap, out_bytes);
 }
 
 // One round of the ring reduce-scatter (Section 3.1.2: per round a received compressed chunk

@@ -40,6 +40,8 @@ def lib():
                                         C.POINTER(C.c_size_t)]
         L.zcref_reduce.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_size_t), C.c_int, C.c_void_p,
                                    C.c_size_t, C.POINTER(C.c_size_t)]
+        L.zcref_reduce_op.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_size_t), C.c_int, C.c_int, C.c_void_p,
+                                      C.c_size_t, C.POINTER(C.c_size_t)]
         _lib = L
     return _lib
 
@@ -127,8 +129,9 @@ def inspect(stream):
     return st, q[:n], w[:nb], off[:nb]
 
 
-def reduce(streams, out_cap=None):
-    """Returns (status, stream bytes, total_bytes reported)."""
+def reduce(streams, out_cap=None, op=0):
+    """k streams -> the stream of their sum (op 0), elementwise maximum (1) or minimum (2) on the common grid.
+    Returns (status, stream bytes, total_bytes reported)."""
     streams = [np.ascontiguousarray(s, dtype=np.uint8) for s in streams]
     k = len(streams)
     ptrs = (C.c_void_p * max(k, 1))(*[s.ctypes.data for s in streams])
@@ -138,7 +141,10 @@ def reduce(streams, out_cap=None):
         out_cap = compress_bound(min(n, 2**31))
     out = np.zeros(max(out_cap, 1), dtype=np.uint8)
     nbytes = C.c_size_t(0)
-    st = lib().zcref_reduce(ptrs, sizes, k, _ptr(out), out_cap, C.byref(nbytes))
+    if op == 0:
+        st = lib().zcref_reduce(ptrs, sizes, k, _ptr(out), out_cap, C.byref(nbytes))
+    else:
+        st = lib().zcref_reduce_op(ptrs, sizes, k, int(op), _ptr(out), out_cap, C.byref(nbytes))
     return st, (out[: nbytes.value].copy() if st == OK else out[:0]), nbytes.value
 
 

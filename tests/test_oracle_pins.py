@@ -686,6 +686,47 @@ def test_ring_max_min_by_hand_and_symmetry(zcref):
     assert zcref.reduce_step(sx, loc, op=zcref.OP_SUM)[1].tobytes() == zcref.reduce_step(sx, loc)[1].tobytes()
 
 
+@pytest.mark.parametrize("k", [1, 2, 5, 64])
+def test_kway_max_min_on_the_codes(zcref, k):
+    """The k-way Max / Min of compressed operands: numpy's extreme of the decoded codes, encoded by the
+    numpy model of the stream; the ring of Max rounds over the same buffers; compressing numpy's
+    elementwise extreme once; within one bound of it, inside Theorem 2's variance; and its error paths."""
+    n = 4 * 32 * 33 - 7
+    xs = [synth.power_law_field((4, 33, 32), seed=400 + i).numpy().ravel()[:n] for i in range(k)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), 1e-3)
+    streams = [zcref.compress(x, eb)[1] for x in xs]
+    codes = np.stack([zcref.inspect(s)[1] for s in streams])
+    for op, extreme in ((zcref.OP_MAX, np.maximum), (zcref.OP_MIN, np.minimum)):
+        st, got, total = zcref.reduce(streams, op=op)
+        assert st == zcref.OK and total == got.size
+        want_codes = extreme.reduce(codes)
+        assert np.array_equal(zcref.inspect(got)[1], want_codes)
+        assert got.tobytes() == lm.stream_from_codes(want_codes, eb, nsum=k)[0].tobytes()
+        # the ring of rounds over the uncompressed buffers ends in the same stream
+        assert _ring(zcref, xs, eb, op).tobytes() == got.tobytes()
+        once = zcref.compress(extreme.reduce(xs), eb)[1].copy()
+        once[20:24] = np.array([k], "<u4").view(np.uint8)
+        assert once.tobytes() == got.tobytes()
+        err = np.abs(zcref.decompress(got)[1].astype(np.float64) - extreme.reduce(xs))
+        assert err.max() <= eb
+        assert err.var() + err.mean() ** 2 <= (2 - (k + 2) / 2 ** k) * lm.step(eb) ** 2 / 12 * 1.1 or k == 1
+    # Sum through the same entry is the Sum
+    assert zcref.reduce(streams, op=zcref.OP_SUM)[1].tobytes() == zcref.reduce(streams)[1].tobytes()
+    # by hand: three operands of four values each
+    q = [np.array([3, -2, 0, 7] * 8, np.int32), np.array([1, -1, -5, 9] * 8, np.int32), np.array([2, -9, 4, 8] * 8, np.int32)]
+    ss = [zcref.encode_codes(c, 0.5)[1] for c in q]
+    assert list(zcref.inspect(zcref.reduce(ss, op=zcref.OP_MAX)[1])[1][:4]) == [3, -1, 4, 9]
+    assert list(zcref.inspect(zcref.reduce(ss, op=zcref.OP_MIN)[1])[1][:4]) == [1, -9, -5, 7]
+    assert int(zcref.reduce(ss, op=zcref.OP_MIN)[1][20:24].view("<u4")[0]) == 3
+    # errors
+    assert zcref.reduce(ss, op=3)[0] == zcref.ERR_ARG
+    other = zcref.encode_codes(q[0], 0.25)[1]
+    assert zcref.reduce([ss[0], other], op=zcref.OP_MAX)[0] == zcref.ERR_MISMATCH
+    bad = ss[1].copy(); bad[0] ^= 1
+    assert zcref.reduce([ss[0], bad], op=zcref.OP_MIN)[0] == zcref.ERR_FORMAT
+    assert zcref.reduce(ss, op=zcref.OP_MAX, out_cap=40)[0] == zcref.ERR_CAPACITY
+
+
 @pytest.mark.parametrize("k", [1, 2, 8, 64])
 def test_average_decompress(zcref, k):
     xs, eb, streams = _rank_streams(zcref, k, (4, 32, 33), 1e-3, seed0=300)
