@@ -235,6 +235,18 @@ int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_lo
                       void* d_out, size_t out_cap, size_t* out_bytes,
                       void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
+/* The local step of the compressed Allreduce for all three aggregation functions of Section 3.2
+ * on k compressed operands: op ZC_OP_SUM is zc_reduce_compressed_ex; ZC_OP_MAX / ZC_OP_MIN give the
+ * stream of the largest / smallest code of every value.  The operands share the quantisation step
+ * and the quantiser is monotone, so that is exactly the stream of the elementwise maximum (minimum)
+ * of the original buffers compressed once: within abs_eb of it whatever k is (inside Theorem 2's
+ * variance), and equal to what a ring of zc_reduce_step_op rounds over the same buffers ends in.
+ * nsum of the result is the sum of the operands' nsum.  Arguments and errors as
+ * zc_reduce_compressed_ex, and ARG for an unknown op. */
+int zc_reduce_compressed_op(const void* const* d_chunks, const size_t* chunk_bytes, int k, int op,
+                            void* d_out, size_t out_cap, size_t* out_bytes,
+                            void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
+
 /* Quality of a reconstruction d_test against its original d_ref (n binary32 values each,
  * 16-byte aligned): the sums behind the paper's quality figures (NRMSE in Section 3.3, PSNR
  * and NRMSE in Section 4.6).  out4 (host, 4 doubles): max |ref - test|, sum of squared

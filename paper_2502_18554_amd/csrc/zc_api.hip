@@ -15,6 +15,7 @@
 #include "zc_compress.h"
 #include "zc_decompress.h"
 #include "zc_reduce.h"
+#include "zc_reduce_op.h"
 #include "zc_scan.h"
 #include "zc_quality.h"
 #include "zc_step.h"
@@ -453,10 +454,10 @@ int zc_decompress_many(const void* const* d_chunks, const size_t* chunk_bytes, i
   return st;
 }
 
-int zc_reduce_compressed_ex(const void* const* d_chunks, const size_t* chunk_bytes, int k, void* d_out, size_t out_cap,
+int zc_reduce_compressed_op(const void* const* d_chunks, const size_t* chunk_bytes, int k, int op, void* d_out, size_t out_cap,
                             size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (!flags_valid(flags)) return ZC_ERR_ARG;
+  if (!flags_valid(flags) || (op != ZC_OP_SUM && op != ZC_OP_MAX && op != ZC_OP_MIN)) return ZC_ERR_ARG;
   if (k < 1 || k > ZC_MAX_K || !d_chunks || !chunk_bytes || !d_out || !d_ws) return ZC_ERR_ARG;
   if (!aligned16(d_out) || !aligned16(d_ws)) return ZC_ERR_ARG;
   for (int i = 0; i < k; ++i)
@@ -500,12 +501,28 @@ int zc_reduce_compressed_ex(const void* const* d_chunks, const size_t* chunk_byt
   ra.desc = l.desc;
   ra.ticketed = (flags & ZC_TILES_BY_TICKET) != 0;
   ra.nonce = nonce;
-  launch_main(ZC_KERNEL_REDUCE, ix ? reduce_kernel<true> : reduce_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), stream, ra);
-  // plain streams with blocks wider than 15 bits have a kernel of their own, which returns at once otherwise
-  if (!ix) hipLaunchKernelGGL(reduce_wide_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
+  if (op == ZC_OP_SUM) {
+    launch_main(ZC_KERNEL_REDUCE, ix ? reduce_kernel<true> : reduce_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), stream, ra);
+    // plain streams with blocks wider than 15 bits have a kernel of their own, which returns at once otherwise
+    if (!ix) hipLaunchKernelGGL(reduce_wide_kernel, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
+  } else {
+    // Max and Min: a kernel for operands without blocks wider than 15 bits and one for the others;
+    // each returns at once when the operands are not its
+    void (*narrow)(ReduceArgs) = op == ZC_OP_MAX ? (ix ? reduce_op_kernel<true, ZC_OP_MAX> : reduce_op_kernel<false, ZC_OP_MAX>)
+                                                 : (ix ? reduce_op_kernel<true, ZC_OP_MIN> : reduce_op_kernel<false, ZC_OP_MIN>);
+    void (*wide)(ReduceArgs) = op == ZC_OP_MAX ? (ix ? reduce_op_wide_kernel<true, ZC_OP_MAX> : reduce_op_wide_kernel<false, ZC_OP_MAX>)
+                                               : (ix ? reduce_op_wide_kernel<true, ZC_OP_MIN> : reduce_op_wide_kernel<false, ZC_OP_MIN>);
+    launch_main(ZC_KERNEL_REDUCE, narrow, dim3(u32(tiles)), dim3(kTileThreads), stream, ra);
+    hipLaunchKernelGGL(wide, dim3(u32(tiles)), dim3(kTileThreads), 0, stream, ra);
+  }
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
+}
+
+int zc_reduce_compressed_ex(const void* const* d_chunks, const size_t* chunk_bytes, int k, void* d_out, size_t out_cap,
+                            size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
+  return zc_reduce_compressed_op(d_chunks, chunk_bytes, k, ZC_OP_SUM, d_out, out_cap, out_bytes, d_ws, ws_bytes, hip_stream, flags);
 }
 
 int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes, int k, void* d_out, size_t out_cap,

@@ -653,25 +653,28 @@ __device__ inline void reduce_wide_tile(const ReduceArgs& a, const ReduceCall& c
 // been validated and indexed by the kernels of zc_scan.h, whose verdict and tag are in the
 // control block; indexed streams are judged here, by every workgroup alike, from their headers.
 // `meta`, `early`: see reduce_narrow_tile.  `for_wide`: the caller is the kernel that serves
-// plain streams with blocks wider than 15 bits (the narrow one returns at once on those, and
-// the other way round; either writes the header of its own calls).
+// streams with blocks wider than 15 bits (the narrow one returns at once on those, and
+// the other way round; either writes the header of its own calls); `split`: indexed streams
+// have such a pair of kernels as well (otherwise one kernel takes both kinds).
 template <bool IX>
-__device__ inline bool open_reduce(const ReduceArgs& a, bool for_wide, ReduceCall& c, bool& wide, OperandMeta& meta, bool early,
-                                   u32& tile, u32& ntiles, u32* sh_tile) {
+__device__ inline bool open_reduce(const ReduceArgs& a, bool for_wide, bool split, ReduceCall& c, bool& wide, OperandMeta& meta,
+                                   bool early, u32& tile, u32& ntiles, u32* sh_tile) {
   c.ltag = launch_tag(a.nonce, a.ctl);
   if (IX) {
     const StreamsVerdict v = judge_indexed_streams(a.in, a.k, true);
-    c.tag = call_tag(a.ctl, c.ltag, false);
+    // (of a pair of kernels the narrow one is launched first and opens the call)
+    c.tag = call_tag(a.ctl, c.ltag, split && for_wide);
     c.h = v.h0;
     c.nsum = v.nsum;
     wide = v.wide;
     if (v.err) {
-      if (blockIdx.x == 0 && threadIdx.x == 0) {
+      if (blockIdx.x == 0 && threadIdx.x == 0 && !(split && for_wide)) {
         a.ctl->result = 0;
         raise_status(a.ctl, c.tag, v.err);
       }
       return false;
     }
+    if (split && wide != for_wide) return false;
   } else {
     const u32 zero = opaque_zero();
     if (early) {
@@ -726,7 +729,7 @@ __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
   // indexed streams: where their width bytes are is only known with the header.)
   const bool early = !IX && !a.ticketed;
   u32 tile = 0, ntiles = 0;
-  if (!open_reduce<IX>(a, false, c, wide, meta, early, tile, ntiles, &sh_tile)) return;
+  if (!open_reduce<IX>(a, false, false, c, wide, meta, early, tile, ntiles, &sh_tile)) return;
   if (IX && wide) reduce_wide_tile<true>(a, c, tile, ntiles, lds, sh_wave_total, &sh_base);
   else reduce_narrow_tile<IX>(a, c, tile, ntiles, meta, early, lds, sh_wave_total, &sh_base);
 }
@@ -742,7 +745,7 @@ __global__ __launch_bounds__(kTileThreads) void reduce_wide_kernel(ReduceArgs a)
   bool wide = false;
   OperandMeta meta{};
   u32 tile = 0, ntiles = 0;
-  if (!open_reduce<false>(a, true, c, wide, meta, false, tile, ntiles, &sh_tile)) return;
+  if (!open_reduce<false>(a, true, true, c, wide, meta, false, tile, ntiles, &sh_tile)) return;
   reduce_wide_tile<false>(a, c, tile, ntiles, lds, sh_wave_total, &sh_base);
 }
 

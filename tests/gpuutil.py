@@ -14,7 +14,8 @@ TICKETS = False          # tiles handed out by tickets
 # calls that take the stream variant only, and calls that also take the way tiles are handed out
 _READERS = {"zc_compress_bound", "zc_decompress", "zc_decompress_average", "zc_decompress_range", "zc_decompress_many",
             "zc_debug_block_offsets"}
-_WRITERS = {"zc_compress", "zc_compress_part", "zc_reduce_compressed", "zc_reduce_step", "zc_reduce_step_op"}
+_WRITERS = {"zc_compress", "zc_compress_part", "zc_reduce_compressed", "zc_reduce_compressed_op", "zc_reduce_step",
+            "zc_reduce_step_op"}
 
 
 def flags(writer=True):
@@ -110,13 +111,16 @@ def gpu_decompress(stream, n_cap, in_bytes=None, ws=None, average=False):
     return st, (d_out[:n].cpu().numpy() if st == _zc.binding.ZC_OK else None), n
 
 
-def gpu_reduce(streams, n, out_cap=None, ws=None):
+def gpu_reduce(streams, n, out_cap=None, ws=None, op=None):
     """-> (status, stream bytes, total_bytes)"""
     d_chunks = [to_dev(s) for s in streams]
     cap = zc.zc_compress_bound(n) if out_cap is None else out_cap
     d_out = torch.full((cap + 64,), 0x5A, dtype=torch.uint8, device=DEV)
     ws = workspace(max(n, 1), len(streams)) if ws is None else ws
-    st, total = zc.zc_reduce_compressed(d_chunks, [c.numel() for c in d_chunks], d_out, ws, out_cap=cap)
+    if op is None:
+        st, total = zc.zc_reduce_compressed(d_chunks, [c.numel() for c in d_chunks], d_out, ws, out_cap=cap)
+    else:
+        st, total = zc.zc_reduce_compressed_op(d_chunks, [c.numel() for c in d_chunks], op, d_out, ws, out_cap=cap)
     assert bool((d_out[cap:] == 0x5A).all()), "wrote past out_cap"
     torch.cuda.synchronize()
     return st, (d_out[: min(total, cap)].cpu().numpy() if st == _zc.binding.ZC_OK else None), total

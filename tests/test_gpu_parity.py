@@ -1171,3 +1171,62 @@ def test_infinity_under_a_huge_bound_is_nonfinite(zcref):
     st, s, _ = u.gpu_compress(x, eb)
     st_ref, s_ref, _ = zcref.compress(x, eb)
     assert st == st_ref and (s is None or s.tobytes() == s_ref.tobytes())
+
+
+@pytest.mark.parametrize("k,n,rel", [(1, TILE + 5, 1e-3), (2, 4 * TILE - 37, 1e-2), (3, 9 * 4096 + 1, 1e-4), (8, 16 * 4096, 1e-4),
+                                     (17, 3 * 4096 + 5, 1e-3), (64, 2 * TILE - 9, 1e-3)])
+def test_reduce_max_min_stream_matches_reference(zcref, k, n, rel):
+    """The k-way Max and Min of compressed operands, byte for byte; also against numpy's extreme compressed
+    once and against the ring of Max rounds, both on the GPU."""
+    u = _u()
+    xs, eb, _ = _rank_streams(zcref, k, (n + 4095) // 4096 * 4096, rel, seed0=90)
+    xs = [x[:n] for x in xs]
+    streams = [zcref.compress(x, eb)[1] for x in xs]
+    for op, extreme in ((zc.binding.ZC_OP_MAX, np.maximum), (zc.binding.ZC_OP_MIN, np.minimum)):
+        st_ref, r_ref, total_ref = zcref.reduce(streams, op=op)
+        st, r, total = u.gpu_reduce(streams, n, op=op)
+        assert st == st_ref == ZC_OK and total == total_ref
+        assert r.tobytes() == r_ref.tobytes(), u.first_diff(r, r_ref)
+        st, y, _ = u.gpu_decompress(r, n)
+        assert np.max(np.abs(y.astype(np.float64) - extreme.reduce(xs))) <= eb
+        if k <= 8:
+            ring = streams[0]
+            for x in xs[1:]:
+                st, ring, _ = u.gpu_reduce_step(ring, x, op=op)
+                assert st == ZC_OK
+            assert ring.tobytes() == r.tobytes()
+    # Sum through the same entry point is zc_reduce_compressed
+    st, r, _ = u.gpu_reduce(streams, n, op=zc.binding.ZC_OP_SUM)
+    assert st == ZC_OK and r.tobytes() == zcref.reduce(streams)[1].tobytes()
+
+
+def test_reduce_max_min_wide_blocks_and_errors(zcref):
+    u = _u()
+    rng = np.random.default_rng(12)
+    n = 3 * TILE + 77
+    scale = np.repeat(2.0 ** rng.integers(0, 27, (n + 31) // 32), 32)[:n]
+    qs = [(rng.uniform(-1, 1, n) * scale).astype(np.int32) for _ in range(4)]
+    qs.append(np.zeros(n, np.int32))                  # an all-constant operand
+    qs.append(qs[1].copy())                           # an operand twice
+    streams = [zcref.encode_codes(q, 1e-3)[1] for q in qs]
+    narrow = [zcref.encode_codes((q >> 14).astype(np.int32), 1e-3)[1] for q in qs]
+    for op in (zc.binding.ZC_OP_MAX, zc.binding.ZC_OP_MIN):
+        for ss in (streams, narrow, [streams[0]] + narrow[1:]):
+            st_ref, r_ref, total_ref = zcref.reduce(ss, op=op)
+            st, r, total = u.gpu_reduce(ss, n, op=op)
+            assert st == st_ref == ZC_OK and total == total_ref
+            assert r.tobytes() == r_ref.tobytes(), u.first_diff(r, r_ref)
+    # error paths follow the reference
+    op = zc.binding.ZC_OP_MAX
+    other = zcref.encode_codes(qs[0], 2e-3)[1]
+    assert u.gpu_reduce([streams[0], other], n, op=op)[0] == ZC_ERR_MISMATCH == zcref.reduce([streams[0], other], op=op)[0]
+    shorter = zcref.encode_codes(qs[0][:n - 1], 1e-3)[1]
+    assert u.gpu_reduce([streams[0], shorter], n, op=op)[0] == ZC_ERR_MISMATCH
+    bad = streams[1].copy(); bad[0] ^= 1
+    assert u.gpu_reduce([streams[0], bad], n, op=op)[0] == ZC_ERR_FORMAT == zcref.reduce([streams[0], bad], op=op)[0]
+    st, _, total = u.gpu_reduce(narrow, n, out_cap=4096, op=op)
+    assert st == ZC_ERR_CAPACITY and total == zcref.reduce(narrow, op=op)[2]
+    assert u.gpu_reduce(narrow, n, op=7)[0] == ZC_ERR_ARG
+    empty = [zcref.encode_codes(np.zeros(0, np.int32), 1e-3)[1]] * 3
+    st, r, _ = u.gpu_reduce(empty, 0, op=op)
+    assert st == ZC_OK and r.tobytes() == zcref.reduce(empty, op=op)[1].tobytes()
