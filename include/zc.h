@@ -247,6 +247,31 @@ int zc_reduce_compressed_op(const void* const* d_chunks, const size_t* chunk_byt
                             void* d_out, size_t out_cap, size_t* out_bytes,
                             void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
 
+/* The Sum of zc_reduce_compressed_ex and the round of zc_reduce_step_op done in parts (Section 3.5.2
+ * works on a buffer chunk by chunk inside the rounds of the collective, so that the codec runs on
+ * the chunks that have arrived while the others are still on their way): this call produces the
+ * values [first_value, first_value + count) of the result.  The parts of one result are given in
+ * ascending order, without gaps, to the same d_out and d_ws, on one HIP stream (or ordered by
+ * events), starting with first_value = 0, which also writes the header; first_value and count are
+ * multiples of 8192, except that the last part ends at n.  Indexed streams only (flags without
+ * ZC_STREAM_PLAIN).  Of every operand only the header, and the index entries, width bytes, outliers
+ * and payload of the part's segments are read, so an operand need not be complete beyond them;
+ * chunk_bytes are the operands' full sizes.  n (for the k-way form; n_local for the round) is what
+ * the parts are laid out for and must be the streams' n.  Between the parts the workspace must not
+ * be used for anything else.  After a part has run, the result's tables and payload up to its end are
+ * final, header and index describe a stream that can be read up to there (zc_decompress_range), and
+ * out_bytes (or zc_finish) tells how many bytes of the stream that is; after the last part the stream
+ * is the one the call in one piece writes.  Errors of all parts accumulate in the workspace.
+ * Errors: as the calls in one piece, and ARG for a part that is not as above. */
+int zc_reduce_compressed_part(const void* const* d_chunks, const size_t* chunk_bytes, int k, size_t n,
+                              size_t first_value, size_t count,
+                              void* d_out, size_t out_cap, size_t* out_bytes,
+                              void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
+int zc_reduce_step_part(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, int op,
+                        size_t first_value, size_t count,
+                        void* d_out, size_t out_cap, size_t* out_bytes,
+                        void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags);
+
 /* Quality of a reconstruction d_test against its original d_ref (n binary32 values each,
  * 16-byte aligned): the sums behind the paper's quality figures (NRMSE in Section 3.3, PSNR
  * and NRMSE in Section 4.6).  out4 (host, 4 doubles): max |ref - test|, sum of squared

@@ -21,7 +21,7 @@ ZC_STREAM_PLAIN, ZC_TILES_BY_TICKET = 1, 2
 EXPORTS = [
     "zc_compress_bound", "zc_compress_bound_ex", "zc_workspace_bytes", "zc_compress", "zc_compress_ex", "zc_compress_noalloc",
     "zc_compress_part", "zc_decompress", "zc_decompress_ex", "zc_decompress_many", "zc_reduce_compressed",
-    "zc_reduce_compressed_ex", "zc_reduce_compressed_op", "zc_reduce_step", "zc_reduce_step_op", "zc_decompress_average", "zc_decompress_range",
+    "zc_reduce_compressed_ex", "zc_reduce_compressed_op", "zc_reduce_compressed_part", "zc_reduce_step_part", "zc_reduce_step", "zc_reduce_step_op", "zc_decompress_average", "zc_decompress_range",
     "zc_quality", "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
     "zc_profile_enable", "zc_profile_collect",
 ]
@@ -60,6 +60,8 @@ def lib():
         L.zc_reduce_compressed.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_compressed_ex.argtypes = [C.POINTER(vp), szp, C.c_int, vp, sz, szp, vp, sz, vp, u]
         L.zc_reduce_compressed_op.argtypes = [C.POINTER(vp), szp, C.c_int, C.c_int, vp, sz, szp, vp, sz, vp, u]
+        L.zc_reduce_compressed_part.argtypes = [C.POINTER(vp), szp, C.c_int, sz, sz, sz, vp, sz, szp, vp, sz, vp, u]
+        L.zc_reduce_step_part.argtypes = [vp, sz, vp, sz, C.c_int, sz, sz, vp, sz, szp, vp, sz, vp, u]
         L.zc_reduce_step.argtypes = [vp, sz, vp, sz, vp, sz, szp, vp, sz, vp]
         L.zc_reduce_step_op.argtypes = [vp, sz, vp, sz, C.c_int, vp, sz, szp, vp, sz, vp, u]
         L.zc_decompress_average.argtypes = [vp, sz, vp, sz, szp, vp, sz, vp, u]
@@ -185,6 +187,30 @@ def zc_reduce_compressed_op(d_chunks, chunk_bytes, op, d_out, d_ws, sync=True, s
     cap = _size(d_out) if out_cap is None else out_cap
     st = lib().zc_reduce_compressed_op(ptrs, sizes, k, int(op), _p(d_out), cap, C.byref(nbytes) if sync else None, _p(d_ws),
                                        _size(d_ws), _stream(stream), int(flags))
+    return st, (nbytes.value if sync else None)
+
+
+def zc_reduce_compressed_part(d_chunks, chunk_bytes, n, first_value, count, d_out, d_ws, sync=True, stream=None, out_cap=None,
+                              flags=0):
+    """One part of a k-way Sum done in parts.  Returns (status, bytes of the stream final so far)."""
+    k = len(d_chunks)
+    ptrs = (C.c_void_p * max(k, 1))(*[t.data_ptr() for t in d_chunks])
+    sizes = (C.c_size_t * max(k, 1))(*[int(b) for b in chunk_bytes])
+    nbytes = C.c_size_t(0)
+    cap = _size(d_out) if out_cap is None else out_cap
+    st = lib().zc_reduce_compressed_part(ptrs, sizes, k, int(n), int(first_value), int(count), _p(d_out), cap,
+                                         C.byref(nbytes) if sync else None, _p(d_ws), _size(d_ws), _stream(stream), int(flags))
+    return st, (nbytes.value if sync else None)
+
+
+def zc_reduce_step_part(d_chunk, chunk_bytes, d_local, n_local, op, first_value, count, d_out, d_ws, sync=True, stream=None,
+                        out_cap=None, flags=0):
+    """One part of a ring round done in parts.  Returns (status, bytes of the stream final so far)."""
+    nbytes = C.c_size_t(0)
+    cap = _size(d_out) if out_cap is None else out_cap
+    st = lib().zc_reduce_step_part(_p(d_chunk), int(chunk_bytes), _p(d_local), int(n_local), int(op), int(first_value),
+                                   int(count), _p(d_out), cap, C.byref(nbytes) if sync else None, _p(d_ws), _size(d_ws),
+                                   _stream(stream), int(flags))
     return st, (nbytes.value if sync else None)
 
 

@@ -454,8 +454,11 @@ int zc_decompress_many(const void* const* d_chunks, const size_t* chunk_bytes, i
   return st;
 }
 
-int zc_reduce_compressed_op(const void* const* d_chunks, const size_t* chunk_bytes, int k, int op, void* d_out, size_t out_cap,
-                            size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
+// zc_reduce_compressed_op and zc_reduce_compressed_part.  ranged: the values [first_value, first_value + count)
+// of streams of n values, as one part of a reduce done in parts.
+static int reduce_impl(const void* const* d_chunks, const size_t* chunk_bytes, int k, int op, bool ranged, size_t n,
+                       size_t first_value, size_t count, void* d_out, size_t out_cap, size_t* out_bytes, void* d_ws,
+                       size_t ws_bytes, void* hip_stream, unsigned flags) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (!flags_valid(flags) || (op != ZC_OP_SUM && op != ZC_OP_MAX && op != ZC_OP_MIN)) return ZC_ERR_ARG;
   if (k < 1 || k > ZC_MAX_K || !d_chunks || !chunk_bytes || !d_out || !d_ws) return ZC_ERR_ARG;
@@ -501,6 +504,23 @@ int zc_reduce_compressed_op(const void* const* d_chunks, const size_t* chunk_byt
   ra.desc = l.desc;
   ra.ticketed = (flags & ZC_TILES_BY_TICKET) != 0;
   ra.nonce = nonce;
+  ra.first_tile = ra.end_tile = ra.adopt = 0;
+  ra.n_part = 0;
+  if (ranged) {
+    // parts are laid out in tiles of the reduce kernel; only indexed streams can be taken up in parts
+    if (!ix || op != ZC_OP_SUM || n > ZC_MAX_N || n == 0 || first_value % kTileValues != 0 || first_value >= n ||
+        count == 0 || count > n - first_value)
+      return ZC_ERR_ARG;
+    const bool to_the_end = first_value + count == n;
+    if (!to_the_end && count % kTileValues != 0) return ZC_ERR_ARG;
+    const u64 all_tiles = num_tiles(num_blocks(n));
+    if (all_tiles > l.tiles_cap) return ZC_ERR_ARG;
+    ra.first_tile = u32(first_value / kTileValues);
+    ra.end_tile = to_the_end ? u32(all_tiles) : u32((first_value + count) / kTileValues);
+    ra.adopt = first_value != 0;
+    ra.n_part = n;
+    tiles = ra.end_tile - ra.first_tile;
+  }
   if (op == ZC_OP_SUM) {
     launch_main(ZC_KERNEL_REDUCE, ix ? reduce_kernel<true> : reduce_kernel<false>, dim3(u32(tiles)), dim3(kTileThreads), stream, ra);
     // plain streams with blocks wider than 15 bits have a kernel of their own, which returns at once otherwise
@@ -520,9 +540,22 @@ int zc_reduce_compressed_op(const void* const* d_chunks, const size_t* chunk_byt
   return finish(d_ws, out_bytes, stream);
 }
 
+int zc_reduce_compressed_op(const void* const* d_chunks, const size_t* chunk_bytes, int k, int op, void* d_out, size_t out_cap,
+                            size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
+  return reduce_impl(d_chunks, chunk_bytes, k, op, false, 0, 0, 0, d_out, out_cap, out_bytes, d_ws, ws_bytes, hip_stream, flags);
+}
+
 int zc_reduce_compressed_ex(const void* const* d_chunks, const size_t* chunk_bytes, int k, void* d_out, size_t out_cap,
                             size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
-  return zc_reduce_compressed_op(d_chunks, chunk_bytes, k, ZC_OP_SUM, d_out, out_cap, out_bytes, d_ws, ws_bytes, hip_stream, flags);
+  return reduce_impl(d_chunks, chunk_bytes, k, ZC_OP_SUM, false, 0, 0, 0, d_out, out_cap, out_bytes, d_ws, ws_bytes, hip_stream,
+                     flags);
+}
+
+int zc_reduce_compressed_part(const void* const* d_chunks, const size_t* chunk_bytes, int k, size_t n, size_t first_value,
+                              size_t count, void* d_out, size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes,
+                              void* hip_stream, unsigned flags) {
+  return reduce_impl(d_chunks, chunk_bytes, k, ZC_OP_SUM, true, n, first_value, count, d_out, out_cap, out_bytes, d_ws, ws_bytes,
+                     hip_stream, flags);
 }
 
 int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes, int k, void* d_out, size_t out_cap,
@@ -530,14 +563,20 @@ int zc_reduce_compressed(const void* const* d_chunks, const size_t* chunk_bytes,
   return zc_reduce_compressed_ex(d_chunks, chunk_bytes, k, d_out, out_cap, out_bytes, d_ws, ws_bytes, hip_stream, 0);
 }
 
+static int step_impl(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, int op, bool ranged,
+                     size_t first_value, size_t count, void* d_out, size_t out_cap, size_t* out_bytes, void* d_ws,
+                     size_t ws_bytes, void* hip_stream, unsigned flags);
+
 int zc_reduce_step(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, void* d_out,
                    size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream) {
-  return zc_reduce_step_op(d_chunk, chunk_bytes, d_local, n_local, ZC_OP_SUM, d_out, out_cap, out_bytes, d_ws, ws_bytes,
-                           hip_stream, 0);
+  return step_impl(d_chunk, chunk_bytes, d_local, n_local, ZC_OP_SUM, false, 0, 0, d_out, out_cap, out_bytes, d_ws, ws_bytes,
+                   hip_stream, 0);
 }
 
-int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, int op, void* d_out,
-                      size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
+// zc_reduce_step_op and zc_reduce_step_part.
+static int step_impl(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, int op, bool ranged,
+                     size_t first_value, size_t count, void* d_out, size_t out_cap, size_t* out_bytes, void* d_ws,
+                     size_t ws_bytes, void* hip_stream, unsigned flags) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (!flags_valid(flags) || (op != ZC_OP_SUM && op != ZC_OP_MAX && op != ZC_OP_MIN)) return ZC_ERR_ARG;
   if (!d_chunk || !d_out || !d_ws || (n_local && !d_local) || n_local > ZC_MAX_N) return ZC_ERR_ARG;
@@ -571,6 +610,18 @@ int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_lo
   ta.desc = l.desc;
   ta.ticketed = (flags & ZC_TILES_BY_TICKET) != 0;
   ta.nonce = nonce;
+  ta.first_tile = ta.end_tile = ta.adopt = 0;
+  if (ranged) {
+    if (!ix || n_local == 0 || first_value % kTileValues != 0 || first_value >= n_local || count == 0 ||
+        count > n_local - first_value)
+      return ZC_ERR_ARG;
+    const bool to_the_end = first_value + count == n_local;
+    if (!to_the_end && count % kTileValues != 0) return ZC_ERR_ARG;
+    ta.first_tile = u32(first_value / kTileValues);
+    ta.end_tile = to_the_end ? u32(num_tiles(num_blocks(n_local))) : u32((first_value + count) / kTileValues);
+    ta.adopt = first_value != 0;
+    tiles = ta.end_tile - ta.first_tile;
+  }
   void (*kernel)(StepArgs) = nullptr;
   if (op == ZC_OP_SUM) kernel = ix ? step_kernel<true, ZC_OP_SUM> : step_kernel<false, ZC_OP_SUM>;
   else if (op == ZC_OP_MAX) kernel = ix ? step_kernel<true, ZC_OP_MAX> : step_kernel<false, ZC_OP_MAX>;
@@ -579,6 +630,19 @@ int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_lo
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;
   return finish(d_ws, out_bytes, stream);
+}
+
+int zc_reduce_step_op(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, int op, void* d_out,
+                      size_t out_cap, size_t* out_bytes, void* d_ws, size_t ws_bytes, void* hip_stream, unsigned flags) {
+  return step_impl(d_chunk, chunk_bytes, d_local, n_local, op, false, 0, 0, d_out, out_cap, out_bytes, d_ws, ws_bytes, hip_stream,
+                   flags);
+}
+
+int zc_reduce_step_part(const void* d_chunk, size_t chunk_bytes, const float* d_local, size_t n_local, int op,
+                        size_t first_value, size_t count, void* d_out, size_t out_cap, size_t* out_bytes, void* d_ws,
+                        size_t ws_bytes, void* hip_stream, unsigned flags) {
+  return step_impl(d_chunk, chunk_bytes, d_local, n_local, op, true, first_value, count, d_out, out_cap, out_bytes, d_ws, ws_bytes,
+                   hip_stream, flags);
 }
 
 int zc_quality(const float* d_ref, const float* d_test, size_t n, double* out4, void* d_ws, size_t ws_bytes,

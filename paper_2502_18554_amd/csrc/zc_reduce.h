@@ -42,6 +42,11 @@ struct ReduceArgs {
   u64* desc;
   u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
   u64 nonce;         // drawn by the host per call, goes into the call's tag (see launch_tag)
+  // A reduce done in parts (zc_reduce_compressed_part): this launch takes the tiles
+  // [first_tile, end_tile) of the output, end_tile = 0 meaning all of them; a later part
+  // (adopt) belongs to the call whose tag the first part left in the control block.
+  u32 first_tile, end_tile, adopt;
+  u64 n_part;        // a reduce done in parts: the n the caller laid the parts out for (the streams must have it); else 0
 };
 
 // What a workgroup knows about the call once the headers are judged.
@@ -50,6 +55,7 @@ struct ReduceCall {
   u64 tag;           // the call's tag
   u64 ltag;          // this launch's tag (tile tickets)
   u64 nsum;          // sum of the operands' nsum
+  u32 part_end;      // a reduce done in parts: one past the last tile of this part; else 0
 };
 
 // Header fields and table padding of the output stream; one thread.
@@ -114,7 +120,7 @@ __device__ inline void place_sum(const ReduceArgs& a, const ReduceCall& c, const
   }
   lds_barrier();                // the wave totals; the stores above stay in flight
   sum_wave_totals(sh_wave_total, wave, ix, pl);
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix, 0u, c.tag};
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix, c.part_end, c.tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) raise_status(a.ctl, c.tag, err);
   finish_tile<NW>(sink, word, pl, tile, ntiles, wl, sh_base, wave, lane);
@@ -167,7 +173,7 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ReduceCall& c
   }
   lds_barrier();                // the wave totals (and the words above); the stores stay in flight
   sum_wave_totals(sh_wave_total, wave, ix, pl);
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix, 0u, c.tag};
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix, c.part_end, c.tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) raise_status(a.ctl, c.tag, err);
   const TileBase tb = resolve_tile_base(sink, pl, tile, sh_base, wave, lane);
@@ -662,16 +668,22 @@ __device__ inline bool open_reduce(const ReduceArgs& a, bool for_wide, bool spli
   c.ltag = launch_tag(a.nonce, a.ctl);
   if (IX) {
     const StreamsVerdict v = judge_indexed_streams(a.in, a.k, true);
-    // (of a pair of kernels the narrow one is launched first and opens the call)
-    c.tag = call_tag(a.ctl, c.ltag, split && for_wide);
+    // (of a pair of kernels the narrow one is launched first and opens the call; a later part of a
+    //  reduce done in parts belongs to the call its first part opened)
+    const bool adopt = a.adopt != 0 || (split && for_wide);
+    c.tag = call_tag(a.ctl, c.ltag, adopt);
     c.h = v.h0;
     c.nsum = v.nsum;
     wide = v.wide;
     if (v.err) {
       if (blockIdx.x == 0 && threadIdx.x == 0 && !(split && for_wide)) {
-        a.ctl->result = 0;
+        if (!a.adopt) a.ctl->result = 0;
         raise_status(a.ctl, c.tag, v.err);
       }
+      return false;
+    }
+    if (a.n_part && a.n_part != c.h.n) {      // the parts were laid out for another n
+      if (blockIdx.x == 0 && threadIdx.x == 0) raise_status(a.ctl, c.tag, status_bit(ZC_ERR_MISMATCH));
       return false;
     }
     if (split && wide != for_wide) return false;
@@ -693,7 +705,9 @@ __device__ inline bool open_reduce(const ReduceArgs& a, bool for_wide, bool spli
     c.nsum = 0;
   }
   ntiles = u32(num_tiles(c.h.nb));
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
+  const u32 end_tile = a.end_tile && a.end_tile < ntiles ? a.end_tile : ntiles;
+  c.part_end = a.end_tile ? end_tile : 0u;
+  if (blockIdx.x == 0 && threadIdx.x == 0 && a.first_tile == 0) {
     if (!IX) c.nsum = a.ctl->nsum;           // of all operands, summed by the validation kernel
     write_reduce_header(a, c, ntiles, IX);
   }
@@ -702,13 +716,17 @@ __device__ inline bool open_reduce(const ReduceArgs& a, bool for_wide, bool spli
       raise_status(a.ctl, c.tag, status_bit(ZC_ERR_FORMAT));
     return false;
   }
-  tile = blockIdx.x;                         // tiles in the order in which workgroups start
+  if (a.first_tile >= end_tile) return false;
+  tile = a.first_tile + blockIdx.x;          // tiles in the order in which workgroups start
   if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
-    if (threadIdx.x == 0) *sh_tile = take_tile(a.ctl, c.ltag, ntiles, xcc_id());
+    if (threadIdx.x == 0) {
+      const u32 t = take_tile(a.ctl, c.ltag, end_tile - a.first_tile, xcc_id());
+      *sh_tile = t == kNoTile ? kNoTile : a.first_tile + t;
+    }
     __syncthreads();
     tile = uniform(*sh_tile);
   }
-  return tile < ntiles;
+  return tile < end_tile;
 }
 
 // Indexed streams: one launch per call, whatever the widths.  Plain streams: the common case;

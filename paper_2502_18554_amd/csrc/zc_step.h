@@ -50,6 +50,10 @@ struct StepArgs {
   u64* desc;
   u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
   u64 nonce;         // drawn by the host per call, goes into the call's tag (see launch_tag)
+  // A round done in parts (zc_reduce_step_part): this launch takes the tiles [first_tile, end_tile)
+  // of the output, end_tile = 0 meaning all of them; a later part (adopt) belongs to the call whose
+  // tag the first part left in the control block.
+  u32 first_tile, end_tile, adopt;
 };
 
 // LDS of one wave: 64 rows (blocks) of 16 local values + 4 words of padding (an odd number of
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   SegmentOffsetParts seg_parts{0, 0, 0};
   u32 w = 0, seg_end = 0;
   if (early) {
-    const u32 seg = blockIdx.x * kTileWaves + u32(wave);
+    const u32 seg = (a.first_tile + blockIdx.x) * kTileWaves + u32(wave);
     const u32 b = seg * kWaveBlocks + u32(lane);
     const u64 v0 = u64(seg) * kWaveBlocks * kBlockValues;
     const bool whole = v0 + u64(kWaveBlocks) * kBlockValues <= a.n_local;
@@ -308,10 +312,10 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   const u64 ltag = launch_tag(a.nonce, a.ctl);
   u64 tag;
   if (IX) {
-    tag = call_tag(a.ctl, ltag, false);
+    tag = call_tag(a.ctl, ltag, a.adopt != 0);
     if (!h.ok) {
       if (blockIdx.x == 0 && threadIdx.x == 0) {
-        a.ctl->result = 0;
+        if (!a.adopt) a.ctl->result = 0;
         raise_status(a.ctl, tag, status_bit(ZC_ERR_FORMAT));
       }
       return;
@@ -327,20 +331,25 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   }
   const u64 tend = tables_end(h.nb, IX);
   const u32 ntiles = u32(num_tiles(h.nb));
-  if (blockIdx.x == 0 && threadIdx.x == 0) write_step_header(a, h, tag, ntiles, IX);
+  if (blockIdx.x == 0 && threadIdx.x == 0 && a.first_tile == 0) write_step_header(a, h, tag, ntiles, IX);
   if (ntiles == 0) {                         // a stream without blocks: its one index entry must say so
     if (IX && blockIdx.x == 0 && wave == 0 && !index_ends_consistent(&a.in, 1, h, 0) && lane == 0)
       raise_status(a.ctl, tag, status_bit(ZC_ERR_FORMAT));
     return;
   }
+  const u32 end_tile = a.end_tile && a.end_tile < ntiles ? a.end_tile : ntiles;
+  if (a.first_tile >= end_tile) return;
 
-  u32 tile = blockIdx.x;                     // tiles in the order in which workgroups start
+  u32 tile = a.first_tile + blockIdx.x;      // tiles in the order in which workgroups start
   if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
-    if (threadIdx.x == 0) sh_tile = take_tile(a.ctl, ltag, ntiles, xcc_id());
+    if (threadIdx.x == 0) {
+      const u32 t = take_tile(a.ctl, ltag, end_tile - a.first_tile, xcc_id());
+      sh_tile = t == kNoTile ? kNoTile : a.first_tile + t;
+    }
     __syncthreads();
     tile = uniform(sh_tile);
   }
-  if (tile >= ntiles) return;
+  if (tile >= end_tile) return;
 
   const u32 seg = tile * kTileWaves + u32(wave);
   const bool seg_live = seg < num_segments(h.nb);
@@ -476,7 +485,7 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   if (lane == 0) sh_wave_total[wave] = pl.wave_total | (IX && pl.wmax > 15 ? kWaveWideMark : 0u);
   lds_barrier();                // the wave totals; the stores above stay in flight
   sum_wave_totals(sh_wave_total, wave, IX, pl);
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX, 0u, tag};
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX, a.end_tile ? end_tile : 0u, tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) raise_status(a.ctl, tag, err);
   const TileBase tb = resolve_tile_base(sink, pl, tile, &sh_base, wave, lane);

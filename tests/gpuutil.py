@@ -15,7 +15,7 @@ TICKETS = False          # tiles handed out by tickets
 _READERS = {"zc_compress_bound", "zc_decompress", "zc_decompress_average", "zc_decompress_range", "zc_decompress_many",
             "zc_debug_block_offsets"}
 _WRITERS = {"zc_compress", "zc_compress_part", "zc_reduce_compressed", "zc_reduce_compressed_op", "zc_reduce_step",
-            "zc_reduce_step_op"}
+            "zc_reduce_step_op", "zc_reduce_compressed_part", "zc_reduce_step_part"}
 
 
 def flags(writer=True):

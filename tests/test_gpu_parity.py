@@ -1230,3 +1230,91 @@ def test_reduce_max_min_wide_blocks_and_errors(zcref):
     empty = [zcref.encode_codes(np.zeros(0, np.int32), 1e-3)[1]] * 3
     st, r, _ = u.gpu_reduce(empty, 0, op=op)
     assert st == ZC_OK and r.tobytes() == zcref.reduce(empty, op=op)[1].tobytes()
+
+
+def _poison_beyond(stream, nb, end_block, off):
+    """A copy of an indexed stream in which everything that describes blocks from end_block on (index entries,
+    width bytes, outliers, payload) is overwritten: what a part that ends there must not look at."""
+    import gpuutil as u
+    s = stream.copy()
+    if end_block >= nb:
+        return s
+    nseg = (nb + 63) // 64
+    wb, te = u.widths_begin(nb), u.tables_end(nb)
+    ob = wb + u.pad16(nb)
+    first_seg = (end_block + 63) // 64 + 1          # the entry at the part's end is the end of its last segment
+    s[32 + 4 * first_seg:32 + 4 * (nseg + 1)] = 0xEE
+    s[wb + end_block:wb + nb] = 0xEE
+    s[ob + 4 * end_block:ob + 4 * nb] = 0xEE
+    s[te + int(off[end_block]):] = 0xEE
+    return s
+
+
+def test_reduce_and_ring_round_in_parts_match_reference(zcref, stream_variant):
+    """zc_reduce_compressed_part and zc_reduce_step_part: the parts add up, byte for byte, to the stream of the
+    call in one piece (the reference's), each part leaves a stream that can be read up to its end, and a part
+    looks at nothing of its operands beyond its own segments."""
+    u = _u()
+    n = 5 * TILE + 1000
+    k = 3
+    xs = [synth.power_law_field((n // 4096 + 1, 64, 64), seed=710 + i).numpy().ravel()[:n] for i in range(k)]
+    eb = synth.abs_bound(torch.from_numpy(xs[0]), 1e-3)
+    streams = [zcref.compress(x, eb)[1] for x in xs]
+    nb = (n + 31) // 32
+    cap = zc.zc_compress_bound(n)
+    d_out = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device=u.DEV)
+    ws = u.workspace(n, k)
+    d_streams = [u.to_dev(s) for s in streams]
+    sizes = [s.size for s in streams]
+    parts = [(0, TILE), (TILE, 2 * TILE), (3 * TILE, n - 3 * TILE)]
+    if stream_variant == "plain":              # plain streams cannot be taken up in parts
+        assert zc.zc_reduce_compressed_part(d_streams, sizes, n, 0, TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
+        assert zc.zc_reduce_step_part(d_streams[0], sizes[0], u.to_dev(xs[1]), n, 0, 0, TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
+        return
+    offs = [zcref.inspect(s)[3] for s in streams]
+    cases = [("sum", lambda: zcref.reduce(streams), None)]
+    for op in (zc.binding.ZC_OP_SUM, zc.binding.ZC_OP_MAX):
+        cases.append((f"round {op}", (lambda op=op: zcref.reduce_step(streams[0], xs[1], op=op)), op))
+    for name, reference, op in cases:
+        st_ref, r_ref, total_ref = reference()
+        assert st_ref == ZC_OK
+        off_r = zcref.inspect(r_ref)[3]
+        d_out.fill_(0xA5)
+        d_loc = u.to_dev(xs[1])
+        for first, count in parts:
+            end_block = (first + count + 31) // 32
+            poisoned = [u.to_dev(_poison_beyond(s, nb, end_block, o)) for s, o in zip(streams, offs)]
+            if op is None:
+                st, so_far = zc.zc_reduce_compressed_part(poisoned, sizes, n, first, count, d_out, ws, out_cap=cap)
+            else:
+                st, so_far = zc.zc_reduce_step_part(poisoned[0], sizes[0], d_loc, n, op, first, count, d_out, ws, out_cap=cap)
+            assert st == ZC_OK, (name, first)
+            want = u.tables_end(nb) + (int(off_r[end_block]) if end_block < nb else total_ref - u.tables_end(nb))
+            assert so_far == want, (name, first, so_far, want)
+            if first + count < n:                 # what exists so far can be read
+                part = torch.full((first + count,), float("nan"), dtype=torch.float32, device=u.DEV)
+                st, m = zc.zc_decompress_range(d_out, so_far, 0, first + count, part, u.workspace(n))
+                assert st == ZC_OK and m == first + count
+                assert np.array_equal(part.cpu().numpy().view(np.uint32), zcref.decompress(r_ref)[1][:first + count].view(np.uint32))
+        got = d_out[:total_ref].cpu().numpy()
+        assert so_far == total_ref and got.tobytes() == r_ref.tobytes(), (name, u.first_diff(got, r_ref))
+        assert bool((d_out[cap:] == 0xA5).all())
+    # the asynchronous form, one part that is everything, and parts that do not fit the rules
+    d_out.fill_(0x5A)
+    for first, count in parts:
+        assert zc.zc_reduce_compressed_part(d_streams, sizes, n, first, count, d_out, ws, sync=False, out_cap=cap)[0] == ZC_OK
+    st, total = zc.zc_finish(ws)
+    assert st == ZC_OK and d_out[:total].cpu().numpy().tobytes() == zcref.reduce(streams)[1].tobytes()
+    st, total = zc.zc_reduce_compressed_part(d_streams, sizes, n, 0, n, d_out, ws, out_cap=cap)
+    assert st == ZC_OK and d_out[:total].cpu().numpy().tobytes() == zcref.reduce(streams)[1].tobytes()
+    assert zc.zc_reduce_compressed_part(d_streams, sizes, n, 100, TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
+    assert zc.zc_reduce_compressed_part(d_streams, sizes, n, 0, 100, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
+    assert zc.zc_reduce_compressed_part(d_streams, sizes, n, 6 * TILE, TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
+    assert zc.zc_reduce_compressed_part(d_streams, sizes, n + 32, 0, TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_MISMATCH
+    assert zc.zc_reduce_step_part(d_streams[0], sizes[0], d_loc, n, 0, 0, 100, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
+    # an error in a middle part shows at the end
+    bad = xs[1].copy(); bad[TILE + 5] = np.nan
+    d_bad = u.to_dev(bad)
+    assert zc.zc_reduce_step_part(d_streams[0], sizes[0], d_bad, n, 0, 0, TILE, d_out, ws, out_cap=cap)[0] == ZC_OK
+    assert zc.zc_reduce_step_part(d_streams[0], sizes[0], d_bad, n, 0, TILE, TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_NONFINITE
+    assert zc.zc_reduce_step_part(d_streams[0], sizes[0], d_bad, n, 0, 2 * TILE, n - 2 * TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_NONFINITE
