@@ -89,6 +89,23 @@ __device__ inline void write_stream_header(u8* out, u64 n, u64 nb, u32 eb_bits, 
   for (u64 i = 4 * nb; i < pad16(4 * nb); ++i) ot[i] = 0;
 }
 
+// Copies `limit` staged words of a wave to dst with coalesced stores that each cover whole 128-byte
+// lines of memory (the first and the last line of the run aside): lane 0 of every store sits on a
+// line boundary, so a line is written by one instruction and not by the tail of one and the head of
+// the next.  The stores bypass the caches: a stream is on its way to another device, or to a later
+// call, and keeping it in cache lines would only push the write-back into the kernels that follow.
+// ROUNDS * 64 >= limit + 31.
+template <int ROUNDS>
+__device__ inline void copy_staged_words(const u32* wl, u32* dst, u32 limit, int lane) {
+  const u32 lead = u32(reinterpret_cast<uintptr_t>(dst) >> 2) & 31u;   // words of dst's line before dst
+#pragma unroll 4
+  for (u32 r = 0; r < u32(ROUNDS); ++r) {
+    if (64u * r >= limit + lead) break;        // uniform
+    const u32 i = u32(lane) + 64u * r - lead;  // wraps for the lanes ahead of dst: they sit out
+    if (i < limit) store_once(dst + i, wl[i]);
+  }
+}
+
 // Writes the payload words of the lanes of one half-wave to the wave's staging area and copies
 // them out with coalesced stores.  Word 0 is the sign word, word 1 + p is plane p; `word(i)`
 // yields word i from registers and is only ever called with compile-time constants.
@@ -104,12 +121,7 @@ __device__ inline void stage_and_copy_half(WordFn word, u32 w, bool in_half, u32
   }
   wave_lds_sync();
   const u32 limit = u64(half_total) < dst_room ? half_total : u32(dst_room);
-#pragma unroll
-  for (int r = 0; r < NW / 2; ++r) {
-    const u32 i = u32(lane) + 64u * u32(r);
-    if (64u * u32(r) >= limit) break;          // uniform
-    if (i < limit) dst[i] = wl[i];
-  }
+  copy_staged_words<NW / 2 + 1>(wl, dst, limit, lane);
   wave_lds_sync();
 }
 
@@ -212,12 +224,7 @@ __device__ inline void copy_wave_out_whole(const PayloadSink& s, WordFn word, co
   u32* const dst = reinterpret_cast<u32*>(s.out + tend) + d0;
   const u64 room = cap_words > d0 ? cap_words - d0 : 0;
   const u32 limit = u64(pl.wave_total) < room ? pl.wave_total : u32(room);
-#pragma unroll 4
-  for (u32 r = 0; r < u32(NW); ++r) {
-    const u32 i = u32(lane) + 64u * r;
-    if (64u * r >= limit) break;             // uniform
-    if (i < limit) dst[i] = wl[i];
-  }
+  copy_staged_words<NW + 1>(wl, dst, limit, lane);
   wave_lds_sync();
 }
 
@@ -229,7 +236,8 @@ __device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Plac
                                    u32* wl, u64* sh_base, int wave, int lane, MeanwhileFn meanwhile) {
   const TileBase tb = resolve_tile_base(s, pl, tile, sh_base, wave, lane, meanwhile);
   if (lane == 0) write_index_entry(s, tile * (blockDim.x >> 6) + u32(wave), tb.words + pl.wave_off);
-  copy_wave_out<NW>(s, word, pl, tb.words, wl, lane);
+  if constexpr (64 * NW <= kWaveStage) copy_wave_out_whole<NW>(s, word, pl, tb.words, wl, lane);
+  else copy_wave_out<NW>(s, word, pl, tb.words, wl, lane);
   finish_stream(s, pl, tile, ntiles, tb);
 }
 
