@@ -344,22 +344,24 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
 
     // ---- fields -> sign + plane words in registers, then the back half ----
     if (tile_wmax <= 15) {
-      u32 pw[16];          // pw[0] = sign, pw[1 + p] = plane p
-      if (pl.wmax <= 7) {
-        u32 r[8];
-        planes8_from_fields16(bf.f, r);
-        pw[0] = r[7];
+      finish_staged_tile<16>(sink, pl, tile, ntiles, wl, &sh_base, wave, lane, [&] {
+        u32 pw[16];          // pw[0] = sign, pw[1 + p] = plane p
+        if (pl.wmax <= 7) {
+          u32 r[8];
+          planes8_from_fields16(bf.f, r);
+          pw[0] = r[7];
 #pragma unroll
-        for (int p = 0; p < 7; ++p) pw[1 + p] = r[p];
+          for (int p = 0; p < 7; ++p) pw[1 + p] = r[p];
 #pragma unroll
-        for (int p = 8; p < 16; ++p) pw[p] = 0;
-      } else {
-        planes16_from_fields(bf.f);
-        pw[0] = bf.f[15];
+          for (int p = 8; p < 16; ++p) pw[p] = 0;
+        } else {
+          planes16_from_fields(bf.f);
+          pw[0] = bf.f[15];
 #pragma unroll
-        for (int p = 0; p < 15; ++p) pw[1 + p] = bf.f[p];
-      }
-      finish_tile<16>(sink, [&](auto i) { return pw[decltype(i)::value]; }, pl, tile, ntiles, wl, &sh_base, wave, lane);
+          for (int p = 0; p < 15; ++p) pw[1 + p] = bf.f[p];
+        }
+        stage_wave_words<16>([&](auto i) { return pw[decltype(i)::value]; }, pl, wl);
+      });
     } else {
       wide_tile<FULL>(a, sink, pl, tile, ntiles, wblock0, wl, &sh_base, wave, lane);
     }

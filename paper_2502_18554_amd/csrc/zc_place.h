@@ -207,16 +207,22 @@ __device__ inline void copy_wave_out(const PayloadSink& s, WordFn word, const Pl
   }
 }
 
-// The same in one pass, for a wave whose whole payload fits its staging area (64 * NW words): every
-// lane writes its block's words once, and the copy-out is a plain LDS-to-memory copy of the wave's words.
+// The same in one pass, for a wave whose whole payload fits its staging area (64 * NW words), in two
+// steps.  First every lane writes its block's words to the staging area at the block's offset inside
+// the wave: this needs no base offset, so it can be done while the look-back is under way.
 template <int NW, typename WordFn>
-__device__ inline void copy_wave_out_whole(const PayloadSink& s, WordFn word, const Placement& pl, u64 base, u32* wl, int lane) {
+__device__ inline void stage_wave_words(WordFn word, const Placement& pl, u32* wl) {
   if (pl.w) {
     wl[pl.off_in_wave] = word(std::integral_constant<int, 0>{});
     [&]<int... P>(std::integer_sequence<int, P...>) {
       ((u32(P) < pl.w ? void(wl[pl.off_in_wave + 1 + P] = word(std::integral_constant<int, 1 + P>{})) : void()), ...);
     }(std::make_integer_sequence<int, NW - 1>{});
   }
+}
+
+// Then the copy-out is a plain LDS-to-memory copy of the wave's words.
+template <int NW>
+__device__ inline void copy_staged_wave(const PayloadSink& s, const Placement& pl, u64 base, u32* wl, int lane) {
   wave_lds_sync();
   const u64 tend = tables_end(s.nb, s.ix);
   const u64 cap_words = s.out_cap > tend ? (s.out_cap - tend) / 4 : 0;
@@ -228,16 +234,28 @@ __device__ inline void copy_wave_out_whole(const PayloadSink& s, WordFn word, co
   wave_lds_sync();
 }
 
-// Back half of a tile once the plane words sit in registers (`word(i)`: 0 = sign, 1 + p =
-// plane p) and its size is published: look back for the base offset, then move the payload
-// out.  Called by every wave of the workgroup; one barrier.
+// Back half of a tile whose size is published: look back for the base offset, then move the
+// payload out.  Called by every wave of the workgroup; one barrier.  `make_words()` runs while the
+// look-back's first poll is on its way and leaves the wave's words in its staging area (see
+// stage_wave_words): whatever turns the tile's codes into plane words belongs there.
+template <int NW, typename MakeWordsFn>
+__device__ inline void finish_staged_tile(const PayloadSink& s, const Placement& pl, u32 tile, u32 ntiles, u32* wl,
+                                          u64* sh_base, int wave, int lane, MakeWordsFn make_words) {
+  static_assert(64 * NW <= kWaveStage, "a wave of widest blocks must fit the staging area");
+  const TileBase tb = resolve_tile_base(s, pl, tile, sh_base, wave, lane, make_words);
+  if (lane == 0) write_index_entry(s, tile * (blockDim.x >> 6) + u32(wave), tb.words + pl.wave_off);
+  copy_staged_wave<NW>(s, pl, tb.words, wl, lane);
+  finish_stream(s, pl, tile, ntiles, tb);
+}
+
+// The same with the plane words in registers (`word(i)`: 0 = sign, 1 + p = plane p), for waves
+// whose payload need not fit the staging area at once.
 template <int NW, typename WordFn, typename MeanwhileFn>
 __device__ inline void finish_tile(const PayloadSink& s, WordFn word, const Placement& pl, u32 tile, u32 ntiles,
                                    u32* wl, u64* sh_base, int wave, int lane, MeanwhileFn meanwhile) {
   const TileBase tb = resolve_tile_base(s, pl, tile, sh_base, wave, lane, meanwhile);
   if (lane == 0) write_index_entry(s, tile * (blockDim.x >> 6) + u32(wave), tb.words + pl.wave_off);
-  if constexpr (64 * NW <= kWaveStage) copy_wave_out_whole<NW>(s, word, pl, tb.words, wl, lane);
-  else copy_wave_out<NW>(s, word, pl, tb.words, wl, lane);
+  copy_wave_out<NW>(s, word, pl, tb.words, wl, lane);
   finish_stream(s, pl, tile, ntiles, tb);
 }
 

@@ -183,12 +183,7 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ReduceCall& c
   u32* const dst = reinterpret_cast<u32*>(a.out + tend) + d0;
   const u64 room = cap_words > d0 ? cap_words - d0 : 0;
   const u32 limit = u64(pl.wave_total) < room ? pl.wave_total : u32(room);
-#pragma unroll 4
-  for (u32 r = 0; r < u32(NW); ++r) {
-    const u32 i = u32(lane) + 64u * r;
-    if (64u * r >= limit) break;             // uniform
-    if (i < limit) store_once(dst + i, wl[i]);
-  }
+  copy_staged_words<NW + 1>(wl, dst, limit, lane);
   wave_lds_sync();
   finish_stream(sink, pl, tile, ntiles, tb);
 }

@@ -76,16 +76,20 @@ __device__ inline void place_codes(const ReduceArgs& a, const ReduceCall& c, i32
   const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX, 0u, c.tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) raise_status(a.ctl, c.tag, err);
-  const TileBase tb = resolve_tile_base(sink, pl, tile, sh_base, wave, lane);
-  if (lane == 0) write_index_entry(sink, tile * kTileWaves + u32(wave), tb.words + pl.wave_off);
-  if (!WIDE || pl.wmax <= 15) {
+  const bool narrow = !WIDE || pl.wmax <= 15;
+  const TileBase tb = resolve_tile_base(sink, pl, tile, sh_base, wave, lane, [&] {
+    if (!narrow) return;
     u32 pw[16];
     planes_from_deltas16(q, pw);
-    copy_wave_out_whole<16>(sink, [&](auto i) {
+    stage_wave_words<16>([&](auto i) {
       constexpr int I = decltype(i)::value;          // 0: sign, 1 + p: plane p
       if constexpr (I == 0) return pw[15];
       else return pw[I - 1];
-    }, pl, tb.words, wl, lane);
+    }, pl, wl);
+  });
+  if (lane == 0) write_index_entry(sink, tile * kTileWaves + u32(wave), tb.words + pl.wave_off);
+  if (narrow) {
+    copy_staged_wave<16>(sink, pl, tb.words, wl, lane);
   } else {
     u32 plo[16], phi[16];
     planes_from_deltas32(q, plo, phi);

@@ -488,12 +488,9 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX, a.end_tile ? end_tile : 0u, tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) raise_status(a.ctl, tag, err);
-  const TileBase tb = resolve_tile_base(sink, pl, tile, &sh_base, wave, lane);
-  const u64 base = tb.words;
-  if (lane == 0) write_index_entry(sink, seg, base + pl.wave_off);
-
-  // ---- the new deltas as sign + plane words, out ----
-  if (!slow) {
+  // ---- the new deltas as sign + plane words into the staging area, while the look-back is under way ----
+  const TileBase tb = resolve_tile_base(sink, pl, tile, &sh_base, wave, lane, [&] {
+    if (slow) return;
     u32 pw[16];          // pw[0] = sign, pw[1 + p] = plane p
     if (pl.wmax <= 7) {
       // four 8-bit fields per word: word j = values j, j + 8 (word j of nf), j + 16, j + 24 (word j + 8)
@@ -513,7 +510,14 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
 #pragma unroll
       for (int p = 0; p < 15; ++p) pw[1 + p] = swap_middle_bytes(nf[p]);
     }
-    copy_wave_out_whole<16>(sink, [&](auto i) { return pw[decltype(i)::value]; }, pl, base, wl, lane);
+    stage_wave_words<16>([&](auto i) { return pw[decltype(i)::value]; }, pl, wl);
+  });
+  const u64 base = tb.words;
+  if (lane == 0) write_index_entry(sink, seg, base + pl.wave_off);
+
+  // ---- out ----
+  if (!slow) {
+    copy_staged_wave<16>(sink, pl, base, wl, lane);
   } else {
     const u64 cap_words = a.out_cap > tend ? (a.out_cap - tend) / 4 : 0;
     u32 ignored = 0;
