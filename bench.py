@@ -52,11 +52,17 @@ def parse():
                     help="untimed steps run for this long before the warmup steps: the first milliseconds of work on an "
                          "idle GPU run several percent slow")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the untimed sweep over the other error bounds")
+    ap.add_argument("--extras", choices=("all", "none", "ring"), default="all",
+                    help="the untimed measurements after the timed step: all of them, none, or only the ring round and "
+                         "the k-way Max (what a profile of those two kernels needs)")
+    ap.add_argument("--no-extras", action="store_true", help="the same as --extras none")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run plain device copies of the field (4n B read + 4n B written each): the known "
                          "traffic that calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.no_extras:
+        args.extras = "none"
+    return args
 
 
 def source_digest():
@@ -226,7 +232,7 @@ def main():
     torch.cuda.synchronize()
     kernel_ms = kernel_averages(zc.zc_profile_collect())
     kernel_ms[dominant] = sum(ms for _, ms in timed_records) / len(timed_records)
-    # the decompression of the stream that the compression has just written (found in the memory-side cache)
+    # the decompression of the stream that the compression of the same step has just written
     for i in range(args.steps):
         step(rotate=False)
     torch.cuda.synchronize()
@@ -252,9 +258,9 @@ def main():
             "algorithmic_bytes": alg_bytes[s],
         }
     stages["decompress"]["input"] = f"cold: the stream was written {ROTATION - 1} steps earlier"
-    stages["decompress"]["warm"] = {"kernel_ms": round(warm_ms, 4),
-                                    "frac": round(alg_bytes["decompress"] / warm_ms / 1e6 / HBM_PEAK_GBS, 4),
-                                    "input": "the stream the compression has just written (memory-side cache)"}
+    stages["decompress"]["just_written"] = {"kernel_ms": round(warm_ms, 4),
+                                            "frac": round(alg_bytes["decompress"] / warm_ms / 1e6 / HBM_PEAK_GBS, 4),
+                                            "input": "the stream the compression of the same step has just written"}
     total_fp32 = sum(fp32_bytes.values())
     total_alg = sum(alg_bytes.values())
     value = total_fp32 / ms_per_step / 1e6
@@ -272,7 +278,7 @@ def main():
 
     # ---------------- untimed extras ----------------
     extras = {}
-    if not args.no_extras:
+    if args.extras == "all":
         # the three error bounds of the 512^3 configuration; the decompression reads a stream written four
         # compressions earlier (cold, as in the step)
         for rel in (1e-2, 1e-3, 1e-4):
@@ -405,6 +411,7 @@ def main():
         check(st, "decompress_many extra")
         extras["decompress_many"] = res
         del outs, ws_k
+    if args.extras in ("all", "ring"):
         # one round of the ring reduce-scatter at the shape of the reduce above: the received
         # stream of rank 0 plus the uncompressed buffer of rank 1 -> stream of the sums
         st, s_bytes = zc.zc_reduce_step(chunks[0], chunk_bytes[0], ranks[1], m, scratch, ws_r, flags=flags)
@@ -439,6 +446,45 @@ def main():
         ms_max = timed(lambda: ring_round(zc.binding.ZC_OP_MAX))
         st, _ = zc.zc_finish(ws_r)
         check(st, "reduce_step_op extra")
+        # k-way Max of the same compressed rank buffers (Section 3.2), and the k-way Sum and the ring
+        # round each done in 4 parts of whole tiles, as a pipeline over a collective's chunks would
+        d_red_alt = u8(zc.zc_compress_bound(m, variant))
+        st, x_bytes = zc.zc_reduce_compressed_op(chunks, chunk_bytes, zc.binding.ZC_OP_MAX, d_red_alt, ws_r, flags=flags)
+        check(st, "reduce_compressed_op extra")
+        ms_kmax = timed(lambda: zc.zc_reduce_compressed_op(chunks, chunk_bytes, zc.binding.ZC_OP_MAX, d_red_alt, ws_r,
+                                                           sync=False, flags=flags))
+        st, _ = zc.zc_finish(ws_r)
+        check(st, "reduce_compressed_op extra")
+        quarter = m // 4
+
+        def sum_in_parts():
+            for i in range(4):
+                zc.zc_reduce_compressed_part(chunks, chunk_bytes, m, i * quarter, quarter if i < 3 else m - 3 * quarter,
+                                             d_red_alt, ws_r, sync=False, flags=flags)
+
+        def round_in_parts():
+            for i in range(4):
+                zc.zc_reduce_step_part(chunks[0], chunk_bytes[0], ranks[1], m, zc.binding.ZC_OP_SUM, i * quarter,
+                                       quarter if i < 3 else m - 3 * quarter, scratch, ws_r, sync=False, flags=flags)
+
+        parts = None
+        if quarter % 8192 == 0:
+            ms_sum_parts = timed(sum_in_parts)
+            st, b_sum_parts = zc.zc_finish(ws_r)
+            check(st, "reduce_compressed_part extra")
+            assert b_sum_parts == r_bytes and torch.equal(d_red_alt[:r_bytes], d_red[:r_bytes]), "parts != whole (Sum)"
+            ms_round_parts = timed(round_in_parts)
+            st, b_round_parts = zc.zc_finish(ws_r)
+            check(st, "reduce_step_part extra")
+            assert b_round_parts == s_bytes
+            parts = {"reduce_in_4_parts_ms": round(ms_sum_parts, 4), "ring_round_in_4_parts_ms": round(ms_round_parts, 4)}
+        alg_kmax = sum(chunk_bytes) + x_bytes
+        extras["reduce_max"] = {"workload": f"k-way Max of the {K} compressed rank buffers", "ms": round(ms_kmax, 4),
+                                "algorithmic_bytes": alg_kmax, "call_frac": round(alg_kmax / ms_kmax / 1e6 / HBM_PEAK_GBS, 4)}
+        if parts:
+            extras["in_parts"] = parts
+        extras["reduce_step"]["max_ms"] = round(ms_max, 4)
+    if args.extras == "all":
         d_avg = torch.empty(m, dtype=torch.float32, device=dev)      # (d_y keeps the field for the cross-check below)
         ms_avg = timed(lambda: zc.zc_decompress_average(d_red, r_bytes, d_avg, ws_d, sync=False, flags=variant))
         st, n_avg = zc.zc_finish(ws_d)
@@ -466,8 +512,7 @@ def main():
             check(st, "decompress_range extra")
             assert float((d_y.double() - x.double()).abs().max()) <= eb, "chunks do not add up to the field"
             extras["pipelined"] = {"compress_in_8_parts_ms": round(ms_parts, 4), "decompress_in_8_chunks_ms": round(ms_chunks, 4)}
-        extras["other_ops"] = {"reduce_step_max_ms": round(ms_max, 4),
-                               "decompress_average": {"ms": round(ms_avg, 4), "values": n_avg,
+        extras["other_ops"] = {"decompress_average": {"ms": round(ms_avg, 4), "values": n_avg,
                                                       "call_frac": round((r_bytes + 4 * m) / ms_avg / 1e6 / HBM_PEAK_GBS, 4)}}
 
     # ---------------- reference CPU codec on the same buffers (same mix as the step) ----------------
