@@ -76,10 +76,11 @@ def source_digest():
     return h.hexdigest()[:16]
 
 
-def profiled_traffic(workload_key):
-    """HBM bytes per launch of the main kernels from the rocprofv3 counter runs summarised in
-    profiles/traffic.json (counters cannot be read from inside this script), or {} when that file
-    was taken on other kernel sources or another workload."""
+def profiled(workload_key):
+    """What the rocprofv3 counter runs summarised in profiles/traffic.json say about the main kernels of this
+    workload (counters cannot be read from inside this script): HBM bytes per launch (`traffic_bytes`) and VALU
+    instructions per launch (`valu_instructions`); {} when that file was taken on other kernel sources or
+    another workload."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         rec = json.load(open(path))
@@ -88,7 +89,15 @@ def profiled_traffic(workload_key):
     entry = rec.get(workload_key)
     if not entry or entry.get("source_digest") != source_digest():
         return {}
-    return entry.get("traffic_bytes", {})
+    return entry
+
+
+def valu_frac(instructions, kernel_ms):
+    """Share of the kernel's duration that its VALU instructions need to issue: a wave64 instruction holds
+    the 16 lanes of its SIMD for 4 cycles, there are 256 x 4 SIMDs, and the clock is 2.4 GHz."""
+    if not instructions:
+        return None
+    return round(instructions * 4 / (1024 * 2.4e9) / (kernel_ms * 1e-3), 4)
 
 
 def main():
@@ -243,7 +252,9 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     stage_ms = {s: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, s in enumerate(stage_names)}
     workload_key = f"{side}^3 rel {args.rel:g} + reduce {K}x{m}, {args.streams} streams, tiles {args.tiles}"
-    traffic = profiled_traffic(workload_key)
+    counters = profiled(workload_key)
+    traffic = counters.get("traffic_bytes", {})
+    valu = counters.get("valu_instructions", {})
     stages = {}
     for s in stage_names:
         # roofline = the main kernel alone; ms / call_frac = the whole call (on plain streams: the kernels ahead of it too)
@@ -255,6 +266,7 @@ def main():
             "kernel_ms": round(kernel_ms[s], 4),
             "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic.get(s)},
+            "valu_frac": valu_frac(valu.get(s), kernel_ms[s]),
             "algorithmic_bytes": alg_bytes[s],
         }
     stages["decompress"]["input"] = f"cold: the stream was written {ROTATION - 1} steps earlier"
@@ -440,6 +452,7 @@ def main():
                                  "algorithmic_bytes": alg, "fp32_GBps": round(8 * m / ms / 1e6, 1),
                                  "hbm_frac": round(alg / k_ms / 1e6 / HBM_PEAK_GBS, 4),
                                  "call_frac": round(alg / ms / 1e6 / HBM_PEAK_GBS, 4),
+                                 "valu_frac": valu_frac(valu.get("reduce_step"), k_ms),
                                  "traffic": traffic.get("reduce_step")}
         # the other aggregation functions: a Max round at the same shape, and the averaging
         # decompression of the reduced stream of the step above
@@ -480,7 +493,8 @@ def main():
             parts = {"reduce_in_4_parts_ms": round(ms_sum_parts, 4), "ring_round_in_4_parts_ms": round(ms_round_parts, 4)}
         alg_kmax = sum(chunk_bytes) + x_bytes
         extras["reduce_max"] = {"workload": f"k-way Max of the {K} compressed rank buffers", "ms": round(ms_kmax, 4),
-                                "algorithmic_bytes": alg_kmax, "call_frac": round(alg_kmax / ms_kmax / 1e6 / HBM_PEAK_GBS, 4)}
+                                "algorithmic_bytes": alg_kmax, "call_frac": round(alg_kmax / ms_kmax / 1e6 / HBM_PEAK_GBS, 4),
+                                "valu_frac": valu_frac(valu.get("reduce_max"), ms_kmax)}
         if parts:
             extras["in_parts"] = parts
         extras["reduce_step"]["max_ms"] = round(ms_max, 4)

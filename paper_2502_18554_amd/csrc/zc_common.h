@@ -303,9 +303,10 @@ __device__ inline u32 status_bits(const Control* ctl, u64 tag) {
 // (times of the three kernels inside one loop): the input values of the compression (-21 us
 // for it, +15 us for the kernel after it), the floats the decompression writes (-27 us for
 // it, nothing lost elsewhere), the payload loads of the reduce (-23 us; they read several
-// streams side by side) and the payload it writes (-14 us).  It costs time on the payload the
-// compression writes (the decompression that follows finds it in the memory-side cache
-// otherwise) and on the payload and outlier loads of the decompression.
+// streams side by side), the payload it writes (-14 us), and the payload the compression writes
+// (nothing for it once every store covers whole lines, see copy_staged_words; -17 us and -5 us
+// for the two kernels after it, measured with the decompression reading a stream that is no
+// longer in any cache).  It costs time on the payload and outlier loads of the decompression.
 __device__ inline uint4 load_once(const uint4* p) {
   const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(t.x, t.y, t.z, t.w);
