@@ -403,7 +403,6 @@ constexpr u64 kDescTagMask = ((u64(1) << 29) - 1) << 32;
 // Descriptors are polled by every tile in flight, so neighbours must not share a memory
 // line (polls of one line queue up behind each other): one descriptor per 128 bytes.
 constexpr int kDescStride = 16;            // in u64
-__host__ __device__ inline u64 desc_slot(u64 tile) { return tile * kDescStride; }
 
 // Both words travel in one 16-byte access (a hot line serves its requests one after the other,
 // so a second access per poll or publication would double the time the look-back chain takes),
