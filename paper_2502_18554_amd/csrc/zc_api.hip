@@ -231,6 +231,14 @@ void* scratch_of_current_device() {
 
 }  // namespace
 
+namespace {
+template <int OP>
+void (*pick_step_kernel(bool ix, bool tickets))(StepArgs) {
+  if (ix) return tickets ? step_kernel<true, OP, true> : step_kernel<true, OP, false>;
+  return tickets ? step_kernel<false, OP, true> : step_kernel<false, OP, false>;
+}
+}  // namespace
+
 extern "C" {
 
 size_t zc_compress_bound_ex(size_t n, unsigned flags) {
@@ -623,9 +631,10 @@ static int step_impl(const void* d_chunk, size_t chunk_bytes, const float* d_loc
     tiles = ta.end_tile - ta.first_tile;
   }
   void (*kernel)(StepArgs) = nullptr;
-  if (op == ZC_OP_SUM) kernel = ix ? step_kernel<true, ZC_OP_SUM> : step_kernel<false, ZC_OP_SUM>;
-  else if (op == ZC_OP_MAX) kernel = ix ? step_kernel<true, ZC_OP_MAX> : step_kernel<false, ZC_OP_MAX>;
-  else kernel = ix ? step_kernel<true, ZC_OP_MIN> : step_kernel<false, ZC_OP_MIN>;
+  const bool tickets = ta.ticketed != 0;
+  if (op == ZC_OP_SUM) kernel = pick_step_kernel<ZC_OP_SUM>(ix, tickets);
+  else if (op == ZC_OP_MAX) kernel = pick_step_kernel<ZC_OP_MAX>(ix, tickets);
+  else kernel = pick_step_kernel<ZC_OP_MIN>(ix, tickets);
   launch_main(ZC_KERNEL_REDUCE_STEP, kernel, dim3(u32(tiles)), dim3(kTileThreads), stream, ta);
   if (!launch_ok()) return ZC_ERR_HIP;
   if (!out_bytes) return ZC_OK;

@@ -39,38 +39,55 @@ struct DecompressArgs {
 // with the loads of the tables; a segment whose widths add up to another figure, a width above
 // 31, or one above 15 in a stream that promised none (!may_be_wide) make the stream malformed
 // (`err`), and nothing of the segment's payload is used.
+constexpr int kWaveStageLoads = 4;
 struct WaveStage {
-  uint4 v[5];
+  uint4 v[kWaveStageLoads];
 };
 
 // The copy starts at the 16-byte boundary at or below the segment (the payload area itself is
 // 16-byte aligned) and keeps that misalignment in LDS, so it moves 16 bytes per lane and
 // instruction, all loads in flight together.  span = words to bring in, <= 1027.
-__device__ inline WaveStage load_wave_stage(const u32* payload, u64 payload_words, u64 src0, u32 span, int lane) {
+// Four loads cover 1024 words; only whole 16-byte pieces are asked for here: the up to three
+// words beyond (a wave whose 64 blocks are all 15 bits wide, off the 16-byte grid) and the
+// last words of a stream that do not fill a piece are fetched by store_wave_stage.  The loads
+// are written without any branch: a lane with nothing to fetch reads the 16 bytes at `safe`
+// (the stream's header) instead.  (With a branch around a load and a zero on its other side,
+// or with the stream's last words fetched into single components of the same registers, the
+// compiler copied a component after every 16-byte load and waited for the load to do so: the
+// loads went out one round trip after the other.)
+__device__ inline WaveStage load_wave_stage(const u32* payload, u64 payload_words, u64 src0, u32 span, int lane,
+                                            const uint4* safe) {
   WaveStage st;
 #pragma unroll
-  for (int i = 0; i < 5; ++i) {
+  for (int i = 0; i < kWaveStageLoads; ++i) {
     const u32 idx = 4u * u32(lane) + 256u * u32(i);
-    st.v[i] = make_uint4(0, 0, 0, 0);
-    if (idx < span) {
-      if (src0 + idx + 4 <= payload_words) {
-        st.v[i] = *reinterpret_cast<const uint4*>(payload + src0 + idx);
-      } else {                                       // the last words of the stream
-        const u64 left = payload_words - (src0 + idx);
-        st.v[i].x = payload[src0 + idx];
-        if (left > 1) st.v[i].y = payload[src0 + idx + 1];
-        if (left > 2) st.v[i].z = payload[src0 + idx + 2];
-      }
-    }
+    const bool piece = idx < span && src0 + idx + 4 <= payload_words;
+    st.v[i] = *(piece ? reinterpret_cast<const uint4*>(payload + src0 + idx) : safe);
   }
   return st;
 }
 
-__device__ inline void store_wave_stage(const WaveStage& st, u32 span, u32* wl, int lane) {
+__device__ inline void store_wave_stage(const WaveStage& st, const u32* payload, u64 payload_words, u64 src0, u32 span,
+                                        u32* wl, int lane) {
 #pragma unroll
-  for (int i = 0; i < 5; ++i) {
+  for (int i = 0; i < kWaveStageLoads; ++i) {
     const u32 idx = 4u * u32(lane) + 256u * u32(i);
     if (idx < span) *reinterpret_cast<uint4*>(wl + idx) = st.v[i];
+  }
+  const u32 staged = span < 256u * kWaveStageLoads ? span : 256u * kWaveStageLoads;
+  if (src0 + ((u64(staged) + 3) & ~u64(3)) > payload_words) {    // uniform: the wave that holds the end of the stream
+#pragma unroll
+    for (int i = 0; i < kWaveStageLoads; ++i) {
+      const u32 idx = 4u * u32(lane) + 256u * u32(i);
+      if (idx < span && src0 + idx + 4 > payload_words) {
+        for (u32 j = 0; j < 3; ++j)
+          if (src0 + idx + j < payload_words) wl[idx + j] = payload[src0 + idx + j];
+      }
+    }
+  }
+  if (span > 256u * kWaveStageLoads) {                           // uniform, and rare: words 1024 .. 1026
+    const u32 idx = 256u * kWaveStageLoads + u32(lane);
+    if (idx < span && src0 + idx < payload_words) wl[idx] = payload[src0 + idx];
   }
 }
 
@@ -85,7 +102,7 @@ struct WavePayload {
 // First half of wave_block_words: scan of the widths, the checks, and the staged copy of the
 // segment's payload into `wl` when no block is wider than 15 bits.
 __device__ inline WavePayload stage_wave_payload(const u32* payload, u64 payload_words, u32 w, u64 seg_off, u32* wl, int lane,
-                                                 bool ix, u32 seg_words, bool may_be_wide, u32& err) {
+                                                 bool ix, u32 seg_words, bool may_be_wide, u32& err, const uint4* safe) {
   const u32 mis = u32(seg_off) & 3u;
   const u64 src0 = seg_off - mis;                      // in words, multiple of 4
   WaveStage st;
@@ -93,8 +110,8 @@ __device__ inline WavePayload stage_wave_payload(const u32* payload, u64 payload
   if (ix) {
     // at most 64 * 16 words when no block is wider than 15 bits
     if (seg_words <= 64u * 16u && seg_off + seg_words <= payload_words) span = mis + seg_words;
-    st = load_wave_stage(payload, payload_words, src0, span, lane);
-    store_wave_stage(st, span, wl, lane);              // at once: the registers are free for what follows
+    st = load_wave_stage(payload, payload_words, src0, span, lane, safe);
+    store_wave_stage(st, payload, payload_words, src0, span, wl, lane);   // at once: the registers are free for what follows
   }
   bool unfit = false;
   if (ix) {
@@ -116,8 +133,8 @@ __device__ inline WavePayload stage_wave_payload(const u32* payload, u64 payload
   }
   if (wp.wmax <= 15 && !ix) {
     span = wp.inside ? mis + wave_total : 0u;
-    st = load_wave_stage(payload, payload_words, src0, span, lane);
-    store_wave_stage(st, span, wl, lane);
+    st = load_wave_stage(payload, payload_words, src0, span, lane, safe);
+    store_wave_stage(st, payload, payload_words, src0, span, wl, lane);
   }
   return wp;
 }
@@ -142,8 +159,8 @@ __device__ inline void pick_block_words(const WavePayload& wp, u64 seg_off, cons
 
 __device__ inline u32 wave_block_words(const u32* payload, u64 payload_words, u32 w, u64 seg_off, u32* wl, int lane,
                                        u32 (&lo)[16], u32 (&hi)[16], bool ix, u32 seg_words, bool may_be_wide,
-                                       u32& err) {
-  const WavePayload wp = stage_wave_payload(payload, payload_words, w, seg_off, wl, lane, ix, seg_words, may_be_wide, err);
+                                       u32& err, const uint4* safe) {
+  const WavePayload wp = stage_wave_payload(payload, payload_words, w, seg_off, wl, lane, ix, seg_words, may_be_wide, err, safe);
   if (wp.wmax <= 15) {
     pick_block_words(wp, seg_off, wl, lo);
   } else {
@@ -278,7 +295,7 @@ __device__ inline void decompress_tile(const StreamRef& in, float* out_values, u
     u32 lo[16], hi[16];
     u32 err = 0;
     const u32 wmax = wave_block_words(payload, payload_words, w, seg_off, wl, lane, lo, hi, ix,
-                                      uniform(seg_end) - u32(seg_off), h.wide, err);
+                                      uniform(seg_end) - u32(seg_off), h.wide, err, reinterpret_cast<const uint4*>(a.in.base));
     if (ix && !index_ends_ok(h, seg, u32(seg_off), uniform(seg_end))) err |= status_bit(ZC_ERR_FORMAT);
     if (err && lane == 0) raise_status(a.ctl, tag, err);
     deltas_from_block_words(wmax, lo, hi, d);

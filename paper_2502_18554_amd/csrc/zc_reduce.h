@@ -315,16 +315,8 @@ __device__ inline OperandStage load_operand_payload(const u32* payload, const Op
   for (int i = 0; i < kStageLoads; ++i) {
     const u32 idx = 4u * u32(lane) + 256u * u32(i);
     st.v[i] = make_uint4(0, 0, 0, 0);
-    if (idx < p.span) {
-      if (idx + 4 <= p.room) {
-        st.v[i] = load_once(reinterpret_cast<const uint4*>(src + idx));
-      } else {                                     // the last words of the caller's buffer
-        const u32 left = p.room - idx;
-        st.v[i].x = src[idx];
-        if (left > 1) st.v[i].y = src[idx + 1];
-        if (left > 2) st.v[i].z = src[idx + 2];
-      }
-    }
+    // whole 16-byte pieces only: the last words of the caller's buffer are left to stage_to_lds (see load_wave_stage)
+    if (idx < p.span && idx + 4 <= p.room) st.v[i] = load_once(reinterpret_cast<const uint4*>(src + idx));
   }
   return st;
 }
@@ -334,6 +326,17 @@ __device__ inline void stage_to_lds(const OperandStage& st, const OperandPlace& 
   for (int i = 0; i < kStageLoads; ++i) {
     const u32 idx = 4u * u32(lane) + 256u * u32(i);
     if (idx < p.span) *reinterpret_cast<uint4*>(wl + idx) = st.v[i];
+  }
+  const u32 staged = p.span < 256u * kStageLoads ? p.span : 256u * kStageLoads;
+  if (((staged + 3u) & ~3u) > p.room) {            // uniform, and rare: the buffer ends inside a 16-byte piece
+#pragma unroll
+    for (int i = 0; i < kStageLoads; ++i) {
+      const u32 idx = 4u * u32(lane) + 256u * u32(i);
+      if (idx < p.span && idx + 4 > p.room) {
+        for (u32 j = 0; j < 3; ++j)
+          if (idx + j < p.room) wl[idx + j] = payload[p.src0 + idx + j];
+      }
+    }
   }
   if (p.span > 256u * kStageLoads) {               // uniform, and rare: words 1024 .. 1026
     const u32 idx = 256u * kStageLoads + u32(lane);

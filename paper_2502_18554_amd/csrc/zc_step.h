@@ -260,7 +260,10 @@ __device__ inline void step_wave_slow(const StepArgs& a, const ParsedHeader& h, 
   }
 }
 
-template <bool IX, int OP>
+// TICKETS: tiles are handed out by tickets (take_tile) instead of by workgroup id.  A template parameter,
+// not an argument: a workgroup that knows its tile from its id asks for everything at once, and the waits
+// for those loads can only be counted exactly when no other path joins them.
+template <bool IX, int OP, bool TICKETS>
 __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kStepStage];
   __shared__ u32 sh_tile;
@@ -274,7 +277,7 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   // Everything that can be asked for before the header is known goes out at once.  A workgroup
   // that takes the tile of its own number also asks for its local values, its segment's
   // position and its width bytes (fenced in by sizes the host passed).
-  const bool early = !a.ticketed;
+  constexpr bool early = !TICKETS;
   const u32 zero = opaque_zero();
   uint4 gate_raw = make_uint4(0, 0, 0, 0);
   if (!IX) gate_raw = load_gate(a.ctl, zero);
@@ -287,12 +290,8 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
     const u32 b = seg * kWaveBlocks + u32(lane);
     const u64 v0 = u64(seg) * kWaveBlocks * kBlockValues;
     const bool whole = v0 + u64(kWaveBlocks) * kBlockValues <= a.n_local;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const u64 idx = v0 + u64(256 * i + 4 * lane);
-      x[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (whole) x[i] = load_once(reinterpret_cast<const float4*>(a.local + idx));     // (a ragged wave fetches its values later)
-    }
+    // the segment's position and the width bytes first: loads return in the order in which they were asked
+    // for, and the payload can be asked for as soon as these are there, while the local values still arrive
     if (IX) {                 // the width bytes sit behind the index, whose size follows from n (= n_local, or the call fails)
       if (u64(kHeaderBytes) + 4 * u64(seg) + 8 <= a.in.bytes) {
         seg_parts = load_segment_offset(a.index, 0, seg, zero, a.in.base);
@@ -303,6 +302,12 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
     } else {
       if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, 0, seg, zero);
       if (u64(kHeaderBytes) + b < a.in.bytes) w = u32(*at_bytes(a.in.base, kHeaderBytes + b));
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const u64 idx = v0 + u64(256 * i + 4 * lane);
+      x[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      if (whole) x[i] = load_once(reinterpret_cast<const float4*>(a.local + idx));     // (a ragged wave fetches its values later)
     }
   }
 
@@ -341,7 +346,7 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   if (a.first_tile >= end_tile) return;
 
   u32 tile = a.first_tile + blockIdx.x;      // tiles in the order in which workgroups start
-  if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
+  if (TICKETS) {                             // ... or handed out by tickets, see take_tile
     if (threadIdx.x == 0) {
       const u32 t = take_tile(a.ctl, ltag, end_tile - a.first_tile, xcc_id());
       sh_tile = t == kNoTile ? kNoTile : a.first_tile + t;
@@ -387,7 +392,7 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   u32 err = 0;
   const u64 seg_off = IX ? u64(uniform(seg_parts.seg)) : segment_offset(seg_parts);
   const WavePayload wp = stage_wave_payload(payload_in, (h.total - tend) / 4, w, seg_off, wl, lane, IX,
-                                            uniform(seg_end) - u32(seg_off), h.wide, err);
+                                            uniform(seg_end) - u32(seg_off), h.wide, err, reinterpret_cast<const uint4*>(a.in.base));
   if (IX && seg_live && !index_ends_ok(h, seg, u32(seg_off), uniform(seg_end))) err |= status_bit(ZC_ERR_FORMAT);
 
   CompressArgs qa;               // the quantiser's constants, from the stream's own bound
