@@ -290,24 +290,30 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
     const u32 b = seg * kWaveBlocks + u32(lane);
     const u64 v0 = u64(seg) * kWaveBlocks * kBlockValues;
     const bool whole = v0 + u64(kWaveBlocks) * kBlockValues <= a.n_local;
-    // the segment's position and the width bytes first: loads return in the order in which they were asked
-    // for, and the payload can be asked for as soon as these are there, while the local values still arrive
+    // The segment's position and the width bytes first: loads return in the order in which they were asked
+    // for, and the payload can be asked for as soon as these are there, while the local values still arrive.
+    // None of these loads sits behind a branch (what must not be read is replaced by the stream's first
+    // bytes and dropped afterwards): where paths with different numbers of loads under way meet, the
+    // compiler has to wait for all of them at the first use of any.
     if (IX) {                 // the width bytes sit behind the index, whose size follows from n (= n_local, or the call fails)
-      if (u64(kHeaderBytes) + 4 * u64(seg) + 8 <= a.in.bytes) {
-        seg_parts = load_segment_offset(a.index, 0, seg, zero, a.in.base);
-        seg_end = load_segment_end(a.in.base, seg, zero);
-      }
+      const bool have = u64(kHeaderBytes) + 4 * u64(seg) + 8 <= a.in.bytes;
+      const u32 at = have ? kHeaderBytes + 4u * seg : 0u;
+      const u32 e0 = *reinterpret_cast<const u32*>(at_bytes(a.in.base, at + zero));
+      const u32 e1 = *reinterpret_cast<const u32*>(at_bytes(a.in.base, at + 4u + zero));
       const u64 w_at = widths_begin(num_blocks(a.n_local), true) + b;
-      if (w_at < a.in.bytes) w = u32(*at_bytes(a.in.base, u32(w_at)));
+      const u32 wb = u32(*at_bytes(a.in.base, w_at < a.in.bytes ? u32(w_at) : 0u));
+      seg_parts.seg = have ? e0 : 0u;
+      seg_end = have ? e1 : 0u;
+      w = w_at < a.in.bytes ? wb : 0u;
     } else {
       if (seg < 4 * a.index.tiles_cap) seg_parts = load_segment_offset(a.index, 0, seg, zero);
       if (u64(kHeaderBytes) + b < a.in.bytes) w = u32(*at_bytes(a.in.base, kHeaderBytes + b));
     }
+    const float4* const nothing = reinterpret_cast<const float4*>(a.in.base);      // (a ragged wave fetches its values later)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const u64 idx = v0 + u64(256 * i + 4 * lane);
-      x[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (whole) x[i] = load_once(reinterpret_cast<const float4*>(a.local + idx));     // (a ragged wave fetches its values later)
+      x[i] = load_once(whole ? reinterpret_cast<const float4*>(a.local + idx) : nothing);
     }
   }
 
