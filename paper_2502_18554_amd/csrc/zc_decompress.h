@@ -141,19 +141,23 @@ __device__ inline WavePayload stage_wave_payload(const u32* payload, u64 payload
 
 // Second half, widths up to 15: every lane picks its block's words out of the staged copy.
 // lo[0..15) = planes 0..14, lo[15] = sign word.  `wl` is free again on return.
+// All sixteen reads are issued at once and without conditions (the words behind a block's own
+// belong to the next blocks, or are whatever the staging area held: they are dropped
+// afterwards; the area is large enough for 15 words behind any staged word).  A loop that
+// stops at the wave's widest block costs far more than the reads it saves: it is compiled as
+// a loop, with a wait after every read.
 __device__ inline void pick_block_words(const WavePayload& wp, u64 seg_off, const u32* wl, u32 (&lo)[16]) {
-#pragma unroll
-  for (int p = 0; p < 16; ++p) lo[p] = 0;
+  static_assert(kWaveStage >= 1027 + 16, "reads behind the last staged word stay inside the staging area");
   wave_lds_sync();
-  if (wp.w && wp.inside) {
-    const u32* mine = wl + (u32(seg_off) & 3u) + wp.off_in_wave;
-    lo[15] = mine[0];
+  const bool have = wp.w && wp.inside;
+  const u32* mine = wl + (have ? (u32(seg_off) & 3u) + wp.off_in_wave : 0u);
+  u32 t[16];
 #pragma unroll
-    for (int p = 0; p < 15; ++p) {
-      if (u32(p) >= wp.wmax) break;
-      if (u32(p) < wp.w) lo[p] = mine[1 + p];
-    }
-  }
+  for (int p = 0; p < 16; ++p) t[p] = mine[p];
+  const u32 keep = have ? (1u << wp.w) - 1u : 0u;      // bit p: the block has plane p
+  lo[15] = have ? t[0] : 0u;
+#pragma unroll
+  for (int p = 0; p < 15; ++p) lo[p] = t[1 + p] & u32(__builtin_amdgcn_sbfe(i32(keep), u32(p), 1u));
   wave_lds_sync();
 }
 

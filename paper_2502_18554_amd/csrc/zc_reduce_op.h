@@ -149,17 +149,17 @@ __global__ __launch_bounds__(kTileThreads, 4) void reduce_op_kernel(ReduceArgs a
       outlier_next = load_operand_outlier(a, s + 1, h, b, active, IX);
     }
     // the lane's sign and plane words out of the staged payload, then deltas by the bit-matrix transposes
+    // (all reads at once and without conditions, what is not the block's own is dropped: see pick_block_words)
     u32 lo[16];
+    {
+      const u32* mine = wl + (cur.w ? cur.pick : 0u);
+      u32 t[16];
 #pragma unroll
-    for (int p = 0; p < 16; ++p) lo[p] = 0;
-    if (cur.w) {
-      const u32* mine = wl + cur.pick;
-      lo[15] = mine[0];
+      for (int p = 0; p < 16; ++p) t[p] = mine[p];
+      const u32 keep = cur.w ? (1u << cur.w) - 1u : 0u;      // bit p: the block has plane p
+      lo[15] = cur.w ? t[0] : 0u;
 #pragma unroll
-      for (int p = 0; p < 15; ++p) {
-        if (u32(p) >= cur.wcap) break;
-        if (u32(p) < cur.w) lo[p] = mine[1 + p];
-      }
+      for (int p = 0; p < 15; ++p) lo[p] = t[1 + p] & u32(__builtin_amdgcn_sbfe(i32(keep), u32(p), 1u));
     }
     wave_lds_sync();
     if (cur.wcap == 0) {                       // nothing but constant blocks: every code is the block's first

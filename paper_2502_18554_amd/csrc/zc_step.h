@@ -62,7 +62,7 @@ struct StepArgs {
 // through the same area.
 constexpr int kStepRow = 20;
 constexpr int kStepStage = kWaveBlocks * kStepRow;     // 1280 words = 5 KiB per wave
-static_assert(kStepStage >= 1028 && kStepStage >= 64 * 16, "payload staging must fit the wave's area");
+static_assert(kStepStage >= 1027 + 16 && kStepStage >= 64 * 16, "payload staging, and the reads behind its last word, must fit the wave's area");
 
 // Header fields and table padding of the output stream; one thread.
 __device__ inline void write_step_header(const StepArgs& a, const ParsedHeader& h, u64 tag, u32 ntiles, bool ix) {
