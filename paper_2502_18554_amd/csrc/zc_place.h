@@ -97,12 +97,21 @@ __device__ inline void write_stream_header(u8* out, u64 n, u64 nb, u32 eb_bits, 
 // ROUNDS * 64 >= limit + 31.
 template <int ROUNDS>
 __device__ inline void copy_staged_words(const u32* wl, u32* dst, u32 limit, int lane) {
-  const u32 lead = u32(reinterpret_cast<uintptr_t>(dst) >> 2) & 31u;   // words of dst's line before dst
-#pragma unroll 4
-  for (u32 r = 0; r < u32(ROUNDS); ++r) {
-    if (64u * r >= limit + lead) break;        // uniform
-    const u32 i = u32(lane) + 64u * r - lead;  // wraps for the lanes ahead of dst: they sit out
-    if (i < limit) store_once(dst + i, wl[i]);
+  const u32 lead = uniform(u32(reinterpret_cast<uintptr_t>(dst) >> 2) & 31u);   // words of dst's line before dst
+  const u32 end = uniform(limit) + lead;
+  // four rounds at a time: their LDS reads are all under way before the first store needs its word
+#pragma unroll
+  for (int r0 = 0; r0 < ROUNDS; r0 += 4) {
+    if (64u * u32(r0) >= end) break;           // uniform
+    u32 i[4], v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      i[k] = u32(lane) + 64u * u32(r0 + k) - lead;   // wraps for the lanes ahead of dst: they sit out
+      v[k] = wl[i[k] < limit ? i[k] : 0u];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (r0 + k < ROUNDS && i[k] < limit) store_once(dst + i[k], v[k]);
   }
 }
 

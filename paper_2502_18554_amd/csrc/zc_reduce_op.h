@@ -104,7 +104,7 @@ __device__ inline void place_codes(const ReduceArgs& a, const ReduceCall& c, i32
 }
 
 template <bool IX, int OP>
-__global__ __launch_bounds__(kTileThreads, 4) void reduce_op_kernel(ReduceArgs a) {
+__global__ __launch_bounds__(kTileThreads, 3) void reduce_op_kernel(ReduceArgs a) {
   __shared__ __attribute__((aligned(16))) u32 lds[kTileWaves * kWholeStage];
   __shared__ u32 sh_tile;
   __shared__ u32 sh_wave_total[kTileWaves];
