@@ -143,8 +143,11 @@ __device__ inline void publish_tile_size(const PayloadSink& s, u32 tile, u32 til
 
 // Base offset of the tile, in payload words: wave 0 looks back, everyone meets at one barrier.
 // The tile's size must have been published.  Called by every wave of the workgroup.
-// `meanwhile()` runs in every wave once wave 0 has sent its first poll: memory operations
-// issued there overlap with the poll's round trip instead of queueing in front of it.
+// `meanwhile()` runs in every wave: in the other waves while wave 0 looks back, in wave 0 between
+// its first poll and the rest of the look-back.  (Measured against the two other orders, wave 0's
+// share inside the first poll's round trip, and after the tile's prefix is published: both are 1-2 %
+// slower over the whole kernel; a first poll that is read a little later more often finds what it
+// needs, and saves a second poll of the same busy lines.)
 template <typename MeanwhileFn>
 __device__ inline TileBase resolve_tile_base(const PayloadSink& s, const Placement& pl, u32 tile, u64* sh_base, int wave,
                                              int lane, MeanwhileFn meanwhile) {
