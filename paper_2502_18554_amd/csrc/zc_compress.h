@@ -310,10 +310,8 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
     Placement pl;
     pl.w = (active && bf.any) ? 32u - u32(__builtin_clz(bf.any)) : 0u;
     pl.wmax = wave_max_u32(pl.w);
-    if (active && tables_fit) {
-      a.out[widths_begin(a.nb, a.ix) + b] = u8(pl.w);
-      reinterpret_cast<i32*>(a.out + outliers_begin(a.nb, a.ix))[b] = bf.outlier;
-    }
+    // (the width and the outlier go to their tables at the very end: a store that is under way is
+    // waited for by the barrier below, and by every poll of the look-back)
 
     // ---- place the block inside the wave and the wave inside the tile ----
     const u32 words = psize_words(pl.w);
@@ -325,7 +323,7 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
       sh_wave_total[wave] = pl.wave_total;
       sh_wave_wmax[wave] = pl.wmax;
     }
-    __syncthreads();   // wave totals visible; also fences the previous tile's use of sh_base
+    lds_barrier();     // wave totals visible
     pl.wave_off = 0;
     pl.tile_total = 0;
     u32 tile_wmax = 0;
@@ -364,6 +362,10 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
       });
     } else {
       wide_tile<FULL>(a, sink, pl, tile, ntiles, wblock0, wl, &sh_base, wave, lane);
+    }
+    if (active && tables_fit) {
+      a.out[widths_begin(a.nb, a.ix) + b] = u8(pl.w);
+      reinterpret_cast<i32*>(a.out + outliers_begin(a.nb, a.ix))[b] = bf.outlier;
     }
   }
   if (err) raise_status(a.ctl, tag, err);
