@@ -160,11 +160,8 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ReduceCall& c
   pl.half0_total = lane_value(incl, 31);
   pl.off_in_wave = incl - words;
   if (lane == 0) sh_wave_total[wave] = pl.wave_total | (ix && pl.wmax > 15 ? kWaveWideMark : 0u);
-  if (active && a.out_cap >= tend) {
-    // (the whole output stream is written with the non-temporal hint, see store_once)
-    __builtin_nontemporal_store(u8(w), a.out + widths_begin(h.nb, ix) + b);
-    __builtin_nontemporal_store(i32(outlier), reinterpret_cast<i32*>(a.out + outliers_begin(h.nb, ix)) + b);
-  }
+  // (width and outlier go to their tables at the very end: a store that is under way is waited for by
+  // every poll of the look-back)
   if (w) {
     wl[pl.off_in_wave] = word(std::integral_constant<int, 0>{});
     [&]<int... P>(std::integer_sequence<int, P...>) {
@@ -185,6 +182,11 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ReduceCall& c
   const u32 limit = u64(pl.wave_total) < room ? pl.wave_total : u32(room);
   copy_staged_words<NW + 1>(wl, dst, limit, lane);
   wave_lds_sync();
+  if (active && a.out_cap >= tend) {
+    // (the whole output stream is written with the non-temporal hint, see store_once)
+    __builtin_nontemporal_store(u8(w), a.out + widths_begin(h.nb, ix) + b);
+    __builtin_nontemporal_store(i32(outlier), reinterpret_cast<i32*>(a.out + outliers_begin(h.nb, ix)) + b);
+  }
   finish_stream(sink, pl, tile, ntiles, tb);
 }
 

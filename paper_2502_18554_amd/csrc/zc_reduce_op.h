@@ -61,10 +61,6 @@ __device__ inline void place_codes(const ReduceArgs& a, const ReduceCall& c, i32
     pl.w = 0;
   }
   pl.wmax = wave_max_u32(pl.w);
-  if (active && a.out_cap >= tend) {
-    __builtin_nontemporal_store(u8(pl.w), a.out + widths_begin(h.nb, IX) + b);
-    __builtin_nontemporal_store(outlier, reinterpret_cast<i32*>(a.out + outliers_begin(h.nb, IX)) + b);
-  }
   const u32 words = psize_words(pl.w);
   const u32 incl = wave_inclusive_sum(words);
   pl.wave_total = lane_value(incl, 63);
@@ -99,6 +95,10 @@ __device__ inline void place_codes(const ReduceArgs& a, const ReduceCall& c, i32
       else if constexpr (I <= 16) return plo[I - 1];
       else return phi[I - 17];
     }, pl, tb.words, wl, lane);
+  }
+  if (active && a.out_cap >= tend) {     // (at the very end: see place_sum_staged)
+    __builtin_nontemporal_store(u8(pl.w), a.out + widths_begin(h.nb, IX) + b);
+    __builtin_nontemporal_store(outlier, reinterpret_cast<i32*>(a.out + outliers_begin(h.nb, IX)) + b);
   }
   finish_stream(sink, pl, tile, ntiles, tb);
 }

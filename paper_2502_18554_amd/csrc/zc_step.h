@@ -484,10 +484,8 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
 
   // ---- width, tables, placement ----
   pl.wmax = wave_max_u32(pl.w);
-  if (active && a.out_cap >= tend) {
-    a.out[widths_begin(h.nb, IX) + b] = u8(pl.w);
-    reinterpret_cast<i32*>(a.out + outliers_begin(h.nb, IX))[b] = outlier;
-  }
+  // (width and outlier go to their tables at the very end: a store that is under way is waited for by
+  // every poll of the look-back)
   const u32 words = psize_words(pl.w);
   const u32 incl = wave_inclusive_sum(words);
   pl.wave_total = lane_value(incl, 63);
@@ -534,6 +532,10 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
     u32 ignored = 0;
     step_wave_slow<OP, true>(a, h, qa, seg, si, pl.w, outlier, pl.off_in_wave, base + pl.wave_off, cap_words,
                              reinterpret_cast<u32*>(a.out + tend), ignored);
+  }
+  if (active && a.out_cap >= tend) {
+    a.out[widths_begin(h.nb, IX) + b] = u8(pl.w);
+    reinterpret_cast<i32*>(a.out + outliers_begin(h.nb, IX))[b] = outlier;
   }
   finish_stream(sink, pl, tile, ntiles, tb);
 }
