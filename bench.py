@@ -311,8 +311,8 @@ def main():
 
             for name, fn in (("compress", comp), ("decompress", decomp)):
                 ms = timed(fn, reps=12, warm=8)
-                res[name] = {"ms": round(ms, 4), "fp32_GBps": round(4 * n / ms / 1e6, 1),
-                             "call_frac": round((4 * n + cb) / ms / 1e6 / HBM_PEAK_GBS, 4)}
+                frac = round((4 * n + cb) / ms / 1e6 / HBM_PEAK_GBS, 4)      # the whole call: it is one launch
+                res[name] = {"ms": round(ms, 4), "fp32_GBps": round(4 * n / ms / 1e6, 1), "call_frac": frac, "hbm_frac": frac}
             extras[f"rel_{rel:g}"] = res
         finish_all("error bound sweep")
         for s in d_streams:                  # back to the step's bound

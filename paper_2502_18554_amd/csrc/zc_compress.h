@@ -122,11 +122,12 @@ template <bool FULL>
 __device__ inline void block_codes(const CompressArgs& a, const float4 (&x)[8], u64 wblock0, int lane, u32* wl,
                                    i32 (&q)[32], u32& err) {
   // Some value of this wave outside the screened domain: the checked arithmetic for all of it.
-  bool flagged = false;
+  u32 flagged = 0;            // (no short-circuit: the four compares of a load are independent)
 #pragma unroll
   for (int i = 0; i < 8; ++i)
-    flagged |= needs_checks(x[i].x, a) | needs_checks(x[i].y, a) | needs_checks(x[i].z, a) | needs_checks(x[i].w, a);
-  const bool checked = __any(flagged);
+    flagged |= u32(needs_checks(x[i].x, a)) | u32(needs_checks(x[i].y, a)) | u32(needs_checks(x[i].z, a)) |
+               u32(needs_checks(x[i].w, a));
+  const bool checked = __any(flagged != 0);
 
   // Loads 0..3 hold blocks 0..31 (lanes 0..31), loads 4..7 blocks 32..63.
 #pragma unroll

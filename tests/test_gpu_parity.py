@@ -1318,3 +1318,48 @@ def test_reduce_and_ring_round_in_parts_match_reference(zcref, stream_variant):
     assert zc.zc_reduce_step_part(d_streams[0], sizes[0], d_bad, n, 0, 0, TILE, d_out, ws, out_cap=cap)[0] == ZC_OK
     assert zc.zc_reduce_step_part(d_streams[0], sizes[0], d_bad, n, 0, TILE, TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_NONFINITE
     assert zc.zc_reduce_step_part(d_streams[0], sizes[0], d_bad, n, 0, 2 * TILE, n - 2 * TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_NONFINITE
+
+
+@pytest.mark.parametrize("lead_width", [0, 1, 2, 3, 6])
+def test_staging_corners_full_width_waves_off_the_grid(zcref, lead_width):
+    """The copy of a wave's payload into LDS moves whole 16-byte pieces and fetches what is left separately:
+    waves whose 64 blocks are all 15 bits wide (1024 words) starting 0..3 words off the 16-byte grid (up to three
+    words beyond the four pieces), and streams whose payload ends inside a piece.  Decompression, the k-way Sum,
+    Max and the ring round, against the reference."""
+    u = _u()
+    rng = np.random.default_rng(900 + lead_width)
+    nseg = 9
+    n = 2048 * nseg - 5                                   # the last block is ragged
+    q = np.zeros(n, np.int64)
+    # block 0 decides how far off the grid everything behind it starts: 1 + lead_width payload words, or none
+    if lead_width:
+        q[1:32:2] = 2 ** (lead_width - 1)
+    sign = np.where(np.arange(n - 32) % 2 == 0, 1, -1)
+    q[32:] = sign * (2 ** 13 + rng.integers(0, 2 ** 13 - 1, n - 32))      # deltas of magnitude 2^14 .. 2^15 - 1
+    q = q.astype(np.int32)
+    eb = 1e-3
+    st, s, total = zcref.encode_codes(q, eb)
+    assert st == ZC_OK
+    nb = (n + 31) // 32
+    w = u.widths_of(s, nb)
+    assert w[0] == lead_width and (w[1:] == 15).all()
+    st, y, m = u.gpu_decompress(s, n)
+    st_ref, y_ref, _ = zcref.decompress(s)
+    assert st == st_ref == ZC_OK and m == n and np.array_equal(y.view(np.uint32), y_ref.view(np.uint32))
+    # a second operand with small codes keeps the sums inside 15 bits where it matters less: widths stay mixed
+    q2 = rng.integers(-3, 4, n).astype(np.int32)
+    s2 = zcref.encode_codes(q2, eb)[1]
+    for op in (None, 1):
+        st_ref, r_ref, t_ref = zcref.reduce([s, s2]) if op is None else zcref.reduce([s, s2], op=op)
+        st, r, t = u.gpu_reduce([s, s2], n, op=op)
+        assert st == st_ref and t == t_ref and r.tobytes() == r_ref.tobytes(), (op, u.first_diff(r, r_ref))
+    local = (rng.uniform(-1, 1, n) * eb).astype(np.float32)
+    st_ref, t_ref, b_ref = zcref.reduce_step(s, local)
+    st, t, b = u.gpu_reduce_step(s, local)
+    assert st == st_ref and b == b_ref and t.tobytes() == t_ref.tobytes()
+    # every length of the payload modulo four words, by cutting blocks off the end
+    for cut in (1, 2, 3, 4, 5):
+        qc = q[: n - 32 * cut]
+        sc = zcref.encode_codes(qc, eb)[1]
+        st, y, m = u.gpu_decompress(sc, qc.size)
+        assert st == ZC_OK and np.array_equal(y.view(np.uint32), zcref.decompress(sc)[1].view(np.uint32)), cut
