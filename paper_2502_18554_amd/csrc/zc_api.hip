@@ -98,7 +98,8 @@ int finish(const void* d_ws, size_t* result, hipStream_t stream) {
 
 // Validation and block positions of plain input streams, ahead of the kernel that reads them
 // (indexed streams bring their positions along and are judged by that kernel itself).
-// `tiles`: enough for the largest stream.  Returns the nonce the main kernel must be given.
+// `tiles`: enough for the largest stream.  index_prep_kernel opens the call: the main kernel
+// adopts the tag it leaves in the control block.
 void launch_plain_index(ScanArgs& sa, u64 tiles, hipStream_t stream) {
   hipLaunchKernelGGL(stream_index_kernel, dim3(index_grid(tiles), u32(sa.k)), dim3(256), 0, stream, sa);
   hipLaunchKernelGGL(index_prep_kernel, dim3(1), dim3(256), 0, stream, sa);
