@@ -394,7 +394,12 @@ def main():
             torch.cuda.synchronize()
             finish_all("other variant")
             calls = {s: round(sum(e[i].elapsed_time(e[i + 1]) for e in o_evs) / args.steps, 4) for i, s in enumerate(stage_names)}
+            st, or_bytes = zc.zc_finish(ws_r)                  # the reduced stream's size in this variant
+            check(st, "other variant")
+            o_alg = {"compress": 4 * n + oc_bytes, "decompress": 4 * n + oc_bytes, "reduce": sum(o_bytes) + or_bytes}
+            fracs = {s: round(o_alg[s] / calls[s] / 1e6 / HBM_PEAK_GBS, 4) for s in stage_names}
             return {"ms_per_step": round(ms_o, 4), "value_GBps": round(total_fp32 / ms_o / 1e6, 1), "call_ms": calls,
+                    "call_frac": fracs, "hbm_frac_step": round(sum(o_alg.values()) / ms_o / 1e6 / HBM_PEAK_GBS, 4),
                     "compressed_bytes": oc_bytes}
 
         o_variant = ZC_STREAM_PLAIN if indexed else 0
