@@ -364,6 +364,23 @@ def _allreduce_8x64M(zcref):
         assert st == 0 and ref_total == total
         assert_same_bytes(red[:total], ref, "reduced stream")
         del ref
+    # the k-way Max and Min of the same operands: the quantiser is monotone, so the whole stream must be that of
+    # the elementwise extreme of the buffers compressed once (a call pinned above), but for its nsum (8 against 1)
+    red_x = u8(zc.zc_compress_bound(m))
+    for op, fold in ((zc.binding.ZC_OP_MAX, torch.maximum), (zc.binding.ZC_OP_MIN, torch.minimum)):
+        st, _ = zc.zc_reduce_compressed_op([s.buf for s in streams], [s.total for s in streams], op, red_x, ws, sync=False)
+        assert st == ZC_OK
+        st, total_x = zc.zc_finish(ws)
+        assert st == ZC_OK
+        ext = xs[0]
+        for x in xs[1:]:
+            ext = fold(ext, x)
+        st, direct, total_d = compress_async(ext, eb, ws)
+        assert st == ZC_OK and total_d == total_x, (op, total_d, total_x)
+        assert torch.equal(red_x[:20], direct[:20]) and torch.equal(red_x[24:total_x], direct[24:total_x]), op
+        assert int(red_x[20:24].cpu().numpy().view("<u4")[0]) == 8
+        del ext, direct
+    del red_x
     # sampled slices: the reference reduce of the operands' slices reproduces the GPU stream there
     for b0 in sample_starts(m, rng, 4):
         v0, v1 = 32 * b0, min(m, 32 * b0 + SLICE)
