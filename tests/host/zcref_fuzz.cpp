@@ -48,9 +48,10 @@ int main() {
         const void* chunks[2] = {good.data(), s.data()};
         const size_t sizes[2] = {total, s.size()};
         r = zcref_reduce(chunks, sizes, 2, out.data(), out.size(), &ob);
+        r = zcref_reduce_op(chunks, sizes, 2, 1 + int(rng() % 2), out.data(), out.size(), &ob);
         r = zcref_reduce_step_op(s.data(), s.size(), x.data(), n, int(rng() % 3), out.data(), out.size(), &ob);
         (void)r;
-        calls += 6;
+        calls += 7;
       }
     }
   }
