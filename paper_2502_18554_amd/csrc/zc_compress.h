@@ -104,6 +104,9 @@ __device__ inline void load_raw(const CompressArgs& a, u64 wblock0, int lane, fl
   if (FULL) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) x[i] = load_once(reinterpret_cast<const float4*>(a.in + v0 + u64(256 * i + 4 * lane)));
+    // Nothing moves across this line: left to itself the compiler puts the first use of the first value,
+    // and the wait for it, in front of the last four loads, which then go out a round trip late.
+    __builtin_amdgcn_sched_barrier(0);
   } else {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {

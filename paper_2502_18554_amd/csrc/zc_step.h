@@ -315,6 +315,9 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
       const u64 idx = v0 + u64(256 * i + 4 * lane);
       x[i] = load_once(whole ? reinterpret_cast<const float4*>(a.local + idx) : nothing);
     }
+    // Nothing moves across this line: left to itself the compiler puts the wait for the header in front of
+    // the last of these loads, which then goes out a round trip late.
+    __builtin_amdgcn_sched_barrier(0);
   }
 
   // Plain streams: validated and indexed by the kernels of zc_scan.h, whose verdict and tag are in
