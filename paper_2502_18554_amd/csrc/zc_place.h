@@ -137,30 +137,38 @@ __device__ inline void stage_and_copy_half(WordFn word, u32 w, bool in_half, u32
 // Publishes the tile's payload size; called by one thread as soon as the size is known,
 // because the tiles after this one wait for it.
 __device__ inline void publish_tile_size(const PayloadSink& s, u32 tile, u32 tile_total, bool tile_wide) {
+  // (the first tile of a chain has nothing before it in the chain: its size is its chain sum)
   desc_store(s.desc, tile,
-             (tile == 0 ? kDescPrefix : kDescAggregate) | (tile_wide ? kDescWide : 0) | u64(tile_total), s.tag);
+             (tile < u32(kChains) ? kDescChain : kDescAggregate) | (tile_wide ? kDescWide : 0) | u64(tile_total), s.tag);
 }
 
-// Base offset of the tile, in payload words: wave 0 looks back, everyone meets at one barrier.
-// The tile's size must have been published.  Called by every wave of the workgroup.
-// `meanwhile()` runs in every wave: in the other waves while wave 0 looks back, in wave 0 between
-// its first poll and the rest of the look-back.  (Measured against the two other orders, wave 0's
-// share inside the first poll's round trip, and after the tile's prefix is published: both are 1-2 %
-// slower over the whole kernel; a first poll that is read a little later more often finds what it
-// needs, and saves a second poll of the same busy lines.)
+// Base offset of the tile, in payload words: wave 0 looks back (see "Look-back by chains"),
+// everyone meets at one barrier.  The tile's size must have been published.  Called by every wave
+// of the workgroup.  `meanwhile()` runs in every wave: in the other waves while wave 0 looks back,
+// in wave 0 between the publication of its chain sum and its poll of the other chains, whose
+// tiles publish their chain sums at about the same time: a poll that goes out a little later
+// more often finds them and saves a second one (measured: 1 % over the whole kernel against
+// the poll ahead of `meanwhile()`).
 template <typename MeanwhileFn>
 __device__ inline TileBase resolve_tile_base(const PayloadSink& s, const Placement& pl, u32 tile, u64* sh_base, int wave,
                                              int lane, MeanwhileFn meanwhile) {
-  u64 first = 0;
-  if (wave == 0 && tile) first = lookback_poll(s.desc, i64(tile) - 1, s.tag);
+  u32 own = 0;              // sizes of the tile's chain before it
+  u64 wide = pl.tile_wide ? kDescWide : 0;
+  if (wave == 0 && tile >= u32(kChains)) {
+    u64 own_wide = 0;
+    if (!own_chain_scalar(s.desc, tile, s.tag, own, own_wide)) {
+      const u64 v = chains_lookback(s.desc, tile, s.ctl, s.tag, kOwnChain);
+      own = u32(v);
+      own_wide = v & kDescWide;
+    }
+    wide |= own_wide;
+    if (lane == 0) desc_store(s.desc, tile, kDescChain | wide | u64(u32(own + pl.tile_total)), s.tag);
+  }
   meanwhile();
   if (wave == 0) {
     // words of the tiles before this one, and kDescWide if one of them, or this one, is wide
-    const u64 before = (tile ? lookback_exclusive(s.desc, tile, s.ctl, s.tag, first) : 0) | (pl.tile_wide ? kDescWide : 0);
-    if (lane == 0) {
-      if (tile) desc_store(s.desc, tile, kDescPrefix | (before + pl.tile_total), s.tag);
-      *sh_base = before;
-    }
+    const u64 others = chains_lookback(s.desc, tile, s.ctl, s.tag, kOtherChains);
+    if (lane == 0) *sh_base = u64(u32(own + u32(others))) | wide | (others & kDescWide);
   }
   lds_barrier();                // only sh_base passes through it
   const u64 before = *sh_base;
