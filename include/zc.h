@@ -50,6 +50,13 @@
  *                       dispatcher works but not an architectural promise; tickets need no
  *                       such assumption and cost a few percent.  Either way a wait that does
  *                       not end within 2^20 polls ends the call with ZC_ERR_HIP, never in a hang.
+ *   ZC_CHAINS_COHERENT  (calls that write a stream) the look-back reads every tile descriptor
+ *                       with device-coherent loads.  By default a tile reads the descriptors of
+ *                       the tiles 8, 16, ... before it through the L2 cache of its XCD, which is
+ *                       faster and is where they are written when workgroup ids (and tickets) go
+ *                       round the 8 XCDs; where they do not, such a read may find nothing new for
+ *                       a while, and the tile turns to coherent loads by itself after 64 tries.
+ *                       The flag skips the tries.  Results are the same either way.
  * An index that contradicts the width table, a width above 31, or a width above 15 in a
  * version-2 stream is ZC_ERR_FORMAT, which the kernels find as they use each segment: the
  * output of such a call is unspecified.
@@ -88,6 +95,7 @@ typedef enum {
 
 #define ZC_STREAM_PLAIN 1u
 #define ZC_TILES_BY_TICKET 2u
+#define ZC_CHAINS_COHERENT 4u
 
 /* Worst-case stream size in bytes for n values (every block at width 31: 133 B per 128 B):
  * of the default (indexed) variant, or of the variant that flags name. */

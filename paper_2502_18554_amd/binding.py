@@ -16,7 +16,7 @@ ZC_OK, ZC_ERR_ARG, ZC_ERR_CAPACITY, ZC_ERR_FORMAT, ZC_ERR_NONFINITE, ZC_ERR_RANG
     ZC_ERR_MISMATCH, ZC_ERR_HIP = range(9)
 ZC_MAX_K = 64
 
-ZC_STREAM_PLAIN, ZC_TILES_BY_TICKET = 1, 2
+ZC_STREAM_PLAIN, ZC_TILES_BY_TICKET, ZC_CHAINS_COHERENT = 1, 2, 4
 
 EXPORTS = [
     "zc_compress_bound", "zc_compress_bound_ex", "zc_workspace_bytes", "zc_compress", "zc_compress_ex", "zc_compress_noalloc",

@@ -74,7 +74,7 @@ void launch_main(int kind, void (*kernel)(Args...), dim3 grid, dim3 block, hipSt
   else hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
 }
 
-bool flags_valid(unsigned flags) { return (flags & ~(ZC_STREAM_PLAIN | ZC_TILES_BY_TICKET)) == 0; }
+bool flags_valid(unsigned flags) { return (flags & ~(ZC_STREAM_PLAIN | ZC_TILES_BY_TICKET | ZC_CHAINS_COHERENT)) == 0; }
 bool is_indexed(unsigned flags) { return (flags & ZC_STREAM_PLAIN) == 0; }
 
 // A number per call for its tag (see launch_tag): the host's monotonic clock.  One workspace
@@ -181,6 +181,7 @@ void fill_compress_args(CompressArgs& ca, const float* d_in, u64 n, float abs_eb
   ca.ctl = l.ctl;
   ca.desc = l.desc;
   ca.ticketed = (flags & ZC_TILES_BY_TICKET) != 0;
+  ca.coherent = (flags & ZC_CHAINS_COHERENT) != 0;
   ca.ix = is_indexed(flags);
   ca.part_end = 0;
   ca.adopt = 0;
@@ -512,6 +513,7 @@ static int reduce_impl(const void* const* d_chunks, const size_t* chunk_bytes, i
   ra.ctl = l.ctl;
   ra.desc = l.desc;
   ra.ticketed = (flags & ZC_TILES_BY_TICKET) != 0;
+  ra.coherent = (flags & ZC_CHAINS_COHERENT) != 0;
   ra.nonce = nonce;
   ra.first_tile = ra.end_tile = ra.adopt = 0;
   ra.n_part = 0;
@@ -618,6 +620,7 @@ static int step_impl(const void* d_chunk, size_t chunk_bytes, const float* d_loc
   ta.ctl = l.ctl;
   ta.desc = l.desc;
   ta.ticketed = (flags & ZC_TILES_BY_TICKET) != 0;
+  ta.coherent = (flags & ZC_CHAINS_COHERENT) != 0;
   ta.nonce = nonce;
   ta.first_tile = ta.end_tile = ta.adopt = 0;
   if (ranged) {

@@ -39,6 +39,7 @@ struct CompressArgs {
   Control* ctl;
   u64* desc;
   u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
+  u32 coherent;      // the look-back reads the tile's own chain with device-coherent loads too
   u32 ix;            // write an indexed stream (see index_bytes)
   u32 part_end;      // zc_compress_part: one past the last tile of this call; else 0
   u32 adopt;         // this launch continues a call (a later part, the ragged last tile): its tag is in the control block
@@ -341,7 +342,7 @@ __global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs 
     tile_wmax = uniform(tile_wmax);
     // publish the tile's size as early as possible: the tiles after this one wait for it
     pl.tile_wide = a.ix && tile_wmax > 15;
-    const PayloadSink sink{a.out, a.out_cap, a.nb, a.ctl, a.desc, a.ix != 0, a.part_end, tag};
+    const PayloadSink sink{a.out, a.out_cap, a.nb, a.ctl, a.desc, a.ix != 0, a.coherent != 0, a.part_end, tag};
     if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
 
     // ---- fields -> sign + plane words in registers, then the back half ----

@@ -19,6 +19,7 @@ struct PayloadSink {
   Control* ctl;
   u64* desc;        // look-back descriptors
   bool ix;          // the stream carries a segment index (see index_bytes)
+  bool coherent;    // the look-back reads the tile's own chain with device-coherent loads (ZC_CHAINS_COHERENT)
   u32 part_end;     // a stream produced in parts (zc_compress_part): one past the last tile of this part; else 0
   u64 tag;          // the call's tag (see launch_tag): descriptors and status bits carry it
 };
@@ -156,7 +157,7 @@ __device__ inline TileBase resolve_tile_base(const PayloadSink& s, const Placeme
   u64 wide = pl.tile_wide ? kDescWide : 0;
   if (wave == 0 && tile >= u32(kChains)) {
     u64 own_wide = 0;
-    if (!own_chain_scalar(s.desc, tile, s.tag, own, own_wide)) {
+    if (s.coherent || !own_chain_scalar(s.desc, tile, s.tag, own, own_wide)) {
       const u64 v = chains_lookback(s.desc, tile, s.ctl, s.tag, kOwnChain);
       own = u32(v);
       own_wide = v & kDescWide;

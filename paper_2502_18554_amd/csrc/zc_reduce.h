@@ -41,6 +41,7 @@ struct ReduceArgs {
   Control* ctl;
   u64* desc;
   u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
+  u32 coherent;      // the look-back reads the tile's own chain with device-coherent loads too
   u64 nonce;         // drawn by the host per call, goes into the call's tag (see launch_tag)
   // A reduce done in parts (zc_reduce_compressed_part): this launch takes the tiles
   // [first_tile, end_tile) of the output, end_tile = 0 meaning all of them; a later part
@@ -120,7 +121,7 @@ __device__ inline void place_sum(const ReduceArgs& a, const ReduceCall& c, const
   }
   lds_barrier();                // the wave totals; the stores above stay in flight
   sum_wave_totals(sh_wave_total, wave, ix, pl);
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix, c.part_end, c.tag};
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix, a.coherent != 0, c.part_end, c.tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) raise_status(a.ctl, c.tag, err);
   finish_tile<NW>(sink, word, pl, tile, ntiles, wl, sh_base, wave, lane);
@@ -170,7 +171,7 @@ __device__ inline void place_sum_staged(const ReduceArgs& a, const ReduceCall& c
   }
   lds_barrier();                // the wave totals (and the words above); the stores stay in flight
   sum_wave_totals(sh_wave_total, wave, ix, pl);
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix, c.part_end, c.tag};
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, ix, a.coherent != 0, c.part_end, c.tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) raise_status(a.ctl, c.tag, err);
   const TileBase tb = resolve_tile_base(sink, pl, tile, sh_base, wave, lane);

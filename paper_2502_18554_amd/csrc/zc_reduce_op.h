@@ -69,7 +69,7 @@ __device__ inline void place_codes(const ReduceArgs& a, const ReduceCall& c, i32
   if (lane == 0) sh_wave_total[wave] = pl.wave_total | (IX && pl.wmax > 15 ? kWaveWideMark : 0u);
   lds_barrier();
   sum_wave_totals(sh_wave_total, wave, IX, pl);
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX, 0u, c.tag};
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX, a.coherent != 0, 0u, c.tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) raise_status(a.ctl, c.tag, err);
   const bool narrow = !WIDE || pl.wmax <= 15;

@@ -49,6 +49,7 @@ struct StepArgs {
   Control* ctl;
   u64* desc;
   u32 ticketed;      // tiles handed out by tickets instead of by workgroup id
+  u32 coherent;      // the look-back reads the tile's own chain with device-coherent loads too
   u64 nonce;         // drawn by the host per call, goes into the call's tag (see launch_tag)
   // A round done in parts (zc_reduce_step_part): this launch takes the tiles [first_tile, end_tile)
   // of the output, end_tile = 0 meaning all of them; a later part (adopt) belongs to the call whose
@@ -497,7 +498,7 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   if (lane == 0) sh_wave_total[wave] = pl.wave_total | (IX && pl.wmax > 15 ? kWaveWideMark : 0u);
   lds_barrier();                // the wave totals; the stores above stay in flight
   sum_wave_totals(sh_wave_total, wave, IX, pl);
-  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX, a.end_tile ? end_tile : 0u, tag};
+  const PayloadSink sink{a.out, a.out_cap, h.nb, a.ctl, a.desc, IX, a.coherent != 0, a.end_tile ? end_tile : 0u, tag};
   if (threadIdx.x == 0) publish_tile_size(sink, tile, pl.tile_total, pl.tile_wide);
   if (err) raise_status(a.ctl, tag, err);
   // ---- the new deltas as sign + plane words into the staging area, while the look-back is under way ----

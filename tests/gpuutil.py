@@ -4,12 +4,13 @@ import numpy as np
 import torch
 
 import paper_2502_18554_amd as _zc
-from paper_2502_18554_amd.binding import ZC_STREAM_PLAIN, ZC_TILES_BY_TICKET
+from paper_2502_18554_amd.binding import ZC_CHAINS_COHERENT, ZC_STREAM_PLAIN, ZC_TILES_BY_TICKET
 
 DEV = "cuda:0"
 
 INDEXED = False          # the stream variant the tests are run on (the reference is set to the same; it starts out plain)
 TICKETS = False          # tiles handed out by tickets
+COHERENT = False         # the look-back reads every descriptor with device-coherent loads
 
 # calls that take the stream variant only, and calls that also take the way tiles are handed out
 _READERS = {"zc_compress_bound", "zc_decompress", "zc_decompress_average", "zc_decompress_range", "zc_decompress_many",
@@ -20,7 +21,8 @@ _WRITERS = {"zc_compress", "zc_compress_part", "zc_reduce_compressed", "zc_reduc
 
 def flags(writer=True):
     """The flags argument for the stream variant (and tile hand-out) the tests are running under."""
-    return (0 if INDEXED else ZC_STREAM_PLAIN) | (ZC_TILES_BY_TICKET if writer and TICKETS else 0)
+    return ((0 if INDEXED else ZC_STREAM_PLAIN) | (ZC_TILES_BY_TICKET if writer and TICKETS else 0)
+            | (ZC_CHAINS_COHERENT if writer and COHERENT else 0))
 
 
 class _Library:
@@ -53,6 +55,11 @@ def set_variant(zcref, indexed):
 def set_tickets(on):
     global TICKETS
     TICKETS = bool(on)
+
+
+def set_coherent(on):
+    global COHERENT
+    COHERENT = bool(on)
 
 
 def pad16(v):

@@ -64,7 +64,7 @@ def test_argument_checks_without_gpu(libzc):
     assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 0, 100, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None, 0) == 1       # not a whole tile
     assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 1 << 20, 16384, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None, 0) == 1  # past the end
     libzc.zc_compress_ex.argtypes = [vp, sz, C.c_float, vp, sz, C.POINTER(sz), vp, sz, vp, C.c_uint]
-    assert libzc.zc_compress_ex(0x1000, 10, 1e-3, 0x2000, 100, None, 0x3000, 4096, None, 4) == 1   # unknown flag
+    assert libzc.zc_compress_ex(0x1000, 10, 1e-3, 0x2000, 100, None, 0x3000, 4096, None, 8) == 1   # unknown flag
     assert libzc.zc_decompress(None, 100, None, 0, None, None, 0, None) == 1
     assert libzc.zc_decompress(0x1000, 16, 0x2000, 8, None, 0x3000, 4096, None) == 3           # shorter than a header
     assert libzc.zc_reduce_compressed(None, None, 0, None, 0, None, None, 0, None) == 1
