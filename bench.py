@@ -92,6 +92,31 @@ def profiled(workload_key):
     return entry
 
 
+def streaming_rate(zc, read_bytes, write_bytes, stage_gbs, reps=12):
+    """Times zc_debug_stream on about read_bytes + write_bytes in the nearest mix of 1..16 loads : 1..16 stores per lane."""
+    import torch
+    unit = 8192
+    ratio = read_bytes / write_bytes
+    loads, stores = min(((a, b) for a in range(1, 17) for b in range(1, 17)), key=lambda ab: (abs(ab[0] / ab[1] - ratio), -ab[0]))
+    tiles = max(1, round((read_bytes + write_bytes) / ((loads + stores) * unit)))
+    src = torch.zeros(tiles * loads * unit, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty(tiles * stores * unit, dtype=torch.uint8, device="cuda:0")
+    for _ in range(3):
+        assert zc.zc_debug_stream(src, dst, tiles, loads, stores) == 0
+    torch.cuda.synchronize()
+    zc.zc_profile_enable(True, only=["stream"])
+    for _ in range(reps):
+        zc.zc_debug_stream(src, dst, tiles, loads, stores)
+    torch.cuda.synchronize()
+    times = [ms for name, ms in zc.zc_profile_collect() if name == "stream"]
+    zc.zc_profile_enable(False)
+    ms = sum(times) / len(times)
+    gbs = tiles * (loads + stores) * unit / ms / 1e6
+    return {"loads_per_lane": loads, "stores_per_lane": stores, "workgroups": tiles, "bytes": tiles * (loads + stores) * unit,
+            "kernel_ms": round(ms, 4), "GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4),
+            "stage_over_streaming": round(stage_gbs / gbs, 4)}
+
+
 def valu_frac(instructions, kernel_ms):
     """Share of the kernel's duration that its VALU instructions need to issue: a wave64 instruction holds
     the 16 lanes of its SIMD for 4 cycles, there are 256 x 4 SIMDs, and the clock is 2.4 GHz."""
@@ -273,6 +298,11 @@ def main():
     stages["decompress"]["just_written"] = {"kernel_ms": round(warm_ms, 4),
                                             "frac": round(alg_bytes["decompress"] / warm_ms / 1e6 / HBM_PEAK_GBS, 4),
                                             "input": "the stream the compression of the same step has just written"}
+    # Beside every stage: a kernel that only streams the same bytes in the same read : write mix, with the
+    # access shape of the codec's kernels (zc_debug_stream): what the memory system gives such a kernel.
+    read_write = {"compress": (4 * n, c_bytes), "decompress": (c_bytes, 4 * n), "reduce": (sum(chunk_bytes), r_bytes)}
+    for s in stage_names:
+        stages[s]["streaming_kernel"] = streaming_rate(zc, *read_write[s], alg_bytes[s] / kernel_ms[s] / 1e6)
     total_fp32 = sum(fp32_bytes.values())
     total_alg = sum(alg_bytes.values())
     value = total_fp32 / ms_per_step / 1e6

@@ -333,8 +333,21 @@ int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_wo
 #define ZC_KERNEL_DECOMPRESS 2
 #define ZC_KERNEL_REDUCE 3
 #define ZC_KERNEL_REDUCE_STEP 4
+#define ZC_KERNEL_STREAM 5
 int zc_profile_enable(int on);
 int zc_profile_collect(float* ms, int* kernel, int cap);
+
+/* Measurement aid (not part of the method): a kernel that only streams, with the access shape
+ * of the codec's kernels (workgroups of 512 threads, every lane 16 bytes per access, 8 KiB per
+ * workgroup and access, non-temporal), so that a kernel's rate can be put beside what the
+ * memory system gives a kernel of the same read : write mix that does nothing else.  Workgroup
+ * t of `tiles` reads loads x 8 KiB at d_in + t x loads x 8 KiB and writes stores x 8 KiB at
+ * d_out + t x stores x 8 KiB (every store holds the exclusive-or of what the lane read, so no
+ * load is dead).  loads and stores in 0..16, not both 0; d_in (device, tiles x loads x 8 KiB,
+ * may be NULL when loads is 0) and d_out (device, tiles x stores x 8 KiB, may be NULL when
+ * stores is 0) 16-byte aligned.  Asynchronous on hip_stream; its launch is timed as
+ * ZC_KERNEL_STREAM while zc_profile_enable asks for that.  Errors: ARG, HIP. */
+int zc_debug_stream(const void* d_in, void* d_out, size_t tiles, int loads, int stores, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,7 @@ EXPORTS = [
     "zc_compress_bound", "zc_compress_bound_ex", "zc_workspace_bytes", "zc_compress", "zc_compress_ex", "zc_compress_noalloc",
     "zc_compress_part", "zc_decompress", "zc_decompress_ex", "zc_decompress_many", "zc_reduce_compressed",
     "zc_reduce_compressed_ex", "zc_reduce_compressed_op", "zc_reduce_compressed_part", "zc_reduce_step_part", "zc_reduce_step", "zc_reduce_step_op", "zc_decompress_average", "zc_decompress_range",
-    "zc_quality", "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets",
+    "zc_quality", "zc_finish", "zc_peek_header", "zc_strerror", "zc_debug_quantize", "zc_debug_block_offsets", "zc_debug_stream",
     "zc_profile_enable", "zc_profile_collect",
 ]
 
@@ -74,6 +74,7 @@ def lib():
         L.zc_strerror.argtypes = [C.c_int]
         L.zc_debug_quantize.argtypes = [vp, sz, C.c_float, vp, vp, sz, vp]
         L.zc_debug_block_offsets.argtypes = [vp, sz, vp, sz, vp, sz, vp, u]
+        L.zc_debug_stream.argtypes = [vp, vp, sz, C.c_int, C.c_int, vp]
         L.zc_profile_enable.argtypes = [C.c_int]
         L.zc_profile_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int), C.c_int]
         _lib = L
@@ -284,7 +285,13 @@ def zc_debug_block_offsets(d_in, in_bytes, d_off_words, d_ws, stream=None, flags
                                         _size(d_ws), _stream(stream), int(flags))
 
 
-KERNEL_NAMES = {1: "compress", 2: "decompress", 3: "reduce", 4: "reduce_step"}
+def zc_debug_stream(d_in, d_out, tiles, loads, stores, stream=None):
+    """A kernel that only streams: workgroup t reads loads x 8 KiB of d_in and writes stores x 8 KiB of d_out."""
+    return lib().zc_debug_stream(_p(d_in) if d_in is not None else None, _p(d_out) if d_out is not None else None,
+                                 int(tiles), int(loads), int(stores), _stream(stream))
+
+
+KERNEL_NAMES = {1: "compress", 2: "decompress", 3: "reduce", 4: "reduce_step", 5: "stream"}
 
 
 def zc_profile_enable(on, only=None):

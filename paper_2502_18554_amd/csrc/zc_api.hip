@@ -19,6 +19,7 @@
 #include "zc_scan.h"
 #include "zc_quality.h"
 #include "zc_step.h"
+#include "zc_stream_probe.h"
 
 using namespace zc;
 
@@ -752,6 +753,15 @@ int zc_debug_quantize(const float* d_in, size_t n, float abs_eb, int32_t* d_q, v
   hipLaunchKernelGGL(quantize_kernel, dim3(u32(n ? (n + 255) / 256 : 1)), dim3(256), 0, stream, qa);
   if (!launch_ok()) return ZC_ERR_HIP;
   return finish(d_ws, nullptr, stream);
+}
+
+int zc_debug_stream(const void* d_in, void* d_out, size_t tiles, int loads, int stores, void* hip_stream) {
+  if (loads < 0 || stores < 0 || loads > kProbeMaxAccesses || stores > kProbeMaxAccesses || loads + stores == 0) return ZC_ERR_ARG;
+  if ((loads && !d_in) || (stores && !d_out) || !aligned16(d_in) || !aligned16(d_out) || tiles > 0x7fffffffull) return ZC_ERR_ARG;
+  if (tiles == 0) return ZC_OK;
+  StreamProbeArgs pa{static_cast<const uint4*>(d_in), static_cast<uint4*>(d_out), u32(loads), u32(stores)};
+  launch_main(ZC_KERNEL_STREAM, stream_probe_by_loads(loads), dim3(u32(tiles)), dim3(kProbeThreads), static_cast<hipStream_t>(hip_stream), pa);
+  return launch_ok() ? ZC_OK : ZC_ERR_HIP;
 }
 
 int zc_debug_block_offsets(const void* d_in, size_t in_bytes, uint32_t* d_off_words, size_t off_cap, void* d_ws,

@@ -60,3 +60,33 @@ def test_wide_tiles_with_coherent_chains(zcref):
         st_r, red_ref = zcref.reduce([ref, ref])[:2]
         st_g, red, _ = u.gpu_reduce([ref, ref], n)
         assert st_g == st_r and (st_r != ZC_OK or red.tobytes() == red_ref.tobytes())
+
+
+def test_streaming_probe_moves_what_it_says():
+    """zc_debug_stream: every 16-byte store holds the exclusive-or of the lane's loads (and of the lane's and the
+    workgroup's numbers); nothing outside the two ranges is touched."""
+    import paper_2502_18554_amd as lib
+    dev = gpuutil.DEV
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    for tiles, loads, stores in ((3, 1, 1), (5, 8, 3), (2, 16, 16), (4, 0, 2), (4, 3, 0)):
+        words = 512 * 4                                   # 32-bit words of one 8 KiB access
+        src = torch.randint(0, 2**31 - 1, (tiles * max(loads, 1) * words + 4,), dtype=torch.int32, device=dev, generator=gen)
+        dst = torch.full((tiles * max(stores, 1) * words + 4,), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+        before = dst.clone()
+        assert lib.zc_debug_stream(src if loads else None, dst if stores else None, tiles, loads, stores) == ZC_OK
+        torch.cuda.synchronize()
+        if not stores:
+            assert torch.equal(dst, before)
+            continue
+        got = dst[: tiles * stores * words].view(tiles, stores, 512, 4).cpu().numpy()
+        want = np.zeros((tiles, 512, 4), dtype=np.int32)
+        want[:, :, 0] = np.arange(512)[None, :]
+        want[:, :, 1] = np.arange(tiles)[:, None]
+        if loads:
+            x = src[: tiles * loads * words].view(tiles, loads, 512, 4).cpu().numpy()
+            for i in range(loads):
+                want ^= x[:, i]
+        for j in range(stores):
+            assert np.array_equal(got[:, j], want), (tiles, loads, stores, j)
+        assert torch.equal(dst[tiles * stores * words:], before[tiles * stores * words:])

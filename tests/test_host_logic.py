@@ -65,6 +65,11 @@ def test_argument_checks_without_gpu(libzc):
     assert libzc.zc_compress_part(0x1000, 1 << 20, 1e-3, 1 << 20, 16384, 0x2000, 1 << 22, None, 0x3000, 1 << 20, None, 0) == 1  # past the end
     libzc.zc_compress_ex.argtypes = [vp, sz, C.c_float, vp, sz, C.POINTER(sz), vp, sz, vp, C.c_uint]
     assert libzc.zc_compress_ex(0x1000, 10, 1e-3, 0x2000, 100, None, 0x3000, 4096, None, 8) == 1   # unknown flag
+    libzc.zc_debug_stream.argtypes = [vp, vp, sz, C.c_int, C.c_int, vp]
+    assert libzc.zc_debug_stream(0x1000, 0x2000, 4, 0, 0, None) == 1        # nothing to do per lane
+    assert libzc.zc_debug_stream(0x1000, 0x2000, 4, 17, 1, None) == 1       # more than 16 accesses
+    assert libzc.zc_debug_stream(None, 0x2000, 4, 1, 1, None) == 1          # loads without a source
+    assert libzc.zc_debug_stream(0x1008, 0x2000, 4, 1, 1, None) == 1        # alignment
     assert libzc.zc_decompress(None, 100, None, 0, None, None, 0, None) == 1
     assert libzc.zc_decompress(0x1000, 16, 0x2000, 8, None, 0x3000, 4096, None) == 3           # shorter than a header
     assert libzc.zc_reduce_compressed(None, None, 0, None, 0, None, None, 0, None) == 1
