@@ -133,7 +133,12 @@ __device__ inline void block_codes(const CompressArgs& a, const float4 (&x)[8], 
                u32(needs_checks(x[i].w, a));
   const bool checked = __any(flagged != 0);
 
-  // Loads 0..3 hold blocks 0..31 (lanes 0..31), loads 4..7 blocks 32..63.
+  // Loads 0..3 hold blocks 0..31, loads 4..7 blocks 32..63.  Either half goes through LDS as 32 rows
+  // of 32 codes, and every lane takes half a row: lane l and lane l + 32 the first and the second 16
+  // codes of block l (then of block 32 + l).  That keeps 16 registers per half and lane instead of 32 in
+  // half the lanes; one swap of the upper 32 lanes of a register with the lower 32 of another per pair
+  // of codes then gives every lane the 32 codes of its own block.
+  i32 h0[16], h1[16];
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
 #pragma unroll
@@ -141,14 +146,20 @@ __device__ inline void block_codes(const CompressArgs& a, const float4 (&x)[8], 
       *reinterpret_cast<int4*>(wl + (8 * i + (lane >> 3)) * kStageRow + 4 * (lane & 7)) =
           quantize4(x[4 * half + i], a, checked, err);
     wave_lds_sync();
-    if ((lane >> 5) == half) {
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const int4 r = *reinterpret_cast<const int4*>(wl + (lane & 31) * kStageRow + 4 * t);
-        q[4 * t + 0] = r.x; q[4 * t + 1] = r.y; q[4 * t + 2] = r.z; q[4 * t + 3] = r.w;
-      }
+    for (int t = 0; t < 4; ++t) {
+      const int4 r = *reinterpret_cast<const int4*>(wl + (lane & 31) * kStageRow + 16 * (lane >> 5) + 4 * t);
+      i32* const h = half ? h1 : h0;
+      h[4 * t + 0] = r.x; h[4 * t + 1] = r.y; h[4 * t + 2] = r.z; h[4 * t + 3] = r.w;
     }
     wave_lds_sync();
+  }
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    // -> {lanes 0..31 of h0 | lanes 0..31 of h1}, {lanes 32..63 of h0 | lanes 32..63 of h1}
+    const auto r = __builtin_amdgcn_permlane32_swap(u32(h0[j]), u32(h1[j]), false, false);
+    q[j] = i32(r[0]);
+    q[16 + j] = i32(r[1]);
   }
   if (!FULL) {
     // the last block repeats its last code up to 32 values
@@ -269,7 +280,7 @@ __device__ inline void wide_tile(const CompressArgs& a, const PayloadSink& sink,
 // of its own, of one workgroup, with FULL = false on tile first_tile.  There is no set-up
 // launch: tile 0 writes the header, and nothing in the workspace needs clearing (see launch_tag).
 template <bool FULL>
-__global__ __launch_bounds__(kPackThreads, 6) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
+__global__ __launch_bounds__(kPackThreads, FULL ? 8 : 6) void compress_kernel(CompressArgs a, u32 first_tile, u32 end_tile) {
   __shared__ __attribute__((aligned(16))) u32 lds[kPackWaves * kWaveStage];
   __shared__ u32 sh_tile;
   __shared__ u32 sh_wave_total[kPackWaves];
