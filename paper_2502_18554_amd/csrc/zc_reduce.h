@@ -464,7 +464,10 @@ __device__ inline void reduce_narrow_tile(const ReduceArgs& a, const ReduceCall&
     const bool active = b < h.nb;
     if (early) {
       if (!active) meta.w = 0;
-      if (!seg_live) meta.seg_off = SegmentOffsetParts{0, 0, 0};
+      if (!seg_live) {
+        meta.seg_off = SegmentOffsetParts{0, 0, 0};
+        meta.seg_end = 0;
+      }
       meta.payload_room = payload_room(a, 0, h, IX);
     } else {
       meta = load_operand_meta(a, 0, h, seg, b, active, seg_live, IX);
@@ -668,6 +671,24 @@ __device__ inline bool open_reduce(const ReduceArgs& a, bool for_wide, bool spli
                                    bool early, u32& tile, u32& ntiles, u32* sh_tile) {
   c.ltag = launch_tag(a.nonce, a.ctl);
   if (IX) {
+    if (early) {
+      // the caller has said what n is (a reduce in parts): where the first operand's tables are follows from
+      // that, and they are asked for together with the headers; a stream of another n ends the call below
+      const u32 nb_said = u32(num_blocks(a.n_part));
+      const u32 seg = (a.first_tile + blockIdx.x) * kTileWaves + u32(wave_id());
+      const u32 b = seg * kWaveBlocks + u32(fresh_lane());
+      const u8* base = a.in[0].base;
+      const u32 zero = opaque_zero();
+      const bool seg_ok = seg < num_segments(nb_said) && u64(kHeaderBytes) + 4ull * seg + 8 <= a.in[0].bytes;
+      const bool w_ok = b < nb_said && widths_begin(nb_said, true) + b < a.in[0].bytes;
+      meta.seg_off = SegmentOffsetParts{0, 0, 0};
+      meta.seg_end = 0;
+      if (seg_ok) {
+        meta.seg_off = load_segment_offset(a.index, 0, seg, zero, base);
+        meta.seg_end = load_segment_end(base, seg, zero);
+      }
+      meta.w = w_ok ? u32(*at_bytes(base, u32(widths_begin(nb_said, true)) + b + zero)) : 0u;
+    }
     const StreamsVerdict v = judge_indexed_streams(a.in, a.k, true);
     // (of a pair of kernels the narrow one is launched first and opens the call; a later part of a
     //  reduce done in parts belongs to the call its first part opened)
@@ -746,7 +767,7 @@ __global__ __launch_bounds__(kTileThreads, 6) void reduce_kernel(ReduceArgs a) {
   // together with the control block and the header, before it knows the header: one memory
   // round trip instead of two.  The loads are fenced in by sizes the host passed.  (Not for
   // indexed streams: where their width bytes are is only known with the header.)
-  const bool early = !IX && !a.ticketed;
+  const bool early = !a.ticketed && (!IX || a.n_part != 0);
   u32 tile = 0, ntiles = 0;
   if (!open_reduce<IX>(a, false, false, c, wide, meta, early, tile, ntiles, &sh_tile)) return;
   if (IX && wide) reduce_wide_tile<true>(a, c, tile, ntiles, lds, sh_wave_total, &sh_base);
