@@ -48,7 +48,7 @@
  *                       in work or finished.  By workgroup id that rests on the GPU starting the
  *                       workgroups of a launch in increasing id order, which is how its
  *                       dispatcher works but not an architectural promise; tickets need no
- *                       such assumption and cost an atomic round trip per workgroup (a seventh more
+ *                       such assumption and cost an atomic round trip per workgroup (a ninth more
  *                       time on the 512^3 benchmark step).  Either way a wait that does
  *                       not end within 2^20 polls ends the call with ZC_ERR_HIP, never in a hang.
  *   ZC_CHAINS_COHERENT  (calls that write a stream) the look-back reads every tile descriptor
