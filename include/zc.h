@@ -48,15 +48,16 @@
  *                       in work or finished.  By workgroup id that rests on the GPU starting the
  *                       workgroups of a launch in increasing id order, which is how its
  *                       dispatcher works but not an architectural promise; tickets need no
- *                       such assumption and cost an atomic round trip per workgroup (a ninth more
- *                       time on the 512^3 benchmark step).  Either way a wait that does
+ *                       such assumption and cost an atomic round trip per workgroup (about 7 % more
+ *                       time on the 512^3 benchmark step; every XCD must receive workgroups of
+ *                       the launch, i.e. no CU mask that leaves one out).  Either way a wait that does
  *                       not end within 2^20 polls ends the call with ZC_ERR_HIP, never in a hang.
  *   ZC_CHAINS_COHERENT  (calls that write a stream) the look-back reads every tile descriptor
  *                       with device-coherent loads.  By default a tile reads the descriptors of
  *                       the tiles 8, 16, ... before it through the L2 cache of its XCD, which is
  *                       faster and is where they are written when workgroup ids (and tickets) go
  *                       round the 8 XCDs; where they do not, such a read may find nothing new for
- *                       a while, and the tile turns to coherent loads by itself after 64 tries.
+ *                       a while, and the tile turns to coherent loads by itself after 16 tries.
  *                       The flag skips the tries.  Results are the same either way.
  * An index that contradicts the width table, a width above 31, or a width above 15 in a
  * version-2 stream is ZC_ERR_FORMAT, which the kernels find as they use each segment: the

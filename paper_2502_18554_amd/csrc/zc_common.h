@@ -67,7 +67,7 @@ constexpr u32 kGateBits = status_bit(ZC_ERR_ARG) | status_bit(ZC_ERR_FORMAT) | s
 // tables follow.  Nothing in a workspace is ever cleared: whatever one call shares between its
 // workgroups or its launches carries the call's tag (below), and a word with another tag counts
 // as empty, so a workspace may hold anything when a call starts.
-constexpr int kTicketShards = 8;
+constexpr int kTicketShards = 32;
 struct Control {
   u64 status;                  // bits 63..32: high half of the tag of the call that raised them; bits 31..0: OR of status_bit()s and kStatusWide
   u64 call_tag;                // tag of the last call's first launch; its later launches take it from here
@@ -77,7 +77,7 @@ struct Control {
 };
 static_assert(sizeof(Control) == 64, "control block is 64 bytes");
 
-// Tile hand-out counters, one per XCD (see take_tile), follow the control block.  Each sits
+// Tile hand-out counters, four per XCD (see take_tile), follow the control block.  Each sits
 // in a 128-byte line of its own, and none shares the line of the control block: accesses to
 // one line retire one after the other even when they address different words of it, and every
 // workgroup reads the control block when it starts.
@@ -169,19 +169,30 @@ constexpr u32 kStatusWide = 1u << 16;
 //    all started.  That order is how the hardware works, not an architectural promise, which
 //    is why every look-back wait is bounded and turns into ZC_ERR_HIP instead of a hang.
 //  - by tickets: the order of the claims is the order of the tiles, whatever the dispatcher
-//    does.  It costs each workgroup one atomic round trip before it can issue its first load.
+//    does.  It costs each workgroup one atomic round trip before it can issue its first load
+//    (the kernels that read headers first ask for the ticket before that, see ask_ticket).
 // Tickets: one atomic counter would serialise the whole kernel: atomics on one
-// address retire at about 11 ns each on this machine, which for 16384 tiles is longer than
-// the kernel should run.  So there is one counter per XCD, picked by the hardware XCC_ID of
-// the wave that asks, and counter y hands out tiles y, y + 8, y + 16, ...  A workgroup whose
-// own counter is exhausted helps the others, so every tile is claimed exactly once whatever
-// the placement of workgroups.  Look-back stays deadlock-free: workgroups resident on one
-// XCD hold tiles of its counter in increasing order, so the smallest unfinished tile overall
-// is either running or is the next one its XCD will claim as soon as a slot frees up there,
-// and the slots of that XCD are held by smaller tiles, which finish.
+// address retire at about 11 ns each on this machine when nothing else runs and far slower
+// under load, which for 16384 tiles is longer than the kernel should run.  So there are 32
+// counters, four per XCD: a workgroup asks the one picked by the hardware XCC_ID of its waves
+// and two bits of its id (ticket_shard), and counter y hands out tiles y, y + 32, y + 64, ...,
+// which are tiles of the XCD's own chains (y mod 8 is the XCD).  With one counter per XCD the
+// atomics alone took a tenth of a kernel's time (512^3 compress by ticket 149 us, with four
+// 135 us).  A workgroup whose own counter is exhausted helps the others, its XCD's first, so
+// every tile is claimed exactly once whatever the placement of workgroups.  Look-back stays
+// deadlock-free: the workgroups that ask a counter hold its tiles in increasing order, so the
+// smallest unfinished tile overall is either running or is the next one its counter hands out,
+// to the next workgroup that asks it, and the workgroups that asked it before hold smaller
+// tiles, which finish.  (A counter that no workgroup asks, because the launch is kept off an XCD
+// altogether, is served only once the others are exhausted, which the tiles that wait for its
+// tiles keep from happening: such a launch ends in ZC_ERR_HIP when the waits run out, and
+// should use the other hand-out.)
 __device__ inline u32 xcc_id() {
-  return u32(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11))) & (kTicketShards - 1);   // HW_REG_XCC_ID[3:0]
+  return u32(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11))) & 7u;   // HW_REG_XCC_ID[3:0]
 }
+// The counter a workgroup asks: one of the four of its XCD, in turn (workgroup ids go round the XCDs,
+// so id / 8 counts the workgroups of an XCD).
+__device__ inline u32 ticket_shard() { return xcc_id() | (((blockIdx.x >> 3) & 3u) << 3); }
 
 constexpr u32 kNoTile = 0xffffffffu;
 
@@ -196,9 +207,11 @@ __device__ inline u32 tile_of_ticket(u32 shard, u32 ticket, u32 ntiles) {
 // launch (or anything at all) in it and install their own by compare-and-swap.
 constexpr u64 kTicketCountMask = (u64(1) << 24) - 1;
 
-__device__ inline u32 take_ticket(u64* counter, u64 ltag) {
+// (in two halves, so that a caller can have the add under way while it does other work)
+__device__ inline u64 ask_ticket(u64* counter) { return atomicAdd(reinterpret_cast<unsigned long long*>(counter), 1ull); }
+
+__device__ inline u32 take_ticket(u64* counter, u64 ltag, u64 old) {      // old = ask_ticket(counter)
   const u64 mine = ltag & ~kTicketCountMask;
-  u64 old = atomicAdd(reinterpret_cast<unsigned long long*>(counter), 1ull);
   if ((old & ~kTicketCountMask) == mine) return u32(old & kTicketCountMask);
   old = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   for (u32 tries = 0; tries < kSpinLimit; ++tries) {
@@ -214,15 +227,20 @@ __device__ inline u32 take_ticket(u64* counter, u64 ltag) {
 }
 
 // Claims the next tile (called by one thread of a workgroup).  kNoTile when none is left.
-__device__ inline u32 take_tile(Control* ctl, u64 ltag, u32 ntiles, u32 first_shard) {
+// `asked` = ask_ticket(ticket_counter(ctl, first_shard)), which the caller may have issued earlier.
+__device__ inline u32 take_tile(Control* ctl, u64 ltag, u32 ntiles, u32 first_shard, u64 asked) {
 #pragma nounroll
   for (u32 i = 0; i < u32(kTicketShards); ++i) {
-    const u32 y = (first_shard + i) & (kTicketShards - 1);
+    const u32 y = (first_shard + 8u * (i & 3u) + (i >> 2)) & (kTicketShards - 1);   // the XCD's own counters first
+    if (i) asked = ask_ticket(ticket_counter(ctl, y));
     if (y >= ntiles) continue;
-    const u32 t = tile_of_ticket(y, take_ticket(ticket_counter(ctl, y), ltag), ntiles);
+    const u32 t = tile_of_ticket(y, take_ticket(ticket_counter(ctl, y), ltag, asked), ntiles);
     if (t != kNoTile) return t;
   }
   return kNoTile;
+}
+__device__ inline u32 take_tile(Control* ctl, u64 ltag, u32 ntiles, u32 first_shard) {
+  return take_tile(ctl, ltag, ntiles, first_shard, ask_ticket(ticket_counter(ctl, first_shard)));
 }
 
 // Lane-crossing primitives are built from DPP moves and v_readlane, which need no address
@@ -470,8 +488,8 @@ __device__ inline void wave_lds_sync() {
 // resident workgroup (or done) and publishes without waiting for anything, so the waits end.
 // ---------------------------------------------------------------------------------------
 constexpr int kChains = 8;
-static_assert(kChains == kTicketShards, "tickets hand out the tiles of a chain on one XCD");
-constexpr u32 kLocalPolls = 64;
+static_assert(kTicketShards % kChains == 0, "tickets hand out the tiles of a chain on one XCD");
+constexpr u32 kLocalPolls = 16;
 constexpr u32 kOwnChain = 1u << (kChains - 1);               // lane 7: the chain of tile - 8, the tile's own
 constexpr u32 kOtherChains = kOwnChain - 1u;                 // lanes 0..6: the chains of tile - 1 .. tile - 7
 

@@ -301,7 +301,7 @@ __global__ __launch_bounds__(kPackThreads, FULL ? 8 : 6) void compress_kernel(Co
     tile = first_tile + blockIdx.x;          // tiles in the order in which workgroups start
     if (a.ticketed) {                        // ... or handed out by tickets, see take_tile
       if (threadIdx.x == 0) {
-        const u32 t = take_tile(a.ctl, ltag, end_tile - first_tile, xcc_id());
+        const u32 t = take_tile(a.ctl, ltag, end_tile - first_tile, ticket_shard());
         sh_tile = t == kNoTile ? kNoTile : first_tile + t;
       }
       __syncthreads();

@@ -670,6 +670,9 @@ template <bool IX>
 __device__ inline bool open_reduce(const ReduceArgs& a, bool for_wide, bool split, ReduceCall& c, bool& wide, OperandMeta& meta,
                                    bool early, u32& tile, u32& ntiles, u32* sh_tile) {
   c.ltag = launch_tag(a.nonce, a.ctl);
+  // (with tickets the ticket is asked for first of all: its round trip runs beside the headers')
+  u64 asked = 0;
+  if (a.ticketed && threadIdx.x == 0) asked = ask_ticket(ticket_counter(a.ctl, ticket_shard()));
   if (IX) {
     if (early) {
       // the caller has said what n is (a reduce in parts): where the first operand's tables are follows from
@@ -742,7 +745,7 @@ __device__ inline bool open_reduce(const ReduceArgs& a, bool for_wide, bool spli
   tile = a.first_tile + blockIdx.x;          // tiles in the order in which workgroups start
   if (a.ticketed) {                          // ... or handed out by tickets, see take_tile
     if (threadIdx.x == 0) {
-      const u32 t = take_tile(a.ctl, c.ltag, end_tile - a.first_tile, xcc_id());
+      const u32 t = take_tile(a.ctl, c.ltag, end_tile - a.first_tile, ticket_shard(), asked);
       *sh_tile = t == kNoTile ? kNoTile : a.first_tile + t;
     }
     __syncthreads();

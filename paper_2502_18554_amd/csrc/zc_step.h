@@ -280,6 +280,9 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   // position and its width bytes (fenced in by sizes the host passed).
   constexpr bool early = !TICKETS;
   const u32 zero = opaque_zero();
+  // (with tickets the ticket is asked for first of all: its round trip runs beside the header's)
+  u64 asked = 0;
+  if (TICKETS && threadIdx.x == 0) asked = ask_ticket(ticket_counter(a.ctl, ticket_shard()));
   uint4 gate_raw = make_uint4(0, 0, 0, 0);
   if (!IX) gate_raw = load_gate(a.ctl, zero);
   const HeaderWords hw = load_header_words(a.in.base, zero);
@@ -358,7 +361,7 @@ __global__ __launch_bounds__(kTileThreads, 5) void step_kernel(StepArgs a) {
   u32 tile = a.first_tile + blockIdx.x;      // tiles in the order in which workgroups start
   if (TICKETS) {                             // ... or handed out by tickets, see take_tile
     if (threadIdx.x == 0) {
-      const u32 t = take_tile(a.ctl, ltag, end_tile - a.first_tile, xcc_id());
+      const u32 t = take_tile(a.ctl, ltag, end_tile - a.first_tile, ticket_shard(), asked);
       sh_tile = t == kNoTile ? kNoTile : a.first_tile + t;
     }
     __syncthreads();
