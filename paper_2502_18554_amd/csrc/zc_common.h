@@ -67,7 +67,8 @@ constexpr u32 kGateBits = status_bit(ZC_ERR_ARG) | status_bit(ZC_ERR_FORMAT) | s
 // tables follow.  Nothing in a workspace is ever cleared: whatever one call shares between its
 // workgroups or its launches carries the call's tag (below), and a word with another tag counts
 // as empty, so a workspace may hold anything when a call starts.
-constexpr int kTicketShards = 32;
+constexpr int kTicketsPerXcd = 4;
+constexpr int kTicketShards = 8 * kTicketsPerXcd;
 struct Control {
   u64 status;                  // bits 63..32: high half of the tag of the call that raised them; bits 31..0: OR of status_bit()s and kStatusWide
   u64 call_tag;                // tag of the last call's first launch; its later launches take it from here
@@ -192,7 +193,7 @@ __device__ inline u32 xcc_id() {
 }
 // The counter a workgroup asks: one of the four of its XCD, in turn (workgroup ids go round the XCDs,
 // so id / 8 counts the workgroups of an XCD).
-__device__ inline u32 ticket_shard() { return xcc_id() | (((blockIdx.x >> 3) & 3u) << 3); }
+__device__ inline u32 ticket_shard() { return xcc_id() | (((blockIdx.x >> 3) & u32(kTicketsPerXcd - 1)) << 3); }
 
 constexpr u32 kNoTile = 0xffffffffu;
 
@@ -231,7 +232,7 @@ __device__ inline u32 take_ticket(u64* counter, u64 ltag, u64 old) {      // old
 __device__ inline u32 take_tile(Control* ctl, u64 ltag, u32 ntiles, u32 first_shard, u64 asked) {
 #pragma nounroll
   for (u32 i = 0; i < u32(kTicketShards); ++i) {
-    const u32 y = (first_shard + 8u * (i & 3u) + (i >> 2)) & (kTicketShards - 1);   // the XCD's own counters first
+    const u32 y = (first_shard + 8u * (i % u32(kTicketsPerXcd)) + i / u32(kTicketsPerXcd)) & (kTicketShards - 1);   // the XCD's own counters first
     if (i) asked = ask_ticket(ticket_counter(ctl, y));
     if (y >= ntiles) continue;
     const u32 t = tile_of_ticket(y, take_ticket(ticket_counter(ctl, y), ltag, asked), ntiles);
