@@ -1311,6 +1311,12 @@ def test_reduce_and_ring_round_in_parts_match_reference(zcref, stream_variant):
     assert zc.zc_reduce_compressed_part(d_streams, sizes, n, 0, 100, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
     assert zc.zc_reduce_compressed_part(d_streams, sizes, n, 6 * TILE, TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
     assert zc.zc_reduce_compressed_part(d_streams, sizes, n + 32, 0, TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_MISMATCH
+    # (workgroups ask for their tables where the n they are told puts them, before they know the headers: a
+    #  wrong n, far too large or too small, must neither read outside the streams nor pass)
+    big_ws = u.workspace(64 * n, len(d_streams))
+    assert zc.zc_reduce_compressed_part(d_streams, sizes, 64 * n, 0, TILE, d_out, big_ws, out_cap=cap)[0] == ZC_ERR_MISMATCH
+    assert zc.zc_reduce_compressed_part(d_streams, sizes, 64 * n, 32 * n // TILE * TILE, TILE, d_out, big_ws, out_cap=cap)[0] == ZC_ERR_MISMATCH
+    assert zc.zc_reduce_compressed_part(d_streams, sizes, TILE, 0, TILE, d_out, ws, out_cap=cap)[0] == ZC_ERR_MISMATCH
     assert zc.zc_reduce_step_part(d_streams[0], sizes[0], d_loc, n, 0, 0, 100, d_out, ws, out_cap=cap)[0] == ZC_ERR_ARG
     # an error in a middle part shows at the end
     bad = xs[1].copy(); bad[TILE + 5] = np.nan
